@@ -1,0 +1,484 @@
+"""Planner oracle (TEST INFRASTRUCTURE ONLY): uKernel-set derivation and runtime covering.
+
+Pure Python, integers only (Python ints are unbounded, so nothing can overflow), written
+from the paper's algorithms in the paper's order and notation:
+
+  * uKernel data structure: reg_tile, smem_tile, padding_threshold (Pad), usage_eff (Occ),
+    compute_eff (CMR)                                        -- Fig. 6 caption, Table 1
+  * HardwareAlign / RegTileRule / SmemTileRule                -- Sec. 4.1, Alg. 1
+  * mem.IsOverflow, Eq. 4 (register bound, block.bound)       -- Sec. 4.2, Alg. 1
+  * Pad (Eq. 2), Occ (Eq. 3), CrossPick epsilon/lambda sweep  -- Sec. 4.2
+  * space-axis saturation (Eq. 5), compute_eff (Eq. 6, 7)     -- Sec. 4.3
+  * CombinSearch on the main axis tau (Alg. 2)                -- Sec. 5.1
+  * SIA score (Eq. 1), Top-1                                  -- Sec. 5.2
+
+The paper's device is an NVIDIA GPU with fp32 CUDA cores; here its terms are re-based on
+gfx950 resources (CU, wave64, LDS, unified VGPR/AGPR file, MFMA shapes).  The readings
+taken where the paper is silent or loose are listed next to each function.
+
+Shares no code with the GPU library.  Fixed-point scores are floor(x * 2**20) of exact
+rationals so that a second implementation can reproduce every decision bit for bit.
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+Q = 20                      # fixed-point fraction bits of the cached metrics
+ONE = 1 << Q
+GRANULE = 16                # smallest MFMA output extent on gfx950 (16x16x32)
+
+OP_MATMUL, OP_BMM, OP_CONV2D = 0, 1, 2
+F16, BF16 = 0, 1
+PLAN_PATCHWORK, PLAN_PAD_BASELINE = 0, 1
+
+
+def default_hw():
+    """Hardware description 'script' (Sec. 8): bandwidth per memory level, clock, cores."""
+    return dict(num_cus=256, simds_per_cu=4, wave_size=64, regs_per_lane=512,
+                max_waves_per_simd=8, lds_bytes_per_cu=163840, clock_mhz=2400,
+                mfma_flops_per_clk_per_cu=4096, bw_global_bytes_per_clk_per_cu=64,
+                bw_lds_bytes_per_clk_per_cu=128, hbm_gbytes_per_s=8000, num_xcds=8)
+
+
+def default_tuning():
+    """Hyper-parameters (Sec. 4.2: epsilon 50%..95% step 1%, lambda 95%..90% step 0.1%,
+    zeta = 2; Sec. 5.2: c0 = c1 = c2 = 1).  Per-mille units; psi is never given a value in
+    the paper, 1/8 here."""
+    return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
+                lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
+                zeta=2, rest_regs=64, psi_num=1, psi_den=8, c0=1, c1=1, c2=1)
+
+
+# --------------------------------------------------------------------------------------
+# small closed-form pieces
+# --------------------------------------------------------------------------------------
+def ceil_div(a, b):
+    return -((-a) // b)
+
+
+def ceil_by(x, m):
+    """ceil_by of Eq. 3: x rounded up to a multiple of m."""
+    return m * ceil_div(x, m)
+
+
+def occ_fraction(num_tiles, slots):
+    """Eq. 3 as an exact fraction (numerator, denominator): (wkl/K) / ceil_by(wkl/K, slots)."""
+    return num_tiles, ceil_by(num_tiles, slots)
+
+
+def pad_fraction(base, padded_total):
+    """Eq. 2 as an exact fraction: base / (pad + base), both counted in multiply-accumulates
+    per unit of the reduce axis (the reduce extent is common to numerator and denominator)."""
+    return base, padded_total
+
+
+def sweep_points(t):
+    """Lock-step epsilon/lambda staircase of CrossPick (Alg. 1, 'Forward' = one stride of
+    both): starts at (eps_min, lam_max), stops when either bound is passed."""
+    pts = []
+    eps, lam = t["eps_min_pm"], t["lam_max_pm"]
+    while eps <= t["eps_max_pm"] and lam >= t["lam_min_pm"]:
+        pts.append((eps, lam))
+        eps += t["eps_step_pm"]
+        lam -= t["lam_step_pm"]
+    return pts
+
+
+def cross_pick(pad, occ, t):
+    """CrossPick test for one candidate: kept iff at some step of the staircase
+    K.pad >= eps_i and K.occ >= lam_j (exact integer comparison of fractions)."""
+    pn, pd = pad
+    on, od = occ
+    for eps, lam in sweep_points(t):
+        if 1000 * pn >= eps * pd and 1000 * on >= lam * od:
+            return True
+    return False
+
+
+def factors(n):
+    return [d for d in range(1, n + 1) if n % d == 0]
+
+
+def reg_tile_rule_factors(length):
+    """RegTileRule as printed (Sec. 4.1): all factors of the dynamic-axis length; for a
+    prime length the factors of the two neighbours instead.  On gfx950 the register tile
+    is a multiple of an MFMA shape, so this form survives only for its worked example."""
+    def is_prime(n):
+        return n > 1 and all(n % d for d in range(2, int(n ** 0.5) + 1))
+    if is_prime(length):
+        return sorted(set(factors(length - 1)) | set(factors(length + 1)))
+    return factors(length)
+
+
+def combin_search(H, extents, trace=None):
+    """Alg. 2 on bare main-axis extents, paper form (first success): for each K1 in set
+    order, a single-uKernel program if K1 divides H; otherwise H is reduced by K1 once per
+    search round until some other extent K2 divides what is left:
+        H = Num1*K1 + Num2*K2.
+    Returns a list of programs [(K1, Num1)] or [(K1, Num1), (K2, Num2)], one per K1 that
+    admits one (first K2 in set order).  trace, if a list, receives (K1, H) for every
+    reduced H the search visits."""
+    progs = []
+    for k1 in extents:
+        if H % k1 == 0:
+            progs.append([(k1, H // k1)])
+            continue
+        left, n1 = H, 0
+        found = None
+        while left - k1 > 0 and found is None:
+            left -= k1
+            n1 += 1
+            if trace is not None:
+                trace.append((k1, left))
+            for k2 in extents:
+                if k2 != k1 and left % k2 == 0:
+                    found = [(k1, n1), (k2, left // k2)]
+                    break
+        if found:
+            progs.append(found)
+    return progs
+
+
+# --------------------------------------------------------------------------------------
+# uKernel set (compile stage, Sec. 4)
+# --------------------------------------------------------------------------------------
+@dataclass
+class UKernel:
+    tm: int
+    tn: int
+    tk: int
+    wm: int          # reg_tile: per-wave accumulator tile
+    wn: int
+    gm: int          # wave grid inside the workgroup
+    gn: int
+    mfma: int        # 0 = 32x32x16, 1 = 16x16x32
+    stages: int
+    lds_bytes: int
+    acc_regs: int
+    regs: int
+    max_wg_per_cu: int
+    cmr_q: int
+    id: int = -1
+
+
+@dataclass
+class Op:
+    kind: int
+    dtype: int
+    # GEMM view; a static extent is > 0, a dynamic one is 0 with its [lo, hi] range
+    m: int = 0
+    n: int = 0
+    k: int = 0
+    m_range: Tuple[int, int] = (1, 1)
+    n_range: Tuple[int, int] = (1, 1)
+    k_range: Tuple[int, int] = (1, 1)
+    # conv only (NHWC, RSCK)
+    c_in: int = 0
+    c_out: int = 0
+    r: int = 0
+    s: int = 0
+    stride: int = 1
+    pad: int = 0
+
+    def gemm_static(self):
+        if self.kind == OP_CONV2D:
+            return 0, self.c_out, self.r * self.s * self.c_in
+        return self.m, self.n, self.k
+
+    def k_ref(self):
+        _, _, k = self.gemm_static()
+        return k if k > 0 else self.k_range[1]
+
+
+def wave_tiles():
+    """RegTileRule on gfx950: per-wave accumulator tiles are power-of-two multiples of an
+    MFMA output shape, at most 128 on a side.  Rows of 16 use the 16x16x32 instruction
+    (columns up to 64); everything else the 32x32x16 one with aspect ratio within 2."""
+    out = []
+    sizes = (16, 32, 64, 128)
+    for wm in sizes:
+        for wn in sizes:
+            if wm == 16 and wn <= 64:
+                out.append((wm, wn, 1))
+            elif wm >= 32 and wn >= 32 and wm <= 2 * wn and wn <= 2 * wm:
+                out.append((wm, wn, 0))
+    return out
+
+
+WAVE_GRIDS = ((1, 4), (2, 2), (4, 1))      # four wave64 per workgroup, one per SIMD
+TK_CHOICES = (64,)                          # 64 16-bit elements = one 128-byte line
+STAGES = 2
+ELT = 2
+
+
+def compute_eff(tm, tn, gm, gn, k_ref, hw):
+    """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, K_mem = max of global and shared time.
+    Returns (numerator, denominator) of the exact ratio."""
+    flops = 2 * tm * tn * k_ref
+    data_r = (tm + tn) * k_ref * ELT
+    data_w = tm * tn * 4
+    data_tw = data_r
+    data_tr = k_ref * ELT * (tm * gn + tn * gm)
+    bw_g, bw_s = hw["bw_global_bytes_per_clk_per_cu"], hw["bw_lds_bytes_per_clk_per_cu"]
+    g_num, g_den = data_r + data_w, bw_g
+    s_num, s_den = data_tw + data_tr, bw_s
+    if g_num * s_den >= s_num * g_den:
+        mem_num, mem_den = g_num, g_den
+    else:
+        mem_num, mem_den = s_num, s_den
+    # (flops / FLOPS) / (mem_num / mem_den)
+    return flops * mem_den, hw["mfma_flops_per_clk_per_cu"] * mem_num
+
+
+def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
+    """HardwareAlign + the shape-independent filters (IsOverflow, Eq. 4 at block.bound = 1,
+    Eq. 6), in the canonical set order: larger smem_tile area first."""
+    hw = hw or default_hw()
+    t = t or default_tuning()
+    m_s, n_s, _ = op.gemm_static()
+    k_ref = op.k_ref()
+    waves_per_simd = 1                      # 4 waves on 4 SIMDs
+    cand = []
+    for wm, wn, mfma in wave_tiles():
+        for gm, gn in WAVE_GRIDS:
+            for tk in TK_CHOICES:
+                tm, tn = gm * wm, gn * wn
+                # static space axes are divided evenly (after rounding to the MFMA granule,
+                # the gfx950 form of "factors of the neighbours")
+                if m_s > 0 and ceil_by(m_s, GRANULE) % tm:
+                    continue
+                if n_s > 0 and ceil_by(n_s, GRANULE) % tn:
+                    continue
+                lds = STAGES * (tm + tn) * tk * ELT
+                if lds > hw["lds_bytes_per_cu"]:
+                    continue                                        # mem.IsOverflow
+                acc = wm * wn // hw["wave_size"]
+                regs = acc + t["rest_regs"]
+                if regs * waves_per_simd > hw["regs_per_lane"]:
+                    continue                                        # Eq. 4, block.bound = 1
+                cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw)
+                if cn * t["psi_den"] < t["psi_num"] * cd:
+                    continue                                        # Eq. 6
+                cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // regs,
+                          hw["max_waves_per_simd"])
+                cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, mfma, STAGES, lds, acc, regs,
+                                    cap, (cn << Q) // cd))
+    cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))
+    for i, u in enumerate(cand):
+        u.id = i
+    return cand
+
+
+# --------------------------------------------------------------------------------------
+# runtime stage (Sec. 5)
+# --------------------------------------------------------------------------------------
+@dataclass
+class Desc:
+    ukernel_id: int
+    batch: int
+    m0: int
+    n0: int
+    m_valid: int
+    n_valid: int
+    flags: int
+
+    def pack(self):
+        import struct
+        return struct.pack("<IIIIHHI", self.ukernel_id, self.batch, self.m0, self.n0,
+                           self.m_valid, self.n_valid, self.flags)
+
+
+@dataclass
+class Program:
+    parts: List[Tuple[int, int]]            # (ukernel id, count along tau), ascending id
+    num_tiles: int = 0
+    area: int = 0                           # sum of tm*tn over one batch entry's tiles
+    block_bound: int = 1
+    in_bound: bool = True
+    cross: bool = False
+    saturated: bool = False
+    pad_q: int = 0
+    occ_q: int = 0
+    cmr_q: int = 0
+    sia_q: int = 0
+    k1: int = -1
+    k2: int = -1
+
+
+@dataclass
+class Plan:
+    batch: int
+    M: int
+    N: int
+    K: int
+    tau: int                                # 0: rows (M) are the main axis, 1: columns (N)
+    program: Optional[Program]
+    descs: List[Desc] = field(default_factory=list)
+    pool_size: int = 0
+    level: int = 0
+    useful: int = 0
+    covered: int = 0
+
+
+def resolve_shape(op: Op, batch=1, m=0, n=0, k=0, img_n=0, img_h=0, img_w=0):
+    """Runtime shape -> GEMM view (batch, M, N, K); conv maps space (n,p,q) to rows."""
+    if op.kind == OP_CONV2D:
+        P = (img_h + 2 * op.pad - op.r) // op.stride + 1
+        Qo = (img_w + 2 * op.pad - op.s) // op.stride + 1
+        return 1, img_n * P * Qo, op.c_out, op.r * op.s * op.c_in
+    ms, ns, ks = op.gemm_static()
+    return batch, (ms or m), (ns or n), (ks or k)
+
+
+def main_axis(op: Op, M, N):
+    """Main axis tau = the largest dynamic space axis (tie: rows); rows if none is dynamic."""
+    ms, ns, _ = op.gemm_static()
+    dyn_m, dyn_n = ms == 0, ns == 0
+    if dyn_m and dyn_n:
+        return 0 if M >= N else 1
+    if dyn_n and not dyn_m:
+        return 1
+    return 0
+
+
+def _ext(u: UKernel, axis):
+    return u.tm if axis == 0 else u.tn
+
+
+def build_pool(extents, Hp):
+    """Alg. 2 over the main-axis extents of the uKernel set (extents[i] belongs to uKernel
+    i) on the main-axis size Hp.  For each K1 in set order: a single-uKernel program when
+    K1 divides Hp; otherwise Hp = Num1*K1 + Num2*K2 with a second uKernel K2.
+    Reading: on gfx950 every extent is a multiple of the 16-row granule, so the *first*
+    success of the printed search (smallest Num1) is always Num1 = 1 followed by a long run
+    of granule tiles; the search is therefore run from the other end and stops at its
+    *last* success (largest Num1 whose positive remainder some K2 divides), and every K2
+    dividing that remainder yields a program.  On the paper's worked example the success
+    is unique, so both readings give 53 = 3*7 + 4*8."""
+    pool = []
+    for i1, e1 in enumerate(extents):
+        if Hp % e1 == 0:
+            pool.append([(i1, Hp // e1)])
+            continue
+        for n1 in range(Hp // e1, 0, -1):
+            rem = Hp - n1 * e1
+            found = [(i2, rem // e2) for i2, e2 in enumerate(extents)
+                     if e2 != e1 and rem % e2 == 0]
+            if found:
+                pool.extend([(i1, n1), f] for f in found)
+                break
+    return pool
+
+
+def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q):
+    """Cached-metric evaluation of one program (Sec. 5.2) on the actual shape."""
+    Wp = ceil_by(N if tau == 0 else M, GRANULE)
+    tiles_per_batch, area = 0, 0
+    for uid, cnt in parts:
+        u = uks[uid]
+        across = ceil_div(Wp, _ext(u, 1 - tau))
+        tiles_per_batch += cnt * across
+        area += cnt * across * u.tm * u.tn
+    T = batch * tiles_per_batch
+    p = Program(parts=sorted(parts), num_tiles=T, area=area)
+    p.k1 = parts[0][0]
+    p.k2 = parts[1][0] if len(parts) > 1 else -1
+    # SetBound (Alg. 1): block.bound = min(K.wkl.block, zeta)
+    p.block_bound = min(max(1, ceil_div(T, hw["num_cus"])), t["zeta"])
+    p.in_bound = all(uks[uid].max_wg_per_cu >= p.block_bound for uid, _ in parts)
+    slots = hw["num_cus"] * p.block_bound
+    occ = occ_fraction(T, slots)
+    pad = pad_fraction(M * N, area)
+    p.occ_q = (occ[0] << Q) // occ[1]
+    p.pad_q = (pad[0] << Q) // pad[1]
+    p.cross = cross_pick(pad, occ, t)
+    p.saturated = T >= t["zeta"] * hw["num_cus"]                 # Eq. 5
+    # compute_eff is unbounded, the other two terms lie in [0, 1]: normalise by the set's
+    # best; a two-uKernel program takes the average of its constituents (Sec. 5.2)
+    acc = 0
+    for uid, _ in parts:
+        acc += (min(uks[uid].cmr_q, cap_q) << Q) // cap_q
+    p.cmr_q = acc // len(parts)
+    p.sia_q = t["c0"] * p.cmr_q + t["c1"] * p.pad_q + t["c2"] * p.occ_q       # Eq. 1
+    return p
+
+
+def emit(parts, uks, batch, M, N, tau):
+    """Tile descriptors in canonical order: uKernel id, batch, m0, n0 ascending.  Along tau
+    the constituent with the lower id (larger tile) comes first."""
+    descs = []
+    off = 0
+    Wp = ceil_by(N if tau == 0 else M, GRANULE)
+    for uid, cnt in sorted(parts):
+        u = uks[uid]
+        across = ceil_div(Wp, _ext(u, 1 - tau))
+        if tau == 0:
+            m_list = [off + i * u.tm for i in range(cnt)]
+            n_list = [j * u.tn for j in range(across)]
+        else:
+            m_list = [i * u.tm for i in range(across)]
+            n_list = [off + j * u.tn for j in range(cnt)]
+        off += cnt * _ext(u, tau)
+        for b in range(batch):
+            for m0 in m_list:
+                for n0 in n_list:
+                    mv, nv = min(u.tm, M - m0), min(u.tn, N - n0)
+                    descs.append(Desc(uid, b, m0, n0, mv, nv,
+                                      1 if (mv < u.tm or nv < u.tn) else 0))
+    return descs
+
+
+def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None) -> Plan:
+    """Runtime stage: pool construction (Alg. 2), evaluation (Eq. 1-3, 5), Top-1, descriptors.
+
+    mode PLAN_PAD_BASELINE instead pads every dynamic axis up to a multiple of the single
+    largest uKernel of the set (the 'optimized kernel in the manual library', Fig. 2)."""
+    hw = hw or default_hw()
+    t = t or default_tuning()
+    batch, M, N, K = shape
+    if not uks:
+        raise ValueError("empty uKernel set")
+    tau = main_axis(op, M, N)
+    pl = Plan(batch, M, N, K, tau, None, useful=batch * M * N)
+    if batch == 0 or M == 0 or N == 0:
+        return pl
+    cap_q = max(u.cmr_q for u in uks)
+    if mode == PLAN_PAD_BASELINE:
+        u = uks[0]
+        Hp = ceil_by(M if tau == 0 else N, _ext(u, tau))
+        parts = [(0, Hp // _ext(u, tau))]
+        prog = evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
+        pl.pool_size, pl.level = 1, 3
+    else:
+        Hp = ceil_by(M if tau == 0 else N, GRANULE)
+        pool = [evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
+                for parts in build_pool([_ext(u, tau) for u in uks], Hp)]
+        if not pool:
+            raise ValueError("no cover")
+        pl.pool_size = len(pool)
+        levels = [
+            [p for p in pool if p.in_bound and p.cross and p.saturated],
+            [p for p in pool if p.in_bound and p.cross],
+            [p for p in pool if p.in_bound],
+            pool,
+        ]
+        for lv, cands in enumerate(levels):
+            if cands:
+                pl.level = lv
+                break
+        # Top-1 by SIA; ties: fewer tiles, then lower K1 index, then lower K2 index
+        prog = min(cands, key=lambda p: (-p.sia_q, p.num_tiles, p.k1, p.k2))
+    pl.program = prog
+    pl.descs = emit(prog.parts, uks, batch, M, N, tau)
+    pl.covered = batch * prog.area
+    assert len(pl.descs) == prog.num_tiles
+    return pl
+
+
+def exact_cover_counts(pl: Plan, uks: List[UKernel]):
+    """Paint every descriptor's valid region into an integer count array [batch, M, N];
+    a correct plan gives all ones.  Independent of emit(): uses only the descriptors."""
+    import numpy as np
+    cnt = np.zeros((pl.batch, pl.M, pl.N), dtype=np.int32)
+    for d in pl.descs:
+        cnt[d.batch, d.m0:d.m0 + d.m_valid, d.n0:d.n0 + d.n_valid] += 1
+    return cnt

@@ -1,0 +1,270 @@
+"""Pins of the planner oracle: the paper's printed worked examples (tests/golden), closed
+forms of Eq. 2-4, brute-force enumeration of decompositions, and the exact-cover invariant
+of every emitted plan.  CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import planner as P
+
+
+def read_golden(golden_dir, name):
+    out = {}
+    with open(os.path.join(golden_dir, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [int(v) for v in vals]
+    return out
+
+
+def test_paper_combination_example(golden_dir):
+    gdn = read_golden(golden_dir, "combination_example.txt")
+    H, k1, k2 = gdn["H"][0], gdn["K1"][0], gdn["K2"][0]
+    trace = []
+    progs = P.combin_search(H, [k1, k2], trace=trace)
+    assert progs[0] == [(k1, gdn["NUM1"][0]), (k2, gdn["NUM2"][0])]
+    assert trace[0] == (k1, gdn["FIRST_REDUCED_H"][0])
+    # the gfx950 reading (last success) gives the same decomposition on this example
+    pool = P.build_pool([k1, k2], H)
+    assert [(0, gdn["NUM1"][0]), (1, gdn["NUM2"][0])] in pool
+    for prog in pool:
+        assert sum([k1, k2][i] * c for i, c in prog) == H
+
+
+def test_paper_prime_rule(golden_dir):
+    gdn = read_golden(golden_dir, "regtile_prime_example.txt")
+    n = gdn["LENGTH"][0]
+    want = set()
+    for m in gdn["NEIGHBOURS"]:
+        want |= {d for d in range(1, m + 1) if m % d == 0}
+    assert P.reg_tile_rule_factors(n) == sorted(want)
+    assert P.reg_tile_rule_factors(12) == [1, 2, 3, 4, 6, 12]
+
+
+def test_paper_occupancy_example(golden_dir):
+    gdn = read_golden(golden_dir, "occupancy_example.txt")
+    assert P.occ_fraction(gdn["BLOCKS"][0], gdn["CORES"][0]) == (gdn["OCC_NUM"][0], gdn["OCC_DEN"][0])
+    for t in range(1, 400):
+        n, d = P.occ_fraction(t, 80)
+        assert 0 < n <= d and (n == d) == (t % 80 == 0)
+
+
+def test_paper_crosspick_sweep(golden_dir):
+    gdn = read_golden(golden_dir, "crosspick_sweep.txt")
+    t = P.default_tuning()
+    for key, name in [("EPS_MIN", "eps_min_pm"), ("EPS_MAX", "eps_max_pm"), ("EPS_STEP", "eps_step_pm"),
+                      ("LAM_MAX", "lam_max_pm"), ("LAM_MIN", "lam_min_pm"), ("LAM_STEP", "lam_step_pm")]:
+        assert t[name] == gdn[key][0]
+    pts = P.sweep_points(t)
+    assert len(pts) == gdn["POINTS"][0]
+    assert pts[0] == (gdn["EPS_MIN"][0], gdn["LAM_MAX"][0])
+    assert pts[-1] == (gdn["LAST_EPS"][0], gdn["LAST_LAM"][0])
+    # staircase semantics on hand-made fractions
+    assert P.cross_pick((1, 2), (95, 100), t)            # pad 0.50, occ 0.95: first step
+    assert not P.cross_pick((49, 100), (1, 1), t)        # pad below eps_min never passes
+    assert P.cross_pick((1, 1), (905, 1000), t)          # occ 0.905 passes only at the last step
+    assert not P.cross_pick((1, 1), (904, 1000), t)
+    assert not P.cross_pick((94, 100), (905, 1000), t)   # needs eps=0.95 for lam=0.905
+    assert P.cross_pick((60, 100), (94, 100), t)         # step 10: eps 0.60, lam 0.94
+
+
+def test_pad_fraction_closed_form():
+    assert P.pad_fraction(77 * 768, 80 * 768) == (77 * 768, 80 * 768)
+    n, d = P.pad_fraction(64 * 64, 64 * 64)
+    assert n == d
+
+
+def test_default_hyper_parameters_from_paper():
+    t = P.default_tuning()
+    assert t["zeta"] == 2 and (t["c0"], t["c1"], t["c2"]) == (1, 1, 1)
+
+
+def test_resource_closed_forms():
+    op = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(1, 8192))
+    uks = P.derive_ukernels(op)
+    by = {(u.tm, u.tn, u.wm, u.wn): u for u in uks}
+    u = by[(256, 256, 128, 128)]
+    assert u.lds_bytes == 131072 and u.acc_regs == 256 and u.max_wg_per_cu == 1
+    u = by[(128, 128, 64, 64)]
+    assert u.lds_bytes == 65536 and u.acc_regs == 64 and u.max_wg_per_cu == 2
+    for u in uks:
+        assert u.lds_bytes == 2 * (u.tm + u.tn) * u.tk * 2 <= 163840
+        assert u.acc_regs * 64 == u.wm * u.wn
+        assert u.tm == u.gm * u.wm and u.tn == u.gn * u.wn and u.gm * u.gn == 4
+        assert 768 % u.tn == 0                              # static axis divided evenly
+        assert u.tk % (16 if u.mfma == 0 else 32) == 0
+        assert (u.mfma == 1) == (u.wm == 16)
+    # canonical order: non-increasing area, ids consecutive
+    areas = [u.tm * u.tn for u in uks]
+    assert areas == sorted(areas, reverse=True)
+    assert [u.id for u in uks] == list(range(len(uks)))
+    assert len({(u.tm, u.tn, u.tk, u.wm, u.wn) for u in uks}) == len(uks)
+
+
+def test_compute_eff_closed_form():
+    hw = P.default_hw()
+    # 128x128 tile, 2x2 waves, K = 768: flops 2*128*128*768 at 4096 flop/clk = 6144 clk;
+    # global (256*768*2 + 128*128*4) / 64 = 7168 clk; LDS (393216 + 768*2*512) / 128 = 9216 clk
+    n, d = P.compute_eff(128, 128, 2, 2, 768, hw)
+    assert n * 9216 == d * 6144
+    # a bigger tile is more compute-intensive
+    n2, d2 = P.compute_eff(256, 256, 2, 2, 768, hw)
+    assert n2 * d > n * d2
+
+
+def brute_decompositions(H, extents):
+    out = set()
+    for (i1, e1), (i2, e2) in itertools.permutations(list(enumerate(extents)), 2):
+        for n1 in range(1, H // e1 + 1):
+            rem = H - n1 * e1
+            if rem > 0 and rem % e2 == 0:
+                out.add((i1, n1, i2, rem // e2))
+    return out
+
+
+@pytest.mark.parametrize("extents", [[7, 8], [16, 32, 48, 64], [5, 9, 12], [16, 64, 256]])
+def test_pool_against_brute_force(extents):
+    for H in range(1, 200):
+        pool = P.build_pool(extents, H)
+        brute = brute_decompositions(H, extents)
+        for prog in pool:
+            assert sum(extents[i] * c for i, c in prog) == H and all(c >= 1 for _, c in prog)
+        for i1, e1 in enumerate(extents):
+            mine = [p for p in pool if p[0][0] == i1]
+            if H % e1 == 0:
+                assert mine == [[(i1, H // e1)]]
+                continue
+            feas = [d for d in brute if d[0] == i1]
+            if not feas:
+                assert mine == []
+                continue
+            n1max = max(d[1] for d in feas)
+            want = sorted((i1, n1, i2, n2) for (_, n1, i2, n2) in feas if n1 == n1max)
+            got = sorted((p[0][0], p[0][1], p[1][0], p[1][1]) for p in mine)
+            assert got == want
+
+
+SHAPES = [(1, 77, 768, 768), (1, 1, 768, 768), (1, 15, 768, 768), (1, 16, 768, 768),
+          (1, 17, 768, 768), (1, 1232, 3072, 768), (1, 2048, 768, 3072), (1, 8191, 768, 768)]
+
+
+@pytest.mark.parametrize("mode", [P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_matmul_plans_cover_exactly_once(shape, mode):
+    _, M, N, K = shape
+    op = P.Op(P.OP_MATMUL, P.F16, n=N, k=K, m_range=(1, 8192))
+    uks = P.derive_ukernels(op)
+    pl = P.plan(op, uks, shape, mode)
+    cnt = P.exact_cover_counts(pl, uks)
+    assert cnt.min() == 1 and cnt.max() == 1
+    check_plan_invariants(pl, uks, mode)
+
+
+def check_plan_invariants(pl, uks, mode):
+    prog = pl.program
+    tau_ext = lambda u: u.tm if pl.tau == 0 else u.tn
+    H = pl.M if pl.tau == 0 else pl.N
+    total = sum(tau_ext(uks[i]) * c for i, c in prog.parts)
+    if mode == P.PLAN_PATCHWORK:
+        assert total == P.ceil_by(H, 16)                 # zero padding on tau up to the granule
+        assert len(prog.parts) <= 2
+    else:
+        assert prog.parts[0][0] == 0 and total == P.ceil_by(H, tau_ext(uks[0]))
+    seen = set()
+    area = 0
+    for d in pl.descs:
+        u = uks[d.ukernel_id]
+        assert d.m0 % 16 == 0 and d.n0 % 16 == 0
+        assert d.m_valid == min(u.tm, pl.M - d.m0) and d.n_valid == min(u.tn, pl.N - d.n0)
+        assert d.m_valid > 0 and d.n_valid > 0
+        assert d.flags == (1 if (d.m_valid < u.tm or d.n_valid < u.tn) else 0)
+        key = (d.batch, d.m0, d.n0)
+        assert key not in seen
+        seen.add(key)
+        area += u.tm * u.tn
+    assert area == pl.covered and pl.useful == pl.batch * pl.M * pl.N
+    order = [(d.ukernel_id, d.batch, d.m0, d.n0) for d in pl.descs]
+    assert order == sorted(order)
+    assert prog.pad_q == (pl.useful << 20) // pl.covered
+    assert len(pl.descs[0].pack()) == 24
+
+
+def test_bmm_two_dynamic_axes_and_dynamic_k():
+    qk = P.Op(P.OP_BMM, P.F16, k=64, m_range=(1, 512), n_range=(1, 512))
+    pv = P.Op(P.OP_BMM, P.F16, n=64, m_range=(1, 512), k_range=(1, 512))
+    uq, up = P.derive_ukernels(qk), P.derive_ukernels(pv)
+    assert all(u.tn in (16, 32, 64) for u in up)
+    for L in (1, 7, 16, 33, 100, 257, 512):
+        for op, uks, shape in ((qk, uq, (3, L, L, 64)), (pv, up, (3, L, 64, L))):
+            for mode in (P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE):
+                pl = P.plan(op, uks, shape, mode)
+                cnt = P.exact_cover_counts(pl, uks)
+                assert cnt.min() == 1 and cnt.max() == 1
+                check_plan_invariants(pl, uks, mode)
+
+
+def test_main_axis_choice():
+    both = P.Op(P.OP_BMM, P.F16, k=64, m_range=(1, 512), n_range=(1, 512))
+    assert P.main_axis(both, 100, 100) == 0 and P.main_axis(both, 10, 100) == 1
+    only_n = P.Op(P.OP_BMM, P.F16, m=64, k=64, n_range=(1, 512))
+    assert P.main_axis(only_n, 64, 7) == 1
+    uks = P.derive_ukernels(only_n)
+    pl = P.plan(only_n, uks, (2, 64, 77, 64))
+    assert pl.tau == 1
+    cnt = P.exact_cover_counts(pl, uks)
+    assert cnt.min() == 1 and cnt.max() == 1
+    check_plan_invariants(pl, uks, P.PLAN_PATCHWORK)
+
+
+def test_conv_shape_mapping_and_cover():
+    op = P.Op(P.OP_CONV2D, P.F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1, m_range=(1, 1 << 20))
+    uks = P.derive_ukernels(op)
+    assert all(128 % u.tn == 0 for u in uks)
+    shape = P.resolve_shape(op, img_n=8, img_h=37, img_w=37)
+    assert shape == (1, 8 * 37 * 37, 128, 576)
+    pl = P.plan(op, uks, shape)
+    cnt = P.exact_cover_counts(pl, uks)
+    assert cnt.min() == 1 and cnt.max() == 1
+    check_plan_invariants(pl, uks, P.PLAN_PATCHWORK)
+
+
+def test_empty_shapes_give_empty_plans():
+    op = P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512))
+    uks = P.derive_ukernels(op)
+    for shape in [(0, 5, 5, 64), (2, 0, 5, 64), (2, 5, 0, 64)]:
+        pl = P.plan(op, uks, shape)
+        assert pl.descs == [] and pl.program is None
+
+
+def test_pad_baseline_wastes_at_least_as_much_as_patchwork():
+    op = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(1, 8192))
+    uks = P.derive_ukernels(op)
+    for M in [1, 5, 77, 80, 100, 272, 528, 1000, 1232, 1600, 2048, 4097]:
+        a = P.plan(op, uks, (1, M, 768, 768), P.PLAN_PATCHWORK)
+        b = P.plan(op, uks, (1, M, 768, 768), P.PLAN_PAD_BASELINE)
+        assert a.covered <= b.covered
+        assert a.covered == P.ceil_by(M, 16) * 768       # only granule padding is left
+
+
+def test_sia_is_the_weighted_sum_and_top1_is_max():
+    op = P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(1, 8192))
+    uks = P.derive_ukernels(op)
+    hw, t = P.default_hw(), P.default_tuning()
+    t2 = dict(t, c0=3, c1=5, c2=7)
+    cap = max(u.cmr_q for u in uks)
+    shape = (1, 528, 3072, 768)
+    pool = [P.evaluate(p, uks, 1, 528, 3072, 0, hw, t2, cap)
+            for p in P.build_pool([u.tm for u in uks], 528)]
+    for p in pool:
+        assert p.sia_q == 3 * p.cmr_q + 5 * p.pad_q + 7 * p.occ_q
+        assert 0 <= p.cmr_q <= 1 << 20 and 0 < p.pad_q <= 1 << 20 and 0 < p.occ_q <= 1 << 20
+    pl = P.plan(op, uks, shape, hw=hw, t=t2)
+    lvl = [[p for p in pool if p.in_bound and p.cross and p.saturated],
+           [p for p in pool if p.in_bound and p.cross], [p for p in pool if p.in_bound], pool]
+    cands = next(c for c in lvl if c)
+    assert pl.program.sia_q == max(p.sia_q for p in cands)
