@@ -1,0 +1,252 @@
+/*
+ * ftuner.h -- C ABI of the MI355X (gfx950) dynamic-shape contraction library.
+ *
+ * The library runs dense contractions whose shape is known only at run time -- Matmul,
+ * batched Matmul and NHWC Conv2d as implicit GEMM -- as a patchwork of differently sized
+ * uKernel tiles (Sec. 3; Fig. 4(c)): each workgroup computes one tile of the output with
+ * fp16/bf16 MFMA and fp32 accumulation, and the tiles of one or two uKernel shapes cover
+ * the output exactly once with no padding on the main axis beyond the 16-row MFMA granule.
+ *
+ * The four stages follow the paper's problem statement:
+ *   (a) ft_op_register      operator template + every possible shape        (Sec. 3, Sec. 4)
+ *   (b) ft_ukernels_derive  uKernel set from the hardware model             (Sec. 4, Alg. 1)
+ *   (c) ft_plan             uKernel-based program for one runtime shape     (Sec. 5, Alg. 2, Eq. 1)
+ *   (d) ft_launch           one launch over the tile-descriptor table       (Sec. 3: uKernel = thread block)
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross the boundary; every call returns ft_status (0 = FT_OK).
+ *   - Every struct starts with struct_size, which the caller sets to sizeof(the struct).
+ *   - "host pointer" / "device pointer" is stated per argument.  The caller owns A, B, C and
+ *     the HIP stream; the library owns its handles and the descriptor tables.
+ *   - Everything except ft_hw_query, ft_launch and the device half of ft_plan works in a
+ *     process without a GPU.
+ *   - Handles are not thread-safe against concurrent mutation; distinct handles may be used
+ *     from distinct threads.
+ */
+#ifndef FTUNER_H
+#define FTUNER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t ft_status;
+enum {
+    FT_OK = 0,
+    FT_ERR_INVALID_ARG = -1,   /* null pointer, wrong struct_size, inconsistent fields      */
+    FT_ERR_UNSUPPORTED = -2,   /* valid request the library has no kernel for               */
+    FT_ERR_OUT_OF_RANGE = -3,  /* runtime extent outside the registered dynamic range       */
+    FT_ERR_NO_COVER = -4,      /* uKernel set empty / no program covers the shape           */
+    FT_ERR_HIP = -5,           /* a HIP runtime call failed (see ft_last_hip_error)         */
+    FT_ERR_OOM = -6            /* host or device allocation failed                          */
+};
+
+/* Static string for a status code (never NULL). */
+const char *ft_status_string(ft_status s);
+/* hipError_t value of the last failing HIP call made by this library on this thread. */
+int32_t ft_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Hardware description (Sec. 8: bandwidth per memory level, core clock, core count), in
+ * gfx950 terms.  All fields are integers so that every derived metric is an exact rational.
+ * ------------------------------------------------------------------------------------- */
+typedef struct ft_hw_model {
+    uint32_t struct_size;
+    uint32_t num_cus;                        /* NumCores: compute units (256)                */
+    uint32_t simds_per_cu;                   /* 4                                            */
+    uint32_t wave_size;                      /* 64                                           */
+    uint32_t regs_per_lane;                  /* unified VGPR+AGPR per lane per SIMD (512)    */
+    uint32_t max_waves_per_simd;             /* 8                                            */
+    uint32_t lds_bytes_per_cu;               /* 163840                                       */
+    uint32_t clock_mhz;                      /* 2400                                         */
+    uint32_t mfma_flops_per_clk_per_cu;      /* FLOPS of Eq. 6 for dense 16-bit MFMA (4096)  */
+    uint32_t bw_global_bytes_per_clk_per_cu; /* bw_G of Eq. 7: L2 -> CU path (64)            */
+    uint32_t bw_lds_bytes_per_clk_per_cu;    /* bw_S of Eq. 7 (128)                          */
+    uint32_t hbm_gbytes_per_s;               /* 8000; used for rooflines only                */
+    uint32_t num_xcds;                       /* 8                                            */
+} ft_hw_model;
+
+/* gfx950 defaults; host only. out: host pointer. */
+ft_status ft_hw_default_gfx950(ft_hw_model *out);
+/* Defaults overridden by what hipGetDeviceProperties reports for hip_device (CU count,
+ * clock, LDS size, wave size).  Needs a GPU. out: host pointer. */
+ft_status ft_hw_query(int32_t hip_device, ft_hw_model *out);
+
+/* ---------------------------------------------------------------------------------------
+ * Hyper-parameters (Sec. 4.2: epsilon/lambda sweep and zeta; Sec. 4.3: psi; Sec. 5.2: SIA
+ * coefficients).  Fractions are per-mille or num/den pairs.
+ * ------------------------------------------------------------------------------------- */
+typedef struct ft_tuning {
+    uint32_t struct_size;
+    uint32_t eps_min_pm, eps_max_pm, eps_step_pm;   /* 500, 950, 10                         */
+    uint32_t lam_max_pm, lam_min_pm, lam_step_pm;   /* 950, 900, 1                          */
+    uint32_t zeta;                                  /* default active workgroups per CU: 2  */
+    uint32_t rest_regs;                             /* RestRegs of Eq. 4: 64                */
+    uint32_t psi_num, psi_den;                      /* threshold of Eq. 6: 1/8              */
+    uint32_t c0, c1, c2;                            /* Eq. 1 coefficients: 1, 1, 1          */
+} ft_tuning;
+
+ft_status ft_tuning_default(ft_tuning *out);        /* out: host pointer */
+
+/* ---------------------------------------------------------------------------------------
+ * (a) Operator template.
+ * ------------------------------------------------------------------------------------- */
+enum { FT_OP_MATMUL = 0, FT_OP_BMM = 1, FT_OP_CONV2D = 2 };
+enum { FT_F16 = 0, FT_BF16 = 1 };
+
+typedef struct ft_op_desc {
+    uint32_t struct_size;
+    uint32_t kind;                 /* FT_OP_*                                                */
+    uint32_t dtype;                /* FT_F16 / FT_BF16 inputs; accumulation and C are fp32   */
+    /* GEMM view C[b,i,j] = sum_k A[b,i,k] B[b,k,j].  An extent > 0 is static; 0 means dynamic
+     * with the inclusive range [lo, hi] below (lo may be 0: empty inputs are legal).  Matmul
+     * and BMM use these directly (Matmul has batch 1; the BMM batch count is always a runtime
+     * value).  For Conv2d they are ignored except m_lo/m_hi, the range of n*P*Q.            */
+    uint32_t m, n, k;
+    uint32_t m_lo, m_hi, n_lo, n_hi, k_lo, k_hi;
+    /* Conv2d (NHWC input, RSCK weights, NHWC fp32 output): space axes (n,p,q,k), reduce axes
+     * (r,s,c) (Fig. 7 caption).  GEMM view: M = n*P*Q, N = c_out, K = r*s*c_in.            */
+    uint32_t c_in, c_out, r, s, stride, pad;
+} ft_op_desc;
+
+typedef struct ft_op ft_op;
+/* desc: host pointer, copied.  *out: new handle, released with ft_op_destroy. */
+ft_status ft_op_register(const ft_op_desc *desc, ft_op **out);
+void ft_op_destroy(ft_op *op);
+
+/* ---------------------------------------------------------------------------------------
+ * (b) uKernel set: HardwareAlign + IsOverflow + Eq. 4 + Eq. 6 (Alg. 1), in canonical order
+ * (larger smem_tile area first).  The shape-dependent filters (CrossPick, SetBound with the
+ * workload's block.bound, Eq. 5) run inside ft_plan.
+ * ------------------------------------------------------------------------------------- */
+typedef struct ft_ukernel_info {
+    uint32_t struct_size;
+    uint32_t id;                   /* index in the set                                       */
+    uint32_t tm, tn, tk;           /* smem_tile: workgroup tile staged in LDS                */
+    uint32_t wm, wn;               /* reg_tile: per-wave fp32 accumulator tile               */
+    uint32_t gm, gn;               /* wave grid (gm*gn = 4 wave64)                           */
+    uint32_t mfma;                 /* 0: 32x32x16, 1: 16x16x32                               */
+    uint32_t stages;               /* LDS buffers                                            */
+    uint32_t lds_bytes;            /* stages*(tm+tn)*tk*2                                    */
+    uint32_t acc_regs;             /* wm*wn/64 per lane                                      */
+    uint32_t regs;                 /* acc_regs + RestRegs                                    */
+    uint32_t max_wg_per_cu;        /* resident workgroups per CU allowed by LDS and registers*/
+    uint32_t reg_budget;           /* registers per lane granted to the body: 128, 256 or 512*/
+    uint64_t cmr_q20;              /* compute_eff (Eq. 6), floor(x * 2^20)                   */
+} ft_ukernel_info;
+
+typedef struct ft_ukset ft_ukset;
+/* hw, tuning: host pointers or NULL for the defaults; copied.  The set keeps a reference to
+ * nothing in op after the call except the copied descriptor. */
+ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tuning *tuning,
+                             ft_ukset **out);
+ft_status ft_ukset_size(const ft_ukset *set, uint32_t *n);
+ft_status ft_ukset_get(const ft_ukset *set, uint32_t i, ft_ukernel_info *out);
+void ft_ukset_destroy(ft_ukset *set);
+
+/* ---------------------------------------------------------------------------------------
+ * (c) Plan.
+ * ------------------------------------------------------------------------------------- */
+typedef struct ft_shape {
+    uint32_t struct_size;
+    uint32_t batch;                /* BMM batch count; ignored for Matmul / Conv2d           */
+    uint32_t m, n, k;              /* dynamic GEMM extents (static ones: 0 or the same value)*/
+    uint32_t img_n, img_h, img_w;  /* Conv2d input: images, height, width                    */
+} ft_shape;
+
+enum {
+    FT_PLAN_PATCHWORK = 0u,        /* Alg. 2 pool + SIA Top-1                                */
+    FT_PLAN_PAD_BASELINE = 1u,     /* pad every dynamic axis to the largest uKernel (Fig. 2) */
+    FT_PLAN_FORCED = 2u,           /* take the program given in ft_forced_program            */
+    FT_PLAN_MODE_MASK = 3u,
+    FT_PLAN_HOST_ONLY = 16u        /* no device table; the plan cannot be launched           */
+};
+
+/* Program to build when the mode is FT_PLAN_FORCED (used to measure every program of the
+ * pool against its SIA score, Sec. 6.3): count1 tiles of uKernel k1 along the main axis,
+ * then count2 of k2 (count2 = 0: single uKernel).  The counts must cover the granule-rounded
+ * main-axis extent exactly. */
+typedef struct ft_forced_program {
+    uint32_t struct_size;
+    uint32_t k1, count1, k2, count2;
+} ft_forced_program;
+
+/* Tile descriptor: one workgroup's work.  24 bytes, little endian, compared byte for byte
+ * with the planner oracle.  Order in the table: ukernel_id, batch, m0, n0 ascending. */
+typedef struct ft_tile_desc {
+    uint32_t ukernel_id;           /* index into the uKernel set                             */
+    uint32_t batch;
+    uint32_t m0, n0;               /* tile origin in the GEMM view                           */
+    uint16_t m_valid, n_valid;     /* min(tm, M - m0), min(tn, N - n0)                       */
+    uint32_t flags;                /* bit 0: edge tile (some rows/columns predicated off)    */
+} ft_tile_desc;
+
+typedef struct ft_plan_stats {
+    uint32_t struct_size;
+    uint32_t tau;                  /* main axis: 0 rows (M), 1 columns (N)                   */
+    uint32_t batch, m, n, k;       /* resolved GEMM view                                     */
+    uint32_t n_ukernels;           /* 0 (empty plan), 1 or 2                                 */
+    uint32_t ukernel_id[2];        /* ascending                                              */
+    uint32_t count_tau[2];         /* Num1, Num2 of Alg. 2 in the same order                 */
+    uint32_t block_bound;          /* min(K.wkl.block, zeta)                                 */
+    uint32_t pool_size;            /* programs in uProg                                      */
+    uint32_t level;                /* 0: bound+CrossPick+Eq.5, 1: bound+CrossPick, 2: bound, 3: none */
+    uint32_t pad_q20, occ_q20, cmr_q20;   /* Eq. 2, Eq. 3, normalised Eq. 6; floor(x * 2^20) */
+    uint32_t lds_bytes;            /* dynamic LDS of the launch                              */
+    uint32_t kernel_class;         /* which dispatcher kernel runs the plan                  */
+    uint64_t sia_q20;              /* Eq. 1                                                  */
+    uint64_t n_tiles;
+    uint64_t useful_elems;         /* batch*M*N                                              */
+    uint64_t covered_elems;        /* sum of tm*tn over all tiles                            */
+} ft_plan_stats;
+
+typedef struct ft_plan ft_plan;
+/* op, set, shape: host pointers.  forced: host pointer, read only in mode FT_PLAN_FORCED, else
+ * may be NULL.  Unless FT_PLAN_HOST_ONLY is set the descriptor table is also copied to the
+ * current HIP device (one hipMalloc + one synchronous hipMemcpy).  Plans are immutable and may
+ * be launched any number of times. */
+ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
+                         const ft_forced_program *forced, ft_plan **out);
+/* *descs: host pointer to library-owned memory, valid until ft_plan_destroy. */
+ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, uint64_t *n);
+ft_status ft_plan_stats_get(const ft_plan *plan, ft_plan_stats *out);
+void ft_plan_destroy(ft_plan *plan);
+
+/* Scores of every program of the pool for one shape (Sec. 5.1 pool, Sec. 5.2 evaluation):
+ * fills up to cap entries of out (host pointer) and stores the pool size in *n. */
+typedef struct ft_pool_entry {
+    uint32_t k1, count1, k2, count2;       /* k2 = UINT32_MAX for a single-uKernel program   */
+    uint32_t pad_q20, occ_q20, cmr_q20;
+    uint32_t flags;                        /* bit0 in_bound, bit1 CrossPick, bit2 Eq. 5      */
+    uint64_t sia_q20;
+    uint64_t n_tiles;
+} ft_pool_entry;
+ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *shape,
+                       ft_pool_entry *out, uint32_t cap, uint32_t *n);
+
+/* ---------------------------------------------------------------------------------------
+ * (d) Launch: ONE kernel launch; workgroup i runs the uKernel body named by descriptor i.
+ *   Matmul: A [M,K], B [K,N] row-major 16-bit; C [M,N] row-major fp32.
+ *   BMM:    A [batch,M,K], B [batch,K,N], C [batch,M,N], densely packed.
+ *   Conv2d: A = X [n,H,W,c_in], B = W [r,s,c_in,c_out], C = Y [n,P,Q,c_out] fp32.
+ * A, B, C: device pointers owned by the caller (A, B at least 2-byte aligned, C 4-byte
+ * aligned; 16-byte aligned A/B with row lengths that are multiples of 8 take the vector
+ * path).  hip_stream: a hipStream_t (NULL = default stream).  Asynchronous; allocates
+ * nothing and does not synchronise.  An empty plan launches nothing.
+ * ------------------------------------------------------------------------------------- */
+ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, void *hip_stream);
+
+/* Timing helper for benchmarks: launches the plan `iters` times back to back on hip_stream,
+ * launch i using buffer set i % n_sets (A, B, C: host arrays of n_sets device pointers; rotating
+ * over many sets keeps operands out of the caches), between two HIP events recorded on that same
+ * stream; waits for the second event and stores the mean milliseconds per launch in
+ * *ms_per_launch (host pointer). */
+ft_status ft_launch_timed(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
+                          uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTUNER_H */

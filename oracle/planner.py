@@ -155,6 +155,7 @@ class UKernel:
     lds_bytes: int
     acc_regs: int
     regs: int
+    reg_budget: int  # register allocation of the kernel the body is compiled into
     max_wg_per_cu: int
     cmr_q: int
     id: int = -1
@@ -229,6 +230,17 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw):
     return flops * mem_den, hw["mfma_flops_per_clk_per_cu"] * mem_num
 
 
+def reg_budget(regs, hw):
+    """Registers are granted per wave in power-of-two fractions of the file that a whole
+    number of waves can share: regs_per_lane / 4, / 2, / 1 (128, 256, 512 on gfx950).  The
+    budget of a uKernel is the smallest such fraction holding reg_tile + RestRegs; it is
+    the K.RegsInBlock / lanes of Eq. 4."""
+    b = hw["regs_per_lane"] // 4
+    while b < regs:
+        b *= 2
+    return b
+
+
 def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     """HardwareAlign + the shape-independent filters (IsOverflow, Eq. 4 at block.bound = 1,
     Eq. 6), in the canonical set order: larger smem_tile area first."""
@@ -255,13 +267,14 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 regs = acc + t["rest_regs"]
                 if regs * waves_per_simd > hw["regs_per_lane"]:
                     continue                                        # Eq. 4, block.bound = 1
+                budget = reg_budget(regs, hw)
                 cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw)
                 if cn * t["psi_den"] < t["psi_num"] * cd:
                     continue                                        # Eq. 6
-                cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // regs,
+                cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
                           hw["max_waves_per_simd"])
                 cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, mfma, STAGES, lds, acc, regs,
-                                    cap, (cn << Q) // cd))
+                                    budget, cap, (cn << Q) // cd))
     cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))
     for i, u in enumerate(cand):
         u.id = i
@@ -453,7 +466,11 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         pool = [evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
                 for parts in build_pool([_ext(u, tau) for u in uks], Hp)]
         if not pool:
-            raise ValueError("no cover")
+            # Alg. 2 found nothing (the main axis is shorter than every extent the static
+            # axes admit): pad it up to the uKernel with the smallest main-axis extent
+            e_min = min(_ext(u, tau) for u in uks)
+            u = next(u for u in uks if _ext(u, tau) == e_min)
+            pool = [evaluate([(u.id, ceil_div(Hp, e_min))], uks, batch, M, N, tau, hw, t, cap_q)]
         pl.pool_size = len(pool)
         levels = [
             [p for p in pool if p.in_bound and p.cross and p.saturated],

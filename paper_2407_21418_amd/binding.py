@@ -1,0 +1,269 @@
+"""ctypes binding of libftuner.so (see include/ftuner.h for the contract of every call).
+
+Only marshals arguments.  The library must have been built (python -m
+paper_2407_21418_amd.build, or __graft_entry__.build()); a missing library is an error,
+there is no fallback path.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libftuner.so")
+
+FT_OK = 0
+FT_ERR_INVALID_ARG, FT_ERR_UNSUPPORTED, FT_ERR_OUT_OF_RANGE = -1, -2, -3
+FT_ERR_NO_COVER, FT_ERR_HIP, FT_ERR_OOM = -4, -5, -6
+FT_OP_MATMUL, FT_OP_BMM, FT_OP_CONV2D = 0, 1, 2
+FT_F16, FT_BF16 = 0, 1
+FT_PLAN_PATCHWORK, FT_PLAN_PAD_BASELINE, FT_PLAN_FORCED, FT_PLAN_HOST_ONLY = 0, 1, 2, 16
+
+u32, u64, u16 = C.c_uint32, C.c_uint64, C.c_uint16
+
+
+class _S(C.Structure):
+    def __init__(self, **kw):
+        super().__init__()
+        self.struct_size = C.sizeof(self)
+        for k, v in kw.items():
+            setattr(self, k, v)
+
+    def as_dict(self):
+        out = {}
+        for name, _t in self._fields_:
+            v = getattr(self, name)
+            out[name] = list(v) if hasattr(v, "__len__") else v
+        return out
+
+
+class ft_hw_model(_S):
+    _fields_ = [(n, u32) for n in (
+        "struct_size", "num_cus", "simds_per_cu", "wave_size", "regs_per_lane", "max_waves_per_simd",
+        "lds_bytes_per_cu", "clock_mhz", "mfma_flops_per_clk_per_cu", "bw_global_bytes_per_clk_per_cu",
+        "bw_lds_bytes_per_clk_per_cu", "hbm_gbytes_per_s", "num_xcds")]
+
+
+class ft_tuning(_S):
+    _fields_ = [(n, u32) for n in (
+        "struct_size", "eps_min_pm", "eps_max_pm", "eps_step_pm", "lam_max_pm", "lam_min_pm", "lam_step_pm",
+        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2")]
+
+
+class ft_op_desc(_S):
+    _fields_ = [(n, u32) for n in (
+        "struct_size", "kind", "dtype", "m", "n", "k", "m_lo", "m_hi", "n_lo", "n_hi", "k_lo", "k_hi",
+        "c_in", "c_out", "r", "s", "stride", "pad")]
+
+
+class ft_ukernel_info(_S):
+    _fields_ = [(n, u32) for n in (
+        "struct_size", "id", "tm", "tn", "tk", "wm", "wn", "gm", "gn", "mfma", "stages", "lds_bytes",
+        "acc_regs", "regs", "max_wg_per_cu", "reg_budget")] + [("cmr_q20", u64)]
+
+
+class ft_shape(_S):
+    _fields_ = [(n, u32) for n in ("struct_size", "batch", "m", "n", "k", "img_n", "img_h", "img_w")]
+
+
+class ft_forced_program(_S):
+    _fields_ = [(n, u32) for n in ("struct_size", "k1", "count1", "k2", "count2")]
+
+
+class ft_tile_desc(C.Structure):
+    _fields_ = [("ukernel_id", u32), ("batch", u32), ("m0", u32), ("n0", u32),
+                ("m_valid", u16), ("n_valid", u16), ("flags", u32)]
+
+
+class ft_plan_stats(_S):
+    _fields_ = [("struct_size", u32), ("tau", u32), ("batch", u32), ("m", u32), ("n", u32), ("k", u32),
+                ("n_ukernels", u32), ("ukernel_id", u32 * 2), ("count_tau", u32 * 2), ("block_bound", u32),
+                ("pool_size", u32), ("level", u32), ("pad_q20", u32), ("occ_q20", u32), ("cmr_q20", u32),
+                ("lds_bytes", u32), ("kernel_class", u32), ("sia_q20", u64), ("n_tiles", u64),
+                ("useful_elems", u64), ("covered_elems", u64)]
+
+
+class ft_pool_entry(C.Structure):
+    _fields_ = [("k1", u32), ("count1", u32), ("k2", u32), ("count2", u32), ("pad_q20", u32),
+                ("occ_q20", u32), ("cmr_q20", u32), ("flags", u32), ("sia_q20", u64), ("n_tiles", u64)]
+
+
+class FtError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {ft_status_string(status)} ({status})")
+
+
+_lib = None
+
+# every symbol include/ftuner.h declares: name -> (restype, argtypes)
+_P = C.c_void_p
+SYMBOLS = {
+    "ft_status_string": (C.c_char_p, [C.c_int32]),
+    "ft_last_hip_error": (C.c_int32, []),
+    "ft_hw_default_gfx950": (C.c_int32, [C.POINTER(ft_hw_model)]),
+    "ft_hw_query": (C.c_int32, [C.c_int32, C.POINTER(ft_hw_model)]),
+    "ft_tuning_default": (C.c_int32, [C.POINTER(ft_tuning)]),
+    "ft_op_register": (C.c_int32, [C.POINTER(ft_op_desc), C.POINTER(_P)]),
+    "ft_op_destroy": (None, [_P]),
+    "ft_ukernels_derive": (C.c_int32, [_P, C.POINTER(ft_hw_model), C.POINTER(ft_tuning), C.POINTER(_P)]),
+    "ft_ukset_size": (C.c_int32, [_P, C.POINTER(u32)]),
+    "ft_ukset_get": (C.c_int32, [_P, u32, C.POINTER(ft_ukernel_info)]),
+    "ft_ukset_destroy": (None, [_P]),
+    "ft_plan_create": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, C.POINTER(ft_forced_program), C.POINTER(_P)]),
+    "ft_plan_descriptors": (C.c_int32, [_P, C.POINTER(C.POINTER(ft_tile_desc)), C.POINTER(u64)]),
+    "ft_plan_stats_get": (C.c_int32, [_P, C.POINTER(ft_plan_stats)]),
+    "ft_plan_destroy": (None, [_P]),
+    "ft_plan_pool": (C.c_int32, [_P, _P, C.POINTER(ft_shape), C.POINTER(ft_pool_entry), u32, C.POINTER(u32)]),
+    "ft_launch": (C.c_int32, [_P, _P, _P, _P, _P]),
+    "ft_launch_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
+                                    C.POINTER(C.c_float)]),
+}
+
+
+def lib():
+    """Load libftuner.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_21418_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(status, what):
+    if status != FT_OK:
+        raise FtError(status, what)
+
+
+def ft_status_string(status):
+    return lib().ft_status_string(status).decode()
+
+
+def ft_last_hip_error():
+    return lib().ft_last_hip_error()
+
+
+def ft_hw_default_gfx950():
+    hw = ft_hw_model()
+    _check(lib().ft_hw_default_gfx950(C.byref(hw)), "ft_hw_default_gfx950")
+    return hw
+
+
+def ft_hw_query(device=0):
+    hw = ft_hw_model()
+    _check(lib().ft_hw_query(device, C.byref(hw)), "ft_hw_query")
+    return hw
+
+
+def ft_tuning_default():
+    t = ft_tuning()
+    _check(lib().ft_tuning_default(C.byref(t)), "ft_tuning_default")
+    return t
+
+
+class _Handle:
+    _destroy = None
+
+    def __init__(self, ptr):
+        self.ptr = ptr
+
+    def close(self):
+        if self.ptr:
+            getattr(lib(), self._destroy)(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Op(_Handle):
+    _destroy = "ft_op_destroy"
+
+
+class UkSet(_Handle):
+    _destroy = "ft_ukset_destroy"
+
+
+class Plan(_Handle):
+    _destroy = "ft_plan_destroy"
+
+
+def ft_op_register(desc: ft_op_desc) -> Op:
+    out = _P()
+    _check(lib().ft_op_register(C.byref(desc), C.byref(out)), "ft_op_register")
+    op = Op(out.value)
+    op.desc = desc
+    return op
+
+
+def ft_ukernels_derive(op: Op, hw=None, tuning=None) -> UkSet:
+    out = _P()
+    _check(lib().ft_ukernels_derive(op.ptr, C.byref(hw) if hw is not None else None,
+                                    C.byref(tuning) if tuning is not None else None, C.byref(out)),
+           "ft_ukernels_derive")
+    return UkSet(out.value)
+
+
+def ft_ukset_size(s: UkSet) -> int:
+    n = u32()
+    _check(lib().ft_ukset_size(s.ptr, C.byref(n)), "ft_ukset_size")
+    return n.value
+
+
+def ft_ukset_get(s: UkSet, i: int) -> ft_ukernel_info:
+    info = ft_ukernel_info()
+    _check(lib().ft_ukset_get(s.ptr, i, C.byref(info)), "ft_ukset_get")
+    return info
+
+
+def ft_plan_create(op: Op, s: UkSet, shape: ft_shape, flags=FT_PLAN_PATCHWORK, forced=None) -> Plan:
+    out = _P()
+    _check(lib().ft_plan_create(op.ptr, s.ptr, C.byref(shape), flags,
+                                C.byref(forced) if forced is not None else None, C.byref(out)),
+           "ft_plan_create")
+    return Plan(out.value)
+
+
+def ft_plan_descriptors(p: Plan) -> bytes:
+    """The descriptor table as raw bytes (24 bytes per tile, little endian)."""
+    ptr = C.POINTER(ft_tile_desc)()
+    n = u64()
+    _check(lib().ft_plan_descriptors(p.ptr, C.byref(ptr), C.byref(n)), "ft_plan_descriptors")
+    if n.value == 0:
+        return b""
+    return C.string_at(ptr, n.value * C.sizeof(ft_tile_desc))
+
+
+def ft_plan_stats_get(p: Plan) -> ft_plan_stats:
+    st = ft_plan_stats()
+    _check(lib().ft_plan_stats_get(p.ptr, C.byref(st)), "ft_plan_stats_get")
+    return st
+
+
+def ft_plan_pool(op: Op, s: UkSet, shape: ft_shape):
+    n = u32()
+    _check(lib().ft_plan_pool(op.ptr, s.ptr, C.byref(shape), None, 0, C.byref(n)), "ft_plan_pool")
+    arr = (ft_pool_entry * max(1, n.value))()
+    _check(lib().ft_plan_pool(op.ptr, s.ptr, C.byref(shape), arr, n.value, C.byref(n)), "ft_plan_pool")
+    return [arr[i] for i in range(n.value)]
+
+
+def ft_launch(p: Plan, A: int, B: int, Cptr: int, stream: int = 0):
+    """A, B, Cptr: device addresses (e.g. torch.Tensor.data_ptr()); stream: hipStream_t value."""
+    _check(lib().ft_launch(p.ptr, A, B, Cptr, stream), "ft_launch")
+
+
+def ft_launch_timed(p: Plan, A, B, Cs, stream: int, iters: int) -> float:
+    """A, B, Cs: equally long lists of device addresses (rotating buffer sets)."""
+    n = len(A)
+    arr = lambda xs: (_P * n)(*xs)
+    ms = C.c_float()
+    _check(lib().ft_launch_timed(p.ptr, arr(A), arr(B), arr(Cs), n, stream, iters, C.byref(ms)),
+           "ft_launch_timed")
+    return ms.value

@@ -1,0 +1,77 @@
+"""Build libftuner.so (host logic + HIP dispatcher kernels) for gfx950, in-tree.
+
+hipcc cross-compiles without a GPU.  Objects go to paper_2407_21418_amd/_build/, the
+library to paper_2407_21418_amd/libftuner.so.
+"""
+import concurrent.futures as cf
+import os
+import subprocess
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OUT = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libftuner.so")
+INC = os.path.join(os.path.dirname(HERE), "include")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INC, "-I", CSRC,
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+
+
+def _run(cmd, log):
+    t = time.time()
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    lines = [l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l]
+    with open(log, "w") as f:
+        f.write(" ".join(cmd) + "\n" + "\n".join(lines) + "\n")
+    if p.returncode != 0:
+        raise RuntimeError("build step failed: %s\n%s" % (" ".join(cmd), "\n".join(lines[-40:])))
+    return time.time() - t
+
+
+def _stale(obj, srcs):
+    if not os.path.exists(obj):
+        return True
+    t = os.path.getmtime(obj)
+    return any(os.path.getmtime(s) > t for s in srcs)
+
+
+def build(verbose=True, remarks=False, jobs=None, incremental=False):
+    """incremental=True recompiles only objects older than the sources they include."""
+    os.makedirs(OUT, exist_ok=True)
+    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + \
+           [os.path.join(INC, "ftuner.h")]
+    steps = []
+    for dt in (0, 1):
+        for cl in (0, 1, 2):
+            obj = os.path.join(OUT, f"dispatch_dt{dt}_c{cl}.o")
+            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-c",
+                                      os.path.join(CSRC, "dispatch.hip"), "-o", obj]
+            if remarks:
+                cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+            steps.append((obj, cmd))
+    for src in ("host.cpp", "device.hip"):
+        obj = os.path.join(OUT, src.replace(".", "_") + ".o")
+        steps.append((obj, [HIPCC] + COMMON + ["-c", os.path.join(CSRC, src), "-o", obj]))
+    jobs = jobs or min(8, len(steps))
+    todo = steps
+    if incremental:
+        src_of = lambda cmd: cmd[cmd.index("-c") + 1]
+        todo = [(o, c) for o, c in steps if _stale(o, hdrs + [src_of(c)])]
+    with cf.ThreadPoolExecutor(max_workers=jobs) as ex:
+        futs = {ex.submit(_run, cmd, obj + ".log"): obj for obj, cmd in todo}
+        for fut in cf.as_completed(futs):
+            dt = fut.result()
+            if verbose:
+                print(f"  built {os.path.basename(futs[fut])} in {dt:.1f}s", flush=True)
+    link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in steps]
+    _run(link, os.path.join(OUT, "link.log"))
+    if verbose:
+        print("  linked", LIB, flush=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(remarks="--remarks" in sys.argv, incremental="--incremental" in sys.argv)

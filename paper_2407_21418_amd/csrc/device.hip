@@ -1,0 +1,125 @@
+// HIP-facing half of the library: device query, descriptor-table upload and the launch.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "family.h"
+#include "ft_internal.h"
+#include "gemm_body.h"
+#include "launch_iface.h"
+
+namespace {
+
+typedef int (*launch_fn)(const ftk::KArgs *, uint32_t, void *);
+const launch_fn kLaunch[2][FT_NUM_CLASSES] = {
+    {ft_launch_dt0_c0, ft_launch_dt0_c1, ft_launch_dt0_c2},
+    {ft_launch_dt1_c0, ft_launch_dt1_c1, ft_launch_dt1_c2},
+};
+
+static_assert(sizeof(ftk::TileDesc) == sizeof(ft_tile_desc) && sizeof(ft_tile_desc) == 24,
+              "descriptor layout is part of the ABI");
+
+ft_status hip_fail(hipError_t e) {
+    ftd_set_hip_error((int)e);
+    return FT_ERR_HIP;
+}
+
+void fill_args(const ft_plan *p, const void *A, const void *B, void *C, ftk::KArgs *a) {
+    std::memset(a, 0, sizeof(*a));
+    const ft_plan_stats &s = p->st;
+    a->A = static_cast<const uint16_t *>(A);
+    a->B = static_cast<const uint16_t *>(B);
+    a->C = static_cast<float *>(C);
+    a->descs = static_cast<const ftk::TileDesc *>(p->d_descs);
+    a->n_tiles = (uint32_t)s.n_tiles;
+    a->M = s.m; a->N = s.n; a->K = s.k;
+    a->lda = s.k; a->ldb = s.n; a->ldc = s.n;
+    a->strideA = (uint64_t)s.m * s.k;
+    a->strideB = (uint64_t)s.k * s.n;
+    a->strideC = (uint64_t)s.m * s.n;
+    a->is_conv = p->op.kind == FT_OP_CONV2D;
+    if (a->is_conv) {
+        a->H = p->img_h; a->W = p->img_w; a->Cin = p->op.c_in;
+        a->P = p->out_p; a->Q = p->out_q; a->R = p->op.r; a->S = p->op.s;
+        a->cstride = p->op.stride; a->cpad = p->op.pad;
+        a->lda = 0; a->strideA = 0;
+    }
+    a->slot_ukernel[0] = p->slot_id[0]; a->slot_ukernel[1] = p->slot_id[1];
+    a->slot_code[0] = p->slot_code[0]; a->slot_code[1] = p->slot_code[1];
+    a->num_xcds = p->num_xcds;
+}
+
+}  // namespace
+
+ft_status ftd_upload(ft_plan *p) {
+    if (p->descs.empty()) return FT_OK;
+    hipError_t e = hipGetDevice(&p->device);
+    if (e != hipSuccess) return hip_fail(e);
+    size_t bytes = p->descs.size() * sizeof(ft_tile_desc);
+    e = hipMalloc(&p->d_descs, bytes);
+    if (e != hipSuccess) { p->d_descs = nullptr; return e == hipErrorOutOfMemory ? FT_ERR_OOM : hip_fail(e); }
+    e = hipMemcpy(p->d_descs, p->descs.data(), bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(p->d_descs); p->d_descs = nullptr; return hip_fail(e); }
+    return FT_OK;
+}
+
+void ftd_release(ft_plan *p) {
+    if (p->d_descs) { (void)hipFree(p->d_descs); p->d_descs = nullptr; }
+}
+
+extern "C" {
+
+ft_status ft_hw_query(int32_t hip_device, ft_hw_model *out) {
+    if (!out) return FT_ERR_INVALID_ARG;
+    ft_status st = ft_hw_default_gfx950(out);
+    if (st != FT_OK) return st;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, hip_device);
+    if (e != hipSuccess) return hip_fail(e);
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return FT_ERR_UNSUPPORTED;
+    out->num_cus = (uint32_t)prop.multiProcessorCount;
+    out->wave_size = (uint32_t)prop.warpSize;
+    out->clock_mhz = (uint32_t)(prop.clockRate / 1000);
+    out->lds_bytes_per_cu = (uint32_t)prop.sharedMemPerBlock;   // a workgroup may own the whole CU's LDS
+    return FT_OK;
+}
+
+ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, void *hip_stream) {
+    if (!plan) return FT_ERR_INVALID_ARG;
+    if (plan->st.n_tiles == 0) return FT_OK;
+    if (!A || !B || !C) return FT_ERR_INVALID_ARG;
+    if (!plan->d_descs) return FT_ERR_INVALID_ARG;              // host-only plan
+    if (plan->st.kernel_class >= FT_NUM_CLASSES || plan->op.dtype > 1) return FT_ERR_UNSUPPORTED;
+    ftk::KArgs a;
+    fill_args(plan, A, B, C, &a);
+    int rc = kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
+    if (rc != 0) return hip_fail((hipError_t)rc);
+    return FT_OK;
+}
+
+ft_status ft_launch_timed(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
+                          uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch) {
+    if (!plan || !A || !B || !C || !n_sets || !iters || !ms_per_launch) return FT_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventCreate(&e1);
+    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e); }
+    ft_status st = FT_OK;
+    e = hipEventRecord(e0, s);
+    for (uint32_t i = 0; i < iters && st == FT_OK && e == hipSuccess; ++i)
+        st = ft_launch(plan, A[i % n_sets], B[i % n_sets], C[i % n_sets], hip_stream);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != FT_OK) return st;
+    if (e != hipSuccess) return hip_fail(e);
+    *ms_per_launch = ms / (float)iters;
+    return FT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+// One dispatcher kernel per (input dtype, register class).  Workgroup i takes tile descriptor
+// remap(i) and runs the uKernel body the descriptor names, so a single launch executes a
+// program made of one or two uKernel shapes (Sec. 5.1; Fig. 8 item 2).
+// Compiled once per -DFT_DT={0,1} -DFT_CLASS={0,1,2}.
+#include "gemm_body.h"
+#include "family.h"
+#include "launch_iface.h"
+
+#ifndef FT_DT
+#error "define FT_DT"
+#endif
+#ifndef FT_CLASS
+#error "define FT_CLASS"
+#endif
+
+#if FT_CLASS == 0
+#define FT_MIN_WAVES 4
+#define FT_ACC_MAX 64
+#elif FT_CLASS == 1
+#define FT_MIN_WAVES 2
+#define FT_ACC_MAX 128
+#else
+#define FT_MIN_WAVES 1
+#define FT_ACC_MAX 256
+#endif
+
+namespace ftk {
+
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).  Give each
+// XCD one contiguous slice of the descriptor table, so tiles that share an A row panel (and
+// walk the same B columns) meet in the same per-XCD L2.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t b, uint32_t n, uint32_t nx) {
+    uint32_t x = b % nx, j = b / nx;
+    uint32_t q = n / nx, r = n % nx;
+    return x * q + (x < r ? x : r) + j;
+}
+
+__global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t t = xcd_remap(blockIdx.x, g.n_tiles, g.num_xcds);
+    const TileDesc d = g.descs[t];
+    const uint32_t code = (d.ukernel_id == g.slot_ukernel[0]) ? g.slot_code[0] : g.slot_code[1];
+    switch (code) {
+#define FT_X(CODE, WM, WN, GM, GN)                                              \
+    case CODE:                                                                  \
+        if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
+            UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(g, d, smem);         \
+        break;
+        FT_FAMILY(FT_X)
+#undef FT_X
+    default: break;
+    }
+}
+
+}  // namespace ftk
+
+extern "C" int FT_LAUNCH_NAME(const ftk::KArgs *args, uint32_t lds_bytes, void *stream) {
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ftk::FT_KERNEL_NAME),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
+        if (e != hipSuccess) return (int)e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(ftk::FT_KERNEL_NAME, dim3(args->n_tiles), dim3(256), lds_bytes,
+                       static_cast<hipStream_t>(stream), *args);
+    return (int)hipGetLastError();
+}

@@ -1,0 +1,29 @@
+// The compiled uKernel family: every (reg_tile, wave grid) the generator can emit has a body.
+// X(code, WM, WN, GM, GN); TK = 64 for all.  reg_tile = WM x WN per wave, smem_tile =
+// (GM*WM) x (GN*WN) x 64.  Rows of 16 use v_mfma_f32_16x16x32, all others v_mfma_f32_32x32x16.
+#pragma once
+#define FT_FAMILY(X)                                                                     \
+    X(0, 16, 16, 1, 4)   X(1, 16, 16, 2, 2)   X(2, 16, 16, 4, 1)                         \
+    X(3, 16, 32, 1, 4)   X(4, 16, 32, 2, 2)   X(5, 16, 32, 4, 1)                         \
+    X(6, 16, 64, 1, 4)   X(7, 16, 64, 2, 2)   X(8, 16, 64, 4, 1)                         \
+    X(9, 32, 32, 1, 4)   X(10, 32, 32, 2, 2)  X(11, 32, 32, 4, 1)                        \
+    X(12, 32, 64, 1, 4)  X(13, 32, 64, 2, 2)  X(14, 32, 64, 4, 1)                        \
+    X(15, 64, 32, 1, 4)  X(16, 64, 32, 2, 2)  X(17, 64, 32, 4, 1)                        \
+    X(18, 64, 64, 1, 4)  X(19, 64, 64, 2, 2)  X(20, 64, 64, 4, 1)                        \
+    X(21, 64, 128, 1, 4) X(22, 64, 128, 2, 2) X(23, 64, 128, 4, 1)                       \
+    X(24, 128, 64, 1, 4) X(25, 128, 64, 2, 2) X(26, 128, 64, 4, 1)                       \
+    X(27, 128, 128, 1, 4) X(28, 128, 128, 2, 2) X(29, 128, 128, 4, 1)
+
+#define FT_TK 64
+#define FT_NUM_CLASSES 3
+// register class of a body: accumulator registers per lane -> launch-bounds budget
+//   class 0: acc <= 64  (kernel compiled for 4 waves/SIMD, <= 128 registers)
+//   class 1: acc <= 128 (2 waves/SIMD, <= 256 registers)
+//   class 2: acc <= 256 (1 wave/SIMD,  <= 512 registers)
+static inline int ft_class_of_acc(int acc_regs) { return acc_regs <= 64 ? 0 : (acc_regs <= 128 ? 1 : 2); }
+static inline int ft_body_code(int wm, int wn, int gm, int gn) {
+#define FT_X(code, WM, WN, GM, GN) if (wm == WM && wn == WN && gm == GM && gn == GN) return code;
+    FT_FAMILY(FT_X)
+#undef FT_X
+    return -1;
+}

@@ -1,0 +1,36 @@
+// Internal types shared by the host logic (host.cpp) and the HIP-facing code (device.hip).
+#pragma once
+#include <stdint.h>
+#include <vector>
+
+#include "ftuner.h"
+
+struct ft_op {
+    ft_op_desc d;
+};
+
+struct ft_ukset {
+    ft_op_desc op;
+    ft_hw_model hw;
+    ft_tuning t;
+    std::vector<ft_ukernel_info> uk;   // canonical order
+    uint64_t cap_q;                    // best compute_eff of the set (normaliser of Eq. 1's CMR term)
+};
+
+struct ft_plan {
+    ft_op_desc op;
+    ft_plan_stats st;
+    std::vector<ft_tile_desc> descs;
+    // launch parameters
+    uint32_t slot_id[2];
+    uint32_t slot_code[2];
+    uint32_t num_xcds;
+    uint32_t img_h, img_w, out_p, out_q;   // conv geometry
+    void *d_descs;                          // device copy of descs (NULL for host-only / empty plans)
+    int device;
+};
+
+// device.hip
+ft_status ftd_upload(ft_plan *p);
+void ftd_release(ft_plan *p);
+void ftd_set_hip_error(int e);

@@ -1,0 +1,329 @@
+// uKernel bodies for gfx950: one workgroup (4 wave64, one per SIMD) computes one output tile
+//   C[m0:m0+TM, n0:n0+TN] (+batch) = sum_k A * B          (Sec. 3: uKernel = thread block)
+// with v_mfma_f32_32x32x16 / v_mfma_f32_16x16x32 (f16 or bf16 in, fp32 accumulate).
+//
+// The tiling hierarchy of Fig. 7: block-level tile (i.0, j.0) = one tile descriptor;
+// LDS tile (i.1, j.1) = TM x TN x TK staged in LDS, double buffered along k; register tile
+// (i.2, j.2) = the WM x WN fp32 accumulator block each wave keeps in VGPR/AGPR.
+//
+// LDS layout (16-byte chunks = 8 elements):
+//   A tile  [TM rows][TK]  k-contiguous, row pitch 128 B, chunk position = kc ^ swzA(row)
+//   B tile  [TK rows][TN]  n-contiguous as in memory (no transpose on the way in), row pitch
+//           2*TN B, chunk position = nc ^ swzB(row).  The MFMA B operand wants 8 consecutive
+//           k per lane; ds_read_b64_tr_b16 transposes 4 rows x 16 columns on the way out.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+namespace ftk {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+struct TileDesc {            // mirrors the 24-byte descriptor of the C ABI
+    uint32_t ukernel_id, batch, m0, n0;
+    uint16_t m_valid, n_valid;
+    uint32_t flags;
+};
+
+struct KArgs {
+    const uint16_t *A;
+    const uint16_t *B;
+    float *C;
+    const TileDesc *descs;
+    uint32_t n_tiles;
+    uint32_t M, N, K;                 // GEMM view
+    uint32_t lda, ldb, ldc;           // row pitches in elements
+    uint64_t strideA, strideB, strideC;   // per-batch strides in elements
+    uint32_t is_conv;
+    uint32_t H, W, Cin, P, Q, R, S, cstride, cpad;   // conv geometry (A = NHWC image)
+    uint32_t slot_ukernel[2];         // uKernel ids of the plan's (up to) two constituents
+    uint32_t slot_code[2];            // their body codes in the compiled family
+    uint32_t num_xcds;
+};
+
+enum { DT_F16 = 0, DT_BF16 = 1 };
+
+template <int DT> __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
+    if constexpr (DT == DT_F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                       __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+template <int DT> __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
+    if constexpr (DT == DT_F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                       __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// XOR swizzles on the 16-byte chunk index.  A: 128-byte rows; 16 consecutive rows at one
+// logical chunk land on 16 distinct bank quads whether the LDS resolves 8 or 16 lanes per
+// cycle.  B: keeps 32-byte pairs together (one transposing read covers 2 chunks of 4 rows).
+__device__ __forceinline__ uint32_t swzA(uint32_t row) { return (row ^ ((row >> 3) & 1u)) & 7u; }
+template <int TN> __device__ __forceinline__ uint32_t swzB(uint32_t row) {
+    if constexpr (TN >= 128) return (row & 3u) << 2;
+    else if constexpr (TN == 64) return ((row >> 1) & 1u) << 2;
+    else return 0u;
+}
+
+__device__ __forceinline__ uint4 ld16(const uint16_t *p) {
+    return *reinterpret_cast<const uint4 *>(p);      // global_load_dwordx4; any 2-byte alignment
+}
+
+// 8 elements starting at p, of which the first nvalid (0..8) exist; the rest read as zero.
+__device__ __forceinline__ uint4 ld_partial(const uint16_t *p, int nvalid) {
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (e < nvalid) w[e >> 1] |= (uint32_t)p[e] << ((e & 1) * 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int DT, int WM, int WN, int GM, int GN, int TK>
+struct UKernelBody {
+    static constexpr int TM = GM * WM, TN = GN * WN;
+    static constexpr bool M16 = (WM == 16);
+    static constexpr int MB = M16 ? 16 : 32;          // MFMA output block edge
+    static constexpr int KSTEP = M16 ? 32 : 16;       // k per MFMA
+    static constexpr int BM = WM / MB, BN = WN / MB;  // accumulator blocks per wave
+    static constexpr int NTHREADS = 256;
+    static constexpr int A_CHUNKS = TM * TK / 8, B_CHUNKS = TK * TN / 8;
+    static constexpr int A_ITERS = (A_CHUNKS + NTHREADS - 1) / NTHREADS;
+    static constexpr int B_ITERS = (B_CHUNKS + NTHREADS - 1) / NTHREADS;
+    static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TK * TN * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static constexpr int KCH = TK / 8;                // chunks per A row
+    static constexpr int NCH = TN / 8;                // chunks per B row
+    static_assert(TK == 64, "A-tile swizzle assumes 128-byte rows");
+    static_assert(GM * GN == 4, "four waves per workgroup");
+
+    using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
+
+    __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem) {
+        const uint32_t tid = threadIdx.x;
+        const uint32_t lane = tid & 63u, wave = tid >> 6;
+        const uint32_t wave_m = wave / GN, wave_n = wave % GN;
+        const uint32_t m0 = d.m0, n0 = d.n0;
+        const uint32_t M = g.M, N = g.N, K = g.K;
+        const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
+        const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
+        float *__restrict__ Cb = g.C + (uint64_t)d.batch * g.strideC;
+
+        // ---- per-thread copy assignments (loop invariant) -------------------------------
+        // A copy: iteration i moves chunk (row0 + 32*i, kc); 32 rows keep the swizzle phase.
+        uint32_t a_off[A_ITERS];                      // element offset of the chunk at k = 0
+        uint32_t a_pix[A_ITERS];                      // conv: packed (p, q) origin
+        const bool a_on = (A_CHUNKS % NTHREADS == 0) || tid < (uint32_t)A_CHUNKS;
+        const uint32_t a_row0 = (tid / KCH) % TM, a_kc = tid % KCH;
+        const uint32_t a_lds0 = a_row0 * (TK * 2) + ((a_kc ^ swzA(a_row0)) << 4);
+        constexpr int A_RSTEP = NTHREADS / KCH;       // 32 rows per iteration
+#pragma unroll
+        for (int i = 0; i < A_ITERS; ++i) {
+            const uint32_t kc = a_kc;
+            uint32_t gm = m0 + a_row0 + i * A_RSTEP;
+            if (gm >= M) gm = M - 1;                  // clamp: garbage rows are never stored
+            if (!g.is_conv) {
+                a_off[i] = gm * g.lda + kc * 8;
+                a_pix[i] = 0;
+            } else {
+                uint32_t img = gm / (g.P * g.Q), rem = gm % (g.P * g.Q);
+                uint32_t p = rem / g.Q, q = rem % g.Q;
+                a_off[i] = img * g.H * g.W * g.Cin;   // image base
+                a_pix[i] = (p * g.cstride) << 16 | (q * g.cstride);
+            }
+        }
+        // B copy: iteration i moves chunk (krow0 + i*B_RSTEP, nc); the swizzle only depends on
+        // row bits that B_RSTEP (a multiple of 4) leaves alone, so one base address serves all i.
+        constexpr int B_RSTEP = (NTHREADS / NCH) > 0 ? (NTHREADS / NCH) : 1;
+        static_assert(B_RSTEP % 4 == 0, "row step must keep the B swizzle phase");
+        const bool b_on = (B_CHUNKS % NTHREADS == 0) || tid < (uint32_t)B_CHUNKS;
+        const uint32_t b_krow0 = (tid / NCH) % TK, b_nc = tid % NCH;
+        const uint32_t b_col = n0 + b_nc * 8;
+        const uint32_t b_ccol = (b_col + 8 <= N) ? b_col : n0;   // clamp: garbage columns are never stored
+        const uint32_t b_off0 = b_krow0 * g.ldb + b_ccol;
+        const uint32_t b_lds0 = A_BYTES + b_krow0 * (TN * 2) + ((b_nc ^ swzB<TN>(b_krow0)) << 4);
+        const uint32_t b_rstep_ld = B_RSTEP * g.ldb;
+        // every B chunk of this tile is wholly inside or wholly outside [0, N)
+        const bool b_fast = (N % 8 == 0) || (n0 + TN <= N);
+        const bool a_vec_conv = (g.Cin % 8 == 0);
+
+        // ---- fragment read addresses (loop invariant apart from the k step) -------------
+        // A operand: lane holds 8 consecutive k of one row.
+        //   32x32x16: row = lane % 32, k chunk = 2*ks + lane / 32
+        //   16x16x32: row = lane % 16, k chunk = 4*ks + lane / 16
+        uint32_t fa_row[BM];
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi) fa_row[bi] = wave_m * WM + bi * MB + (lane % MB);
+        const uint32_t fa_kc = lane / MB;
+        // B operand through the transposing read: a 16-lane group fetches 4 k-rows x 16 columns;
+        // lane j of the group supplies the address of row j/4, columns 4*(j%4)..+3 and receives
+        // column j, rows 0..3.  Group -> (column half, k half) as the MFMA operand layout asks.
+        const uint32_t j16 = lane & 15u;
+        uint32_t fb_colgrp, fb_k8;                     // 16-column group inside the block; k offset / 8
+        if constexpr (M16) { fb_colgrp = 0; fb_k8 = lane >> 4; }
+        else { fb_colgrp = (lane >> 4) & 1u; fb_k8 = lane >> 5; }
+        const uint32_t fb_rowin = j16 >> 2;            // row inside the 4-row group
+        const uint32_t fb_cole = (j16 & 3u) * 4;       // element column inside the 16-col group
+
+        Acc acc[BM][BN];
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
+
+        uint4 ra[A_ITERS], rb[B_ITERS];
+
+        auto load_a = [&](uint32_t k0, bool careful) {
+            if (!a_on) return;
+            const uint32_t kk = k0 + a_kc * 8;
+#pragma unroll
+            for (int i = 0; i < A_ITERS; ++i) {
+                if (!g.is_conv) {
+                    const uint16_t *p = Ab + a_off[i] + k0;
+                    if (!careful || kk + 8 <= K) ra[i] = ld16(p);
+                    else ra[i] = ld_partial(p, kk < K ? (int)(K - kk) : 0);
+                } else {
+                    // k = (r*S + s)*Cin + c ; input pixel (p*stride - pad + r, q*stride - pad + s)
+                    uint32_t p0 = a_pix[i] >> 16, q0 = a_pix[i] & 0xffffu;
+                    if (a_vec_conv) {
+                        uint32_t tap = kk / g.Cin, ch = kk % g.Cin;
+                        uint32_t r = tap / g.S, s = tap % g.S;
+                        int h = (int)(p0 + r) - (int)g.cpad, w = (int)(q0 + s) - (int)g.cpad;
+                        bool ok = kk < K && h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W;
+                        ra[i] = ok ? ld16(Ab + a_off[i] + ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch)
+                                   : make_uint4(0, 0, 0, 0);
+                    } else {
+                        uint32_t wv[4] = {0u, 0u, 0u, 0u};
+                        for (int e = 0; e < 8; ++e) {
+                            uint32_t ke = kk + e;
+                            uint32_t tap = ke / g.Cin, ch = ke % g.Cin;
+                            uint32_t r = tap / g.S, s = tap % g.S;
+                            int h = (int)(p0 + r) - (int)g.cpad, w = (int)(q0 + s) - (int)g.cpad;
+                            if (ke < K && h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W)
+                                wv[e >> 1] |= (uint32_t)Ab[a_off[i] + ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch]
+                                              << ((e & 1) * 16);
+                        }
+                        ra[i] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                    }
+                }
+            }
+        };
+        auto load_b = [&](uint32_t k0, bool careful) {
+            if (!b_on) return;
+            const uint16_t *pk = Bb + k0 * g.ldb;
+#pragma unroll
+            for (int i = 0; i < B_ITERS; ++i) {
+                const uint16_t *p = pk + (b_off0 + i * b_rstep_ld);
+                if (!careful) { rb[i] = ld16(p); continue; }
+                uint32_t kr = k0 + b_krow0 + i * B_RSTEP;
+                if (kr >= K) rb[i] = make_uint4(0, 0, 0, 0);
+                else if (b_col + 8 <= N) rb[i] = ld16(p);
+                else if (b_col < N) rb[i] = ld_partial(Bb + (kr * g.ldb + b_col), (int)(N - b_col));
+                else rb[i] = make_uint4(0, 0, 0, 0);
+            }
+        };
+        auto store_lds = [&](uint32_t stage) {
+            unsigned char *base = smem + stage * STAGE_BYTES;
+            if (a_on) {
+#pragma unroll
+                for (int i = 0; i < A_ITERS; ++i)
+                    *reinterpret_cast<uint4 *>(base + a_lds0 + i * (A_RSTEP * TK * 2)) = ra[i];
+            }
+            if (b_on) {
+#pragma unroll
+                for (int i = 0; i < B_ITERS; ++i)
+                    *reinterpret_cast<uint4 *>(base + b_lds0 + i * (B_RSTEP * TN * 2)) = rb[i];
+            }
+        };
+        auto compute = [&](uint32_t stage) {
+            const unsigned char *sa = smem + stage * STAGE_BYTES;
+            const unsigned char *sb = sa + A_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < TK / KSTEP; ++ks) {
+                uint4 fa[BM], fb[BN];
+#pragma unroll
+                for (int bi = 0; bi < BM; ++bi) {
+                    uint32_t kc = ks * (KSTEP / 8) + fa_kc;
+                    fa[bi] = *reinterpret_cast<const uint4 *>(sa + fa_row[bi] * (TK * 2) +
+                                                              ((kc ^ swzA(fa_row[bi])) << 4));
+                }
+#pragma unroll
+                for (int bj = 0; bj < BN; ++bj) {
+                    uint32_t col = wave_n * WN + bj * MB + fb_colgrp * 16 + fb_cole;
+                    uint32_t nc = col >> 3, cin = (col & 7u) * 2;
+                    s16x4 h[2];
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        uint32_t row = ks * KSTEP + fb_k8 * 8 + hh * 4 + fb_rowin;
+                        uint32_t off = row * (TN * 2) + ((nc ^ swzB<TN>(row)) << 4) + cin;
+                        h[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(sb + off));
+                    }
+                    uint2 lo = __builtin_bit_cast(uint2, h[0]), hi = __builtin_bit_cast(uint2, h[1]);
+                    fb[bj] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                }
+#pragma unroll
+                for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+                    for (int bj = 0; bj < BN; ++bj) {
+                        if constexpr (M16) acc[bi][bj] = mfma16<DT>(fa[bi], fb[bj], acc[bi][bj]);
+                        else acc[bi][bj] = mfma32<DT>(fa[bi], fb[bj], acc[bi][bj]);
+                    }
+            }
+        };
+
+        // ---- main loop: double-buffered LDS, global loads of tile kt+1 overlap MFMA of kt ----
+        const uint32_t nk = (K + TK - 1) / TK;
+        const bool k_tail = (K % TK) != 0;
+        if (nk > 0) {
+            const bool tail0 = (nk == 1) && k_tail;
+            load_a(0, tail0);
+            load_b(0, tail0 || !b_fast);
+            store_lds(0);
+            __syncthreads();
+            for (uint32_t kt = 0; kt < nk; ++kt) {
+                const bool more = kt + 1 < nk;
+                if (more) {
+                    bool last = (kt + 2 == nk) && k_tail;
+                    load_a((kt + 1) * TK, last);
+                    load_b((kt + 1) * TK, last || !b_fast);
+                }
+                compute(kt & 1u);
+                if (more) store_lds((kt + 1) & 1u);
+                __syncthreads();
+            }
+        }
+
+        // ---- epilogue: fp32 store with row / column predication --------------------------
+        // 32x32 block: acc[4*i + j] -> row 8*i + 4*(lane/32) + j, column lane % 32
+        // 16x16 block: acc[j]       -> row 4*(lane/16) + j,        column lane % 16
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) {
+                uint32_t col = n0 + wave_n * WN + bj * MB + (lane % MB);
+                uint32_t rbase = m0 + wave_m * WM + bi * MB;
+                if (col >= N) continue;
+#pragma unroll
+                for (int e = 0; e < (M16 ? 4 : 16); ++e) {
+                    uint32_t row = M16 ? rbase + 4 * (lane / 16) + e
+                                       : rbase + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
+                    if (row < M) Cb[row * g.ldc + col] = acc[bi][bj][e];
+                }
+            }
+    }
+};
+
+}  // namespace ftk

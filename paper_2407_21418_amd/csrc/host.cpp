@@ -1,0 +1,595 @@
+// Host half of the library: hardware model, uKernel-set generator (compile stage, Sec. 4) and
+// runtime planner (Sec. 5).  Integer arithmetic throughout: every cached metric is the floor of
+// an exact rational times 2^20, so plans are reproducible bit for bit.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "family.h"
+#include "ft_internal.h"
+
+namespace {
+
+typedef unsigned __int128 u128;
+constexpr uint32_t QBITS = 20;
+constexpr uint32_t GRANULE = 16;      // smallest MFMA output extent (16x16x32)
+constexpr uint32_t ELT = 2;           // bytes per input element
+constexpr uint32_t STAGES = 2;
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+inline uint64_t ceil_by(uint64_t x, uint64_t m) { return m * ceil_div(x, m); }
+
+void hw_defaults(ft_hw_model *h) {
+    std::memset(h, 0, sizeof(*h));
+    h->struct_size = sizeof(*h);
+    h->num_cus = 256;
+    h->simds_per_cu = 4;
+    h->wave_size = 64;
+    h->regs_per_lane = 512;
+    h->max_waves_per_simd = 8;
+    h->lds_bytes_per_cu = 163840;
+    h->clock_mhz = 2400;
+    h->mfma_flops_per_clk_per_cu = 4096;
+    h->bw_global_bytes_per_clk_per_cu = 64;
+    h->bw_lds_bytes_per_clk_per_cu = 128;
+    h->hbm_gbytes_per_s = 8000;
+    h->num_xcds = 8;
+}
+
+void tuning_defaults(ft_tuning *t) {
+    std::memset(t, 0, sizeof(*t));
+    t->struct_size = sizeof(*t);
+    t->eps_min_pm = 500; t->eps_max_pm = 950; t->eps_step_pm = 10;   // Sec. 4.2: 50%..95%, +1%
+    t->lam_max_pm = 950; t->lam_min_pm = 900; t->lam_step_pm = 1;    // 95%..90%, -0.1%
+    t->zeta = 2;                                                     // Sec. 4.2
+    t->rest_regs = 64;
+    t->psi_num = 1; t->psi_den = 8;
+    t->c0 = t->c1 = t->c2 = 1;                                       // Sec. 5.2
+}
+
+struct Gemm {                // GEMM view of an operator: static extents (0 = dynamic)
+    uint32_t m, n, k;
+};
+
+Gemm static_view(const ft_op_desc &d) {
+    if (d.kind == FT_OP_CONV2D) return {0u, d.c_out, d.r * d.s * d.c_in};
+    return {d.m, d.n, d.k};
+}
+
+// Eq. 6 / Eq. 7: compute_eff = (FLOPs / FLOPS) : max(global time, LDS time), as num/den.
+void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint64_t kref, const ft_hw_model &hw,
+                 u128 *num, u128 *den) {
+    u128 flops = (u128)2 * tm * tn * kref;
+    u128 data_r = (u128)(tm + tn) * kref * ELT;
+    u128 data_w = (u128)tm * tn * 4;
+    u128 data_tw = data_r;
+    u128 data_tr = (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
+    u128 g_num = data_r + data_w, g_den = hw.bw_global_bytes_per_clk_per_cu;
+    u128 s_num = data_tw + data_tr, s_den = hw.bw_lds_bytes_per_clk_per_cu;
+    u128 mem_num, mem_den;
+    if (g_num * s_den >= s_num * g_den) { mem_num = g_num; mem_den = g_den; }
+    else { mem_num = s_num; mem_den = s_den; }
+    *num = flops * mem_den;
+    *den = (u128)hw.mfma_flops_per_clk_per_cu * mem_num;
+}
+
+struct Part { uint32_t id, count; };
+
+struct Program {
+    Part part[2];
+    uint32_t nparts;
+    int64_t k1, k2;           // pool identity (k2 = -1: single)
+    uint64_t tiles, area;
+    uint32_t block_bound;
+    bool in_bound, cross, saturated;
+    uint32_t pad_q, occ_q, cmr_q;
+    uint64_t sia_q;
+};
+
+inline uint32_t ext(const ft_ukernel_info &u, uint32_t axis) { return axis == 0 ? u.tm : u.tn; }
+
+bool cross_pick(u128 pn, u128 pd, u128 on, u128 od, const ft_tuning &t) {
+    // lock-step staircase: eps up, lambda down, until either bound is passed (Alg. 1)
+    uint32_t eps = t.eps_min_pm;
+    int64_t lam = t.lam_max_pm;
+    if (t.eps_step_pm == 0 && t.lam_step_pm == 0)
+        return 1000 * pn >= (u128)eps * pd && 1000 * on >= (u128)lam * od;
+    while (eps <= t.eps_max_pm && lam >= (int64_t)t.lam_min_pm) {
+        if (1000 * pn >= (u128)eps * pd && 1000 * on >= (u128)lam * od) return true;
+        eps += t.eps_step_pm;
+        lam -= t.lam_step_pm;
+    }
+    return false;
+}
+
+void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint64_t N, uint32_t tau) {
+    const ft_hw_model &hw = set.hw;
+    const ft_tuning &t = set.t;
+    uint64_t Wp = ceil_by(tau == 0 ? N : M, GRANULE);
+    uint64_t per_batch = 0, area = 0;
+    for (uint32_t i = 0; i < p.nparts; ++i) {
+        const ft_ukernel_info &u = set.uk[p.part[i].id];
+        uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
+        per_batch += p.part[i].count * across;
+        area += p.part[i].count * across * u.tm * u.tn;
+    }
+    p.tiles = batch * per_batch;
+    p.area = area;
+    uint64_t need = std::max<uint64_t>(1, ceil_div(p.tiles, hw.num_cus));          // K.wkl.block
+    p.block_bound = (uint32_t)std::min<uint64_t>(need, t.zeta);                     // SetBound
+    p.in_bound = true;
+    for (uint32_t i = 0; i < p.nparts; ++i)
+        if (set.uk[p.part[i].id].max_wg_per_cu < p.block_bound) p.in_bound = false;
+    uint64_t slots = (uint64_t)hw.num_cus * p.block_bound;
+    u128 on = p.tiles, od = ceil_by(p.tiles, slots);                                // Eq. 3
+    u128 pn = (u128)M * N, pd = area;                                               // Eq. 2
+    p.occ_q = (uint32_t)((on << QBITS) / od);
+    p.pad_q = (uint32_t)((pn << QBITS) / pd);
+    p.cross = cross_pick(pn, pd, on, od, t);
+    p.saturated = p.tiles >= (uint64_t)t.zeta * hw.num_cus;                         // Eq. 5
+    uint64_t acc = 0;
+    for (uint32_t i = 0; i < p.nparts; ++i) {
+        uint64_t c = std::min<uint64_t>(set.uk[p.part[i].id].cmr_q20, set.cap_q);
+        acc += (uint64_t)(((u128)c << QBITS) / set.cap_q);
+    }
+    p.cmr_q = (uint32_t)(acc / p.nparts);
+    p.sia_q = (uint64_t)t.c0 * p.cmr_q + (uint64_t)t.c1 * p.pad_q + (uint64_t)t.c2 * p.occ_q;   // Eq. 1
+    if (p.nparts == 2 && p.part[0].id > p.part[1].id) std::swap(p.part[0], p.part[1]);
+}
+
+// Alg. 2 over the set's main-axis extents on the granule-rounded size Hp (last-success form).
+void build_pool(const ft_ukset &set, uint64_t Hp, uint32_t tau, std::vector<Program> &pool) {
+    const size_t n = set.uk.size();
+    for (size_t i1 = 0; i1 < n; ++i1) {
+        uint64_t e1 = ext(set.uk[i1], tau);
+        if (Hp % e1 == 0) {
+            Program p{};
+            p.nparts = 1;
+            p.part[0] = {(uint32_t)i1, (uint32_t)(Hp / e1)};
+            p.k1 = (int64_t)i1; p.k2 = -1;
+            pool.push_back(p);
+            continue;
+        }
+        for (uint64_t n1 = Hp / e1; n1 >= 1; --n1) {
+            uint64_t rem = Hp - n1 * e1;
+            bool found = false;
+            for (size_t i2 = 0; i2 < n; ++i2) {
+                uint64_t e2 = ext(set.uk[i2], tau);
+                if (e2 != e1 && rem % e2 == 0) {
+                    Program p{};
+                    p.nparts = 2;
+                    p.part[0] = {(uint32_t)i1, (uint32_t)n1};
+                    p.part[1] = {(uint32_t)i2, (uint32_t)(rem / e2)};
+                    p.k1 = (int64_t)i1; p.k2 = (int64_t)i2;
+                    pool.push_back(p);
+                    found = true;
+                }
+            }
+            if (found) break;
+        }
+    }
+}
+
+uint32_t main_axis(const ft_op_desc &d, uint64_t M, uint64_t N) {
+    Gemm s = static_view(d);
+    bool dyn_m = s.m == 0, dyn_n = s.n == 0;
+    if (dyn_m && dyn_n) return M >= N ? 0u : 1u;
+    if (dyn_n && !dyn_m) return 1u;
+    return 0u;
+}
+
+struct Resolved { uint64_t batch, M, N, K; uint32_t P, Q; };
+
+ft_status resolve_axis(uint32_t stat, uint32_t lo, uint32_t hi, uint32_t given, uint64_t *out) {
+    if (stat > 0) {
+        if (given != 0 && given != stat) return FT_ERR_INVALID_ARG;
+        *out = stat;
+        return FT_OK;
+    }
+    if (given < lo || given > hi) return FT_ERR_OUT_OF_RANGE;
+    *out = given;
+    return FT_OK;
+}
+
+ft_status resolve(const ft_op_desc &d, const ft_shape &s, Resolved *r) {
+    r->P = r->Q = 0;
+    if (d.kind == FT_OP_CONV2D) {
+        if (s.img_h + 2 * d.pad < d.r || s.img_w + 2 * d.pad < d.s) {
+            if (s.img_n == 0 || s.img_h == 0 || s.img_w == 0) { r->batch = 1; r->M = 0; r->N = d.c_out; r->K = d.r * d.s * d.c_in; return FT_OK; }
+            return FT_ERR_INVALID_ARG;
+        }
+        r->P = (s.img_h + 2 * d.pad - d.r) / d.stride + 1;
+        r->Q = (s.img_w + 2 * d.pad - d.s) / d.stride + 1;
+        r->batch = 1;
+        r->M = (uint64_t)s.img_n * r->P * r->Q;
+        r->N = d.c_out;
+        r->K = (uint64_t)d.r * d.s * d.c_in;
+        if (r->M < d.m_lo || r->M > d.m_hi) return FT_ERR_OUT_OF_RANGE;
+        return FT_OK;
+    }
+    r->batch = d.kind == FT_OP_BMM ? s.batch : 1;
+    ft_status st;
+    if ((st = resolve_axis(d.m, d.m_lo, d.m_hi, s.m, &r->M)) != FT_OK) return st;
+    if ((st = resolve_axis(d.n, d.n_lo, d.n_hi, s.n, &r->N)) != FT_OK) return st;
+    if ((st = resolve_axis(d.k, d.k_lo, d.k_hi, s.k, &r->K)) != FT_OK) return st;
+    return FT_OK;
+}
+
+void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau, std::vector<ft_tile_desc> &out) {
+    out.clear();
+    out.reserve(p.tiles);
+    uint64_t Wp = ceil_by(tau == 0 ? r.N : r.M, GRANULE);
+    uint64_t off = 0;
+    for (uint32_t i = 0; i < p.nparts; ++i) {           // parts are in ascending id order
+        const ft_ukernel_info &u = set.uk[p.part[i].id];
+        uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
+        uint64_t cnt = p.part[i].count;
+        uint64_t m_cnt = tau == 0 ? cnt : across, n_cnt = tau == 0 ? across : cnt;
+        uint64_t m_base = tau == 0 ? off : 0, n_base = tau == 0 ? 0 : off;
+        for (uint64_t b = 0; b < r.batch; ++b)
+            for (uint64_t im = 0; im < m_cnt; ++im)
+                for (uint64_t in = 0; in < n_cnt; ++in) {
+                    ft_tile_desc d;
+                    d.ukernel_id = u.id;
+                    d.batch = (uint32_t)b;
+                    d.m0 = (uint32_t)(m_base + im * u.tm);
+                    d.n0 = (uint32_t)(n_base + in * u.tn);
+                    d.m_valid = (uint16_t)std::min<uint64_t>(u.tm, r.M - d.m0);
+                    d.n_valid = (uint16_t)std::min<uint64_t>(u.tn, r.N - d.n0);
+                    d.flags = (d.m_valid < u.tm || d.n_valid < u.tn) ? 1u : 0u;
+                    out.push_back(d);
+                }
+        off += cnt * ext(u, tau);
+    }
+}
+
+bool better(const Program &a, const Program &b) {      // Top-1 order: SIA, then fewer tiles, K1, K2
+    if (a.sia_q != b.sia_q) return a.sia_q > b.sia_q;
+    if (a.tiles != b.tiles) return a.tiles < b.tiles;
+    if (a.k1 != b.k1) return a.k1 < b.k1;
+    return a.k2 < b.k2;
+}
+
+int level_of(const Program &p) {
+    if (p.in_bound && p.cross && p.saturated) return 0;
+    if (p.in_bound && p.cross) return 1;
+    if (p.in_bound) return 2;
+    return 3;
+}
+
+thread_local int g_last_hip_error = 0;
+
+}  // namespace
+
+void ftd_set_hip_error(int e) { g_last_hip_error = e; }
+
+extern "C" {
+
+const char *ft_status_string(ft_status s) {
+    switch (s) {
+    case FT_OK: return "FT_OK";
+    case FT_ERR_INVALID_ARG: return "FT_ERR_INVALID_ARG";
+    case FT_ERR_UNSUPPORTED: return "FT_ERR_UNSUPPORTED";
+    case FT_ERR_OUT_OF_RANGE: return "FT_ERR_OUT_OF_RANGE";
+    case FT_ERR_NO_COVER: return "FT_ERR_NO_COVER";
+    case FT_ERR_HIP: return "FT_ERR_HIP";
+    case FT_ERR_OOM: return "FT_ERR_OOM";
+    default: return "FT_ERR_UNKNOWN";
+    }
+}
+
+int32_t ft_last_hip_error(void) { return g_last_hip_error; }
+
+ft_status ft_hw_default_gfx950(ft_hw_model *out) {
+    if (!out) return FT_ERR_INVALID_ARG;
+    hw_defaults(out);
+    return FT_OK;
+}
+
+ft_status ft_tuning_default(ft_tuning *out) {
+    if (!out) return FT_ERR_INVALID_ARG;
+    tuning_defaults(out);
+    return FT_OK;
+}
+
+ft_status ft_op_register(const ft_op_desc *desc, ft_op **out) {
+    if (!desc || !out || desc->struct_size != sizeof(ft_op_desc)) return FT_ERR_INVALID_ARG;
+    const ft_op_desc &d = *desc;
+    if (d.kind > FT_OP_CONV2D || d.dtype > FT_BF16) return FT_ERR_INVALID_ARG;
+    if (d.kind == FT_OP_CONV2D) {
+        if (!d.c_in || !d.c_out || !d.r || !d.s || !d.stride) return FT_ERR_INVALID_ARG;
+        if (d.m_lo > d.m_hi) return FT_ERR_INVALID_ARG;
+        if ((uint64_t)d.r * d.s * d.c_in >= (1ull << 31)) return FT_ERR_UNSUPPORTED;
+    } else {
+        if (d.m == 0 && d.m_lo > d.m_hi) return FT_ERR_INVALID_ARG;
+        if (d.n == 0 && d.n_lo > d.n_hi) return FT_ERR_INVALID_ARG;
+        if (d.k == 0 && d.k_lo > d.k_hi) return FT_ERR_INVALID_ARG;
+    }
+    ft_op *op = new (std::nothrow) ft_op;
+    if (!op) return FT_ERR_OOM;
+    op->d = d;
+    *out = op;
+    return FT_OK;
+}
+
+void ft_op_destroy(ft_op *op) { delete op; }
+
+ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tuning *tuning, ft_ukset **out) {
+    if (!op || !out) return FT_ERR_INVALID_ARG;
+    if (hw && hw->struct_size != sizeof(ft_hw_model)) return FT_ERR_INVALID_ARG;
+    if (tuning && tuning->struct_size != sizeof(ft_tuning)) return FT_ERR_INVALID_ARG;
+    ft_ukset *set = new (std::nothrow) ft_ukset;
+    if (!set) return FT_ERR_OOM;
+    set->op = op->d;
+    if (hw) set->hw = *hw; else hw_defaults(&set->hw);
+    if (tuning) set->t = *tuning; else tuning_defaults(&set->t);
+    const ft_hw_model &h = set->hw;
+    const ft_tuning &t = set->t;
+    if (!h.num_cus || !h.wave_size || h.regs_per_lane < 4 || !h.mfma_flops_per_clk_per_cu || !h.bw_global_bytes_per_clk_per_cu ||
+        !h.bw_lds_bytes_per_clk_per_cu || !t.zeta || !t.psi_den) {
+        delete set;
+        return FT_ERR_INVALID_ARG;
+    }
+    Gemm sv = static_view(op->d);
+    uint64_t kref = sv.k ? sv.k : op->d.k_hi;
+    if (kref == 0) kref = 1;
+
+    // HardwareAlign: RegTileRule (per-wave accumulator tiles built from MFMA shapes) x
+    // SmemTileRule (wave grids; tk = one 128-byte line of 16-bit elements)
+    static const uint32_t sizes[4] = {16, 32, 64, 128};
+    static const uint32_t grids[3][2] = {{1, 4}, {2, 2}, {4, 1}};
+    for (uint32_t wm : sizes)
+        for (uint32_t wn : sizes) {
+            uint32_t mfma;
+            if (wm == 16 && wn <= 64) mfma = 1;
+            else if (wm >= 32 && wn >= 32 && wm <= 2 * wn && wn <= 2 * wm) mfma = 0;
+            else continue;
+            for (auto &g : grids) {
+                uint32_t gm = g[0], gn = g[1], tk = FT_TK;
+                uint32_t tm = gm * wm, tn = gn * wn;
+                if (ft_body_code(wm, wn, gm, gn) < 0) continue;          // no compiled body
+                // static space axes are divided evenly (after rounding to the MFMA granule)
+                if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
+                if (sv.n && ceil_by(sv.n, GRANULE) % tn) continue;
+                uint32_t lds = STAGES * (tm + tn) * tk * ELT;
+                if (lds > h.lds_bytes_per_cu) continue;                  // mem.IsOverflow
+                uint32_t acc = wm * wn / h.wave_size;
+                uint32_t regs = acc + t.rest_regs;
+                if (regs > h.regs_per_lane) continue;                    // Eq. 4 at block.bound = 1
+                u128 cn, cd;
+                compute_eff(tm, tn, gm, gn, kref, h, &cn, &cd);
+                if (cn * t.psi_den < (u128)t.psi_num * cd) continue;     // Eq. 6
+                ft_ukernel_info u;
+                std::memset(&u, 0, sizeof(u));
+                u.struct_size = sizeof(u);
+                u.tm = tm; u.tn = tn; u.tk = tk; u.wm = wm; u.wn = wn; u.gm = gm; u.gn = gn;
+                u.mfma = mfma; u.stages = STAGES; u.lds_bytes = lds; u.acc_regs = acc; u.regs = regs;
+                // registers are granted in power-of-two fractions of the file (128, 256, 512)
+                uint32_t budget = h.regs_per_lane / 4;
+                while (budget < regs) budget *= 2;
+                u.reg_budget = budget;
+                u.max_wg_per_cu = std::min(std::min(h.lds_bytes_per_cu / lds, h.regs_per_lane / budget),
+                                           h.max_waves_per_simd);
+                u.cmr_q20 = (uint64_t)((cn << QBITS) / cd);
+                set->uk.push_back(u);
+            }
+        }
+    std::sort(set->uk.begin(), set->uk.end(), [](const ft_ukernel_info &a, const ft_ukernel_info &b) {
+        uint64_t aa = (uint64_t)a.tm * a.tn, ab = (uint64_t)b.tm * b.tn;
+        if (aa != ab) return aa > ab;
+        if (a.tm != b.tm) return a.tm > b.tm;
+        if (a.tn != b.tn) return a.tn > b.tn;
+        if (a.tk != b.tk) return a.tk > b.tk;
+        if (a.wm != b.wm) return a.wm > b.wm;
+        return a.wn > b.wn;
+    });
+    set->cap_q = 0;
+    for (size_t i = 0; i < set->uk.size(); ++i) {
+        set->uk[i].id = (uint32_t)i;
+        set->cap_q = std::max(set->cap_q, set->uk[i].cmr_q20);
+    }
+    if (set->uk.empty()) {
+        delete set;
+        return FT_ERR_NO_COVER;
+    }
+    *out = set;
+    return FT_OK;
+}
+
+ft_status ft_ukset_size(const ft_ukset *set, uint32_t *n) {
+    if (!set || !n) return FT_ERR_INVALID_ARG;
+    *n = (uint32_t)set->uk.size();
+    return FT_OK;
+}
+
+ft_status ft_ukset_get(const ft_ukset *set, uint32_t i, ft_ukernel_info *out) {
+    if (!set || !out || i >= set->uk.size()) return FT_ERR_INVALID_ARG;
+    *out = set->uk[i];
+    return FT_OK;
+}
+
+void ft_ukset_destroy(ft_ukset *set) { delete set; }
+
+static ft_status check_common(const ft_op *op, const ft_ukset *set, const ft_shape *shape, Resolved *r) {
+    if (!op || !set || !shape || shape->struct_size != sizeof(ft_shape)) return FT_ERR_INVALID_ARG;
+    if (std::memcmp(&op->d, &set->op, sizeof(ft_op_desc)) != 0) return FT_ERR_INVALID_ARG;
+    ft_status st = resolve(op->d, *shape, r);
+    if (st != FT_OK) return st;
+    const uint64_t lim = 1ull << 31;      // 32-bit element offsets inside one batch entry
+    if (op->d.kind == FT_OP_CONV2D) {
+        if ((uint64_t)shape->img_n * shape->img_h * shape->img_w * op->d.c_in >= lim) return FT_ERR_UNSUPPORTED;
+        if (shape->img_h >= 32768 || shape->img_w >= 32768) return FT_ERR_UNSUPPORTED;
+    } else if (r->M * r->K >= lim) return FT_ERR_UNSUPPORTED;
+    if (r->K * r->N >= lim || r->M * r->N >= lim || r->batch >= lim) return FT_ERR_UNSUPPORTED;
+    return FT_OK;
+}
+
+ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *shape, ft_pool_entry *out,
+                       uint32_t cap, uint32_t *n) {
+    Resolved r;
+    ft_status st = check_common(op, set, shape, &r);
+    if (st != FT_OK) return st;
+    if (!n || (cap && !out)) return FT_ERR_INVALID_ARG;
+    *n = 0;
+    if (r.batch == 0 || r.M == 0 || r.N == 0) return FT_OK;
+    uint32_t tau = main_axis(op->d, r.M, r.N);
+    std::vector<Program> pool;
+    build_pool(*set, ceil_by(tau == 0 ? r.M : r.N, GRANULE), tau, pool);
+    *n = (uint32_t)pool.size();
+    for (size_t i = 0; i < pool.size() && i < cap; ++i) {
+        Program p = pool[i];
+        uint32_t c1 = p.part[0].count, c2 = p.nparts == 2 ? p.part[1].count : 0;
+        evaluate(p, *set, r.batch, r.M, r.N, tau);
+        ft_pool_entry &e = out[i];
+        e.k1 = (uint32_t)p.k1; e.count1 = c1;
+        e.k2 = p.k2 < 0 ? UINT32_MAX : (uint32_t)p.k2; e.count2 = c2;
+        e.pad_q20 = p.pad_q; e.occ_q20 = p.occ_q; e.cmr_q20 = p.cmr_q;
+        e.flags = (p.in_bound ? 1u : 0u) | (p.cross ? 2u : 0u) | (p.saturated ? 4u : 0u);
+        e.sia_q20 = p.sia_q; e.n_tiles = p.tiles;
+    }
+    return FT_OK;
+}
+
+ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
+                         const ft_forced_program *forced, ft_plan **out) {
+    Resolved r;
+    ft_status st = check_common(op, set, shape, &r);
+    if (st != FT_OK) return st;
+    if (!out) return FT_ERR_INVALID_ARG;
+    const uint32_t mode = flags & FT_PLAN_MODE_MASK;
+    if (mode > FT_PLAN_FORCED) return FT_ERR_INVALID_ARG;
+    if (mode == FT_PLAN_FORCED && (!forced || forced->struct_size != sizeof(ft_forced_program)))
+        return FT_ERR_INVALID_ARG;
+
+    ft_plan *pl = new (std::nothrow) ft_plan;
+    if (!pl) return FT_ERR_OOM;
+    pl->op = op->d;
+    pl->d_descs = nullptr;
+    pl->device = -1;
+    pl->num_xcds = set->hw.num_xcds ? set->hw.num_xcds : 1;
+    pl->img_h = shape->img_h; pl->img_w = shape->img_w; pl->out_p = r.P; pl->out_q = r.Q;
+    pl->slot_id[0] = pl->slot_id[1] = 0;
+    pl->slot_code[0] = pl->slot_code[1] = 0;
+    ft_plan_stats &s = pl->st;
+    std::memset(&s, 0, sizeof(s));
+    s.struct_size = sizeof(s);
+    uint32_t tau = main_axis(op->d, r.M, r.N);
+    s.tau = tau;
+    s.batch = (uint32_t)r.batch; s.m = (uint32_t)r.M; s.n = (uint32_t)r.N; s.k = (uint32_t)r.K;
+    s.useful_elems = r.batch * r.M * r.N;
+    if (r.batch == 0 || r.M == 0 || r.N == 0) {           // empty input: empty plan
+        *out = pl;
+        return FT_OK;
+    }
+
+    Program best{};
+    if (mode == FT_PLAN_PAD_BASELINE) {
+        // pad every dynamic axis up to the largest uKernel of the set (Fig. 2)
+        const ft_ukernel_info &u = set->uk[0];
+        uint64_t Hp = ceil_by(tau == 0 ? r.M : r.N, ext(u, tau));
+        best.nparts = 1;
+        best.part[0] = {0u, (uint32_t)(Hp / ext(u, tau))};
+        best.k1 = 0; best.k2 = -1;
+        evaluate(best, *set, r.batch, r.M, r.N, tau);
+        s.pool_size = 1;
+        s.level = 3;
+    } else if (mode == FT_PLAN_FORCED) {
+        uint64_t Hp = ceil_by(tau == 0 ? r.M : r.N, GRANULE);
+        if (forced->k1 >= set->uk.size() || forced->count1 == 0) { delete pl; return FT_ERR_INVALID_ARG; }
+        uint64_t total = (uint64_t)forced->count1 * ext(set->uk[forced->k1], tau);
+        best.nparts = 1;
+        best.part[0] = {forced->k1, forced->count1};
+        best.k1 = forced->k1; best.k2 = -1;
+        if (forced->count2) {
+            if (forced->k2 >= set->uk.size() || forced->k2 == forced->k1) { delete pl; return FT_ERR_INVALID_ARG; }
+            total += (uint64_t)forced->count2 * ext(set->uk[forced->k2], tau);
+            best.nparts = 2;
+            best.part[1] = {forced->k2, forced->count2};
+            best.k2 = forced->k2;
+        }
+        if (total != Hp) { delete pl; return FT_ERR_NO_COVER; }
+        evaluate(best, *set, r.batch, r.M, r.N, tau);
+        s.pool_size = 1;
+        s.level = (uint32_t)level_of(best);
+    } else {
+        std::vector<Program> pool;
+        build_pool(*set, ceil_by(tau == 0 ? r.M : r.N, GRANULE), tau, pool);
+        if (pool.empty()) {
+            // Alg. 2 found nothing (main axis shorter than every extent the static axes admit):
+            // pad it up to the uKernel with the smallest main-axis extent (first in set order)
+            uint64_t Hp = ceil_by(tau == 0 ? r.M : r.N, GRANULE);
+            size_t pick = 0;
+            for (size_t i = 1; i < set->uk.size(); ++i)
+                if (ext(set->uk[i], tau) < ext(set->uk[pick], tau)) pick = i;
+            Program p{};
+            p.nparts = 1;
+            p.part[0] = {(uint32_t)pick, (uint32_t)ceil_div(Hp, ext(set->uk[pick], tau))};
+            p.k1 = (int64_t)pick; p.k2 = -1;
+            pool.push_back(p);
+        }
+        int lvl = 4;
+        for (Program &p : pool) {
+            evaluate(p, *set, r.batch, r.M, r.N, tau);
+            lvl = std::min(lvl, level_of(p));
+        }
+        bool have = false;
+        for (const Program &p : pool) {
+            // a program belongs to every level at or above its own
+            if (level_of(p) > lvl) continue;
+            if (!have || better(p, best)) { best = p; have = true; }
+        }
+        s.pool_size = (uint32_t)pool.size();
+        s.level = (uint32_t)lvl;
+    }
+
+    emit(best, *set, r, tau, pl->descs);
+    s.n_ukernels = best.nparts;
+    uint32_t lds = 0, klass = 0;
+    for (uint32_t i = 0; i < best.nparts; ++i) {
+        const ft_ukernel_info &u = set->uk[best.part[i].id];
+        s.ukernel_id[i] = u.id;
+        s.count_tau[i] = best.part[i].count;
+        pl->slot_id[i] = u.id;
+        pl->slot_code[i] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn);
+        lds = std::max(lds, u.lds_bytes);
+        uint32_t by_model = 0;
+        for (uint32_t b = set->hw.regs_per_lane / 4; b < u.reg_budget && by_model < FT_NUM_CLASSES - 1; b *= 2) ++by_model;
+        klass = std::max<uint32_t>(klass, std::max<uint32_t>(by_model, (uint32_t)ft_class_of_acc((int)u.acc_regs)));
+    }
+    if (best.nparts == 1) { pl->slot_id[1] = pl->slot_id[0]; pl->slot_code[1] = pl->slot_code[0]; }
+    s.block_bound = best.block_bound;
+    s.pad_q20 = best.pad_q; s.occ_q20 = best.occ_q; s.cmr_q20 = best.cmr_q; s.sia_q20 = best.sia_q;
+    s.lds_bytes = lds;
+    s.kernel_class = klass;
+    s.n_tiles = pl->descs.size();
+    s.covered_elems = r.batch * best.area;
+
+    if (!(flags & FT_PLAN_HOST_ONLY)) {
+        st = ftd_upload(pl);
+        if (st != FT_OK) { delete pl; return st; }
+    }
+    *out = pl;
+    return FT_OK;
+}
+
+ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, uint64_t *n) {
+    if (!plan || !descs || !n) return FT_ERR_INVALID_ARG;
+    *descs = plan->descs.empty() ? nullptr : plan->descs.data();
+    *n = plan->descs.size();
+    return FT_OK;
+}
+
+ft_status ft_plan_stats_get(const ft_plan *plan, ft_plan_stats *out) {
+    if (!plan || !out) return FT_ERR_INVALID_ARG;
+    *out = plan->st;
+    return FT_OK;
+}
+
+void ft_plan_destroy(ft_plan *plan) {
+    if (!plan) return;
+    ftd_release(plan);
+    delete plan;
+}
+
+}  // extern "C"

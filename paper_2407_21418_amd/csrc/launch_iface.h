@@ -1,0 +1,19 @@
+// Names of the per-(dtype, class) dispatcher entry points, shared by the dispatcher
+// translation units and the launch code.
+#pragma once
+#include <stdint.h>
+#define FT_CAT_(a, b, c, d) a##b##c##d
+#define FT_CAT(a, b, c, d) FT_CAT_(a, b, c, d)
+#if defined(FT_DT) && defined(FT_CLASS)
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _c, FT_CLASS)
+#endif
+namespace ftk { struct KArgs; }
+extern "C" {
+int ft_launch_dt0_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_c2(const ftk::KArgs *, uint32_t, void *);
+}

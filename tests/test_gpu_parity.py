@@ -1,0 +1,235 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerance: max relative error 2e-3 (fp32 accumulation of fp16/bf16 products),
+both against the output scale and element-wise against sum|a||b|; plans bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_21418_amd as ft
+import synth_inputs as si
+from oracle import contraction as oc
+from oracle import planner as P
+
+from gpu_util import REL_TOL, alloc_out, check, dev_bits, matmul_op, out_view, run, stream
+
+pytestmark = pytest.mark.gpu
+
+
+def test_hw_query_reports_gfx950():
+    hw = ft.ft_hw_query(0)
+    assert hw.num_cus == 256 and hw.wave_size == 64 and hw.lds_bytes_per_cu == 163840
+
+
+def test_config0_odd_m_matmul():
+    p = si.config0()
+    op = matmul_op(p["N"], p["K"], ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=p["M"]), mode)
+        got = run(plan, p["A"], p["B"], p["M"] * p["N"])
+        ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+        check(got, ref, refabs, f"config0 mode {mode}")
+
+
+def family():
+    op = P.Op(P.OP_BMM, P.F16, k_range=(0, 4096), m_range=(0, 8192), n_range=(0, 8192))
+    return [(u.tm, u.tn, u.wm, u.wn, u.gm, u.gn) for u in P.derive_ukernels(op)]
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+@pytest.mark.parametrize("body", family(), ids=lambda b: "t%dx%d_w%dx%d" % b[:4])
+def test_every_ukernel_body(body, dtype):
+    """Each compiled body alone (forced single-uKernel program): 2 x 2 tiles with a ragged tail
+    on both axes, a ragged k tail, a column count that is not a multiple of 8 (element-wise
+    loads on the last column tile) and batch 2."""
+    tm, tn, wm, wn, gm, gn = body
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=8192, n_lo=0, n_hi=8192,
+                                         k_lo=0, k_hi=4096))
+    s = ft.ft_ukernels_derive(op)
+    ids = [i for i in range(ft.ft_ukset_size(s))
+           if (lambda u: (u.tm, u.tn, u.wm, u.wn) == (tm, tn, wm, wn))(ft.ft_ukset_get(s, i))]
+    assert len(ids) == 1
+    M, N, K, nb = 2 * tm - 5, 2 * tn - 11, 200, 2
+    g = np.random.default_rng(tm * 7 + tn * 3 + wm + dtype)
+    A = si.normal_bits(g, (nb, M, K), 1.0, dtype)
+    B = si.normal_bits(g, (nb, K, N), 1.0, dtype)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=M, n=N, k=K), ft.FT_PLAN_FORCED,
+                             ft.ft_forced_program(k1=ids[0], count1=2))
+    st = ft.ft_plan_stats_get(plan)
+    assert st.n_tiles == nb * 4
+    got = run(plan, A, B, nb * M * N)
+    ref, refabs = oc.bmm(A, B, dtype, want_abs=True)
+    check(got, ref, refabs, f"body {body} dtype {dtype}")
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+def test_permutation_matrix_is_bit_exact(dtype):
+    """A = permutation matrix: every output is a single product 1*b, exact in fp32; pins the
+    MFMA operand and accumulator lane layouts and the LDS swizzles."""
+    g = np.random.default_rng(4)
+    n, N = 384, 768
+    B = si.normal_bits(g, (n, N), 1.0, dtype)
+    perm = g.permutation(n)
+    Pm = np.zeros((n, n), dtype=np.float32)
+    Pm[np.arange(n), perm] = 1.0
+    A = si.to_bits(Pm, dtype)
+    op = matmul_op(N, n, dtype)
+    s = ft.ft_ukernels_derive(op)
+    want = oc.decode(B, dtype)[perm]
+    for i in range(ft.ft_ukset_size(s)):
+        u = ft.ft_ukset_get(s, i)
+        if n % u.tm:
+            continue
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=n), ft.FT_PLAN_FORCED,
+                                 ft.ft_forced_program(k1=i, count1=n // u.tm))
+        got = run(plan, A, B, n * N).reshape(n, N)
+        assert np.array_equal(got, want), (u.tm, u.tn, u.wm, u.wn)
+
+
+@pytest.mark.parametrize("M,N,K", [(80, 768, 768), (272, 3072, 768), (528, 768, 3072), (1232, 768, 768)])
+def test_bert_shapes_patchwork_and_baseline(M, N, K):
+    p = si.config1_problem(M, N, K)
+    op = matmul_op(N, K, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    oop = P.Op(P.OP_MATMUL, P.F16, n=N, k=K, m_range=(0, 8192))
+    ouk = P.derive_ukernels(oop)
+    for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), mode)
+        assert ft.ft_plan_descriptors(plan) == b"".join(d.pack() for d in P.plan(oop, ouk, (1, M, N, K), mode).descs)
+        check(run(plan, p["A"], p["B"], M * N), ref, refabs, f"bert {M}x{N}x{K} mode {mode}")
+
+
+def test_two_ukernel_program_mixed_in_one_launch():
+    """A program of two different uKernel shapes runs as ONE launch over the descriptor table."""
+    M, N, K = 1232, 768, 768
+    p = si.config1_problem(M, N, K)
+    op = matmul_op(N, K, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    infos = [ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))]
+    big = next(u.id for u in infos if (u.tm, u.tn, u.wm) == (128, 128, 64))
+    small = next(u.id for u in infos if (u.tm, u.tn, u.wm) == (16, 64, 16))
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED,
+                             ft.ft_forced_program(k1=big, count1=9, k2=small, count2=5))
+    st = ft.ft_plan_stats_get(plan)
+    assert st.n_ukernels == 2 and st.n_tiles == 9 * 6 + 5 * 12
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    check(run(plan, p["A"], p["B"], M * N), ref, refabs, "mixed program")
+
+
+@pytest.mark.parametrize("L", [1, 7, 33, 77, 100, 257])
+def test_attention_bmm_dynamic_length(L):
+    """QK^T (two dynamic space axes) and PV (dynamic reduce axis) with odd lengths: rows that
+    are not 16-byte aligned, partial chunks, k tails."""
+    nb = 24
+    qk_op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=0, m_hi=512, n_lo=0, n_hi=512))
+    pv_op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, n=64, m_lo=0, m_hi=512, k_lo=0, k_hi=512))
+    for which, op, shape in (("qk", qk_op, ft.ft_shape(batch=nb, m=L, n=L)), ("pv", pv_op, ft.ft_shape(batch=nb, m=L, k=L))):
+        p = si.config2_problem(2, L, which)
+        s = ft.ft_ukernels_derive(op)
+        for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+            plan = ft.ft_plan_create(op, s, shape, mode)
+            got = run(plan, p["A"], p["B"], nb * p["M"] * p["N"])
+            ref, refabs = oc.bmm(p["A"], p["B"], si.F16, want_abs=True)
+            check(got, ref, refabs, f"{which} L={L} mode {mode}")
+
+
+@pytest.mark.parametrize("res,batch", [(5, 2), (13, 3), (28, 8), (37, 8)])
+def test_conv2d_implicit_gemm(res, batch):
+    p = si.config4_problem(res, batch=batch)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=ft.FT_F16, c_in=64, c_out=128, r=3, s=3,
+                                         stride=1, pad=1, m_lo=0, m_hi=1 << 22))
+    s = ft.ft_ukernels_derive(op)
+    ref, refabs = oc.conv2d_nhwc(p["X"], p["Wt"], si.F16, want_abs=True)
+    for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(img_n=batch, img_h=res, img_w=res), mode)
+        got = run(plan, p["X"], p["Wt"], batch * res * res * 128)
+        check(got, ref, refabs, f"conv res {res} mode {mode}")
+
+
+def test_conv2d_general_geometry():
+    """Stride 2, no padding, channel count not a multiple of 8 (element-wise gather path)."""
+    g = np.random.default_rng(77)
+    n, H, W, Cin, Cout = 2, 11, 9, 12, 32
+    X = si.normal_bits(g, (n, H, W, Cin), 1.0, si.F16)
+    Wt = si.normal_bits(g, (3, 3, Cin, Cout), 1.0, si.F16)
+    for stride, pad in ((2, 0), (2, 1), (1, 0)):
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=ft.FT_F16, c_in=Cin, c_out=Cout, r=3, s=3,
+                                             stride=stride, pad=pad, m_lo=0, m_hi=1 << 20))
+        s = ft.ft_ukernels_derive(op)
+        ref, refabs = oc.conv2d_nhwc(X, Wt, si.F16, stride=stride, pad=pad, want_abs=True)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(img_n=n, img_h=H, img_w=W))
+        got = run(plan, X, Wt, ref.size)
+        check(got, ref, refabs, f"conv stride {stride} pad {pad}")
+
+
+def test_llm_bf16_sampled_rows_full_size():
+    """Largest configured GEMM (8192 x 11008 x 4096, bf16) in the launch configuration the
+    benchmark uses; the oracle checks 64 sampled rows plus the rows around tile boundaries."""
+    M, N = 8192, 11008
+    p = si.config3_problem(M, N)
+    op = matmul_op(N, si.LLM_K, ft.FT_BF16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    A, B = dev_bits(p["A"]), dev_bits(p["B"])
+    Cd = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    ft.ft_launch(plan, A.data_ptr(), B.data_ptr(), Cd.data_ptr(), stream())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Cd).all())
+    g = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([g.integers(0, M, 64), [0, 1, 127, 128, 255, 256, 257, M - 2, M - 1]])).astype(np.int64)
+    ref, refabs = oc.matmul(p["A"], p["B"], si.BF16, rows=rows, want_abs=True)
+    got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    check(got, ref, refabs, "llm 8192x11008")
+
+
+@pytest.mark.parametrize("M", [1, 3, 16, 45, 300])
+def test_llm_bf16_small_token_counts(M):
+    N = 4096
+    p = si.config3_problem(M, N)
+    op = matmul_op(N, si.LLM_K, ft.FT_BF16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    ref, refabs = oc.matmul(p["A"], p["B"], si.BF16, want_abs=True)
+    check(run(plan, p["A"], p["B"], M * N), ref, refabs, f"llm M={M}")
+
+
+def test_empty_and_degenerate_inputs():
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, n=64, m_lo=0, m_hi=512, k_lo=0, k_hi=512))
+    s = ft.ft_ukernels_derive(op)
+    # empty output: nothing is launched, nothing is touched
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=3, m=0, k=7))
+    assert ft.ft_plan_stats_get(plan).n_tiles == 0
+    buf = alloc_out(16)
+    ft.ft_launch(plan, 0, 0, buf.data_ptr(), stream())
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(buf[256:272]).all())
+    # empty reduce axis: the sum over no terms is zero
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=2, m=5, k=0))
+    A = torch.zeros(16, dtype=torch.int16, device="cuda")
+    got = out_view_after(plan, A, A, 2 * 5 * 64)
+    assert np.array_equal(got, np.zeros(2 * 5 * 64))
+
+
+def out_view_after(plan, A, B, n):
+    buf = alloc_out(n)
+    ft.ft_launch(plan, A.data_ptr(), B.data_ptr(), buf.data_ptr() + 4 * 256, stream())
+    torch.cuda.synchronize()
+    return out_view(buf, n)
+
+
+def test_launch_on_a_side_stream_and_relaunch():
+    p = si.config1_problem(272, 768, 768)
+    op = matmul_op(768, 768, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=272))
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    side = torch.cuda.Stream()
+    A, B = dev_bits(p["A"]), dev_bits(p["B"])
+    torch.cuda.synchronize()
+    for _ in range(3):
+        buf = alloc_out(272 * 768)
+        torch.cuda.synchronize()
+        ft.ft_launch(plan, A.data_ptr(), B.data_ptr(), buf.data_ptr() + 4 * 256, side.cuda_stream)
+        side.synchronize()
+        check(out_view(buf, 272 * 768), ref, refabs, "side stream")

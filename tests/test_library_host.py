@@ -1,0 +1,209 @@
+"""Host-side checks of libftuner.so that need no GPU: every declared symbol is exported, the
+uKernel table and every plan are bit-identical to the planner oracle's, error codes."""
+import os
+import re
+
+import pytest
+
+import paper_2407_21418_amd as ft
+from oracle import planner as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HOST = ft.FT_PLAN_HOST_ONLY
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ftuner.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ft_[a-z0-9_]+)\s*\(", hdr))
+    assert declared, "no declarations parsed"
+    lib = ft.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in ftuner.h but not exported"
+    assert declared == set(ft.SYMBOLS), (declared ^ set(ft.SYMBOLS))
+
+
+def to_lib_op(op: P.Op):
+    d = ft.ft_op_desc(kind=op.kind, dtype=op.dtype, m=op.m, n=op.n, k=op.k,
+                      m_lo=op.m_range[0], m_hi=op.m_range[1], n_lo=op.n_range[0], n_hi=op.n_range[1],
+                      k_lo=op.k_range[0], k_hi=op.k_range[1], c_in=op.c_in, c_out=op.c_out, r=op.r, s=op.s,
+                      stride=op.stride, pad=op.pad)
+    return ft.ft_op_register(d)
+
+
+OPS = {
+    "dense768": P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(0, 8192)),
+    "dense3072": P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(0, 8192)),
+    "dense768k3072": P.Op(P.OP_MATMUL, P.F16, n=768, k=3072, m_range=(0, 8192)),
+    "llm11008": P.Op(P.OP_MATMUL, P.BF16, n=11008, k=4096, m_range=(1, 8192)),
+    "qk": P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512)),
+    "pv": P.Op(P.OP_BMM, P.F16, n=64, m_range=(0, 512), k_range=(0, 512)),
+    "onlyn": P.Op(P.OP_BMM, P.F16, m=64, k=64, n_range=(1, 512)),
+    "conv": P.Op(P.OP_CONV2D, P.F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1, m_range=(0, 1 << 22)),
+    "odd_static_n": P.Op(P.OP_MATMUL, P.F16, n=1000, k=100, m_range=(1, 4096)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(OPS))
+def test_ukernel_table_matches_oracle(name):
+    op = OPS[name]
+    want = P.derive_ukernels(op)
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop)
+    assert ft.ft_ukset_size(s) == len(want)
+    for i, w in enumerate(want):
+        g = ft.ft_ukset_get(s, i)
+        got = (g.id, g.tm, g.tn, g.tk, g.wm, g.wn, g.gm, g.gn, g.mfma, g.stages, g.lds_bytes, g.acc_regs,
+               g.regs, g.reg_budget, g.max_wg_per_cu, g.cmr_q20)
+        assert got == (w.id, w.tm, w.tn, w.tk, w.wm, w.wn, w.gm, w.gn, w.mfma, w.stages, w.lds_bytes,
+                       w.acc_regs, w.regs, w.reg_budget, w.max_wg_per_cu, w.cmr_q)
+
+
+def shapes_for(name):
+    if name in ("qk",):
+        return [dict(batch=b, m=L, n=L) for b in (1, 12, 96) for L in (1, 7, 16, 33, 77, 100, 257, 512)] + \
+               [dict(batch=3, m=100, n=40), dict(batch=3, m=40, n=100), dict(batch=0, m=5, n=5), dict(batch=2, m=0, n=0)]
+    if name == "pv":
+        return [dict(batch=b, m=L, k=L) for b in (1, 12) for L in (1, 7, 16, 33, 77, 100, 257, 512)]
+    if name == "onlyn":
+        return [dict(batch=2, n=L) for L in (1, 15, 16, 17, 77, 500)]
+    if name == "conv":
+        return [dict(img_n=8, img_h=h, img_w=h) for h in (1, 5, 28, 37, 56, 91)] + [dict(img_n=2, img_h=9, img_w=13)]
+    ms = [1, 2, 15, 16, 17, 31, 32, 33, 77, 80, 100, 128, 272, 528, 1000, 1024, 1232, 1600, 2048, 4095, 8192]
+    if name.startswith("dense"):
+        ms = [0] + ms
+    if name == "odd_static_n":
+        ms = [1, 77, 1000, 4096]
+    return [dict(m=m) for m in ms]
+
+
+def oracle_shape(op, kw):
+    return P.resolve_shape(op, batch=kw.get("batch", 1), m=kw.get("m", 0), n=kw.get("n", 0), k=kw.get("k", 0),
+                           img_n=kw.get("img_n", 0), img_h=kw.get("img_h", 0), img_w=kw.get("img_w", 0))
+
+
+@pytest.mark.parametrize("mode", [P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE])
+@pytest.mark.parametrize("name", sorted(OPS))
+def test_plans_bit_identical_to_oracle(name, mode):
+    op = OPS[name]
+    uks = P.derive_ukernels(op)
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop)
+    for kw in shapes_for(name):
+        shape = oracle_shape(op, kw)
+        if op.kind != P.OP_BMM:
+            shape = (1,) + tuple(shape[1:])
+        want = P.plan(op, uks, shape, mode)
+        pl = ft.ft_plan_create(lop, s, ft.ft_shape(**kw), mode | HOST)
+        got = ft.ft_plan_descriptors(pl)
+        assert got == b"".join(d.pack() for d in want.descs), (name, kw)
+        st = ft.ft_plan_stats_get(pl)
+        assert (st.batch, st.m, st.n, st.k) == tuple(shape) and st.tau == want.tau
+        assert st.n_tiles == len(want.descs) and st.useful_elems == want.useful
+        if want.program is None:
+            assert st.n_ukernels == 0
+            continue
+        pr = want.program
+        assert st.covered_elems == want.covered
+        assert st.n_ukernels == len(pr.parts)
+        assert [(st.ukernel_id[i], st.count_tau[i]) for i in range(st.n_ukernels)] == list(pr.parts)
+        assert (st.pad_q20, st.occ_q20, st.cmr_q20, st.sia_q20) == (pr.pad_q, pr.occ_q, pr.cmr_q, pr.sia_q)
+        assert st.block_bound == pr.block_bound and st.level == want.level and st.pool_size == want.pool_size
+        assert st.lds_bytes == max(uks[i].lds_bytes for i, _ in pr.parts)
+
+
+@pytest.mark.parametrize("name", ["dense768", "qk", "conv"])
+def test_pool_scores_match_oracle(name):
+    op = OPS[name]
+    uks = P.derive_ukernels(op)
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop)
+    hw, t = P.default_hw(), P.default_tuning()
+    cap = max(u.cmr_q for u in uks)
+    for kw in shapes_for(name)[:10]:
+        b, M, N, K = oracle_shape(op, kw)
+        if b == 0 or M == 0 or N == 0:
+            continue
+        tau = P.main_axis(op, M, N)
+        Hp = P.ceil_by(M if tau == 0 else N, 16)
+        want = P.build_pool([u.tm if tau == 0 else u.tn for u in uks], Hp)
+        got = ft.ft_plan_pool(lop, s, ft.ft_shape(**kw))
+        assert len(got) == len(want)
+        for g, parts in zip(got, want):
+            p = P.evaluate(parts, uks, b, M, N, tau, hw, t, cap)
+            k2 = parts[1][0] if len(parts) > 1 else 0xFFFFFFFF
+            c2 = parts[1][1] if len(parts) > 1 else 0
+            assert (g.k1, g.count1, g.k2, g.count2) == (parts[0][0], parts[0][1], k2, c2)
+            assert (g.pad_q20, g.occ_q20, g.cmr_q20, g.sia_q20, g.n_tiles) == (p.pad_q, p.occ_q, p.cmr_q, p.sia_q, p.num_tiles)
+            assert g.flags == (1 if p.in_bound else 0) | (2 if p.cross else 0) | (4 if p.saturated else 0)
+
+
+def test_custom_tuning_and_hw_are_honoured():
+    op = OPS["dense3072"]
+    hw, t = P.default_hw(), P.default_tuning()
+    hw2 = dict(hw, num_cus=80, bw_lds_bytes_per_clk_per_cu=256)
+    t2 = dict(t, c0=1, c1=2, c2=6, zeta=1, rest_regs=96, psi_num=1, psi_den=5)
+    uks = P.derive_ukernels(op, hw2, t2)
+    lhw = ft.ft_hw_default_gfx950(); lhw.num_cus = 80; lhw.bw_lds_bytes_per_clk_per_cu = 256
+    lt = ft.ft_tuning_default(); lt.c1 = 2; lt.c2 = 6; lt.zeta = 1; lt.rest_regs = 96; lt.psi_den = 5
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop, lhw, lt)
+    assert ft.ft_ukset_size(s) == len(uks)
+    for M in (77, 528, 1232, 2048):
+        want = P.plan(op, uks, (1, M, 3072, 768), hw=hw2, t=t2)
+        pl = ft.ft_plan_create(lop, s, ft.ft_shape(m=M), HOST)
+        assert ft.ft_plan_descriptors(pl) == b"".join(d.pack() for d in want.descs)
+
+
+def test_forced_program_mode():
+    op = OPS["dense768"]
+    uks = P.derive_ukernels(op)
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop)
+    by = {(u.tm, u.tn, u.wm): u.id for u in uks}
+    k1, k2 = by[(64, 64, 32)], by[(16, 64, 16)]
+    pl = ft.ft_plan_create(lop, s, ft.ft_shape(m=77), ft.FT_PLAN_FORCED | HOST,
+                           ft.ft_forced_program(k1=k1, count1=1, k2=k2, count2=1))
+    want = P.emit([(k1, 1), (k2, 1)], uks, 1, 77, 768, 0)
+    assert ft.ft_plan_descriptors(pl) == b"".join(d.pack() for d in want)
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_plan_create(lop, s, ft.ft_shape(m=77), ft.FT_PLAN_FORCED | HOST,
+                          ft.ft_forced_program(k1=k1, count1=2, k2=k2, count2=1))
+    assert e.value.status == ft.FT_ERR_NO_COVER
+
+
+def test_error_codes():
+    lop = to_lib_op(OPS["dense768"])
+    s = ft.ft_ukernels_derive(lop)
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_plan_create(lop, s, ft.ft_shape(m=8193), HOST)
+    assert e.value.status == ft.FT_ERR_OUT_OF_RANGE
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_plan_create(lop, s, ft.ft_shape(m=5, n=512), HOST)       # static n contradicted
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    bad = ft.ft_shape(m=5)
+    bad.struct_size = 3
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_plan_create(lop, s, bad, HOST)
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_op_register(ft.ft_op_desc(kind=7))
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_op_register(ft.ft_op_desc(kind=0, m_lo=5, m_hi=1, n=8, k=8))
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    other = to_lib_op(OPS["dense3072"])
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_plan_create(other, s, ft.ft_shape(m=5), HOST)              # set derived for another op
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    # a hardware model whose LDS holds no tile leaves no uKernel
+    hw = ft.ft_hw_default_gfx950(); hw.lds_bytes_per_cu = 1024
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_ukernels_derive(lop, hw, None)
+    assert e.value.status == ft.FT_ERR_NO_COVER
+    assert ft.ft_status_string(ft.FT_ERR_NO_COVER) == "FT_ERR_NO_COVER"
+    # host-only plans cannot be launched, and need no GPU to find that out
+    pl = ft.ft_plan_create(lop, s, ft.ft_shape(m=16), HOST)
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_launch(pl, 16, 16, 16, 0)
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
