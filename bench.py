@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the dynamic-shape contraction path on one MI355X.
+
+Workload (N=1): the BERT-base-shaped dynamic sweep -- for seq_len L in {5,17,33,64,77,100,128},
+batch 16: [16L,768]x[768,768], [16L,768]x[768,3072], [16L,3072]x[3072,768]; fp16 inputs,
+fp32 accumulate/output.  One "step" = one pass over the 21 GEMMs through plan (cached per
+shape) + launch.  Steps are executed shape-major: each GEMM is launched `steps` times back to
+back between two HIP events on the launch stream, so every GEMM gets its own time; the sum
+over GEMMs is the time of one step.
+
+Headline `value`: geomean over the 21 GEMMs of useful TFLOP/s with operands resident in HBM
+but NOT in cache (each launch uses the next of a ring of buffer sets totalling > 600 MB).
+The same measurement with a single, cache-warm buffer set is reported beside it as
+`warm_cache`, and the pad-to-library baseline plan as `pad_baseline`.
+
+Prints ONE JSON line on stdout; per-GEMM details go to gpurun_out/bench_detail.json.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2516.6      # dense fp16/bf16 MFMA, 256 CU x 4096 flop/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+RING_BYTES = 600e6             # > 256 MB Infinity Cache + 8 x 4 MB L2
+
+
+def geomean(xs):
+    return math.exp(sum(math.log(x) for x in xs) / len(xs))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by rows with no exchange step, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2407_21418_amd as ft
+    import synth_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    hw = ft.ft_hw_query(0)
+
+    shapes = si.config1_shapes()
+    ops = {}
+    rows = []
+    t_plan_cold = 0.0
+    for (M, N, K) in shapes:
+        if (N, K) not in ops:
+            t0 = time.perf_counter()
+            op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=1, m_hi=8192))
+            uks = ft.ft_ukernels_derive(op, hw, None)
+            ops[(N, K)] = (op, uks, time.perf_counter() - t0)
+        op, uks, _ = ops[(N, K)]
+        t0 = time.perf_counter()
+        plan = ft.ft_plan_create(op, uks, ft.ft_shape(m=M), ft.FT_PLAN_PATCHWORK)
+        t_plan_cold += time.perf_counter() - t0
+        base = ft.ft_plan_create(op, uks, ft.ft_shape(m=M), ft.FT_PLAN_PAD_BASELINE)
+        rows.append(dict(M=M, N=N, K=K, plan=plan, base=base))
+
+    total_wall0 = None
+    per_class_time = {}
+    per_class_flops = {}
+    per_class_launches = {}
+    for r in rows:
+        M, N, K = r["M"], r["N"], r["K"]
+        p = si.config1_problem(M, N, K)
+        A0 = torch.from_numpy(p["A"].view(np.int16)).cuda()
+        B0 = torch.from_numpy(p["B"].view(np.int16)).cuda()
+        bytes_alg = 2 * (M * K + K * N) + 4 * M * N
+        flops = 2.0 * M * N * K
+        n_sets = max(2, int(math.ceil(RING_BYTES / bytes_alg)))
+        As = [A0] + [A0.clone() for _ in range(n_sets - 1)]
+        Bs = [B0] + [B0.clone() for _ in range(n_sets - 1)]
+        Cs = [torch.empty((M, N), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
+        pa, pb, pc = [t.data_ptr() for t in As], [t.data_ptr() for t in Bs], [t.data_ptr() for t in Cs]
+        torch.cuda.synchronize()
+        st = ft.ft_plan_stats_get(r["plan"])
+        sb = ft.ft_plan_stats_get(r["base"])
+        # warm-up (untimed), then exactly `steps` timed launches per variant
+        ft.ft_launch_timed(r["plan"], pa, pb, pc, stream, max(1, args.warmup))
+        if total_wall0 is None:
+            torch.cuda.synchronize()
+            total_wall0 = time.perf_counter()
+        ms_cold = ft.ft_launch_timed(r["plan"], pa, pb, pc, stream, args.steps)
+        r["wall_mark"] = time.perf_counter()
+        ft.ft_launch_timed(r["plan"], pa[:1], pb[:1], pc[:1], stream, max(1, args.warmup))
+        ms_warm = ft.ft_launch_timed(r["plan"], pa[:1], pb[:1], pc[:1], stream, args.steps)
+        ft.ft_launch_timed(r["base"], pa, pb, pc, stream, max(1, args.warmup))
+        ms_base = ft.ft_launch_timed(r["base"], pa, pb, pc, stream, args.steps)
+        t_roof = max(flops / (MFMA_PEAK_TFLOPS * 1e12), bytes_alg / (HBM_PEAK_GBS * 1e9))
+        r.update(ms_cold=ms_cold, ms_warm=ms_warm, ms_base=ms_base, flops=flops, bytes_alg=bytes_alg,
+                 tflops_cold=flops / ms_cold / 1e9, tflops_warm=flops / ms_warm / 1e9,
+                 tflops_base=flops / ms_base / 1e9, gbs_cold=bytes_alg / ms_cold / 1e6,
+                 roof_frac_cold=t_roof * 1e3 / ms_cold, n_tiles=st.n_tiles, n_ukernels=st.n_ukernels,
+                 kernel_class=st.kernel_class, useful=st.useful_elems, covered=st.covered_elems,
+                 base_covered=sb.covered_elems, base_tiles=sb.n_tiles)
+        k = "ft_dispatch_dt0_c%d" % st.kernel_class
+        per_class_time[k] = per_class_time.get(k, 0.0) + ms_cold * args.steps
+        per_class_flops[k] = per_class_flops.get(k, 0.0) + flops * args.steps
+        per_class_launches[k] = per_class_launches.get(k, 0) + args.steps
+        del As, Bs, Cs
+        torch.cuda.empty_cache()
+
+    ms_per_step = sum(r["ms_cold"] for r in rows)
+    value = geomean([r["tflops_cold"] for r in rows])
+    warm = geomean([r["tflops_warm"] for r in rows])
+    basev = geomean([r["tflops_base"] for r in rows])
+    useful = sum(r["useful"] for r in rows)
+    waste_patch = 100.0 * (1.0 - useful / sum(r["covered"] for r in rows))
+    waste_base = 100.0 * (1.0 - useful / sum(r["base_covered"] for r in rows))
+    dom = max(per_class_time, key=per_class_time.get)
+    achieved = per_class_flops[dom] / per_class_time[dom] / 1e9          # TFLOP/s
+    total_flops = sum(r["flops"] for r in rows)
+    total_bytes = sum(r["bytes_alg"] for r in rows)
+
+    out = {
+        "metric": "geomean TFLOP/s & % MFMA peak over dynamic-shape sweep; padding waste %",
+        "value": round(value, 3),
+        "unit": "TFLOP/s (geomean over 21 GEMMs, useful flops, operands from HBM)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "configs[1]: BERT-base-shaped dynamic sweep, 21 GEMMs, M=16*L, L in "
+                               "{5,17,33,64,77,100,128}, (K,N) in {(768,768),(768,3072),(3072,768)}",
+                   "order": "shape-major: each GEMM launched `steps` times back to back",
+                   "buffers": "ring of buffer sets > 600 MB per GEMM (cold caches)"},
+        "pct_mfma_peak_geomean": round(100.0 * value / MFMA_PEAK_TFLOPS, 3),
+        "aggregate_tflops": round(total_flops / ms_per_step / 1e9, 3),
+        "aggregate_hbm_gbs": round(total_bytes / ms_per_step / 1e6, 1),
+        "roofline_frac_geomean": round(geomean([r["roof_frac_cold"] for r in rows]), 4),
+        "padding_waste_pct": {"patchwork": round(waste_patch, 3), "pad_baseline": round(waste_base, 3)},
+        "warm_cache": {"value": round(warm, 3), "pct_mfma_peak_geomean": round(100.0 * warm / MFMA_PEAK_TFLOPS, 3),
+                       "ms_per_step": round(sum(r["ms_warm"] for r in rows), 5)},
+        "pad_baseline": {"value": round(basev, 3), "ms_per_step": round(sum(r["ms_base"] for r in rows), 5)},
+        "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 5), "traffic": None,
+                     "avg_launch_us": round(1e3 * per_class_time[dom] / per_class_launches[dom], 3),
+                     "launches": per_class_launches[dom],
+                     "note": "achieved = useful flops of the launches that ran this kernel / their "
+                             "event-timed duration (back-to-back launches, launch gaps included)"},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import contraction as oc
+        t0 = time.perf_counter()
+        fl = 0.0
+        for r in rows:
+            p = si.config1_problem(r["M"], r["N"], r["K"])
+            t1 = time.perf_counter()
+            oc.matmul(p["A"], p["B"], si.F16)
+            r["oracle_s"] = time.perf_counter() - t1
+            fl += r["flops"]
+            if time.perf_counter() - t0 > 60:
+                break
+        secs = sum(r.get("oracle_s", 0.0) for r in rows)
+        done = [r for r in rows if "oracle_s" in r]
+        out["cpu_baseline"] = {
+            "value": round(geomean([r["flops"] / r["oracle_s"] / 1e12 for r in done]), 6),
+            "unit": "TFLOP/s (geomean, fp64 oracle)", "cores": oc.num_threads(), "kind": "oracle",
+            "sample": "%d of the 21 GEMMs of the same sweep, one pass, %.1f s" % (len(done), secs),
+            "aggregate_gflops": round(fl / secs / 1e9, 2)}
+
+    os.makedirs(os.path.dirname(args.detail), exist_ok=True)
+    with open(args.detail, "w") as f:
+        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base")} for r in rows], f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
