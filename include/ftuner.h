@@ -83,7 +83,7 @@ typedef struct ft_tuning {
     uint32_t eps_min_pm, eps_max_pm, eps_step_pm;   /* 500, 950, 10                         */
     uint32_t lam_max_pm, lam_min_pm, lam_step_pm;   /* 950, 900, 1                          */
     uint32_t zeta;                                  /* default active workgroups per CU: 2  */
-    uint32_t rest_regs;                             /* RestRegs of Eq. 4: 64                */
+    uint32_t rest_regs;                             /* RestRegs of Eq. 4: 72                */
     uint32_t psi_num, psi_den;                      /* threshold of Eq. 6: 1/8              */
     uint32_t c0, c1, c2;                            /* Eq. 1 coefficients: 1, 1, 1          */
 } ft_tuning;
@@ -128,7 +128,7 @@ typedef struct ft_ukernel_info {
     uint32_t wm, wn;               /* reg_tile: per-wave fp32 accumulator tile               */
     uint32_t gm, gn;               /* wave grid (gm*gn = 4 wave64)                           */
     uint32_t mfma;                 /* 0: 32x32x16, 1: 16x16x32                               */
-    uint32_t stages;               /* LDS buffers                                            */
+    uint32_t stages;               /* LDS ring depth: k-tiles resident at once (2..8)        */
     uint32_t lds_bytes;            /* stages*(tm+tn)*tk*2                                    */
     uint32_t acc_regs;             /* wm*wn/64 per lane                                      */
     uint32_t regs;                 /* acc_regs + RestRegs                                    */

@@ -45,7 +45,7 @@ def default_tuning():
     the paper, 1/8 here."""
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
-                zeta=2, rest_regs=64, psi_num=1, psi_den=8, c0=1, c1=1, c2=1)
+                zeta=2, rest_regs=72, psi_num=1, psi_den=8, c0=1, c1=1, c2=1)
 
 
 # --------------------------------------------------------------------------------------
@@ -207,7 +207,7 @@ def wave_tiles():
 
 WAVE_GRIDS = ((1, 4), (2, 2), (4, 1))      # four wave64 per workgroup, one per SIMD
 TK_CHOICES = (64,)                          # 64 16-bit elements = one 128-byte line
-STAGES = 2
+MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
 
 
@@ -260,7 +260,11 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     continue
                 if n_s > 0 and ceil_by(n_s, GRANULE) % tn:
                     continue
-                lds = STAGES * (tm + tn) * tk * ELT
+                # LDS ring depth: the k-tiles that fit in one workgroup's share of the LDS when
+                # zeta workgroups are resident, between 2 and 8
+                stage_bytes = (tm + tn) * tk * ELT
+                stages = max(MIN_STAGES, min(MAX_STAGES, (hw["lds_bytes_per_cu"] // t["zeta"]) // stage_bytes))
+                lds = stages * stage_bytes
                 if lds > hw["lds_bytes_per_cu"]:
                     continue                                        # mem.IsOverflow
                 acc = wm * wn // hw["wave_size"]
@@ -273,7 +277,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     continue                                        # Eq. 6
                 cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
                           hw["max_waves_per_simd"])
-                cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, mfma, STAGES, lds, acc, regs,
+                cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, mfma, stages, lds, acc, regs,
                                     budget, cap, (cn << Q) // cd))
     cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))
     for i, u in enumerate(cand):

@@ -52,6 +52,13 @@ def build(verbose=True, remarks=False, jobs=None, incremental=False):
             if remarks:
                 cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             steps.append((obj, cmd))
+    for dt in (0, 1):
+        obj = os.path.join(OUT, f"dispatch_dt{dt}_gen.o")
+        cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", "-DFT_CLASS=2", "-DFT_GENERIC=1", "-c",
+                                  os.path.join(CSRC, "dispatch.hip"), "-o", obj]
+        if remarks:
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+        steps.append((obj, cmd))
     for src in ("host.cpp", "device.hip"):
         obj = os.path.join(OUT, src.replace(".", "_") + ".o")
         steps.append((obj, [HIPCC] + COMMON + ["-c", os.path.join(CSRC, src), "-o", obj]))

@@ -16,6 +16,8 @@ const launch_fn kLaunch[2][FT_NUM_CLASSES] = {
     {ft_launch_dt1_c0, ft_launch_dt1_c1, ft_launch_dt1_c2},
 };
 
+const launch_fn kLaunchGeneric[2] = {ft_launch_dt0_gen, ft_launch_dt1_gen};
+
 static_assert(sizeof(ftk::TileDesc) == sizeof(ft_tile_desc) && sizeof(ft_tile_desc) == 24,
               "descriptor layout is part of the ABI");
 
@@ -46,6 +48,7 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, ftk::KAr
     }
     a->slot_ukernel[0] = p->slot_id[0]; a->slot_ukernel[1] = p->slot_id[1];
     a->slot_code[0] = p->slot_code[0]; a->slot_code[1] = p->slot_code[1];
+    a->slot_stages[0] = p->slot_stages[0]; a->slot_stages[1] = p->slot_stages[1];
     a->num_xcds = p->num_xcds;
 }
 
@@ -92,7 +95,13 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
     if (plan->st.kernel_class >= FT_NUM_CLASSES || plan->op.dtype > 1) return FT_ERR_UNSUPPORTED;
     ftk::KArgs a;
     fill_args(plan, A, B, C, &a);
-    int rc = kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
+    // The LDS-DMA bodies need 16-byte aligned operands whose row pitches and reduce extent are
+    // multiples of 8 elements; everything else (and the convolution gather) takes the general bodies.
+    const bool fast = !a.is_conv && a.K % 8 == 0 && a.N % 8 == 0 &&
+                      (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0) &&
+                      (a.strideA % 8 == 0) && (a.strideB % 8 == 0);
+    int rc = fast ? kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream)
+                  : kLaunchGeneric[plan->op.dtype](&a, plan->st.lds_bytes, hip_stream);
     if (rc != 0) return hip_fail((hipError_t)rc);
     return FT_OK;
 }

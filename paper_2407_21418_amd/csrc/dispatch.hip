@@ -1,8 +1,10 @@
 // One dispatcher kernel per (input dtype, register class).  Workgroup i takes tile descriptor
 // remap(i) and runs the uKernel body the descriptor names, so a single launch executes a
 // program made of one or two uKernel shapes (Sec. 5.1; Fig. 8 item 2).
-// Compiled once per -DFT_DT={0,1} -DFT_CLASS={0,1,2}.
-#include "gemm_body.h"
+// Compiled once per -DFT_DT={0,1} -DFT_CLASS={0,1,2} with the fast bodies (LDS-DMA ring, aligned
+// operands) and once per dtype with -DFT_CLASS=2 -DFT_GENERIC=1 for the general bodies (any
+// alignment, ragged reduce axis, convolution gather).
+#include "gemm_fast.h"
 #include "family.h"
 #include "launch_iface.h"
 
@@ -15,7 +17,7 @@
 
 #if FT_CLASS == 0
 #define FT_MIN_WAVES 4
-#define FT_ACC_MAX 64
+#define FT_ACC_MAX 32
 #elif FT_CLASS == 1
 #define FT_MIN_WAVES 2
 #define FT_ACC_MAX 128
@@ -36,16 +38,24 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t b, uint32_t n, uint32_t n
 }
 
 __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const uint32_t t = xcd_remap(blockIdx.x, g.n_tiles, g.num_xcds);
     const TileDesc d = g.descs[t];
-    const uint32_t code = (d.ukernel_id == g.slot_ukernel[0]) ? g.slot_code[0] : g.slot_code[1];
+    const uint32_t slot = (d.ukernel_id == g.slot_ukernel[0]) ? 0u : 1u;
+    const uint32_t code = g.slot_code[slot];
     switch (code) {
+#ifdef FT_GENERIC
+#define FT_X(CODE, WM, WN, GM, GN)                                              \
+    case CODE:                                                                  \
+        UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(g, d, smem);             \
+        break;
+#else
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
-            UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(g, d, smem);         \
+            UKernelFast<FT_DT, WM, WN, GM, GN>::run(g, d, smem, g.slot_stages[slot]); \
         break;
+#endif
         FT_FAMILY(FT_X)
 #undef FT_X
     default: break;

@@ -17,10 +17,10 @@
 #define FT_TK 64
 #define FT_NUM_CLASSES 3
 // register class of a body: accumulator registers per lane -> launch-bounds budget
-//   class 0: acc <= 64  (kernel compiled for 4 waves/SIMD, <= 128 registers)
+//   class 0: acc <= 32  (kernel compiled for 4 waves/SIMD, <= 128 registers)
 //   class 1: acc <= 128 (2 waves/SIMD, <= 256 registers)
 //   class 2: acc <= 256 (1 wave/SIMD,  <= 512 registers)
-static inline int ft_class_of_acc(int acc_regs) { return acc_regs <= 64 ? 0 : (acc_regs <= 128 ? 1 : 2); }
+static inline int ft_class_of_acc(int acc_regs) { return acc_regs <= 32 ? 0 : (acc_regs <= 128 ? 1 : 2); }
 static inline int ft_body_code(int wm, int wn, int gm, int gn) {
 #define FT_X(code, WM, WN, GM, GN) if (wm == WM && wn == WN && gm == GM && gn == GN) return code;
     FT_FAMILY(FT_X)

@@ -44,6 +44,7 @@ struct KArgs {
     uint32_t H, W, Cin, P, Q, R, S, cstride, cpad;   // conv geometry (A = NHWC image)
     uint32_t slot_ukernel[2];         // uKernel ids of the plan's (up to) two constituents
     uint32_t slot_code[2];            // their body codes in the compiled family
+    uint32_t slot_stages[2];          // LDS ring depth of each (fast path)
     uint32_t num_xcds;
 };
 

@@ -1,0 +1,290 @@
+// Fast uKernel bodies for gfx950 (aligned Matmul / BMM operands).
+//
+// Same tiling hierarchy and LDS layout as gemm_body.h, but the copy global -> LDS never touches
+// registers: global_load_lds_dwordx4 (one wave instruction = 64 lanes x 16 B = 1 KB of contiguous
+// LDS, each lane fetching from its own global address) fills a ring of `stages` LDS buffers, so
+// stages-1 k-tiles are in flight while the MFMAs consume the oldest one.  The XOR swizzles are
+// applied on the *source* side: the lane that owns LDS chunk position p of a row fetches global
+// chunk p ^ swz(row).
+//
+// The LDS reads of the MFMA fragments are issued as inline asm with hand-placed s_waitcnt, so the
+// compiler's conservative "wait for every outstanding LDS-DMA before any LDS read" does not
+// serialise the ring.  Register cost per lane: accumulators + two fragment sets + a few addresses.
+//
+// Preconditions (checked by the host before this path is chosen): A, B 16-byte aligned; row
+// pitches lda, ldb and K, N multiples of 8 elements; not a convolution.
+#pragma once
+#include "gemm_body.h"
+
+namespace ftk {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// 256 bytes of zeros: source of k-tail chunks (rows/columns of the reduce axis beyond K)
+__device__ __attribute__((aligned(256))) uint32_t ft_zero_page[64];
+
+template <int OFF> __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int OFF> __device__ __forceinline__ u32x2 lds_read_tr16_b64(uint32_t addr) {
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned char *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+template <int DT, int WM, int WN, int GM, int GN>
+struct UKernelFast {
+    static constexpr int TK = 64;
+    static constexpr int TM = GM * WM, TN = GN * WN;
+    static constexpr bool M16 = (WM == 16);
+    static constexpr int MB = M16 ? 16 : 32;
+    static constexpr int KSTEP = M16 ? 32 : 16;
+    static constexpr int KS = TK / KSTEP;             // MFMA k-steps per tile
+    static constexpr int BM = WM / MB, BN = WN / MB;
+    static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TK * TN * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    // wave-level copy instructions per stage: each wave moves a quarter of A's rows and a quarter
+    // of B's rows (16 k-rows); a quarter smaller than 1 KB is moved by the low lanes only
+    static constexpr int A_WAVE_BYTES = A_BYTES / 4, B_WAVE_BYTES = B_BYTES / 4;
+    static constexpr int LA = (A_WAVE_BYTES + 1023) / 1024, LB = (B_WAVE_BYTES + 1023) / 1024;
+    static constexpr int L = LA + LB;                 // vmcnt increments per stage per wave
+    static constexpr int MAX_AHEAD = (63 / L) < 6 ? (63 / L) : 6;   // tiles in flight beyond the current
+    static constexpr int NR = BM + 2 * BN;            // LDS read instructions per k-step
+    static_assert(NR <= 15, "lgkmcnt is 4 bits");
+    using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
+
+    template <int T> __device__ static __forceinline__ void wait_tiles(int ahead) {
+        // wait until at most `ahead` whole stages of this wave's copies are outstanding
+        if constexpr (T >= MAX_AHEAD) wait_vmcnt<MAX_AHEAD * L>();
+        else {
+            if (ahead <= T) wait_vmcnt<T * L>();
+            else wait_tiles<T + 1>(ahead);
+        }
+    }
+
+    __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem,
+                                               uint32_t stages_in) {
+        const uint32_t tid = threadIdx.x;
+        const uint32_t lane = tid & 63u;
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const uint32_t wave_m = wave / GN, wave_n = wave % GN;
+        const uint32_t m0 = d.m0, n0 = d.n0;
+        const uint32_t M = g.M, N = g.N, K = g.K;
+        const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
+        const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
+        float *__restrict__ Cb = g.C + (uint64_t)d.batch * g.strideC;
+        const uint32_t nk = (K + TK - 1) / TK;
+        uint32_t S = stages_in < 2 ? 2u : stages_in;
+        if (S > (uint32_t)MAX_AHEAD + 2) S = MAX_AHEAD + 2;
+
+        // ---- copy assignments ---------------------------------------------------------------
+        // A instruction i of this wave fills LDS bytes [wave*A_WAVE_BYTES + i*1024, +1024) of the
+        // A tile: row = that offset / 128 (+ lane / 8), chunk position = lane % 8.
+        uint32_t goff_a[LA];
+        {
+            uint32_t row0 = (wave * A_WAVE_BYTES) / 128 + lane / 8;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                uint32_t row = row0 + i * 8;
+                uint32_t kc = (lane & 7u) ^ swzA(row);
+                uint32_t gm = m0 + row;
+                if (gm >= M) gm = M - 1;              // clamp: garbage rows are never stored
+                goff_a[i] = gm * g.lda + kc * 8;
+            }
+        }
+        const bool a_lane_on = (A_WAVE_BYTES >= 1024) || lane < (uint32_t)(A_WAVE_BYTES / 16);
+        // B instruction i fills bytes [wave*B_WAVE_BYTES + i*1024, +1024) of the B tile.
+        uint32_t goff_b[LB];
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            uint32_t o = wave * B_WAVE_BYTES + i * 1024 + lane * 16;
+            uint32_t krow = o / (TN * 2), p = (o % (TN * 2)) / 16;
+            uint32_t nc = p ^ swzB<TN>(krow);
+            uint32_t col = n0 + nc * 8;
+            if (col >= N) col = n0;                   // clamp: garbage columns are never stored
+            goff_b[i] = krow * g.ldb + col;
+        }
+        const bool b_lane_on = (B_WAVE_BYTES >= 1024) || lane < (uint32_t)(B_WAVE_BYTES / 16);
+        const bool k_tail = (K % TK) != 0;
+
+        auto issue_impl = [&](uint32_t kt, auto tail_c) {
+            constexpr bool tail = decltype(tail_c)::value;
+            unsigned char *st = smem + (kt % S) * STAGE_BYTES;
+            const uint32_t k0 = kt * TK;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const uint16_t *p = Ab + (goff_a[i] + k0);
+                if constexpr (tail) {
+                    // logical chunk of this lane in instruction i (recomputed: tail tile only)
+                    uint32_t row = (wave * A_WAVE_BYTES) / 128 + lane / 8 + i * 8;
+                    uint32_t kc = (lane & 7u) ^ swzA(row);
+                    if (k0 + kc * 8 >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                }
+                if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const uint16_t *p = Bb + (goff_b[i] + k0 * g.ldb);
+                if constexpr (tail) {
+                    uint32_t krow = (wave * B_WAVE_BYTES + i * 1024 + lane * 16) / (TN * 2);
+                    if (k0 + krow >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                }
+                if (b_lane_on) lds_dma16(p, st + A_BYTES + wave * B_WAVE_BYTES + i * 1024);
+            }
+        };
+        auto issue = [&](uint32_t kt) {
+            if (k_tail && kt + 1 == nk) issue_impl(kt, std::true_type{});
+            else issue_impl(kt, std::false_type{});
+        };
+
+        // ---- fragment read addresses -----------------------------------------------------------
+        const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+        // A: row = wave_m*WM + bi*MB + lane%MB ; chunk = ks*(KSTEP/8) + lane/MB, position = chunk ^ swzA(row).
+        // The ks term only touches bits the lane term leaves clear, so it is an XOR by a constant.
+        const uint32_t fa_row = wave_m * WM + (lane % MB);
+        const uint32_t fa_addr0 = sbase + fa_row * (TK * 2) + (((lane / MB) ^ swzA(fa_row)) << 4);
+        // B through the transposing read (see gemm_body.h): lane j of a 16-lane group addresses row
+        // j/4, columns 4*(j%4)..+3 of a 4 x 16 block and receives column j, rows 0..3.
+        const uint32_t j16 = lane & 15u;
+        uint32_t fb_colgrp, fb_k8;
+        if constexpr (M16) { fb_colgrp = 0; fb_k8 = lane >> 4; }
+        else { fb_colgrp = (lane >> 4) & 1u; fb_k8 = lane >> 5; }
+        const uint32_t fb_row0 = fb_k8 * 8 + (j16 >> 2);
+        uint32_t fb_addr[BN];
+#pragma unroll
+        for (int bj = 0; bj < BN; ++bj) {
+            uint32_t col = wave_n * WN + bj * MB + fb_colgrp * 16 + (j16 & 3u) * 4;
+            fb_addr[bj] = sbase + A_BYTES + fb_row0 * (TN * 2) + (((col >> 3) ^ swzB<TN>(fb_row0)) << 4) + (col & 7u) * 2;
+        }
+
+        Acc acc[BM][BN];
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
+
+        // ---- prologue: fill S-1 stages ------------------------------------------------------------
+        for (uint32_t s = 0; s + 1 < S && s < nk; ++s) issue(s);
+
+        for (uint32_t kt = 0; kt < nk; ++kt) {
+            // copies issued so far: tiles 0 .. min(kt+S-2, nk-1); tile kt must have landed
+            uint32_t newest = kt + S - 2 < nk - 1 ? kt + S - 2 : nk - 1;
+            wait_tiles<0>((int)(newest - kt));
+            __builtin_amdgcn_s_barrier();      // tile kt visible to every wave; stage (kt-1)%S is free again
+            if (kt + S - 1 < nk) issue(kt + S - 1);
+
+            const uint32_t soff = (kt % S) * STAGE_BYTES;
+            const uint32_t a_addr = fa_addr0 + soff;
+            uint32_t b_addr[BN];
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + soff;
+
+            u32x4 fa[2][BM];
+            u32x2 fb[2][BN][2];
+            read_step<0, 0>(a_addr, b_addr, fa, fb);
+            step<0>(a_addr, b_addr, fa, fb, acc);
+        }
+
+        // ---- epilogue (same lane layout as gemm_body.h) ------------------------------------------------
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) {
+                uint32_t col = n0 + wave_n * WN + bj * MB + (lane % MB);
+                uint32_t rbase = m0 + wave_m * WM + bi * MB;
+                if (col >= N) continue;
+#pragma unroll
+                for (int e = 0; e < (M16 ? 4 : 16); ++e) {
+                    uint32_t row = M16 ? rbase + 4 * (lane / 16) + e
+                                       : rbase + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
+                    if (row < M) Cb[row * g.ldc + col] = acc[bi][bj][e];
+                }
+            }
+    }
+
+    // LDS reads of the A and B fragments of k-step ks into fragment set buf.  Row offsets of the
+    // accumulator blocks and the k-step offset of B go into the instructions' offset fields.
+    template <int ks, int buf, int bi = 0>
+    __device__ static __forceinline__ void read_a(uint32_t aa, u32x4 (&fa)[2][BM]) {
+        fa[buf][bi] = lds_read_b128<bi * MB * TK * 2>(aa);
+        if constexpr (bi + 1 < BM) read_a<ks, buf, bi + 1>(aa, fa);
+    }
+    template <int ks, int buf, int bj = 0>
+    __device__ static __forceinline__ void read_b(const uint32_t (&b_addr)[BN], u32x2 (&fb)[2][BN][2]) {
+        fb[buf][bj][0] = lds_read_tr16_b64<(ks * KSTEP) * TN * 2>(b_addr[bj]);
+        fb[buf][bj][1] = lds_read_tr16_b64<(ks * KSTEP + 4) * TN * 2>(b_addr[bj]);
+        if constexpr (bj + 1 < BN) read_b<ks, buf, bj + 1>(b_addr, fb);
+    }
+    template <int ks, int buf>
+    __device__ static __forceinline__ void read_step(uint32_t a_addr, const uint32_t (&b_addr)[BN],
+                                                     u32x4 (&fa)[2][BM], u32x2 (&fb)[2][BN][2]) {
+        read_a<ks, buf>(a_addr ^ (uint32_t)(ks * (KSTEP / 8) * 16), fa);
+        read_b<ks, buf>(b_addr, fb);
+    }
+
+    // k-steps of one tile, software pipelined: the reads of step ks+1 are in flight during the MFMAs of ks
+    template <int ks>
+    __device__ static __forceinline__ void step(uint32_t a_addr, const uint32_t (&b_addr)[BN], u32x4 (&fa)[2][BM],
+                                                u32x2 (&fb)[2][BN][2], Acc (&acc)[BM][BN]) {
+        constexpr int buf = ks & 1;
+        if constexpr (ks + 1 < KS) {
+            read_step<ks + 1, buf ^ 1>(a_addr, b_addr, fa, fb);
+            wait_frag<NR>(fa[buf], fb[buf]);
+        } else {
+            wait_frag<0>(fa[buf], fb[buf]);
+        }
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) {
+                uint4 a = __builtin_bit_cast(uint4, fa[buf][bi]);
+                uint4 b = make_uint4(fb[buf][bj][0][0], fb[buf][bj][0][1], fb[buf][bj][1][0], fb[buf][bj][1][1]);
+                if constexpr (M16) acc[bi][bj] = mfma16<DT>(a, b, acc[bi][bj]);
+                else acc[bi][bj] = mfma32<DT>(a, b, acc[bi][bj]);
+            }
+        if constexpr (ks + 1 < KS) step<ks + 1>(a_addr, b_addr, fa, fb, acc);
+    }
+
+    // s_waitcnt lgkmcnt(N) that also "produces" the fragment registers, so no consumer can be
+    // scheduled above it
+    template <int N>
+    __device__ static __forceinline__ void wait_frag(u32x4 (&a)[BM], u32x2 (&b)[BN][2]) {
+        if constexpr (BM == 1 && BN == 1)
+            asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a[0]), "+v"(b[0][0]), "+v"(b[0][1]) : "n"(N));
+        else if constexpr (BM == 1 && BN == 2)
+            asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a[0]), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]) : "n"(N));
+        else if constexpr (BM == 1 && BN == 4)
+            asm volatile("s_waitcnt lgkmcnt(%9)" : "+v"(a[0]), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]),
+                         "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1]) : "n"(N));
+        else if constexpr (BM == 2 && BN == 1)
+            asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0][0]), "+v"(b[0][1]) : "n"(N));
+        else if constexpr (BM == 2 && BN == 2)
+            asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]) : "n"(N));
+        else if constexpr (BM == 2 && BN == 4)
+            asm volatile("s_waitcnt lgkmcnt(%10)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1]),
+                         "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1]) : "n"(N));
+        else if constexpr (BM == 4 && BN == 2)
+            asm volatile("s_waitcnt lgkmcnt(%8)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0][0]), "+v"(b[0][1]),
+                         "+v"(b[1][0]), "+v"(b[1][1]) : "n"(N));
+        else if constexpr (BM == 4 && BN == 4)
+            asm volatile("s_waitcnt lgkmcnt(%12)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0][0]), "+v"(b[0][1]),
+                         "+v"(b[1][0]), "+v"(b[1][1]), "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1]) : "n"(N));
+        else
+            static_assert(BM == 0, "unsupported fragment shape");
+    }
+};
+
+}  // namespace ftk

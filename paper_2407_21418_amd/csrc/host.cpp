@@ -15,7 +15,7 @@ typedef unsigned __int128 u128;
 constexpr uint32_t QBITS = 20;
 constexpr uint32_t GRANULE = 16;      // smallest MFMA output extent (16x16x32)
 constexpr uint32_t ELT = 2;           // bytes per input element
-constexpr uint32_t STAGES = 2;
+constexpr uint32_t MIN_STAGES = 2, MAX_STAGES = 8;
 
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 inline uint64_t ceil_by(uint64_t x, uint64_t m) { return m * ceil_div(x, m); }
@@ -43,7 +43,7 @@ void tuning_defaults(ft_tuning *t) {
     t->eps_min_pm = 500; t->eps_max_pm = 950; t->eps_step_pm = 10;   // Sec. 4.2: 50%..95%, +1%
     t->lam_max_pm = 950; t->lam_min_pm = 900; t->lam_step_pm = 1;    // 95%..90%, -0.1%
     t->zeta = 2;                                                     // Sec. 4.2
-    t->rest_regs = 64;
+    t->rest_regs = 72;
     t->psi_num = 1; t->psi_den = 8;
     t->c0 = t->c1 = t->c2 = 1;                                       // Sec. 5.2
 }
@@ -352,7 +352,13 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
                 if (sv.n && ceil_by(sv.n, GRANULE) % tn) continue;
-                uint32_t lds = STAGES * (tm + tn) * tk * ELT;
+                // LDS ring depth: as many k-tiles as fit in one workgroup's share of the LDS when
+                // zeta workgroups are resident (2..8); every stage beyond the one being consumed
+                // is global-memory traffic in flight
+                uint32_t stage_bytes = (tm + tn) * tk * ELT;
+                uint32_t stages = (h.lds_bytes_per_cu / t.zeta) / stage_bytes;
+                stages = std::max(MIN_STAGES, std::min(MAX_STAGES, stages));
+                uint32_t lds = stages * stage_bytes;
                 if (lds > h.lds_bytes_per_cu) continue;                  // mem.IsOverflow
                 uint32_t acc = wm * wn / h.wave_size;
                 uint32_t regs = acc + t.rest_regs;
@@ -364,7 +370,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 std::memset(&u, 0, sizeof(u));
                 u.struct_size = sizeof(u);
                 u.tm = tm; u.tn = tn; u.tk = tk; u.wm = wm; u.wn = wn; u.gm = gm; u.gn = gn;
-                u.mfma = mfma; u.stages = STAGES; u.lds_bytes = lds; u.acc_regs = acc; u.regs = regs;
+                u.mfma = mfma; u.stages = stages; u.lds_bytes = lds; u.acc_regs = acc; u.regs = regs;
                 // registers are granted in power-of-two fractions of the file (128, 256, 512)
                 uint32_t budget = h.regs_per_lane / 4;
                 while (budget < regs) budget *= 2;
@@ -471,6 +477,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     pl->img_h = shape->img_h; pl->img_w = shape->img_w; pl->out_p = r.P; pl->out_q = r.Q;
     pl->slot_id[0] = pl->slot_id[1] = 0;
     pl->slot_code[0] = pl->slot_code[1] = 0;
+    pl->slot_stages[0] = pl->slot_stages[1] = MIN_STAGES;
     ft_plan_stats &s = pl->st;
     std::memset(&s, 0, sizeof(s));
     s.struct_size = sizeof(s);
@@ -552,12 +559,13 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         s.count_tau[i] = best.part[i].count;
         pl->slot_id[i] = u.id;
         pl->slot_code[i] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn);
+        pl->slot_stages[i] = u.stages;
         lds = std::max(lds, u.lds_bytes);
         uint32_t by_model = 0;
         for (uint32_t b = set->hw.regs_per_lane / 4; b < u.reg_budget && by_model < FT_NUM_CLASSES - 1; b *= 2) ++by_model;
         klass = std::max<uint32_t>(klass, std::max<uint32_t>(by_model, (uint32_t)ft_class_of_acc((int)u.acc_regs)));
     }
-    if (best.nparts == 1) { pl->slot_id[1] = pl->slot_id[0]; pl->slot_code[1] = pl->slot_code[0]; }
+    if (best.nparts == 1) { pl->slot_id[1] = pl->slot_id[0]; pl->slot_code[1] = pl->slot_code[0]; pl->slot_stages[1] = pl->slot_stages[0]; }
     s.block_bound = best.block_bound;
     s.pad_q20 = best.pad_q; s.occ_q20 = best.occ_q; s.cmr_q20 = best.cmr_q; s.sia_q20 = best.sia_q;
     s.lds_bytes = lds;

@@ -5,8 +5,13 @@
 #define FT_CAT_(a, b, c, d) a##b##c##d
 #define FT_CAT(a, b, c, d) FT_CAT_(a, b, c, d)
 #if defined(FT_DT) && defined(FT_CLASS)
+#ifdef FT_GENERIC
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _gen, )
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _gen, )
+#else
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _c, FT_CLASS)
+#endif
 #endif
 namespace ftk { struct KArgs; }
 extern "C" {
@@ -16,4 +21,6 @@ int ft_launch_dt0_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c0(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_gen(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_gen(const ftk::KArgs *, uint32_t, void *);
 }

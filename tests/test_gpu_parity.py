@@ -36,12 +36,14 @@ def family():
     return [(u.tm, u.tn, u.wm, u.wn, u.gm, u.gn) for u in P.derive_ukernels(op)]
 
 
+@pytest.mark.parametrize("aligned", [True, False], ids=["dma", "general"])
 @pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
 @pytest.mark.parametrize("body", family(), ids=lambda b: "t%dx%d_w%dx%d" % b[:4])
-def test_every_ukernel_body(body, dtype):
+def test_every_ukernel_body(body, dtype, aligned):
     """Each compiled body alone (forced single-uKernel program): 2 x 2 tiles with a ragged tail
-    on both axes, a ragged k tail, a column count that is not a multiple of 8 (element-wise
-    loads on the last column tile) and batch 2."""
+    on both axes, a k extent that is not a multiple of the k-tile, and batch 2.  aligned: row
+    lengths are multiples of 8 elements (LDS-DMA bodies, zero-page k tail); otherwise odd row
+    lengths (general bodies: unaligned vector loads, element-wise partial chunks)."""
     tm, tn, wm, wn, gm, gn = body
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=8192, n_lo=0, n_hi=8192,
                                          k_lo=0, k_hi=4096))
@@ -49,8 +51,8 @@ def test_every_ukernel_body(body, dtype):
     ids = [i for i in range(ft.ft_ukset_size(s))
            if (lambda u: (u.tm, u.tn, u.wm, u.wn) == (tm, tn, wm, wn))(ft.ft_ukset_get(s, i))]
     assert len(ids) == 1
-    M, N, K, nb = 2 * tm - 5, 2 * tn - 11, 200, 2
-    g = np.random.default_rng(tm * 7 + tn * 3 + wm + dtype)
+    M, N, K, nb = (2 * tm - 5, 2 * tn - 8, 200, 2) if aligned else (2 * tm - 5, 2 * tn - 11, 203, 2)
+    g = np.random.default_rng(tm * 7 + tn * 3 + wm + dtype + 1000 * aligned)
     A = si.normal_bits(g, (nb, M, K), 1.0, dtype)
     B = si.normal_bits(g, (nb, K, N), 1.0, dtype)
     plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=M, n=N, k=K), ft.FT_PLAN_FORCED,

@@ -90,13 +90,16 @@ def test_resource_closed_forms():
     by = {(u.tm, u.tn, u.wm, u.wn): u for u in uks}
     u = by[(256, 256, 128, 128)]
     assert u.lds_bytes == 131072 and u.acc_regs == 256 and u.max_wg_per_cu == 1
-    assert u.regs == 320 and u.reg_budget == 512
+    assert u.regs == 328 and u.reg_budget == 512
     u = by[(128, 128, 64, 64)]
     assert u.lds_bytes == 65536 and u.acc_regs == 64 and u.max_wg_per_cu == 2
-    assert u.regs == 128 and u.reg_budget == 128      # 4 waves/SIMD by registers, 2 by LDS
+    assert u.regs == 136 and u.reg_budget == 256 and u.stages == 2   # 2 waves/SIMD by registers, 2 workgroups by LDS
+    assert by[(64, 128, 32, 64)].reg_budget == 128
+    assert by[(16, 64, 16, 16)].stages == 8 and by[(64, 64, 32, 32)].stages == 5
     assert by[(128, 256, 64, 128)].reg_budget == 256
     for u in uks:
-        assert u.lds_bytes == 2 * (u.tm + u.tn) * u.tk * 2 <= 163840
+        assert 2 <= u.stages <= 8 and u.stages == max(2, min(8, 81920 // ((u.tm + u.tn) * 128)))
+        assert u.lds_bytes == u.stages * (u.tm + u.tn) * u.tk * 2 <= 163840
         assert u.acc_regs * 64 == u.wm * u.wn
         assert u.tm == u.gm * u.wm and u.tn == u.gn * u.wn and u.gm * u.gn == 4
         assert 768 % u.tn == 0                              # static axis divided evenly
