@@ -126,10 +126,10 @@ typedef struct ft_ukernel_info {
     uint32_t id;                   /* index in the set                                       */
     uint32_t tm, tn, tk;           /* smem_tile: workgroup tile staged in LDS                */
     uint32_t wm, wn;               /* reg_tile: per-wave fp32 accumulator tile               */
-    uint32_t gm, gn;               /* wave grid (gm*gn = 4 wave64)                           */
+    uint32_t gm, gn, gk;           /* wave grid over rows, columns, reduce axis (gm*gn*gk = 4)*/
     uint32_t mfma;                 /* 0: 32x32x16, 1: 16x16x32                               */
     uint32_t stages;               /* LDS ring depth: k-tiles resident at once (2..8)        */
-    uint32_t lds_bytes;            /* stages*(tm+tn)*tk*2                                    */
+    uint32_t lds_bytes;            /* gk*stages*(tm+tn)*tk*2                                 */
     uint32_t acc_regs;             /* wm*wn/64 per lane                                      */
     uint32_t regs;                 /* acc_regs + RestRegs                                    */
     uint32_t max_wg_per_cu;        /* resident workgroups per CU allowed by LDS and registers*/

@@ -148,8 +148,9 @@ class UKernel:
     tk: int
     wm: int          # reg_tile: per-wave accumulator tile
     wn: int
-    gm: int          # wave grid inside the workgroup
+    gm: int          # wave grid inside the workgroup: rows, columns, reduce axis
     gn: int
+    gk: int
     mfma: int        # 0 = 32x32x16, 1 = 16x16x32
     stages: int
     lds_bytes: int
@@ -205,7 +206,9 @@ def wave_tiles():
     return out
 
 
-WAVE_GRIDS = ((1, 4), (2, 2), (4, 1))      # four wave64 per workgroup, one per SIMD
+# four wave64 per workgroup, one per SIMD, arranged over (rows, columns, reduce axis); in the
+# split-k grid every wave owns the whole tile and a quarter of k
+WAVE_GRIDS = ((1, 4, 1), (2, 2, 1), (4, 1, 1), (1, 1, 4))
 TK_CHOICES = (64,)                          # 64 16-bit elements = one 128-byte line
 MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
@@ -251,7 +254,9 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     waves_per_simd = 1                      # 4 waves on 4 SIMDs
     cand = []
     for wm, wn, mfma in wave_tiles():
-        for gm, gn in WAVE_GRIDS:
+        for gm, gn, gk in WAVE_GRIDS:
+            if gk > 1 and not (1024 <= wm * wn <= 4096):
+                continue
             for tk in TK_CHOICES:
                 tm, tn = gm * wm, gn * wn
                 # static space axes are divided evenly (after rounding to the MFMA granule,
@@ -262,9 +267,14 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     continue
                 # LDS ring depth: the k-tiles that fit in one workgroup's share of the LDS when
                 # zeta workgroups are resident, between 2 and 8
+                # (a split-k workgroup keeps one ring per wave and is meant to own the CU's LDS)
                 stage_bytes = (tm + tn) * tk * ELT
-                stages = max(MIN_STAGES, min(MAX_STAGES, (hw["lds_bytes_per_cu"] // t["zeta"]) // stage_bytes))
-                lds = stages * stage_bytes
+                if gk == 1:
+                    stages = (hw["lds_bytes_per_cu"] // t["zeta"]) // stage_bytes
+                else:
+                    stages = hw["lds_bytes_per_cu"] // (gk * stage_bytes)
+                stages = max(MIN_STAGES, min(MAX_STAGES, stages))
+                lds = gk * stages * stage_bytes
                 if lds > hw["lds_bytes_per_cu"]:
                     continue                                        # mem.IsOverflow
                 acc = wm * wn // hw["wave_size"]
@@ -277,7 +287,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     continue                                        # Eq. 6
                 cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
                           hw["max_waves_per_simd"])
-                cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, mfma, stages, lds, acc, regs,
+                cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, gk, mfma, stages, lds, acc, regs,
                                     budget, cap, (cn << Q) // cd))
     cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))
     for i, u in enumerate(cand):

@@ -56,7 +56,7 @@ class ft_op_desc(_S):
 
 class ft_ukernel_info(_S):
     _fields_ = [(n, u32) for n in (
-        "struct_size", "id", "tm", "tn", "tk", "wm", "wn", "gm", "gn", "mfma", "stages", "lds_bytes",
+        "struct_size", "id", "tm", "tn", "tk", "wm", "wn", "gm", "gn", "gk", "mfma", "stages", "lds_bytes",
         "acc_regs", "regs", "max_wg_per_cu", "reg_budget")] + [("cmr_q20", u64)]
 
 

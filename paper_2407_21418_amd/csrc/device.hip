@@ -100,6 +100,10 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
     const bool fast = !a.is_conv && a.K % 8 == 0 && a.N % 8 == 0 &&
                       (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0) &&
                       (a.strideA % 8 == 0) && (a.strideB % 8 == 0);
+    if (!fast) {
+        a.slot_code[0] = (uint32_t)ft_general_code((int)a.slot_code[0]);
+        a.slot_code[1] = (uint32_t)ft_general_code((int)a.slot_code[1]);
+    }
     int rc = fast ? kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream)
                   : kLaunchGeneric[plan->op.dtype](&a, plan->st.lds_bytes, hip_stream);
     if (rc != 0) return hip_fail((hipError_t)rc);

@@ -58,6 +58,15 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #endif
         FT_FAMILY(FT_X)
 #undef FT_X
+#ifndef FT_GENERIC
+#define FT_X(CODE, TM, TN, TWIN)                                                \
+    case CODE:                                                                  \
+        if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \
+            UKernelSplitK<FT_DT, TM, TN>::run(g, d, smem, g.slot_stages[slot]);  \
+        break;
+        FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+#endif
     default: break;
     }
 }

@@ -14,6 +14,12 @@
     X(24, 128, 64, 1, 4) X(25, 128, 64, 2, 2) X(26, 128, 64, 4, 1)                       \
     X(27, 128, 128, 1, 4) X(28, 128, 128, 2, 2) X(29, 128, 128, 4, 1)
 
+// Split-k wave grid (1 x 1 x 4): X(code, TM, TN, twin) -- every wave owns the whole TM x TN tile and
+// a quarter of the reduce axis.  twin = code of the standard-grid body with the same tile, used by
+// the general (unaligned / convolution) path, which has no split-k variant.
+#define FT_FAMILY_SPLITK(X)                                                              \
+    X(30, 16, 64, 0) X(31, 32, 32, 1) X(32, 32, 64, 4) X(33, 64, 32, 5) X(34, 64, 64, 10)
+
 #define FT_TK 64
 #define FT_NUM_CLASSES 3
 // register class of a body: accumulator registers per lane -> launch-bounds budget
@@ -21,9 +27,22 @@
 //   class 1: acc <= 128 (2 waves/SIMD, <= 256 registers)
 //   class 2: acc <= 256 (1 wave/SIMD,  <= 512 registers)
 static inline int ft_class_of_acc(int acc_regs) { return acc_regs <= 32 ? 0 : (acc_regs <= 128 ? 1 : 2); }
-static inline int ft_body_code(int wm, int wn, int gm, int gn) {
+static inline int ft_body_code(int wm, int wn, int gm, int gn, int gk) {
+    if (gk == 1) {
 #define FT_X(code, WM, WN, GM, GN) if (wm == WM && wn == WN && gm == GM && gn == GN) return code;
-    FT_FAMILY(FT_X)
+        FT_FAMILY(FT_X)
 #undef FT_X
+    } else if (gk == 4 && gm == 1 && gn == 1) {
+#define FT_X(code, TM, TN, TWIN) if (wm == TM && wn == TN) return code;
+        FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+    }
     return -1;
+}
+// body the general path runs for a given code (split-k codes map to their standard-grid twin)
+static inline int ft_general_code(int code) {
+#define FT_X(c, TM, TN, TWIN) if (code == c) return TWIN;
+    FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+    return code;
 }

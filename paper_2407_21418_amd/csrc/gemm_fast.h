@@ -287,4 +287,177 @@ struct UKernelFast {
     }
 };
 
+
+// ---------------------------------------------------------------------------------------------
+// Split-k wave grid (1 x 1 x 4): every wave owns the whole TM x TN output tile and a quarter of the
+// reduce axis (k-tiles w, w+4, w+8, ...), with a private LDS ring filled by its own LDS-DMA copies.
+// No workgroup barrier in the main loop; the four partial tiles are summed through LDS at the end.
+// For shapes with few tiles and a long reduce axis the barrier-per-k-tile loop above is bound by
+// its own latency chain; here each SIMD runs an independent, deeply prefetched stream.
+// ---------------------------------------------------------------------------------------------
+template <int DT, int TM, int TN>
+struct UKernelSplitK {
+    static constexpr int TK = 64;
+    static constexpr bool M16 = (TM == 16);
+    static constexpr int MB = M16 ? 16 : 32;
+    static constexpr int KSTEP = M16 ? 32 : 16;
+    static constexpr int KS = TK / KSTEP;
+    static constexpr int BM = TM / MB, BN = TN / MB;
+    static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TK * TN * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LA = A_BYTES / 1024, LB = B_BYTES / 1024;
+    static constexpr int L = LA + LB;
+    static constexpr int MAX_AHEAD = (63 / L) < 6 ? (63 / L) : 6;
+    static constexpr int NR = BM + 2 * BN;
+    static constexpr int NREG = TM * TN / 64;          // accumulator registers per lane
+    static_assert(NR <= 15 && LA >= 1 && LB >= 1 && NREG % 4 == 0, "unsupported split-k tile");
+    using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
+    using Std = UKernelFast<DT, TM, TN, 1, 1>;         // fragment helpers only (same layouts)
+
+    template <int T> __device__ static __forceinline__ void wait_tiles(int ahead) {
+        if constexpr (T >= MAX_AHEAD) wait_vmcnt<MAX_AHEAD * L>();
+        else {
+            if (ahead <= T) wait_vmcnt<T * L>();
+            else wait_tiles<T + 1>(ahead);
+        }
+    }
+
+    __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem,
+                                               uint32_t stages_in) {
+        const uint32_t tid = threadIdx.x;
+        const uint32_t lane = tid & 63u;
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const uint32_t m0 = d.m0, n0 = d.n0;
+        const uint32_t M = g.M, N = g.N, K = g.K;
+        const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
+        const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
+        float *__restrict__ Cb = g.C + (uint64_t)d.batch * g.strideC;
+        const uint32_t nk = (K + TK - 1) / TK;
+        const uint32_t nkw = nk > wave ? (nk - wave + 3) / 4 : 0;     // k-tiles of this wave
+        uint32_t S = stages_in < 2 ? 2u : stages_in;
+        if (S > (uint32_t)MAX_AHEAD + 2) S = MAX_AHEAD + 2;
+        unsigned char *ring = smem + wave * S * STAGE_BYTES;          // this wave's private ring
+
+        uint32_t goff_a[LA], goff_b[LB];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            uint32_t row = i * 8 + lane / 8;
+            uint32_t kc = (lane & 7u) ^ swzA(row);
+            uint32_t gm = m0 + row;
+            if (gm >= M) gm = M - 1;
+            goff_a[i] = gm * g.lda + kc * 8;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            uint32_t o = i * 1024 + lane * 16;
+            uint32_t krow = o / (TN * 2), p = (o % (TN * 2)) / 16;
+            uint32_t nc = p ^ swzB<TN>(krow);
+            uint32_t col = n0 + nc * 8;
+            if (col >= N) col = n0;
+            goff_b[i] = krow * g.ldb + col;
+        }
+        const bool k_tail = (K % TK) != 0;
+
+        auto issue_impl = [&](uint32_t j, auto tail_c) {
+            constexpr bool tail = decltype(tail_c)::value;
+            unsigned char *st = ring + (j % S) * STAGE_BYTES;
+            const uint32_t k0 = (wave + 4 * j) * TK;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const uint16_t *p = Ab + (goff_a[i] + k0);
+                if constexpr (tail) {
+                    uint32_t row = i * 8 + lane / 8;
+                    uint32_t kc = (lane & 7u) ^ swzA(row);
+                    if (k0 + kc * 8 >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                }
+                lds_dma16(p, st + i * 1024);
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const uint16_t *p = Bb + (goff_b[i] + k0 * g.ldb);
+                if constexpr (tail) {
+                    uint32_t krow = (i * 1024 + lane * 16) / (TN * 2);
+                    if (k0 + krow >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                }
+                lds_dma16(p, st + A_BYTES + i * 1024);
+            }
+        };
+        auto issue = [&](uint32_t j) {
+            if (k_tail && wave + 4 * j + 1 == nk) issue_impl(j, std::true_type{});
+            else issue_impl(j, std::false_type{});
+        };
+
+        const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem +
+                               wave * S * STAGE_BYTES;
+        const uint32_t fa_row = lane % MB;
+        const uint32_t fa_addr0 = sbase + fa_row * (TK * 2) + (((lane / MB) ^ swzA(fa_row)) << 4);
+        const uint32_t j16 = lane & 15u;
+        uint32_t fb_colgrp, fb_k8;
+        if constexpr (M16) { fb_colgrp = 0; fb_k8 = lane >> 4; }
+        else { fb_colgrp = (lane >> 4) & 1u; fb_k8 = lane >> 5; }
+        const uint32_t fb_row0 = fb_k8 * 8 + (j16 >> 2);
+        uint32_t fb_addr[BN];
+#pragma unroll
+        for (int bj = 0; bj < BN; ++bj) {
+            uint32_t col = bj * MB + fb_colgrp * 16 + (j16 & 3u) * 4;
+            fb_addr[bj] = sbase + A_BYTES + fb_row0 * (TN * 2) + (((col >> 3) ^ swzB<TN>(fb_row0)) << 4) + (col & 7u) * 2;
+        }
+
+        Acc acc[BM][BN];
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
+
+        for (uint32_t s = 0; s + 1 < S && s < nkw; ++s) issue(s);
+        for (uint32_t j = 0; j < nkw; ++j) {
+            uint32_t newest = j + S - 2 < nkw - 1 ? j + S - 2 : nkw - 1;
+            wait_tiles<0>((int)(newest - j));
+            // stage (j-1)%S was fully read by this wave (its last k-step waited lgkmcnt(0))
+            if (j + S - 1 < nkw) issue(j + S - 1);
+            const uint32_t soff = (j % S) * STAGE_BYTES;
+            const uint32_t a_addr = fa_addr0 + soff;
+            uint32_t b_addr[BN];
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + soff;
+            u32x4 fa[2][BM];
+            u32x2 fb[2][BN][2];
+            Std::template read_step<0, 0>(a_addr, b_addr, fa, fb);
+            Std::template step<0>(a_addr, b_addr, fa, fb, acc);
+        }
+
+        // ---- sum the four partial tiles: partials go to the wave's own (now idle) ring as
+        // [register][lane] floats, then wave w adds up and stores registers w*NREG/4 .. +NREG/4
+        float *part = reinterpret_cast<float *>(ring);
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                for (int e = 0; e < (M16 ? 4 : 16); ++e)
+                    part[((bi * BN + bj) * (M16 ? 4 : 16) + e) * 64 + lane] = acc[bi][bj][e];
+        __syncthreads();
+        constexpr int PER = NREG / 4;
+        constexpr int RPB = M16 ? 4 : 16;               // registers per accumulator block
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                for (int e = 0; e < RPB; ++e) {
+                    const int r = (bi * BN + bj) * RPB + e;
+                    if (r / PER != (int)wave) continue;         // uniform per wave
+                    float sum = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        sum += reinterpret_cast<const float *>(smem + w * S * STAGE_BYTES)[r * 64 + lane];
+                    uint32_t col = n0 + bj * MB + (lane % MB);
+                    uint32_t row = m0 + bi * MB + (M16 ? 4 * (lane / 16) + e : 8 * (e / 4) + 4 * (lane / 32) + (e % 4));
+                    if (row < M && col < N) Cb[row * g.ldc + col] = sum;
+                }
+    }
+};
+
 }  // namespace ftk

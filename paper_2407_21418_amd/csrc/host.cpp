@@ -338,7 +338,9 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
     // HardwareAlign: RegTileRule (per-wave accumulator tiles built from MFMA shapes) x
     // SmemTileRule (wave grids; tk = one 128-byte line of 16-bit elements)
     static const uint32_t sizes[4] = {16, 32, 64, 128};
-    static const uint32_t grids[3][2] = {{1, 4}, {2, 2}, {4, 1}};
+    // wave grids over (rows, columns, reduce axis); the split-k grid lets each wave own the whole
+    // tile and a quarter of k (accumulator tiles of 1024..4096 elements only)
+    static const uint32_t grids[4][3] = {{1, 4, 1}, {2, 2, 1}, {4, 1, 1}, {1, 1, 4}};
     for (uint32_t wm : sizes)
         for (uint32_t wn : sizes) {
             uint32_t mfma;
@@ -346,19 +348,22 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
             else if (wm >= 32 && wn >= 32 && wm <= 2 * wn && wn <= 2 * wm) mfma = 0;
             else continue;
             for (auto &g : grids) {
-                uint32_t gm = g[0], gn = g[1], tk = FT_TK;
+                uint32_t gm = g[0], gn = g[1], gk = g[2], tk = FT_TK;
                 uint32_t tm = gm * wm, tn = gn * wn;
-                if (ft_body_code(wm, wn, gm, gn) < 0) continue;          // no compiled body
+                if (gk > 1 && (wm * wn < 1024 || wm * wn > 4096)) continue;
+                if (ft_body_code(wm, wn, gm, gn, gk) < 0) continue;      // no compiled body
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
                 if (sv.n && ceil_by(sv.n, GRANULE) % tn) continue;
                 // LDS ring depth: as many k-tiles as fit in one workgroup's share of the LDS when
                 // zeta workgroups are resident (2..8); every stage beyond the one being consumed
                 // is global-memory traffic in flight
+                // (a split-k workgroup keeps one ring per wave and is meant to own the CU's LDS)
                 uint32_t stage_bytes = (tm + tn) * tk * ELT;
-                uint32_t stages = (h.lds_bytes_per_cu / t.zeta) / stage_bytes;
+                uint32_t stages = gk == 1 ? (h.lds_bytes_per_cu / t.zeta) / stage_bytes
+                                          : h.lds_bytes_per_cu / (gk * stage_bytes);
                 stages = std::max(MIN_STAGES, std::min(MAX_STAGES, stages));
-                uint32_t lds = stages * stage_bytes;
+                uint32_t lds = gk * stages * stage_bytes;
                 if (lds > h.lds_bytes_per_cu) continue;                  // mem.IsOverflow
                 uint32_t acc = wm * wn / h.wave_size;
                 uint32_t regs = acc + t.rest_regs;
@@ -369,7 +374,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 ft_ukernel_info u;
                 std::memset(&u, 0, sizeof(u));
                 u.struct_size = sizeof(u);
-                u.tm = tm; u.tn = tn; u.tk = tk; u.wm = wm; u.wn = wn; u.gm = gm; u.gn = gn;
+                u.tm = tm; u.tn = tn; u.tk = tk; u.wm = wm; u.wn = wn; u.gm = gm; u.gn = gn; u.gk = gk;
                 u.mfma = mfma; u.stages = stages; u.lds_bytes = lds; u.acc_regs = acc; u.regs = regs;
                 // registers are granted in power-of-two fractions of the file (128, 256, 512)
                 uint32_t budget = h.regs_per_lane / 4;
@@ -558,7 +563,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         s.ukernel_id[i] = u.id;
         s.count_tau[i] = best.part[i].count;
         pl->slot_id[i] = u.id;
-        pl->slot_code[i] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn);
+        pl->slot_code[i] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn, u.gk);
         pl->slot_stages[i] = u.stages;
         lds = std::max(lds, u.lds_bytes);
         uint32_t by_model = 0;

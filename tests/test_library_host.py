@@ -53,9 +53,9 @@ def test_ukernel_table_matches_oracle(name):
     assert ft.ft_ukset_size(s) == len(want)
     for i, w in enumerate(want):
         g = ft.ft_ukset_get(s, i)
-        got = (g.id, g.tm, g.tn, g.tk, g.wm, g.wn, g.gm, g.gn, g.mfma, g.stages, g.lds_bytes, g.acc_regs,
+        got = (g.id, g.tm, g.tn, g.tk, g.wm, g.wn, g.gm, g.gn, g.gk, g.mfma, g.stages, g.lds_bytes, g.acc_regs,
                g.regs, g.reg_budget, g.max_wg_per_cu, g.cmr_q20)
-        assert got == (w.id, w.tm, w.tn, w.tk, w.wm, w.wn, w.gm, w.gn, w.mfma, w.stages, w.lds_bytes,
+        assert got == (w.id, w.tm, w.tn, w.tk, w.wm, w.wn, w.gm, w.gn, w.gk, w.mfma, w.stages, w.lds_bytes,
                        w.acc_regs, w.regs, w.reg_budget, w.max_wg_per_cu, w.cmr_q)
 
 

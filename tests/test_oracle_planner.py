@@ -88,6 +88,7 @@ def test_resource_closed_forms():
     op = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(1, 8192))
     uks = P.derive_ukernels(op)
     by = {(u.tm, u.tn, u.wm, u.wn): u for u in uks}
+    assert by[(32, 32, 32, 32)].gk == 4 and by[(32, 32, 32, 32)].stages == 5 and by[(32, 32, 32, 32)].max_wg_per_cu == 1
     u = by[(256, 256, 128, 128)]
     assert u.lds_bytes == 131072 and u.acc_regs == 256 and u.max_wg_per_cu == 1
     assert u.regs == 328 and u.reg_budget == 512
@@ -98,10 +99,11 @@ def test_resource_closed_forms():
     assert by[(16, 64, 16, 16)].stages == 8 and by[(64, 64, 32, 32)].stages == 5
     assert by[(128, 256, 64, 128)].reg_budget == 256
     for u in uks:
-        assert 2 <= u.stages <= 8 and u.stages == max(2, min(8, 81920 // ((u.tm + u.tn) * 128)))
-        assert u.lds_bytes == u.stages * (u.tm + u.tn) * u.tk * 2 <= 163840
+        share = 81920 if u.gk == 1 else 163840 // 4
+        assert 2 <= u.stages <= 8 and u.stages == max(2, min(8, share // ((u.tm + u.tn) * 128)))
+        assert u.lds_bytes == u.gk * u.stages * (u.tm + u.tn) * u.tk * 2 <= 163840
         assert u.acc_regs * 64 == u.wm * u.wn
-        assert u.tm == u.gm * u.wm and u.tn == u.gn * u.wn and u.gm * u.gn == 4
+        assert u.tm == u.gm * u.wm and u.tn == u.gn * u.wn and u.gm * u.gn * u.gk == 4
         assert 768 % u.tn == 0                              # static axis divided evenly
         assert u.tk % (16 if u.mfma == 0 else 32) == 0
         assert (u.mfma == 1) == (u.wm == 16)
