@@ -117,9 +117,11 @@ ft_status ft_op_register(const ft_op_desc *desc, ft_op **out);
 void ft_op_destroy(ft_op *op);
 
 /* ---------------------------------------------------------------------------------------
- * (b) uKernel set: HardwareAlign + IsOverflow + Eq. 4 + Eq. 6 (Alg. 1), in canonical order
- * (larger smem_tile area first).  The shape-dependent filters (CrossPick, SetBound with the
- * workload's block.bound, Eq. 5) run inside ft_plan.
+ * (b) uKernel set: HardwareAlign, then IsOverflow, Eq. 4 (one workgroup per CU), Eq. 6, and
+ * CrossPick + Eq. 5 (Alg. 1, Sec. 4.3) evaluated over the workload = every shape of the
+ * registered dynamic ranges (sampled at the range ends and at multiples of 16); canonical
+ * order = larger smem_tile area first.  If nothing survives the workload filters they are
+ * skipped.  SetBound (block.bound of the shape at hand) is applied by ft_plan_create.
  * ------------------------------------------------------------------------------------- */
 typedef struct ft_ukernel_info {
     uint32_t struct_size;
@@ -192,7 +194,7 @@ typedef struct ft_plan_stats {
     uint32_t count_tau[2];         /* Num1, Num2 of Alg. 2 in the same order                 */
     uint32_t block_bound;          /* min(K.wkl.block, zeta)                                 */
     uint32_t pool_size;            /* programs in uProg                                      */
-    uint32_t level;                /* 0: bound+CrossPick+Eq.5, 1: bound+CrossPick, 2: bound, 3: none */
+    uint32_t level;                /* 0: Top-1 among programs within block.bound, 1: none was      */
     uint32_t pad_q20, occ_q20, cmr_q20;   /* Eq. 2, Eq. 3, normalised Eq. 6; floor(x * 2^20) */
     uint32_t lds_bytes;            /* dynamic LDS of the launch                              */
     uint32_t kernel_class;         /* which dispatcher kernel runs the plan                  */

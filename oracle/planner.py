@@ -244,15 +244,60 @@ def reg_budget(regs, hw):
     return b
 
 
+def axis_samples(lo, hi, cap):
+    """Shapes of the workload ('every possible shape', Sec. 4) along one dynamic axis: both ends
+    of the registered range and the multiples of the granule between them, thinned to about cap
+    points by a fixed stride."""
+    lo = max(lo, 1)
+    if hi < lo:
+        return []
+    pts = {lo, hi}
+    first = ceil_by(lo, GRANULE)
+    if first <= hi:
+        n_mult = (hi - first) // GRANULE + 1
+        stride = max(1, ceil_div(n_mult, cap)) * GRANULE
+        pts.update(range(first, hi + 1, stride))
+    return sorted(pts)
+
+
+def workload_shapes(op: Op):
+    """(M, N) pairs the compile stage evaluates a uKernel on."""
+    m_s, n_s, _ = op.gemm_static()
+    both = m_s == 0 and n_s == 0
+    cap = 48 if both else 256
+    ms = [m_s] if m_s else axis_samples(op.m_range[0], op.m_range[1], cap)
+    ns = [n_s] if n_s else axis_samples(op.n_range[0], op.n_range[1], cap)
+    return [(m, n) for m in ms for n in ns]
+
+
+def passes_workload(tm, tn, shapes, hw, t):
+    """CrossPick (Alg. 1) and the space-axis test (Eq. 5) for one uKernel K over the workload:
+    kept iff for some shape, composed of K alone (padding where K does not divide), K.pad and
+    K.occ pass the staircase and the number of uKernels reaches Active Blocks = zeta x NumCores.
+    SetBound's K.IsInBound depends on block.bound = min(K.wkl.block, zeta), which is known
+    only per shape: it is applied at the runtime stage."""
+    for M, N in shapes:
+        T = ceil_div(M, tm) * ceil_div(N, tn)
+        if T < t["zeta"] * hw["num_cus"]:
+            continue                                                # Eq. 5
+        if cross_pick(pad_fraction(M * N, T * tm * tn), occ_fraction(T, hw["num_cus"]), t):
+            return True
+    return False
+
+
 def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
-    """HardwareAlign + the shape-independent filters (IsOverflow, Eq. 4 at block.bound = 1,
-    Eq. 6), in the canonical set order: larger smem_tile area first."""
+    """Compile stage: HardwareAlign, then the filters of Alg. 1 and Sec. 4.3 over the workload
+    (IsOverflow, Eq. 4 at block.bound = 1, CrossPick, Eq. 5, Eq. 6), in the canonical set order: larger
+    smem_tile area first.  If no uKernel survives the workload filters (ranges too small to
+    ever fill the device), the set before them is kept."""
     hw = hw or default_hw()
     t = t or default_tuning()
     m_s, n_s, _ = op.gemm_static()
     k_ref = op.k_ref()
     waves_per_simd = 1                      # 4 waves on 4 SIMDs
+    shapes = workload_shapes(op)
     cand = []
+    kept = []
     for wm, wn, mfma in wave_tiles():
         for gm, gn, gk in WAVE_GRIDS:
             if gk > 1 and not (1024 <= wm * wn <= 4096):
@@ -289,6 +334,9 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                           hw["max_waves_per_simd"])
                 cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, gk, mfma, stages, lds, acc, regs,
                                     budget, cap, (cn << Q) // cd))
+                kept.append(passes_workload(tm, tn, shapes, hw, t))
+    if any(kept):
+        cand = [u for u, k in zip(cand, kept) if k]
     cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))
     for i, u in enumerate(cand):
         u.id = i
@@ -412,8 +460,7 @@ def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q):
     # SetBound (Alg. 1): block.bound = min(K.wkl.block, zeta)
     p.block_bound = min(max(1, ceil_div(T, hw["num_cus"])), t["zeta"])
     p.in_bound = all(uks[uid].max_wg_per_cu >= p.block_bound for uid, _ in parts)
-    slots = hw["num_cus"] * p.block_bound
-    occ = occ_fraction(T, slots)
+    occ = occ_fraction(T, hw["num_cus"])
     pad = pad_fraction(M * N, area)
     p.occ_q = (occ[0] << Q) // occ[1]
     p.pad_q = (pad[0] << Q) // pad[1]
@@ -474,7 +521,7 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         Hp = ceil_by(M if tau == 0 else N, _ext(u, tau))
         parts = [(0, Hp // _ext(u, tau))]
         prog = evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
-        pl.pool_size, pl.level = 1, 3
+        pl.pool_size, pl.level = 1, 0 if prog.in_bound else 1
     else:
         Hp = ceil_by(M if tau == 0 else N, GRANULE)
         pool = [evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
@@ -486,16 +533,12 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
             u = next(u for u in uks if _ext(u, tau) == e_min)
             pool = [evaluate([(u.id, ceil_div(Hp, e_min))], uks, batch, M, N, tau, hw, t, cap_q)]
         pl.pool_size = len(pool)
-        levels = [
-            [p for p in pool if p.in_bound and p.cross and p.saturated],
-            [p for p in pool if p.in_bound and p.cross],
-            [p for p in pool if p.in_bound],
-            pool,
-        ]
-        for lv, cands in enumerate(levels):
-            if cands:
-                pl.level = lv
-                break
+        # runtime stage: the programs whose uKernels fit block.bound workgroups per CU on this
+        # shape (SetBound); all of them if none does
+        cands = [p for p in pool if p.in_bound]
+        pl.level = 0
+        if not cands:
+            cands, pl.level = pool, 1
         # Top-1 by SIA; ties: fewer tiles, then lower K1 index, then lower K2 index
         prog = min(cands, key=lambda p: (-p.sia_q, p.num_tiles, p.k1, p.k2))
     pl.program = prog

@@ -74,6 +74,24 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint64_t kr
     *den = (u128)hw.mfma_flops_per_clk_per_cu * mem_num;
 }
 
+// Shapes of the workload along one dynamic axis: both ends of the registered range and the
+// multiples of the granule between them, thinned to about cap points by a fixed stride.
+void axis_samples(uint64_t lo, uint64_t hi, uint64_t cap, std::vector<uint64_t> &out) {
+    out.clear();
+    if (lo < 1) lo = 1;
+    if (hi < lo) return;
+    out.push_back(lo);
+    uint64_t first = ceil_by(lo, GRANULE);
+    if (first <= hi) {
+        uint64_t n_mult = (hi - first) / GRANULE + 1;
+        uint64_t stride = std::max<uint64_t>(1, ceil_div(n_mult, cap)) * GRANULE;
+        for (uint64_t v = first; v <= hi; v += stride) out.push_back(v);
+    }
+    out.push_back(hi);
+    std::sort(out.begin(), out.end());
+    out.erase(std::unique(out.begin(), out.end()), out.end());
+}
+
 struct Part { uint32_t id, count; };
 
 struct Program {
@@ -103,6 +121,22 @@ bool cross_pick(u128 pn, u128 pd, u128 on, u128 od, const ft_tuning &t) {
     return false;
 }
 
+// CrossPick and Eq. 5 for one uKernel over the workload: kept iff some shape, composed of this
+// uKernel alone, passes the staircase with a tile count of at least Active Blocks = zeta x NumCores.
+// (SetBound needs the shape's block.bound and is applied when a shape is planned.)
+bool passes_workload(uint32_t tm, uint32_t tn, const std::vector<uint64_t> &ms,
+                     const std::vector<uint64_t> &ns, const ft_hw_model &hw, const ft_tuning &t) {
+    for (uint64_t M : ms)
+        for (uint64_t N : ns) {
+            uint64_t T = ceil_div(M, tm) * ceil_div(N, tn);
+            if (T < (uint64_t)t.zeta * hw.num_cus) continue;        // Eq. 5
+            u128 pn = (u128)M * N, pd = (u128)T * tm * tn;
+            u128 on = T, od = ceil_by(T, hw.num_cus);
+            if (cross_pick(pn, pd, on, od, t)) return true;
+        }
+    return false;
+}
+
 void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint64_t N, uint32_t tau) {
     const ft_hw_model &hw = set.hw;
     const ft_tuning &t = set.t;
@@ -121,8 +155,7 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
     p.in_bound = true;
     for (uint32_t i = 0; i < p.nparts; ++i)
         if (set.uk[p.part[i].id].max_wg_per_cu < p.block_bound) p.in_bound = false;
-    uint64_t slots = (uint64_t)hw.num_cus * p.block_bound;
-    u128 on = p.tiles, od = ceil_by(p.tiles, slots);                                // Eq. 3
+    u128 on = p.tiles, od = ceil_by(p.tiles, hw.num_cus);                           // Eq. 3
     u128 pn = (u128)M * N, pd = area;                                               // Eq. 2
     p.occ_q = (uint32_t)((on << QBITS) / od);
     p.pad_q = (uint32_t)((pn << QBITS) / pd);
@@ -251,12 +284,7 @@ bool better(const Program &a, const Program &b) {      // Top-1 order: SIA, then
     return a.k2 < b.k2;
 }
 
-int level_of(const Program &p) {
-    if (p.in_bound && p.cross && p.saturated) return 0;
-    if (p.in_bound && p.cross) return 1;
-    if (p.in_bound) return 2;
-    return 3;
-}
+int level_of(const Program &p) { return p.in_bound ? 0 : 1; }
 
 thread_local int g_last_hip_error = 0;
 
@@ -337,6 +365,14 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
 
     // HardwareAlign: RegTileRule (per-wave accumulator tiles built from MFMA shapes) x
     // SmemTileRule (wave grids; tk = one 128-byte line of 16-bit elements)
+    std::vector<uint64_t> ms, ns;
+    {
+        const bool both = sv.m == 0 && sv.n == 0;
+        const uint64_t cap = both ? 48 : 256;
+        if (sv.m) ms.assign(1, sv.m); else axis_samples(op->d.m_lo, op->d.m_hi, cap, ms);
+        if (sv.n) ns.assign(1, sv.n); else axis_samples(op->d.n_lo, op->d.n_hi, cap, ns);
+    }
+    std::vector<char> kept;
     static const uint32_t sizes[4] = {16, 32, 64, 128};
     // wave grids over (rows, columns, reduce axis); the split-k grid lets each wave own the whole
     // tile and a quarter of k (accumulator tiles of 1024..4096 elements only)
@@ -384,8 +420,16 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                                            h.max_waves_per_simd);
                 u.cmr_q20 = (uint64_t)((cn << QBITS) / cd);
                 set->uk.push_back(u);
+                kept.push_back(passes_workload(tm, tn, ms, ns, h, t) ? 1 : 0);
             }
         }
+    // K.Filter: the uKernels that pass the workload filters; all of them if none does
+    if (std::find(kept.begin(), kept.end(), 1) != kept.end()) {
+        std::vector<ft_ukernel_info> f;
+        for (size_t i = 0; i < set->uk.size(); ++i)
+            if (kept[i]) f.push_back(set->uk[i]);
+        set->uk.swap(f);
+    }
     std::sort(set->uk.begin(), set->uk.end(), [](const ft_ukernel_info &a, const ft_ukernel_info &b) {
         uint64_t aa = (uint64_t)a.tm * a.tn, ab = (uint64_t)b.tm * b.tn;
         if (aa != ab) return aa > ab;
@@ -505,7 +549,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         best.k1 = 0; best.k2 = -1;
         evaluate(best, *set, r.batch, r.M, r.N, tau);
         s.pool_size = 1;
-        s.level = 3;
+        s.level = (uint32_t)level_of(best);
     } else if (mode == FT_PLAN_FORCED) {
         uint64_t Hp = ceil_by(tau == 0 ? r.M : r.N, GRANULE);
         if (forced->k1 >= set->uk.size() || forced->count1 == 0) { delete pl; return FT_ERR_INVALID_ARG; }
@@ -540,7 +584,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
             p.k1 = (int64_t)pick; p.k2 = -1;
             pool.push_back(p);
         }
-        int lvl = 4;
+        int lvl = 2;
         for (Program &p : pool) {
             evaluate(p, *set, r.batch, r.M, r.N, tau);
             lvl = std::min(lvl, level_of(p));

@@ -109,12 +109,12 @@ def test_two_ukernel_program_mixed_in_one_launch():
     op = matmul_op(N, K, ft.FT_F16)
     s = ft.ft_ukernels_derive(op)
     infos = [ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))]
-    big = next(u.id for u in infos if (u.tm, u.tn, u.wm) == (128, 128, 64))
-    small = next(u.id for u in infos if (u.tm, u.tn, u.wm) == (16, 64, 16))
+    big = next(u for u in infos if (u.tm, u.tn, u.gk) == (128, 64, 1))
+    small = next(u for u in infos if (u.tm, u.tn, u.gk) == (16, 64, 4))
     plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED,
-                             ft.ft_forced_program(k1=big, count1=9, k2=small, count2=5))
+                             ft.ft_forced_program(k1=big.id, count1=9, k2=small.id, count2=5))
     st = ft.ft_plan_stats_get(plan)
-    assert st.n_ukernels == 2 and st.n_tiles == 9 * 6 + 5 * 12
+    assert st.n_ukernels == 2 and st.n_tiles == 9 * 12 + 5 * 12
     ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
     check(run(plan, p["A"], p["B"], M * N), ref, refabs, "mixed program")
 

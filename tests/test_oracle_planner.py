@@ -85,8 +85,8 @@ def test_default_hyper_parameters_from_paper():
 
 
 def test_resource_closed_forms():
-    op = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(1, 8192))
-    uks = P.derive_ukernels(op)
+    op = P.Op(P.OP_BMM, P.F16, n=768, k=768, m_range=(1, 100))     # too small to ever fill the device:
+    uks = P.derive_ukernels(op)                                     # the workload filters are skipped
     by = {(u.tm, u.tn, u.wm, u.wn): u for u in uks}
     assert by[(32, 32, 32, 32)].gk == 4 and by[(32, 32, 32, 32)].stages == 5 and by[(32, 32, 32, 32)].max_wg_per_cu == 1
     u = by[(256, 256, 128, 128)]
@@ -112,6 +112,28 @@ def test_resource_closed_forms():
     assert areas == sorted(areas, reverse=True)
     assert [u.id for u in uks] == list(range(len(uks)))
     assert len({(u.tm, u.tn, u.tk, u.wm, u.wn) for u in uks}) == len(uks)
+
+
+def test_workload_filters_crosspick_and_eq5():
+    """A uKernel survives iff some shape of the workload, tiled by it alone, reaches
+    zeta x NumCores tiles and passes the CrossPick staircase (checked here by enumerating
+    every M of a range whose samples are all its multiples of 16)."""
+    hw, t = P.default_hw(), P.default_tuning()
+    op = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(1, 4096))
+    assert P.axis_samples(1, 4096, 256) == [1] + list(range(16, 4097, 16))
+    assert P.axis_samples(1, 8192, 256)[:3] == [1, 16, 48] and P.axis_samples(1, 8192, 256)[-1] == 8192
+    assert P.axis_samples(5, 3, 256) == [] and P.axis_samples(0, 7, 256) == [1, 7]
+    got = {(u.tm, u.tn, u.wm, u.wn) for u in P.derive_ukernels(op)}
+    for tm, tn in [(256, 256), (128, 128), (128, 64), (64, 64), (16, 64), (256, 32)]:
+        want = False
+        for M in range(1, 4097):
+            T = -(-M // tm) * (768 // tn)
+            if T >= 512 and P.cross_pick((M * 768, T * tm * tn), P.occ_fraction(T, 256), t):
+                want = True
+                break
+        assert any(k[:2] == (tm, tn) for k in got) == want, (tm, tn)
+    # 256x256 on N = 768 never reaches 512 tiles for M <= 4096; 64x64 does
+    assert not any(k[:2] == (256, 256) for k in got) and any(k[:2] == (64, 64) for k in got)
 
 
 def test_compute_eff_closed_form():
