@@ -6,7 +6,9 @@ batch 16: [16L,768]x[768,768], [16L,768]x[768,3072], [16L,3072]x[3072,768]; fp16
 fp32 accumulate/output.  One "step" = one pass over the 21 GEMMs through plan (cached per
 shape) + launch.  Steps are executed shape-major: each GEMM is launched `steps` times back to
 back between two HIP events on the launch stream, so every GEMM gets its own time; the sum
-over GEMMs is the time of one step.
+over GEMMs is the time of one step.  With --graph the `steps` launches of a GEMM are captured
+into a HIP graph and the timed region is one replay of it (measured: no gain over direct
+launches on this machine).
 
 Headline `value`: geomean over the 21 GEMMs of useful TFLOP/s with operands resident in HBM
 but NOT in cache (each launch uses the next of a ring of buffer sets totalling > 600 MB).
@@ -40,6 +42,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="time one HIP-graph replay of the launches instead of direct launches")
     ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -54,8 +57,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    stream = torch.cuda.current_stream().cuda_stream
+    side = torch.cuda.Stream()                      # graph capture needs a non-NULL stream
+    stream = side.cuda_stream
+    use_graph = args.graph
     hw = ft.ft_hw_query(0)
+
+    def timed(plan, pa, pb, pc, iters, graph=None):
+        return ft.ft_launch_timed(plan, pa, pb, pc, stream, iters, graph=use_graph if graph is None else graph)
 
     shapes = si.config1_shapes()
     ops = {}
@@ -74,7 +82,6 @@ def main():
         base = ft.ft_plan_create(op, uks, ft.ft_shape(m=M), ft.FT_PLAN_PAD_BASELINE)
         rows.append(dict(M=M, N=N, K=K, plan=plan, base=base))
 
-    total_wall0 = None
     per_class_time = {}
     per_class_flops = {}
     per_class_launches = {}
@@ -94,16 +101,12 @@ def main():
         st = ft.ft_plan_stats_get(r["plan"])
         sb = ft.ft_plan_stats_get(r["base"])
         # warm-up (untimed), then exactly `steps` timed launches per variant
-        ft.ft_launch_timed(r["plan"], pa, pb, pc, stream, max(1, args.warmup))
-        if total_wall0 is None:
-            torch.cuda.synchronize()
-            total_wall0 = time.perf_counter()
-        ms_cold = ft.ft_launch_timed(r["plan"], pa, pb, pc, stream, args.steps)
-        r["wall_mark"] = time.perf_counter()
-        ft.ft_launch_timed(r["plan"], pa[:1], pb[:1], pc[:1], stream, max(1, args.warmup))
-        ms_warm = ft.ft_launch_timed(r["plan"], pa[:1], pb[:1], pc[:1], stream, args.steps)
-        ft.ft_launch_timed(r["base"], pa, pb, pc, stream, max(1, args.warmup))
-        ms_base = ft.ft_launch_timed(r["base"], pa, pb, pc, stream, args.steps)
+        timed(r["plan"], pa, pb, pc, max(1, args.warmup), graph=False)
+        ms_cold = timed(r["plan"], pa, pb, pc, args.steps)
+        timed(r["plan"], pa[:1], pb[:1], pc[:1], max(1, args.warmup), graph=False)
+        ms_warm = timed(r["plan"], pa[:1], pb[:1], pc[:1], args.steps)
+        timed(r["base"], pa, pb, pc, max(1, args.warmup), graph=False)
+        ms_base = timed(r["base"], pa, pb, pc, args.steps)
         t_roof = max(flops / (MFMA_PEAK_TFLOPS * 1e12), bytes_alg / (HBM_PEAK_GBS * 1e9))
         r.update(ms_cold=ms_cold, ms_warm=ms_warm, ms_base=ms_base, flops=flops, bytes_alg=bytes_alg,
                  tflops_cold=flops / ms_cold / 1e9, tflops_warm=flops / ms_warm / 1e9,
@@ -141,6 +144,7 @@ def main():
         "config": {"workload": "configs[1]: BERT-base-shaped dynamic sweep, 21 GEMMs, M=16*L, L in "
                                "{5,17,33,64,77,100,128}, (K,N) in {(768,768),(768,3072),(3072,768)}",
                    "order": "shape-major: each GEMM launched `steps` times back to back",
+                   "launch": "one HIP-graph replay of the `steps` launches" if use_graph else "direct launches",
                    "buffers": "ring of buffer sets > 600 MB per GEMM (cold caches)"},
         "pct_mfma_peak_geomean": round(100.0 * value / MFMA_PEAK_TFLOPS, 3),
         "aggregate_tflops": round(total_flops / ms_per_step / 1e9, 3),
@@ -156,7 +160,8 @@ def main():
                      "avg_launch_us": round(1e3 * per_class_time[dom] / per_class_launches[dom], 3),
                      "launches": per_class_launches[dom],
                      "note": "achieved = useful flops of the launches that ran this kernel / their "
-                             "event-timed duration (back-to-back launches, launch gaps included)"},
+                             "event-timed duration (back-to-back launches on one stream, gaps between "
+                             "kernels included)"},
     }
 
     if not args.no_cpu_baseline:

@@ -248,6 +248,13 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
 ft_status ft_launch_timed(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
                           uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch);
 
+/* Same measurement with the `iters` launches captured once into a HIP graph (stream capture of
+ * ft_launch on hip_stream, which must not be the NULL stream) and replayed: one untimed replay,
+ * then one replay between the two events.  Removes the host's per-launch cost from the timed
+ * region; the kernels and their order are the same. */
+ft_status ft_launch_timed_graph(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
+                                uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch);
+
 #ifdef __cplusplus
 }
 #endif

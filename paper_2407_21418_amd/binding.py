@@ -116,6 +116,8 @@ SYMBOLS = {
     "ft_launch": (C.c_int32, [_P, _P, _P, _P, _P]),
     "ft_launch_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
                                     C.POINTER(C.c_float)]),
+    "ft_launch_timed_graph": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
+                                          C.POINTER(C.c_float)]),
 }
 
 
@@ -259,11 +261,13 @@ def ft_launch(p: Plan, A: int, B: int, Cptr: int, stream: int = 0):
     _check(lib().ft_launch(p.ptr, A, B, Cptr, stream), "ft_launch")
 
 
-def ft_launch_timed(p: Plan, A, B, Cs, stream: int, iters: int) -> float:
-    """A, B, Cs: equally long lists of device addresses (rotating buffer sets)."""
+def ft_launch_timed(p: Plan, A, B, Cs, stream: int, iters: int, graph: bool = False) -> float:
+    """A, B, Cs: equally long lists of device addresses (rotating buffer sets).  graph=True times
+    one replay of a HIP graph holding the `iters` launches (stream must not be the NULL stream)."""
     n = len(A)
     arr = lambda xs: (_P * n)(*xs)
     ms = C.c_float()
-    _check(lib().ft_launch_timed(p.ptr, arr(A), arr(B), arr(Cs), n, stream, iters, C.byref(ms)),
-           "ft_launch_timed")
+    fn = lib().ft_launch_timed_graph if graph else lib().ft_launch_timed
+    _check(fn(p.ptr, arr(A), arr(B), arr(Cs), n, stream, iters, C.byref(ms)),
+           "ft_launch_timed_graph" if graph else "ft_launch_timed")
     return ms.value

@@ -49,6 +49,11 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, ftk::KAr
     a->slot_ukernel[0] = p->slot_id[0]; a->slot_ukernel[1] = p->slot_id[1];
     a->slot_code[0] = p->slot_code[0]; a->slot_code[1] = p->slot_code[1];
     a->slot_stages[0] = p->slot_stages[0]; a->slot_stages[1] = p->slot_stages[1];
+    for (int i = 0; i < 2; ++i) {
+        a->slot_first[i] = p->slot_first[i];
+        a->slot_rows[i] = p->slot_rows[i];
+        a->slot_cols[i] = p->slot_cols[i];
+    }
     a->num_xcds = p->num_xcds;
 }
 
@@ -129,6 +134,40 @@ ft_status ft_launch_timed(const ft_plan *plan, const void *const *A, const void 
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    if (st != FT_OK) return st;
+    if (e != hipSuccess) return hip_fail(e);
+    *ms_per_launch = ms / (float)iters;
+    return FT_OK;
+}
+
+ft_status ft_launch_timed_graph(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
+                                uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch) {
+    if (!plan || !A || !B || !C || !n_sets || !iters || !ms_per_launch || !hip_stream) return FT_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ft_status st = FT_OK;
+    hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return hip_fail(e);
+    for (uint32_t i = 0; i < iters && st == FT_OK; ++i)
+        st = ft_launch(plan, A[i % n_sets], B[i % n_sets], C[i % n_sets], hip_stream);
+    e = hipStreamEndCapture(s, &graph);          // always end the capture, also after a failed launch
+    if (st == FT_OK && e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (st == FT_OK && e == hipSuccess) e = hipEventCreate(&e0);
+    if (st == FT_OK && e == hipSuccess) e = hipEventCreate(&e1);
+    if (st == FT_OK && e == hipSuccess) e = hipGraphLaunch(exec, s);             // untimed replay
+    if (st == FT_OK && e == hipSuccess) e = hipStreamSynchronize(s);
+    if (st == FT_OK && e == hipSuccess) e = hipEventRecord(e0, s);
+    if (st == FT_OK && e == hipSuccess) e = hipGraphLaunch(exec, s);
+    if (st == FT_OK && e == hipSuccess) e = hipEventRecord(e1, s);
+    if (st == FT_OK && e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (st == FT_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
     if (st != FT_OK) return st;
     if (e != hipSuccess) return hip_fail(e);
     *ms_per_launch = ms / (float)iters;

@@ -45,6 +45,9 @@ struct KArgs {
     uint32_t slot_ukernel[2];         // uKernel ids of the plan's (up to) two constituents
     uint32_t slot_code[2];            // their body codes in the compiled family
     uint32_t slot_stages[2];          // LDS ring depth of each (fast path)
+    uint32_t slot_first[2];           // first descriptor of each constituent's block of the table
+    uint32_t slot_rows[2];            // its tile grid per batch entry: rows (m) x columns (n)
+    uint32_t slot_cols[2];
     uint32_t num_xcds;
 };
 
@@ -69,11 +72,16 @@ template <int DT> __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x
 
 // XOR swizzles on the 16-byte chunk index.  A: 128-byte rows; 16 consecutive rows at one
 // logical chunk land on 16 distinct bank quads whether the LDS resolves 8 or 16 lanes per
-// cycle.  B: keeps 32-byte pairs together (one transposing read covers 2 chunks of 4 rows).
+// cycle.  B: a transposing read moves 8 bytes per lane, so 32 lanes (two 16-lane groups of
+// 4 rows x 32 bytes) share the 64 banks of one cycle.  The two groups are either the two column
+// halves of a 32-wide block at the same 4 rows (32x32x16) or the same columns at rows r and r+8
+// (16x16x32): the XOR puts rows r..r+3 and r+8..r+11 on 8 distinct 32-byte bank groups and never
+// touches chunk bit 0 (the 32-byte pair a group reads stays contiguous).
 __device__ __forceinline__ uint32_t swzA(uint32_t row) { return (row ^ ((row >> 3) & 1u)) & 7u; }
 template <int TN> __device__ __forceinline__ uint32_t swzB(uint32_t row) {
-    if constexpr (TN >= 128) return (row & 3u) << 2;
-    else if constexpr (TN == 64) return ((row >> 1) & 1u) << 2;
+    if constexpr (TN >= 128) return ((row & 3u) << 2) | (((row >> 3) & 1u) << 1);
+    else if constexpr (TN == 64) return (((row >> 1) & 1u) << 2) | (((row >> 3) & 1u) << 1);
+    else if constexpr (TN == 32) return ((row >> 3) & 1u) << 1;
     else return 0u;
 }
 
@@ -144,16 +152,13 @@ struct UKernelBody {
                 a_pix[i] = (p * g.cstride) << 16 | (q * g.cstride);
             }
         }
-        // B copy: iteration i moves chunk (krow0 + i*B_RSTEP, nc); the swizzle only depends on
-        // row bits that B_RSTEP (a multiple of 4) leaves alone, so one base address serves all i.
+        // B copy: iteration i moves chunk (krow0 + i*B_RSTEP, nc)
         constexpr int B_RSTEP = (NTHREADS / NCH) > 0 ? (NTHREADS / NCH) : 1;
-        static_assert(B_RSTEP % 4 == 0, "row step must keep the B swizzle phase");
         const bool b_on = (B_CHUNKS % NTHREADS == 0) || tid < (uint32_t)B_CHUNKS;
         const uint32_t b_krow0 = (tid / NCH) % TK, b_nc = tid % NCH;
         const uint32_t b_col = n0 + b_nc * 8;
         const uint32_t b_ccol = (b_col + 8 <= N) ? b_col : n0;   // clamp: garbage columns are never stored
         const uint32_t b_off0 = b_krow0 * g.ldb + b_ccol;
-        const uint32_t b_lds0 = A_BYTES + b_krow0 * (TN * 2) + ((b_nc ^ swzB<TN>(b_krow0)) << 4);
         const uint32_t b_rstep_ld = B_RSTEP * g.ldb;
         // every B chunk of this tile is wholly inside or wholly outside [0, N)
         const bool b_fast = (N % 8 == 0) || (n0 + TN <= N);
@@ -245,8 +250,10 @@ struct UKernelBody {
             }
             if (b_on) {
 #pragma unroll
-                for (int i = 0; i < B_ITERS; ++i)
-                    *reinterpret_cast<uint4 *>(base + b_lds0 + i * (B_RSTEP * TN * 2)) = rb[i];
+                for (int i = 0; i < B_ITERS; ++i) {
+                    const uint32_t row = b_krow0 + i * B_RSTEP;
+                    *reinterpret_cast<uint4 *>(base + A_BYTES + row * (TN * 2) + ((b_nc ^ swzB<TN>(row)) << 4)) = rb[i];
+                }
             }
         };
         auto compute = [&](uint32_t stage) {

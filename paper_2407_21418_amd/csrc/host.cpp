@@ -249,7 +249,10 @@ ft_status resolve(const ft_op_desc &d, const ft_shape &s, Resolved *r) {
     return FT_OK;
 }
 
-void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau, std::vector<ft_tile_desc> &out) {
+struct SlotGrid { uint32_t first, rows, cols; };
+
+void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau, std::vector<ft_tile_desc> &out,
+          SlotGrid (&grid)[2]) {
     out.clear();
     out.reserve(p.tiles);
     uint64_t Wp = ceil_by(tau == 0 ? r.N : r.M, GRANULE);
@@ -260,6 +263,7 @@ void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau
         uint64_t cnt = p.part[i].count;
         uint64_t m_cnt = tau == 0 ? cnt : across, n_cnt = tau == 0 ? across : cnt;
         uint64_t m_base = tau == 0 ? off : 0, n_base = tau == 0 ? 0 : off;
+        grid[i] = {(uint32_t)out.size(), (uint32_t)m_cnt, (uint32_t)n_cnt};
         for (uint64_t b = 0; b < r.batch; ++b)
             for (uint64_t im = 0; im < m_cnt; ++im)
                 for (uint64_t in = 0; in < n_cnt; ++in) {
@@ -527,6 +531,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     pl->slot_id[0] = pl->slot_id[1] = 0;
     pl->slot_code[0] = pl->slot_code[1] = 0;
     pl->slot_stages[0] = pl->slot_stages[1] = MIN_STAGES;
+    for (int i = 0; i < 2; ++i) { pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = 1; }
     ft_plan_stats &s = pl->st;
     std::memset(&s, 0, sizeof(s));
     s.struct_size = sizeof(s);
@@ -599,7 +604,14 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         s.level = (uint32_t)lvl;
     }
 
-    emit(best, *set, r, tau, pl->descs);
+    SlotGrid grid[2] = {{0, 1, 1}, {0, 1, 1}};
+    emit(best, *set, r, tau, pl->descs, grid);
+    if (best.nparts == 1) grid[1] = {(uint32_t)pl->descs.size(), 1, 1};
+    for (int i = 0; i < 2; ++i) {
+        pl->slot_first[i] = grid[i].first;
+        pl->slot_rows[i] = grid[i].rows;
+        pl->slot_cols[i] = grid[i].cols;
+    }
     s.n_ukernels = best.nparts;
     uint32_t lds = 0, klass = 0;
     for (uint32_t i = 0; i < best.nparts; ++i) {
