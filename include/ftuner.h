@@ -86,7 +86,13 @@ typedef struct ft_tuning {
     uint32_t rest_regs;                             /* RestRegs of Eq. 4: 72                */
     uint32_t psi_num, psi_den;                      /* threshold of Eq. 6: 1/8              */
     uint32_t c0, c1, c2;                            /* Eq. 1 coefficients: 1, 1, 1          */
+    uint32_t sia_form;                              /* FT_SIA_LINEAR: c0*CMR + c1*Pad + c2*Occ of
+                                                       the program, as printed; FT_SIA_PRODUCT
+                                                       (default): mean over the program's uKernels
+                                                       of CMR^c0 * Pad^c1 * Occ^c2, each on its own
+                                                       sub-workload (c0..c2 <= 4)               */
 } ft_tuning;
+enum { FT_SIA_LINEAR = 0, FT_SIA_PRODUCT = 1 };
 
 ft_status ft_tuning_default(ft_tuning *out);        /* out: host pointer */
 

@@ -29,6 +29,7 @@ GRANULE = 16                # smallest MFMA output extent on gfx950 (16x16x32)
 OP_MATMUL, OP_BMM, OP_CONV2D = 0, 1, 2
 F16, BF16 = 0, 1
 PLAN_PATCHWORK, PLAN_PAD_BASELINE = 0, 1
+SIA_LINEAR, SIA_PRODUCT = 0, 1
 
 
 def default_hw():
@@ -45,7 +46,7 @@ def default_tuning():
     the paper, 1/8 here."""
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
-                zeta=2, rest_regs=72, psi_num=1, psi_den=8, c0=1, c1=1, c2=1)
+                zeta=2, rest_regs=72, psi_num=1, psi_den=8, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT)
 
 
 # --------------------------------------------------------------------------------------
@@ -472,8 +473,44 @@ def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q):
     for uid, _ in parts:
         acc += (min(uks[uid].cmr_q, cap_q) << Q) // cap_q
     p.cmr_q = acc // len(parts)
-    p.sia_q = t["c0"] * p.cmr_q + t["c1"] * p.pad_q + t["c2"] * p.occ_q       # Eq. 1
+    if t.get("sia_form", SIA_LINEAR) == SIA_LINEAR:
+        p.sia_q = t["c0"] * p.cmr_q + t["c1"] * p.pad_q + t["c2"] * p.occ_q   # Eq. 1 as printed
+    else:
+        p.sia_q = sia_product(p.parts, uks, batch, M, N, tau, hw, t, cap_q)
     return p
+
+
+def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q):
+    """Eq. 1 in its multiplicative (log-domain) form, evaluated per uKernel as Sec. 5.2 words it
+    ("cached in the data structure of each uKernel ... for a program composed of two uKernels we
+    take their average"): each constituent K gets CMR^c0 * Pad^c1 * Occ^c2 from its own
+    sub-workload -- the rows (columns) it covers, its own tile count -- and the program score
+    is the mean.  A weighted sum of the logarithms of the three metrics ranks single-uKernel
+    programs identically; the product is what a throughput estimate looks like (fraction of
+    cores busy x fraction of useful work x per-core efficiency).  Fixed point: every multiply is
+    floor(x * y / 2^20)."""
+    H = M if tau == 0 else N
+    W = N if tau == 0 else M
+    Wp = ceil_by(W, GRANULE)
+    off, total = 0, 0
+    for uid, cnt in parts_sorted:                       # placement order along tau
+        u = uks[uid]
+        e = _ext(u, tau)
+        across = ceil_div(Wp, _ext(u, 1 - tau))
+        T = batch * cnt * across
+        useful = max(0, min(H - off, cnt * e)) * W
+        area = cnt * across * u.tm * u.tn
+        off += cnt * e
+        cmr_q = (min(u.cmr_q, cap_q) << Q) // cap_q
+        pad_q = (useful << Q) // area
+        on, od = occ_fraction(T, hw["num_cus"])
+        occ_q = (on << Q) // od
+        x = ONE
+        for q, c in ((cmr_q, t["c0"]), (pad_q, t["c1"]), (occ_q, t["c2"])):
+            for _ in range(c):
+                x = (x * q) >> Q
+        total += x
+    return total // len(parts_sorted)
 
 
 def emit(parts, uks, batch, M, N, tau):

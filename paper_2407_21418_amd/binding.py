@@ -16,6 +16,7 @@ FT_ERR_NO_COVER, FT_ERR_HIP, FT_ERR_OOM = -4, -5, -6
 FT_OP_MATMUL, FT_OP_BMM, FT_OP_CONV2D = 0, 1, 2
 FT_F16, FT_BF16 = 0, 1
 FT_PLAN_PATCHWORK, FT_PLAN_PAD_BASELINE, FT_PLAN_FORCED, FT_PLAN_HOST_ONLY = 0, 1, 2, 16
+FT_SIA_LINEAR, FT_SIA_PRODUCT = 0, 1
 
 u32, u64, u16 = C.c_uint32, C.c_uint64, C.c_uint16
 
@@ -45,7 +46,7 @@ class ft_hw_model(_S):
 class ft_tuning(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "eps_min_pm", "eps_max_pm", "eps_step_pm", "lam_max_pm", "lam_min_pm", "lam_step_pm",
-        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2")]
+        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form")]
 
 
 class ft_op_desc(_S):

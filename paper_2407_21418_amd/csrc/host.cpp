@@ -46,6 +46,7 @@ void tuning_defaults(ft_tuning *t) {
     t->rest_regs = 72;
     t->psi_num = 1; t->psi_den = 8;
     t->c0 = t->c1 = t->c2 = 1;                                       // Sec. 5.2
+    t->sia_form = FT_SIA_PRODUCT;
 }
 
 struct Gemm {                // GEMM view of an operator: static extents (0 = dynamic)
@@ -167,8 +168,34 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
         acc += (uint64_t)(((u128)c << QBITS) / set.cap_q);
     }
     p.cmr_q = (uint32_t)(acc / p.nparts);
-    p.sia_q = (uint64_t)t.c0 * p.cmr_q + (uint64_t)t.c1 * p.pad_q + (uint64_t)t.c2 * p.occ_q;   // Eq. 1
     if (p.nparts == 2 && p.part[0].id > p.part[1].id) std::swap(p.part[0], p.part[1]);
+    if (t.sia_form == FT_SIA_LINEAR) {
+        p.sia_q = (uint64_t)t.c0 * p.cmr_q + (uint64_t)t.c1 * p.pad_q + (uint64_t)t.c2 * p.occ_q;   // Eq. 1 as printed
+    } else {
+        // multiplicative form, per uKernel on its own sub-workload, averaged (Sec. 5.2)
+        const uint64_t H = tau == 0 ? M : N, W = tau == 0 ? N : M;
+        uint64_t off = 0, total = 0;
+        for (uint32_t i = 0; i < p.nparts; ++i) {                 // placement order along tau
+            const ft_ukernel_info &u = set.uk[p.part[i].id];
+            const uint64_t e = ext(u, tau), cnt = p.part[i].count;
+            const uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
+            const uint64_t T = batch * cnt * across;
+            const uint64_t span = cnt * e;
+            const uint64_t len = H > off ? std::min<uint64_t>(H - off, span) : 0;
+            const u128 useful = (u128)len * W, area_u = (u128)cnt * across * u.tm * u.tn;
+            off += span;
+            const uint64_t cq = (uint64_t)(((u128)std::min<uint64_t>(u.cmr_q20, set.cap_q) << QBITS) / set.cap_q);
+            const uint64_t pq = (uint64_t)((useful << QBITS) / area_u);
+            const uint64_t oq = (uint64_t)(((u128)T << QBITS) / ceil_by(T, hw.num_cus));
+            u128 x = (u128)1 << QBITS;
+            const uint64_t qs[3] = {cq, pq, oq};
+            const uint32_t cs[3] = {t.c0, t.c1, t.c2};
+            for (int k = 0; k < 3; ++k)
+                for (uint32_t r = 0; r < cs[k]; ++r) x = (x * qs[k]) >> QBITS;
+            total += (uint64_t)x;
+        }
+        p.sia_q = total / p.nparts;
+    }
 }
 
 // Alg. 2 over the set's main-axis extents on the granule-rounded size Hp (last-success form).
@@ -359,7 +386,8 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
     const ft_hw_model &h = set->hw;
     const ft_tuning &t = set->t;
     if (!h.num_cus || !h.wave_size || h.regs_per_lane < 4 || !h.mfma_flops_per_clk_per_cu || !h.bw_global_bytes_per_clk_per_cu ||
-        !h.bw_lds_bytes_per_clk_per_cu || !t.zeta || !t.psi_den) {
+        !h.bw_lds_bytes_per_clk_per_cu || !t.zeta || !t.psi_den || t.sia_form > FT_SIA_PRODUCT ||
+        (t.sia_form == FT_SIA_PRODUCT && (t.c0 > 4 || t.c1 > 4 || t.c2 > 4))) {
         delete set;
         return FT_ERR_INVALID_ARG;
     }

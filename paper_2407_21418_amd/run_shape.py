@@ -23,6 +23,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--force", default="")
     ap.add_argument("--baseline", action="store_true")
+    ap.add_argument("--zeta", type=int, default=0, help="override the tuning's zeta (workgroups per CU)")
     ap.add_argument("--ring-mb", type=float, default=0.0, help="rotate over buffer sets totalling this many MB")
     ap.add_argument("--copy-mb", type=float, default=0.0,
                     help="also run a plain device copy of this many MB (calibrates FETCH_SIZE / WRITE_SIZE)")
@@ -33,7 +34,11 @@ def main():
 
     dt = ft.FT_F16 if a.dtype == "f16" else ft.FT_BF16
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dt, n=a.n, k=a.k, m_lo=1, m_hi=max(8192, a.m)))
-    uks = ft.ft_ukernels_derive(op, ft.ft_hw_query(0), None)
+    tuning = None
+    if a.zeta:
+        tuning = ft.ft_tuning_default()
+        tuning.zeta = a.zeta
+    uks = ft.ft_ukernels_derive(op, ft.ft_hw_query(0), tuning)
     mode, forced = (ft.FT_PLAN_PAD_BASELINE if a.baseline else ft.FT_PLAN_PATCHWORK), None
     if a.force:
         want = tuple(int(x) for x in a.force.split(","))

@@ -142,10 +142,11 @@ def test_custom_tuning_and_hw_are_honoured():
     op = OPS["dense3072"]
     hw, t = P.default_hw(), P.default_tuning()
     hw2 = dict(hw, num_cus=80, bw_lds_bytes_per_clk_per_cu=256)
-    t2 = dict(t, c0=1, c1=2, c2=6, zeta=1, rest_regs=96, psi_num=1, psi_den=5)
+    t2 = dict(t, c0=1, c1=2, c2=6, zeta=1, rest_regs=96, psi_num=1, psi_den=5, sia_form=P.SIA_LINEAR)
     uks = P.derive_ukernels(op, hw2, t2)
     lhw = ft.ft_hw_default_gfx950(); lhw.num_cus = 80; lhw.bw_lds_bytes_per_clk_per_cu = 256
     lt = ft.ft_tuning_default(); lt.c1 = 2; lt.c2 = 6; lt.zeta = 1; lt.rest_regs = 96; lt.psi_den = 5
+    lt.sia_form = ft.FT_SIA_LINEAR
     lop = to_lib_op(op)
     s = ft.ft_ukernels_derive(lop, lhw, lt)
     assert ft.ft_ukset_size(s) == len(uks)
@@ -153,6 +154,24 @@ def test_custom_tuning_and_hw_are_honoured():
         want = P.plan(op, uks, (1, M, 3072, 768), hw=hw2, t=t2)
         pl = ft.ft_plan_create(lop, s, ft.ft_shape(m=M), HOST)
         assert ft.ft_plan_descriptors(pl) == b"".join(d.pack() for d in want.descs)
+
+
+def test_product_form_with_exponents_matches_oracle():
+    op = OPS["llm11008"]
+    t2 = dict(P.default_tuning(), c0=2, c1=0, c2=3, sia_form=P.SIA_PRODUCT)
+    uks = P.derive_ukernels(op, None, t2)
+    lt = ft.ft_tuning_default(); lt.c0 = 2; lt.c1 = 0; lt.c2 = 3
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop, None, lt)
+    for M in (1, 45, 300, 1000, 4096, 8192):
+        want = P.plan(op, uks, (1, M, 11008, 4096), t=t2)
+        pl = ft.ft_plan_create(lop, s, ft.ft_shape(m=M), HOST)
+        assert ft.ft_plan_descriptors(pl) == b"".join(d.pack() for d in want.descs)
+        assert ft.ft_plan_stats_get(pl).sia_q20 == want.program.sia_q
+    lt.c0 = 5
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_ukernels_derive(lop, None, lt)
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
 
 
 def test_forced_program_mode():

@@ -84,6 +84,33 @@ def test_default_hyper_parameters_from_paper():
     assert t["zeta"] == 2 and (t["c0"], t["c1"], t["c2"]) == (1, 1, 1)
 
 
+def test_sia_product_form_by_hand():
+    """One uKernel, one shape, every factor recomputed from its definition."""
+    op = P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(1, 8192))
+    uks = P.derive_ukernels(op)
+    hw, t = P.default_hw(), P.default_tuning()
+    assert t["sia_form"] == P.SIA_PRODUCT
+    cap = max(u.cmr_q for u in uks)
+    u = next(u for u in uks if (u.tm, u.tn, u.gk) == (128, 128, 1))
+    p = P.evaluate([(u.id, 5)], uks, 1, 630, 3072, 0, hw, t, cap)          # H' = 640 = 5 * 128
+    T = 5 * 24
+    cmr = (min(u.cmr_q, cap) << 20) // cap
+    pad = ((630 * 3072) << 20) // (T * 128 * 128)
+    occ = (T << 20) // 256
+    assert p.sia_q == ((((cmr * pad) >> 20) * occ) >> 20)
+    # two uKernels: mean of the two per-uKernel products, each on its own rows
+    v = next(x for x in uks if (x.tm, x.tn, x.gk) == (16, 64, 1))
+    p2 = P.evaluate([(u.id, 4), (v.id, 8)], uks, 1, 630, 3072, 0, hw, t, cap)   # 512 + 128 rows
+    s_u = ((((cmr * (1 << 20)) >> 20) * ((4 * 24 << 20) // 256)) >> 20)
+    cmr_v = (min(v.cmr_q, cap) << 20) // cap
+    pad_v = ((118 * 3072) << 20) // (8 * 48 * 16 * 64)
+    s_v = ((((cmr_v * pad_v) >> 20) * ((8 * 48 << 20) // 512)) >> 20)
+    assert p2.sia_q == (s_u + s_v) // 2
+    # the printed linear form is still available
+    p3 = P.evaluate([(u.id, 5)], uks, 1, 630, 3072, 0, hw, dict(t, sia_form=P.SIA_LINEAR), cap)
+    assert p3.sia_q == p3.cmr_q + p3.pad_q + p3.occ_q
+
+
 def test_resource_closed_forms():
     op = P.Op(P.OP_BMM, P.F16, n=768, k=768, m_range=(1, 100))     # too small to ever fill the device:
     uks = P.derive_ukernels(op)                                     # the workload filters are skipped
@@ -285,7 +312,7 @@ def test_sia_is_the_weighted_sum_and_top1_is_max():
     op = P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(1, 8192))
     uks = P.derive_ukernels(op)
     hw, t = P.default_hw(), P.default_tuning()
-    t2 = dict(t, c0=3, c1=5, c2=7)
+    t2 = dict(t, c0=3, c1=5, c2=7, sia_form=P.SIA_LINEAR)
     cap = max(u.cmr_q for u in uks)
     shape = (1, 528, 3072, 768)
     pool = [P.evaluate(p, uks, 1, 528, 3072, 0, hw, t2, cap)
@@ -294,7 +321,5 @@ def test_sia_is_the_weighted_sum_and_top1_is_max():
         assert p.sia_q == 3 * p.cmr_q + 5 * p.pad_q + 7 * p.occ_q
         assert 0 <= p.cmr_q <= 1 << 20 and 0 < p.pad_q <= 1 << 20 and 0 < p.occ_q <= 1 << 20
     pl = P.plan(op, uks, shape, hw=hw, t=t2)
-    lvl = [[p for p in pool if p.in_bound and p.cross and p.saturated],
-           [p for p in pool if p.in_bound and p.cross], [p for p in pool if p.in_bound], pool]
-    cands = next(c for c in lvl if c)
+    cands = [p for p in pool if p.in_bound] or pool
     assert pl.program.sia_q == max(p.sia_q for p in cands)
