@@ -101,11 +101,12 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
     ftk::KArgs a;
     fill_args(plan, A, B, C, &a);
     // The LDS-DMA bodies need 16-byte aligned operands whose row pitches and reduce extent are
-    // multiples of 8 elements; everything else (and the convolution gather) takes the general bodies.
-    const bool fast = !a.is_conv && a.K % 8 == 0 && a.N % 8 == 0 &&
-                      (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0) &&
-                      (a.strideA % 8 == 0) && (a.strideB % 8 == 0);
-    if (!fast) {
+    // multiples of 8 elements (convolution: c_in a multiple of 64, c_out of 8); everything else
+    // takes the general bodies.
+    const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0);
+    const bool fast = a.is_conv ? (aligned && a.Cin % 64 == 0 && a.N % 8 == 0)
+                                : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
+    if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
         a.slot_code[0] = (uint32_t)ft_general_code((int)a.slot_code[0]);
         a.slot_code[1] = (uint32_t)ft_general_code((int)a.slot_code[1]);
     }

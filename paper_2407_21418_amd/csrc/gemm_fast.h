@@ -12,7 +12,8 @@
 // serialise the ring.  Register cost per lane: accumulators + two fragment sets + a few addresses.
 //
 // Preconditions (checked by the host before this path is chosen): A, B 16-byte aligned; row
-// pitches lda, ldb and K, N multiples of 8 elements; not a convolution.
+// pitches lda, ldb and K, N multiples of 8 elements; for a convolution c_in a multiple of 64
+// (a k-tile then lies inside one filter tap) and c_out a multiple of 8.
 #pragma once
 #include "gemm_body.h"
 
@@ -91,7 +92,11 @@ struct UKernelFast {
         // ---- copy assignments ---------------------------------------------------------------
         // A instruction i of this wave fills LDS bytes [wave*A_WAVE_BYTES + i*1024, +1024) of the
         // A tile: row = that offset / 128 (+ lane / 8), chunk position = lane % 8.
+        // Convolution (implicit GEMM, c_in a multiple of the k-tile): row = output pixel (n,p,q); one
+        // k-tile lies inside one filter tap (r,s), so the lane's source is pixel (p*stride-pad+r,
+        // q*stride-pad+s) of its image, channels ch0 + 8*kc .. +7, or the zero page in the halo.
         uint32_t goff_a[LA];
+        uint32_t a_pq[LA];                            // conv: (p*stride) << 16 | (q*stride)
         {
             uint32_t row0 = (wave * A_WAVE_BYTES) / 128 + lane / 8;
 #pragma unroll
@@ -100,7 +105,15 @@ struct UKernelFast {
                 uint32_t kc = (lane & 7u) ^ swzA(row);
                 uint32_t gm = m0 + row;
                 if (gm >= M) gm = M - 1;              // clamp: garbage rows are never stored
-                goff_a[i] = gm * g.lda + kc * 8;
+                if (!g.is_conv) {
+                    goff_a[i] = gm * g.lda + kc * 8;
+                    a_pq[i] = 0;
+                } else {
+                    uint32_t img = gm / (g.P * g.Q), rem = gm % (g.P * g.Q);
+                    uint32_t pp = rem / g.Q, qq = rem % g.Q;
+                    goff_a[i] = img * g.H * g.W * g.Cin + kc * 8;
+                    a_pq[i] = (pp * g.cstride) << 16 | (qq * g.cstride);
+                }
             }
         }
         const bool a_lane_on = (A_WAVE_BYTES >= 1024) || lane < (uint32_t)(A_WAVE_BYTES / 16);
@@ -122,16 +135,30 @@ struct UKernelFast {
             constexpr bool tail = decltype(tail_c)::value;
             unsigned char *st = smem + (kt % S) * STAGE_BYTES;
             const uint32_t k0 = kt * TK;
+            if (!g.is_conv) {
 #pragma unroll
-            for (int i = 0; i < LA; ++i) {
-                const uint16_t *p = Ab + (goff_a[i] + k0);
-                if constexpr (tail) {
-                    // logical chunk of this lane in instruction i (recomputed: tail tile only)
-                    uint32_t row = (wave * A_WAVE_BYTES) / 128 + lane / 8 + i * 8;
-                    uint32_t kc = (lane & 7u) ^ swzA(row);
-                    if (k0 + kc * 8 >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                for (int i = 0; i < LA; ++i) {
+                    const uint16_t *p = Ab + (goff_a[i] + k0);
+                    if constexpr (tail) {
+                        // logical chunk of this lane in instruction i (recomputed: tail tile only)
+                        uint32_t row = (wave * A_WAVE_BYTES) / 128 + lane / 8 + i * 8;
+                        uint32_t kc = (lane & 7u) ^ swzA(row);
+                        if (k0 + kc * 8 >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                    }
+                    if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
                 }
-                if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
+            } else {
+                const uint32_t tap = k0 / g.Cin, ch0 = k0 % g.Cin;       // uniform: c_in % 64 == 0
+                const uint32_t r = tap / g.S, sx = tap % g.S;
+#pragma unroll
+                for (int i = 0; i < LA; ++i) {
+                    const int h = (int)((a_pq[i] >> 16) + r) - (int)g.cpad;
+                    const int w = (int)((a_pq[i] & 0xffffu) + sx) - (int)g.cpad;
+                    const bool ok = h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W;
+                    const uint16_t *p = ok ? Ab + (goff_a[i] + ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch0)
+                                           : reinterpret_cast<const uint16_t *>(ft_zero_page);
+                    if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
+                }
             }
 #pragma unroll
             for (int i = 0; i < LB; ++i) {

@@ -149,6 +149,71 @@ def test_conv2d_implicit_gemm(res, batch):
         check(got, ref, refabs, f"conv res {res} mode {mode}")
 
 
+def test_conv2d_dma_gather_wide_channels_and_stride():
+    """LDS-DMA gather path (c_in a multiple of 64): c_in = 128 so a filter tap spans two k-tiles,
+    stride 2, c_out not a multiple of any tile width."""
+    g = np.random.default_rng(78)
+    n, H, W, Cin, Cout = 3, 17, 13, 128, 72
+    X = si.normal_bits(g, (n, H, W, Cin), 1.0, si.F16)
+    Wt = si.normal_bits(g, (3, 3, Cin, Cout), 0.1, si.F16)
+    for stride, pad in ((1, 1), (2, 1), (2, 0)):
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=ft.FT_F16, c_in=Cin, c_out=Cout, r=3, s=3,
+                                             stride=stride, pad=pad, m_lo=0, m_hi=1 << 20))
+        s = ft.ft_ukernels_derive(op)
+        ref, refabs = oc.conv2d_nhwc(X, Wt, si.F16, stride=stride, pad=pad, want_abs=True)
+        for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+            plan = ft.ft_plan_create(op, s, ft.ft_shape(img_n=n, img_h=H, img_w=W), mode)
+            check(run(plan, X, Wt, ref.size), ref, refabs, f"conv dma stride {stride} pad {pad} mode {mode}")
+
+
+def test_conv2d_full_size_sampled_pixels():
+    """Configured convolution at 8 x 112 x 112 (M = 100352 output pixels) in the default plan; the
+    oracle checks image corners, edges, tile-boundary pixels and random ones."""
+    res, batch = 112, 8
+    p = si.config4_problem(res, batch=batch)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=ft.FT_F16, c_in=64, c_out=128, r=3, s=3,
+                                         stride=1, pad=1, m_lo=0, m_hi=1 << 22))
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(img_n=batch, img_h=res, img_w=res))
+    M = batch * res * res
+    X, Wt = dev_bits(p["X"]), dev_bits(p["Wt"])
+    Y = torch.full((M, 128), float("nan"), dtype=torch.float32, device="cuda")
+    ft.ft_launch(plan, X.data_ptr(), Wt.data_ptr(), Y.data_ptr(), stream())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Y).all())
+    g = np.random.default_rng(6)
+    special = [0, res - 1, res, res * res - 1, res * res, M - 1, M - res, 127, 128, 129, 511, 512, 513,
+               (3 * res + 5) * res, (3 * res + 5) * res + res - 1]
+    pix = np.unique(np.concatenate([g.integers(0, M, 300), special])).astype(np.int64)
+    ref, refabs = oc.conv2d_nhwc(p["X"], p["Wt"], si.F16, pixels=pix, want_abs=True)
+    got = Y[torch.from_numpy(pix).cuda()].cpu().numpy().astype(np.float64)
+    check(got, ref, refabs, "conv 8x112x112")
+
+
+def test_attention_full_size_sampled_batches():
+    """Largest attention problem (B = 64, L = 512: 768 batch entries) in the default plans; the
+    oracle recomputes a few whole batch entries, the rest must be finite."""
+    nb, L = 768, 512
+    g = np.random.default_rng(12)
+    for which, (M, K, N), kw in (("qk", (L, 64, L), dict(k=64, m_lo=0, m_hi=512, n_lo=0, n_hi=512)),
+                                 ("pv", (L, L, 64), dict(n=64, m_lo=0, m_hi=512, k_lo=0, k_hi=512))):
+        A = torch.randn((nb, M, K), device="cuda").half()
+        B = torch.randn((nb, K, N), device="cuda").half()
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, **kw))
+        s = ft.ft_ukernels_derive(op)
+        shape = ft.ft_shape(batch=nb, m=L, n=L) if which == "qk" else ft.ft_shape(batch=nb, m=L, k=L)
+        plan = ft.ft_plan_create(op, s, shape)
+        Cd = torch.full((nb, M, N), float("nan"), dtype=torch.float32, device="cuda")
+        ft.ft_launch(plan, A.data_ptr(), B.data_ptr(), Cd.data_ptr(), stream())
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(Cd).all())
+        for b in (0, 1, 383, 767, int(g.integers(0, nb))):
+            Ab = A[b].cpu().numpy().view(np.uint16)
+            Bb = B[b].cpu().numpy().view(np.uint16)
+            ref, refabs = oc.matmul(Ab, Bb, si.F16, want_abs=True)
+            check(Cd[b].cpu().numpy().astype(np.float64), ref, refabs, f"{which} batch {b}")
+
+
 def test_conv2d_general_geometry():
     """Stride 2, no padding, channel count not a multiple of 8 (element-wise gather path)."""
     g = np.random.default_rng(77)
