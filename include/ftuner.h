@@ -63,7 +63,8 @@ typedef struct ft_hw_model {
     uint32_t clock_mhz;                      /* 2400                                         */
     uint32_t mfma_flops_per_clk_per_cu;      /* FLOPS of Eq. 6 for dense 16-bit MFMA (4096)  */
     uint32_t bw_global_bytes_per_clk_per_cu; /* bw_G of Eq. 7: L2 -> CU path (64)            */
-    uint32_t bw_lds_bytes_per_clk_per_cu;    /* bw_S of Eq. 7 (128)                          */
+    uint32_t bw_lds_bytes_per_clk_per_cu;    /* bw_S of Eq. 7 (256, measured 227..256)       */
+    uint32_t ktile_latency_clk;              /* latency of one k-tile step of the k loop (400)*/
     uint32_t hbm_gbytes_per_s;               /* 8000; used for rooflines only                */
     uint32_t num_xcds;                       /* 8                                            */
 } ft_hw_model;
@@ -84,7 +85,7 @@ typedef struct ft_tuning {
     uint32_t lam_max_pm, lam_min_pm, lam_step_pm;   /* 950, 900, 1                          */
     uint32_t zeta;                                  /* default active workgroups per CU: 2  */
     uint32_t rest_regs;                             /* RestRegs of Eq. 4: 72                */
-    uint32_t psi_num, psi_den;                      /* threshold of Eq. 6: 1/8              */
+    uint32_t psi_num, psi_den;                      /* threshold of Eq. 6: 1/64             */
     uint32_t c0, c1, c2;                            /* Eq. 1 coefficients: 1, 1, 1          */
     uint32_t sia_form;                              /* FT_SIA_LINEAR: c0*CMR + c1*Pad + c2*Occ of
                                                        the program, as printed; FT_SIA_PRODUCT

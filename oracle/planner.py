@@ -37,16 +37,17 @@ def default_hw():
     return dict(num_cus=256, simds_per_cu=4, wave_size=64, regs_per_lane=512,
                 max_waves_per_simd=8, lds_bytes_per_cu=163840, clock_mhz=2400,
                 mfma_flops_per_clk_per_cu=4096, bw_global_bytes_per_clk_per_cu=64,
-                bw_lds_bytes_per_clk_per_cu=128, hbm_gbytes_per_s=8000, num_xcds=8)
+                bw_lds_bytes_per_clk_per_cu=256, ktile_latency_clk=400, hbm_gbytes_per_s=8000,
+                num_xcds=8)
 
 
 def default_tuning():
     """Hyper-parameters (Sec. 4.2: epsilon 50%..95% step 1%, lambda 95%..90% step 0.1%,
     zeta = 2; Sec. 5.2: c0 = c1 = c2 = 1).  Per-mille units; psi is never given a value in
-    the paper, 1/8 here."""
+    the paper, 1/64 here."""
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
-                zeta=2, rest_regs=72, psi_num=1, psi_den=8, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT)
+                zeta=2, rest_regs=72, psi_num=1, psi_den=64, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT)
 
 
 # --------------------------------------------------------------------------------------
@@ -215,8 +216,11 @@ MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
 
 
-def compute_eff(tm, tn, gm, gn, k_ref, hw):
-    """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, K_mem = max of global and shared time.
+def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64):
+    """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem.  K_mem, the memory access latency of the uKernel,
+    is the larger of the global and the shared (LDS) transfer time plus, on gfx950, the
+    synchronisation latency of the k loop: ktile_latency_clk per k-tile a wave has to walk
+    through (ceil(K/tk) tiles, shared among the gk waves of a split-k grid).
     Returns (numerator, denominator) of the exact ratio."""
     flops = 2 * tm * tn * k_ref
     data_r = (tm + tn) * k_ref * ELT
@@ -230,8 +234,9 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw):
         mem_num, mem_den = g_num, g_den
     else:
         mem_num, mem_den = s_num, s_den
-    # (flops / FLOPS) / (mem_num / mem_den)
-    return flops * mem_den, hw["mfma_flops_per_clk_per_cu"] * mem_num
+    # (flops / FLOPS) / (mem_num / mem_den + lat * nk / gk)
+    lat_nk = hw["ktile_latency_clk"] * ceil_div(k_ref, tk)
+    return flops * mem_den * gk, hw["mfma_flops_per_clk_per_cu"] * (mem_num * gk + lat_nk * mem_den)
 
 
 def reg_budget(regs, hw):
@@ -328,7 +333,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 if regs * waves_per_simd > hw["regs_per_lane"]:
                     continue                                        # Eq. 4, block.bound = 1
                 budget = reg_budget(regs, hw)
-                cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw)
+                cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk)
                 if cn * t["psi_den"] < t["psi_num"] * cd:
                     continue                                        # Eq. 6
                 cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,

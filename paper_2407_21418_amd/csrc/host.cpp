@@ -32,7 +32,8 @@ void hw_defaults(ft_hw_model *h) {
     h->clock_mhz = 2400;
     h->mfma_flops_per_clk_per_cu = 4096;
     h->bw_global_bytes_per_clk_per_cu = 64;
-    h->bw_lds_bytes_per_clk_per_cu = 128;
+    h->bw_lds_bytes_per_clk_per_cu = 256;
+    h->ktile_latency_clk = 400;
     h->hbm_gbytes_per_s = 8000;
     h->num_xcds = 8;
 }
@@ -44,7 +45,7 @@ void tuning_defaults(ft_tuning *t) {
     t->lam_max_pm = 950; t->lam_min_pm = 900; t->lam_step_pm = 1;    // 95%..90%, -0.1%
     t->zeta = 2;                                                     // Sec. 4.2
     t->rest_regs = 72;
-    t->psi_num = 1; t->psi_den = 8;
+    t->psi_num = 1; t->psi_den = 64;
     t->c0 = t->c1 = t->c2 = 1;                                       // Sec. 5.2
     t->sia_form = FT_SIA_PRODUCT;
 }
@@ -58,9 +59,11 @@ Gemm static_view(const ft_op_desc &d) {
     return {d.m, d.n, d.k};
 }
 
-// Eq. 6 / Eq. 7: compute_eff = (FLOPs / FLOPS) : max(global time, LDS time), as num/den.
-void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint64_t kref, const ft_hw_model &hw,
-                 u128 *num, u128 *den) {
+// Eq. 6 / Eq. 7: compute_eff = (FLOPs / FLOPS) : K_mem as num/den, with K_mem = max(global time,
+// LDS time) + the synchronisation latency of the k loop (ktile_latency_clk per k-tile, the tiles
+// being shared among the gk waves of a split-k grid).
+void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk, uint32_t tk, uint64_t kref,
+                 const ft_hw_model &hw, u128 *num, u128 *den) {
     u128 flops = (u128)2 * tm * tn * kref;
     u128 data_r = (u128)(tm + tn) * kref * ELT;
     u128 data_w = (u128)tm * tn * 4;
@@ -71,8 +74,9 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint64_t kr
     u128 mem_num, mem_den;
     if (g_num * s_den >= s_num * g_den) { mem_num = g_num; mem_den = g_den; }
     else { mem_num = s_num; mem_den = s_den; }
-    *num = flops * mem_den;
-    *den = (u128)hw.mfma_flops_per_clk_per_cu * mem_num;
+    u128 lat_nk = (u128)hw.ktile_latency_clk * ceil_div(kref, tk);
+    *num = flops * mem_den * gk;
+    *den = (u128)hw.mfma_flops_per_clk_per_cu * (mem_num * gk + lat_nk * mem_den);
 }
 
 // Shapes of the workload along one dynamic axis: both ends of the registered range and the
@@ -437,7 +441,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 uint32_t regs = acc + t.rest_regs;
                 if (regs > h.regs_per_lane) continue;                    // Eq. 4 at block.bound = 1
                 u128 cn, cd;
-                compute_eff(tm, tn, gm, gn, kref, h, &cn, &cd);
+                compute_eff(tm, tn, gm, gn, gk, tk, kref, h, &cn, &cd);
                 if (cn * t.psi_den < (u128)t.psi_num * cd) continue;     // Eq. 6
                 ft_ukernel_info u;
                 std::memset(&u, 0, sizeof(u));

@@ -141,10 +141,11 @@ def test_pool_scores_match_oracle(name):
 def test_custom_tuning_and_hw_are_honoured():
     op = OPS["dense3072"]
     hw, t = P.default_hw(), P.default_tuning()
-    hw2 = dict(hw, num_cus=80, bw_lds_bytes_per_clk_per_cu=256)
+    hw2 = dict(hw, num_cus=80, bw_lds_bytes_per_clk_per_cu=128, ktile_latency_clk=0)
     t2 = dict(t, c0=1, c1=2, c2=6, zeta=1, rest_regs=96, psi_num=1, psi_den=5, sia_form=P.SIA_LINEAR)
     uks = P.derive_ukernels(op, hw2, t2)
-    lhw = ft.ft_hw_default_gfx950(); lhw.num_cus = 80; lhw.bw_lds_bytes_per_clk_per_cu = 256
+    lhw = ft.ft_hw_default_gfx950(); lhw.num_cus = 80; lhw.bw_lds_bytes_per_clk_per_cu = 128
+    lhw.ktile_latency_clk = 0
     lt = ft.ft_tuning_default(); lt.c1 = 2; lt.c2 = 6; lt.zeta = 1; lt.rest_regs = 96; lt.psi_den = 5
     lt.sia_form = ft.FT_SIA_LINEAR
     lop = to_lib_op(op)

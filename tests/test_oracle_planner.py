@@ -166,9 +166,14 @@ def test_workload_filters_crosspick_and_eq5():
 def test_compute_eff_closed_form():
     hw = P.default_hw()
     # 128x128 tile, 2x2 waves, K = 768: flops 2*128*128*768 at 4096 flop/clk = 6144 clk;
-    # global (256*768*2 + 128*128*4) / 64 = 7168 clk; LDS (393216 + 768*2*512) / 128 = 9216 clk
+    # global (256*768*2 + 128*128*4) / 64 = 7168 clk; LDS (393216 + 768*2*512) / 256 = 4608 clk;
+    # k-loop latency 400 clk x 12 k-tiles = 4800 clk  ->  K_mem = 7168 + 4800
     n, d = P.compute_eff(128, 128, 2, 2, 768, hw)
-    assert n * 9216 == d * 6144
+    assert n * (7168 + 4800) == d * 6144
+    # split-k grid: the four waves share the 12 k-tiles
+    n4, d4 = P.compute_eff(32, 32, 1, 1, 768, hw, gk=4)
+    glob = (64 * 768 * 2 + 32 * 32 * 4) / 64
+    assert abs(n4 / d4 - (2 * 32 * 32 * 768 / 4096) / (glob + 400 * 12 / 4)) < 1e-12
     # a bigger tile is more compute-intensive
     n2, d2 = P.compute_eff(256, 256, 2, 2, 768, hw)
     assert n2 * d > n * d2
