@@ -53,6 +53,7 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, ftk::KAr
         a->slot_first[i] = p->slot_first[i];
         a->slot_rows[i] = p->slot_rows[i];
         a->slot_cols[i] = p->slot_cols[i];
+        a->slot_group[i] = p->slot_group[i];
     }
     a->num_xcds = p->num_xcds;
 }

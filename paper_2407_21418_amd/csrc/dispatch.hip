@@ -38,12 +38,12 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t b, uint32_t n, uint32_t n
 }
 
 // Inside a constituent's tile grid (rows x cols per batch entry, row-major in the table) the
-// sequence is walked in groups of 8 tile rows, column by column, so the ~32 tiles an XCD runs at
+// sequence is walked in groups of G tile rows, column by column, so the tiles an XCD runs at
 // once form a compact 2-D block: they share few A row panels AND few B column panels, which is
-// what the per-XCD L2 can keep (a 1-D strip of tiles makes every XCD fetch all of B).
-__device__ __forceinline__ uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols) {
-    constexpr uint32_t G = 8;
-    if (rows < 2 || cols < 2) return u;
+// what the per-XCD L2 can keep (a 1-D strip of tiles makes every XCD fetch all of B).  The host
+// picks G per constituent from the tile shape and the number of tiles an XCD holds at once.
+__device__ __forceinline__ uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols, uint32_t G) {
+    if (rows < 2 || cols < 2 || G < 2) return u;
     const uint32_t per = rows * cols;
     const uint32_t bidx = u / per, v = u % per;
     const uint32_t grp = v / (G * cols), w = v % (G * cols);
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const uint32_t seq = xcd_remap(blockIdx.x, g.n_tiles, g.num_xcds);
     const uint32_t slot = seq >= g.slot_first[1] ? 1u : 0u;
-    const uint32_t t = g.slot_first[slot] + grouped_index(seq - g.slot_first[slot], g.slot_rows[slot], g.slot_cols[slot]);
+    const uint32_t t = g.slot_first[slot] + grouped_index(seq - g.slot_first[slot], g.slot_rows[slot], g.slot_cols[slot], g.slot_group[slot]);
     const TileDesc d = g.descs[t];
     const uint32_t code = g.slot_code[slot];
     switch (code) {

@@ -26,6 +26,7 @@ struct ft_plan {
     uint32_t slot_code[2];
     uint32_t slot_stages[2];
     uint32_t slot_first[2], slot_rows[2], slot_cols[2];   // tile grid of each constituent in the table
+    uint32_t slot_group[2];                                // tile rows per group of the launch order
     uint32_t num_xcds;
     uint32_t img_h, img_w, out_p, out_q;   // conv geometry
     void *d_descs;                          // device copy of descs (NULL for host-only / empty plans)

@@ -48,6 +48,7 @@ struct KArgs {
     uint32_t slot_first[2];           // first descriptor of each constituent's block of the table
     uint32_t slot_rows[2];            // its tile grid per batch entry: rows (m) x columns (n)
     uint32_t slot_cols[2];
+    uint32_t slot_group[2];           // tile rows walked together in the launch order (XCD locality)
     uint32_t num_xcds;
 };
 

@@ -427,9 +427,16 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
                 if (sv.n && ceil_by(sv.n, GRANULE) % tn) continue;
+                uint32_t acc = wm * wn / h.wave_size;
+                uint32_t regs = acc + t.rest_regs;
+                if (regs > h.regs_per_lane) continue;                    // Eq. 4 at block.bound = 1
+                // registers are granted in power-of-two fractions of the file (128, 256, 512)
+                uint32_t budget = h.regs_per_lane / 4;
+                while (budget < regs) budget *= 2;
                 // LDS ring depth: as many k-tiles as fit in one workgroup's share of the LDS when
                 // zeta workgroups are resident (2..8); every stage beyond the one being consumed
-                // is global-memory traffic in flight
+                // is global-memory traffic in flight (measured: a third stage for tiles that are
+                // alone on the CU anyway gains nothing, the loop is bound by fetch bandwidth)
                 // (a split-k workgroup keeps one ring per wave and is meant to own the CU's LDS)
                 uint32_t stage_bytes = (tm + tn) * tk * ELT;
                 uint32_t stages = gk == 1 ? (h.lds_bytes_per_cu / t.zeta) / stage_bytes
@@ -437,9 +444,6 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 stages = std::max(MIN_STAGES, std::min(MAX_STAGES, stages));
                 uint32_t lds = gk * stages * stage_bytes;
                 if (lds > h.lds_bytes_per_cu) continue;                  // mem.IsOverflow
-                uint32_t acc = wm * wn / h.wave_size;
-                uint32_t regs = acc + t.rest_regs;
-                if (regs > h.regs_per_lane) continue;                    // Eq. 4 at block.bound = 1
                 u128 cn, cd;
                 compute_eff(tm, tn, gm, gn, gk, tk, kref, h, &cn, &cd);
                 if (cn * t.psi_den < (u128)t.psi_num * cd) continue;     // Eq. 6
@@ -448,9 +452,6 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 u.struct_size = sizeof(u);
                 u.tm = tm; u.tn = tn; u.tk = tk; u.wm = wm; u.wn = wn; u.gm = gm; u.gn = gn; u.gk = gk;
                 u.mfma = mfma; u.stages = stages; u.lds_bytes = lds; u.acc_regs = acc; u.regs = regs;
-                // registers are granted in power-of-two fractions of the file (128, 256, 512)
-                uint32_t budget = h.regs_per_lane / 4;
-                while (budget < regs) budget *= 2;
                 u.reg_budget = budget;
                 u.max_wg_per_cu = std::min(std::min(h.lds_bytes_per_cu / lds, h.regs_per_lane / budget),
                                            h.max_waves_per_simd);
@@ -563,7 +564,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     pl->slot_id[0] = pl->slot_id[1] = 0;
     pl->slot_code[0] = pl->slot_code[1] = 0;
     pl->slot_stages[0] = pl->slot_stages[1] = MIN_STAGES;
-    for (int i = 0; i < 2; ++i) { pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = 1; }
+    for (int i = 0; i < 2; ++i) { pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = pl->slot_group[i] = 1; }
     ft_plan_stats &s = pl->st;
     std::memset(&s, 0, sizeof(s));
     s.struct_size = sizeof(s);
@@ -653,6 +654,23 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         pl->slot_id[i] = u.id;
         pl->slot_code[i] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn, u.gk);
         pl->slot_stages[i] = u.stages;
+        // Launch order: an XCD works on a window of consecutive tiles (its share of the table, at
+        // most what its CUs hold at once).  Walk the grid in groups of g tile rows so that window is
+        // a g x (window/g) block, with g chosen to minimise the A + B panel bytes the block touches.
+        {
+            const uint64_t nx = pl->num_xcds;
+            const uint64_t share = ceil_div((uint64_t)grid[i].rows * grid[i].cols * r.batch, nx);
+            const uint64_t held = (uint64_t)std::max<uint32_t>(1, set->hw.num_cus / (uint32_t)nx) * std::max<uint32_t>(1, u.max_wg_per_cu);
+            const uint64_t window = std::max<uint64_t>(1, std::min(share, held));
+            uint32_t best_g = 1;
+            uint64_t best_cost = ~0ull;
+            for (uint32_t g = 1; g <= 16; g *= 2) {
+                const uint64_t rows_in = std::min<uint64_t>(g, grid[i].rows);
+                const uint64_t cost = rows_in * u.tm + std::min<uint64_t>(ceil_div(window, rows_in), grid[i].cols) * u.tn;
+                if (cost <= best_cost) { best_cost = cost; best_g = g; }
+            }
+            pl->slot_group[i] = best_g;
+        }
         lds = std::max(lds, u.lds_bytes);
         uint32_t by_model = 0;
         for (uint32_t b = set->hw.regs_per_lane / 4; b < u.reg_budget && by_model < FT_NUM_CLASSES - 1; b *= 2) ++by_model;
