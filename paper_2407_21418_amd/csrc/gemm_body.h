@@ -99,6 +99,43 @@ __device__ __forceinline__ uint4 ld_partial(const uint16_t *p, int nvalid) {
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// fp32 store of one wave's accumulator blocks (rows m0w.., columns n0w.. of C).
+// 32x32 block: acc[4*i + j] -> row 8*i + 4*(lane/32) + j, column lane % 32
+// 16x16 block: acc[j]       -> row 4*(lane/16) + j,        column lane % 16
+// A wave tile that lies wholly inside C (uniform test) is stored without predication from one
+// per-lane pointer: one 64-bit add per row, the column blocks go into the instruction offsets.
+template <bool M16, int BM, int BN, typename Acc>
+__device__ __forceinline__ void store_acc(float *__restrict__ Cb, uint32_t ldc, uint32_t M, uint32_t N,
+                                          uint32_t m0w, uint32_t n0w, uint32_t lane, const Acc (&acc)[BM][BN]) {
+    constexpr int MB = M16 ? 16 : 32, NE = M16 ? 4 : 16;
+    const uint32_t lrow = 4 * (lane / MB), lcol = lane % MB;
+    if (m0w + BM * MB <= M && n0w + BN * MB <= N) {
+        float *lp = Cb + ((uint64_t)(m0w + lrow) * ldc + n0w + lcol);
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const uint32_t r = bi * MB + (M16 ? e : 8 * (e / 4) + (e % 4));
+                float *rp = lp + (uint64_t)r * ldc;
+#pragma unroll
+                for (int bj = 0; bj < BN; ++bj) rp[bj * MB] = acc[bi][bj][e];
+            }
+        return;
+    }
+#pragma unroll
+    for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < BN; ++bj) {
+            const uint32_t col = n0w + bj * MB + lcol;
+            if (col >= N) continue;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const uint32_t row = m0w + bi * MB + lrow + (M16 ? e : 8 * (e / 4) + (e % 4));
+                if (row < M) Cb[(uint64_t)row * ldc + col] = acc[bi][bj][e];
+            }
+        }
+}
+
 template <int DT, int WM, int WN, int GM, int GN, int TK>
 struct UKernelBody {
     static constexpr int TM = GM * WM, TN = GN * WN;
@@ -315,23 +352,8 @@ struct UKernelBody {
             }
         }
 
-        // ---- epilogue: fp32 store with row / column predication --------------------------
-        // 32x32 block: acc[4*i + j] -> row 8*i + 4*(lane/32) + j, column lane % 32
-        // 16x16 block: acc[j]       -> row 4*(lane/16) + j,        column lane % 16
-#pragma unroll
-        for (int bi = 0; bi < BM; ++bi)
-#pragma unroll
-            for (int bj = 0; bj < BN; ++bj) {
-                uint32_t col = n0 + wave_n * WN + bj * MB + (lane % MB);
-                uint32_t rbase = m0 + wave_m * WM + bi * MB;
-                if (col >= N) continue;
-#pragma unroll
-                for (int e = 0; e < (M16 ? 4 : 16); ++e) {
-                    uint32_t row = M16 ? rbase + 4 * (lane / 16) + e
-                                       : rbase + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
-                    if (row < M) Cb[row * g.ldc + col] = acc[bi][bj][e];
-                }
-            }
+        // ---- epilogue: fp32 store, predicated only for tiles on the edge of C --------------
+        store_acc<M16, BM, BN>(Cb, g.ldc, M, N, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
 };
 

@@ -95,6 +95,8 @@ struct UKernelFast {
         // Convolution (implicit GEMM, c_in a multiple of the k-tile): row = output pixel (n,p,q); one
         // k-tile lies inside one filter tap (r,s), so the lane's source is pixel (p*stride-pad+r,
         // q*stride-pad+s) of its image, channels ch0 + 8*kc .. +7, or the zero page in the halo.
+        // Source offsets are kept in BYTES relative to the (uniform) operand base, so a copy is
+        // "scalar base of this k-tile + 32-bit lane offset": one instruction, no 64-bit vector math.
         uint32_t goff_a[LA];
         uint32_t a_pq[LA];                            // conv: (p*stride) << 16 | (q*stride)
         {
@@ -106,12 +108,12 @@ struct UKernelFast {
                 uint32_t gm = m0 + row;
                 if (gm >= M) gm = M - 1;              // clamp: garbage rows are never stored
                 if (!g.is_conv) {
-                    goff_a[i] = gm * g.lda + kc * 8;
+                    goff_a[i] = (gm * g.lda + kc * 8) * 2;
                     a_pq[i] = 0;
                 } else {
                     uint32_t img = gm / (g.P * g.Q), rem = gm % (g.P * g.Q);
                     uint32_t pp = rem / g.Q, qq = rem % g.Q;
-                    goff_a[i] = img * g.H * g.W * g.Cin + kc * 8;
+                    goff_a[i] = (img * g.H * g.W * g.Cin + kc * 8) * 2;
                     a_pq[i] = (pp * g.cstride) << 16 | (qq * g.cstride);
                 }
             }
@@ -126,7 +128,7 @@ struct UKernelFast {
             uint32_t nc = p ^ swzB<TN>(krow);
             uint32_t col = n0 + nc * 8;
             if (col >= N) col = n0;                   // clamp: garbage columns are never stored
-            goff_b[i] = krow * g.ldb + col;
+            goff_b[i] = (krow * g.ldb + col) * 2;
         }
         const bool b_lane_on = (B_WAVE_BYTES >= 1024) || lane < (uint32_t)(B_WAVE_BYTES / 16);
         const bool k_tail = (K % TK) != 0;
@@ -135,15 +137,18 @@ struct UKernelFast {
             constexpr bool tail = decltype(tail_c)::value;
             unsigned char *st = smem + (kt % S) * STAGE_BYTES;
             const uint32_t k0 = kt * TK;
+            // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
+            const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
+            const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
             if (!g.is_conv) {
 #pragma unroll
                 for (int i = 0; i < LA; ++i) {
-                    const uint16_t *p = Ab + (goff_a[i] + k0);
+                    const void *p = abase + (uint32_t)(goff_a[i] + ka);
                     if constexpr (tail) {
                         // logical chunk of this lane in instruction i (recomputed: tail tile only)
                         uint32_t row = (wave * A_WAVE_BYTES) / 128 + lane / 8 + i * 8;
                         uint32_t kc = (lane & 7u) ^ swzA(row);
-                        if (k0 + kc * 8 >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                        if (k0 + kc * 8 >= K) p = ft_zero_page;
                     }
                     if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
                 }
@@ -155,17 +160,18 @@ struct UKernelFast {
                     const int h = (int)((a_pq[i] >> 16) + r) - (int)g.cpad;
                     const int w = (int)((a_pq[i] & 0xffffu) + sx) - (int)g.cpad;
                     const bool ok = h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W;
-                    const uint16_t *p = ok ? Ab + (goff_a[i] + ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch0)
-                                           : reinterpret_cast<const uint16_t *>(ft_zero_page);
+                    const void *p = ok ? reinterpret_cast<const char *>(Ab) + goff_a[i] +
+                                             (uint64_t)(((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch0) * 2
+                                       : reinterpret_cast<const char *>(ft_zero_page);
                     if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
                 }
             }
 #pragma unroll
             for (int i = 0; i < LB; ++i) {
-                const uint16_t *p = Bb + (goff_b[i] + k0 * g.ldb);
+                const void *p = bbase + (uint32_t)(goff_b[i] + kb);
                 if constexpr (tail) {
                     uint32_t krow = (wave * B_WAVE_BYTES + i * 1024 + lane * 16) / (TN * 2);
-                    if (k0 + krow >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                    if (k0 + krow >= K) p = ft_zero_page;
                 }
                 if (b_lane_on) lds_dma16(p, st + A_BYTES + wave * B_WAVE_BYTES + i * 1024);
             }
@@ -225,21 +231,8 @@ struct UKernelFast {
             step<0>(a_addr, b_addr, fa, fb, acc);
         }
 
-        // ---- epilogue (same lane layout as gemm_body.h) ------------------------------------------------
-#pragma unroll
-        for (int bi = 0; bi < BM; ++bi)
-#pragma unroll
-            for (int bj = 0; bj < BN; ++bj) {
-                uint32_t col = n0 + wave_n * WN + bj * MB + (lane % MB);
-                uint32_t rbase = m0 + wave_m * WM + bi * MB;
-                if (col >= N) continue;
-#pragma unroll
-                for (int e = 0; e < (M16 ? 4 : 16); ++e) {
-                    uint32_t row = M16 ? rbase + 4 * (lane / 16) + e
-                                       : rbase + 8 * (e / 4) + 4 * (lane / 32) + (e % 4);
-                    if (row < M) Cb[row * g.ldc + col] = acc[bi][bj][e];
-                }
-            }
+        // ---- epilogue ------------------------------------------------------------------------------
+        store_acc<M16, BM, BN>(Cb, g.ldc, M, N, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
 
     // LDS reads of the A and B fragments of k-step ks into fragment set buf.  Row offsets of the
@@ -372,7 +365,7 @@ struct UKernelSplitK {
             uint32_t kc = (lane & 7u) ^ swzA(row);
             uint32_t gm = m0 + row;
             if (gm >= M) gm = M - 1;
-            goff_a[i] = gm * g.lda + kc * 8;
+            goff_a[i] = (gm * g.lda + kc * 8) * 2;          // bytes from the operand base
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
@@ -381,7 +374,7 @@ struct UKernelSplitK {
             uint32_t nc = p ^ swzB<TN>(krow);
             uint32_t col = n0 + nc * 8;
             if (col >= N) col = n0;
-            goff_b[i] = krow * g.ldb + col;
+            goff_b[i] = (krow * g.ldb + col) * 2;
         }
         const bool k_tail = (K % TK) != 0;
 
@@ -389,22 +382,25 @@ struct UKernelSplitK {
             constexpr bool tail = decltype(tail_c)::value;
             unsigned char *st = ring + (j % S) * STAGE_BYTES;
             const uint32_t k0 = (wave + 4 * j) * TK;
+            // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
+            const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
+            const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
 #pragma unroll
             for (int i = 0; i < LA; ++i) {
-                const uint16_t *p = Ab + (goff_a[i] + k0);
+                const void *p = abase + (uint32_t)(goff_a[i] + ka);
                 if constexpr (tail) {
                     uint32_t row = i * 8 + lane / 8;
                     uint32_t kc = (lane & 7u) ^ swzA(row);
-                    if (k0 + kc * 8 >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                    if (k0 + kc * 8 >= K) p = ft_zero_page;
                 }
                 lds_dma16(p, st + i * 1024);
             }
 #pragma unroll
             for (int i = 0; i < LB; ++i) {
-                const uint16_t *p = Bb + (goff_b[i] + k0 * g.ldb);
+                const void *p = bbase + (uint32_t)(goff_b[i] + kb);
                 if constexpr (tail) {
                     uint32_t krow = (i * 1024 + lane * 16) / (TN * 2);
-                    if (k0 + krow >= K) p = reinterpret_cast<const uint16_t *>(ft_zero_page);
+                    if (k0 + krow >= K) p = ft_zero_page;
                 }
                 lds_dma16(p, st + A_BYTES + i * 1024);
             }
