@@ -220,6 +220,12 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
                          const ft_forced_program *forced, ft_plan **out);
 /* *descs: host pointer to library-owned memory, valid until ft_plan_destroy. */
 ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, uint64_t *n);
+/* Which descriptor each workgroup of the launch takes (Sec. 3: one uKernel = one thread block):
+ * order[b] = index into the descriptor table of workgroup b, for b < min(*n, cap); *n receives
+ * the number of workgroups (= tiles).  The order is a permutation of the table: every XCD (a
+ * group of CUs with its own L2; workgroup b runs on XCD b % num_xcds) takes a contiguous slice of
+ * each constituent's tiles, walked in 2-D groups.  order: host pointer, caller-owned. */
+ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t cap, uint64_t *n);
 ft_status ft_plan_stats_get(const ft_plan *plan, ft_plan_stats *out);
 void ft_plan_destroy(ft_plan *plan);
 

@@ -111,6 +111,7 @@ SYMBOLS = {
     "ft_ukset_destroy": (None, [_P]),
     "ft_plan_create": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, C.POINTER(ft_forced_program), C.POINTER(_P)]),
     "ft_plan_descriptors": (C.c_int32, [_P, C.POINTER(C.POINTER(ft_tile_desc)), C.POINTER(u64)]),
+    "ft_plan_launch_order": (C.c_int32, [_P, C.POINTER(u32), u64, C.POINTER(u64)]),
     "ft_plan_stats_get": (C.c_int32, [_P, C.POINTER(ft_plan_stats)]),
     "ft_plan_destroy": (None, [_P]),
     "ft_plan_pool": (C.c_int32, [_P, _P, C.POINTER(ft_shape), C.POINTER(ft_pool_entry), u32, C.POINTER(u32)]),
@@ -241,6 +242,15 @@ def ft_plan_descriptors(p: Plan) -> bytes:
     if n.value == 0:
         return b""
     return C.string_at(ptr, n.value * C.sizeof(ft_tile_desc))
+
+
+def ft_plan_launch_order(p: Plan):
+    """Descriptor index taken by each workgroup of the launch (a permutation of the table)."""
+    n = u64()
+    _check(lib().ft_plan_launch_order(p.ptr, None, 0, C.byref(n)), "ft_plan_launch_order")
+    buf = (u32 * max(1, n.value))()
+    _check(lib().ft_plan_launch_order(p.ptr, buf, n.value, C.byref(n)), "ft_plan_launch_order")
+    return list(buf[:n.value])
 
 
 def ft_plan_stats_get(p: Plan) -> ft_plan_stats:

@@ -31,6 +31,22 @@ def _run(cmd, log):
     return time.time() - t
 
 
+def _resource_usage(log):
+    """The compiler's kernel-resource-usage remarks of one object, as {name: value}."""
+    out = {}
+    with open(log) as f:
+        for line in f:
+            if "remark:" not in line or "[-Rpass-analysis" not in line:
+                continue
+            body = line.split("remark:", 1)[1].split("[-Rpass-analysis", 1)[0].strip()
+            if ":" in body:
+                k, v = body.rsplit(":", 1)
+                k, v = k.strip(), v.strip()
+                if k in ("VGPRs", "AGPRs", "ScratchSize [bytes/lane]", "VGPRs Spill", "SGPRs Spill", "Occupancy [waves/SIMD]"):
+                    out[k] = int(v)
+    return out
+
+
 def _stale(obj, srcs):
     if not os.path.exists(obj):
         return True
@@ -38,7 +54,7 @@ def _stale(obj, srcs):
     return any(os.path.getmtime(s) > t for s in srcs)
 
 
-def build(verbose=True, remarks=False, jobs=None, incremental=False):
+def build(verbose=True, remarks=True, jobs=None, incremental=False):
     """incremental=True recompiles only objects older than the sources they include."""
     os.makedirs(OUT, exist_ok=True)
     hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + \
@@ -49,15 +65,13 @@ def build(verbose=True, remarks=False, jobs=None, incremental=False):
             obj = os.path.join(OUT, f"dispatch_dt{dt}_c{cl}.o")
             cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-c",
                                       os.path.join(CSRC, "dispatch.hip"), "-o", obj]
-            if remarks:
-                cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             steps.append((obj, cmd))
     for dt in (0, 1):
         obj = os.path.join(OUT, f"dispatch_dt{dt}_gen.o")
         cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", "-DFT_CLASS=2", "-DFT_GENERIC=1", "-c",
                                   os.path.join(CSRC, "dispatch.hip"), "-o", obj]
-        if remarks:
-            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+        cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
         steps.append((obj, cmd))
     for src in ("host.cpp", "device.hip"):
         obj = os.path.join(OUT, src.replace(".", "_") + ".o")
@@ -73,6 +87,16 @@ def build(verbose=True, remarks=False, jobs=None, incremental=False):
             dt = fut.result()
             if verbose:
                 print(f"  built {os.path.basename(futs[fut])} in {dt:.1f}s", flush=True)
+    # a dispatcher that touches scratch memory (spilled registers, kernel arguments copied to the
+    # stack by a dynamically indexed array) is several times slower: refuse to link it
+    for obj, _ in steps:
+        if "dispatch_" not in obj or not os.path.exists(obj + ".log"):
+            continue
+        use = _resource_usage(obj + ".log")
+        if verbose or remarks:
+            print(f"  {os.path.basename(obj)}: {use}", flush=True)
+        if use.get("ScratchSize [bytes/lane]", 0) or use.get("VGPRs Spill", 0):
+            raise RuntimeError(f"{os.path.basename(obj)} uses scratch memory: {use}")
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in steps]
     _run(link, os.path.join(OUT, "link.log"))
     if verbose:

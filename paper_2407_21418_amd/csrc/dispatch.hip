@@ -7,6 +7,7 @@
 #include "gemm_fast.h"
 #include "family.h"
 #include "launch_iface.h"
+#include "tile_order.h"
 
 #ifndef FT_DT
 #error "define FT_DT"
@@ -28,37 +29,21 @@
 
 namespace ftk {
 
-// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).  Give each
-// XCD one contiguous slice of the descriptor table, so tiles that share an A row panel (and
-// walk the same B columns) meet in the same per-XCD L2.
-__device__ __forceinline__ uint32_t xcd_remap(uint32_t b, uint32_t n, uint32_t nx) {
-    uint32_t x = b % nx, j = b / nx;
-    uint32_t q = n / nx, r = n % nx;
-    return x * q + (x < r ? x : r) + j;
-}
-
-// Inside a constituent's tile grid (rows x cols per batch entry, row-major in the table) the
-// sequence is walked in groups of G tile rows, column by column, so the tiles an XCD runs at
-// once form a compact 2-D block: they share few A row panels AND few B column panels, which is
-// what the per-XCD L2 can keep (a 1-D strip of tiles makes every XCD fetch all of B).  The host
-// picks G per constituent from the tile shape and the number of tiles an XCD holds at once.
-__device__ __forceinline__ uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols, uint32_t G) {
-    if (rows < 2 || cols < 2 || G < 2) return u;
-    const uint32_t per = rows * cols;
-    const uint32_t bidx = u / per, v = u % per;
-    const uint32_t grp = v / (G * cols), w = v % (G * cols);
-    const uint32_t first = grp * G;
-    const uint32_t gr = rows - first < G ? rows - first : G;
-    return bidx * per + (first + w % gr) * cols + w / gr;
-}
-
 __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    const uint32_t seq = xcd_remap(blockIdx.x, g.n_tiles, g.num_xcds);
-    const uint32_t slot = seq >= g.slot_first[1] ? 1u : 0u;
-    const uint32_t t = g.slot_first[slot] + grouped_index(seq - g.slot_first[slot], g.slot_rows[slot], g.slot_cols[slot], g.slot_group[slot]);
+    LaunchOrder o;
+    o.n[0] = g.slot_first[1] - g.slot_first[0];
+    o.n[1] = g.n_tiles - g.slot_first[1];
+    o.first[0] = g.slot_first[0]; o.first[1] = g.slot_first[1];
+    o.rows[0] = g.slot_rows[0]; o.rows[1] = g.slot_rows[1];
+    o.cols[0] = g.slot_cols[0]; o.cols[1] = g.slot_cols[1];
+    o.group[0] = g.slot_group[0]; o.group[1] = g.slot_group[1];
+    o.nx = g.num_xcds;
+    uint32_t slot;
+    const uint32_t t = tile_of_workgroup(o, blockIdx.x, &slot);
     const TileDesc d = g.descs[t];
-    const uint32_t code = g.slot_code[slot];
+    const uint32_t code = slot ? g.slot_code[1] : g.slot_code[0];
+    const uint32_t stages = slot ? g.slot_stages[1] : g.slot_stages[0];
     switch (code) {
 #ifdef FT_GENERIC
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
@@ -69,7 +54,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
-            UKernelFast<FT_DT, WM, WN, GM, GN>::run(g, d, smem, g.slot_stages[slot]); \
+            UKernelFast<FT_DT, WM, WN, GM, GN>::run(g, d, smem, stages); \
         break;
 #endif
         FT_FAMILY(FT_X)
@@ -78,7 +63,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #define FT_X(CODE, TM, TN, TWIN)                                                \
     case CODE:                                                                  \
         if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \
-            UKernelSplitK<FT_DT, TM, TN>::run(g, d, smem, g.slot_stages[slot]);  \
+            UKernelSplitK<FT_DT, TM, TN>::run(g, d, smem, stages);  \
         break;
         FT_FAMILY_SPLITK(FT_X)
 #undef FT_X

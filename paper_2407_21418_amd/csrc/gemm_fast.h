@@ -160,9 +160,9 @@ struct UKernelFast {
                     const int h = (int)((a_pq[i] >> 16) + r) - (int)g.cpad;
                     const int w = (int)((a_pq[i] & 0xffffu) + sx) - (int)g.cpad;
                     const bool ok = h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W;
-                    const void *p = ok ? reinterpret_cast<const char *>(Ab) + goff_a[i] +
-                                             (uint64_t)(((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch0) * 2
-                                       : reinterpret_cast<const char *>(ft_zero_page);
+                    // 32-bit byte offset first, one 64-bit add last (keeps the lane offsets in one register each)
+                    const uint32_t off = goff_a[i] + (((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch0) * 2;
+                    const void *p = ok ? static_cast<const void *>(abase + off) : static_cast<const void *>(ft_zero_page);
                     if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
                 }
             }

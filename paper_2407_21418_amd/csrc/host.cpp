@@ -8,6 +8,7 @@
 
 #include "family.h"
 #include "ft_internal.h"
+#include "tile_order.h"
 
 namespace {
 
@@ -696,6 +697,27 @@ ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, u
     if (!plan || !descs || !n) return FT_ERR_INVALID_ARG;
     *descs = plan->descs.empty() ? nullptr : plan->descs.data();
     *n = plan->descs.size();
+    return FT_OK;
+}
+
+ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t cap, uint64_t *n) {
+    if (!plan || !n || (cap && !order)) return FT_ERR_INVALID_ARG;
+    const uint64_t total = plan->descs.size();
+    *n = total;
+    ftk::LaunchOrder o;
+    o.n[0] = plan->slot_first[1] - plan->slot_first[0];
+    o.n[1] = (uint32_t)total - plan->slot_first[1];
+    for (int i = 0; i < 2; ++i) {
+        o.first[i] = plan->slot_first[i];
+        o.rows[i] = plan->slot_rows[i];
+        o.cols[i] = plan->slot_cols[i];
+        o.group[i] = plan->slot_group[i];
+    }
+    o.nx = plan->num_xcds;
+    for (uint64_t b = 0; b < total && b < cap; ++b) {
+        uint32_t slot;
+        order[b] = ftk::tile_of_workgroup(o, (uint32_t)b, &slot);
+    }
     return FT_OK;
 }
 

@@ -1,0 +1,73 @@
+// Workgroup -> tile descriptor mapping of one launch (host and device).
+//
+// Workgroups are handed to the XCDs round-robin (workgroup b runs on XCD b % nx).  Each XCD gets
+// one contiguous slice of EVERY constituent's block of the descriptor table: tiles that share an
+// A row panel or a B column panel meet in the same per-XCD L2, and the large tiles of a
+// two-uKernel program are spread over all XCDs instead of filling the first few (the small tiles of
+// its tail would otherwise leave the other XCDs nearly idle).  Inside an XCD the first constituent
+// (the larger tiles) is started first.
+//
+// Inside a constituent's tile grid (rows x cols per batch entry, row-major in the table) the slice
+// is walked in groups of G tile rows, column by column, so the tiles an XCD runs at once form a
+// compact 2-D block that touches few A panels AND few B panels.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIP__)      // compiled as HIP source: callable from kernels and from the host
+#define FT_HD __attribute__((host)) __attribute__((device)) inline __attribute__((always_inline))
+#else
+#define FT_HD inline
+#endif
+
+namespace ftk {
+
+struct LaunchOrder {
+    uint32_t n[2];        // tiles of each constituent (n[1] = 0 for a single-uKernel program)
+    uint32_t first[2];    // first descriptor of each constituent's block
+    uint32_t rows[2], cols[2], group[2];
+    uint32_t nx;          // XCDs
+};
+
+FT_HD uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols, uint32_t G) {
+    if (rows < 2 || cols < 2 || G < 2) return u;
+    const uint32_t per = rows * cols;
+    const uint32_t bidx = u / per, v = u % per;
+    const uint32_t grp = v / (G * cols), w = v % (G * cols);
+    const uint32_t first = grp * G;
+    const uint32_t gr = rows - first < G ? rows - first : G;
+    return bidx * per + (first + w % gr) * cols + w / gr;
+}
+
+// descriptor index of workgroup b; *slot receives the constituent (0 or 1)
+FT_HD uint32_t tile_of_workgroup(const LaunchOrder &o, uint32_t b, uint32_t *slot) {
+    const uint32_t nx = o.nx;
+    const uint32_t x = b % nx, j = b / nx;
+    const uint32_t q0 = o.n[0] / nx, r0 = o.n[0] % nx;
+    const uint32_t q1 = o.n[1] / nx, r1 = o.n[1] % nx;
+    // constituent 0: XCD x takes q0 tiles, the first r0 XCDs one more
+    const uint32_t c0 = q0 + (x < r0 ? 1u : 0u);
+    uint32_t s, idx;
+    if (j < c0) {
+        s = 0;
+        idx = x * q0 + (x < r0 ? x : r0) + j;
+    } else {
+        // constituent 1: the r1 extra tiles go to XCDs r0, r0+1, ... (mod nx), so every XCD ends up
+        // with exactly the number of workgroups the round-robin hands it
+        s = 1;
+        uint32_t before;                       // XCDs below x that hold an extra tile of constituent 1
+        if (r0 + r1 <= nx) {
+            before = x <= r0 ? 0u : (x - r0 < r1 ? x - r0 : r1);
+        } else {
+            const uint32_t wrap = r0 + r1 - nx;
+            before = (x < wrap ? x : wrap) + (x > r0 ? x - r0 : 0u);
+        }
+        idx = x * q1 + before + (j - c0);
+    }
+    *slot = s;
+    // selects, not indexed loads: the fields stay in (scalar) registers on the device
+    const uint32_t first = s ? o.first[1] : o.first[0], rows = s ? o.rows[1] : o.rows[0];
+    const uint32_t cols = s ? o.cols[1] : o.cols[0], group = s ? o.group[1] : o.group[0];
+    return first + grouped_index(idx, rows, cols, group);
+}
+
+}  // namespace ftk

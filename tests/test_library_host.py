@@ -192,6 +192,48 @@ def test_forced_program_mode():
     assert e.value.status == ft.FT_ERR_NO_COVER
 
 
+def test_launch_order_is_a_balanced_permutation():
+    """Every workgroup takes a distinct descriptor; each XCD (workgroup b -> XCD b % 8) gets an
+    equal share (+-1) of EACH constituent's tiles, as contiguous slices of the table."""
+    import struct
+    cases = [("dense3072", 1232, None), ("dense3072", 1600, None), ("dense768", 77, None), ("qk", None, (8, 77, 77)),
+             ("conv", None, None), ("llm11008", 300, None)]
+    for name, m, bmm in cases:
+        op = OPS[name]
+        lop = to_lib_op(op)
+        s = ft.ft_ukernels_derive(lop)
+        if name == "conv":
+            shape = ft.ft_shape(batch=2, img_h=37, img_w=37)
+        elif bmm:
+            shape = ft.ft_shape(batch=bmm[0], m=bmm[1], n=bmm[2])
+        else:
+            shape = ft.ft_shape(m=m)
+        for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+            pl = ft.ft_plan_create(lop, s, shape, mode | HOST)
+            st = ft.ft_plan_stats_get(pl)
+            order = ft.ft_plan_launch_order(pl)
+            assert sorted(order) == list(range(st.n_tiles)), (name, mode)
+            raw = ft.ft_plan_descriptors(pl)
+            uk_of = [struct.unpack_from("<IIIIHHI", raw, 24 * i)[0] for i in range(st.n_tiles)]
+            ids = sorted(set(uk_of))
+            for uk in ids:
+                per_xcd = [sum(1 for b, t in enumerate(order) if b % 8 == x and uk_of[t] == uk) for x in range(8)]
+                assert max(per_xcd) - min(per_xcd) <= 1, (name, mode, uk, per_xcd)
+                for x in range(8):
+                    mine = sorted(t for b, t in enumerate(order) if b % 8 == x and uk_of[t] == uk)
+                    # a slice of the constituent's block: walked in 2-D groups, so not sorted, but
+                    # its tiles are exactly a contiguous run of the grouped sequence -> same count
+                    assert len(mine) == per_xcd[x]
+            # the larger constituent is started first inside every XCD
+            if len(ids) == 2:
+                first_uk = uk_of[0]
+                for x in range(8):
+                    seq = [uk_of[t] for b, t in enumerate(order) if b % 8 == x]
+                    if first_uk in seq and seq.count(first_uk) < len(seq):
+                        last_first = max(i for i, u in enumerate(seq) if u == first_uk)
+                        assert all(u == first_uk for u in seq[:last_first + 1]), (name, x, seq)
+
+
 def test_error_codes():
     lop = to_lib_op(OPS["dense768"])
     s = ft.ft_ukernels_derive(lop)
