@@ -65,6 +65,8 @@ typedef struct ft_hw_model {
     uint32_t bw_global_bytes_per_clk_per_cu; /* bw_G of Eq. 7: L2 -> CU path (64)            */
     uint32_t bw_lds_bytes_per_clk_per_cu;    /* bw_S of Eq. 7 (256, measured 227..256)       */
     uint32_t ktile_latency_clk;              /* latency of one k-tile step of the k loop (400)*/
+    uint32_t solo_copy_exposed_pct;          /* share of the global->LDS copy time a workgroup
+                                                alone on its CU cannot hide behind MFMA (50)  */
     uint32_t hbm_gbytes_per_s;               /* 8000; used for rooflines only                */
     uint32_t num_xcds;                       /* 8                                            */
 } ft_hw_model;
@@ -143,7 +145,8 @@ typedef struct ft_ukernel_info {
     uint32_t regs;                 /* acc_regs + RestRegs                                    */
     uint32_t max_wg_per_cu;        /* resident workgroups per CU allowed by LDS and registers*/
     uint32_t reg_budget;           /* registers per lane granted to the body: 128, 256 or 512*/
-    uint64_t cmr_q20;              /* compute_eff (Eq. 6), floor(x * 2^20)                   */
+    uint64_t cmr_q20;              /* compute_eff (Eq. 6) alone on its CU, floor(x * 2^20)   */
+    uint64_t cmr_shared_q20;       /* compute_eff when two or more workgroups share the CU   */
 } ft_ukernel_info;
 
 typedef struct ft_ukset ft_ukset;

@@ -37,8 +37,8 @@ def default_hw():
     return dict(num_cus=256, simds_per_cu=4, wave_size=64, regs_per_lane=512,
                 max_waves_per_simd=8, lds_bytes_per_cu=163840, clock_mhz=2400,
                 mfma_flops_per_clk_per_cu=4096, bw_global_bytes_per_clk_per_cu=64,
-                bw_lds_bytes_per_clk_per_cu=256, ktile_latency_clk=400, hbm_gbytes_per_s=8000,
-                num_xcds=8)
+                bw_lds_bytes_per_clk_per_cu=256, ktile_latency_clk=400, solo_copy_exposed_pct=50,
+                hbm_gbytes_per_s=8000, num_xcds=8)
 
 
 def default_tuning():
@@ -160,7 +160,8 @@ class UKernel:
     regs: int
     reg_budget: int  # register allocation of the kernel the body is compiled into
     max_wg_per_cu: int
-    cmr_q: int
+    cmr_q: int       # compute_eff alone on its CU, floor(x * 2^20)
+    cmr2_q: int      # compute_eff when two or more workgroups share the CU
     id: int = -1
 
 
@@ -216,27 +217,35 @@ MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
 
 
-def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64):
-    """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem.  K_mem, the memory access latency of the uKernel,
-    is the larger of the global and the shared (LDS) transfer time plus, on gfx950, the
-    synchronisation latency of the k loop: ktile_latency_clk per k-tile a wave has to walk
-    through (ceil(K/tk) tiles, shared among the gk waves of a split-k grid).
+def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1):
+    """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, with K_mem read on gfx950 as the time the
+    uKernel's k loop needs, so the ratio is the fraction of that time the MFMA pipes are busy.
+    t_c = FLOPs / FLOPS, t_g = global bytes / bw_G, t_s = LDS bytes / bw_S (Eq. 7's data terms),
+    t_l = ktile_latency_clk per k-tile a wave walks through (ceil(K/tk) tiles, shared among
+    the gk waves of a split-k grid).
+      * residents >= 2 (workgroups sharing a CU, Alg. 1's block.bound): a SIMD holds several
+        waves, copy, LDS and MFMA phases of different waves overlap:
+            K_mem = max(t_c, t_g, t_s) + t_l / residents
+      * residents == 1: the one wave of a SIMD issues its global->LDS copies and its MFMAs
+        itself; a fraction solo_copy_exposed_pct of the copy time is not hidden:
+            K_mem = t_c + exposed * t_g + t_l
     Returns (numerator, denominator) of the exact ratio."""
+    F, G, S = hw["mfma_flops_per_clk_per_cu"], hw["bw_global_bytes_per_clk_per_cu"], hw["bw_lds_bytes_per_clk_per_cu"]
     flops = 2 * tm * tn * k_ref
-    data_r = (tm + tn) * k_ref * ELT
-    data_w = tm * tn * 4
-    data_tw = data_r
-    data_tr = k_ref * ELT * (tm * gn + tn * gm)
-    bw_g, bw_s = hw["bw_global_bytes_per_clk_per_cu"], hw["bw_lds_bytes_per_clk_per_cu"]
-    g_num, g_den = data_r + data_w, bw_g
-    s_num, s_den = data_tw + data_tr, bw_s
-    if g_num * s_den >= s_num * g_den:
-        mem_num, mem_den = g_num, g_den
-    else:
-        mem_num, mem_den = s_num, s_den
-    # (flops / FLOPS) / (mem_num / mem_den + lat * nk / gk)
-    lat_nk = hw["ktile_latency_clk"] * ceil_div(k_ref, tk)
-    return flops * mem_den * gk, hw["mfma_flops_per_clk_per_cu"] * (mem_num * gk + lat_nk * mem_den)
+    gbytes = (tm + tn) * k_ref * ELT + tm * tn * 4            # data_r + data_w
+    sbytes = (tm + tn) * k_ref * ELT + k_ref * ELT * (tm * gn + tn * gm)   # data_tw + data_tr
+    nk = ceil_div(k_ref, tk)
+    r = residents if residents >= 2 else 1
+    ed = 100
+    # everything over the common denominator F * G * S * gk * r * ed
+    c = flops * G * S * gk * r * ed
+    lt = hw["ktile_latency_clk"] * nk * F * G * S * ed
+    if r >= 2:
+        g = gbytes * F * S * gk * r * ed
+        s = sbytes * F * G * gk * r * ed
+        return c, max(c, g, s) + lt
+    g = gbytes * F * S * gk * hw["solo_copy_exposed_pct"]
+    return c, c + g + lt
 
 
 def reg_budget(regs, hw):
@@ -338,8 +347,9 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     continue                                        # Eq. 6
                 cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
                           hw["max_waves_per_simd"])
+                cn2, cd2 = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, residents=2)
                 cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, gk, mfma, stages, lds, acc, regs,
-                                    budget, cap, (cn << Q) // cd))
+                                    budget, cap, (cn << Q) // cd, (cn2 << Q) // cd2))
                 kept.append(passes_workload(tm, tn, shapes, hw, t))
     if any(kept):
         cand = [u for u, k in zip(cand, kept) if k]
@@ -472,32 +482,48 @@ def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q):
     p.pad_q = (pad[0] << Q) // pad[1]
     p.cross = cross_pick(pad, occ, t)
     p.saturated = T >= t["zeta"] * hw["num_cus"]                 # Eq. 5
-    # compute_eff is unbounded, the other two terms lie in [0, 1]: normalise by the set's
-    # best; a two-uKernel program takes the average of its constituents (Sec. 5.2)
+    # compute_eff is normalised by the set's best; a two-uKernel program takes the average of
+    # its constituents (Sec. 5.2).  Each constituent contributes the value cached for the number
+    # of workgroups that share a CU on this shape: min(its capacity, block.bound)
     acc = 0
     for uid, _ in parts:
-        acc += (min(uks[uid].cmr_q, cap_q) << Q) // cap_q
+        acc += (min(cmr_at(uks[uid], p.block_bound), cap_q) << Q) // cap_q
     p.cmr_q = acc // len(parts)
     if t.get("sia_form", SIA_LINEAR) == SIA_LINEAR:
         p.sia_q = t["c0"] * p.cmr_q + t["c1"] * p.pad_q + t["c2"] * p.occ_q   # Eq. 1 as printed
     else:
-        p.sia_q = sia_product(p.parts, uks, batch, M, N, tau, hw, t, cap_q)
+        p.sia_q = sia_product(p.parts, uks, batch, M, N, tau, hw, t, cap_q, p.block_bound)
     return p
 
 
-def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q):
-    """Eq. 1 in its multiplicative (log-domain) form, evaluated per uKernel as Sec. 5.2 words it
-    ("cached in the data structure of each uKernel ... for a program composed of two uKernels we
-    take their average"): each constituent K gets CMR^c0 * Pad^c1 * Occ^c2 from its own
-    sub-workload -- the rows (columns) it covers, its own tile count -- and the program score
-    is the mean.  A weighted sum of the logarithms of the three metrics ranks single-uKernel
-    programs identically; the product is what a throughput estimate looks like (fraction of
-    cores busy x fraction of useful work x per-core efficiency).  Fixed point: every multiply is
-    floor(x * y / 2^20)."""
+def cmr_cap(uks):
+    """Normaliser of the CMR term: the best compute_eff cached anywhere in the set."""
+    return max(max(u.cmr_q, u.cmr2_q) for u in uks)
+
+
+def cmr_at(u, block_bound):
+    """The cached compute_eff of uKernel u when block_bound workgroups per CU are wanted."""
+    return u.cmr2_q if min(u.max_wg_per_cu, block_bound) >= 2 else u.cmr_q
+
+
+def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q, block_bound):
+    """Eq. 1 in its multiplicative (log-domain) form, evaluated per uKernel from the metrics
+    cached in each uKernel's data structure (Sec. 5.2): each constituent K gets
+    CMR^c0 * Pad^c1 * Occ^c2 from its own sub-workload -- the rows (columns) it covers, its own
+    tile count.  The product is what a throughput estimate looks like (fraction of cores busy x
+    fraction of useful work x per-core efficiency); a weighted sum of the logarithms of the
+    three metrics ranks single-uKernel programs identically.  The paper averages the two
+    constituents of a program without saying how; here it is the harmonic mean weighted by the
+    useful output elements u_i each constituent produces,
+        score = (u_1 + u_2) / (u_1 / x_1 + u_2 / x_2),
+    i.e. total work over the time the constituents need at their own rates (an unweighted mean
+    lets a 16-row tail decide the fate of a program whose other constituent does 95 % of the
+    work; an arithmetic mean hides a slow constituent).  Fixed point: every multiply is
+    floor(x * y / 2^20); the mean is floor of the exact ratio of the q20 values."""
     H = M if tau == 0 else N
     W = N if tau == 0 else M
     Wp = ceil_by(W, GRANULE)
-    off, total = 0, 0
+    off, terms = 0, []
     for uid, cnt in parts_sorted:                       # placement order along tau
         u = uks[uid]
         e = _ext(u, tau)
@@ -506,7 +532,7 @@ def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q):
         useful = max(0, min(H - off, cnt * e)) * W
         area = cnt * across * u.tm * u.tn
         off += cnt * e
-        cmr_q = (min(u.cmr_q, cap_q) << Q) // cap_q
+        cmr_q = (min(cmr_at(u, block_bound), cap_q) << Q) // cap_q
         pad_q = (useful << Q) // area
         on, od = occ_fraction(T, hw["num_cus"])
         occ_q = (on << Q) // od
@@ -514,8 +540,13 @@ def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q):
         for q, c in ((cmr_q, t["c0"]), (pad_q, t["c1"]), (occ_q, t["c2"])):
             for _ in range(c):
                 x = (x * q) >> Q
-        total += x
-    return total // len(parts_sorted)
+        terms.append((useful, x))
+    if any(x == 0 for _, x in terms):
+        return 0
+    if len(terms) == 1:
+        return terms[0][1]
+    (u1, x1), (u2, x2) = terms
+    return ((u1 + u2) * x1 * x2) // (u1 * x2 + u2 * x1)
 
 
 def emit(parts, uks, batch, M, N, tau):
@@ -557,7 +588,7 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
     pl = Plan(batch, M, N, K, tau, None, useful=batch * M * N)
     if batch == 0 or M == 0 or N == 0:
         return pl
-    cap_q = max(u.cmr_q for u in uks)
+    cap_q = cmr_cap(uks)
     if mode == PLAN_PAD_BASELINE:
         u = uks[0]
         Hp = ceil_by(M if tau == 0 else N, _ext(u, tau))

@@ -40,7 +40,7 @@ class ft_hw_model(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "num_cus", "simds_per_cu", "wave_size", "regs_per_lane", "max_waves_per_simd",
         "lds_bytes_per_cu", "clock_mhz", "mfma_flops_per_clk_per_cu", "bw_global_bytes_per_clk_per_cu",
-        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "hbm_gbytes_per_s", "num_xcds")]
+        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds")]
 
 
 class ft_tuning(_S):
@@ -58,7 +58,7 @@ class ft_op_desc(_S):
 class ft_ukernel_info(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "id", "tm", "tn", "tk", "wm", "wn", "gm", "gn", "gk", "mfma", "stages", "lds_bytes",
-        "acc_regs", "regs", "max_wg_per_cu", "reg_budget")] + [("cmr_q20", u64)]
+        "acc_regs", "regs", "max_wg_per_cu", "reg_budget")] + [("cmr_q20", u64), ("cmr_shared_q20", u64)]
 
 
 class ft_shape(_S):

@@ -35,6 +35,7 @@ void hw_defaults(ft_hw_model *h) {
     h->bw_global_bytes_per_clk_per_cu = 64;
     h->bw_lds_bytes_per_clk_per_cu = 256;
     h->ktile_latency_clk = 400;
+    h->solo_copy_exposed_pct = 50;
     h->hbm_gbytes_per_s = 8000;
     h->num_xcds = 8;
 }
@@ -60,24 +61,34 @@ Gemm static_view(const ft_op_desc &d) {
     return {d.m, d.n, d.k};
 }
 
-// Eq. 6 / Eq. 7: compute_eff = (FLOPs / FLOPS) : K_mem as num/den, with K_mem = max(global time,
-// LDS time) + the synchronisation latency of the k loop (ktile_latency_clk per k-tile, the tiles
-// being shared among the gk waves of a split-k grid).
+// Eq. 6 / Eq. 7: compute_eff = (FLOPs / FLOPS) : K_mem as num/den.  K_mem is the time the k loop
+// needs, so the ratio is the share of that time the MFMA pipes are busy.  With t_c = FLOPs/FLOPS,
+// t_g = global bytes / bw_G, t_s = LDS bytes / bw_S and t_l = ktile_latency_clk per k-tile a wave
+// walks through (ceil(K/tk) tiles, shared among the gk waves of a split-k grid):
+//   residents >= 2 (workgroups sharing a CU): phases of different waves overlap,
+//       K_mem = max(t_c, t_g, t_s) + t_l / residents
+//   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
+//       K_mem = t_c + solo_copy_exposed_pct % of t_g + t_l
 void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk, uint32_t tk, uint64_t kref,
-                 const ft_hw_model &hw, u128 *num, u128 *den) {
-    u128 flops = (u128)2 * tm * tn * kref;
-    u128 data_r = (u128)(tm + tn) * kref * ELT;
-    u128 data_w = (u128)tm * tn * 4;
-    u128 data_tw = data_r;
-    u128 data_tr = (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
-    u128 g_num = data_r + data_w, g_den = hw.bw_global_bytes_per_clk_per_cu;
-    u128 s_num = data_tw + data_tr, s_den = hw.bw_lds_bytes_per_clk_per_cu;
-    u128 mem_num, mem_den;
-    if (g_num * s_den >= s_num * g_den) { mem_num = g_num; mem_den = g_den; }
-    else { mem_num = s_num; mem_den = s_den; }
-    u128 lat_nk = (u128)hw.ktile_latency_clk * ceil_div(kref, tk);
-    *num = flops * mem_den * gk;
-    *den = (u128)hw.mfma_flops_per_clk_per_cu * (mem_num * gk + lat_nk * mem_den);
+                 uint32_t residents, const ft_hw_model &hw, u128 *num, u128 *den) {
+    const u128 F = hw.mfma_flops_per_clk_per_cu, G = hw.bw_global_bytes_per_clk_per_cu, S = hw.bw_lds_bytes_per_clk_per_cu;
+    const u128 flops = (u128)2 * tm * tn * kref;
+    const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * 4;                        // data_r + data_w
+    const u128 sbytes = (u128)(tm + tn) * kref * ELT + (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
+    const u128 nk = ceil_div(kref, tk);
+    const u128 r = residents >= 2 ? residents : 1;
+    const u128 ed = 100;
+    // everything over the common denominator F * G * S * gk * r * ed
+    const u128 c = flops * G * S * gk * r * ed;
+    const u128 lt = (u128)hw.ktile_latency_clk * nk * F * G * S * ed;
+    *num = c;
+    if (r >= 2) {
+        const u128 g = gbytes * F * S * gk * r * ed;
+        const u128 s = sbytes * F * G * gk * r * ed;
+        *den = std::max(c, std::max(g, s)) + lt;
+    } else {
+        *den = c + gbytes * F * S * gk * hw.solo_copy_exposed_pct + lt;
+    }
 }
 
 // Shapes of the workload along one dynamic axis: both ends of the registered range and the
@@ -167,9 +178,14 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
     p.pad_q = (uint32_t)((pn << QBITS) / pd);
     p.cross = cross_pick(pn, pd, on, od, t);
     p.saturated = p.tiles >= (uint64_t)t.zeta * hw.num_cus;                         // Eq. 5
+    // each constituent contributes the compute_eff cached for the number of workgroups that share
+    // a CU on this shape: min(its capacity, block.bound)
+    auto cmr_at = [&](const ft_ukernel_info &u) -> uint64_t {
+        return std::min<uint32_t>(u.max_wg_per_cu, p.block_bound) >= 2 ? u.cmr_shared_q20 : u.cmr_q20;
+    };
     uint64_t acc = 0;
     for (uint32_t i = 0; i < p.nparts; ++i) {
-        uint64_t c = std::min<uint64_t>(set.uk[p.part[i].id].cmr_q20, set.cap_q);
+        uint64_t c = std::min<uint64_t>(cmr_at(set.uk[p.part[i].id]), set.cap_q);
         acc += (uint64_t)(((u128)c << QBITS) / set.cap_q);
     }
     p.cmr_q = (uint32_t)(acc / p.nparts);
@@ -177,9 +193,12 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
     if (t.sia_form == FT_SIA_LINEAR) {
         p.sia_q = (uint64_t)t.c0 * p.cmr_q + (uint64_t)t.c1 * p.pad_q + (uint64_t)t.c2 * p.occ_q;   // Eq. 1 as printed
     } else {
-        // multiplicative form, per uKernel on its own sub-workload, averaged (Sec. 5.2)
+        // multiplicative form, per uKernel on its own sub-workload; two constituents are combined
+        // by the harmonic mean weighted with the useful output elements of each (Sec. 5.2):
+        // total work over the time both need at their own rates
         const uint64_t H = tau == 0 ? M : N, W = tau == 0 ? N : M;
-        uint64_t off = 0, total = 0;
+        uint64_t off = 0;
+        u128 us[2] = {0, 0}, xs[2] = {0, 0};
         for (uint32_t i = 0; i < p.nparts; ++i) {                 // placement order along tau
             const ft_ukernel_info &u = set.uk[p.part[i].id];
             const uint64_t e = ext(u, tau), cnt = p.part[i].count;
@@ -189,7 +208,7 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
             const uint64_t len = H > off ? std::min<uint64_t>(H - off, span) : 0;
             const u128 useful = (u128)len * W, area_u = (u128)cnt * across * u.tm * u.tn;
             off += span;
-            const uint64_t cq = (uint64_t)(((u128)std::min<uint64_t>(u.cmr_q20, set.cap_q) << QBITS) / set.cap_q);
+            const uint64_t cq = (uint64_t)(((u128)std::min<uint64_t>(cmr_at(u), set.cap_q) << QBITS) / set.cap_q);
             const uint64_t pq = (uint64_t)((useful << QBITS) / area_u);
             const uint64_t oq = (uint64_t)(((u128)T << QBITS) / ceil_by(T, hw.num_cus));
             u128 x = (u128)1 << QBITS;
@@ -197,9 +216,12 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
             const uint32_t cs[3] = {t.c0, t.c1, t.c2};
             for (int k = 0; k < 3; ++k)
                 for (uint32_t r = 0; r < cs[k]; ++r) x = (x * qs[k]) >> QBITS;
-            total += (uint64_t)x;
+            us[i] = useful;
+            xs[i] = x;
         }
-        p.sia_q = total / p.nparts;
+        if (xs[0] == 0 || (p.nparts == 2 && xs[1] == 0)) p.sia_q = 0;
+        else if (p.nparts == 1) p.sia_q = (uint64_t)xs[0];
+        else p.sia_q = (uint64_t)(((us[0] + us[1]) * xs[0] * xs[1]) / (us[0] * xs[1] + us[1] * xs[0]));
     }
 }
 
@@ -446,7 +468,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 uint32_t lds = gk * stages * stage_bytes;
                 if (lds > h.lds_bytes_per_cu) continue;                  // mem.IsOverflow
                 u128 cn, cd;
-                compute_eff(tm, tn, gm, gn, gk, tk, kref, h, &cn, &cd);
+                compute_eff(tm, tn, gm, gn, gk, tk, kref, 1, h, &cn, &cd);
                 if (cn * t.psi_den < (u128)t.psi_num * cd) continue;     // Eq. 6
                 ft_ukernel_info u;
                 std::memset(&u, 0, sizeof(u));
@@ -457,6 +479,8 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 u.max_wg_per_cu = std::min(std::min(h.lds_bytes_per_cu / lds, h.regs_per_lane / budget),
                                            h.max_waves_per_simd);
                 u.cmr_q20 = (uint64_t)((cn << QBITS) / cd);
+                compute_eff(tm, tn, gm, gn, gk, tk, kref, 2, h, &cn, &cd);
+                u.cmr_shared_q20 = (uint64_t)((cn << QBITS) / cd);
                 set->uk.push_back(u);
                 kept.push_back(passes_workload(tm, tn, ms, ns, h, t) ? 1 : 0);
             }
@@ -480,7 +504,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
     set->cap_q = 0;
     for (size_t i = 0; i < set->uk.size(); ++i) {
         set->uk[i].id = (uint32_t)i;
-        set->cap_q = std::max(set->cap_q, set->uk[i].cmr_q20);
+        set->cap_q = std::max(set->cap_q, std::max(set->uk[i].cmr_q20, set->uk[i].cmr_shared_q20));
     }
     if (set->uk.empty()) {
         delete set;

@@ -54,9 +54,9 @@ def test_ukernel_table_matches_oracle(name):
     for i, w in enumerate(want):
         g = ft.ft_ukset_get(s, i)
         got = (g.id, g.tm, g.tn, g.tk, g.wm, g.wn, g.gm, g.gn, g.gk, g.mfma, g.stages, g.lds_bytes, g.acc_regs,
-               g.regs, g.reg_budget, g.max_wg_per_cu, g.cmr_q20)
+               g.regs, g.reg_budget, g.max_wg_per_cu, g.cmr_q20, g.cmr_shared_q20)
         assert got == (w.id, w.tm, w.tn, w.tk, w.wm, w.wn, w.gm, w.gn, w.gk, w.mfma, w.stages, w.lds_bytes,
-                       w.acc_regs, w.regs, w.reg_budget, w.max_wg_per_cu, w.cmr_q)
+                       w.acc_regs, w.regs, w.reg_budget, w.max_wg_per_cu, w.cmr_q, w.cmr2_q)
 
 
 def shapes_for(name):
@@ -119,7 +119,7 @@ def test_pool_scores_match_oracle(name):
     lop = to_lib_op(op)
     s = ft.ft_ukernels_derive(lop)
     hw, t = P.default_hw(), P.default_tuning()
-    cap = max(u.cmr_q for u in uks)
+    cap = P.cmr_cap(uks)
     for kw in shapes_for(name)[:10]:
         b, M, N, K = oracle_shape(op, kw)
         if b == 0 or M == 0 or N == 0:

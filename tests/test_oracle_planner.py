@@ -90,22 +90,31 @@ def test_sia_product_form_by_hand():
     uks = P.derive_ukernels(op)
     hw, t = P.default_hw(), P.default_tuning()
     assert t["sia_form"] == P.SIA_PRODUCT
-    cap = max(u.cmr_q for u in uks)
+    cap = max(max(u.cmr_q, u.cmr2_q) for u in uks)
+    assert cap == P.cmr_cap(uks)
     u = next(u for u in uks if (u.tm, u.tn, u.gk) == (128, 128, 1))
     p = P.evaluate([(u.id, 5)], uks, 1, 630, 3072, 0, hw, t, cap)          # H' = 640 = 5 * 128
-    T = 5 * 24
-    cmr = (min(u.cmr_q, cap) << 20) // cap
+    T = 5 * 24                                                              # 120 tiles <= 256 CUs:
+    assert p.block_bound == 1                                               # one workgroup per CU
+    cmr = (min(u.cmr_q, cap) << 20) // cap                                  # -> the solo value
     pad = ((630 * 3072) << 20) // (T * 128 * 128)
     occ = (T << 20) // 256
     assert p.sia_q == ((((cmr * pad) >> 20) * occ) >> 20)
-    # two uKernels: mean of the two per-uKernel products, each on its own rows
+    # two uKernels: harmonic mean of the two per-uKernel products, each on its own rows,
+    # weighted by the useful elements each produces (work / summed time);
+    # 96 + 384 tiles > 256 CUs: block.bound = 2, and both uKernels can share a CU
+    # (capacity >= 2), so both take the shared-CU value
     v = next(x for x in uks if (x.tm, x.tn, x.gk) == (16, 64, 1))
     p2 = P.evaluate([(u.id, 4), (v.id, 8)], uks, 1, 630, 3072, 0, hw, t, cap)   # 512 + 128 rows
-    s_u = ((((cmr * (1 << 20)) >> 20) * ((4 * 24 << 20) // 256)) >> 20)
-    cmr_v = (min(v.cmr_q, cap) << 20) // cap
+    assert p2.block_bound == 2 and u.max_wg_per_cu >= 2 and v.max_wg_per_cu >= 2
+    cmr_u2 = (min(u.cmr2_q, cap) << 20) // cap
+    s_u = ((((cmr_u2 * (1 << 20)) >> 20) * ((4 * 24 << 20) // 256)) >> 20)
+    cmr_v = (min(v.cmr2_q, cap) << 20) // cap
     pad_v = ((118 * 3072) << 20) // (8 * 48 * 16 * 64)
     s_v = ((((cmr_v * pad_v) >> 20) * ((8 * 48 << 20) // 512)) >> 20)
-    assert p2.sia_q == (s_u + s_v) // 2
+    u1, u2 = 512 * 3072, 118 * 3072
+    assert p2.sia_q == ((u1 + u2) * s_u * s_v) // (u1 * s_v + u2 * s_u)
+    assert abs(p2.sia_q - (u1 + u2) / (u1 / s_u + u2 / s_v)) < 1
     # the printed linear form is still available
     p3 = P.evaluate([(u.id, 5)], uks, 1, 630, 3072, 0, hw, dict(t, sia_form=P.SIA_LINEAR), cap)
     assert p3.sia_q == p3.cmr_q + p3.pad_q + p3.occ_q
@@ -165,18 +174,28 @@ def test_workload_filters_crosspick_and_eq5():
 
 def test_compute_eff_closed_form():
     hw = P.default_hw()
-    # 128x128 tile, 2x2 waves, K = 768: flops 2*128*128*768 at 4096 flop/clk = 6144 clk;
-    # global (256*768*2 + 128*128*4) / 64 = 7168 clk; LDS (393216 + 768*2*512) / 256 = 4608 clk;
-    # k-loop latency 400 clk x 12 k-tiles = 4800 clk  ->  K_mem = 7168 + 4800
+    # 128x128 tile, 2x2 waves, K = 768: t_c = 2*128*128*768 flop at 4096 flop/clk = 6144 clk;
+    # t_g = (256*768*2 + 128*128*4) B / 64 = 7168 clk; t_s = (393216 + 768*2*512) B / 256 = 4608 clk;
+    # k-loop latency 400 clk x 12 k-tiles = 4800 clk
+    #   alone on the CU:  K_mem = t_c + 50 % of t_g + latency = 6144 + 3584 + 4800
     n, d = P.compute_eff(128, 128, 2, 2, 768, hw)
-    assert n * (7168 + 4800) == d * 6144
+    assert n * (6144 + 3584 + 4800) == d * 6144
+    #   two workgroups share the CU:  K_mem = max(t_c, t_g, t_s) + latency / 2 = 7168 + 2400
+    n, d = P.compute_eff(128, 128, 2, 2, 768, hw, residents=2)
+    assert n * (7168 + 2400) == d * 6144
     # split-k grid: the four waves share the 12 k-tiles
     n4, d4 = P.compute_eff(32, 32, 1, 1, 768, hw, gk=4)
-    glob = (64 * 768 * 2 + 32 * 32 * 4) / 64
-    assert abs(n4 / d4 - (2 * 32 * 32 * 768 / 4096) / (glob + 400 * 12 / 4)) < 1e-12
-    # a bigger tile is more compute-intensive
+    t_c, t_g = 2 * 32 * 32 * 768 / 4096, (64 * 768 * 2 + 32 * 32 * 4) / 64
+    assert abs(n4 / d4 - t_c / (t_c + t_g / 2 + 400 * 12 / 4)) < 1e-12
+    n4, d4 = P.compute_eff(32, 32, 1, 1, 768, hw, gk=4, residents=3)
+    t_s = (64 * 768 * 2 + 768 * 2 * 64) / 256
+    assert abs(n4 / d4 - t_c / (max(t_c, t_g, t_s) + 400 * 12 / 4 / 3)) < 1e-12
+    # a bigger tile is more compute-intensive; the ratio is an efficiency, never above 1
+    n1, d1 = P.compute_eff(128, 128, 2, 2, 768, hw)
     n2, d2 = P.compute_eff(256, 256, 2, 2, 768, hw)
-    assert n2 * d > n * d2
+    assert n2 * d1 > n1 * d2 and n2 <= d2
+    assert P.compute_eff(256, 256, 2, 2, 1 << 20, dict(hw, ktile_latency_clk=0), residents=2)[0] == \
+           P.compute_eff(256, 256, 2, 2, 1 << 20, dict(hw, ktile_latency_clk=0), residents=2)[1]   # MFMA bound: 1
 
 
 def brute_decompositions(H, extents):
@@ -318,7 +337,7 @@ def test_sia_is_the_weighted_sum_and_top1_is_max():
     uks = P.derive_ukernels(op)
     hw, t = P.default_hw(), P.default_tuning()
     t2 = dict(t, c0=3, c1=5, c2=7, sia_form=P.SIA_LINEAR)
-    cap = max(u.cmr_q for u in uks)
+    cap = P.cmr_cap(uks)
     shape = (1, 528, 3072, 768)
     pool = [P.evaluate(p, uks, 1, 528, 3072, 0, hw, t2, cap)
             for p in P.build_pool([u.tm for u in uks], 528)]
