@@ -30,6 +30,11 @@ sys.path.insert(0, ROOT)
 MFMA_PEAK_TFLOPS = 2516.6      # dense fp16/bf16 MFMA, 256 CU x 4096 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 RING_BYTES = 600e6             # > 256 MB Infinity Cache + 8 x 4 MB L2
+# Bytes crossing the L2 <-> fabric boundary per launch (average over the cold launches of this
+# sweep), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
+# counters read for a plain 1 GiB copy (x2.0 and x1.0); see profiles/ft_dispatch_pmc.md.
+# Counters cannot be read from inside this process, so the figures are those of the committed profile.
+MEASURED_TRAFFIC_BYTES = {"ft_dispatch_dt0_c0": 17.98e6 + 2.94e6, "ft_dispatch_dt0_c1": 21.70e6 + 9.97e6}
 
 
 def geomean(xs):
@@ -90,6 +95,7 @@ def main():
     per_class_time = {}
     per_class_flops = {}
     per_class_launches = {}
+    per_class_bytes = {}
     for r in rows:
         M, N, K = r["M"], r["N"], r["K"]
         p = si.config1_problem(M, N, K)
@@ -126,6 +132,7 @@ def main():
         per_class_time[k] = per_class_time.get(k, 0.0) + ms_cold * args.steps
         per_class_flops[k] = per_class_flops.get(k, 0.0) + flops * args.steps
         per_class_launches[k] = per_class_launches.get(k, 0) + args.steps
+        per_class_bytes[k] = per_class_bytes.get(k, 0.0) + bytes_alg * args.steps
         del As, Bs, Cs
         torch.cuda.empty_cache()
 
@@ -165,7 +172,11 @@ def main():
                          "ms_per_step": round(sum(r["ms_base"] for r in rows), 5)} if "base" in variants else None,
         "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 5), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 5),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
+                     "traffic_note": "L2-miss read + write-back bytes per launch (rocprofv3 --pmc, copy-calibrated; "
+                                     "Infinity Cache hits included), algorithmic bytes per launch: %d" % round(
+                                         per_class_bytes[dom] / per_class_launches[dom]),
                      "avg_launch_us": round(1e3 * per_class_time[dom] / per_class_launches[dom], 3),
                      "launches": per_class_launches[dom],
                      "note": "achieved = useful flops of the launches that ran this kernel / their "
