@@ -315,7 +315,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     kept = []
     for wm, wn, mfma in wave_tiles():
         for gm, gn, gk in WAVE_GRIDS:
-            if gk > 1 and not (1024 <= wm * wn <= 4096):
+            if gk > 1 and not (256 <= wm * wn <= 4096):
                 continue
             for tk in TK_CHOICES:
                 tm, tn = gm * wm, gn * wn

@@ -105,11 +105,13 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
     // multiples of 8 elements (convolution: c_in a multiple of 64, c_out of 8); everything else
     // takes the general bodies.
     const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0);
-    const bool fast = a.is_conv ? (aligned && a.Cin % 64 == 0 && a.N % 8 == 0)
-                                : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
+    bool fast = a.is_conv ? (aligned && a.Cin % 64 == 0 && a.N % 8 == 0)
+                          : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
     if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
         a.slot_code[0] = (uint32_t)ft_general_code((int)a.slot_code[0]);
         a.slot_code[1] = (uint32_t)ft_general_code((int)a.slot_code[1]);
+        // the twins of the narrowest tiles exist in the general dispatcher only
+        if (ft_is_partial_code((int)a.slot_code[0]) || ft_is_partial_code((int)a.slot_code[1])) fast = false;
     }
     int rc = fast ? kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream)
                   : kLaunchGeneric[plan->op.dtype](&a, plan->st.lds_bytes, hip_stream);

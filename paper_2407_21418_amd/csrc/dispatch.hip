@@ -58,6 +58,9 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
         break;
 #endif
         FT_FAMILY(FT_X)
+#ifdef FT_GENERIC
+        FT_FAMILY_PARTIAL(FT_X)
+#endif
 #undef FT_X
 #ifndef FT_GENERIC
 #define FT_X(CODE, TM, TN, TWIN)                                                \

@@ -18,7 +18,13 @@
 // a quarter of the reduce axis.  twin = code of the standard-grid body with the same tile, used by
 // the general (unaligned / convolution) path, which has no split-k variant.
 #define FT_FAMILY_SPLITK(X)                                                              \
-    X(30, 16, 64, 0) X(31, 32, 32, 1) X(32, 32, 64, 4) X(33, 64, 32, 5) X(34, 64, 64, 10)
+    X(30, 16, 64, 0) X(31, 32, 32, 1) X(32, 32, 64, 4) X(33, 64, 32, 5) X(34, 64, 64, 10)   \
+    X(35, 16, 32, 37) X(36, 16, 16, 38)
+
+// Tiles smaller than four MFMA blocks have no four-wave standard grid; their twins for the general
+// path use fewer computing waves (the idle ones still help with the copies):
+// X(code, WM, WN, GM, GN) with GM*GN < 4.  Compiled into the general dispatcher only.
+#define FT_FAMILY_PARTIAL(X) X(37, 16, 16, 1, 2) X(38, 16, 16, 1, 1)
 
 #define FT_TK 64
 #define FT_NUM_CLASSES 3
@@ -38,6 +44,13 @@ static inline int ft_body_code(int wm, int wn, int gm, int gn, int gk) {
 #undef FT_X
     }
     return -1;
+}
+// bodies that exist in the general dispatcher only
+static inline int ft_is_partial_code(int code) {
+#define FT_X(c, WM, WN, GM, GN) if (code == c) return 1;
+    FT_FAMILY_PARTIAL(FT_X)
+#undef FT_X
+    return 0;
 }
 // body the general path runs for a given code (split-k codes map to their standard-grid twin)
 static inline int ft_general_code(int code) {

@@ -153,7 +153,8 @@ struct UKernelBody {
     static constexpr int KCH = TK / 8;                // chunks per A row
     static constexpr int NCH = TN / 8;                // chunks per B row
     static_assert(TK == 64, "A-tile swizzle assumes 128-byte rows");
-    static_assert(GM * GN == 4, "four waves per workgroup");
+    static_assert(GM * GN <= 4, "at most four computing waves per workgroup");
+    static constexpr bool PARTIAL = GM * GN < 4;      // waves >= GM*GN only copy
 
     using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
 
@@ -346,14 +347,15 @@ struct UKernelBody {
                     load_a((kt + 1) * TK, last);
                     load_b((kt + 1) * TK, last || !b_fast);
                 }
-                compute(kt & 1u);
+                if (!PARTIAL || wave < (uint32_t)(GM * GN)) compute(kt & 1u);
                 if (more) store_lds((kt + 1) & 1u);
                 __syncthreads();
             }
         }
 
         // ---- epilogue: fp32 store, predicated only for tiles on the edge of C --------------
-        store_acc<M16, BM, BN>(Cb, g.ldc, M, N, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
+        if (!PARTIAL || wave < (uint32_t)(GM * GN))
+            store_acc<M16, BM, BN>(Cb, g.ldc, M, N, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
 };
 

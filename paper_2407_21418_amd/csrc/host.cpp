@@ -445,7 +445,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
             for (auto &g : grids) {
                 uint32_t gm = g[0], gn = g[1], gk = g[2], tk = FT_TK;
                 uint32_t tm = gm * wm, tn = gn * wn;
-                if (gk > 1 && (wm * wn < 1024 || wm * wn > 4096)) continue;
+                if (gk > 1 && (wm * wn < 256 || wm * wn > 4096)) continue;
                 if (ft_body_code(wm, wn, gm, gn, gk) < 0) continue;      // no compiled body
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
