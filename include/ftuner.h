@@ -104,11 +104,16 @@ ft_status ft_tuning_default(ft_tuning *out);        /* out: host pointer */
  * ------------------------------------------------------------------------------------- */
 enum { FT_OP_MATMUL = 0, FT_OP_BMM = 1, FT_OP_CONV2D = 2 };
 enum { FT_F16 = 0, FT_BF16 = 1 };
+/* Output element type: fp32 (the default), or the accumulator rounded once, to nearest even, to
+ * the 16-bit type of the inputs.  Epilogue: none, or C[.., j] += bias[j] before that rounding
+ * (the fused Dense + bias-add of the paper's BERT evaluation, Sec. 6.2). */
+enum { FT_OUT_F32 = 0, FT_OUT_SAME = 1 };
+enum { FT_EPI_NONE = 0, FT_EPI_BIAS = 1 };
 
 typedef struct ft_op_desc {
     uint32_t struct_size;
     uint32_t kind;                 /* FT_OP_*                                                */
-    uint32_t dtype;                /* FT_F16 / FT_BF16 inputs; accumulation and C are fp32   */
+    uint32_t dtype;                /* FT_F16 / FT_BF16 inputs; accumulation is fp32          */
     /* GEMM view C[b,i,j] = sum_k A[b,i,k] B[b,k,j].  An extent > 0 is static; 0 means dynamic
      * with the inclusive range [lo, hi] below (lo may be 0: empty inputs are legal).  Matmul
      * and BMM use these directly (Matmul has batch 1; the BMM batch count is always a runtime
@@ -118,6 +123,8 @@ typedef struct ft_op_desc {
     /* Conv2d (NHWC input, RSCK weights, NHWC fp32 output): space axes (n,p,q,k), reduce axes
      * (r,s,c) (Fig. 7 caption).  GEMM view: M = n*P*Q, N = c_out, K = r*s*c_in.            */
     uint32_t c_in, c_out, r, s, stride, pad;
+    uint32_t out_dtype;            /* FT_OUT_*: element type of C                            */
+    uint32_t epilogue;             /* FT_EPI_*                                               */
 } ft_op_desc;
 
 typedef struct ft_op ft_op;
@@ -246,7 +253,7 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
 
 /* ---------------------------------------------------------------------------------------
  * (d) Launch: ONE kernel launch; workgroup i runs the uKernel body named by descriptor i.
- *   Matmul: A [M,K], B [K,N] row-major 16-bit; C [M,N] row-major fp32.
+ *   Matmul: A [M,K], B [K,N] row-major 16-bit; C [M,N] row-major fp32 (or 16-bit, see out_dtype).
  *   BMM:    A [batch,M,K], B [batch,K,N], C [batch,M,N], densely packed.
  *   Conv2d: A = X [n,H,W,c_in], B = W [r,s,c_in,c_out], C = Y [n,P,Q,c_out] fp32.
  * A, B, C: device pointers owned by the caller (A, B at least 2-byte aligned, C 4-byte
@@ -255,6 +262,15 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
  * nothing and does not synchronise.  An empty plan launches nothing.
  * ------------------------------------------------------------------------------------- */
 ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, void *hip_stream);
+
+/* The same launch for operators registered with an epilogue (Sec. 6.2: Dense + bias-add as one
+ * fused operator): C[.., j] = sum_k A B + bias[j].  bias: device pointer to N (= c_out for a
+ * convolution) fp32 values, 4-byte aligned, owned by the caller; must be non-NULL exactly when
+ * the operator has FT_EPI_BIAS (else FT_ERR_INVALID_ARG).  C has the operator's out_dtype
+ * (fp32, or the inputs' 16-bit type: 2-byte aligned, same row-major layout).  ft_launch is this
+ * call with bias = NULL. */
+ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
+                             void *hip_stream);
 
 /* Timing helper for benchmarks: launches the plan `iters` times back to back on hip_stream,
  * launch i using buffer set i % n_sets (A, B, C: host arrays of n_sets device pointers; rotating

@@ -183,6 +183,7 @@ class Op:
     s: int = 0
     stride: int = 1
     pad: int = 0
+    out_bytes: int = 4   # bytes per output element: fp32, or 2 when C has the inputs' 16-bit type
 
     def gemm_static(self):
         if self.kind == OP_CONV2D:
@@ -217,7 +218,7 @@ MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
 
 
-def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1):
+def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4):
     """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, with K_mem read on gfx950 as the time the
     uKernel's k loop needs, so the ratio is the fraction of that time the MFMA pipes are busy.
     t_c = FLOPs / FLOPS, t_g = global bytes / bw_G, t_s = LDS bytes / bw_S (Eq. 7's data terms),
@@ -232,7 +233,7 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1):
     Returns (numerator, denominator) of the exact ratio."""
     F, G, S = hw["mfma_flops_per_clk_per_cu"], hw["bw_global_bytes_per_clk_per_cu"], hw["bw_lds_bytes_per_clk_per_cu"]
     flops = 2 * tm * tn * k_ref
-    gbytes = (tm + tn) * k_ref * ELT + tm * tn * 4            # data_r + data_w
+    gbytes = (tm + tn) * k_ref * ELT + tm * tn * out_bytes    # data_r + data_w
     sbytes = (tm + tn) * k_ref * ELT + k_ref * ELT * (tm * gn + tn * gm)   # data_tw + data_tr
     nk = ceil_div(k_ref, tk)
     r = residents if residents >= 2 else 1
@@ -342,12 +343,12 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 if regs * waves_per_simd > hw["regs_per_lane"]:
                     continue                                        # Eq. 4, block.bound = 1
                 budget = reg_budget(regs, hw)
-                cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk)
+                cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, out_bytes=op.out_bytes)
                 if cn * t["psi_den"] < t["psi_num"] * cd:
                     continue                                        # Eq. 6
                 cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
                           hw["max_waves_per_simd"])
-                cn2, cd2 = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, residents=2)
+                cn2, cd2 = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, residents=2, out_bytes=op.out_bytes)
                 cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, gk, mfma, stages, lds, acc, regs,
                                     budget, cap, (cn << Q) // cd, (cn2 << Q) // cd2))
                 kept.append(passes_workload(tm, tn, shapes, hw, t))

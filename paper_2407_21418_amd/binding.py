@@ -15,6 +15,8 @@ FT_ERR_INVALID_ARG, FT_ERR_UNSUPPORTED, FT_ERR_OUT_OF_RANGE = -1, -2, -3
 FT_ERR_NO_COVER, FT_ERR_HIP, FT_ERR_OOM = -4, -5, -6
 FT_OP_MATMUL, FT_OP_BMM, FT_OP_CONV2D = 0, 1, 2
 FT_F16, FT_BF16 = 0, 1
+FT_OUT_F32, FT_OUT_SAME = 0, 1
+FT_EPI_NONE, FT_EPI_BIAS = 0, 1
 FT_PLAN_PATCHWORK, FT_PLAN_PAD_BASELINE, FT_PLAN_FORCED, FT_PLAN_HOST_ONLY = 0, 1, 2, 16
 FT_SIA_LINEAR, FT_SIA_PRODUCT = 0, 1
 
@@ -52,7 +54,7 @@ class ft_tuning(_S):
 class ft_op_desc(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "kind", "dtype", "m", "n", "k", "m_lo", "m_hi", "n_lo", "n_hi", "k_lo", "k_hi",
-        "c_in", "c_out", "r", "s", "stride", "pad")]
+        "c_in", "c_out", "r", "s", "stride", "pad", "out_dtype", "epilogue")]
 
 
 class ft_ukernel_info(_S):
@@ -116,6 +118,7 @@ SYMBOLS = {
     "ft_plan_destroy": (None, [_P]),
     "ft_plan_pool": (C.c_int32, [_P, _P, C.POINTER(ft_shape), C.POINTER(ft_pool_entry), u32, C.POINTER(u32)]),
     "ft_launch": (C.c_int32, [_P, _P, _P, _P, _P]),
+    "ft_launch_epilogue": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
     "ft_launch_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
                                     C.POINTER(C.c_float)]),
     "ft_launch_timed_graph": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
@@ -270,6 +273,11 @@ def ft_plan_pool(op: Op, s: UkSet, shape: ft_shape):
 def ft_launch(p: Plan, A: int, B: int, Cptr: int, stream: int = 0):
     """A, B, Cptr: device addresses (e.g. torch.Tensor.data_ptr()); stream: hipStream_t value."""
     _check(lib().ft_launch(p.ptr, A, B, Cptr, stream), "ft_launch")
+
+
+def ft_launch_epilogue(p: Plan, A: int, B: int, Cptr: int, bias: int, stream: int = 0):
+    """As ft_launch, with bias = device address of N fp32 values (0 / None for none)."""
+    _check(lib().ft_launch_epilogue(p.ptr, A, B, Cptr, bias or None, stream), "ft_launch_epilogue")
 
 
 def ft_launch_timed(p: Plan, A, B, Cs, stream: int, iters: int, graph: bool = False) -> float:

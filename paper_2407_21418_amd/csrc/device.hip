@@ -26,12 +26,14 @@ ft_status hip_fail(hipError_t e) {
     return FT_ERR_HIP;
 }
 
-void fill_args(const ft_plan *p, const void *A, const void *B, void *C, ftk::KArgs *a) {
+void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const float *bias, ftk::KArgs *a) {
     std::memset(a, 0, sizeof(*a));
     const ft_plan_stats &s = p->st;
     a->A = static_cast<const uint16_t *>(A);
     a->B = static_cast<const uint16_t *>(B);
-    a->C = static_cast<float *>(C);
+    a->C = C;
+    a->bias = bias;
+    a->out_kind = p->op.out_dtype == FT_OUT_SAME ? (p->op.dtype == FT_F16 ? ftk::OUT_F16 : ftk::OUT_BF16) : ftk::OUT_F32;
     a->descs = static_cast<const ftk::TileDesc *>(p->d_descs);
     a->n_tiles = (uint32_t)s.n_tiles;
     a->M = s.m; a->N = s.n; a->K = s.k;
@@ -94,13 +96,19 @@ ft_status ft_hw_query(int32_t hip_device, ft_hw_model *out) {
 }
 
 ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, void *hip_stream) {
+    return ft_launch_epilogue(plan, A, B, C, nullptr, hip_stream);
+}
+
+ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
+                             void *hip_stream) {
     if (!plan) return FT_ERR_INVALID_ARG;
+    if ((plan->op.epilogue == FT_EPI_BIAS) != (bias != nullptr)) return FT_ERR_INVALID_ARG;
     if (plan->st.n_tiles == 0) return FT_OK;
     if (!A || !B || !C) return FT_ERR_INVALID_ARG;
     if (!plan->d_descs) return FT_ERR_INVALID_ARG;              // host-only plan
     if (plan->st.kernel_class >= FT_NUM_CLASSES || plan->op.dtype > 1) return FT_ERR_UNSUPPORTED;
     ftk::KArgs a;
-    fill_args(plan, A, B, C, &a);
+    fill_args(plan, A, B, C, bias, &a);
     // The LDS-DMA bodies need 16-byte aligned operands whose row pitches and reduce extent are
     // multiples of 8 elements (convolution: c_in a multiple of 64, c_out of 8); everything else
     // takes the general bodies.

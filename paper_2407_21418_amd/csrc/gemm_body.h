@@ -34,7 +34,9 @@ struct TileDesc {            // mirrors the 24-byte descriptor of the C ABI
 struct KArgs {
     const uint16_t *A;
     const uint16_t *B;
-    float *C;
+    void *C;                          // fp32, or the 16-bit input type (out_kind)
+    const float *bias;                // one fp32 per output column, or NULL
+    uint32_t out_kind;                // OUT_F32 / OUT_F16 / OUT_BF16
     const TileDesc *descs;
     uint32_t n_tiles;
     uint32_t M, N, K;                 // GEMM view
@@ -99,26 +101,56 @@ __device__ __forceinline__ uint4 ld_partial(const uint16_t *p, int nvalid) {
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// fp32 store of one wave's accumulator blocks (rows m0w.., columns n0w.. of C).
+// Output element kinds of the epilogue: fp32, or the accumulator (+ bias) rounded once, to nearest
+// even, to the 16-bit type of the inputs.
+enum { OUT_F32 = 0, OUT_F16 = 1, OUT_BF16 = 2 };
+
+template <int OUT> struct OutElem { using type = uint16_t; };
+template <> struct OutElem<OUT_F32> { using type = float; };
+
+template <int OUT> __device__ __forceinline__ typename OutElem<OUT>::type out_cvt(float v) {
+    if constexpr (OUT == OUT_F32) {
+        return v;
+    } else if constexpr (OUT == OUT_F16) {
+        return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));       // v_cvt_f16_f32: nearest even
+    } else {
+        uint32_t u = __builtin_bit_cast(uint32_t, v);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)0x7fc0u;      // NaN stays NaN
+        u += 0x7fffu + ((u >> 16) & 1u);                                     // nearest, ties to even
+        return (uint16_t)(u >> 16);
+    }
+}
+
+// Store of one wave's accumulator blocks (rows m0w.., columns n0w.. of C), optionally plus a
+// per-column bias, as fp32 or rounded to 16 bits.
 // 32x32 block: acc[4*i + j] -> row 8*i + 4*(lane/32) + j, column lane % 32
 // 16x16 block: acc[j]       -> row 4*(lane/16) + j,        column lane % 16
 // A wave tile that lies wholly inside C (uniform test) is stored without predication from one
 // per-lane pointer: one 64-bit add per row, the column blocks go into the instruction offsets.
-template <bool M16, int BM, int BN, typename Acc>
-__device__ __forceinline__ void store_acc(float *__restrict__ Cb, uint32_t ldc, uint32_t M, uint32_t N,
-                                          uint32_t m0w, uint32_t n0w, uint32_t lane, const Acc (&acc)[BM][BN]) {
+template <int OUT, bool INTERIOR_PATH, bool M16, int BM, int BN, typename Acc>
+__device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const float *__restrict__ bias, uint32_t ldc,
+                                             uint32_t M, uint32_t N, uint32_t m0w, uint32_t n0w, uint32_t lane,
+                                             const Acc (&acc)[BM][BN]) {
+    using T = typename OutElem<OUT>::type;
+    T *__restrict__ Cb = static_cast<T *>(Cv) + coff;
     constexpr int MB = M16 ? 16 : 32, NE = M16 ? 4 : 16;
     const uint32_t lrow = 4 * (lane / MB), lcol = lane % MB;
-    if (m0w + BM * MB <= M && n0w + BN * MB <= N) {
-        float *lp = Cb + ((uint64_t)(m0w + lrow) * ldc + n0w + lcol);
+    float bv[BN];
+#pragma unroll
+    for (int bj = 0; bj < BN; ++bj) {
+        const uint32_t col = n0w + bj * MB + lcol;
+        bv[bj] = (bias != nullptr && col < N) ? bias[col] : 0.f;
+    }
+    if (INTERIOR_PATH && m0w + BM * MB <= M && n0w + BN * MB <= N) {
+        T *lp = Cb + ((uint64_t)(m0w + lrow) * ldc + n0w + lcol);
 #pragma unroll
         for (int bi = 0; bi < BM; ++bi)
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
                 const uint32_t r = bi * MB + (M16 ? e : 8 * (e / 4) + (e % 4));
-                float *rp = lp + (uint64_t)r * ldc;
+                T *rp = lp + (uint64_t)r * ldc;
 #pragma unroll
-                for (int bj = 0; bj < BN; ++bj) rp[bj * MB] = acc[bi][bj][e];
+                for (int bj = 0; bj < BN; ++bj) rp[bj * MB] = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
             }
         return;
     }
@@ -131,9 +163,21 @@ __device__ __forceinline__ void store_acc(float *__restrict__ Cb, uint32_t ldc, 
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
                 const uint32_t row = m0w + bi * MB + lrow + (M16 ? e : 8 * (e / 4) + (e % 4));
-                if (row < M) Cb[(uint64_t)row * ldc + col] = acc[bi][bj][e];
+                if (row < M) Cb[(uint64_t)row * ldc + col] = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
             }
         }
+}
+
+// The output kind is uniform per launch: fp32 or the 16-bit type of the inputs (DT).
+// INTERIOR_PATH = false keeps only the predicated loops (general bodies: less code).
+template <int DT, bool INTERIOR_PATH, bool M16, int BM, int BN, typename Acc>
+__device__ __forceinline__ void store_acc(const KArgs &g, uint64_t coff, uint32_t m0w, uint32_t n0w, uint32_t lane,
+                                          const Acc (&acc)[BM][BN]) {
+    constexpr int OUT16 = DT == 0 ? OUT_F16 : OUT_BF16;
+    if (g.out_kind == OUT_F32)
+        store_acc_as<OUT_F32, INTERIOR_PATH, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+    else
+        store_acc_as<OUT16, INTERIOR_PATH, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
 }
 
 template <int DT, int WM, int WN, int GM, int GN, int TK>
@@ -166,7 +210,6 @@ struct UKernelBody {
         const uint32_t M = g.M, N = g.N, K = g.K;
         const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
         const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
-        float *__restrict__ Cb = g.C + (uint64_t)d.batch * g.strideC;
 
         // ---- per-thread copy assignments (loop invariant) -------------------------------
         // A copy: iteration i moves chunk (row0 + 32*i, kc); 32 rows keep the swizzle phase.
@@ -355,7 +398,7 @@ struct UKernelBody {
 
         // ---- epilogue: fp32 store, predicated only for tiles on the edge of C --------------
         if (!PARTIAL || wave < (uint32_t)(GM * GN))
-            store_acc<M16, BM, BN>(Cb, g.ldc, M, N, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
+            store_acc<DT, false, M16, BM, BN>(g, (uint64_t)d.batch * g.strideC, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
 };
 

@@ -84,7 +84,6 @@ struct UKernelFast {
         const uint32_t M = g.M, N = g.N, K = g.K;
         const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
         const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
-        float *__restrict__ Cb = g.C + (uint64_t)d.batch * g.strideC;
         const uint32_t nk = (K + TK - 1) / TK;
         uint32_t S = stages_in < 2 ? 2u : stages_in;
         if (S > (uint32_t)MAX_AHEAD + 2) S = MAX_AHEAD + 2;
@@ -232,7 +231,7 @@ struct UKernelFast {
         }
 
         // ---- epilogue ------------------------------------------------------------------------------
-        store_acc<M16, BM, BN>(Cb, g.ldc, M, N, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
+        store_acc<DT, true, M16, BM, BN>(g, (uint64_t)d.batch * g.strideC, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
 
     // LDS reads of the A and B fragments of k-step ks into fragment set buf.  Row offsets of the
@@ -351,7 +350,6 @@ struct UKernelSplitK {
         const uint32_t M = g.M, N = g.N, K = g.K;
         const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
         const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
-        float *__restrict__ Cb = g.C + (uint64_t)d.batch * g.strideC;
         const uint32_t nk = (K + TK - 1) / TK;
         const uint32_t nkw = nk > wave ? (nk - wave + 3) / 4 : 0;     // k-tiles of this wave
         uint32_t S = stages_in < 2 ? 2u : stages_in;
@@ -478,7 +476,12 @@ struct UKernelSplitK {
                         sum += reinterpret_cast<const float *>(smem + w * S * STAGE_BYTES)[r * 64 + lane];
                     uint32_t col = n0 + bj * MB + (lane % MB);
                     uint32_t row = m0 + bi * MB + (M16 ? 4 * (lane / 16) + e : 8 * (e / 4) + 4 * (lane / 32) + (e % 4));
-                    if (row < M && col < N) Cb[row * g.ldc + col] = sum;
+                    if (row < M && col < N) {
+                        if (g.bias != nullptr) sum += g.bias[col];
+                        const uint64_t o = (uint64_t)d.batch * g.strideC + (uint64_t)row * g.ldc + col;
+                        if (g.out_kind == OUT_F32) static_cast<float *>(g.C)[o] = sum;
+                        else static_cast<uint16_t *>(g.C)[o] = out_cvt<DT == 0 ? OUT_F16 : OUT_BF16>(sum);
+                    }
                 }
     }
 };

@@ -70,10 +70,10 @@ Gemm static_view(const ft_op_desc &d) {
 //   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
 //       K_mem = t_c + solo_copy_exposed_pct % of t_g + t_l
 void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk, uint32_t tk, uint64_t kref,
-                 uint32_t residents, const ft_hw_model &hw, u128 *num, u128 *den) {
+                 uint32_t residents, uint32_t out_bytes, const ft_hw_model &hw, u128 *num, u128 *den) {
     const u128 F = hw.mfma_flops_per_clk_per_cu, G = hw.bw_global_bytes_per_clk_per_cu, S = hw.bw_lds_bytes_per_clk_per_cu;
     const u128 flops = (u128)2 * tm * tn * kref;
-    const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * 4;                        // data_r + data_w
+    const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * out_bytes;                // data_r + data_w
     const u128 sbytes = (u128)(tm + tn) * kref * ELT + (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
     const u128 nk = ceil_div(kref, tk);
     const u128 r = residents >= 2 ? residents : 1;
@@ -383,6 +383,7 @@ ft_status ft_op_register(const ft_op_desc *desc, ft_op **out) {
     if (!desc || !out || desc->struct_size != sizeof(ft_op_desc)) return FT_ERR_INVALID_ARG;
     const ft_op_desc &d = *desc;
     if (d.kind > FT_OP_CONV2D || d.dtype > FT_BF16) return FT_ERR_INVALID_ARG;
+    if (d.out_dtype > FT_OUT_SAME || d.epilogue > FT_EPI_BIAS) return FT_ERR_INVALID_ARG;
     if (d.kind == FT_OP_CONV2D) {
         if (!d.c_in || !d.c_out || !d.r || !d.s || !d.stride) return FT_ERR_INVALID_ARG;
         if (d.m_lo > d.m_hi) return FT_ERR_INVALID_ARG;
@@ -468,7 +469,8 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 uint32_t lds = gk * stages * stage_bytes;
                 if (lds > h.lds_bytes_per_cu) continue;                  // mem.IsOverflow
                 u128 cn, cd;
-                compute_eff(tm, tn, gm, gn, gk, tk, kref, 1, h, &cn, &cd);
+                const uint32_t out_bytes = op->d.out_dtype == FT_OUT_SAME ? ELT : 4;
+                compute_eff(tm, tn, gm, gn, gk, tk, kref, 1, out_bytes, h, &cn, &cd);
                 if (cn * t.psi_den < (u128)t.psi_num * cd) continue;     // Eq. 6
                 ft_ukernel_info u;
                 std::memset(&u, 0, sizeof(u));
@@ -479,7 +481,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 u.max_wg_per_cu = std::min(std::min(h.lds_bytes_per_cu / lds, h.regs_per_lane / budget),
                                            h.max_waves_per_simd);
                 u.cmr_q20 = (uint64_t)((cn << QBITS) / cd);
-                compute_eff(tm, tn, gm, gn, gk, tk, kref, 2, h, &cn, &cd);
+                compute_eff(tm, tn, gm, gn, gk, tk, kref, 2, out_bytes, h, &cn, &cd);
                 u.cmr_shared_q20 = (uint64_t)((cn << QBITS) / cd);
                 set->uk.push_back(u);
                 kept.push_back(passes_workload(tm, tn, ms, ns, h, t) ? 1 : 0);

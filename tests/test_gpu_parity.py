@@ -10,7 +10,8 @@ import synth_inputs as si
 from oracle import contraction as oc
 from oracle import planner as P
 
-from gpu_util import REL_TOL, alloc_out, check, dev_bits, matmul_op, out_view, run, stream
+from gpu_util import REL_TOL, alloc_out, check, check_epilogue, dev_bits, matmul_op, out_view, run, run_epilogue, stream
+from oracle import epilogue as oe
 
 pytestmark = pytest.mark.gpu
 
@@ -300,3 +301,71 @@ def test_launch_on_a_side_stream_and_relaunch():
         ft.ft_launch(plan, A.data_ptr(), B.data_ptr(), buf.data_ptr() + 4 * 256, side.cuda_stream)
         side.synchronize()
         check(out_view(buf, 272 * 768), ref, refabs, "side stream")
+
+
+# ---- fused epilogue and 16-bit output (Dense + bias-add, Sec. 6.2) ----------------------------------
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+@pytest.mark.parametrize("out16,with_bias", [(False, True), (True, False), (True, True)])
+@pytest.mark.parametrize("M", [1, 77, 300, 1232])
+def test_matmul_bias_and_narrow_output(M, out16, with_bias, dtype):
+    """C = A B (+ bias), stored as fp32 or rounded once to the inputs' 16-bit type.  M = 1 and 77 run
+    split-k bodies, 300 a two-uKernel program, 1232 large tiles with an edge; N is not a multiple of
+    any tile width, so column-edge wave tiles take the predicated store."""
+    N, K = 760, 768
+    g = np.random.default_rng(1000 * M + 10 * dtype + 2 * out16 + with_bias)
+    A = si.normal_bits(g, (M, K), 1.0, dtype)
+    B = si.normal_bits(g, (K, N), 0.05, dtype)
+    bias = g.normal(0, 1.0, N).astype(np.float32) if with_bias else None
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dtype, n=N, k=K, m_lo=0, m_hi=8192,
+                                         out_dtype=ft.FT_OUT_SAME if out16 else ft.FT_OUT_F32,
+                                         epilogue=ft.FT_EPI_BIAS if with_bias else ft.FT_EPI_NONE))
+    s = ft.ft_ukernels_derive(op)
+    ref, refabs = oc.matmul(A, B, dtype, want_abs=True)
+    if with_bias:
+        ref = oe.add_bias(ref, bias)
+    for mode in (ft.FT_PLAN_PATCHWORK, ft.FT_PLAN_PAD_BASELINE):
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), mode)
+        got = run_epilogue(plan, A, B, M * N, bias=bias, out16=dtype if out16 else None)
+        check_epilogue(got, ref, refabs, bias, dtype if out16 else None, f"epilogue M={M} out16={out16} bias={with_bias} mode {mode}")
+
+
+def test_epilogue_argument_checks():
+    op_b = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=64, k=64, m_lo=0, m_hi=64, epilogue=ft.FT_EPI_BIAS))
+    op_n = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=64, k=64, m_lo=0, m_hi=64))
+    buf = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    ab = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
+    for op, bias_ptr in ((op_b, 0), (op_n, buf.data_ptr())):
+        plan = ft.ft_plan_create(op, ft.ft_ukernels_derive(op), ft.ft_shape(m=64))
+        with pytest.raises(ft.FtError) as e:
+            ft.ft_launch_epilogue(plan, ab.data_ptr(), ab.data_ptr(), buf.data_ptr(), bias_ptr, stream())
+        assert e.value.status == ft.FT_ERR_INVALID_ARG
+    with pytest.raises(ft.FtError):
+        ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=64, k=64, m_lo=0, m_hi=64, out_dtype=7))
+
+
+def test_conv_and_bmm_with_epilogue():
+    """Convolution (LDS-DMA gather path) with bias and fp16 output; BMM with odd L (general bodies)
+    and bf16 output."""
+    g = np.random.default_rng(91)
+    n, H, W, Cin, Cout = 2, 19, 23, 64, 128
+    X = si.normal_bits(g, (n, H, W, Cin), 1.0, si.F16)
+    Wt = si.normal_bits(g, (3, 3, Cin, Cout), 0.05, si.F16)
+    bias = g.normal(0, 0.5, Cout).astype(np.float32)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=ft.FT_F16, c_in=Cin, c_out=Cout, r=3, s=3, stride=1, pad=1,
+                                         m_lo=0, m_hi=1 << 20, out_dtype=ft.FT_OUT_SAME, epilogue=ft.FT_EPI_BIAS))
+    s = ft.ft_ukernels_derive(op)
+    ref, refabs = oc.conv2d_nhwc(X, Wt, si.F16, want_abs=True)
+    ref = oe.add_bias(ref, bias)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(img_n=n, img_h=H, img_w=W))
+    got = run_epilogue(plan, X, Wt, ref.size, bias=bias, out16=ft.FT_F16)
+    check_epilogue(got, ref, refabs, bias, ft.FT_F16, "conv + bias -> fp16")
+    nb, L = 5, 77
+    A = si.normal_bits(g, (nb, L, 64), 1.0, si.BF16)
+    B = si.normal_bits(g, (nb, 64, L), 1.0, si.BF16)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_BF16, k=64, m_lo=0, m_hi=512, n_lo=0, n_hi=512,
+                                         out_dtype=ft.FT_OUT_SAME))
+    s = ft.ft_ukernels_derive(op)
+    ref, refabs = oc.bmm(A, B, si.BF16, want_abs=True)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=L, n=L))
+    got = run_epilogue(plan, A, B, ref.size, out16=ft.FT_BF16)
+    check_epilogue(got, ref, refabs, None, ft.FT_BF16, "bmm -> bf16")

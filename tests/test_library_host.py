@@ -27,7 +27,8 @@ def to_lib_op(op: P.Op):
     d = ft.ft_op_desc(kind=op.kind, dtype=op.dtype, m=op.m, n=op.n, k=op.k,
                       m_lo=op.m_range[0], m_hi=op.m_range[1], n_lo=op.n_range[0], n_hi=op.n_range[1],
                       k_lo=op.k_range[0], k_hi=op.k_range[1], c_in=op.c_in, c_out=op.c_out, r=op.r, s=op.s,
-                      stride=op.stride, pad=op.pad)
+                      stride=op.stride, pad=op.pad,
+                      out_dtype=ft.FT_OUT_SAME if op.out_bytes == 2 else ft.FT_OUT_F32)
     return ft.ft_op_register(d)
 
 
@@ -41,6 +42,7 @@ OPS = {
     "onlyn": P.Op(P.OP_BMM, P.F16, m=64, k=64, n_range=(1, 512)),
     "conv": P.Op(P.OP_CONV2D, P.F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1, m_range=(0, 1 << 22)),
     "odd_static_n": P.Op(P.OP_MATMUL, P.F16, n=1000, k=100, m_range=(1, 4096)),
+    "dense3072_out16": P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(0, 8192), out_bytes=2),
 }
 
 
