@@ -48,9 +48,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="time one HIP-graph replay of the launches instead of direct launches")
-    ap.add_argument("--variants", default="cold,warm,base",
+    ap.add_argument("--variants", default="cold,warm,base,out16",
                     help="comma list of the timed variants: cold (headline), warm (one buffer set), base "
-                         "(pad-to-library plan); 'cold' alone is what the committed profiles run")
+                         "(pad-to-library plan), out16 (same sweep with C stored as fp16, reported beside the "
+                         "headline); 'cold' alone is what the committed profiles run")
     ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -69,7 +70,7 @@ def main():
     stream = side.cuda_stream
     use_graph = args.graph
     variants = set(args.variants.split(","))
-    assert "cold" in variants and variants <= {"cold", "warm", "base"}, "--variants: cold[,warm][,base]"
+    assert "cold" in variants and variants <= {"cold", "warm", "base", "out16"}, "--variants: cold[,warm][,base][,out16]"
     hw = ft.ft_hw_query(0)
 
     def timed(plan, pa, pb, pc, iters, graph=None):
@@ -91,6 +92,13 @@ def main():
         t_plan_cold += time.perf_counter() - t0
         base = ft.ft_plan_create(op, uks, ft.ft_shape(m=M), ft.FT_PLAN_PAD_BASELINE)
         rows.append(dict(M=M, N=N, K=K, plan=plan, base=base))
+        if "out16" in variants:                      # the same operator with a 16-bit C
+            if (N, K, 16) not in ops:
+                op16 = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=1, m_hi=8192,
+                                                       out_dtype=ft.FT_OUT_SAME))
+                ops[(N, K, 16)] = (op16, ft.ft_ukernels_derive(op16, hw, None), 0.0)
+            op16, uks16, _ = ops[(N, K, 16)]
+            rows[-1]["plan16"] = ft.ft_plan_create(op16, uks16, ft.ft_shape(m=M), ft.FT_PLAN_PATCHWORK)
 
     per_class_time = {}
     per_class_flops = {}
@@ -121,8 +129,13 @@ def main():
         if "base" in variants:
             timed(r["base"], pa, pb, pc, max(1, args.warmup), graph=False)
             ms_base = timed(r["base"], pa, pb, pc, args.steps)
+        ms_out16 = float("inf")
+        if "out16" in variants:                      # C buffers are large enough for either type
+            timed(r["plan16"], pa, pb, pc, max(1, args.warmup), graph=False)
+            ms_out16 = timed(r["plan16"], pa, pb, pc, args.steps)
         t_roof = max(flops / (MFMA_PEAK_TFLOPS * 1e12), bytes_alg / (HBM_PEAK_GBS * 1e9))
-        r.update(ms_cold=ms_cold, ms_warm=ms_warm, ms_base=ms_base, flops=flops, bytes_alg=bytes_alg,
+        r.update(ms_cold=ms_cold, ms_warm=ms_warm, ms_base=ms_base, ms_out16=ms_out16, tflops_out16=flops / ms_out16 / 1e9,
+                 flops=flops, bytes_alg=bytes_alg,
                  tflops_cold=flops / ms_cold / 1e9, tflops_warm=flops / ms_warm / 1e9,
                  tflops_base=flops / ms_base / 1e9, gbs_cold=bytes_alg / ms_cold / 1e6,
                  roof_frac_cold=t_roof * 1e3 / ms_cold, n_tiles=st.n_tiles, n_ukernels=st.n_ukernels,
@@ -170,6 +183,10 @@ def main():
                        "ms_per_step": round(sum(r["ms_warm"] for r in rows), 5)} if "warm" in variants else None,
         "pad_baseline": {"value": round(basev, 3),
                          "ms_per_step": round(sum(r["ms_base"] for r in rows), 5)} if "base" in variants else None,
+        "fp16_output": {"value": round(geomean([r["tflops_out16"] for r in rows]), 3),
+                        "ms_per_step": round(sum(r["ms_out16"] for r in rows), 5),
+                        "note": "same sweep, cold, C rounded to fp16 in the epilogue (not the headline: the "
+                                "north star fixes fp32 output)"} if "out16" in variants else None,
         "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 5),
@@ -206,7 +223,7 @@ def main():
 
     os.makedirs(os.path.dirname(args.detail), exist_ok=True)
     with open(args.detail, "w") as f:
-        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base")} for r in rows], f, indent=1)
+        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base", "plan16")} for r in rows], f, indent=1)
     print(json.dumps(out), flush=True)
 
 

@@ -125,6 +125,9 @@ typedef struct ft_op_desc {
     uint32_t c_in, c_out, r, s, stride, pad;
     uint32_t out_dtype;            /* FT_OUT_*: element type of C                            */
     uint32_t epilogue;             /* FT_EPI_*                                               */
+    uint32_t batch_hi;             /* BMM: largest batch count of the workload (the batch of a
+                                      launch is a runtime value); 0 = unknown: the workload
+                                      filters (CrossPick, Eq. 5) are skipped for this operator */
 } ft_op_desc;
 
 typedef struct ft_op ft_op;
@@ -171,7 +174,9 @@ void ft_ukset_destroy(ft_ukset *set);
 typedef struct ft_shape {
     uint32_t struct_size;
     uint32_t batch;                /* BMM batch count; ignored for Matmul / Conv2d           */
-    uint32_t m, n, k;              /* dynamic GEMM extents (static ones: 0 or the same value)*/
+    uint32_t m, n, k;              /* dynamic GEMM extents (static ones: 0 or the same value);
+                                      every operand of one batch entry must stay below 2^31
+                                      elements and N below 2^20, else FT_ERR_UNSUPPORTED      */
     uint32_t img_n, img_h, img_w;  /* Conv2d input: images, height, width                    */
 } ft_shape;
 

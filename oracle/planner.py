@@ -184,6 +184,8 @@ class Op:
     stride: int = 1
     pad: int = 0
     out_bytes: int = 4   # bytes per output element: fp32, or 2 when C has the inputs' 16-bit type
+    batch_hi: int = 0    # BMM: largest batch count of the workload (the batch itself is a runtime
+                         # value); 0 = unknown: the workload filters cannot be evaluated and are skipped
 
     def gemm_static(self):
         if self.kind == OP_CONV2D:
@@ -221,32 +223,35 @@ ELT = 2
 def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4):
     """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, with K_mem read on gfx950 as the time the
     uKernel's k loop needs, so the ratio is the fraction of that time the MFMA pipes are busy.
-    t_c = FLOPs / FLOPS, t_g = global bytes / bw_G, t_s = LDS bytes / bw_S (Eq. 7's data terms),
-    t_l = ktile_latency_clk per k-tile a wave walks through (ceil(K/tk) tiles, shared among
-    the gk waves of a split-k grid).
+    t_c = FLOPs / FLOPS, t_g = global bytes / bw_G, t_s = LDS bytes / bw_S (Eq. 7's data terms).
+    A wave walks through nk_w = ceil(nk / gk) of the nk = ceil(K / tk) k-tiles (all of them in a
+    standard grid, every gk-th in a split-k grid): the MFMA phase lasts t_ce = t_c * gk * nk_w / nk
+    (= t_c unless a split-k grid leaves waves idle) and the loop pays t_l = ktile_latency_clk * nk_w.
       * residents >= 2 (workgroups sharing a CU, Alg. 1's block.bound): a SIMD holds several
         waves, copy, LDS and MFMA phases of different waves overlap:
-            K_mem = max(t_c, t_g, t_s) + t_l / residents
+            K_mem = max(t_ce, t_g, t_s) + t_l / residents
       * residents == 1: the one wave of a SIMD issues its global->LDS copies and its MFMAs
         itself; a fraction solo_copy_exposed_pct of the copy time is not hidden:
-            K_mem = t_c + exposed * t_g + t_l
+            K_mem = t_ce + exposed * t_g + t_l
     Returns (numerator, denominator) of the exact ratio."""
     F, G, S = hw["mfma_flops_per_clk_per_cu"], hw["bw_global_bytes_per_clk_per_cu"], hw["bw_lds_bytes_per_clk_per_cu"]
     flops = 2 * tm * tn * k_ref
     gbytes = (tm + tn) * k_ref * ELT + tm * tn * out_bytes    # data_r + data_w
     sbytes = (tm + tn) * k_ref * ELT + k_ref * ELT * (tm * gn + tn * gm)   # data_tw + data_tr
     nk = ceil_div(k_ref, tk)
+    nk_w = ceil_div(nk, gk)
     r = residents if residents >= 2 else 1
     ed = 100
-    # everything over the common denominator F * G * S * gk * r * ed
-    c = flops * G * S * gk * r * ed
-    lt = hw["ktile_latency_clk"] * nk * F * G * S * ed
+    # everything over the common denominator F * G * S * nk * r * ed
+    c = flops * G * S * nk * r * ed
+    ce = flops * G * S * gk * nk_w * r * ed
+    lt = hw["ktile_latency_clk"] * nk_w * F * G * S * nk * ed
     if r >= 2:
-        g = gbytes * F * S * gk * r * ed
-        s = sbytes * F * G * gk * r * ed
-        return c, max(c, g, s) + lt
-    g = gbytes * F * S * gk * hw["solo_copy_exposed_pct"]
-    return c, c + g + lt
+        g = gbytes * F * S * nk * r * ed
+        s = sbytes * F * G * nk * r * ed
+        return c, max(ce, g, s) + lt
+    g = gbytes * F * S * nk * hw["solo_copy_exposed_pct"]
+    return c, ce + g + lt
 
 
 def reg_budget(regs, hw):
@@ -286,14 +291,15 @@ def workload_shapes(op: Op):
     return [(m, n) for m in ms for n in ns]
 
 
-def passes_workload(tm, tn, shapes, hw, t):
+def passes_workload(tm, tn, shapes, hw, t, batch=1):
     """CrossPick (Alg. 1) and the space-axis test (Eq. 5) for one uKernel K over the workload:
     kept iff for some shape, composed of K alone (padding where K does not divide), K.pad and
     K.occ pass the staircase and the number of uKernels reaches Active Blocks = zeta x NumCores.
     SetBound's K.IsInBound depends on block.bound = min(K.wkl.block, zeta), which is known
-    only per shape: it is applied at the runtime stage."""
+    only per shape: it is applied at the runtime stage.  batch: the largest batch count of the
+    workload (every batch entry is tiled alike, so it multiplies the number of uKernels)."""
     for M, N in shapes:
-        T = ceil_div(M, tm) * ceil_div(N, tn)
+        T = batch * ceil_div(M, tm) * ceil_div(N, tn)
         if T < t["zeta"] * hw["num_cus"]:
             continue                                                # Eq. 5
         if cross_pick(pad_fraction(M * N, T * tm * tn), occ_fraction(T, hw["num_cus"]), t):
@@ -351,7 +357,11 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 cn2, cd2 = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, residents=2, out_bytes=op.out_bytes)
                 cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, gk, mfma, stages, lds, acc, regs,
                                     budget, cap, (cn << Q) // cd, (cn2 << Q) // cd2))
-                kept.append(passes_workload(tm, tn, shapes, hw, t))
+                if op.kind == OP_BMM:
+                    # the tile count of a batched workload scales with a batch only known at run time
+                    kept.append(op.batch_hi == 0 or passes_workload(tm, tn, shapes, hw, t, op.batch_hi))
+                else:
+                    kept.append(passes_workload(tm, tn, shapes, hw, t))
     if any(kept):
         cand = [u for u, k in zip(cand, kept) if k]
     cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))

@@ -54,7 +54,7 @@ class ft_tuning(_S):
 class ft_op_desc(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "kind", "dtype", "m", "n", "k", "m_lo", "m_hi", "n_lo", "n_hi", "k_lo", "k_hi",
-        "c_in", "c_out", "r", "s", "stride", "pad", "out_dtype", "epilogue")]
+        "c_in", "c_out", "r", "s", "stride", "pad", "out_dtype", "epilogue", "batch_hi")]
 
 
 class ft_ukernel_info(_S):

@@ -16,7 +16,10 @@ const launch_fn kLaunch[2][FT_NUM_CLASSES] = {
     {ft_launch_dt1_c0, ft_launch_dt1_c1, ft_launch_dt1_c2},
 };
 
-const launch_fn kLaunchGeneric[2] = {ft_launch_dt0_gen, ft_launch_dt1_gen};
+// general bodies: [dtype][0] = bodies with <= 64 accumulator registers (256-register kernel),
+// [dtype][1] = all bodies (512-register kernel)
+const launch_fn kLaunchGeneric[2][2] = {{ft_launch_dt0_gen_c1, ft_launch_dt0_gen_c2},
+                                        {ft_launch_dt1_gen_c1, ft_launch_dt1_gen_c2}};
 
 static_assert(sizeof(ftk::TileDesc) == sizeof(ft_tile_desc) && sizeof(ft_tile_desc) == 24,
               "descriptor layout is part of the ABI");
@@ -121,8 +124,16 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
         // the twins of the narrowest tiles exist in the general dispatcher only
         if (ft_is_partial_code((int)a.slot_code[0]) || ft_is_partial_code((int)a.slot_code[1])) fast = false;
     }
-    int rc = fast ? kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream)
-                  : kLaunchGeneric[plan->op.dtype](&a, plan->st.lds_bytes, hip_stream);
+    int rc;
+    if (fast) {
+        rc = kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
+    } else {
+        // the general bodies stage through registers into two LDS stages, whatever ring depth the
+        // uKernel has on the LDS-DMA path
+        const uint32_t lds = 2 * std::max(ft_stage_bytes_of_code((int)a.slot_code[0]), ft_stage_bytes_of_code((int)a.slot_code[1]));
+        const int acc = std::max(ft_acc_of_code((int)a.slot_code[0]), ft_acc_of_code((int)a.slot_code[1]));
+        rc = kLaunchGeneric[plan->op.dtype][acc <= 64 ? 0 : 1](&a, lds, hip_stream);
+    }
     if (rc != 0) return hip_fail((hipError_t)rc);
     return FT_OK;
 }

@@ -2,8 +2,9 @@
 // remap(i) and runs the uKernel body the descriptor names, so a single launch executes a
 // program made of one or two uKernel shapes (Sec. 5.1; Fig. 8 item 2).
 // Compiled once per -DFT_DT={0,1} -DFT_CLASS={0,1,2} with the fast bodies (LDS-DMA ring, aligned
-// operands) and once per dtype with -DFT_CLASS=2 -DFT_GENERIC=1 for the general bodies (any
-// alignment, ragged reduce axis, convolution gather).
+// operands) and per dtype with -DFT_GENERIC=1 -DFT_CLASS={1,2} for the general bodies (any alignment,
+// ragged reduce axis, convolution gather): class 1 holds every body with at most 64 accumulator
+// registers in a 256-register kernel (two workgroups per CU), class 2 all of them in 512 registers.
 #include "gemm_fast.h"
 #include "family.h"
 #include "launch_iface.h"
@@ -21,7 +22,11 @@
 #define FT_ACC_MAX 32
 #elif FT_CLASS == 1
 #define FT_MIN_WAVES 2
+#ifdef FT_GENERIC
+#define FT_ACC_MAX 64        // the general bodies also hold their staging registers
+#else
 #define FT_ACC_MAX 128
+#endif
 #else
 #define FT_MIN_WAVES 1
 #define FT_ACC_MAX 256
@@ -48,7 +53,8 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #ifdef FT_GENERIC
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
-        UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(g, d, smem);             \
+        if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
+            UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(g, d, smem);         \
         break;
 #else
 #define FT_X(CODE, WM, WN, GM, GN)                                              \

@@ -45,6 +45,28 @@ static inline int ft_body_code(int wm, int wn, int gm, int gn, int gk) {
     }
     return -1;
 }
+// LDS bytes of one stage (A tile + B tile, tk = 64, 16-bit elements) of the body with this code
+static inline uint32_t ft_stage_bytes_of_code(int code) {
+#define FT_X(c, WM, WN, GM, GN) if (code == c) return (uint32_t)(((GM) * (WM) + (GN) * (WN)) * FT_TK * 2);
+    FT_FAMILY(FT_X)
+    FT_FAMILY_PARTIAL(FT_X)
+#undef FT_X
+#define FT_X(c, TM, TN, TWIN) if (code == c) return (uint32_t)(((TM) + (TN)) * FT_TK * 2);
+    FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+    return 0;
+}
+// accumulator registers per lane of the body with this code
+static inline int ft_acc_of_code(int code) {
+#define FT_X(c, WM, WN, GM, GN) if (code == c) return (WM) * (WN) / 64;
+    FT_FAMILY(FT_X)
+    FT_FAMILY_PARTIAL(FT_X)
+#undef FT_X
+#define FT_X(c, TM, TN, TWIN) if (code == c) return (TM) * (TN) / 64;
+    FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+    return 1 << 30;
+}
 // bodies that exist in the general dispatcher only
 static inline int ft_is_partial_code(int code) {
 #define FT_X(c, WM, WN, GM, GN) if (code == c) return 1;

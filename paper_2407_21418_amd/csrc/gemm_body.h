@@ -154,16 +154,35 @@ __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const floa
             }
         return;
     }
+    // Edge tile: buffer stores through a descriptor that covers exactly the valid rows of this wave
+    // tile, so the hardware drops what lies beyond the last valid row; a lane whose column is
+    // beyond N gets an offset past the descriptor's range (offsets inside a wave tile stay below
+    // 2^31: the host rejects operands with a row pitch of 2^20 elements or more).
+    const uint32_t m0u = __builtin_amdgcn_readfirstlane(m0w), n0u = __builtin_amdgcn_readfirstlane(n0w);
+    if (m0u >= M || n0u >= N) return;
+    constexpr uint32_t ES = sizeof(T);
+    const uint32_t rows_valid = M - m0u < (uint32_t)(BM * MB) ? M - m0u : (uint32_t)(BM * MB);
+    const uint32_t cols_valid = N - n0u < (uint32_t)(BN * MB) ? N - n0u : (uint32_t)(BN * MB);
+    const uint32_t num_records = ((rows_valid - 1) * ldc + cols_valid) * ES;
+    T *tile = Cb + ((uint64_t)m0u * ldc + n0u);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(tile, 0, (int)num_records, 0x00020000);
+    uint32_t vb[BN];
+#pragma unroll
+    for (int bj = 0; bj < BN; ++bj)
+        vb[bj] = (bj * MB + lcol < cols_valid) ? (lrow * ldc + bj * MB + lcol) * ES : 0x80000000u;
 #pragma unroll
     for (int bi = 0; bi < BM; ++bi)
 #pragma unroll
-        for (int bj = 0; bj < BN; ++bj) {
-            const uint32_t col = n0w + bj * MB + lcol;
-            if (col >= N) continue;
+        for (int e = 0; e < NE; ++e) {
+            const uint32_t r = bi * MB + (M16 ? e : 8 * (e / 4) + (e % 4));
+            const uint32_t roff = r * ldc * ES;                       // uniform
 #pragma unroll
-            for (int e = 0; e < NE; ++e) {
-                const uint32_t row = m0w + bi * MB + lrow + (M16 ? e : 8 * (e / 4) + (e % 4));
-                if (row < M) Cb[(uint64_t)row * ldc + col] = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
+            for (int bj = 0; bj < BN; ++bj) {
+                const T v = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
+                if constexpr (OUT == OUT_F32)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), rsrc, (int)(vb[bj] + roff), 0, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b16(v, rsrc, (int)(vb[bj] + roff), 0, 0);
             }
         }
 }

@@ -63,12 +63,13 @@ Gemm static_view(const ft_op_desc &d) {
 
 // Eq. 6 / Eq. 7: compute_eff = (FLOPs / FLOPS) : K_mem as num/den.  K_mem is the time the k loop
 // needs, so the ratio is the share of that time the MFMA pipes are busy.  With t_c = FLOPs/FLOPS,
-// t_g = global bytes / bw_G, t_s = LDS bytes / bw_S and t_l = ktile_latency_clk per k-tile a wave
-// walks through (ceil(K/tk) tiles, shared among the gk waves of a split-k grid):
+// t_g = global bytes / bw_G, t_s = LDS bytes / bw_S; a wave walks through nk_w = ceil(nk / gk) of the
+// nk = ceil(K/tk) k-tiles, so the MFMA phase lasts t_ce = t_c * gk * nk_w / nk (= t_c unless a split-k
+// grid leaves waves idle) and the loop pays t_l = ktile_latency_clk * nk_w:
 //   residents >= 2 (workgroups sharing a CU): phases of different waves overlap,
-//       K_mem = max(t_c, t_g, t_s) + t_l / residents
+//       K_mem = max(t_ce, t_g, t_s) + t_l / residents
 //   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
-//       K_mem = t_c + solo_copy_exposed_pct % of t_g + t_l
+//       K_mem = t_ce + solo_copy_exposed_pct % of t_g + t_l
 void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk, uint32_t tk, uint64_t kref,
                  uint32_t residents, uint32_t out_bytes, const ft_hw_model &hw, u128 *num, u128 *den) {
     const u128 F = hw.mfma_flops_per_clk_per_cu, G = hw.bw_global_bytes_per_clk_per_cu, S = hw.bw_lds_bytes_per_clk_per_cu;
@@ -76,18 +77,20 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk
     const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * out_bytes;                // data_r + data_w
     const u128 sbytes = (u128)(tm + tn) * kref * ELT + (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
     const u128 nk = ceil_div(kref, tk);
+    const u128 nk_w = ceil_div((uint64_t)nk, gk);
     const u128 r = residents >= 2 ? residents : 1;
     const u128 ed = 100;
-    // everything over the common denominator F * G * S * gk * r * ed
-    const u128 c = flops * G * S * gk * r * ed;
-    const u128 lt = (u128)hw.ktile_latency_clk * nk * F * G * S * ed;
+    // everything over the common denominator F * G * S * nk * r * ed
+    const u128 c = flops * G * S * nk * r * ed;
+    const u128 ce = flops * G * S * gk * nk_w * r * ed;
+    const u128 lt = (u128)hw.ktile_latency_clk * nk_w * F * G * S * nk * ed;
     *num = c;
     if (r >= 2) {
-        const u128 g = gbytes * F * S * gk * r * ed;
-        const u128 s = sbytes * F * G * gk * r * ed;
-        *den = std::max(c, std::max(g, s)) + lt;
+        const u128 g = gbytes * F * S * nk * r * ed;
+        const u128 s = sbytes * F * G * nk * r * ed;
+        *den = std::max(ce, std::max(g, s)) + lt;
     } else {
-        *den = c + gbytes * F * S * gk * hw.solo_copy_exposed_pct + lt;
+        *den = ce + gbytes * F * S * nk * hw.solo_copy_exposed_pct + lt;
     }
 }
 
@@ -142,10 +145,10 @@ bool cross_pick(u128 pn, u128 pd, u128 on, u128 od, const ft_tuning &t) {
 // uKernel alone, passes the staircase with a tile count of at least Active Blocks = zeta x NumCores.
 // (SetBound needs the shape's block.bound and is applied when a shape is planned.)
 bool passes_workload(uint32_t tm, uint32_t tn, const std::vector<uint64_t> &ms,
-                     const std::vector<uint64_t> &ns, const ft_hw_model &hw, const ft_tuning &t) {
+                     const std::vector<uint64_t> &ns, uint64_t batch, const ft_hw_model &hw, const ft_tuning &t) {
     for (uint64_t M : ms)
         for (uint64_t N : ns) {
-            uint64_t T = ceil_div(M, tm) * ceil_div(N, tn);
+            uint64_t T = batch * ceil_div(M, tm) * ceil_div(N, tn);
             if (T < (uint64_t)t.zeta * hw.num_cus) continue;        // Eq. 5
             u128 pn = (u128)M * N, pd = (u128)T * tm * tn;
             u128 on = T, od = ceil_by(T, hw.num_cus);
@@ -484,7 +487,12 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 compute_eff(tm, tn, gm, gn, gk, tk, kref, 2, out_bytes, h, &cn, &cd);
                 u.cmr_shared_q20 = (uint64_t)((cn << QBITS) / cd);
                 set->uk.push_back(u);
-                kept.push_back(passes_workload(tm, tn, ms, ns, h, t) ? 1 : 0);
+                // the tile count of a batched workload scales with a batch only known at run time:
+                // with no upper bound given the workload filters cannot be evaluated and keep everything
+                if (op->d.kind == FT_OP_BMM)
+                    kept.push_back(op->d.batch_hi == 0 || passes_workload(tm, tn, ms, ns, op->d.batch_hi, h, t) ? 1 : 0);
+                else
+                    kept.push_back(passes_workload(tm, tn, ms, ns, 1, h, t) ? 1 : 0);
             }
         }
     // K.Filter: the uKernels that pass the workload filters; all of them if none does
@@ -541,6 +549,7 @@ static ft_status check_common(const ft_op *op, const ft_ukset *set, const ft_sha
         if (shape->img_h >= 32768 || shape->img_w >= 32768) return FT_ERR_UNSUPPORTED;
     } else if (r->M * r->K >= lim) return FT_ERR_UNSUPPORTED;
     if (r->K * r->N >= lim || r->M * r->N >= lim || r->batch >= lim) return FT_ERR_UNSUPPORTED;
+    if (r->N >= (1ull << 20)) return FT_ERR_UNSUPPORTED;   // byte offsets inside one wave tile of C stay below 2^31
     return FT_OK;
 }
 

@@ -6,8 +6,8 @@
 #define FT_CAT(a, b, c, d) FT_CAT_(a, b, c, d)
 #if defined(FT_DT) && defined(FT_CLASS)
 #ifdef FT_GENERIC
-#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _gen, )
-#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _gen, )
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _gen_c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _gen_c, FT_CLASS)
 #else
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _c, FT_CLASS)
@@ -21,6 +21,8 @@ int ft_launch_dt0_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c0(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c2(const ftk::KArgs *, uint32_t, void *);
-int ft_launch_dt0_gen(const ftk::KArgs *, uint32_t, void *);
-int ft_launch_dt1_gen(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_gen_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_gen_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_gen_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_gen_c2(const ftk::KArgs *, uint32_t, void *);
 }

@@ -28,7 +28,7 @@ def to_lib_op(op: P.Op):
                       m_lo=op.m_range[0], m_hi=op.m_range[1], n_lo=op.n_range[0], n_hi=op.n_range[1],
                       k_lo=op.k_range[0], k_hi=op.k_range[1], c_in=op.c_in, c_out=op.c_out, r=op.r, s=op.s,
                       stride=op.stride, pad=op.pad,
-                      out_dtype=ft.FT_OUT_SAME if op.out_bytes == 2 else ft.FT_OUT_F32)
+                      out_dtype=ft.FT_OUT_SAME if op.out_bytes == 2 else ft.FT_OUT_F32, batch_hi=op.batch_hi)
     return ft.ft_op_register(d)
 
 
@@ -38,6 +38,7 @@ OPS = {
     "dense768k3072": P.Op(P.OP_MATMUL, P.F16, n=768, k=3072, m_range=(0, 8192)),
     "llm11008": P.Op(P.OP_MATMUL, P.BF16, n=11008, k=4096, m_range=(1, 8192)),
     "qk": P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512)),
+    "qk_b768": P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512), batch_hi=768),
     "pv": P.Op(P.OP_BMM, P.F16, n=64, m_range=(0, 512), k_range=(0, 512)),
     "onlyn": P.Op(P.OP_BMM, P.F16, m=64, k=64, n_range=(1, 512)),
     "conv": P.Op(P.OP_CONV2D, P.F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1, m_range=(0, 1 << 22)),
@@ -62,7 +63,7 @@ def test_ukernel_table_matches_oracle(name):
 
 
 def shapes_for(name):
-    if name in ("qk",):
+    if name in ("qk", "qk_b768"):
         return [dict(batch=b, m=L, n=L) for b in (1, 12, 96) for L in (1, 7, 16, 33, 77, 100, 257, 512)] + \
                [dict(batch=3, m=100, n=40), dict(batch=3, m=40, n=100), dict(batch=0, m=5, n=5), dict(batch=2, m=0, n=0)]
     if name == "pv":

@@ -190,6 +190,15 @@ def test_compute_eff_closed_form():
     n4, d4 = P.compute_eff(32, 32, 1, 1, 768, hw, gk=4, residents=3)
     t_s = (64 * 768 * 2 + 768 * 2 * 64) / 256
     assert abs(n4 / d4 - t_c / (max(t_c, t_g, t_s) + 400 * 12 / 4 / 3)) < 1e-12
+    # a split-k grid on a single k-tile (K = 64) leaves three of its four waves idle: the MFMA
+    # phase lasts 4 x t_c and the one working wave pays the full k-tile latency
+    n1, d1 = P.compute_eff(32, 32, 1, 1, 64, hw, gk=4)
+    t_c1, t_g1 = 2 * 32 * 32 * 64 / 4096, (64 * 64 * 2 + 32 * 32 * 4) / 64
+    assert abs(n1 / d1 - t_c1 / (4 * t_c1 + t_g1 / 2 + 400)) < 1e-12
+    # K = 576 (nine k-tiles): a wave of the split-k grid walks ceil(9 / 4) = 3 of them
+    n9, d9 = P.compute_eff(32, 32, 1, 1, 576, hw, gk=4)
+    t_c9, t_g9 = 2 * 32 * 32 * 576 / 4096, (64 * 576 * 2 + 32 * 32 * 4) / 64
+    assert abs(n9 / d9 - t_c9 / (t_c9 * 12 / 9 + t_g9 / 2 + 400 * 3)) < 1e-12
     # a bigger tile is more compute-intensive; the ratio is an efficiency, never above 1
     n1, d1 = P.compute_eff(128, 128, 2, 2, 768, hw)
     n2, d2 = P.compute_eff(256, 256, 2, 2, 768, hw)
