@@ -10,7 +10,7 @@ import synth_inputs as si
 from oracle import contraction as oc
 from oracle import planner as P
 
-from gpu_util import REL_TOL, alloc_out, check, check_epilogue, dev_bits, matmul_op, out_view, run, run_epilogue, stream
+from gpu_util import GUARD, REL_TOL, alloc_out, check, check_epilogue, dev_bits, matmul_op, out_view, run, run_epilogue, stream
 from oracle import epilogue as oe
 
 pytestmark = pytest.mark.gpu
@@ -369,3 +369,29 @@ def test_conv_and_bmm_with_epilogue():
     plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=L, n=L))
     got = run_epilogue(plan, A, B, ref.size, out16=ft.FT_BF16)
     check_epilogue(got, ref, refabs, None, ft.FT_BF16, "bmm -> bf16")
+
+
+def test_timing_entry_points_leave_correct_results():
+    """ft_launch_timed and ft_launch_timed_graph (stream capture + replay of the same launches) run
+    the plan on rotating buffer sets: every set must hold the oracle's result afterwards, after
+    several replays with eager launches and synchronisations in between."""
+    p = si.config1_problem(272, 768, 768)
+    op = matmul_op(768, 768, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=272))
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    side = torch.cuda.Stream()
+    n_sets = 3
+    A = [dev_bits(p["A"]) for _ in range(n_sets)]
+    B = [dev_bits(p["B"]) for _ in range(n_sets)]
+    for use_graph in (False, True, True):
+        bufs = [alloc_out(272 * 768) for _ in range(n_sets)]
+        torch.cuda.synchronize()
+        ms = ft.ft_launch_timed(plan, [t.data_ptr() for t in A], [t.data_ptr() for t in B],
+                                [b.data_ptr() + 4 * GUARD for b in bufs], side.cuda_stream, 7, graph=use_graph)
+        torch.cuda.synchronize()
+        assert 0.0 < ms < 10.0
+        for b in bufs:
+            check(out_view(b, 272 * 768), ref, refabs, f"timed launch graph={use_graph}")
+        # eager work between the replays
+        check(run(plan, p["A"], p["B"], 272 * 768), ref, refabs, "eager launch between timed runs")

@@ -272,3 +272,29 @@ def test_error_codes():
     with pytest.raises(ft.FtError) as e:
         ft.ft_launch(pl, 16, 16, 16, 0)
     assert e.value.status == ft.FT_ERR_INVALID_ARG
+
+
+def test_limits_are_reported():
+    """Shapes beyond the 32-bit offset arithmetic of the kernels are refused at plan time."""
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=1, m_hi=64, n_lo=1, n_hi=1 << 21))
+    s = ft.ft_ukernels_derive(op)
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_plan_create(op, s, ft.ft_shape(batch=1, m=16, n=1 << 20), HOST)
+    assert e.value.status == ft.FT_ERR_UNSUPPORTED
+    ft.ft_plan_create(op, s, ft.ft_shape(batch=1, m=16, n=(1 << 20) - 16), HOST)
+
+
+def test_batch_bound_of_a_batched_workload():
+    """Without a batch bound the workload filters are skipped for BMM; with one, the tile count of
+    the workload scales with it (a single 512 x 512 entry cannot fill the device with large tiles,
+    768 of them can)."""
+    full = P.derive_ukernels(P.Op(P.OP_BMM, P.F16, k=64, m_range=(1, 512), n_range=(1, 512)))
+    one = P.derive_ukernels(P.Op(P.OP_BMM, P.F16, k=64, m_range=(1, 512), n_range=(1, 512), batch_hi=1))
+    many = P.derive_ukernels(P.Op(P.OP_BMM, P.F16, k=64, m_range=(1, 512), n_range=(1, 512), batch_hi=768))
+    key = lambda us: {(u.tm, u.tn, u.gk) for u in us}
+    assert key(many) == key(full) and len(one) < len(full)
+    assert (128, 128, 1) in key(many) and (128, 128, 1) not in key(one)
+    for bh, want in ((0, full), (1, one), (768, many)):
+        lop = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=1, m_hi=512, n_lo=1, n_hi=512, batch_hi=bh))
+        s = ft.ft_ukernels_derive(lop)
+        assert ft.ft_ukset_size(s) == len(want)
