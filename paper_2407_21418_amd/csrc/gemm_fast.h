@@ -479,8 +479,8 @@ struct UKernelSplitK {
                     if (row < M && col < N) {
                         if (g.bias != nullptr) sum += g.bias[col];
                         const uint64_t o = (uint64_t)d.batch * g.strideC + (uint64_t)row * g.ldc + col;
-                        if (g.out_kind == OUT_F32) static_cast<float *>(g.C)[o] = sum;
-                        else static_cast<uint16_t *>(g.C)[o] = out_cvt<DT == 0 ? OUT_F16 : OUT_BF16>(sum);
+                        if (g.out_kind == OUT_F32) __builtin_nontemporal_store(sum, static_cast<float *>(g.C) + o);
+                        else __builtin_nontemporal_store(out_cvt<DT == 0 ? OUT_F16 : OUT_BF16>(sum), static_cast<uint16_t *>(g.C) + o);
                     }
                 }
     }
