@@ -69,6 +69,8 @@ typedef struct ft_hw_model {
                                                 alone on its CU cannot hide behind MFMA (50)  */
     uint32_t hbm_gbytes_per_s;               /* 8000; used for rooflines only                */
     uint32_t num_xcds;                       /* 8                                            */
+    uint32_t part_exchange_clk;              /* reduce-axis split: latency of handing a partial
+                                                tile to the workgroup that sums them (4000)   */
 } ft_hw_model;
 
 /* gfx950 defaults; host only. out: host pointer. */
@@ -94,6 +96,12 @@ typedef struct ft_tuning {
                                                        (default): mean over the program's uKernels
                                                        of CMR^c0 * Pad^c1 * Occ^c2, each on its own
                                                        sub-workload (c0..c2 <= 4)               */
+    /* Occupancy rescue for shapes whose tiles do not fill the device (the weakness Sec. 6.2
+     * reports for short sequences): Matmul programs are also scored with the reduce axis of
+     * every tile split over 2, 3, 4, 6 or 8 workgroups (Occ and block.bound count workgroups,
+     * compute_eff is taken on one part), as long as all workgroups are resident at once.      */
+    uint32_t k_parts_max;                           /* most parts per tile; 1 = never split: 8    */
+    uint32_t k_part_min_tiles;                      /* fewest k-tiles (of tk) a part may get: 8   */
 } ft_tuning;
 enum { FT_SIA_LINEAR = 0, FT_SIA_PRODUCT = 1 };
 
@@ -195,6 +203,9 @@ enum {
 typedef struct ft_forced_program {
     uint32_t struct_size;
     uint32_t k1, count1, k2, count2;
+    uint32_t k_parts;              /* workgroups per tile along the reduce axis (0 or 1: none); cut
+                                      down to the k-tiles there are; ignored (1) when a constituent
+                                      has more than 128 accumulator registers per lane          */
 } ft_forced_program;
 
 /* Tile descriptor: one workgroup's work.  24 bytes, little endian, compared byte for byte
@@ -224,13 +235,19 @@ typedef struct ft_plan_stats {
     uint64_t n_tiles;
     uint64_t useful_elems;         /* batch*M*N                                              */
     uint64_t covered_elems;        /* sum of tm*tn over all tiles                            */
+    uint32_t k_parts;              /* workgroups per tile along the reduce axis (1 = no split)*/
+    uint32_t k_part_tiles;         /* k-tiles (of tk) per part; the last part may get fewer  */
+    uint64_t workspace_bytes;      /* device memory the plan owns for the partial tiles      */
 } ft_plan_stats;
 
 typedef struct ft_plan ft_plan;
 /* op, set, shape: host pointers.  forced: host pointer, read only in mode FT_PLAN_FORCED, else
  * may be NULL.  Unless FT_PLAN_HOST_ONLY is set the descriptor table is also copied to the
  * current HIP device (one hipMalloc + one synchronous hipMemcpy).  Plans are immutable and may
- * be launched any number of times. */
+ * be launched any number of times.  A plan with k_parts > 1 also owns workspace_bytes of device
+ * memory for the fp32 partial tiles plus 16 bytes of counters per tile: launches of one such plan
+ * must be ordered (same stream, or otherwise not overlapping), every launch leaves the counters
+ * at zero, and the sum over the parts is taken in part order, so results are reproducible. */
 ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_forced_program *forced, ft_plan **out);
 /* *descs: host pointer to library-owned memory, valid until ft_plan_destroy. */
@@ -239,7 +256,9 @@ ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, u
  * order[b] = index into the descriptor table of workgroup b, for b < min(*n, cap); *n receives
  * the number of workgroups (= tiles).  The order is a permutation of the table: every XCD (a
  * group of CUs with its own L2; workgroup b runs on XCD b % num_xcds) takes a contiguous slice of
- * each constituent's tiles, walked in 2-D groups.  order: host pointer, caller-owned. */
+ * each constituent's tiles, walked in 2-D groups.  order: host pointer, caller-owned.
+ * With k_parts = P > 1 every entry of this order is worked on by P workgroups of the same XCD:
+ * workgroup b takes entry (b / (P*X))*X + b % X and part (b / X) % P, X = num_xcds. */
 ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t cap, uint64_t *n);
 ft_status ft_plan_stats_get(const ft_plan *plan, ft_plan_stats *out);
 void ft_plan_destroy(ft_plan *plan);

@@ -38,6 +38,7 @@ def default_hw():
                 max_waves_per_simd=8, lds_bytes_per_cu=163840, clock_mhz=2400,
                 mfma_flops_per_clk_per_cu=4096, bw_global_bytes_per_clk_per_cu=64,
                 bw_lds_bytes_per_clk_per_cu=256, ktile_latency_clk=400, solo_copy_exposed_pct=50,
+                part_exchange_clk=4000,
                 hbm_gbytes_per_s=8000, num_xcds=8)
 
 
@@ -47,7 +48,8 @@ def default_tuning():
     the paper, 1/64 here."""
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
-                zeta=2, rest_regs=72, psi_num=1, psi_den=64, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT)
+                zeta=2, rest_regs=72, psi_num=1, psi_den=64, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT,
+                k_parts_max=8, k_part_min_tiles=8)
 
 
 # --------------------------------------------------------------------------------------
@@ -220,7 +222,7 @@ MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
 
 
-def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4):
+def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4, exchange_clk=0):
     """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, with K_mem read on gfx950 as the time the
     uKernel's k loop needs, so the ratio is the fraction of that time the MFMA pipes are busy.
     t_c = FLOPs / FLOPS, t_g = global bytes / bw_G, t_s = LDS bytes / bw_S (Eq. 7's data terms).
@@ -233,6 +235,8 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
       * residents == 1: the one wave of a SIMD issues its global->LDS copies and its MFMAs
         itself; a fraction solo_copy_exposed_pct of the copy time is not hidden:
             K_mem = t_ce + exposed * t_g + t_l
+    exchange_clk: a fixed time added to K_mem (divided by residents like t_l): the round trips of
+    a workgroup that hands its partial tile to the others of a reduce-axis split.
     Returns (numerator, denominator) of the exact ratio."""
     F, G, S = hw["mfma_flops_per_clk_per_cu"], hw["bw_global_bytes_per_clk_per_cu"], hw["bw_lds_bytes_per_clk_per_cu"]
     flops = 2 * tm * tn * k_ref
@@ -245,7 +249,7 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
     # everything over the common denominator F * G * S * nk * r * ed
     c = flops * G * S * nk * r * ed
     ce = flops * G * S * gk * nk_w * r * ed
-    lt = hw["ktile_latency_clk"] * nk_w * F * G * S * nk * ed
+    lt = (hw["ktile_latency_clk"] * nk_w + exchange_clk) * F * G * S * nk * ed
     if r >= 2:
         g = gbytes * F * S * nk * r * ed
         s = sbytes * F * G * nk * r * ed
@@ -404,6 +408,7 @@ class Program:
     sia_q: int = 0
     k1: int = -1
     k2: int = -1
+    k_parts: int = 1                        # workgroups per tile along the reduce axis
 
 
 @dataclass
@@ -419,6 +424,8 @@ class Plan:
     level: int = 0
     useful: int = 0
     covered: int = 0
+    k_parts: int = 1                        # workgroups per tile along the reduce axis
+    k_part_tiles: int = 0                   # k-tiles per part (the last part may get fewer)
 
 
 def resolve_shape(op: Op, batch=1, m=0, n=0, k=0, img_n=0, img_h=0, img_w=0):
@@ -471,8 +478,41 @@ def build_pool(extents, Hp):
     return pool
 
 
-def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q):
-    """Cached-metric evaluation of one program (Sec. 5.2) on the actual shape."""
+K_PART_CHOICES = (1, 2, 3, 4, 6, 8)    # workgroups per tile along the reduce axis the planner considers
+KPART_ACC_MAX = 128                    # uKernels with more accumulator registers per lane are never split
+
+
+def part_tiles(K, tk, k_parts):
+    """k-tiles per part when the nk = ceil(K / tk) k-tiles are dealt out in equal runs."""
+    return ceil_div(max(ceil_div(K, tk), 1), k_parts)
+
+
+def split_allowed(parts, uks, K, k_parts, t, hw, tiles):
+    """May every tile of this program (tiles of them) be split over k_parts workgroups along the
+    reduce axis?  One part is always allowed.  More need: room in the registers of every
+    constituent for the exchange, at least k_part_min_tiles k-tiles per part, no empty part, and
+    all tiles * k_parts workgroups resident at once (the split is there to fill a device the
+    tiles alone leave partly idle, not to queue more rounds of workgroups)."""
+    if k_parts == 1:
+        return True
+    if k_parts > t.get("k_parts_max", 1):
+        return False
+    if any(uks[uid].acc_regs > KPART_ACC_MAX for uid, _ in parts):
+        return False
+    per_cu = min([t["zeta"]] + [uks[uid].max_wg_per_cu for uid, _ in parts])
+    if tiles * k_parts > hw["num_cus"] * per_cu:
+        return False
+    tk = uks[parts[0][0]].tk
+    nk = max(ceil_div(K, tk), 1)
+    per = ceil_div(nk, k_parts)
+    return nk // k_parts >= max(t.get("k_part_min_tiles", 1), 1) and ceil_div(nk, per) == k_parts
+
+
+def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, k_parts=1, K=0, out_bytes=4):
+    """Cached-metric evaluation of one program (Sec. 5.2) on the actual shape.  With k_parts > 1
+    every tile is worked on by k_parts workgroups (occupancy rescue, see split_k_note): the
+    workgroup count of Eq. 3, Eq. 5 and SetBound is k_parts times the tile count, and compute_eff
+    is taken on one part of the reduce axis."""
     Wp = ceil_by(N if tau == 0 else M, GRANULE)
     tiles_per_batch, area = 0, 0
     for uid, cnt in parts:
@@ -481,29 +521,30 @@ def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q):
         tiles_per_batch += cnt * across
         area += cnt * across * u.tm * u.tn
     T = batch * tiles_per_batch
-    p = Program(parts=sorted(parts), num_tiles=T, area=area)
+    Wg = T * k_parts
+    p = Program(parts=sorted(parts), num_tiles=T, area=area, k_parts=k_parts)
     p.k1 = parts[0][0]
     p.k2 = parts[1][0] if len(parts) > 1 else -1
     # SetBound (Alg. 1): block.bound = min(K.wkl.block, zeta)
-    p.block_bound = min(max(1, ceil_div(T, hw["num_cus"])), t["zeta"])
+    p.block_bound = min(max(1, ceil_div(Wg, hw["num_cus"])), t["zeta"])
     p.in_bound = all(uks[uid].max_wg_per_cu >= p.block_bound for uid, _ in parts)
-    occ = occ_fraction(T, hw["num_cus"])
+    occ = occ_fraction(Wg, hw["num_cus"])
     pad = pad_fraction(M * N, area)
     p.occ_q = (occ[0] << Q) // occ[1]
     p.pad_q = (pad[0] << Q) // pad[1]
     p.cross = cross_pick(pad, occ, t)
-    p.saturated = T >= t["zeta"] * hw["num_cus"]                 # Eq. 5
+    p.saturated = Wg >= t["zeta"] * hw["num_cus"]                # Eq. 5
     # compute_eff is normalised by the set's best; a two-uKernel program takes the average of
     # its constituents (Sec. 5.2).  Each constituent contributes the value cached for the number
     # of workgroups that share a CU on this shape: min(its capacity, block.bound)
     acc = 0
     for uid, _ in parts:
-        acc += (min(cmr_at(uks[uid], p.block_bound), cap_q) << Q) // cap_q
+        acc += (min(cmr_split(uks[uid], p.block_bound, k_parts, K, hw, out_bytes), cap_q) << Q) // cap_q
     p.cmr_q = acc // len(parts)
     if t.get("sia_form", SIA_LINEAR) == SIA_LINEAR:
         p.sia_q = t["c0"] * p.cmr_q + t["c1"] * p.pad_q + t["c2"] * p.occ_q   # Eq. 1 as printed
     else:
-        p.sia_q = sia_product(p.parts, uks, batch, M, N, tau, hw, t, cap_q, p.block_bound)
+        p.sia_q = sia_product(p.parts, uks, batch, M, N, tau, hw, t, cap_q, p.block_bound, k_parts, K, out_bytes)
     return p
 
 
@@ -517,7 +558,21 @@ def cmr_at(u, block_bound):
     return u.cmr2_q if min(u.max_wg_per_cu, block_bound) >= 2 else u.cmr_q
 
 
-def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q, block_bound):
+def cmr_split(u, block_bound, k_parts, K, hw, out_bytes):
+    """compute_eff of uKernel u on this shape: the cached value when a tile is one workgroup; for
+    a reduce-axis split, Eq. 6 re-evaluated on one part: its share of the k-tiles, 8 more bytes of
+    global traffic per output element (the fp32 partial written once and read once) and the
+    exchange's round trips (part_exchange_clk)."""
+    if k_parts == 1:
+        return cmr_at(u, block_bound)
+    r = 2 if min(u.max_wg_per_cu, block_bound) >= 2 else 1
+    k_part = part_tiles(K, u.tk, k_parts) * u.tk
+    cn, cd = compute_eff(u.tm, u.tn, u.gm, u.gn, k_part, hw, u.gk, u.tk, residents=r,
+                         out_bytes=out_bytes + 8, exchange_clk=hw["part_exchange_clk"])
+    return (cn << Q) // cd
+
+
+def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q, block_bound, k_parts=1, K=0, out_bytes=4):
     """Eq. 1 in its multiplicative (log-domain) form, evaluated per uKernel from the metrics
     cached in each uKernel's data structure (Sec. 5.2): each constituent K gets
     CMR^c0 * Pad^c1 * Occ^c2 from its own sub-workload -- the rows (columns) it covers, its own
@@ -539,11 +594,11 @@ def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q, block_bound):
         u = uks[uid]
         e = _ext(u, tau)
         across = ceil_div(Wp, _ext(u, 1 - tau))
-        T = batch * cnt * across
+        T = batch * cnt * across * k_parts                  # workgroups of this constituent
         useful = max(0, min(H - off, cnt * e)) * W
         area = cnt * across * u.tm * u.tn
         off += cnt * e
-        cmr_q = (min(cmr_at(u, block_bound), cap_q) << Q) // cap_q
+        cmr_q = (min(cmr_split(u, block_bound, k_parts, K, hw, out_bytes), cap_q) << Q) // cap_q
         pad_q = (useful << Q) // area
         on, od = occ_fraction(T, hw["num_cus"])
         occ_q = (on << Q) // od
@@ -608,26 +663,36 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         pl.pool_size, pl.level = 1, 0 if prog.in_bound else 1
     else:
         Hp = ceil_by(M if tau == 0 else N, GRANULE)
-        pool = [evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
-                for parts in build_pool([_ext(u, tau) for u in uks], Hp)]
-        if not pool:
+        covers = build_pool([_ext(u, tau) for u in uks], Hp)
+        if not covers:
             # Alg. 2 found nothing (the main axis is shorter than every extent the static
             # axes admit): pad it up to the uKernel with the smallest main-axis extent
             e_min = min(_ext(u, tau) for u in uks)
             u = next(u for u in uks if _ext(u, tau) == e_min)
-            pool = [evaluate([(u.id, ceil_div(Hp, e_min))], uks, batch, M, N, tau, hw, t, cap_q)]
-        pl.pool_size = len(pool)
+            covers = [[(u.id, ceil_div(Hp, e_min))]]
+        pl.pool_size = len(covers)
+        # Occupancy rescue (Matmul): every program is also scored with its tiles split over
+        # 2, 3, ... workgroups along the reduce axis, where that is allowed
+        choices = K_PART_CHOICES if op.kind == OP_MATMUL else (1,)
+        pool = []
+        for parts in covers:
+            whole = evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
+            pool.append(whole)
+            pool.extend(evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, kp, K, op.out_bytes)
+                        for kp in choices[1:] if split_allowed(parts, uks, K, kp, t, hw, whole.num_tiles))
         # runtime stage: the programs whose uKernels fit block.bound workgroups per CU on this
         # shape (SetBound); all of them if none does
         cands = [p for p in pool if p.in_bound]
         pl.level = 0
         if not cands:
             cands, pl.level = pool, 1
-        # Top-1 by SIA; ties: fewer tiles, then lower K1 index, then lower K2 index
-        prog = min(cands, key=lambda p: (-p.sia_q, p.num_tiles, p.k1, p.k2))
+        # Top-1 by SIA; ties: fewer parts, fewer tiles, then lower K1 index, then lower K2 index
+        prog = min(cands, key=lambda p: (-p.sia_q, p.k_parts, p.num_tiles, p.k1, p.k2))
     pl.program = prog
     pl.descs = emit(prog.parts, uks, batch, M, N, tau)
     pl.covered = batch * prog.area
+    pl.k_parts = prog.k_parts
+    pl.k_part_tiles = part_tiles(K, uks[prog.parts[0][0]].tk, prog.k_parts)
     assert len(pl.descs) == prog.num_tiles
     return pl
 

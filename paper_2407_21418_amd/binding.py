@@ -42,13 +42,13 @@ class ft_hw_model(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "num_cus", "simds_per_cu", "wave_size", "regs_per_lane", "max_waves_per_simd",
         "lds_bytes_per_cu", "clock_mhz", "mfma_flops_per_clk_per_cu", "bw_global_bytes_per_clk_per_cu",
-        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds")]
+        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds", "part_exchange_clk")]
 
 
 class ft_tuning(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "eps_min_pm", "eps_max_pm", "eps_step_pm", "lam_max_pm", "lam_min_pm", "lam_step_pm",
-        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form")]
+        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form", "k_parts_max", "k_part_min_tiles")]
 
 
 class ft_op_desc(_S):
@@ -68,7 +68,7 @@ class ft_shape(_S):
 
 
 class ft_forced_program(_S):
-    _fields_ = [(n, u32) for n in ("struct_size", "k1", "count1", "k2", "count2")]
+    _fields_ = [(n, u32) for n in ("struct_size", "k1", "count1", "k2", "count2", "k_parts")]
 
 
 class ft_tile_desc(C.Structure):
@@ -81,7 +81,8 @@ class ft_plan_stats(_S):
                 ("n_ukernels", u32), ("ukernel_id", u32 * 2), ("count_tau", u32 * 2), ("block_bound", u32),
                 ("pool_size", u32), ("level", u32), ("pad_q20", u32), ("occ_q20", u32), ("cmr_q20", u32),
                 ("lds_bytes", u32), ("kernel_class", u32), ("sia_q20", u64), ("n_tiles", u64),
-                ("useful_elems", u64), ("covered_elems", u64)]
+                ("useful_elems", u64), ("covered_elems", u64), ("k_parts", u32), ("k_part_tiles", u32),
+                ("workspace_bytes", u64)]
 
 
 class ft_pool_entry(C.Structure):

@@ -61,6 +61,11 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const fl
         a->slot_group[i] = p->slot_group[i];
     }
     a->num_xcds = p->num_xcds;
+    a->k_parts = s.k_parts > 1 && p->d_ws ? s.k_parts : 1;
+    a->k_part_tiles = s.k_part_tiles;
+    a->ws_tile_stride = p->ws_tile_stride;
+    a->ws = static_cast<float *>(p->d_ws);
+    a->arrive = static_cast<uint32_t *>(p->d_arrive);
 }
 
 }  // namespace
@@ -73,12 +78,24 @@ ft_status ftd_upload(ft_plan *p) {
     e = hipMalloc(&p->d_descs, bytes);
     if (e != hipSuccess) { p->d_descs = nullptr; return e == hipErrorOutOfMemory ? FT_ERR_OOM : hip_fail(e); }
     e = hipMemcpy(p->d_descs, p->descs.data(), bytes, hipMemcpyHostToDevice);
-    if (e != hipSuccess) { (void)hipFree(p->d_descs); p->d_descs = nullptr; return hip_fail(e); }
+    if (e != hipSuccess) { ftd_release(p); return hip_fail(e); }
+    if (p->st.k_parts > 1) {
+        const size_t ctr_bytes = p->descs.size() * 4 * sizeof(uint32_t);
+        e = hipMalloc(&p->d_ws, (size_t)p->st.workspace_bytes);
+        if (e != hipSuccess) { p->d_ws = nullptr; ftd_release(p); return e == hipErrorOutOfMemory ? FT_ERR_OOM : hip_fail(e); }
+        e = hipMalloc(&p->d_arrive, ctr_bytes);
+        if (e != hipSuccess) { p->d_arrive = nullptr; ftd_release(p); return e == hipErrorOutOfMemory ? FT_ERR_OOM : hip_fail(e); }
+        e = hipMemset(p->d_arrive, 0, ctr_bytes);        // once: every launch leaves the counters at zero
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+        if (e != hipSuccess) { ftd_release(p); return hip_fail(e); }
+    }
     return FT_OK;
 }
 
 void ftd_release(ft_plan *p) {
     if (p->d_descs) { (void)hipFree(p->d_descs); p->d_descs = nullptr; }
+    if (p->d_ws) { (void)hipFree(p->d_ws); p->d_ws = nullptr; }
+    if (p->d_arrive) { (void)hipFree(p->d_arrive); p->d_arrive = nullptr; }
 }
 
 extern "C" {
@@ -123,6 +140,7 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
         a.slot_code[1] = (uint32_t)ft_general_code((int)a.slot_code[1]);
         // the twins of the narrowest tiles exist in the general dispatcher only
         if (ft_is_partial_code((int)a.slot_code[0]) || ft_is_partial_code((int)a.slot_code[1])) fast = false;
+        a.k_parts = 1;                 // these bodies walk the whole reduce axis in one workgroup
     }
     int rc;
     if (fast) {

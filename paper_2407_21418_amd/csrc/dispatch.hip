@@ -44,8 +44,17 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     o.cols[0] = g.slot_cols[0]; o.cols[1] = g.slot_cols[1];
     o.group[0] = g.slot_group[0]; o.group[1] = g.slot_group[1];
     o.nx = g.num_xcds;
+    // Reduce axis split over workgroups: the k_parts workgroups of a tile are k_parts consecutive
+    // multiples of num_xcds apart, so they share an XCD (workgroup b runs on XCD b % num_xcds) and
+    // their partial tiles meet in that XCD's L2.  The grid is rounded up to whole XCD rounds.
+    uint32_t b = blockIdx.x, part = 0;
+    if (g.k_parts > 1) {
+        part = (b / o.nx) % g.k_parts;
+        b = (b / (o.nx * g.k_parts)) * o.nx + b % o.nx;
+        if (b >= g.n_tiles) return;
+    }
     uint32_t slot;
-    const uint32_t t = tile_of_workgroup(o, blockIdx.x, &slot);
+    const uint32_t t = tile_of_workgroup(o, b, &slot);
     const TileDesc d = g.descs[t];
     const uint32_t code = slot ? g.slot_code[1] : g.slot_code[0];
     const uint32_t stages = slot ? g.slot_stages[1] : g.slot_stages[0];
@@ -60,7 +69,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
-            UKernelFast<FT_DT, WM, WN, GM, GN>::run(g, d, smem, stages); \
+            UKernelFast<FT_DT, WM, WN, GM, GN>::run(g, d, smem, stages, t, part); \
         break;
 #endif
         FT_FAMILY(FT_X)
@@ -72,7 +81,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #define FT_X(CODE, TM, TN, TWIN)                                                \
     case CODE:                                                                  \
         if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \
-            UKernelSplitK<FT_DT, TM, TN>::run(g, d, smem, stages);  \
+            UKernelSplitK<FT_DT, TM, TN>::run(g, d, smem, stages, t, part);  \
         break;
         FT_FAMILY_SPLITK(FT_X)
 #undef FT_X
@@ -91,7 +100,12 @@ extern "C" int FT_LAUNCH_NAME(const ftk::KArgs *args, uint32_t lds_bytes, void *
         if (e != hipSuccess) return (int)e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(ftk::FT_KERNEL_NAME, dim3(args->n_tiles), dim3(256), lds_bytes,
+    uint32_t grid = args->n_tiles;
+    if (args->k_parts > 1) {
+        const uint32_t nx = args->num_xcds ? args->num_xcds : 1;
+        grid = (args->n_tiles + nx - 1) / nx * nx * args->k_parts;
+    }
+    hipLaunchKernelGGL(ftk::FT_KERNEL_NAME, dim3(grid), dim3(256), lds_bytes,
                        static_cast<hipStream_t>(stream), *args);
     return (int)hipGetLastError();
 }

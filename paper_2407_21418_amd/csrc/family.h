@@ -28,6 +28,9 @@
 
 #define FT_TK 64
 #define FT_NUM_CLASSES 3
+// bodies with more accumulator registers per lane than this cannot take part in a reduce-axis
+// split over workgroups (no registers left for the exchange of the partial tiles)
+#define FT_KPART_ACC_MAX 128
 // register class of a body: accumulator registers per lane -> launch-bounds budget
 //   class 0: acc <= 32  (kernel compiled for 4 waves/SIMD, <= 128 registers)
 //   class 1: acc <= 128 (2 waves/SIMD, <= 256 registers)

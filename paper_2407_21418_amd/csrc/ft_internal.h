@@ -30,6 +30,10 @@ struct ft_plan {
     uint32_t num_xcds;
     uint32_t img_h, img_w, out_p, out_q;   // conv geometry
     void *d_descs;                          // device copy of descs (NULL for host-only / empty plans)
+    // reduce axis split over workgroups (st.k_parts > 1): fp32 partial tiles and arrival counters
+    uint32_t ws_tile_stride;                // floats per (tile, part) slab: largest tm*tn of the plan
+    void *d_ws;                             // [n_tiles][k_parts][ws_tile_stride] floats
+    void *d_arrive;                         // [n_tiles][4] counters, zero between launches
     int device;
 };
 

@@ -52,6 +52,12 @@ struct KArgs {
     uint32_t slot_cols[2];
     uint32_t slot_group[2];           // tile rows walked together in the launch order (XCD locality)
     uint32_t num_xcds;
+    // reduce axis split over workgroups (1 = off): tile t is computed by k_parts workgroups, part p
+    // taking k-tiles [p * k_part_tiles, (p + 1) * k_part_tiles); partial tiles meet in ws
+    uint32_t k_parts, k_part_tiles;
+    uint32_t ws_tile_stride;          // floats between consecutive (tile, part) slabs of ws
+    float *ws;                        // [n_tiles][k_parts][ws_tile_stride] fp32 partial tiles
+    uint32_t *arrive;                 // [n_tiles][4] arrival counters, zero between launches
 };
 
 enum { DT_F16 = 0, DT_BF16 = 1 };

@@ -15,6 +15,7 @@
 // pitches lda, ldb and K, N multiples of 8 elements; for a convolution c_in a multiple of 64
 // (a k-tile then lies inside one filter tap) and c_out a multiple of 8.
 #pragma once
+#include "family.h"
 #include "gemm_body.h"
 
 namespace ftk {
@@ -42,6 +43,55 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned char *lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// Reduce axis split over workgroups: the k_parts workgroups of one tile each leave their fp32
+// partial in the workspace, one slab per (tile, part), laid out [register][lane] per wave so every
+// store and load is one contiguous 256-byte line per wave.  Arrival is counted per (tile, wave):
+// a wave writes its lines, waits until they are acknowledged, bumps the counter, and the wave that
+// arrives last sums the k_parts slabs in part order (the result does not depend on who came last),
+// resets the counter for the next launch and runs the normal epilogue.  Nobody waits for anybody.
+//
+// Coherence between the XCDs' L2 caches is kept per access, not per cache: the partials are written
+// and read as relaxed agent-scope atomics (stores that write through, loads that do not trust a
+// cached copy), so no whole-L2 write-back / invalidate is needed -- an agent-scope release/acquire
+// fence pair here cost 40 us per launch, several times the GEMM itself.  Ordering: the wave's
+// stores are complete when its vmcnt reaches zero, before the counter is touched; the loads of
+// the last wave are issued after its counter increment has returned.
+__device__ __forceinline__ bool k_part_arrive_last(const KArgs &g, uint32_t t, uint32_t wave) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    uint32_t *ctr = g.arrive + (t * 4u + wave);
+    uint32_t old = 0;
+    if ((threadIdx.x & 63u) == 0)
+        old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    asm volatile("" ::: "memory");
+    if (old + 1 != g.k_parts) return false;
+    if ((threadIdx.x & 63u) == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+// This wave's values <-> its lines of the slab of (tile t, part): floats [wave * NREGW + r][lane].
+// get(r) / set(r, x) read and write value r in place (accumulator registers: a copy would double
+// the register need of the largest tiles).
+template <int NREGW, typename Get, typename Set>
+__device__ __forceinline__ bool k_part_exchange(const KArgs &g, uint32_t t, uint32_t part, uint32_t wave,
+                                                uint32_t lane, Get get, Set set) {
+    const uint64_t tile0 = (uint64_t)t * g.k_parts * g.ws_tile_stride;
+    const uint32_t in_slab = wave * (NREGW * 64) + lane;
+    float *mine = g.ws + tile0 + (uint64_t)part * g.ws_tile_stride + in_slab;
+#pragma unroll
+    for (int r = 0; r < NREGW; ++r) __hip_atomic_store(mine + r * 64, get(r), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!k_part_arrive_last(g, t, wave)) return false;
+    float *p = g.ws + tile0 + in_slab;
+#pragma unroll
+    for (int r = 0; r < NREGW; ++r) set(r, __hip_atomic_load(p + r * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    for (uint32_t q = 1; q < g.k_parts; ++q) {
+        p += g.ws_tile_stride;
+#pragma unroll
+        for (int r = 0; r < NREGW; ++r) set(r, get(r) + __hip_atomic_load(p + r * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
+    return true;
 }
 
 template <int DT, int WM, int WN, int GM, int GN>
@@ -75,7 +125,7 @@ struct UKernelFast {
     }
 
     __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem,
-                                               uint32_t stages_in) {
+                                               uint32_t stages_in, uint32_t t, uint32_t part) {
         const uint32_t tid = threadIdx.x;
         const uint32_t lane = tid & 63u;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -84,7 +134,10 @@ struct UKernelFast {
         const uint32_t M = g.M, N = g.N, K = g.K;
         const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
         const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
-        const uint32_t nk = (K + TK - 1) / TK;
+        // this workgroup's k-tiles: kt0 .. kt0 + nk - 1 of the nk_all of the reduce axis
+        const uint32_t nk_all = (K + TK - 1) / TK;
+        const uint32_t kt0 = part * g.k_part_tiles;
+        const uint32_t nk = g.k_parts > 1 ? (nk_all - kt0 < g.k_part_tiles ? nk_all - kt0 : g.k_part_tiles) : nk_all;
         uint32_t S = stages_in < 2 ? 2u : stages_in;
         if (S > (uint32_t)MAX_AHEAD + 2) S = MAX_AHEAD + 2;
 
@@ -135,7 +188,7 @@ struct UKernelFast {
         auto issue_impl = [&](uint32_t kt, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
             unsigned char *st = smem + (kt % S) * STAGE_BYTES;
-            const uint32_t k0 = kt * TK;
+            const uint32_t k0 = (kt0 + kt) * TK;
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
             const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
             const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
@@ -176,7 +229,7 @@ struct UKernelFast {
             }
         };
         auto issue = [&](uint32_t kt) {
-            if (k_tail && kt + 1 == nk) issue_impl(kt, std::true_type{});
+            if (k_tail && kt0 + kt + 1 == nk_all) issue_impl(kt, std::true_type{});
             else issue_impl(kt, std::false_type{});
         };
 
@@ -231,6 +284,13 @@ struct UKernelFast {
         }
 
         // ---- epilogue ------------------------------------------------------------------------------
+        // (bodies with more than 128 accumulator registers have no room for it: the host never splits them)
+        if constexpr (WM * WN / 64 <= FT_KPART_ACC_MAX) if (g.k_parts > 1) {
+            constexpr int NE = M16 ? 4 : 16;
+            auto get = [&](int r) -> float { return acc[r / (BN * NE)][(r / NE) % BN][r % NE]; };
+            auto set = [&](int r, float x) { acc[r / (BN * NE)][(r / NE) % BN][r % NE] = x; };
+            if (!k_part_exchange<BM * BN * NE>(g, t, part, wave, lane, get, set)) return;
+        }
         store_acc<DT, true, M16, BM, BN>(g, (uint64_t)d.batch * g.strideC, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
 
@@ -342,7 +402,7 @@ struct UKernelSplitK {
     }
 
     __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem,
-                                               uint32_t stages_in) {
+                                               uint32_t stages_in, uint32_t t, uint32_t part) {
         const uint32_t tid = threadIdx.x;
         const uint32_t lane = tid & 63u;
         const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -350,7 +410,10 @@ struct UKernelSplitK {
         const uint32_t M = g.M, N = g.N, K = g.K;
         const uint16_t *__restrict__ Ab = g.A + (uint64_t)d.batch * g.strideA;
         const uint16_t *__restrict__ Bb = g.B + (uint64_t)d.batch * g.strideB;
-        const uint32_t nk = (K + TK - 1) / TK;
+        // this workgroup's k-tiles: kt0 .. kt0 + nk - 1 of the nk_all of the reduce axis
+        const uint32_t nk_all = (K + TK - 1) / TK;
+        const uint32_t kt0 = part * g.k_part_tiles;
+        const uint32_t nk = g.k_parts > 1 ? (nk_all - kt0 < g.k_part_tiles ? nk_all - kt0 : g.k_part_tiles) : nk_all;
         const uint32_t nkw = nk > wave ? (nk - wave + 3) / 4 : 0;     // k-tiles of this wave
         uint32_t S = stages_in < 2 ? 2u : stages_in;
         if (S > (uint32_t)MAX_AHEAD + 2) S = MAX_AHEAD + 2;
@@ -379,7 +442,7 @@ struct UKernelSplitK {
         auto issue_impl = [&](uint32_t j, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
             unsigned char *st = ring + (j % S) * STAGE_BYTES;
-            const uint32_t k0 = (wave + 4 * j) * TK;
+            const uint32_t k0 = (kt0 + wave + 4 * j) * TK;
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
             const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
             const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
@@ -404,7 +467,7 @@ struct UKernelSplitK {
             }
         };
         auto issue = [&](uint32_t j) {
-            if (k_tail && wave + 4 * j + 1 == nk) issue_impl(j, std::true_type{});
+            if (k_tail && kt0 + wave + 4 * j + 1 == nk_all) issue_impl(j, std::true_type{});
             else issue_impl(j, std::false_type{});
         };
 
@@ -451,38 +514,42 @@ struct UKernelSplitK {
 
         // ---- sum the four partial tiles: partials go to the wave's own (now idle) ring as
         // [register][lane] floats, then wave w adds up and stores registers w*NREG/4 .. +NREG/4
-        float *part = reinterpret_cast<float *>(ring);
+        float *own = reinterpret_cast<float *>(ring);
 #pragma unroll
         for (int bi = 0; bi < BM; ++bi)
 #pragma unroll
             for (int bj = 0; bj < BN; ++bj)
 #pragma unroll
                 for (int e = 0; e < (M16 ? 4 : 16); ++e)
-                    part[((bi * BN + bj) * (M16 ? 4 : 16) + e) * 64 + lane] = acc[bi][bj][e];
+                    own[((bi * BN + bj) * (M16 ? 4 : 16) + e) * 64 + lane] = acc[bi][bj][e];
         __syncthreads();
         constexpr int PER = NREG / 4;
         constexpr int RPB = M16 ? 4 : 16;               // registers per accumulator block
+        float fin[PER];
 #pragma unroll
-        for (int bi = 0; bi < BM; ++bi)
+        for (int q = 0; q < PER; ++q) {
+            float sum = 0.f;
 #pragma unroll
-            for (int bj = 0; bj < BN; ++bj)
+            for (int w = 0; w < 4; ++w)
+                sum += reinterpret_cast<const float *>(smem + w * S * STAGE_BYTES)[(wave * PER + q) * 64 + lane];
+            fin[q] = sum;
+        }
+        if (g.k_parts > 1 && !k_part_exchange<PER>(g, t, part, wave, lane, [&](int r) -> float { return fin[r]; },
+                                                  [&](int r, float x) { fin[r] = x; })) return;
 #pragma unroll
-                for (int e = 0; e < RPB; ++e) {
-                    const int r = (bi * BN + bj) * RPB + e;
-                    if (r / PER != (int)wave) continue;         // uniform per wave
-                    float sum = 0.f;
-#pragma unroll
-                    for (int w = 0; w < 4; ++w)
-                        sum += reinterpret_cast<const float *>(smem + w * S * STAGE_BYTES)[r * 64 + lane];
-                    uint32_t col = n0 + bj * MB + (lane % MB);
-                    uint32_t row = m0 + bi * MB + (M16 ? 4 * (lane / 16) + e : 8 * (e / 4) + 4 * (lane / 32) + (e % 4));
-                    if (row < M && col < N) {
-                        if (g.bias != nullptr) sum += g.bias[col];
-                        const uint64_t o = (uint64_t)d.batch * g.strideC + (uint64_t)row * g.ldc + col;
-                        if (g.out_kind == OUT_F32) __builtin_nontemporal_store(sum, static_cast<float *>(g.C) + o);
-                        else __builtin_nontemporal_store(out_cvt<DT == 0 ? OUT_F16 : OUT_BF16>(sum), static_cast<uint16_t *>(g.C) + o);
-                    }
-                }
+        for (int q = 0; q < PER; ++q) {
+            const uint32_t r = wave * PER + q;          // uniform: register r of the tile's accumulator layout
+            const uint32_t e = r % RPB, bj = (r / RPB) % BN, bi = r / (RPB * BN);
+            float sum = fin[q];
+            uint32_t col = n0 + bj * MB + (lane % MB);
+            uint32_t row = m0 + bi * MB + (M16 ? 4 * (lane / 16) + e : 8 * (e / 4) + 4 * (lane / 32) + (e % 4));
+            if (row < M && col < N) {
+                if (g.bias != nullptr) sum += g.bias[col];
+                const uint64_t o = (uint64_t)d.batch * g.strideC + (uint64_t)row * g.ldc + col;
+                if (g.out_kind == OUT_F32) __builtin_nontemporal_store(sum, static_cast<float *>(g.C) + o);
+                else __builtin_nontemporal_store(out_cvt<DT == 0 ? OUT_F16 : OUT_BF16>(sum), static_cast<uint16_t *>(g.C) + o);
+            }
+        }
     }
 };
 

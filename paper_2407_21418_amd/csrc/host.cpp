@@ -38,6 +38,7 @@ void hw_defaults(ft_hw_model *h) {
     h->solo_copy_exposed_pct = 50;
     h->hbm_gbytes_per_s = 8000;
     h->num_xcds = 8;
+    h->part_exchange_clk = 4000;
 }
 
 void tuning_defaults(ft_tuning *t) {
@@ -50,6 +51,8 @@ void tuning_defaults(ft_tuning *t) {
     t->psi_num = 1; t->psi_den = 64;
     t->c0 = t->c1 = t->c2 = 1;                                       // Sec. 5.2
     t->sia_form = FT_SIA_PRODUCT;
+    t->k_parts_max = 8;
+    t->k_part_min_tiles = 8;
 }
 
 struct Gemm {                // GEMM view of an operator: static extents (0 = dynamic)
@@ -70,8 +73,11 @@ Gemm static_view(const ft_op_desc &d) {
 //       K_mem = max(t_ce, t_g, t_s) + t_l / residents
 //   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
 //       K_mem = t_ce + solo_copy_exposed_pct % of t_g + t_l
+// exchange_clk: a fixed time added to t_l: the round trips of a workgroup that hands its partial
+// tile to the others of a reduce-axis split.
 void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk, uint32_t tk, uint64_t kref,
-                 uint32_t residents, uint32_t out_bytes, const ft_hw_model &hw, u128 *num, u128 *den) {
+                 uint32_t residents, uint32_t out_bytes, const ft_hw_model &hw, u128 *num, u128 *den,
+                 uint32_t exchange_clk = 0) {
     const u128 F = hw.mfma_flops_per_clk_per_cu, G = hw.bw_global_bytes_per_clk_per_cu, S = hw.bw_lds_bytes_per_clk_per_cu;
     const u128 flops = (u128)2 * tm * tn * kref;
     const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * out_bytes;                // data_r + data_w
@@ -83,7 +89,7 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk
     // everything over the common denominator F * G * S * nk * r * ed
     const u128 c = flops * G * S * nk * r * ed;
     const u128 ce = flops * G * S * gk * nk_w * r * ed;
-    const u128 lt = (u128)hw.ktile_latency_clk * nk_w * F * G * S * nk * ed;
+    const u128 lt = ((u128)hw.ktile_latency_clk * nk_w + exchange_clk) * F * G * S * nk * ed;
     *num = c;
     if (r >= 2) {
         const u128 g = gbytes * F * S * nk * r * ed;
@@ -123,9 +129,21 @@ struct Program {
     bool in_bound, cross, saturated;
     uint32_t pad_q, occ_q, cmr_q;
     uint64_t sia_q;
+    uint32_t k_parts;         // workgroups per tile along the reduce axis (0 reads as 1)
 };
 
 inline uint32_t ext(const ft_ukernel_info &u, uint32_t axis) { return axis == 0 ? u.tm : u.tn; }
+
+// Reduce-axis split (occupancy rescue): k-tiles per part when the nk = ceil(K / tk) k-tiles are
+// dealt out in equal runs.
+inline uint64_t part_tiles(uint64_t K, uint32_t tk, uint32_t k_parts) {
+    return ceil_div(std::max<uint64_t>(ceil_div(K, tk), 1), k_parts);
+}
+
+const uint32_t kPartChoices[] = {1, 2, 3, 4, 6, 8};     // parts per tile the planner considers
+
+struct Program;
+bool split_allowed(const Program &p, const ft_ukset &set, uint64_t K, uint32_t k_parts);
 
 bool cross_pick(u128 pn, u128 pd, u128 on, u128 od, const ft_tuning &t) {
     // lock-step staircase: eps up, lambda down, until either bound is passed (Alg. 1)
@@ -157,7 +175,13 @@ bool passes_workload(uint32_t tm, uint32_t tn, const std::vector<uint64_t> &ms,
     return false;
 }
 
-void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint64_t N, uint32_t tau) {
+// Cached-metric evaluation of one program on the actual shape (Sec. 5.2).  With k_parts > 1 every
+// tile is worked on by k_parts workgroups: the workgroup count of Eq. 3, Eq. 5 and SetBound is
+// k_parts times the tile count and compute_eff is taken on one part of the reduce axis (its share
+// of the k-tiles, 8 more bytes of global traffic per output element for the fp32 partial written
+// and read once, and the exchange's round trips).
+void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint64_t N, uint32_t tau,
+              uint32_t k_parts = 1, uint64_t K = 0) {
     const ft_hw_model &hw = set.hw;
     const ft_tuning &t = set.t;
     uint64_t Wp = ceil_by(tau == 0 ? N : M, GRANULE);
@@ -170,21 +194,29 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
     }
     p.tiles = batch * per_batch;
     p.area = area;
-    uint64_t need = std::max<uint64_t>(1, ceil_div(p.tiles, hw.num_cus));          // K.wkl.block
+    p.k_parts = k_parts;
+    const uint64_t wgs = p.tiles * k_parts;                                         // workgroups
+    const uint32_t out_bytes = set.op.out_dtype == FT_OUT_SAME ? ELT : 4;
+    uint64_t need = std::max<uint64_t>(1, ceil_div(wgs, hw.num_cus));              // K.wkl.block
     p.block_bound = (uint32_t)std::min<uint64_t>(need, t.zeta);                     // SetBound
     p.in_bound = true;
     for (uint32_t i = 0; i < p.nparts; ++i)
         if (set.uk[p.part[i].id].max_wg_per_cu < p.block_bound) p.in_bound = false;
-    u128 on = p.tiles, od = ceil_by(p.tiles, hw.num_cus);                           // Eq. 3
+    u128 on = wgs, od = ceil_by(wgs, hw.num_cus);                                   // Eq. 3
     u128 pn = (u128)M * N, pd = area;                                               // Eq. 2
     p.occ_q = (uint32_t)((on << QBITS) / od);
     p.pad_q = (uint32_t)((pn << QBITS) / pd);
     p.cross = cross_pick(pn, pd, on, od, t);
-    p.saturated = p.tiles >= (uint64_t)t.zeta * hw.num_cus;                         // Eq. 5
+    p.saturated = wgs >= (uint64_t)t.zeta * hw.num_cus;                             // Eq. 5
     // each constituent contributes the compute_eff cached for the number of workgroups that share
     // a CU on this shape: min(its capacity, block.bound)
     auto cmr_at = [&](const ft_ukernel_info &u) -> uint64_t {
-        return std::min<uint32_t>(u.max_wg_per_cu, p.block_bound) >= 2 ? u.cmr_shared_q20 : u.cmr_q20;
+        const bool shared = std::min<uint32_t>(u.max_wg_per_cu, p.block_bound) >= 2;
+        if (k_parts == 1) return shared ? u.cmr_shared_q20 : u.cmr_q20;
+        u128 cn, cd;
+        compute_eff(u.tm, u.tn, u.gm, u.gn, u.gk, u.tk, part_tiles(K, u.tk, k_parts) * u.tk, shared ? 2 : 1,
+                    out_bytes + 8, hw, &cn, &cd, hw.part_exchange_clk);
+        return (uint64_t)((cn << QBITS) / cd);
     };
     uint64_t acc = 0;
     for (uint32_t i = 0; i < p.nparts; ++i) {
@@ -206,7 +238,7 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
             const ft_ukernel_info &u = set.uk[p.part[i].id];
             const uint64_t e = ext(u, tau), cnt = p.part[i].count;
             const uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
-            const uint64_t T = batch * cnt * across;
+            const uint64_t T = batch * cnt * across * k_parts;      // workgroups of this constituent
             const uint64_t span = cnt * e;
             const uint64_t len = H > off ? std::min<uint64_t>(H - off, span) : 0;
             const u128 useful = (u128)len * W, area_u = (u128)cnt * across * u.tm * u.tn;
@@ -226,6 +258,25 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
         else if (p.nparts == 1) p.sia_q = (uint64_t)xs[0];
         else p.sia_q = (uint64_t)(((us[0] + us[1]) * xs[0] * xs[1]) / (us[0] * xs[1] + us[1] * xs[0]));
     }
+}
+
+// May every tile of program p (evaluated: p.tiles is set) be split over k_parts workgroups along
+// the reduce axis?  Needs room in the registers of every constituent for the exchange, at least
+// k_part_min_tiles k-tiles per part, no empty part, and all tiles * k_parts workgroups resident at
+// once (the split fills a device the tiles alone leave partly idle; it does not queue more rounds).
+bool split_allowed(const Program &p, const ft_ukset &set, uint64_t K, uint32_t k_parts) {
+    if (k_parts == 1) return true;
+    if (k_parts > set.t.k_parts_max) return false;
+    uint32_t per_cu = set.t.zeta;
+    for (uint32_t i = 0; i < p.nparts; ++i) {
+        const ft_ukernel_info &u = set.uk[p.part[i].id];
+        if (u.acc_regs > FT_KPART_ACC_MAX) return false;
+        per_cu = std::min(per_cu, u.max_wg_per_cu);
+    }
+    if (p.tiles * k_parts > (uint64_t)set.hw.num_cus * per_cu) return false;
+    const uint64_t nk = std::max<uint64_t>(ceil_div(K, set.uk[p.part[0].id].tk), 1);
+    const uint64_t per = ceil_div(nk, k_parts);
+    return nk / k_parts >= std::max<uint32_t>(set.t.k_part_min_tiles, 1) && ceil_div(nk, per) == k_parts;
 }
 
 // Alg. 2 over the set's main-axis extents on the granule-rounded size Hp (last-success form).
@@ -338,8 +389,9 @@ void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau
     }
 }
 
-bool better(const Program &a, const Program &b) {      // Top-1 order: SIA, then fewer tiles, K1, K2
+bool better(const Program &a, const Program &b) {      // Top-1 order: SIA, then fewer parts, fewer tiles, K1, K2
     if (a.sia_q != b.sia_q) return a.sia_q > b.sia_q;
+    if (a.k_parts != b.k_parts) return a.k_parts < b.k_parts;
     if (a.tiles != b.tiles) return a.tiles < b.tiles;
     if (a.k1 != b.k1) return a.k1 < b.k1;
     return a.k2 < b.k2;
@@ -594,6 +646,9 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     if (!pl) return FT_ERR_OOM;
     pl->op = op->d;
     pl->d_descs = nullptr;
+    pl->d_ws = nullptr;
+    pl->d_arrive = nullptr;
+    pl->ws_tile_stride = 0;
     pl->device = -1;
     pl->num_xcds = set->hw.num_xcds ? set->hw.num_xcds : 1;
     pl->img_h = shape->img_h; pl->img_w = shape->img_w; pl->out_p = r.P; pl->out_q = r.Q;
@@ -608,6 +663,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     s.tau = tau;
     s.batch = (uint32_t)r.batch; s.m = (uint32_t)r.M; s.n = (uint32_t)r.N; s.k = (uint32_t)r.K;
     s.useful_elems = r.batch * r.M * r.N;
+    s.k_parts = 1;
     if (r.batch == 0 || r.M == 0 || r.N == 0) {           // empty input: empty plan
         *out = pl;
         return FT_OK;
@@ -639,7 +695,20 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
             best.k2 = forced->k2;
         }
         if (total != Hp) { delete pl; return FT_ERR_NO_COVER; }
-        evaluate(best, *set, r.batch, r.M, r.N, tau);
+        // parts per tile: as asked, cut down to the k-tiles there are (no empty part); 1 if a
+        // constituent has no registers left for the exchange
+        uint32_t parts = 1;
+        if (forced->k_parts > 1) {
+            if (forced->k_parts > 64) { delete pl; return FT_ERR_INVALID_ARG; }
+            bool room = true;
+            for (uint32_t i = 0; i < best.nparts; ++i) room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX;
+            if (room) {
+                const uint64_t nk = std::max<uint64_t>(ceil_div(r.K, FT_TK), 1);
+                const uint64_t per = ceil_div(nk, std::min<uint64_t>(forced->k_parts, nk));
+                parts = (uint32_t)ceil_div(nk, per);
+            }
+        }
+        evaluate(best, *set, r.batch, r.M, r.N, tau, parts, r.K);
         s.pool_size = 1;
         s.level = (uint32_t)level_of(best);
     } else {
@@ -658,18 +727,33 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
             p.k1 = (int64_t)pick; p.k2 = -1;
             pool.push_back(p);
         }
-        int lvl = 2;
-        for (Program &p : pool) {
-            evaluate(p, *set, r.batch, r.M, r.N, tau);
-            lvl = std::min(lvl, level_of(p));
+        // Occupancy rescue (Matmul): every program is also scored with its tiles split over
+        // 2, 3, ... workgroups along the reduce axis, where that is allowed
+        s.pool_size = (uint32_t)pool.size();
+        {
+            std::vector<Program> scored;
+            scored.reserve(pool.size());
+            for (Program &p : pool) {
+                evaluate(p, *set, r.batch, r.M, r.N, tau);
+                scored.push_back(p);
+                if (op->d.kind != FT_OP_MATMUL) continue;
+                for (uint32_t kp : kPartChoices) {
+                    if (kp == 1 || !split_allowed(p, *set, r.K, kp)) continue;
+                    Program q = p;
+                    evaluate(q, *set, r.batch, r.M, r.N, tau, kp, r.K);
+                    scored.push_back(q);
+                }
+            }
+            pool.swap(scored);
         }
+        int lvl = 2;
+        for (const Program &p : pool) lvl = std::min(lvl, level_of(p));
         bool have = false;
         for (const Program &p : pool) {
             // a program belongs to every level at or above its own
             if (level_of(p) > lvl) continue;
             if (!have || better(p, best)) { best = p; have = true; }
         }
-        s.pool_size = (uint32_t)pool.size();
         s.level = (uint32_t)lvl;
     }
 
@@ -719,6 +803,22 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     s.kernel_class = klass;
     s.n_tiles = pl->descs.size();
     s.covered_elems = r.batch * best.area;
+
+    // Reduce-axis split: the planner's choice travels with the program; a forced program names its own
+    {
+        const uint64_t nk = std::max<uint64_t>(ceil_div(r.K, FT_TK), 1);
+        uint32_t parts = best.k_parts ? best.k_parts : 1;
+        const uint64_t per = ceil_div(nk, parts);
+        uint32_t stride = 0;
+        for (uint32_t i = 0; i < best.nparts; ++i) {
+            const ft_ukernel_info &u = set->uk[best.part[i].id];
+            stride = std::max(stride, u.tm * u.tn);
+        }
+        s.k_parts = parts;
+        s.k_part_tiles = (uint32_t)per;
+        s.workspace_bytes = parts > 1 ? s.n_tiles * parts * stride * 4ull : 0;
+        pl->ws_tile_stride = stride;
+    }
 
     if (!(flags & FT_PLAN_HOST_ONLY)) {
         st = ftd_upload(pl);

@@ -1,0 +1,145 @@
+"""GPU parity of the reduce-axis split over workgroups (occupancy rescue for shapes with few
+tiles): k_parts workgroups per tile leave fp32 partials in the plan's workspace and the last to
+arrive sums them in part order.  Same oracle, same tolerance as the unsplit path; on top of that
+two launches of one plan must agree bit for bit (fixed summation order, counters back at zero)."""
+import numpy as np
+import pytest
+
+import paper_2407_21418_amd as ft
+import synth_inputs as si
+from oracle import contraction as oc
+from oracle import planner as P
+
+from gpu_util import check, check_epilogue, matmul_op, run, run_epilogue
+
+pytestmark = pytest.mark.gpu
+
+
+def family():
+    op = P.Op(P.OP_BMM, P.F16, k_range=(0, 4096), m_range=(0, 8192), n_range=(0, 8192))
+    return [(u.tm, u.tn, u.wm, u.wn, u.gm, u.gn, u.gk) for u in P.derive_ukernels(op)]
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+@pytest.mark.parametrize("body", family(), ids=lambda b: "t%dx%d_w%dx%d_gk%d" % (b[0], b[1], b[2], b[3], b[6]))
+def test_every_fast_body_split_in_three(body, dtype):
+    """2 x 2 ragged tiles x batch 2, K = 11 k-tiles + a tail of 8: three parts of 4, 4 and 4 k-tiles
+    (the last holding the zero-filled tail)."""
+    tm, tn, wm, wn = body[:4]
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=8192, n_lo=0, n_hi=8192,
+                                         k_lo=0, k_hi=4096))
+    s = ft.ft_ukernels_derive(op)
+    ids = [i for i in range(ft.ft_ukset_size(s))
+           if (lambda u: (u.tm, u.tn, u.wm, u.wn) == (tm, tn, wm, wn))(ft.ft_ukset_get(s, i))]
+    assert len(ids) == 1
+    M, N, K, nb = 2 * tm - 5, 2 * tn - 8, 712, 2
+    g = np.random.default_rng(tm * 11 + tn * 5 + wm + dtype)
+    A = si.normal_bits(g, (nb, M, K), 1.0, dtype)
+    B = si.normal_bits(g, (nb, K, N), 1.0, dtype)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=M, n=N, k=K), ft.FT_PLAN_FORCED,
+                             ft.ft_forced_program(k1=ids[0], count1=2, k_parts=3))
+    st = ft.ft_plan_stats_get(plan)
+    if wm * wn // 64 > P.KPART_ACC_MAX:           # no registers left for the exchange: never split
+        assert (st.n_tiles, st.k_parts, st.k_part_tiles, st.workspace_bytes) == (nb * 4, 1, 12, 0)
+    else:
+        assert (st.n_tiles, st.k_parts, st.k_part_tiles) == (nb * 4, 3, 4)
+        assert st.workspace_bytes == st.n_tiles * 3 * tm * tn * 4
+    ref, refabs = oc.bmm(A, B, dtype, want_abs=True)
+    first = run(plan, A, B, nb * M * N)
+    check(first, ref, refabs, f"body {body} dtype {dtype} split 3")
+    again = run(plan, A, B, nb * M * N)
+    assert np.array_equal(first, again), "second launch of the same plan differs"
+
+
+@pytest.mark.parametrize("parts,K", [(2, 768), (4, 3072), (5, 1000), (8, 3072), (64, 200)])
+def test_mixed_program_bias_and_16bit_output(parts, K):
+    """Two uKernel shapes in one launch (a standard grid and a split-k wave grid), every tile split
+    over `parts` workgroups, with the fused bias and a 16-bit C.  parts = 64 exceeds the k-tiles of
+    K = 200 and is cut down to one k-tile per part."""
+    M, N = 1232, 768
+    g = np.random.default_rng(parts * 1000 + K)
+    A = si.normal_bits(g, (M, K), 1.0, ft.FT_F16)
+    B = si.normal_bits(g, (K, N), 0.05, ft.FT_F16)
+    bias = g.standard_normal(N).astype(np.float32)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=0, m_hi=8192,
+                                         out_dtype=ft.FT_OUT_SAME, epilogue=ft.FT_EPI_BIAS))
+    s = ft.ft_ukernels_derive(op)
+    infos = [ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))]
+    big = next(u for u in infos if u.tm == 128 and u.gk == 1)
+    small = next(u for u in infos if u.tm == 16)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED,
+                             ft.ft_forced_program(k1=big.id, count1=9, k2=small.id, count2=5, k_parts=parts))
+    st = ft.ft_plan_stats_get(plan)
+    nk = -(-K // 64)
+    per = -(-nk // min(parts, nk))
+    assert (st.k_parts, st.k_part_tiles) == (-(-nk // per), per)
+    assert st.workspace_bytes == st.n_tiles * st.k_parts * max(big.tm * big.tn, small.tm * small.tn) * 4
+    ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
+    ref = ref + bias[None, :]
+    got = run_epilogue(plan, A, B, M * N, bias=bias, out16=ft.FT_F16)
+    check_epilogue(got, ref, refabs, bias[None, :], ft.FT_F16, f"mixed split {parts} K {K}")
+    again = run_epilogue(plan, A, B, M * N, bias=bias, out16=ft.FT_F16)
+    assert np.array_equal(got, again)
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+def test_permutation_matrix_stays_bit_exact_when_split(dtype):
+    """A = permutation matrix: each output is one product plus zeros from the other parts."""
+    g = np.random.default_rng(14)
+    n, N = 384, 768
+    B = si.normal_bits(g, (n, N), 1.0, dtype)
+    perm = g.permutation(n)
+    Pm = np.zeros((n, n), dtype=np.float32)
+    Pm[np.arange(n), perm] = 1.0
+    A = si.to_bits(Pm, dtype)
+    op = matmul_op(N, n, dtype)
+    s = ft.ft_ukernels_derive(op)
+    want = oc.decode(B, dtype)[perm]
+    for i in range(ft.ft_ukset_size(s)):
+        u = ft.ft_ukset_get(s, i)
+        if n % u.tm:
+            continue
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=n), ft.FT_PLAN_FORCED,
+                                 ft.ft_forced_program(k1=i, count1=n // u.tm, k_parts=3))
+        assert ft.ft_plan_stats_get(plan).k_parts == (3 if u.acc_regs <= P.KPART_ACC_MAX else 1)
+        got = run(plan, A, B, n * N).reshape(n, N)
+        assert np.array_equal(got, want), (u.tm, u.tn, u.wm, u.wn)
+
+
+@pytest.mark.parametrize("M,N,K", [(80, 768, 3072), (272, 768, 3072), (528, 768, 3072), (1232, 768, 3072), (16, 4096, 4096)])
+def test_planner_chosen_split_matches_oracle(M, N, K):
+    """Patchwork plans of shapes with few tiles: the library's choice of k_parts is the oracle's,
+    and the result is within tolerance."""
+    dtype = ft.FT_F16
+    g = np.random.default_rng(M + N + K)
+    A = si.normal_bits(g, (M, K), 1.0, dtype)
+    B = si.normal_bits(g, (K, N), 0.02, dtype)
+    op = matmul_op(N, K, dtype)
+    s = ft.ft_ukernels_derive(op)
+    oop = P.Op(P.OP_MATMUL, P.F16, n=N, k=K, m_range=(0, 8192))
+    want = P.plan(oop, P.derive_ukernels(oop), (1, M, N, K))
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    st = ft.ft_plan_stats_get(plan)
+    assert (st.k_parts, st.k_part_tiles) == (want.k_parts, want.k_part_tiles)
+    assert ft.ft_plan_descriptors(plan) == b"".join(d.pack() for d in want.descs)
+    ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
+    check(run(plan, A, B, M * N), ref, refabs, f"{M}x{N}x{K} k_parts {st.k_parts}")
+
+
+def test_unaligned_operands_ignore_the_split():
+    """Odd row lengths take the general bodies, which walk the whole reduce axis themselves."""
+    M, N, K = 100, 203, 331
+    g = np.random.default_rng(5)
+    A = si.normal_bits(g, (M, K), 1.0, ft.FT_F16)
+    B = si.normal_bits(g, (K, N), 1.0, ft.FT_F16)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=0, m_hi=4096))
+    s = ft.ft_ukernels_derive(op)
+    u = ft.ft_ukset_get(s, 0)
+    Hp = -(-M // 16) * 16
+    ids = [i for i in range(ft.ft_ukset_size(s)) if Hp % ft.ft_ukset_get(s, i).tm == 0]
+    u = ft.ft_ukset_get(s, ids[0])
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED,
+                             ft.ft_forced_program(k1=ids[0], count1=Hp // u.tm, k_parts=3))
+    assert ft.ft_plan_stats_get(plan).k_parts == 3
+    ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
+    check(run(plan, A, B, M * N), ref, refabs, "general path, split ignored")

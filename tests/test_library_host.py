@@ -37,6 +37,7 @@ OPS = {
     "dense3072": P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(0, 8192)),
     "dense768k3072": P.Op(P.OP_MATMUL, P.F16, n=768, k=3072, m_range=(0, 8192)),
     "llm11008": P.Op(P.OP_MATMUL, P.BF16, n=11008, k=4096, m_range=(1, 8192)),
+    "llm4096": P.Op(P.OP_MATMUL, P.BF16, n=4096, k=4096, m_range=(1, 8192)),
     "qk": P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512)),
     "qk_b768": P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512), batch_hi=768),
     "pv": P.Op(P.OP_BMM, P.F16, n=64, m_range=(0, 512), k_range=(0, 512)),
@@ -77,6 +78,8 @@ def shapes_for(name):
         ms = [0] + ms
     if name == "odd_static_n":
         ms = [1, 77, 1000, 4096]
+    if name == "llm4096":
+        ms = [1, 16, 45, 128, 300, 512, 1024, 2048, 8192]
     return [dict(m=m) for m in ms]
 
 
@@ -113,6 +116,33 @@ def test_plans_bit_identical_to_oracle(name, mode):
         assert (st.pad_q20, st.occ_q20, st.cmr_q20, st.sia_q20) == (pr.pad_q, pr.occ_q, pr.cmr_q, pr.sia_q)
         assert st.block_bound == pr.block_bound and st.level == want.level and st.pool_size == want.pool_size
         assert st.lds_bytes == max(uks[i].lds_bytes for i, _ in pr.parts)
+        assert (st.k_parts, st.k_part_tiles) == (want.k_parts, want.k_part_tiles), (name, kw)
+        slab = max(uks[i].tm * uks[i].tn for i, _ in pr.parts)
+        assert st.workspace_bytes == (st.n_tiles * st.k_parts * slab * 4 if st.k_parts > 1 else 0)
+
+
+def test_some_plans_split_the_reduce_axis_like_the_oracle():
+    """The shapes of the bit-identity test above include plans with k_parts > 1 (few tiles, long
+    reduce axis) and the switch that turns the rescue off is honoured."""
+    seen = set()
+    for name in ("dense768k3072", "llm4096", "dense768"):
+        op = OPS[name]
+        uks = P.derive_ukernels(op)
+        lop = to_lib_op(op)
+        s = ft.ft_ukernels_derive(lop)
+        t_off = ft.ft_tuning_default()
+        t_off.k_parts_max = 1
+        s_off = ft.ft_ukernels_derive(lop, None, t_off)
+        for kw in shapes_for(name):
+            if kw["m"] == 0:
+                continue
+            st = ft.ft_plan_stats_get(ft.ft_plan_create(lop, s, ft.ft_shape(**kw), HOST))
+            want = P.plan(op, uks, (1,) + tuple(oracle_shape(op, kw)[1:]))
+            assert st.k_parts == want.k_parts
+            seen.add((name, st.k_parts > 1))
+            off = ft.ft_plan_stats_get(ft.ft_plan_create(lop, s_off, ft.ft_shape(**kw), HOST))
+            assert off.k_parts == 1 and off.workspace_bytes == 0
+    assert ("dense768k3072", True) in seen and ("llm4096", True) in seen and ("dense768", True) not in seen
 
 
 @pytest.mark.parametrize("name", ["dense768", "qk", "conv"])

@@ -356,3 +356,88 @@ def test_sia_is_the_weighted_sum_and_top1_is_max():
     pl = P.plan(op, uks, shape, hw=hw, t=t2)
     cands = [p for p in pool if p.in_bound] or pool
     assert pl.program.sia_q == max(p.sia_q for p in cands)
+
+
+# --------------------------------------------------------------------------------------
+# reduce-axis split over workgroups (occupancy rescue)
+# --------------------------------------------------------------------------------------
+def test_compute_eff_of_one_part_closed_form():
+    """One part of a split tile: 128x128, 2x2 waves, its share of the reduce axis 1024 (16 k-tiles),
+    12 bytes of global traffic per output element (fp32 C + the partial written and read once) and
+    4000 clk of exchange latency.  t_c = 2*128*128*1024 / 4096 = 8192 clk;
+    t_g = (256*1024*2 + 128*128*12) / 64 = 11264 clk; t_s = (524288 + 1024*2*512) / 256 = 6144 clk;
+    t_l = 400 * 16 = 6400 clk."""
+    hw = P.default_hw()
+    n, d = P.compute_eff(128, 128, 2, 2, 1024, hw, out_bytes=12, exchange_clk=4000)
+    assert n * (8192 + 5632 + 6400 + 4000) == d * 8192             # alone: t_c + t_g/2 + t_l + X
+    n, d = P.compute_eff(128, 128, 2, 2, 1024, hw, residents=2, out_bytes=12, exchange_clk=4000)
+    assert n * (11264 + (6400 + 4000) // 2) == d * 8192             # shared: max(..) + (t_l + X)/2
+    # without the exchange arguments nothing changes
+    assert P.compute_eff(128, 128, 2, 2, 1024, hw, exchange_clk=0) == P.compute_eff(128, 128, 2, 2, 1024, hw)
+
+
+def test_part_tiles_and_split_rules():
+    hw, t = P.default_hw(), P.default_tuning()
+    assert P.part_tiles(3072, 64, 3) == 16 and P.part_tiles(712, 64, 5) == 3 and P.part_tiles(0, 64, 1) == 1
+    op = P.Op(P.OP_MATMUL, P.F16, n=768, k=3072, m_range=(0, 8192))
+    uks = P.derive_ukernels(op)
+    by = {(u.tm, u.tn, u.gk): u for u in uks}
+    small = by[(64, 128, 1)]                        # 32 accumulator registers, two workgroups per CU
+    assert small.acc_regs <= P.KPART_ACC_MAX and small.max_wg_per_cu >= 2
+    parts = [(small.id, 25)]                        # M = 1600: 25 x 6 = 150 tiles
+    ok = lambda kp, tiles=150, K=3072, tt=t: P.split_allowed(parts, uks, K, kp, tt, hw, tiles)
+    assert ok(1) and ok(2) and ok(3)
+    assert not ok(4)                                # 600 workgroups > 256 CUs x 2
+    assert ok(4, tiles=128) and not ok(4, tiles=129)
+    assert not ok(8, tiles=10)                      # 48 k-tiles / 8 = 6 < k_part_min_tiles
+    assert ok(8, tiles=10, tt=dict(t, k_part_min_tiles=6))
+    assert not ok(2, tt=dict(t, k_parts_max=1))
+    assert not ok(5, tiles=10, K=712)               # 12 k-tiles in runs of 3 make 4 parts, not 5
+    assert not ok(2, K=768)                         # 12 k-tiles / 2 = 6 < 8
+    big = max(uks, key=lambda u: u.acc_regs)
+    if big.acc_regs > P.KPART_ACC_MAX:
+        assert not P.split_allowed([(big.id, 1)], uks, 3072, 2, t, hw, 1)
+    # a uKernel that owns its CU (split-k wave grid) offers one slot per CU
+    solo = next(u for u in uks if u.max_wg_per_cu == 1 and u.acc_regs <= P.KPART_ACC_MAX)
+    assert P.split_allowed([(solo.id, 1)], uks, 3072, 2, t, hw, 128)
+    assert not P.split_allowed([(solo.id, 1)], uks, 3072, 2, t, hw, 129)
+
+
+def test_split_program_counts_workgroups():
+    """Eq. 3, Eq. 5 and SetBound on tiles x k_parts workgroups; Eq. 2 unchanged."""
+    hw, t = P.default_hw(), P.default_tuning()
+    op = P.Op(P.OP_MATMUL, P.F16, n=768, k=3072, m_range=(0, 8192))
+    uks = P.derive_ukernels(op)
+    u = next(u for u in uks if (u.tm, u.tn, u.gk) == (64, 128, 1))
+    cap = P.cmr_cap(uks)
+    whole = P.evaluate([(u.id, 25)], uks, 1, 1600, 768, 0, hw, t, cap)
+    split = P.evaluate([(u.id, 25)], uks, 1, 1600, 768, 0, hw, t, cap, 3, 3072, 4)
+    assert (whole.num_tiles, whole.block_bound, whole.occ_q) == (150, 1, (150 << 20) // 256)
+    assert (split.num_tiles, split.block_bound, split.occ_q) == (150, 2, (450 << 20) // 512)
+    assert split.pad_q == whole.pad_q == 1 << 20 and split.k_parts == 3
+    # its compute_eff is Eq. 6 on 16 k-tiles with the exchange, two workgroups per CU, normalised
+    n, d = P.compute_eff(64, 128, u.gm, u.gn, 1024, hw, residents=2, out_bytes=12, exchange_clk=hw["part_exchange_clk"])
+    assert split.cmr_q == (min((n << 20) // d, cap) << 20) // cap
+    assert split.sia_q == (((split.cmr_q * split.pad_q) >> 20) * split.occ_q) >> 20
+
+
+@pytest.mark.parametrize("M,N,K,expect_split", [(1600, 768, 3072, True), (1600, 768, 768, False),
+                                                (16, 4096, 4096, True), (8192, 4096, 4096, False)])
+def test_plans_split_only_where_the_device_is_underfilled(M, N, K, expect_split):
+    hw, t = P.default_hw(), P.default_tuning()
+    op = P.Op(P.OP_MATMUL, P.BF16, n=N, k=K, m_range=(1, 8192))
+    uks = P.derive_ukernels(op)
+    pl = P.plan(op, uks, (1, M, N, K))
+    assert (pl.k_parts > 1) == expect_split
+    nk = -(-K // 64)
+    assert (pl.k_parts - 1) * pl.k_part_tiles < nk <= pl.k_parts * pl.k_part_tiles      # no empty part
+    if pl.k_parts > 1:
+        per_cu = min([t["zeta"]] + [uks[i].max_wg_per_cu for i, _ in pl.program.parts])
+        assert pl.program.num_tiles * pl.k_parts <= hw["num_cus"] * per_cu
+        assert pl.k_part_tiles >= t["k_part_min_tiles"]
+        assert all(uks[i].acc_regs <= P.KPART_ACC_MAX for i, _ in pl.program.parts)
+    # switching the rescue off gives a plan of whole tiles, never a better-scored one
+    off = P.plan(op, uks, (1, M, N, K), t=dict(t, k_parts_max=1))
+    assert off.k_parts == 1 and off.program.sia_q <= pl.program.sia_q
+    # BMM and the pad baseline never split
+    assert P.plan(op, uks, (1, M, N, K), P.PLAN_PAD_BASELINE).k_parts == 1
