@@ -34,7 +34,7 @@ RING_BYTES = 600e6             # > 256 MB Infinity Cache + 8 x 4 MB L2
 # sweep), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
 # counters read for a plain 1 GiB copy (x2.0 and x1.0); see profiles/ft_dispatch_pmc.md.
 # Counters cannot be read from inside this process, so the figures are those of the committed profile.
-MEASURED_TRAFFIC_BYTES = {"ft_dispatch_dt0_c0": 17.86e6 + 2.94e6, "ft_dispatch_dt0_c1": 21.95e6 + 9.97e6}
+MEASURED_TRAFFIC_BYTES = {"ft_dispatch_dt0_c0": 20.44e6 + 5.32e6, "ft_dispatch_dt0_c1": 21.84e6 + 9.99e6}
 
 
 def geomean(xs):
@@ -158,6 +158,9 @@ def main():
     waste_base = 100.0 * (1.0 - useful / sum(r["base_covered"] for r in rows))
     dom = max(per_class_time, key=per_class_time.get)
     achieved = per_class_flops[dom] / per_class_time[dom] / 1e9          # TFLOP/s
+    achieved_gbs = per_class_bytes[dom] / per_class_time[dom] / 1e6      # GB/s, algorithmic bytes
+    # which roofline binds the dominant kernel's launches: the one that alone would take longer
+    hbm_bound = per_class_bytes[dom] / HBM_PEAK_GBS / 1e9 > per_class_flops[dom] / MFMA_PEAK_TFLOPS / 1e12
     total_flops = sum(r["flops"] for r in rows)
     total_bytes = sum(r["bytes_alg"] for r in rows)
 
@@ -188,17 +191,25 @@ def main():
                         "note": "same sweep, cold, C rounded to fp16 in the epilogue (not the headline: the "
                                 "north star fixes fp32 output)"} if "out16" in variants else None,
         "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 5),
+        "roofline": {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
+                     "achieved": round(achieved_gbs if hbm_bound else achieved, 3),
+                     "peak": HBM_PEAK_GBS if hbm_bound else MFMA_PEAK_TFLOPS,
+                     "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                     "frac": round(achieved_gbs / HBM_PEAK_GBS if hbm_bound else achieved / MFMA_PEAK_TFLOPS, 5),
+                     "other_roof": {"bound": "mfma" if hbm_bound else "hbm",
+                                    "achieved": round(achieved if hbm_bound else achieved_gbs, 3),
+                                    "unit": "TFLOP/s" if hbm_bound else "GB/s",
+                                    "frac": round(achieved / MFMA_PEAK_TFLOPS if hbm_bound else achieved_gbs / HBM_PEAK_GBS, 5)},
                      "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
                      "traffic_note": "L2-miss read + write-back bytes per launch (rocprofv3 --pmc, copy-calibrated; "
                                      "Infinity Cache hits included), algorithmic bytes per launch: %d" % round(
                                          per_class_bytes[dom] / per_class_launches[dom]),
                      "avg_launch_us": round(1e3 * per_class_time[dom] / per_class_launches[dom], 3),
                      "launches": per_class_launches[dom],
-                     "note": "achieved = useful flops of the launches that ran this kernel / their "
-                             "event-timed duration (back-to-back launches on one stream, gaps between "
-                             "kernels included)"},
+                     "note": "achieved = algorithmic bytes (hbm) or useful flops (mfma) of the launches that ran "
+                             "this kernel / their event-timed duration (back-to-back launches on one stream, "
+                             "gaps between kernels included); bound = the roofline that alone takes longer "
+                             "for those launches"},
     }
 
     if not args.no_cpu_baseline:
