@@ -283,7 +283,8 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
  * A, B, C: device pointers owned by the caller (A, B at least 2-byte aligned, C 4-byte
  * aligned; 16-byte aligned A/B with row lengths that are multiples of 8 take the vector
  * path).  hip_stream: a hipStream_t (NULL = default stream).  Asynchronous; allocates
- * nothing and does not synchronise.  An empty plan launches nothing.
+ * nothing and does not synchronise.  An empty plan launches nothing.  The current HIP device must
+ * be the one the plan was created on (else FT_ERR_INVALID_ARG).
  * ------------------------------------------------------------------------------------- */
 ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, void *hip_stream);
 

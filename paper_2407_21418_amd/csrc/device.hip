@@ -126,6 +126,12 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
     if (plan->st.n_tiles == 0) return FT_OK;
     if (!A || !B || !C) return FT_ERR_INVALID_ARG;
     if (!plan->d_descs) return FT_ERR_INVALID_ARG;              // host-only plan
+    {
+        int dev = -1;                                           // the plan's tables live on one device
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if (dev != plan->device) return FT_ERR_INVALID_ARG;
+    }
     if (plan->st.kernel_class >= FT_NUM_CLASSES || plan->op.dtype > 1) return FT_ERR_UNSUPPORTED;
     ftk::KArgs a;
     fill_args(plan, A, B, C, bias, &a);

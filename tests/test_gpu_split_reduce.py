@@ -10,7 +10,9 @@ import synth_inputs as si
 from oracle import contraction as oc
 from oracle import planner as P
 
-from gpu_util import check, check_epilogue, matmul_op, run, run_epilogue
+import torch
+
+from gpu_util import GUARD, alloc_out, check, check_epilogue, dev_bits, matmul_op, out_view, run, run_epilogue
 
 pytestmark = pytest.mark.gpu
 
@@ -106,7 +108,8 @@ def test_permutation_matrix_stays_bit_exact_when_split(dtype):
         assert np.array_equal(got, want), (u.tm, u.tn, u.wm, u.wn)
 
 
-@pytest.mark.parametrize("M,N,K", [(80, 768, 3072), (272, 768, 3072), (528, 768, 3072), (1232, 768, 3072), (16, 4096, 4096)])
+@pytest.mark.parametrize("M,N,K", [(80, 768, 3072), (272, 768, 3072), (528, 768, 3072), (1232, 768, 3072), (16, 4096, 4096),
+                                   (1600, 768, 3072), (400, 1536, 4096), (200, 5120, 2048)])
 def test_planner_chosen_split_matches_oracle(M, N, K):
     """Patchwork plans of shapes with few tiles: the library's choice of k_parts is the oracle's,
     and the result is within tolerance."""
@@ -143,3 +146,32 @@ def test_unaligned_operands_ignore_the_split():
     assert ft.ft_plan_stats_get(plan).k_parts == 3
     ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
     check(run(plan, A, B, M * N), ref, refabs, "general path, split ignored")
+
+
+def test_split_plan_through_the_timing_entry_points_and_a_graph():
+    """Back-to-back launches of one split plan on rotating buffers, eagerly and as a replayed HIP
+    graph (the arrival counters are reset by the kernel itself, no memset node): every buffer set
+    holds the same bits as a single eager launch."""
+    M, N, K = 1600, 768, 3072
+    p = si.config1_problem(M, N, K)
+    op = matmul_op(N, K, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    assert ft.ft_plan_stats_get(plan).k_parts > 1
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    single = run(plan, p["A"], p["B"], M * N)
+    check(single, ref, refabs, "single launch")
+    side = torch.cuda.Stream()
+    n_sets = 3
+    A = [dev_bits(p["A"]) for _ in range(n_sets)]
+    B = [dev_bits(p["B"]) for _ in range(n_sets)]
+    for use_graph in (False, True, True):
+        bufs = [alloc_out(M * N) for _ in range(n_sets)]
+        torch.cuda.synchronize()
+        ms = ft.ft_launch_timed(plan, [t.data_ptr() for t in A], [t.data_ptr() for t in B],
+                                [b.data_ptr() + 4 * GUARD for b in bufs], side.cuda_stream, 7, graph=use_graph)
+        torch.cuda.synchronize()
+        assert 0.0 < ms < 10.0
+        for b in bufs:
+            assert np.array_equal(out_view(b, M * N), single), f"timed launches, graph={use_graph}"
+        assert np.array_equal(run(plan, p["A"], p["B"], M * N), single), "eager launch between timed runs"
