@@ -175,3 +175,28 @@ def test_split_plan_through_the_timing_entry_points_and_a_graph():
         for b in bufs:
             assert np.array_equal(out_view(b, M * N), single), f"timed launches, graph={use_graph}"
         assert np.array_equal(run(plan, p["A"], p["B"], M * N), single), "eager launch between timed runs"
+
+
+def test_relaunch_with_other_inputs_sees_no_stale_partials():
+    """The workspace slabs are reused by every launch of a plan: launches with different operands,
+    back to back on one stream without host synchronisation in between, must each give their own
+    result (a partial tile left over from the previous launch, in any cache, would show)."""
+    M, N, K = 1600, 768, 3072
+    op = matmul_op(N, K, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    assert ft.ft_plan_stats_get(plan).k_parts > 1
+    g = np.random.default_rng(77)
+    sets = []
+    for i in range(3):
+        A = si.normal_bits(g, (M, K), 1.0 + i, ft.FT_F16)
+        B = si.normal_bits(g, (K, N), 0.02 * (i + 1), ft.FT_F16)
+        sets.append((A, B, dev_bits(A), dev_bits(B), alloc_out(M * N)))
+    stream = torch.cuda.current_stream().cuda_stream
+    for rep in range(4):                       # 12 launches, operands changing every launch
+        for (_, _, dA, dB, buf) in sets:
+            ft.ft_launch(plan, dA.data_ptr(), dB.data_ptr(), buf.data_ptr() + 4 * GUARD, stream)
+    torch.cuda.synchronize()
+    for i, (A, B, _, _, buf) in enumerate(sets):
+        ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
+        check(out_view(buf, M * N), ref, refabs, f"operand set {i} after interleaved launches")
