@@ -15,7 +15,7 @@ but NOT in cache (each launch uses the next of a ring of buffer sets totalling >
 The same measurement with a single, cache-warm buffer set is reported beside it as
 `warm_cache`, and the pad-to-library baseline plan as `pad_baseline`.
 
-Prints ONE JSON line on stdout; per-GEMM details go to gpurun_out/bench_detail.json.
+Prints ONE JSON line on stdout; per-GEMM details go to the JSON file named by --detail.
 """
 import argparse
 import json
@@ -56,7 +56,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by rows with no exchange step, see DESIGN.md)", file=sys.stderr)
+              "(the path shards by rows with no exchange step)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

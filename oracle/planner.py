@@ -510,7 +510,7 @@ def split_allowed(parts, uks, K, k_parts, t, hw, tiles):
 
 def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, k_parts=1, K=0, out_bytes=4):
     """Cached-metric evaluation of one program (Sec. 5.2) on the actual shape.  With k_parts > 1
-    every tile is worked on by k_parts workgroups (occupancy rescue, see split_k_note): the
+    every tile is worked on by k_parts workgroups (occupancy rescue, see split_allowed): the
     workgroup count of Eq. 3, Eq. 5 and SetBound is k_parts times the tile count, and compute_eff
     is taken on one part of the reduce axis."""
     Wp = ceil_by(N if tau == 0 else M, GRANULE)
