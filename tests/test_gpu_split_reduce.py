@@ -200,3 +200,31 @@ def test_relaunch_with_other_inputs_sees_no_stale_partials():
     for i, (A, B, _, _, buf) in enumerate(sets):
         ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
         check(out_view(buf, M * N), ref, refabs, f"operand set {i} after interleaved launches")
+
+
+@pytest.mark.parametrize("M,N,K,forced", [(64, 64, 65536, 0), (40, 128, 16384, 0), (256, 256, 4096, 64), (100, 72, 4104, 64)])
+def test_extreme_reduce_extents_and_part_counts(M, N, K, forced):
+    """Very long reduce axes on one or two tiles (the planner splits as far as its rules allow) and
+    the largest part count a caller may force: 64 parts of a single k-tile each (65 k-tiles with a
+    tail of 8 in the last case, so the last part holds the zero-filled tail alone)."""
+    g = np.random.default_rng(M + K)
+    A = si.normal_bits(g, (M, K), 1.0, ft.FT_BF16)
+    B = si.normal_bits(g, (K, N), 0.05, ft.FT_BF16)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_BF16, n=N, k=K, m_lo=0, m_hi=4096))
+    s = ft.ft_ukernels_derive(op)
+    if forced:
+        infos = [ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))]
+        Hp = -(-M // 16) * 16
+        u = next(u for u in infos if Hp % u.tm == 0 and u.acc_regs <= P.KPART_ACC_MAX)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED,
+                                 ft.ft_forced_program(k1=u.id, count1=Hp // u.tm, k_parts=forced))
+        nk = -(-K // 64)
+        per = -(-nk // min(forced, nk))
+        assert ft.ft_plan_stats_get(plan).k_parts == -(-nk // per)
+    else:
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+        assert ft.ft_plan_stats_get(plan).k_parts > 1
+    ref, refabs = oc.matmul(A, B, si.BF16, want_abs=True)
+    got = run(plan, A, B, M * N)
+    check(got, ref, refabs, f"{M}x{N}x{K} forced {forced}")
+    assert np.array_equal(run(plan, A, B, M * N), got)
