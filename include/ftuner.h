@@ -102,6 +102,12 @@ typedef struct ft_tuning {
      * compute_eff is taken on one part), as long as all workgroups are resident at once.      */
     uint32_t k_parts_max;                           /* most parts per tile; 1 = never split: 8    */
     uint32_t k_part_min_tiles;                      /* fewest k-tiles (of tk) a part may get: 8   */
+    /* Operators with two dynamic space axes (Fig. 4(d)): programs are also scored with a second,
+     * narrower uKernel covering what the part's own tiles leave of the other axis (up to four
+     * uKernel shapes per launch).                                                                */
+    uint32_t second_axis_strips;                    /* 0: off (default: measured slower on gfx950,
+                                                       where the fp32 score matrix is bound by its
+                                                       own write), 1: on                           */
 } ft_tuning;
 enum { FT_SIA_LINEAR = 0, FT_SIA_PRODUCT = 1 };
 
@@ -238,6 +244,12 @@ typedef struct ft_plan_stats {
     uint32_t k_parts;              /* workgroups per tile along the reduce axis (1 = no split)*/
     uint32_t k_part_tiles;         /* k-tiles (of tk) per part; the last part may get fewer  */
     uint64_t workspace_bytes;      /* device memory the plan owns for the partial tiles      */
+    /* Second-axis strips (operators with two dynamic space axes, Fig. 4(d)): part i places
+     * main_tiles[i] tiles of its own uKernel across the other axis and, if strip_ukernel_id[i] is not
+     * UINT32_MAX, strip_tiles[i] tiles of that narrower uKernel (same extent along tau) after them. */
+    uint32_t main_tiles[2];
+    uint32_t strip_ukernel_id[2];
+    uint32_t strip_tiles[2];
 } ft_plan_stats;
 
 typedef struct ft_plan ft_plan;
@@ -257,6 +269,9 @@ ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, u
  * the number of workgroups (= tiles).  The order is a permutation of the table: every XCD (a
  * group of CUs with its own L2; workgroup b runs on XCD b % num_xcds) takes a contiguous slice of
  * each constituent's tiles, walked in 2-D groups.  order: host pointer, caller-owned.
+ * A plan with second-axis strips (up to four uKernel shapes) is walked in table order, dealt to the
+ * XCDs in chunks of 16 consecutive descriptors; its grid is rounded up to whole rounds of chunks, so
+ * *n may exceed the tile count and order[b] = UINT32_MAX marks a workgroup with nothing to do.
  * With k_parts = P > 1 every entry of this order is worked on by P workgroups of the same XCD:
  * workgroup b takes entry (b / (P*X))*X + b % X and part (b / X) % P, X = num_xcds. */
 ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t cap, uint64_t *n);

@@ -49,7 +49,7 @@ def default_tuning():
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
                 zeta=2, rest_regs=72, psi_num=1, psi_den=64, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT,
-                k_parts_max=8, k_part_min_tiles=8)
+                k_parts_max=8, k_part_min_tiles=8, second_axis_strips=0)
 
 
 # --------------------------------------------------------------------------------------
@@ -409,6 +409,9 @@ class Program:
     k1: int = -1
     k2: int = -1
     k_parts: int = 1                        # workgroups per tile along the reduce axis
+    # second-axis strips (two dynamic space axes): per part (strip ukernel id or -1, tiles of the
+    # part's own uKernel across the other axis, tiles of the strip uKernel after them)
+    strips: List[Tuple[int, int, int]] = field(default_factory=list)
 
 
 @dataclass
@@ -508,26 +511,86 @@ def split_allowed(parts, uks, K, k_parts, t, hw, tiles):
     return nk // k_parts >= max(t.get("k_part_min_tiles", 1), 1) and ceil_div(nk, per) == k_parts
 
 
-def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, k_parts=1, K=0, out_bytes=4):
+STRIP_CHOICES = 3       # strip uKernels tried per part (the widest ones that pad less than one more K1 tile)
+
+
+def strip_choices(u, uks, Wp, tau):
+    """Second-axis combination for one part (Fig. 4(d): both space axes of a batched Matmul are
+    dynamic): along the other axis sigma a part of uKernel K1 places Num1 = floor(W' / K1.ext)
+    whole tiles and covers the rest with Num2 tiles of a narrower uKernel K2 that has K1's extent
+    along tau (so the rows of the two line up): W' = Num1*K1 + Num2*K2 - padding, Alg. 2's form
+    with K1 given.  Candidates for K2: every narrower uKernel with that tau extent whose Num2 tiles
+    pad less than one more K1 tile would, widest first (ties: lower index), at most STRIP_CHOICES
+    of them.  None if K1 divides W' or is wider than W'.
+    Returns a list of (K2 id, Num1, Num2)."""
+    e = _ext(u, 1 - tau)
+    n_full, rem = Wp // e, Wp % e
+    if n_full < 1 or rem == 0:
+        return []
+    cands = [v for v in uks
+             if _ext(v, tau) == _ext(u, tau) and _ext(v, 1 - tau) < e and ceil_by(rem, _ext(v, 1 - tau)) < e]
+    cands.sort(key=lambda v: (-_ext(v, 1 - tau), v.id))
+    return [(v.id, n_full, ceil_div(rem, _ext(v, 1 - tau))) for v in cands[:STRIP_CHOICES]]
+
+
+def strip_variants(parts, uks, Wp, tau):
+    """Every way to give the parts of a program a strip or none (at least one strip), in a fixed
+    order: the choices of the first part vary slowest, 'no strip' comes first."""
+    per_part = []
+    for uid, _ in parts:
+        u = uks[uid]
+        per_part.append([(-1, ceil_div(Wp, _ext(u, 1 - tau)), 0)] + strip_choices(u, uks, Wp, tau))
+    out = [[]]
+    for choices in per_part:
+        out = [prev + [c] for prev in out for c in choices]
+    return [v for v in out if any(c[0] >= 0 for c in v)]
+
+
+def constituents(parts, strips, uks, batch, M, N, tau):
+    """The uKernel-homogeneous regions of a program in placement order: for each one
+    (ukernel id, tiles per batch entry, useful output elements per batch entry, area per batch entry)."""
+    H = M if tau == 0 else N
+    W = N if tau == 0 else M
+    Wp = ceil_by(W, GRANULE)
+    off, out = 0, []
+    for i, (uid, cnt) in enumerate(parts):
+        u = uks[uid]
+        e = _ext(u, tau)
+        rows = max(0, min(H - off, cnt * e))
+        off += cnt * e
+        if strips is None or strips[i][0] < 0:
+            across = ceil_div(Wp, _ext(u, 1 - tau))
+            out.append((uid, cnt * across, rows * W, cnt * across * u.tm * u.tn))
+        else:
+            sid, n_full, n_strip = strips[i]
+            v = uks[sid]
+            w_main = min(W, n_full * _ext(u, 1 - tau))
+            out.append((uid, cnt * n_full, rows * w_main, cnt * n_full * u.tm * u.tn))
+            out.append((sid, cnt * n_strip, rows * (W - w_main), cnt * n_strip * v.tm * v.tn))
+    return out
+
+
+def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, k_parts=1, K=0, out_bytes=4, strips=None):
     """Cached-metric evaluation of one program (Sec. 5.2) on the actual shape.  With k_parts > 1
     every tile is worked on by k_parts workgroups (occupancy rescue, see split_allowed): the
     workgroup count of Eq. 3, Eq. 5 and SetBound is k_parts times the tile count, and compute_eff
     is taken on one part of the reduce axis."""
-    Wp = ceil_by(N if tau == 0 else M, GRANULE)
-    tiles_per_batch, area = 0, 0
-    for uid, cnt in parts:
-        u = uks[uid]
-        across = ceil_div(Wp, _ext(u, 1 - tau))
-        tiles_per_batch += cnt * across
-        area += cnt * across * u.tm * u.tn
+    order = sorted(range(len(parts)), key=lambda i: parts[i])
+    parts_sorted = [parts[i] for i in order]
+    strips_sorted = [strips[i] for i in order] if strips is not None else None
+    cons = constituents(parts_sorted, strips_sorted, uks, batch, M, N, tau)
+    tiles_per_batch = sum(c[1] for c in cons)
+    area = sum(c[3] for c in cons)
     T = batch * tiles_per_batch
     Wg = T * k_parts
-    p = Program(parts=sorted(parts), num_tiles=T, area=area, k_parts=k_parts)
+    p = Program(parts=parts_sorted, num_tiles=T, area=area, k_parts=k_parts,
+                strips=strips_sorted if strips_sorted is not None else [])
     p.k1 = parts[0][0]
     p.k2 = parts[1][0] if len(parts) > 1 else -1
     # SetBound (Alg. 1): block.bound = min(K.wkl.block, zeta)
     p.block_bound = min(max(1, ceil_div(Wg, hw["num_cus"])), t["zeta"])
-    p.in_bound = all(uks[uid].max_wg_per_cu >= p.block_bound for uid, _ in parts)
+    ids = [c[0] for c in cons]
+    p.in_bound = all(uks[uid].max_wg_per_cu >= p.block_bound for uid in ids)
     occ = occ_fraction(Wg, hw["num_cus"])
     pad = pad_fraction(M * N, area)
     p.occ_q = (occ[0] << Q) // occ[1]
@@ -538,13 +601,13 @@ def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, k_parts=1, K=0, out_byt
     # its constituents (Sec. 5.2).  Each constituent contributes the value cached for the number
     # of workgroups that share a CU on this shape: min(its capacity, block.bound)
     acc = 0
-    for uid, _ in parts:
+    for uid in ids:
         acc += (min(cmr_split(uks[uid], p.block_bound, k_parts, K, hw, out_bytes), cap_q) << Q) // cap_q
-    p.cmr_q = acc // len(parts)
+    p.cmr_q = acc // len(ids)
     if t.get("sia_form", SIA_LINEAR) == SIA_LINEAR:
         p.sia_q = t["c0"] * p.cmr_q + t["c1"] * p.pad_q + t["c2"] * p.occ_q   # Eq. 1 as printed
     else:
-        p.sia_q = sia_product(p.parts, uks, batch, M, N, tau, hw, t, cap_q, p.block_bound, k_parts, K, out_bytes)
+        p.sia_q = sia_product(cons, uks, batch, hw, t, cap_q, p.block_bound, k_parts, K, out_bytes)
     return p
 
 
@@ -572,32 +635,26 @@ def cmr_split(u, block_bound, k_parts, K, hw, out_bytes):
     return (cn << Q) // cd
 
 
-def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q, block_bound, k_parts=1, K=0, out_bytes=4):
+def sia_product(cons, uks, batch, hw, t, cap_q, block_bound, k_parts=1, K=0, out_bytes=4):
     """Eq. 1 in its multiplicative (log-domain) form, evaluated per uKernel from the metrics
-    cached in each uKernel's data structure (Sec. 5.2): each constituent K gets
-    CMR^c0 * Pad^c1 * Occ^c2 from its own sub-workload -- the rows (columns) it covers, its own
-    tile count.  The product is what a throughput estimate looks like (fraction of cores busy x
-    fraction of useful work x per-core efficiency); a weighted sum of the logarithms of the
-    three metrics ranks single-uKernel programs identically.  The paper averages the two
-    constituents of a program without saying how; here it is the harmonic mean weighted by the
-    useful output elements u_i each constituent produces,
-        score = (u_1 + u_2) / (u_1 / x_1 + u_2 / x_2),
+    cached in each uKernel's data structure (Sec. 5.2): each constituent K (a region of the
+    program tiled by one uKernel, see constituents()) gets CMR^c0 * Pad^c1 * Occ^c2 from its own
+    sub-workload -- the outputs it covers, its own tile count.  The product is what a throughput
+    estimate looks like (fraction of cores busy x fraction of useful work x per-core efficiency);
+    a weighted sum of the logarithms of the three metrics ranks single-uKernel programs
+    identically.  The paper averages the constituents of a program without saying how; here it is
+    the harmonic mean weighted by the useful output elements u_i each constituent produces,
+        score = sum(u_i) / sum(u_i / x_i),
     i.e. total work over the time the constituents need at their own rates (an unweighted mean
     lets a 16-row tail decide the fate of a program whose other constituent does 95 % of the
     work; an arithmetic mean hides a slow constituent).  Fixed point: every multiply is
-    floor(x * y / 2^20); the mean is floor of the exact ratio of the q20 values."""
-    H = M if tau == 0 else N
-    W = N if tau == 0 else M
-    Wp = ceil_by(W, GRANULE)
-    off, terms = 0, []
-    for uid, cnt in parts_sorted:                       # placement order along tau
+    floor(x * y / 2^20); the mean is floor of the exact ratio of the q20 values, computed as
+    (sum u_i) * prod x_i / sum_i (u_i * prod_{j != i} x_j).  A constituent with no useful output
+    (a strip or tail that lies wholly in the padding) carries no weight."""
+    terms = []
+    for uid, tiles, useful, area in cons:
         u = uks[uid]
-        e = _ext(u, tau)
-        across = ceil_div(Wp, _ext(u, 1 - tau))
-        T = batch * cnt * across * k_parts                  # workgroups of this constituent
-        useful = max(0, min(H - off, cnt * e)) * W
-        area = cnt * across * u.tm * u.tn
-        off += cnt * e
+        T = batch * tiles * k_parts                         # workgroups of this constituent
         cmr_q = (min(cmr_split(u, block_bound, k_parts, K, hw, out_bytes), cap_q) << Q) // cap_q
         pad_q = (useful << Q) // area
         on, od = occ_fraction(T, hw["num_cus"])
@@ -607,36 +664,47 @@ def sia_product(parts_sorted, uks, batch, M, N, tau, hw, t, cap_q, block_bound, 
             for _ in range(c):
                 x = (x * q) >> Q
         terms.append((useful, x))
+    if len(terms) > 1:
+        terms = [(u_, x) for u_, x in terms if u_ > 0] or terms[:1]
     if any(x == 0 for _, x in terms):
         return 0
     if len(terms) == 1:
         return terms[0][1]
-    (u1, x1), (u2, x2) = terms
-    return ((u1 + u2) * x1 * x2) // (u1 * x2 + u2 * x1)
+    prod_all = 1
+    for _, x in terms:
+        prod_all *= x
+    den = sum(u_ * (prod_all // x) for u_, x in terms)
+    return (sum(u_ for u_, _ in terms) * prod_all) // den
 
 
-def emit(parts, uks, batch, M, N, tau):
+def emit(parts, uks, batch, M, N, tau, strips=None):
     """Tile descriptors in canonical order: uKernel id, batch, m0, n0 ascending.  Along tau
-    the constituent with the lower id (larger tile) comes first."""
+    the part with the lower id (larger tile) comes first; along the other axis a part's own tiles
+    come first, then its strip's."""
     descs = []
     off = 0
     Wp = ceil_by(N if tau == 0 else M, GRANULE)
-    for uid, cnt in sorted(parts):
+    order = sorted(range(len(parts)), key=lambda i: parts[i])
+    for i in order:
+        uid, cnt = parts[i]
         u = uks[uid]
-        across = ceil_div(Wp, _ext(u, 1 - tau))
-        if tau == 0:
-            m_list = [off + i * u.tm for i in range(cnt)]
-            n_list = [j * u.tn for j in range(across)]
+        e_tau = _ext(u, tau)
+        if strips is None or not strips or strips[i][0] < 0:
+            runs = [(u, 0, ceil_div(Wp, _ext(u, 1 - tau)))]
         else:
-            m_list = [i * u.tm for i in range(across)]
-            n_list = [off + j * u.tn for j in range(cnt)]
-        off += cnt * _ext(u, tau)
-        for b in range(batch):
-            for m0 in m_list:
-                for n0 in n_list:
-                    mv, nv = min(u.tm, M - m0), min(u.tn, N - n0)
-                    descs.append(Desc(uid, b, m0, n0, mv, nv,
-                                      1 if (mv < u.tm or nv < u.tn) else 0))
+            sid, n_full, n_strip = strips[i]
+            runs = [(u, 0, n_full), (uks[sid], n_full * _ext(u, 1 - tau), n_strip)]
+        for v, start, count in runs:
+            along = [off + j * e_tau for j in range(cnt)]
+            across = [start + j * _ext(v, 1 - tau) for j in range(count)]
+            m_list, n_list = (along, across) if tau == 0 else (across, along)
+            for b in range(batch):
+                for m0 in m_list:
+                    for n0 in n_list:
+                        mv, nv = min(v.tm, M - m0), min(v.tn, N - n0)
+                        descs.append(Desc(v.id, b, m0, n0, mv, nv, 1 if (mv < v.tm or nv < v.tn) else 0))
+        off += cnt * e_tau
+    descs.sort(key=lambda d: (d.ukernel_id, d.batch, d.m0, d.n0))
     return descs
 
 
@@ -674,22 +742,31 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         # Occupancy rescue (Matmul): every program is also scored with its tiles split over
         # 2, 3, ... workgroups along the reduce axis, where that is allowed
         choices = K_PART_CHOICES if op.kind == OP_MATMUL else (1,)
+        # Two dynamic space axes: every program is also scored with second-axis strips
+        ms, ns, _ = op.gemm_static()
+        two_axes = ms == 0 and ns == 0 and t.get("second_axis_strips", 0) != 0
+        Wp = ceil_by(N if tau == 0 else M, GRANULE)
         pool = []
         for parts in covers:
             whole = evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q)
             pool.append(whole)
             pool.extend(evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, kp, K, op.out_bytes)
                         for kp in choices[1:] if split_allowed(parts, uks, K, kp, t, hw, whole.num_tiles))
+            if two_axes:
+                pool.extend(evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, strips=strips)
+                            for strips in strip_variants(parts, uks, Wp, tau))
         # runtime stage: the programs whose uKernels fit block.bound workgroups per CU on this
         # shape (SetBound); all of them if none does
         cands = [p for p in pool if p.in_bound]
         pl.level = 0
         if not cands:
             cands, pl.level = pool, 1
-        # Top-1 by SIA; ties: fewer parts, fewer tiles, then lower K1 index, then lower K2 index
-        prog = min(cands, key=lambda p: (-p.sia_q, p.k_parts, p.num_tiles, p.k1, p.k2))
+        # Top-1 by SIA; ties: fewer parts, fewer tiles, no strips, then lower K1 index, then lower K2 index
+        # (two strip variants of one program that tie: the one listed first by strip_variants)
+        prog = min(enumerate(cands), key=lambda ip: (-ip[1].sia_q, ip[1].k_parts, ip[1].num_tiles, len(ip[1].strips) > 0,
+                                                     ip[1].k1, ip[1].k2, ip[0]))[1]
     pl.program = prog
-    pl.descs = emit(prog.parts, uks, batch, M, N, tau)
+    pl.descs = emit(prog.parts, uks, batch, M, N, tau, prog.strips or None)
     pl.covered = batch * prog.area
     pl.k_parts = prog.k_parts
     pl.k_part_tiles = part_tiles(K, uks[prog.parts[0][0]].tk, prog.k_parts)

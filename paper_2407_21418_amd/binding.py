@@ -48,7 +48,7 @@ class ft_hw_model(_S):
 class ft_tuning(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "eps_min_pm", "eps_max_pm", "eps_step_pm", "lam_max_pm", "lam_min_pm", "lam_step_pm",
-        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form", "k_parts_max", "k_part_min_tiles")]
+        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form", "k_parts_max", "k_part_min_tiles", "second_axis_strips")]
 
 
 class ft_op_desc(_S):
@@ -82,7 +82,7 @@ class ft_plan_stats(_S):
                 ("pool_size", u32), ("level", u32), ("pad_q20", u32), ("occ_q20", u32), ("cmr_q20", u32),
                 ("lds_bytes", u32), ("kernel_class", u32), ("sia_q20", u64), ("n_tiles", u64),
                 ("useful_elems", u64), ("covered_elems", u64), ("k_parts", u32), ("k_part_tiles", u32),
-                ("workspace_bytes", u64)]
+                ("workspace_bytes", u64), ("main_tiles", u32 * 2), ("strip_ukernel_id", u32 * 2), ("strip_tiles", u32 * 2)]
 
 
 class ft_pool_entry(C.Structure):
@@ -249,7 +249,8 @@ def ft_plan_descriptors(p: Plan) -> bytes:
 
 
 def ft_plan_launch_order(p: Plan):
-    """Descriptor index taken by each workgroup of the launch (a permutation of the table)."""
+    """Descriptor index taken by each workgroup of the launch (a permutation of the table; for a
+    plan walked in table order followed by 0xFFFFFFFF entries for the idle workgroups of the last round)."""
     n = u64()
     _check(lib().ft_plan_launch_order(p.ptr, None, 0, C.byref(n)), "ft_plan_launch_order")
     buf = (u32 * max(1, n.value))()

@@ -51,9 +51,12 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const fl
         a->cstride = p->op.stride; a->cpad = p->op.pad;
         a->lda = 0; a->strideA = 0;
     }
-    a->slot_ukernel[0] = p->slot_id[0]; a->slot_ukernel[1] = p->slot_id[1];
-    a->slot_code[0] = p->slot_code[0]; a->slot_code[1] = p->slot_code[1];
-    a->slot_stages[0] = p->slot_stages[0]; a->slot_stages[1] = p->slot_stages[1];
+    for (int i = 0; i < 4; ++i) {
+        a->slot_ukernel[i] = p->slot_id[i];
+        a->slot_code[i] = p->slot_code[i];
+        a->slot_stages[i] = p->slot_stages[i];
+    }
+    a->table_order = p->table_order ? 1u : 0u;
     for (int i = 0; i < 2; ++i) {
         a->slot_first[i] = p->slot_first[i];
         a->slot_rows[i] = p->slot_rows[i];
@@ -142,10 +145,11 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
     bool fast = a.is_conv ? (aligned && a.Cin % 64 == 0 && a.N % 8 == 0)
                           : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
     if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
-        a.slot_code[0] = (uint32_t)ft_general_code((int)a.slot_code[0]);
-        a.slot_code[1] = (uint32_t)ft_general_code((int)a.slot_code[1]);
-        // the twins of the narrowest tiles exist in the general dispatcher only
-        if (ft_is_partial_code((int)a.slot_code[0]) || ft_is_partial_code((int)a.slot_code[1])) fast = false;
+        for (int i = 0; i < 4; ++i) {
+            a.slot_code[i] = (uint32_t)ft_general_code((int)a.slot_code[i]);
+            // the twins of the narrowest tiles exist in the general dispatcher only
+            if (ft_is_partial_code((int)a.slot_code[i])) fast = false;
+        }
         a.k_parts = 1;                 // these bodies walk the whole reduce axis in one workgroup
     }
     int rc;
@@ -154,8 +158,13 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
     } else {
         // the general bodies stage through registers into two LDS stages, whatever ring depth the
         // uKernel has on the LDS-DMA path
-        const uint32_t lds = 2 * std::max(ft_stage_bytes_of_code((int)a.slot_code[0]), ft_stage_bytes_of_code((int)a.slot_code[1]));
-        const int acc = std::max(ft_acc_of_code((int)a.slot_code[0]), ft_acc_of_code((int)a.slot_code[1]));
+        uint32_t stage = 0;
+        int acc = 0;
+        for (int i = 0; i < 4; ++i) {
+            stage = std::max(stage, ft_stage_bytes_of_code((int)a.slot_code[i]));
+            acc = std::max(acc, ft_acc_of_code((int)a.slot_code[i]));
+        }
+        const uint32_t lds = 2 * stage;
         rc = kLaunchGeneric[plan->op.dtype][acc <= 64 ? 0 : 1](&a, lds, hip_stream);
     }
     if (rc != 0) return hip_fail((hipError_t)rc);

@@ -36,6 +36,29 @@ namespace ftk {
 
 __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    // The arguments span several cache lines and the compiler loads each field right before its
+    // first use, so a cold scalar cache would be missed several times in a row (about half a
+    // microsecond each, on the critical path of every workgroup).  Touch every line once, up front
+    // and in parallel; the later loads hit.  Measured: +2.5 % on the sweep of small GEMMs (a few
+    // hundred workgroups per launch, all in their first round); the general dispatchers, whose
+    // launches on odd-pitch attention shapes have thousands of short workgroups, lost 10-30 % with
+    // it and go without.
+#ifndef FT_GENERIC
+    {
+        const auto ka = __builtin_amdgcn_kernarg_segment_ptr();
+        static_assert(sizeof(KArgs) > 0x100 && sizeof(KArgs) <= 0x140, "one load per 64-byte line of the arguments");
+        uint32_t w0, w1, w2, w3, w4;
+        asm volatile("s_load_dword %0, %5, 0x0\n\t"
+                     "s_load_dword %1, %5, 0x40\n\t"
+                     "s_load_dword %2, %5, 0x80\n\t"
+                     "s_load_dword %3, %5, 0xc0\n\t"
+                     "s_load_dword %4, %5, 0x100\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=s"(w0), "=s"(w1), "=s"(w2), "=s"(w3), "=s"(w4)
+                     : "s"(ka)
+                     : "memory");
+    }
+#endif
     LaunchOrder o;
     o.n[0] = g.slot_first[1] - g.slot_first[0];
     o.n[1] = g.n_tiles - g.slot_first[1];
@@ -54,10 +77,17 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
         if (b >= g.n_tiles) return;
     }
     uint32_t slot;
-    const uint32_t t = tile_of_workgroup(o, b, &slot);
+    const uint32_t t = g.table_order ? table_index_of_workgroup(b, o.nx) : tile_of_workgroup(o, b, &slot);
+    if (t >= g.n_tiles) return;                 // table order: the grid is rounded up to whole rounds of chunks
     const TileDesc d = g.descs[t];
-    const uint32_t code = slot ? g.slot_code[1] : g.slot_code[0];
-    const uint32_t stages = slot ? g.slot_stages[1] : g.slot_stages[0];
+    // a plan with second-axis strips has up to four uKernel shapes and is walked in table order:
+    // the descriptor's uKernel id names the slot (selects, no indexing: the arguments stay in SGPRs)
+    if (g.table_order) {
+        const uint32_t id = __builtin_amdgcn_readfirstlane(d.ukernel_id);       // uniform per workgroup
+        slot = id == g.slot_ukernel[0] ? 0u : id == g.slot_ukernel[1] ? 1u : id == g.slot_ukernel[2] ? 2u : 3u;
+    }
+    const uint32_t code = slot == 0 ? g.slot_code[0] : slot == 1 ? g.slot_code[1] : slot == 2 ? g.slot_code[2] : g.slot_code[3];
+    const uint32_t stages = slot == 0 ? g.slot_stages[0] : slot == 1 ? g.slot_stages[1] : slot == 2 ? g.slot_stages[2] : g.slot_stages[3];
     switch (code) {
 #ifdef FT_GENERIC
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
@@ -100,11 +130,9 @@ extern "C" int FT_LAUNCH_NAME(const ftk::KArgs *args, uint32_t lds_bytes, void *
         if (e != hipSuccess) return (int)e;
         attr_done = true;
     }
-    uint32_t grid = args->n_tiles;
-    if (args->k_parts > 1) {
-        const uint32_t nx = args->num_xcds ? args->num_xcds : 1;
-        grid = (args->n_tiles + nx - 1) / nx * nx * args->k_parts;
-    }
+    const uint32_t nx = args->num_xcds ? args->num_xcds : 1;
+    uint32_t grid = args->table_order ? ftk::table_grid(args->n_tiles, nx) : args->n_tiles;
+    if (args->k_parts > 1) grid = (grid + nx - 1) / nx * nx * args->k_parts;
     hipLaunchKernelGGL(ftk::FT_KERNEL_NAME, dim3(grid), dim3(256), lds_bytes,
                        static_cast<hipStream_t>(stream), *args);
     return (int)hipGetLastError();

@@ -22,9 +22,11 @@ struct ft_plan {
     ft_plan_stats st;
     std::vector<ft_tile_desc> descs;
     // launch parameters
-    uint32_t slot_id[2];
-    uint32_t slot_code[2];
-    uint32_t slot_stages[2];
+    uint32_t slot_id[4];                                   // uKernels of the plan (2 parts + their strips)
+    uint32_t slot_code[4];
+    uint32_t slot_stages[4];
+    uint32_t n_slots;
+    bool table_order;                                      // workgroup b takes descriptor b (plans with strips)
     uint32_t slot_first[2], slot_rows[2], slot_cols[2];   // tile grid of each constituent in the table
     uint32_t slot_group[2];                                // tile rows per group of the launch order
     uint32_t num_xcds;

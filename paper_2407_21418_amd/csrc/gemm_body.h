@@ -44,9 +44,10 @@ struct KArgs {
     uint64_t strideA, strideB, strideC;   // per-batch strides in elements
     uint32_t is_conv;
     uint32_t H, W, Cin, P, Q, R, S, cstride, cpad;   // conv geometry (A = NHWC image)
-    uint32_t slot_ukernel[2];         // uKernel ids of the plan's (up to) two constituents
-    uint32_t slot_code[2];            // their body codes in the compiled family
-    uint32_t slot_stages[2];          // LDS ring depth of each (fast path)
+    uint32_t slot_ukernel[4];         // uKernel ids of the plan's constituents: two parts, then their strips
+    uint32_t slot_code[4];            // their body codes in the compiled family
+    uint32_t slot_stages[4];          // LDS ring depth of each (fast path)
+    uint32_t table_order;             // 1: workgroup b takes descriptor b and finds its slot by uKernel id
     uint32_t slot_first[2];           // first descriptor of each constituent's block of the table
     uint32_t slot_rows[2];            // its tile grid per batch entry: rows (m) x columns (n)
     uint32_t slot_cols[2];

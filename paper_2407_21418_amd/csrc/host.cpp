@@ -53,6 +53,7 @@ void tuning_defaults(ft_tuning *t) {
     t->sia_form = FT_SIA_PRODUCT;
     t->k_parts_max = 8;
     t->k_part_min_tiles = 8;
+    t->second_axis_strips = 0;
 }
 
 struct Gemm {                // GEMM view of an operator: static extents (0 = dynamic)
@@ -119,6 +120,10 @@ void axis_samples(uint64_t lo, uint64_t hi, uint64_t cap, std::vector<uint64_t> 
 }
 
 struct Part { uint32_t id, count; };
+// second-axis strip of a part: id < 0 = none; n_full tiles of the part's own uKernel across the
+// other axis, then n_strip tiles of uKernel id
+struct Strip { int32_t id; uint32_t n_full, n_strip; };
+struct Region { uint32_t id; uint64_t tiles, useful, area; };     // one uKernel-homogeneous region, per batch entry
 
 struct Program {
     Part part[2];
@@ -130,6 +135,8 @@ struct Program {
     uint32_t pad_q, occ_q, cmr_q;
     uint64_t sia_q;
     uint32_t k_parts;         // workgroups per tile along the reduce axis (0 reads as 1)
+    Strip strip[2];           // aligned with part[]
+    bool has_strips;
 };
 
 inline uint32_t ext(const ft_ukernel_info &u, uint32_t axis) { return axis == 0 ? u.tm : u.tn; }
@@ -180,18 +187,43 @@ bool passes_workload(uint32_t tm, uint32_t tn, const std::vector<uint64_t> &ms,
 // k_parts times the tile count and compute_eff is taken on one part of the reduce axis (its share
 // of the k-tiles, 8 more bytes of global traffic per output element for the fp32 partial written
 // and read once, and the exchange's round trips).
+// The uKernel-homogeneous regions of a program in placement order (parts ascending by id; a part's
+// own tiles, then its strip): tiles, useful outputs and covered area per batch entry.
+uint32_t regions_of(const Program &p, const ft_ukset &set, uint64_t M, uint64_t N, uint32_t tau, Region (&out)[4]) {
+    const uint64_t H = tau == 0 ? M : N, W = tau == 0 ? N : M;
+    const uint64_t Wp = ceil_by(W, GRANULE);
+    uint64_t off = 0;
+    uint32_t n = 0;
+    for (uint32_t i = 0; i < p.nparts; ++i) {
+        const ft_ukernel_info &u = set.uk[p.part[i].id];
+        const uint64_t e = ext(u, tau), cnt = p.part[i].count, span = cnt * e;
+        const uint64_t rows = H > off ? std::min<uint64_t>(H - off, span) : 0;
+        off += span;
+        if (!p.has_strips || p.strip[i].id < 0) {
+            const uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
+            out[n++] = {u.id, cnt * across, rows * W, cnt * across * u.tm * u.tn};
+        } else {
+            const ft_ukernel_info &v = set.uk[(uint32_t)p.strip[i].id];
+            const uint64_t w_main = std::min<uint64_t>(W, (uint64_t)p.strip[i].n_full * ext(u, 1 - tau));
+            out[n++] = {u.id, cnt * p.strip[i].n_full, rows * w_main, cnt * p.strip[i].n_full * u.tm * u.tn};
+            out[n++] = {v.id, cnt * p.strip[i].n_strip, rows * (W - w_main), cnt * p.strip[i].n_strip * v.tm * v.tn};
+        }
+    }
+    return n;
+}
+
 void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint64_t N, uint32_t tau,
               uint32_t k_parts = 1, uint64_t K = 0) {
     const ft_hw_model &hw = set.hw;
     const ft_tuning &t = set.t;
-    uint64_t Wp = ceil_by(tau == 0 ? N : M, GRANULE);
-    uint64_t per_batch = 0, area = 0;
-    for (uint32_t i = 0; i < p.nparts; ++i) {
-        const ft_ukernel_info &u = set.uk[p.part[i].id];
-        uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
-        per_batch += p.part[i].count * across;
-        area += p.part[i].count * across * u.tm * u.tn;
+    if (p.nparts == 2 && p.part[0].id > p.part[1].id) {       // placement order: ascending id
+        std::swap(p.part[0], p.part[1]);
+        std::swap(p.strip[0], p.strip[1]);
     }
+    Region reg[4];
+    const uint32_t nreg = regions_of(p, set, M, N, tau, reg);
+    uint64_t per_batch = 0, area = 0;
+    for (uint32_t i = 0; i < nreg; ++i) { per_batch += reg[i].tiles; area += reg[i].area; }
     p.tiles = batch * per_batch;
     p.area = area;
     p.k_parts = k_parts;
@@ -200,8 +232,8 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
     uint64_t need = std::max<uint64_t>(1, ceil_div(wgs, hw.num_cus));              // K.wkl.block
     p.block_bound = (uint32_t)std::min<uint64_t>(need, t.zeta);                     // SetBound
     p.in_bound = true;
-    for (uint32_t i = 0; i < p.nparts; ++i)
-        if (set.uk[p.part[i].id].max_wg_per_cu < p.block_bound) p.in_bound = false;
+    for (uint32_t i = 0; i < nreg; ++i)
+        if (set.uk[reg[i].id].max_wg_per_cu < p.block_bound) p.in_bound = false;
     u128 on = wgs, od = ceil_by(wgs, hw.num_cus);                                   // Eq. 3
     u128 pn = (u128)M * N, pd = area;                                               // Eq. 2
     p.occ_q = (uint32_t)((on << QBITS) / od);
@@ -219,44 +251,63 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
         return (uint64_t)((cn << QBITS) / cd);
     };
     uint64_t acc = 0;
-    for (uint32_t i = 0; i < p.nparts; ++i) {
-        uint64_t c = std::min<uint64_t>(cmr_at(set.uk[p.part[i].id]), set.cap_q);
+    for (uint32_t i = 0; i < nreg; ++i) {
+        uint64_t c = std::min<uint64_t>(cmr_at(set.uk[reg[i].id]), set.cap_q);
         acc += (uint64_t)(((u128)c << QBITS) / set.cap_q);
     }
-    p.cmr_q = (uint32_t)(acc / p.nparts);
-    if (p.nparts == 2 && p.part[0].id > p.part[1].id) std::swap(p.part[0], p.part[1]);
+    p.cmr_q = (uint32_t)(acc / nreg);
     if (t.sia_form == FT_SIA_LINEAR) {
         p.sia_q = (uint64_t)t.c0 * p.cmr_q + (uint64_t)t.c1 * p.pad_q + (uint64_t)t.c2 * p.occ_q;   // Eq. 1 as printed
     } else {
-        // multiplicative form, per uKernel on its own sub-workload; two constituents are combined
+        // multiplicative form, per uKernel on its own sub-workload; the constituents are combined
         // by the harmonic mean weighted with the useful output elements of each (Sec. 5.2):
-        // total work over the time both need at their own rates
-        const uint64_t H = tau == 0 ? M : N, W = tau == 0 ? N : M;
-        uint64_t off = 0;
-        u128 us[2] = {0, 0}, xs[2] = {0, 0};
-        for (uint32_t i = 0; i < p.nparts; ++i) {                 // placement order along tau
-            const ft_ukernel_info &u = set.uk[p.part[i].id];
-            const uint64_t e = ext(u, tau), cnt = p.part[i].count;
-            const uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
-            const uint64_t T = batch * cnt * across * k_parts;      // workgroups of this constituent
-            const uint64_t span = cnt * e;
-            const uint64_t len = H > off ? std::min<uint64_t>(H - off, span) : 0;
-            const u128 useful = (u128)len * W, area_u = (u128)cnt * across * u.tm * u.tn;
-            off += span;
+        // total work over the time all need at their own rates; a constituent with no useful
+        // output carries no weight
+        u128 us[4], xs[4];
+        uint32_t n = 0;
+        for (uint32_t i = 0; i < nreg; ++i) {
+            const ft_ukernel_info &u = set.uk[reg[i].id];
+            const uint64_t T = batch * reg[i].tiles * k_parts;      // workgroups of this constituent
             const uint64_t cq = (uint64_t)(((u128)std::min<uint64_t>(cmr_at(u), set.cap_q) << QBITS) / set.cap_q);
-            const uint64_t pq = (uint64_t)((useful << QBITS) / area_u);
+            const uint64_t pq = (uint64_t)(((u128)reg[i].useful << QBITS) / reg[i].area);
             const uint64_t oq = (uint64_t)(((u128)T << QBITS) / ceil_by(T, hw.num_cus));
             u128 x = (u128)1 << QBITS;
             const uint64_t qs[3] = {cq, pq, oq};
             const uint32_t cs[3] = {t.c0, t.c1, t.c2};
             for (int k = 0; k < 3; ++k)
                 for (uint32_t r = 0; r < cs[k]; ++r) x = (x * qs[k]) >> QBITS;
-            us[i] = useful;
-            xs[i] = x;
+            if (nreg > 1 && reg[i].useful == 0) continue;
+            us[n] = reg[i].useful;
+            xs[n] = x;
+            ++n;
         }
-        if (xs[0] == 0 || (p.nparts == 2 && xs[1] == 0)) p.sia_q = 0;
-        else if (p.nparts == 1) p.sia_q = (uint64_t)xs[0];
-        else p.sia_q = (uint64_t)(((us[0] + us[1]) * xs[0] * xs[1]) / (us[0] * xs[1] + us[1] * xs[0]));
+        if (n == 0) {                     // every region lies in the padding: keep the first
+            n = 1;
+            us[0] = 0;
+            u128 x = (u128)1 << QBITS;
+            const ft_ukernel_info &u = set.uk[reg[0].id];
+            const uint64_t T = batch * reg[0].tiles * k_parts;
+            const uint64_t qs[3] = {(uint64_t)(((u128)std::min<uint64_t>(cmr_at(u), set.cap_q) << QBITS) / set.cap_q), 0,
+                                    (uint64_t)(((u128)T << QBITS) / ceil_by(T, hw.num_cus))};
+            const uint32_t cs[3] = {t.c0, t.c1, t.c2};
+            for (int k = 0; k < 3; ++k)
+                for (uint32_t r = 0; r < cs[k]; ++r) x = (x * qs[k]) >> QBITS;
+            xs[0] = x;
+        }
+        bool zero = false;
+        for (uint32_t i = 0; i < n; ++i) zero = zero || xs[i] == 0;
+        if (zero) p.sia_q = 0;
+        else if (n == 1) p.sia_q = (uint64_t)xs[0];
+        else {
+            u128 usum = 0, prod = 1, den = 0;
+            for (uint32_t i = 0; i < n; ++i) { usum += us[i]; prod *= xs[i]; }
+            for (uint32_t i = 0; i < n; ++i) {
+                u128 others = 1;
+                for (uint32_t j = 0; j < n; ++j) if (j != i) others *= xs[j];
+                den += us[i] * others;
+            }
+            p.sia_q = (uint64_t)((usum * prod) / den);
+        }
     }
 }
 
@@ -277,6 +328,53 @@ bool split_allowed(const Program &p, const ft_ukset &set, uint64_t K, uint32_t k
     const uint64_t nk = std::max<uint64_t>(ceil_div(K, set.uk[p.part[0].id].tk), 1);
     const uint64_t per = ceil_div(nk, k_parts);
     return nk / k_parts >= std::max<uint32_t>(set.t.k_part_min_tiles, 1) && ceil_div(nk, per) == k_parts;
+}
+
+// Second-axis combination for one part (both space axes dynamic): along the other axis a part of
+// uKernel K1 places Num1 = floor(W' / K1.ext) whole tiles and covers the rest with Num2 tiles of a
+// narrower uKernel K2 that has K1's extent along tau.  Candidates for K2: every narrower uKernel
+// with that tau extent whose tiles pad less than one more K1 tile would, widest first (ties: lower
+// index), at most kStripChoices.  None if K1 divides W' or is wider than W'.
+const uint32_t kStripChoices = 3;
+uint32_t strip_choices(const ft_ukernel_info &u, const ft_ukset &set, uint64_t Wp, uint32_t tau, Strip (&out)[kStripChoices]) {
+    const uint64_t e = ext(u, 1 - tau);
+    const uint64_t n_full = Wp / e, rem = Wp % e;
+    if (n_full < 1 || rem == 0) return 0;
+    std::vector<const ft_ukernel_info *> c;
+    for (const ft_ukernel_info &v : set.uk)
+        if (ext(v, tau) == ext(u, tau) && ext(v, 1 - tau) < e && ceil_by(rem, ext(v, 1 - tau)) < e) c.push_back(&v);
+    std::stable_sort(c.begin(), c.end(), [&](const ft_ukernel_info *a, const ft_ukernel_info *b) {
+        if (ext(*a, 1 - tau) != ext(*b, 1 - tau)) return ext(*a, 1 - tau) > ext(*b, 1 - tau);
+        return a->id < b->id;
+    });
+    uint32_t n = 0;
+    for (size_t i = 0; i < c.size() && n < kStripChoices; ++i)
+        out[n++] = {(int32_t)c[i]->id, (uint32_t)n_full, (uint32_t)ceil_div(rem, ext(*c[i], 1 - tau))};
+    return n;
+}
+
+// Every way to give the parts of program p a strip or none (at least one strip), in a fixed order:
+// the choices of the first part vary slowest, "no strip" comes first.
+void strip_variants(const Program &p, const ft_ukset &set, uint64_t Wp, uint32_t tau, std::vector<Program> &out) {
+    Strip ch[2][kStripChoices + 1];
+    uint32_t nch[2] = {1, 1};
+    for (uint32_t i = 0; i < p.nparts; ++i) {
+        const ft_ukernel_info &u = set.uk[p.part[i].id];
+        ch[i][0] = {-1, (uint32_t)ceil_div(Wp, ext(u, 1 - tau)), 0};
+        Strip tmp[kStripChoices];
+        uint32_t n = strip_choices(u, set, Wp, tau, tmp);
+        for (uint32_t j = 0; j < n; ++j) ch[i][1 + j] = tmp[j];
+        nch[i] = 1 + n;
+    }
+    for (uint32_t a = 0; a < nch[0]; ++a)
+        for (uint32_t b = 0; b < (p.nparts == 2 ? nch[1] : 1); ++b) {
+            if (ch[0][a].id < 0 && (p.nparts == 1 || ch[1][b].id < 0)) continue;
+            Program q = p;
+            q.has_strips = true;
+            q.strip[0] = ch[0][a];
+            q.strip[1] = p.nparts == 2 ? ch[1][b] : Strip{-1, 0, 0};
+            out.push_back(q);
+        }
 }
 
 // Alg. 2 over the set's main-axis extents on the granule-rounded size Hp (last-success form).
@@ -367,34 +465,56 @@ void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau
     uint64_t off = 0;
     for (uint32_t i = 0; i < p.nparts; ++i) {           // parts are in ascending id order
         const ft_ukernel_info &u = set.uk[p.part[i].id];
-        uint64_t across = ceil_div(Wp, ext(u, 1 - tau));
-        uint64_t cnt = p.part[i].count;
-        uint64_t m_cnt = tau == 0 ? cnt : across, n_cnt = tau == 0 ? across : cnt;
-        uint64_t m_base = tau == 0 ? off : 0, n_base = tau == 0 ? 0 : off;
-        grid[i] = {(uint32_t)out.size(), (uint32_t)m_cnt, (uint32_t)n_cnt};
-        for (uint64_t b = 0; b < r.batch; ++b)
-            for (uint64_t im = 0; im < m_cnt; ++im)
-                for (uint64_t in = 0; in < n_cnt; ++in) {
-                    ft_tile_desc d;
-                    d.ukernel_id = u.id;
-                    d.batch = (uint32_t)b;
-                    d.m0 = (uint32_t)(m_base + im * u.tm);
-                    d.n0 = (uint32_t)(n_base + in * u.tn);
-                    d.m_valid = (uint16_t)std::min<uint64_t>(u.tm, r.M - d.m0);
-                    d.n_valid = (uint16_t)std::min<uint64_t>(u.tn, r.N - d.n0);
-                    d.flags = (d.m_valid < u.tm || d.n_valid < u.tn) ? 1u : 0u;
-                    out.push_back(d);
-                }
+        const uint64_t cnt = p.part[i].count;
+        // runs across the other axis: the part's own tiles, then (if any) its strip's
+        struct Run { const ft_ukernel_info *v; uint64_t start, count; } runs[2];
+        uint32_t nruns = 1;
+        if (!p.has_strips || p.strip[i].id < 0) {
+            runs[0] = {&u, 0, ceil_div(Wp, ext(u, 1 - tau))};
+        } else {
+            runs[0] = {&u, 0, p.strip[i].n_full};
+            runs[1] = {&set.uk[(uint32_t)p.strip[i].id], (uint64_t)p.strip[i].n_full * ext(u, 1 - tau), p.strip[i].n_strip};
+            nruns = 2;
+        }
+        if (!p.has_strips) grid[i] = {(uint32_t)out.size(), (uint32_t)(tau == 0 ? cnt : runs[0].count),
+                                      (uint32_t)(tau == 0 ? runs[0].count : cnt)};
+        for (uint32_t q = 0; q < nruns; ++q) {
+            const ft_ukernel_info &v = *runs[q].v;
+            for (uint64_t b = 0; b < r.batch; ++b)
+                for (uint64_t ia = 0; ia < (tau == 0 ? cnt : runs[q].count); ++ia)
+                    for (uint64_t ib = 0; ib < (tau == 0 ? runs[q].count : cnt); ++ib) {
+                        // tau == 0: ia walks the part's rows, ib the run's columns; tau == 1: the reverse
+                        const uint64_t m0 = tau == 0 ? off + ia * v.tm : runs[q].start + ia * v.tm;
+                        const uint64_t n0 = tau == 0 ? runs[q].start + ib * v.tn : off + ib * v.tn;
+                        ft_tile_desc d;
+                        d.ukernel_id = v.id;
+                        d.batch = (uint32_t)b;
+                        d.m0 = (uint32_t)m0;
+                        d.n0 = (uint32_t)n0;
+                        d.m_valid = (uint16_t)std::min<uint64_t>(v.tm, r.M - m0);
+                        d.n_valid = (uint16_t)std::min<uint64_t>(v.tn, r.N - n0);
+                        d.flags = (d.m_valid < v.tm || d.n_valid < v.tn) ? 1u : 0u;
+                        out.push_back(d);
+                    }
+        }
         off += cnt * ext(u, tau);
     }
+    if (p.has_strips)       // canonical order of the table: uKernel id, batch, m0, n0
+        std::sort(out.begin(), out.end(), [](const ft_tile_desc &a, const ft_tile_desc &b) {
+            if (a.ukernel_id != b.ukernel_id) return a.ukernel_id < b.ukernel_id;
+            if (a.batch != b.batch) return a.batch < b.batch;
+            if (a.m0 != b.m0) return a.m0 < b.m0;
+            return a.n0 < b.n0;
+        });
 }
 
 bool better(const Program &a, const Program &b) {      // Top-1 order: SIA, then fewer parts, fewer tiles, K1, K2
     if (a.sia_q != b.sia_q) return a.sia_q > b.sia_q;
     if (a.k_parts != b.k_parts) return a.k_parts < b.k_parts;
     if (a.tiles != b.tiles) return a.tiles < b.tiles;
+    if (a.has_strips != b.has_strips) return !a.has_strips;
     if (a.k1 != b.k1) return a.k1 < b.k1;
-    return a.k2 < b.k2;
+    return a.k2 < b.k2;          // (strip variants of one program that tie: the first listed stays)
 }
 
 int level_of(const Program &p) { return p.in_bound ? 0 : 1; }
@@ -652,9 +772,9 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     pl->device = -1;
     pl->num_xcds = set->hw.num_xcds ? set->hw.num_xcds : 1;
     pl->img_h = shape->img_h; pl->img_w = shape->img_w; pl->out_p = r.P; pl->out_q = r.Q;
-    pl->slot_id[0] = pl->slot_id[1] = 0;
-    pl->slot_code[0] = pl->slot_code[1] = 0;
-    pl->slot_stages[0] = pl->slot_stages[1] = MIN_STAGES;
+    for (int i = 0; i < 4; ++i) { pl->slot_id[i] = 0; pl->slot_code[i] = 0; pl->slot_stages[i] = MIN_STAGES; }
+    pl->n_slots = 0;
+    pl->table_order = false;
     for (int i = 0; i < 2; ++i) { pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = pl->slot_group[i] = 1; }
     ft_plan_stats &s = pl->st;
     std::memset(&s, 0, sizeof(s));
@@ -733,16 +853,30 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         {
             std::vector<Program> scored;
             scored.reserve(pool.size());
+            // Two dynamic space axes: every program is also scored with second-axis strips
+            const Gemm sv = static_view(op->d);
+            const bool two_axes = sv.m == 0 && sv.n == 0 && set->t.second_axis_strips != 0;
+            const uint64_t Wp = ceil_by(tau == 0 ? r.N : r.M, GRANULE);
+            std::vector<Program> variants;
             for (Program &p : pool) {
+                if (two_axes) {                       // (before evaluate: it may reorder the parts)
+                    variants.clear();
+                    strip_variants(p, *set, Wp, tau, variants);
+                }
                 evaluate(p, *set, r.batch, r.M, r.N, tau);
                 scored.push_back(p);
-                if (op->d.kind != FT_OP_MATMUL) continue;
-                for (uint32_t kp : kPartChoices) {
-                    if (kp == 1 || !split_allowed(p, *set, r.K, kp)) continue;
-                    Program q = p;
-                    evaluate(q, *set, r.batch, r.M, r.N, tau, kp, r.K);
-                    scored.push_back(q);
-                }
+                if (op->d.kind == FT_OP_MATMUL)
+                    for (uint32_t kp : kPartChoices) {
+                        if (kp == 1 || !split_allowed(p, *set, r.K, kp)) continue;
+                        Program q = p;
+                        evaluate(q, *set, r.batch, r.M, r.N, tau, kp, r.K);
+                        scored.push_back(q);
+                    }
+                if (two_axes)
+                    for (Program &q : variants) {
+                        evaluate(q, *set, r.batch, r.M, r.N, tau);
+                        scored.push_back(q);
+                    }
             }
             pool.swap(scored);
         }
@@ -767,13 +901,25 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     }
     s.n_ukernels = best.nparts;
     uint32_t lds = 0, klass = 0;
+    pl->table_order = best.has_strips;
+    for (uint32_t i = 0; i < 2; ++i) { s.strip_ukernel_id[i] = UINT32_MAX; s.strip_tiles[i] = 0; s.main_tiles[i] = 0; }
+    // slots 0, 1: the parts (the launch order is computed on their tile grids); 2, 3: strips
+    auto set_slot = [&](uint32_t slot, const ft_ukernel_info &u) {
+        pl->slot_id[slot] = u.id;
+        pl->slot_code[slot] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn, u.gk);
+        pl->slot_stages[slot] = u.stages;
+        lds = std::max(lds, u.lds_bytes);
+        uint32_t by_model = 0;
+        for (uint32_t b = set->hw.regs_per_lane / 4; b < u.reg_budget && by_model < FT_NUM_CLASSES - 1; b *= 2) ++by_model;
+        klass = std::max<uint32_t>(klass, std::max<uint32_t>(by_model, (uint32_t)ft_class_of_acc((int)u.acc_regs)));
+    };
+    const uint64_t Wp_plan = ceil_by(tau == 0 ? r.N : r.M, GRANULE);
     for (uint32_t i = 0; i < best.nparts; ++i) {
         const ft_ukernel_info &u = set->uk[best.part[i].id];
         s.ukernel_id[i] = u.id;
         s.count_tau[i] = best.part[i].count;
-        pl->slot_id[i] = u.id;
-        pl->slot_code[i] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn, u.gk);
-        pl->slot_stages[i] = u.stages;
+        s.main_tiles[i] = (uint32_t)ceil_div(Wp_plan, ext(u, 1 - tau));
+        set_slot(i, u);
         // Launch order: an XCD works on a window of consecutive tiles (its share of the table, at
         // most what its CUs hold at once).  Walk the grid in groups of g tile rows so that window is
         // a g x (window/g) block, with g chosen to minimise the A + B panel bytes the block touches.
@@ -791,12 +937,23 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
             }
             pl->slot_group[i] = best_g;
         }
-        lds = std::max(lds, u.lds_bytes);
-        uint32_t by_model = 0;
-        for (uint32_t b = set->hw.regs_per_lane / 4; b < u.reg_budget && by_model < FT_NUM_CLASSES - 1; b *= 2) ++by_model;
-        klass = std::max<uint32_t>(klass, std::max<uint32_t>(by_model, (uint32_t)ft_class_of_acc((int)u.acc_regs)));
     }
     if (best.nparts == 1) { pl->slot_id[1] = pl->slot_id[0]; pl->slot_code[1] = pl->slot_code[0]; pl->slot_stages[1] = pl->slot_stages[0]; }
+    pl->n_slots = 2;
+    for (uint32_t i = 0; i < 2; ++i) {                    // unused strip slots repeat slot 0
+        pl->slot_id[2 + i] = pl->slot_id[0]; pl->slot_code[2 + i] = pl->slot_code[0]; pl->slot_stages[2 + i] = pl->slot_stages[0];
+    }
+    if (best.has_strips) {
+        pl->n_slots = 4;
+        for (uint32_t i = 0; i < best.nparts; ++i) {
+            if (best.strip[i].id < 0) continue;
+            const ft_ukernel_info &v = set->uk[(uint32_t)best.strip[i].id];
+            s.strip_ukernel_id[i] = v.id;
+            s.main_tiles[i] = best.strip[i].n_full;
+            s.strip_tiles[i] = best.strip[i].n_strip;
+            set_slot(2 + i, v);
+        }
+    }
     s.block_bound = best.block_bound;
     s.pad_q20 = best.pad_q; s.occ_q20 = best.occ_q; s.cmr_q20 = best.cmr_q; s.sia_q20 = best.sia_q;
     s.lds_bytes = lds;
@@ -837,11 +994,12 @@ ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, u
 
 ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t cap, uint64_t *n) {
     if (!plan || !n || (cap && !order)) return FT_ERR_INVALID_ARG;
-    const uint64_t total = plan->descs.size();
+    // workgroups of the launch: the tiles, or for a plan walked in table order whole rounds of chunks
+    const uint64_t total = plan->table_order ? ftk::table_grid((uint32_t)plan->descs.size(), plan->num_xcds) : plan->descs.size();
     *n = total;
     ftk::LaunchOrder o;
     o.n[0] = plan->slot_first[1] - plan->slot_first[0];
-    o.n[1] = (uint32_t)total - plan->slot_first[1];
+    o.n[1] = (uint32_t)plan->descs.size() - plan->slot_first[1];
     for (int i = 0; i < 2; ++i) {
         o.first[i] = plan->slot_first[i];
         o.rows[i] = plan->slot_rows[i];
@@ -851,7 +1009,12 @@ ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t ca
     o.nx = plan->num_xcds;
     for (uint64_t b = 0; b < total && b < cap; ++b) {
         uint32_t slot;
-        order[b] = ftk::tile_of_workgroup(o, (uint32_t)b, &slot);
+        if (plan->table_order) {
+            const uint32_t t = ftk::table_index_of_workgroup((uint32_t)b, plan->num_xcds);
+            order[b] = t < plan->descs.size() ? t : UINT32_MAX;          // idle workgroup
+        } else {
+            order[b] = ftk::tile_of_workgroup(o, (uint32_t)b, &slot);
+        }
     }
     return FT_OK;
 }

@@ -30,17 +30,31 @@ struct LaunchOrder {
 
 FT_HD uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols, uint32_t G) {
     if (rows < 2 || cols < 2 || G < 2) return u;
+    // (run-time divisions are costly on the device: a single batch entry and full groups of a
+    // power-of-two height, the common cases, get by with one)
     const uint32_t per = rows * cols;
-    const uint32_t bidx = u / per, v = u % per;
-    const uint32_t grp = v / (G * cols), w = v % (G * cols);
+    uint32_t bidx = 0, v = u;
+    if (u >= per) { bidx = u / per; v = u % per; }
+    const uint32_t grp = v / (G * cols), w = v - grp * (G * cols);
     const uint32_t first = grp * G;
     const uint32_t gr = rows - first < G ? rows - first : G;
-    return bidx * per + (first + w % gr) * cols + w / gr;
+    uint32_t wq, wr;                                   // w / gr, w % gr
+    if (gr == G && (G & (G - 1)) == 0) {
+        const uint32_t sh = 31u - (uint32_t)__builtin_clz(G);
+        wq = w >> sh;
+        wr = w & (G - 1);
+    } else {
+        wq = w / gr;
+        wr = w - wq * gr;
+    }
+    return bidx * per + (first + wr) * cols + wq;
 }
 
-// descriptor index of workgroup b; *slot receives the constituent (0 or 1)
-FT_HD uint32_t tile_of_workgroup(const LaunchOrder &o, uint32_t b, uint32_t *slot) {
-    const uint32_t nx = o.nx;
+// descriptor index of workgroup b; *slot receives the constituent (0 or 1).  NX: the number of XCDs
+// when it is known at compile time (divisions by it become shifts), 0 to take it from o.nx.
+template <uint32_t NX>
+FT_HD uint32_t tile_of_workgroup_nx(const LaunchOrder &o, uint32_t b, uint32_t *slot) {
+    const uint32_t nx = NX ? NX : o.nx;
     const uint32_t x = b % nx, j = b / nx;
     const uint32_t q0 = o.n[0] / nx, r0 = o.n[0] % nx;
     const uint32_t q1 = o.n[1] / nx, r1 = o.n[1] % nx;
@@ -68,6 +82,29 @@ FT_HD uint32_t tile_of_workgroup(const LaunchOrder &o, uint32_t b, uint32_t *slo
     const uint32_t first = s ? o.first[1] : o.first[0], rows = s ? o.rows[1] : o.rows[0];
     const uint32_t cols = s ? o.cols[1] : o.cols[0], group = s ? o.group[1] : o.group[0];
     return first + grouped_index(idx, rows, cols, group);
+}
+
+FT_HD uint32_t tile_of_workgroup(const LaunchOrder &o, uint32_t b, uint32_t *slot) {
+    // integer division by a run-time value costs the device some forty instructions each, on the
+    // critical path of every workgroup: the usual device (8 XCDs) gets its own instance
+    return o.nx == 8 ? tile_of_workgroup_nx<8>(o, b, slot) : tile_of_workgroup_nx<0>(o, b, slot);
+}
+
+// Plans with more than two uKernel shapes (second-axis strips) are walked in table order, dealt to
+// the XCDs in chunks of kTableChunk consecutive descriptors: neighbouring tiles of a row band stay
+// on one XCD (the halves of a cache line of C that two of them share meet in one L2) and every XCD
+// gets the same mix of tile shapes.  The grid is rounded up to whole rounds of chunks; a
+// workgroup beyond the table (returned index >= n_tiles) has nothing to do.
+constexpr uint32_t kTableChunk = 16;
+
+FT_HD uint32_t table_grid(uint32_t n_tiles, uint32_t nx) {
+    const uint32_t round = nx * kTableChunk;
+    return (n_tiles + round - 1) / round * round;
+}
+
+FT_HD uint32_t table_index_of_workgroup(uint32_t b, uint32_t nx) {
+    const uint32_t x = b % nx, j = b / nx;
+    return ((j / kTableChunk) * nx + x) * kTableChunk + j % kTableChunk;
 }
 
 }  // namespace ftk

@@ -66,6 +66,8 @@ def test_ukernel_table_matches_oracle(name):
 def shapes_for(name):
     if name in ("qk", "qk_b768"):
         return [dict(batch=b, m=L, n=L) for b in (1, 12, 96) for L in (1, 7, 16, 33, 77, 100, 257, 512)] + \
+               [dict(batch=768, m=L, n=L) for L in (133, 141, 183, 281, 313, 390, 415, 450)] + \
+               [dict(batch=96, m=313, n=200), dict(batch=96, m=200, n=313), dict(batch=96, m=133, n=281), dict(batch=96, m=313, n=415)] + \
                [dict(batch=3, m=100, n=40), dict(batch=3, m=40, n=100), dict(batch=0, m=5, n=5), dict(batch=2, m=0, n=0)]
     if name == "pv":
         return [dict(batch=b, m=L, k=L) for b in (1, 12) for L in (1, 7, 16, 33, 77, 100, 257, 512)]
@@ -88,18 +90,29 @@ def oracle_shape(op, kw):
                            img_n=kw.get("img_n", 0), img_h=kw.get("img_h", 0), img_w=kw.get("img_w", 0))
 
 
+def strips_on():
+    """(library tuning, oracle tuning) with the second-axis strips switched on (off by default)."""
+    lt = ft.ft_tuning_default()
+    lt.second_axis_strips = 1
+    return lt, dict(P.default_tuning(), second_axis_strips=1)
+
+
 @pytest.mark.parametrize("mode", [P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE])
-@pytest.mark.parametrize("name", sorted(OPS))
+@pytest.mark.parametrize("name", sorted(OPS) + ["qk_b768+strips"])
 def test_plans_bit_identical_to_oracle(name, mode):
+    lib_t, ora_t = (None, None)
+    if name.endswith("+strips"):
+        name = name[:-len("+strips")]
+        lib_t, ora_t = strips_on()
     op = OPS[name]
-    uks = P.derive_ukernels(op)
+    uks = P.derive_ukernels(op, t=ora_t)
     lop = to_lib_op(op)
-    s = ft.ft_ukernels_derive(lop)
+    s = ft.ft_ukernels_derive(lop, None, lib_t)
     for kw in shapes_for(name):
         shape = oracle_shape(op, kw)
         if op.kind != P.OP_BMM:
             shape = (1,) + tuple(shape[1:])
-        want = P.plan(op, uks, shape, mode)
+        want = P.plan(op, uks, shape, mode, t=ora_t)
         pl = ft.ft_plan_create(lop, s, ft.ft_shape(**kw), mode | HOST)
         got = ft.ft_plan_descriptors(pl)
         assert got == b"".join(d.pack() for d in want.descs), (name, kw)
@@ -115,10 +128,45 @@ def test_plans_bit_identical_to_oracle(name, mode):
         assert [(st.ukernel_id[i], st.count_tau[i]) for i in range(st.n_ukernels)] == list(pr.parts)
         assert (st.pad_q20, st.occ_q20, st.cmr_q20, st.sia_q20) == (pr.pad_q, pr.occ_q, pr.cmr_q, pr.sia_q)
         assert st.block_bound == pr.block_bound and st.level == want.level and st.pool_size == want.pool_size
-        assert st.lds_bytes == max(uks[i].lds_bytes for i, _ in pr.parts)
+        used = [i for i, _ in pr.parts] + [sid for sid, _, _ in pr.strips if sid >= 0]
+        assert st.lds_bytes == max(uks[i].lds_bytes for i in used)
         assert (st.k_parts, st.k_part_tiles) == (want.k_parts, want.k_part_tiles), (name, kw)
+        # second-axis strips: per part (strip uKernel or none, own tiles across the other axis, strip tiles)
+        Wp = P.ceil_by(shape[2] if want.tau == 0 else shape[1], 16)
+        for i, (uid, _) in enumerate(pr.parts):
+            sid, n_full, n_strip = pr.strips[i] if pr.strips else (-1, P.ceil_div(Wp, uks[uid].tn if want.tau == 0 else uks[uid].tm), 0)
+            assert (st.strip_ukernel_id[i], st.main_tiles[i], st.strip_tiles[i]) == (sid if sid >= 0 else 0xFFFFFFFF, n_full, n_strip), (name, kw)
         slab = max(uks[i].tm * uks[i].tn for i, _ in pr.parts)
         assert st.workspace_bytes == (st.n_tiles * st.k_parts * slab * 4 if st.k_parts > 1 else 0)
+
+
+def test_some_plans_carry_second_axis_strips():
+    """The attention shapes of the bit-identity test include plans with strips on both main axes;
+    such a plan is launched in table order."""
+    op = OPS["qk_b768"]
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop, None, strips_on()[0])
+    s_default = ft.ft_ukernels_derive(lop)
+    seen = set()
+    for kw in shapes_for("qk_b768"):
+        if kw.get("batch", 1) == 0 or kw["m"] == 0:
+            continue
+        pl = ft.ft_plan_create(lop, s, ft.ft_shape(**kw), HOST)
+        st = ft.ft_plan_stats_get(pl)
+        has = any(st.strip_ukernel_id[i] != 0xFFFFFFFF for i in range(2))
+        seen.add((st.tau, has))
+        off = ft.ft_plan_stats_get(ft.ft_plan_create(lop, s_default, ft.ft_shape(**kw), HOST))
+        assert all(off.strip_ukernel_id[i] == 0xFFFFFFFF for i in range(2))         # off unless asked for
+        if has:
+            # table order in chunks of 16 descriptors per XCD; idle workgroups pad the last round
+            order = ft.ft_plan_launch_order(pl)
+            assert len(order) % (8 * 16) == 0 and len(order) - st.n_tiles < 8 * 16
+            busy = [t for t in order if t != 0xFFFFFFFF]
+            assert sorted(busy) == list(range(st.n_tiles))
+            for b, t in enumerate(order):
+                want_t = ((b // 8 // 16) * 8 + b % 8) * 16 + (b // 8) % 16
+                assert t == (want_t if want_t < st.n_tiles else 0xFFFFFFFF)
+    assert (0, True) in seen and (1, True) in seen and (0, False) in seen
 
 
 def test_some_plans_split_the_reduce_axis_like_the_oracle():

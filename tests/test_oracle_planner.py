@@ -441,3 +441,118 @@ def test_plans_split_only_where_the_device_is_underfilled(M, N, K, expect_split)
     assert off.k_parts == 1 and off.program.sia_q <= pl.program.sia_q
     # BMM and the pad baseline never split
     assert P.plan(op, uks, (1, M, N, K), P.PLAN_PAD_BASELINE).k_parts == 1
+
+
+# --------------------------------------------------------------------------------------
+# second-axis strips (two dynamic space axes, Fig. 4(d))
+# --------------------------------------------------------------------------------------
+def _qk():
+    op = P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512), batch_hi=768)
+    return op, P.derive_ukernels(op)
+
+
+def test_strip_choices_against_brute_force():
+    op, uks = _qk()
+    for Wp in (16, 48, 112, 144, 208, 272, 464, 512):
+        for u in uks:
+            got = P.strip_choices(u, uks, Wp, 0)
+            e = u.tn
+            if Wp % e == 0 or e > Wp:
+                assert got == []
+                continue
+            n_full, rem = divmod(Wp, e)
+            ok = [v for v in uks if v.tm == u.tm and v.tn < e and -(-rem // v.tn) * v.tn < e]
+            ok.sort(key=lambda v: (-v.tn, v.id))
+            assert got == [(v.id, n_full, -(-rem // v.tn)) for v in ok[:P.STRIP_CHOICES]]
+            for sid, a, b in got:                       # the strip closes the gap and pads less than one more K1 tile
+                assert a * e + b * uks[sid].tn >= Wp > a * e + (b - 1) * uks[sid].tn
+                assert a * e + b * uks[sid].tn < (a + 1) * e
+    # along the other main axis the roles of tm and tn swap
+    u = next(u for u in uks if (u.tm, u.tn) == (128, 128))
+    for sid, a, b in P.strip_choices(u, uks, 208, 1):
+        assert uks[sid].tn == 128 and uks[sid].tm < 128 and a == 1
+
+
+def test_strip_variants_order_and_count():
+    op, uks = _qk()
+    by = {(u.tm, u.tn, u.gk): u for u in uks}
+    parts = [(by[(64, 64, 1)].id, 1), (by[(16, 64, 1)].id, 3)]          # L = 100: H' = W' = 112 = 64 + 3*16
+    c0 = P.strip_choices(uks[parts[0][0]], uks, 112, 0)
+    c1 = P.strip_choices(uks[parts[1][0]], uks, 112, 0)
+    assert c0 and c1
+    var = P.strip_variants(parts, uks, 112, 0)
+    assert len(var) == (1 + len(c0)) * (1 + len(c1)) - 1
+    none0, none1 = (-1, 2, 0), (-1, 2, 0)
+    assert var[0] == [none0, c1[0]]                                  # first part varies slowest, 'none' first
+    assert var[len(c1)] == [c0[0], none1]
+    assert all(any(s[0] >= 0 for s in v) for v in var)
+    # a program whose tiles divide W' has no variants
+    assert P.strip_variants([(by[(16, 16, 4)].id, 7)], uks, 112, 0) == []
+
+
+def test_constituents_and_harmonic_mean_of_three_regions_by_hand():
+    from fractions import Fraction
+    op, uks = _qk()
+    hw, t = P.default_hw(), P.default_tuning()
+    by = {(u.tm, u.tn, u.gk): u for u in uks}
+    k1, k2, ks = by[(64, 64, 1)], by[(16, 64, 1)], by[(64, 16, 1)]
+    parts = sorted([(k1.id, 1), (k2.id, 3)])
+    strips = [(ks.id, 1, 3) if uid == k1.id else (-1, 2, 0) for uid, _ in parts]
+    cons = P.constituents(parts, strips, uks, 1, 100, 100, 0)
+    want = {k1.id: (1, 64 * 64, 64 * 64), ks.id: (3, 64 * 36, 3 * 64 * 16), k2.id: (6, 36 * 100, 6 * 16 * 64)}
+    assert {c[0]: c[1:] for c in cons} == want and sum(c[2] for c in cons) == 100 * 100
+    cap = P.cmr_cap(uks)
+    p = P.evaluate(parts, uks, 12, 100, 100, 0, hw, t, cap, strips=strips)
+    assert p.num_tiles == 12 * 10 and p.area == 64 * 64 + 3 * 64 * 16 + 6 * 16 * 64
+    # score = sum u_i / sum (u_i / x_i) with x_i = CMR * Pad * Occ of region i in q20 steps
+    xs = []
+    for uid, tiles, useful, area in cons:
+        u = uks[uid]
+        x = (min(P.cmr_at(u, p.block_bound), cap) << 20) // cap
+        x = (x * ((useful << 20) // area)) >> 20
+        T = 12 * tiles
+        x = (x * ((T << 20) // (256 * -(-T // 256)))) >> 20
+        xs.append((useful, x))
+    exact = Fraction(sum(u for u, _ in xs)) / sum(Fraction(u, x) for u, x in xs)
+    assert p.sia_q == int(exact)                        # floor of the exact ratio
+
+
+def test_every_strip_variant_is_an_exact_cover_and_pads_no_more():
+    op, uks = _qk()
+    hw, t = P.default_hw(), P.default_tuning()
+    cap = P.cmr_cap(uks)
+    checked = 0
+    for L in (33, 100, 141, 257):
+        Hp = P.ceil_by(L, 16)
+        for parts in P.build_pool([u.tm for u in uks], Hp)[::7]:
+            whole = P.evaluate(parts, uks, 2, L, L, 0, hw, t, cap)
+            for strips in P.strip_variants(parts, uks, Hp, 0):
+                p = P.evaluate(parts, uks, 2, L, L, 0, hw, t, cap, strips=strips)
+                assert p.area <= whole.area
+                descs = P.emit(p.parts, uks, 2, L, L, 0, p.strips)
+                assert len(descs) == p.num_tiles
+                assert [(d.ukernel_id, d.batch, d.m0, d.n0) for d in descs] == sorted((d.ukernel_id, d.batch, d.m0, d.n0) for d in descs)
+                pl = P.Plan(2, L, L, 64, 0, p, descs)
+                assert (P.exact_cover_counts(pl, uks) == 1).all(), (L, parts, strips)
+                assert sum(uks[d.ukernel_id].tm * uks[d.ukernel_id].tn for d in descs) == 2 * p.area
+                checked += 1
+    assert checked > 50
+    # main axis = columns (more columns than rows): strips run down the rows
+    pl = P.plan(op, uks, (2, 100, 141, 64), t=dict(t, second_axis_strips=1))
+    assert pl.tau == 1 and (P.exact_cover_counts(pl, uks) == 1).all()
+
+
+def test_strips_only_when_asked_for_and_with_two_dynamic_axes():
+    op, uks = _qk()
+    on = dict(P.default_tuning(), second_axis_strips=1)
+    picked = 0
+    for L in (97, 133, 183, 281, 313, 390, 415, 450):
+        pl = P.plan(op, uks, (768, L, L, 64), t=on)
+        picked += bool(pl.program.strips)
+        assert (P.exact_cover_counts(P.plan(op, uks, (1, L, L, 64), t=on), uks) == 1).all()
+        assert P.plan(op, uks, (768, L, L, 64)).program.strips == []          # off by default
+    assert picked >= 3                                   # the planner does use them
+    one_axis = P.Op(P.OP_BMM, P.F16, n=64, m_range=(0, 512), k_range=(0, 512), batch_hi=768)
+    assert P.plan(one_axis, P.derive_ukernels(one_axis), (96, 141, 64, 141), t=on).program.strips == []
+    mm = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(0, 8192))
+    assert P.plan(mm, P.derive_ukernels(mm), (1, 1232, 768, 768), t=on).program.strips == []
