@@ -250,6 +250,10 @@ typedef struct ft_plan_stats {
     uint32_t main_tiles[2];
     uint32_t strip_ukernel_id[2];
     uint32_t strip_tiles[2];
+    uint32_t table_order;          /* 0: the tiles of each uKernel shape form a grid and a workgroup
+                                      derives its descriptor's contents in closed form (checked against
+                                      the table when the plan is made); 1: workgroups read the table
+                                      (plans with strips)                                          */
 } ft_plan_stats;
 
 typedef struct ft_plan ft_plan;

@@ -82,7 +82,7 @@ class ft_plan_stats(_S):
                 ("pool_size", u32), ("level", u32), ("pad_q20", u32), ("occ_q20", u32), ("cmr_q20", u32),
                 ("lds_bytes", u32), ("kernel_class", u32), ("sia_q20", u64), ("n_tiles", u64),
                 ("useful_elems", u64), ("covered_elems", u64), ("k_parts", u32), ("k_part_tiles", u32),
-                ("workspace_bytes", u64), ("main_tiles", u32 * 2), ("strip_ukernel_id", u32 * 2), ("strip_tiles", u32 * 2)]
+                ("workspace_bytes", u64), ("main_tiles", u32 * 2), ("strip_ukernel_id", u32 * 2), ("strip_tiles", u32 * 2), ("table_order", u32)]
 
 
 class ft_pool_entry(C.Structure):

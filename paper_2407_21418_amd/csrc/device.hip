@@ -62,6 +62,8 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const fl
         a->slot_rows[i] = p->slot_rows[i];
         a->slot_cols[i] = p->slot_cols[i];
         a->slot_group[i] = p->slot_group[i];
+        a->slot_m0[i] = p->slot_m0[i]; a->slot_n0[i] = p->slot_n0[i];
+        a->slot_tm[i] = p->slot_tm[i]; a->slot_tn[i] = p->slot_tn[i];
     }
     a->num_xcds = p->num_xcds;
     a->k_parts = s.k_parts > 1 && p->d_ws ? s.k_parts : 1;

@@ -66,6 +66,10 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     o.rows[0] = g.slot_rows[0]; o.rows[1] = g.slot_rows[1];
     o.cols[0] = g.slot_cols[0]; o.cols[1] = g.slot_cols[1];
     o.group[0] = g.slot_group[0]; o.group[1] = g.slot_group[1];
+    o.m_base[0] = g.slot_m0[0]; o.m_base[1] = g.slot_m0[1];
+    o.n_base[0] = g.slot_n0[0]; o.n_base[1] = g.slot_n0[1];
+    o.tm[0] = g.slot_tm[0]; o.tm[1] = g.slot_tm[1];
+    o.tn[0] = g.slot_tn[0]; o.tn[1] = g.slot_tn[1];
     o.nx = g.num_xcds;
     // Reduce axis split over workgroups: the k_parts workgroups of a tile are k_parts consecutive
     // multiples of num_xcds apart, so they share an XCD (workgroup b runs on XCD b % num_xcds) and
@@ -76,15 +80,34 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
         b = (b / (o.nx * g.k_parts)) * o.nx + b % o.nx;
         if (b >= g.n_tiles) return;
     }
-    uint32_t slot;
-    const uint32_t t = g.table_order ? table_index_of_workgroup(b, o.nx) : tile_of_workgroup(o, b, &slot);
-    if (t >= g.n_tiles) return;                 // table order: the grid is rounded up to whole rounds of chunks
-    const TileDesc d = g.descs[t];
-    // a plan with second-axis strips has up to four uKernel shapes and is walked in table order:
-    // the descriptor's uKernel id names the slot (selects, no indexing: the arguments stay in SGPRs)
+    // A program of one or two uKernel shapes lays its tiles out as grids: the workgroup derives its
+    // descriptor's contents in closed form and saves the dependent load from the table (about a
+    // microsecond on the critical path of a launch whose workgroups all start at once; the host has
+    // checked the closed form against the table).  A plan with second-axis strips has up to four
+    // shapes and is walked in table order: its workgroups read their descriptor, whose uKernel id
+    // names the slot (selects, no indexing: the arguments stay in SGPRs).
+    uint32_t slot, t;
+    TileDesc d;
     if (g.table_order) {
+        t = table_index_of_workgroup(b, o.nx);
+        if (t >= g.n_tiles) return;             // the grid is rounded up to whole rounds of chunks
+        d = g.descs[t];
         const uint32_t id = __builtin_amdgcn_readfirstlane(d.ukernel_id);       // uniform per workgroup
         slot = id == g.slot_ukernel[0] ? 0u : id == g.slot_ukernel[1] ? 1u : id == g.slot_ukernel[2] ? 2u : 3u;
+    } else {
+        const TileOfWorkgroup w = tile_of_workgroup(o, b);
+        t = w.index;
+        slot = w.slot;
+#ifdef FT_GENERIC
+        // The general dispatchers keep the load.  Their heaviest launches (odd-pitch attention
+        // scores: thousands of short workgroups bound by misaligned fp32 stores) ran 10-30 % SLOWER
+        // with either prologue shortcut (this one or the argument prefetch): workgroups that start
+        // faster reach their store phase more in step with each other.
+        d = g.descs[t];
+#else
+        d.ukernel_id = 0; d.m_valid = 0; d.n_valid = 0; d.flags = 0;          // not used by the bodies
+        d.batch = w.batch; d.m0 = w.m0; d.n0 = w.n0;
+#endif
     }
     const uint32_t code = slot == 0 ? g.slot_code[0] : slot == 1 ? g.slot_code[1] : slot == 2 ? g.slot_code[2] : g.slot_code[3];
     const uint32_t stages = slot == 0 ? g.slot_stages[0] : slot == 1 ? g.slot_stages[1] : slot == 2 ? g.slot_stages[2] : g.slot_stages[3];

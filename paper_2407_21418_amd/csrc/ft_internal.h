@@ -29,6 +29,7 @@ struct ft_plan {
     bool table_order;                                      // workgroup b takes descriptor b (plans with strips)
     uint32_t slot_first[2], slot_rows[2], slot_cols[2];   // tile grid of each constituent in the table
     uint32_t slot_group[2];                                // tile rows per group of the launch order
+    uint32_t slot_m0[2], slot_n0[2], slot_tm[2], slot_tn[2];   // closed form of each constituent's descriptors
     uint32_t num_xcds;
     uint32_t img_h, img_w, out_p, out_q;   // conv geometry
     void *d_descs;                          // device copy of descs (NULL for host-only / empty plans)

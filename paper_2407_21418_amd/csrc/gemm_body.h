@@ -52,6 +52,8 @@ struct KArgs {
     uint32_t slot_rows[2];            // its tile grid per batch entry: rows (m) x columns (n)
     uint32_t slot_cols[2];
     uint32_t slot_group[2];           // tile rows walked together in the launch order (XCD locality)
+    uint32_t slot_m0[2], slot_n0[2];  // origin of its block of tiles in the GEMM view
+    uint32_t slot_tm[2], slot_tn[2];  // its tile extents
     uint32_t num_xcds;
     // reduce axis split over workgroups (1 = off): tile t is computed by k_parts workgroups, part p
     // taking k-tiles [p * k_part_tiles, (p + 1) * k_part_tiles); partial tiles meet in ws

@@ -455,7 +455,7 @@ ft_status resolve(const ft_op_desc &d, const ft_shape &s, Resolved *r) {
     return FT_OK;
 }
 
-struct SlotGrid { uint32_t first, rows, cols; };
+struct SlotGrid { uint32_t first, rows, cols, m_base, n_base, tm, tn; };
 
 void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau, std::vector<ft_tile_desc> &out,
           SlotGrid (&grid)[2]) {
@@ -477,7 +477,8 @@ void emit(const Program &p, const ft_ukset &set, const Resolved &r, uint32_t tau
             nruns = 2;
         }
         if (!p.has_strips) grid[i] = {(uint32_t)out.size(), (uint32_t)(tau == 0 ? cnt : runs[0].count),
-                                      (uint32_t)(tau == 0 ? runs[0].count : cnt)};
+                                      (uint32_t)(tau == 0 ? runs[0].count : cnt),
+                                      (uint32_t)(tau == 0 ? off : 0), (uint32_t)(tau == 0 ? 0 : off), u.tm, u.tn};
         for (uint32_t q = 0; q < nruns; ++q) {
             const ft_ukernel_info &v = *runs[q].v;
             for (uint64_t b = 0; b < r.batch; ++b)
@@ -518,6 +519,22 @@ bool better(const Program &a, const Program &b) {      // Top-1 order: SIA, then
 }
 
 int level_of(const Program &p) { return p.in_bound ? 0 : 1; }
+
+ftk::LaunchOrder launch_order_of(const ft_plan &plan) {
+    ftk::LaunchOrder o;
+    o.n[0] = plan.slot_first[1] - plan.slot_first[0];
+    o.n[1] = (uint32_t)plan.descs.size() - plan.slot_first[1];
+    for (int i = 0; i < 2; ++i) {
+        o.first[i] = plan.slot_first[i];
+        o.rows[i] = plan.slot_rows[i];
+        o.cols[i] = plan.slot_cols[i];
+        o.group[i] = plan.slot_group[i];
+        o.m_base[i] = plan.slot_m0[i]; o.n_base[i] = plan.slot_n0[i];
+        o.tm[i] = plan.slot_tm[i]; o.tn[i] = plan.slot_tn[i];
+    }
+    o.nx = plan.num_xcds;
+    return o;
+}
 
 thread_local int g_last_hip_error = 0;
 
@@ -775,7 +792,10 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     for (int i = 0; i < 4; ++i) { pl->slot_id[i] = 0; pl->slot_code[i] = 0; pl->slot_stages[i] = MIN_STAGES; }
     pl->n_slots = 0;
     pl->table_order = false;
-    for (int i = 0; i < 2; ++i) { pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = pl->slot_group[i] = 1; }
+    for (int i = 0; i < 2; ++i) {
+        pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = pl->slot_group[i] = 1;
+        pl->slot_m0[i] = pl->slot_n0[i] = pl->slot_tm[i] = pl->slot_tn[i] = 0;
+    }
     ft_plan_stats &s = pl->st;
     std::memset(&s, 0, sizeof(s));
     s.struct_size = sizeof(s);
@@ -891,13 +911,15 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         s.level = (uint32_t)lvl;
     }
 
-    SlotGrid grid[2] = {{0, 1, 1}, {0, 1, 1}};
+    SlotGrid grid[2] = {{0, 1, 1, 0, 0, 0, 0}, {0, 1, 1, 0, 0, 0, 0}};
     emit(best, *set, r, tau, pl->descs, grid);
-    if (best.nparts == 1) grid[1] = {(uint32_t)pl->descs.size(), 1, 1};
+    if (best.nparts == 1) grid[1] = {(uint32_t)pl->descs.size(), 1, 1, 0, 0, 0, 0};
     for (int i = 0; i < 2; ++i) {
         pl->slot_first[i] = grid[i].first;
         pl->slot_rows[i] = grid[i].rows;
         pl->slot_cols[i] = grid[i].cols;
+        pl->slot_m0[i] = grid[i].m_base; pl->slot_n0[i] = grid[i].n_base;
+        pl->slot_tm[i] = grid[i].tm; pl->slot_tn[i] = grid[i].tn;
     }
     s.n_ukernels = best.nparts;
     uint32_t lds = 0, klass = 0;
@@ -977,6 +999,26 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         pl->ws_tile_stride = stride;
     }
 
+    // The kernels derive a workgroup's tile in closed form from the grids above instead of reading
+    // the table: check that form against every descriptor; a plan that fails is walked in table
+    // order (its workgroups then read their descriptors).
+    if (!pl->table_order) {
+        const ftk::LaunchOrder o = launch_order_of(*pl);
+        const size_t total = pl->descs.size();
+        std::vector<char> seen(total, 0);
+        bool ok = true;
+        for (size_t b = 0; b < total && ok; ++b) {
+            const ftk::TileOfWorkgroup w = ftk::tile_of_workgroup(o, (uint32_t)b);
+            if (w.index >= total || seen[w.index]) { ok = false; break; }
+            seen[w.index] = 1;
+            const ft_tile_desc &d = pl->descs[w.index];
+            const uint32_t want_id = w.slot ? pl->slot_id[1] : pl->slot_id[0];
+            ok = d.batch == w.batch && d.m0 == w.m0 && d.n0 == w.n0 && d.ukernel_id == want_id;
+        }
+        if (!ok) pl->table_order = true;
+    }
+    s.table_order = pl->table_order ? 1u : 0u;
+
     if (!(flags & FT_PLAN_HOST_ONLY)) {
         st = ftd_upload(pl);
         if (st != FT_OK) { delete pl; return st; }
@@ -997,23 +1039,13 @@ ft_status ft_plan_launch_order(const ft_plan *plan, uint32_t *order, uint64_t ca
     // workgroups of the launch: the tiles, or for a plan walked in table order whole rounds of chunks
     const uint64_t total = plan->table_order ? ftk::table_grid((uint32_t)plan->descs.size(), plan->num_xcds) : plan->descs.size();
     *n = total;
-    ftk::LaunchOrder o;
-    o.n[0] = plan->slot_first[1] - plan->slot_first[0];
-    o.n[1] = (uint32_t)plan->descs.size() - plan->slot_first[1];
-    for (int i = 0; i < 2; ++i) {
-        o.first[i] = plan->slot_first[i];
-        o.rows[i] = plan->slot_rows[i];
-        o.cols[i] = plan->slot_cols[i];
-        o.group[i] = plan->slot_group[i];
-    }
-    o.nx = plan->num_xcds;
+    const ftk::LaunchOrder o = launch_order_of(*plan);
     for (uint64_t b = 0; b < total && b < cap; ++b) {
-        uint32_t slot;
         if (plan->table_order) {
             const uint32_t t = ftk::table_index_of_workgroup((uint32_t)b, plan->num_xcds);
             order[b] = t < plan->descs.size() ? t : UINT32_MAX;          // idle workgroup
         } else {
-            order[b] = ftk::tile_of_workgroup(o, (uint32_t)b, &slot);
+            order[b] = ftk::tile_of_workgroup(o, (uint32_t)b).index;
         }
     }
     return FT_OK;

@@ -26,15 +26,33 @@ struct LaunchOrder {
     uint32_t first[2];    // first descriptor of each constituent's block
     uint32_t rows[2], cols[2], group[2];
     uint32_t nx;          // XCDs
+    // what the descriptors of a constituent's block hold, in closed form: descriptor
+    // first + (batch * rows + r) * cols + c has m0 = m_base + r * tm, n0 = n_base + c * tn
+    uint32_t m_base[2], n_base[2], tm[2], tn[2];
 };
 
-FT_HD uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols, uint32_t G) {
-    if (rows < 2 || cols < 2 || G < 2) return u;
+// One workgroup's tile as the kernel derives it without reading the table (the table stays the
+// plan's definition: the host checks every workgroup's closed form against it when the plan is made).
+struct TileOfWorkgroup {
+    uint32_t index;       // descriptor index
+    uint32_t slot;        // constituent (0 or 1)
+    uint32_t batch, m0, n0;
+};
+
+// u-th tile of a constituent in launch order -> (batch entry, tile row, tile column) of its grid
+FT_HD void grouped_coords(uint32_t u, uint32_t rows, uint32_t cols, uint32_t G, uint32_t *bidx, uint32_t *row, uint32_t *col) {
     // (run-time divisions are costly on the device: a single batch entry and full groups of a
     // power-of-two height, the common cases, get by with one)
     const uint32_t per = rows * cols;
-    uint32_t bidx = 0, v = u;
-    if (u >= per) { bidx = u / per; v = u % per; }
+    uint32_t bi = 0, v = u;
+    if (u >= per) { bi = u / per; v = u % per; }
+    *bidx = bi;
+    if (rows < 2 || cols < 2 || G < 2) {
+        const uint32_t r = cols > 1 ? v / cols : v;
+        *row = r;
+        *col = v - r * cols;
+        return;
+    }
     const uint32_t grp = v / (G * cols), w = v - grp * (G * cols);
     const uint32_t first = grp * G;
     const uint32_t gr = rows - first < G ? rows - first : G;
@@ -47,13 +65,14 @@ FT_HD uint32_t grouped_index(uint32_t u, uint32_t rows, uint32_t cols, uint32_t 
         wq = w / gr;
         wr = w - wq * gr;
     }
-    return bidx * per + (first + wr) * cols + wq;
+    *row = first + wr;
+    *col = wq;
 }
 
 // descriptor index of workgroup b; *slot receives the constituent (0 or 1).  NX: the number of XCDs
 // when it is known at compile time (divisions by it become shifts), 0 to take it from o.nx.
 template <uint32_t NX>
-FT_HD uint32_t tile_of_workgroup_nx(const LaunchOrder &o, uint32_t b, uint32_t *slot) {
+FT_HD TileOfWorkgroup tile_of_workgroup_nx(const LaunchOrder &o, uint32_t b) {
     const uint32_t nx = NX ? NX : o.nx;
     const uint32_t x = b % nx, j = b / nx;
     const uint32_t q0 = o.n[0] / nx, r0 = o.n[0] % nx;
@@ -77,17 +96,24 @@ FT_HD uint32_t tile_of_workgroup_nx(const LaunchOrder &o, uint32_t b, uint32_t *
         }
         idx = x * q1 + before + (j - c0);
     }
-    *slot = s;
     // selects, not indexed loads: the fields stay in (scalar) registers on the device
     const uint32_t first = s ? o.first[1] : o.first[0], rows = s ? o.rows[1] : o.rows[0];
     const uint32_t cols = s ? o.cols[1] : o.cols[0], group = s ? o.group[1] : o.group[0];
-    return first + grouped_index(idx, rows, cols, group);
+    uint32_t bidx, row, col;
+    grouped_coords(idx, rows, cols, group, &bidx, &row, &col);
+    TileOfWorkgroup t;
+    t.slot = s;
+    t.index = first + (bidx * rows + row) * cols + col;
+    t.batch = bidx;
+    t.m0 = (s ? o.m_base[1] : o.m_base[0]) + row * (s ? o.tm[1] : o.tm[0]);
+    t.n0 = (s ? o.n_base[1] : o.n_base[0]) + col * (s ? o.tn[1] : o.tn[0]);
+    return t;
 }
 
-FT_HD uint32_t tile_of_workgroup(const LaunchOrder &o, uint32_t b, uint32_t *slot) {
+FT_HD TileOfWorkgroup tile_of_workgroup(const LaunchOrder &o, uint32_t b) {
     // integer division by a run-time value costs the device some forty instructions each, on the
     // critical path of every workgroup: the usual device (8 XCDs) gets its own instance
-    return o.nx == 8 ? tile_of_workgroup_nx<8>(o, b, slot) : tile_of_workgroup_nx<0>(o, b, slot);
+    return o.nx == 8 ? tile_of_workgroup_nx<8>(o, b) : tile_of_workgroup_nx<0>(o, b);
 }
 
 // Plans with more than two uKernel shapes (second-axis strips) are walked in table order, dealt to

@@ -136,6 +136,8 @@ def test_plans_bit_identical_to_oracle(name, mode):
         for i, (uid, _) in enumerate(pr.parts):
             sid, n_full, n_strip = pr.strips[i] if pr.strips else (-1, P.ceil_div(Wp, uks[uid].tn if want.tau == 0 else uks[uid].tm), 0)
             assert (st.strip_ukernel_id[i], st.main_tiles[i], st.strip_tiles[i]) == (sid if sid >= 0 else 0xFFFFFFFF, n_full, n_strip), (name, kw)
+        # the kernels' closed form of the descriptors held for every workgroup of every plan without strips
+        assert st.table_order == (1 if pr.strips else 0), (name, kw)
         slab = max(uks[i].tm * uks[i].tn for i, _ in pr.parts)
         assert st.workspace_bytes == (st.n_tiles * st.k_parts * slab * 4 if st.k_parts > 1 else 0)
 
