@@ -199,7 +199,10 @@ enum {
     FT_PLAN_PAD_BASELINE = 1u,     /* pad every dynamic axis to the largest uKernel (Fig. 2) */
     FT_PLAN_FORCED = 2u,           /* take the program given in ft_forced_program            */
     FT_PLAN_MODE_MASK = 3u,
-    FT_PLAN_HOST_ONLY = 16u        /* no device table; the plan cannot be launched           */
+    FT_PLAN_HOST_ONLY = 16u,       /* no device table; the plan cannot be launched           */
+    FT_PLAN_TABLE_ORDER = 32u      /* workgroups read their descriptors from the table even where
+                                      the closed form of the tile grids would do (ft_plan_stats.
+                                      table_order); same results, for debugging and comparison  */
 };
 
 /* Program to build when the mode is FT_PLAN_FORCED (used to measure every program of the

@@ -17,7 +17,7 @@ FT_OP_MATMUL, FT_OP_BMM, FT_OP_CONV2D = 0, 1, 2
 FT_F16, FT_BF16 = 0, 1
 FT_OUT_F32, FT_OUT_SAME = 0, 1
 FT_EPI_NONE, FT_EPI_BIAS = 0, 1
-FT_PLAN_PATCHWORK, FT_PLAN_PAD_BASELINE, FT_PLAN_FORCED, FT_PLAN_HOST_ONLY = 0, 1, 2, 16
+FT_PLAN_PATCHWORK, FT_PLAN_PAD_BASELINE, FT_PLAN_FORCED, FT_PLAN_HOST_ONLY, FT_PLAN_TABLE_ORDER = 0, 1, 2, 16, 32
 FT_SIA_LINEAR, FT_SIA_PRODUCT = 0, 1
 
 u32, u64, u16 = C.c_uint32, C.c_uint64, C.c_uint16

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     if (g.k_parts > 1) {
         part = (b / o.nx) % g.k_parts;
         b = (b / (o.nx * g.k_parts)) * o.nx + b % o.nx;
-        if (b >= g.n_tiles) return;
+        if (b >= (g.table_order ? table_grid(g.n_tiles, o.nx) : g.n_tiles)) return;
     }
     // A program of one or two uKernel shapes lays its tiles out as grids: the workgroup derives its
     // descriptor's contents in closed form and saves the dependent load from the table (about a

@@ -1017,6 +1017,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         }
         if (!ok) pl->table_order = true;
     }
+    if (flags & FT_PLAN_TABLE_ORDER) pl->table_order = true;
     s.table_order = pl->table_order ? 1u : 0u;
 
     if (!(flags & FT_PLAN_HOST_ONLY)) {

@@ -228,3 +228,26 @@ def test_extreme_reduce_extents_and_part_counts(M, N, K, forced):
     got = run(plan, A, B, M * N)
     check(got, ref, refabs, f"{M}x{N}x{K} forced {forced}")
     assert np.array_equal(run(plan, A, B, M * N), got)
+
+
+@pytest.mark.parametrize("M,N,K", [(1600, 768, 3072), (1232, 3072, 768), (80, 768, 768), (16, 4096, 4096)])
+def test_table_order_gives_the_same_bits(M, N, K):
+    """FT_PLAN_TABLE_ORDER: workgroups read their descriptors (dealt to the XCDs in chunks) instead
+    of deriving them from the tile grids; with and without a reduce-axis split the output must be
+    bit-identical to the default order's (same tiles, same summation order)."""
+    g = np.random.default_rng(M * 3 + N + K)
+    A = si.normal_bits(g, (M, K), 1.0, ft.FT_F16)
+    B = si.normal_bits(g, (K, N), 0.02, ft.FT_F16)
+    op = matmul_op(N, K, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    default = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    table = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_TABLE_ORDER)
+    sd, stt = ft.ft_plan_stats_get(default), ft.ft_plan_stats_get(table)
+    assert (sd.table_order, stt.table_order) == (0, 1) and sd.k_parts == stt.k_parts
+    assert ft.ft_plan_descriptors(default) == ft.ft_plan_descriptors(table)
+    order = ft.ft_plan_launch_order(table)
+    assert sorted(t for t in order if t != 0xFFFFFFFF) == list(range(stt.n_tiles))
+    ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
+    got = run(default, A, B, M * N)
+    check(got, ref, refabs, f"{M}x{N}x{K}")
+    assert np.array_equal(run(table, A, B, M * N), got)
