@@ -13,7 +13,9 @@ launches on this machine).
 Headline `value`: geomean over the 21 GEMMs of useful TFLOP/s with operands resident in HBM
 but NOT in cache (each launch uses the next of a ring of buffer sets totalling > 600 MB).
 The same measurement with a single, cache-warm buffer set is reported beside it as
-`warm_cache`, and the pad-to-library baseline plan as `pad_baseline`.
+`warm_cache`, the pad-to-library baseline plan as `pad_baseline`, the bucketed padding of serving
+stacks (M rounded up to the next power of two) as `bucketed_baseline`, and the latency of a single
+launch followed by a wait as `single_launch_us_geomean`.
 
 Prints ONE JSON line on stdout; per-GEMM details go to the JSON file named by --detail.
 """
@@ -48,10 +50,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="time one HIP-graph replay of the launches instead of direct launches")
-    ap.add_argument("--variants", default="cold,warm,base,out16",
+    ap.add_argument("--variants", default="cold,warm,base,out16,bucket,single",
                     help="comma list of the timed variants: cold (headline), warm (one buffer set), base "
                          "(pad-to-library plan), out16 (same sweep with C stored as fp16, reported beside the "
-                         "headline); 'cold' alone is what the committed profiles run")
+                         "headline), bucket (M padded to the next power of two, the planner's plan for that "
+                         "shape), single (one launch between two events, median of 5); 'cold' alone is what the "
+                         "committed profiles run")
     ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -70,7 +74,8 @@ def main():
     stream = side.cuda_stream
     use_graph = args.graph
     variants = set(args.variants.split(","))
-    assert "cold" in variants and variants <= {"cold", "warm", "base", "out16"}, "--variants: cold[,warm][,base][,out16]"
+    assert "cold" in variants and variants <= {"cold", "warm", "base", "out16", "bucket", "single"}, \
+        "--variants: cold[,warm][,base][,out16][,bucket][,single]"
     hw = ft.ft_hw_query(0)
 
     def timed(plan, pa, pb, pc, iters, graph=None):
@@ -99,6 +104,10 @@ def main():
                 ops[(N, K, 16)] = (op16, ft.ft_ukernels_derive(op16, hw, None), 0.0)
             op16, uks16, _ = ops[(N, K, 16)]
             rows[-1]["plan16"] = ft.ft_plan_create(op16, uks16, ft.ft_shape(m=M), ft.FT_PLAN_PATCHWORK)
+        if "bucket" in variants:                     # what a serving stack does: pad M to the next power of two
+            Mb = max(16, 1 << (M - 1).bit_length())
+            rows[-1]["Mb"] = Mb
+            rows[-1]["planb"] = ft.ft_plan_create(op, uks, ft.ft_shape(m=Mb), ft.FT_PLAN_PATCHWORK)
 
     per_class_time = {}
     per_class_flops = {}
@@ -133,7 +142,24 @@ def main():
         if "out16" in variants:                      # C buffers are large enough for either type
             timed(r["plan16"], pa, pb, pc, max(1, args.warmup), graph=False)
             ms_out16 = timed(r["plan16"], pa, pb, pc, args.steps)
+        ms_bucket = float("inf")
+        if "bucket" in variants:                     # same GEMM with M padded to its bucket, the planner's own plan for it
+            Mb = r["Mb"]
+            nb = max(2, int(math.ceil(RING_BYTES / (2 * (Mb * K + K * N) + 4 * Mb * N))))
+            Ab = [torch.zeros((Mb, K), dtype=torch.int16, device="cuda") for _ in range(nb)]
+            for t in Ab:
+                t[:M].copy_(A0)
+            Cb = [torch.empty((Mb, N), dtype=torch.float32, device="cuda") for _ in range(nb)]
+            qa, qb, qc = [t.data_ptr() for t in Ab], [Bs[i % n_sets].data_ptr() for i in range(nb)], [t.data_ptr() for t in Cb]
+            timed(r["planb"], qa, qb, qc, max(1, args.warmup), graph=False)
+            ms_bucket = timed(r["planb"], qa, qb, qc, args.steps)
+            del Ab, Cb
+        us_single = float("inf")
+        if "single" in variants:                     # one launch between two events, then a wait: median of 5
+            one = sorted(timed(r["plan"], pa[i + 1:i + 2], pb[i + 1:i + 2], pc[i + 1:i + 2], 1, graph=False) for i in range(5))
+            us_single = one[2] * 1e3
         t_roof = max(flops / (MFMA_PEAK_TFLOPS * 1e12), bytes_alg / (HBM_PEAK_GBS * 1e9))
+        r.update(ms_bucket=ms_bucket, tflops_bucket=flops / ms_bucket / 1e9, us_single=us_single)
         r.update(ms_cold=ms_cold, ms_warm=ms_warm, ms_base=ms_base, ms_out16=ms_out16, tflops_out16=flops / ms_out16 / 1e9,
                  flops=flops, bytes_alg=bytes_alg,
                  tflops_cold=flops / ms_cold / 1e9, tflops_warm=flops / ms_warm / 1e9,
@@ -190,6 +216,13 @@ def main():
                         "ms_per_step": round(sum(r["ms_out16"] for r in rows), 5),
                         "note": "same sweep, cold, C rounded to fp16 in the epilogue (not the headline: the "
                                 "north star fixes fp32 output)"} if "out16" in variants else None,
+        "bucketed_baseline": {"value": round(geomean([r["tflops_bucket"] for r in rows]), 3),
+                              "ms_per_step": round(sum(r["ms_bucket"] for r in rows), 5),
+                              "padding_waste_pct": round(100.0 * (1.0 - sum(r["M"] * r["N"] for r in rows) /
+                                                                  sum(r["Mb"] * r["N"] for r in rows)), 3),
+                              "note": "M padded to the next power of two (>= 16), the planner's own plan for the padded "
+                                      "shape, useful flops of the true M; cold"} if "bucket" in variants else None,
+        "single_launch_us_geomean": round(geomean([r["us_single"] for r in rows]), 3) if "single" in variants else None,
         "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
         "roofline": {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
                      "achieved": round(achieved_gbs if hbm_bound else achieved, 3),
@@ -237,7 +270,7 @@ def main():
 
     os.makedirs(os.path.dirname(args.detail), exist_ok=True)
     with open(args.detail, "w") as f:
-        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base", "plan16")} for r in rows], f, indent=1)
+        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base", "plan16", "planb")} for r in rows], f, indent=1)
     print(json.dumps(out), flush=True)
 
 
