@@ -109,6 +109,17 @@ def main():
             rows[-1]["Mb"] = Mb
             rows[-1]["planb"] = ft.ft_plan_create(op, uks, ft.ft_shape(m=Mb), ft.FT_PLAN_PATCHWORK)
 
+    # the same plans through the per-shape cache: what a serving loop pays per call once a shape was seen
+    for r in rows:
+        op, uks, _ = ops[(r["N"], r["K"])]
+        ft.ft_plan_cached(op, uks, ft.ft_shape(m=r["M"]))
+    t0 = time.perf_counter()
+    for _ in range(50):
+        for r in rows:
+            op, uks, _ = ops[(r["N"], r["K"])]
+            ft.ft_plan_cached(op, uks, ft.ft_shape(m=r["M"]))
+    t_plan_cached_us = (time.perf_counter() - t0) * 1e6 / (50 * len(rows))
+
     per_class_time = {}
     per_class_flops = {}
     per_class_launches = {}
@@ -224,6 +235,7 @@ def main():
                                       "shape, useful flops of the true M; cold"} if "bucket" in variants else None,
         "single_launch_us_geomean": round(geomean([r["us_single"] for r in rows]), 3) if "single" in variants else None,
         "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
+        "plan_us_cached_lookup": round(t_plan_cached_us, 2),
         "roofline": {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
                      "achieved": round(achieved_gbs if hbm_bound else achieved, 3),
                      "peak": HBM_PEAK_GBS if hbm_bound else MFMA_PEAK_TFLOPS,

@@ -269,6 +269,14 @@ typedef struct ft_plan ft_plan;
  * at zero, and the sum over the parts is taken in part order, so results are reproducible. */
 ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_forced_program *forced, ft_plan **out);
+/* The same plan through the set's per-shape cache (Sec. 5: the runtime stage is paid once per shape;
+ * with kernels of a few microseconds a plan must not be rebuilt per call): returns the plan made
+ * earlier for the same shape and flags, or makes it (as ft_plan_create would, on the current HIP
+ * device unless FT_PLAN_HOST_ONLY) and keeps it.  *out stays owned by the set: valid until
+ * ft_ukset_destroy, never passed to ft_plan_destroy.  Safe to call from several threads; mode
+ * FT_PLAN_FORCED is not cached (FT_ERR_INVALID_ARG). */
+ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags,
+                         const ft_plan **out);
 /* *descs: host pointer to library-owned memory, valid until ft_plan_destroy. */
 ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, uint64_t *n);
 /* Which descriptor each workgroup of the launch takes (Sec. 3: one uKernel = one thread block):

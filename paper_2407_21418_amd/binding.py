@@ -113,6 +113,7 @@ SYMBOLS = {
     "ft_ukset_get": (C.c_int32, [_P, u32, C.POINTER(ft_ukernel_info)]),
     "ft_ukset_destroy": (None, [_P]),
     "ft_plan_create": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, C.POINTER(ft_forced_program), C.POINTER(_P)]),
+    "ft_plan_cached": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, C.POINTER(_P)]),
     "ft_plan_descriptors": (C.c_int32, [_P, C.POINTER(C.POINTER(ft_tile_desc)), C.POINTER(u64)]),
     "ft_plan_launch_order": (C.c_int32, [_P, C.POINTER(u32), u64, C.POINTER(u64)]),
     "ft_plan_stats_get": (C.c_int32, [_P, C.POINTER(ft_plan_stats)]),
@@ -246,6 +247,21 @@ def ft_plan_descriptors(p: Plan) -> bytes:
     if n.value == 0:
         return b""
     return C.string_at(ptr, n.value * C.sizeof(ft_tile_desc))
+
+
+class CachedPlan:
+    """A plan owned by its uKernel set's cache: same .ptr interface as Plan, never destroyed here.
+    Keeps the set alive."""
+
+    def __init__(self, ptr, owner):
+        self.ptr = ptr
+        self._owner = owner
+
+
+def ft_plan_cached(op: Op, s: UkSet, shape: ft_shape, flags: int = FT_PLAN_PATCHWORK) -> CachedPlan:
+    out = _P()
+    _check(lib().ft_plan_cached(op.ptr, s.ptr, C.byref(shape), flags, C.byref(out)), "ft_plan_cached")
+    return CachedPlan(out.value, s)
 
 
 def ft_plan_launch_order(p: Plan):

@@ -1,6 +1,8 @@
 // Internal types shared by the host logic (host.cpp) and the HIP-facing code (device.hip).
 #pragma once
 #include <stdint.h>
+#include <map>
+#include <mutex>
 #include <vector>
 
 #include "ftuner.h"
@@ -15,6 +17,10 @@ struct ft_ukset {
     ft_tuning t;
     std::vector<ft_ukernel_info> uk;   // canonical order
     uint64_t cap_q;                    // best compute_eff of the set (normaliser of Eq. 1's CMR term)
+    // per-shape plan cache (ft_plan_cached): key = (flags, batch, m, n, k, img_n, img_h, img_w); the
+    // set owns the plans
+    std::mutex cache_mu;
+    std::map<std::vector<uint32_t>, ft_plan *> cache;
 };
 
 struct ft_plan {

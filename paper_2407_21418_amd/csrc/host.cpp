@@ -725,7 +725,11 @@ ft_status ft_ukset_get(const ft_ukset *set, uint32_t i, ft_ukernel_info *out) {
     return FT_OK;
 }
 
-void ft_ukset_destroy(ft_ukset *set) { delete set; }
+void ft_ukset_destroy(ft_ukset *set) {
+    if (!set) return;
+    for (auto &kv : set->cache) ft_plan_destroy(kv.second);
+    delete set;
+}
 
 static ft_status check_common(const ft_op *op, const ft_ukset *set, const ft_shape *shape, Resolved *r) {
     if (!op || !set || !shape || shape->struct_size != sizeof(ft_shape)) return FT_ERR_INVALID_ARG;
@@ -1024,6 +1028,25 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         st = ftd_upload(pl);
         if (st != FT_OK) { delete pl; return st; }
     }
+    *out = pl;
+    return FT_OK;
+}
+
+ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags, const ft_plan **out) {
+    if (!op || !set || !shape || !out || shape->struct_size != sizeof(ft_shape)) return FT_ERR_INVALID_ARG;
+    if ((flags & FT_PLAN_MODE_MASK) == FT_PLAN_FORCED) return FT_ERR_INVALID_ARG;
+    const std::vector<uint32_t> key = {flags, shape->batch, shape->m, shape->n, shape->k,
+                                       shape->img_n, shape->img_h, shape->img_w};
+    std::lock_guard<std::mutex> lock(set->cache_mu);
+    auto it = set->cache.find(key);
+    if (it != set->cache.end()) {
+        *out = it->second;
+        return FT_OK;
+    }
+    ft_plan *pl = nullptr;
+    ft_status st = ft_plan_create(op, set, shape, flags, nullptr, &pl);
+    if (st != FT_OK) return st;
+    set->cache.emplace(key, pl);
     *out = pl;
     return FT_OK;
 }

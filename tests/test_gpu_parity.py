@@ -395,3 +395,15 @@ def test_timing_entry_points_leave_correct_results():
             check(out_view(b, 272 * 768), ref, refabs, f"timed launch graph={use_graph}")
         # eager work between the replays
         check(run(plan, p["A"], p["B"], 272 * 768), ref, refabs, "eager launch between timed runs")
+
+
+def test_cached_plan_launches_like_a_fresh_one():
+    p = si.config1_problem(528, 768, 768)
+    op = matmul_op(768, 768, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    cached = ft.ft_plan_cached(op, s, ft.ft_shape(m=528))
+    assert ft.ft_plan_cached(op, s, ft.ft_shape(m=528)).ptr == cached.ptr
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    got = run(cached, p["A"], p["B"], 528 * 768)
+    check(got, ref, refabs, "cached plan")
+    assert np.array_equal(got, run(ft.ft_plan_create(op, s, ft.ft_shape(m=528)), p["A"], p["B"], 528 * 768))

@@ -378,3 +378,31 @@ def test_batch_bound_of_a_batched_workload():
         lop = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=1, m_hi=512, n_lo=1, n_hi=512, batch_hi=bh))
         s = ft.ft_ukernels_derive(lop)
         assert ft.ft_ukset_size(s) == len(want)
+
+
+def test_plan_cache_returns_the_same_plan_per_shape_and_flags():
+    op = OPS["dense768"]
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop)
+    a = ft.ft_plan_cached(lop, s, ft.ft_shape(m=1232), HOST)
+    b = ft.ft_plan_cached(lop, s, ft.ft_shape(m=1232), HOST)
+    c = ft.ft_plan_cached(lop, s, ft.ft_shape(m=1233), HOST)
+    d = ft.ft_plan_cached(lop, s, ft.ft_shape(m=1232), HOST | ft.FT_PLAN_PAD_BASELINE)
+    assert a.ptr == b.ptr and len({a.ptr, c.ptr, d.ptr}) == 3
+    fresh = ft.ft_plan_create(lop, s, ft.ft_shape(m=1232), HOST)
+    assert ft.ft_plan_descriptors(a) == ft.ft_plan_descriptors(fresh)
+    sa, sf = ft.ft_plan_stats_get(a), ft.ft_plan_stats_get(fresh)
+    assert (sa.n_tiles, sa.sia_q20, sa.k_parts) == (sf.n_tiles, sf.sia_q20, sf.k_parts)
+    with pytest.raises(ft.FtError):                      # forced programs are not cached
+        ft.ft_plan_cached(lop, s, ft.ft_shape(m=1232), HOST | ft.FT_PLAN_FORCED)
+    with pytest.raises(ft.FtError):                      # errors of ft_plan_create pass through, nothing is cached
+        ft.ft_plan_cached(lop, s, ft.ft_shape(m=9000), HOST)
+    # many threads asking for the same new shape get one plan
+    import threading
+    got = []
+    def ask():
+        got.append(ft.ft_plan_cached(lop, s, ft.ft_shape(m=777), HOST).ptr)
+    th = [threading.Thread(target=ask) for _ in range(8)]
+    [t.start() for t in th]
+    [t.join() for t in th]
+    assert len(set(got)) == 1
