@@ -40,10 +40,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     // first use, so a cold scalar cache would be missed several times in a row (about half a
     // microsecond each, on the critical path of every workgroup).  Touch every line once, up front
     // and in parallel; the later loads hit.  Measured: +2.5 % on the sweep of small GEMMs (a few
-    // hundred workgroups per launch, all in their first round); the general dispatchers, whose
-    // launches on odd-pitch attention shapes have thousands of short workgroups, lost 10-30 % with
-    // it and go without.
-#ifndef FT_GENERIC
+    // hundred workgroups per launch, all in their first round).
     {
         const auto ka = __builtin_amdgcn_kernarg_segment_ptr();
         static_assert(sizeof(KArgs) > 0x100 && sizeof(KArgs) <= 0x140, "one load per 64-byte line of the arguments");
@@ -58,7 +55,6 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
                      : "s"(ka)
                      : "memory");
     }
-#endif
     LaunchOrder o;
     o.n[0] = g.slot_first[1] - g.slot_first[0];
     o.n[1] = g.n_tiles - g.slot_first[1];
@@ -98,17 +94,19 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
         const TileOfWorkgroup w = tile_of_workgroup(o, b);
         t = w.index;
         slot = w.slot;
-#ifdef FT_GENERIC
-        // The general dispatchers keep the load.  Their heaviest launches (odd-pitch attention
-        // scores: thousands of short workgroups bound by misaligned fp32 stores) ran 10-30 % SLOWER
-        // with either prologue shortcut (this one or the argument prefetch): workgroups that start
-        // faster reach their store phase more in step with each other.
-        d = g.descs[t];
-#else
         d.ukernel_id = 0; d.m_valid = 0; d.n_valid = 0; d.flags = 0;          // not used by the bodies
         d.batch = w.batch; d.m0 = w.m0; d.n0 = w.n0;
-#endif
     }
+    // Everything a body gets from here is the same for all lanes; say so.  Without it the
+    // compiler's uniformity analysis gave up in the general dispatchers after small changes to
+    // this prologue and built the buffer-store descriptors of every body in "waterfall" loops
+    // (4 000 instead of 80 v_readfirstlane in the kernel, 10 more VGPRs): the store-bound attention
+    // launches ran 10-30 % slower.
+    d.batch = __builtin_amdgcn_readfirstlane(d.batch);
+    d.m0 = __builtin_amdgcn_readfirstlane(d.m0);
+    d.n0 = __builtin_amdgcn_readfirstlane(d.n0);
+    slot = __builtin_amdgcn_readfirstlane(slot);
+    t = __builtin_amdgcn_readfirstlane(t);
     const uint32_t code = slot == 0 ? g.slot_code[0] : slot == 1 ? g.slot_code[1] : slot == 2 ? g.slot_code[2] : g.slot_code[3];
     const uint32_t stages = slot == 0 ? g.slot_stages[0] : slot == 1 ? g.slot_stages[1] : slot == 2 ? g.slot_stages[2] : g.slot_stages[3];
     switch (code) {
