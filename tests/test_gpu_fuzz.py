@@ -1,0 +1,65 @@
+"""Seeded random shapes through the planner's own plans: Matmul with any M, N, K (aligned to 8
+elements or not), both input types, optional bias / 16-bit output, optional forced reduce-axis split
+and table order.  Same oracle and tolerance as the other parity tests; the cases are fixed by the
+seed, so a failure names its case."""
+import numpy as np
+import pytest
+
+import paper_2407_21418_amd as ft
+import synth_inputs as si
+from oracle import contraction as oc
+
+from gpu_util import check, check_epilogue, run, run_epilogue
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(n=72):
+    g = np.random.default_rng(20240721)
+    out = []
+    for i in range(n):
+        aligned = bool(g.integers(0, 2))
+        q = 8 if aligned else 1
+        M = int(g.integers(1, 700))
+        N = int(g.integers(1, 130)) * q if aligned else int(g.integers(1, 1040))
+        K = int(g.integers(1, 260)) * q if aligned else int(g.integers(1, 2080))
+        dtype = int(g.integers(0, 2))
+        epi = int(g.integers(0, 4))            # 0 plain, 1 bias, 2 16-bit C, 3 both
+        parts = int(g.choice([0, 0, 2, 3, 5])) if aligned else 0
+        table = bool(g.integers(0, 4) == 0)
+        out.append((i, M, N, K, dtype, epi, parts, table))
+    return out
+
+
+@pytest.mark.parametrize("case", _cases(), ids=lambda c: "c%d_%dx%dx%d_dt%d_e%d_p%d_t%d" % (c[0], c[1], c[2], c[3], c[4], c[5], c[6], int(c[7])))
+def test_random_matmul(case):
+    i, M, N, K, dtype, epi, parts, table = case
+    g = np.random.default_rng(1000 + i)
+    A = si.normal_bits(g, (M, K), 1.0, dtype)
+    B = si.normal_bits(g, (K, N), 0.1, dtype)
+    bias = g.standard_normal(N).astype(np.float32) if epi & 1 else None
+    out16 = dtype if epi & 2 else None
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dtype, n=N, k=K, m_lo=0, m_hi=1024,
+                                         out_dtype=ft.FT_OUT_SAME if epi & 2 else ft.FT_OUT_F32,
+                                         epilogue=ft.FT_EPI_BIAS if epi & 1 else ft.FT_EPI_NONE))
+    s = ft.ft_ukernels_derive(op)
+    flags = ft.FT_PLAN_TABLE_ORDER if table else 0
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), flags)
+    st = ft.ft_plan_stats_get(plan)
+    covered_rows = sum(st.count_tau[j] * ft.ft_ukset_get(s, st.ukernel_id[j]).tm for j in range(st.n_ukernels))
+    # (a program that pads the rows beyond the 16-row granule -- the fallback when no uKernel
+    # extent fits -- cannot be named through ft_forced_program, which takes exact covers only)
+    if parts and covered_rows == -(-M // 16) * 16:
+        # the planner's program again, its tiles split over `parts` workgroups
+        forced = ft.ft_forced_program(k1=st.ukernel_id[0], count1=st.count_tau[0],
+                                      k2=st.ukernel_id[1] if st.n_ukernels == 2 else 0,
+                                      count2=st.count_tau[1] if st.n_ukernels == 2 else 0, k_parts=parts)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED | flags, forced)
+    ref, refabs = oc.matmul(A, B, dtype, want_abs=True)
+    if epi:
+        if bias is not None:
+            ref = ref + bias[None, :]
+        got = run_epilogue(plan, A, B, M * N, bias=bias, out16=out16)
+        check_epilogue(got, ref, refabs, bias[None, :] if bias is not None else None, out16, str(case))
+    else:
+        check(run(plan, A, B, M * N), ref, refabs, str(case))
