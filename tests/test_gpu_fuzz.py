@@ -63,3 +63,46 @@ def test_random_matmul(case):
         check_epilogue(got, ref, refabs, bias[None, :] if bias is not None else None, out16, str(case))
     else:
         check(run(plan, A, B, M * N), ref, refabs, str(case))
+
+
+def _bmm_cases(n=48):
+    g = np.random.default_rng(99173)
+    out = []
+    for i in range(n):
+        aligned = bool(g.integers(0, 2))
+        q = 8 if aligned else 1
+        nb = int(g.integers(1, 7))
+        M = int(g.integers(1, 400))
+        N = int(g.integers(1, 50)) * q if aligned else int(g.integers(1, 400))
+        K = int(g.integers(1, 40)) * q if aligned else int(g.integers(1, 300))
+        dtype = int(g.integers(0, 2))
+        strips = bool(g.integers(0, 2))
+        parts = int(g.choice([0, 0, 2, 3])) if aligned and not strips else 0
+        out.append((i, nb, M, N, K, dtype, strips, parts))
+    return out
+
+
+@pytest.mark.parametrize("case", _bmm_cases(), ids=lambda c: "b%d_%dx%dx%dx%d_dt%d_s%d_p%d" % (c[0], c[1], c[2], c[3], c[4], c[5], int(c[6]), c[7]))
+def test_random_batched_matmul_all_axes_dynamic(case):
+    """Batched Matmul with every extent dynamic (two dynamic space axes: the second-axis strips can
+    apply and are switched on for half of the cases)."""
+    i, nb, M, N, K, dtype, strips, parts = case
+    g = np.random.default_rng(5000 + i)
+    A = si.normal_bits(g, (nb, M, K), 1.0, dtype)
+    B = si.normal_bits(g, (nb, K, N), 0.2, dtype)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=512, n_lo=0, n_hi=512,
+                                         k_lo=0, k_hi=512, batch_hi=768))
+    t = ft.ft_tuning_default()
+    t.second_axis_strips = 1 if strips else 0
+    s = ft.ft_ukernels_derive(op, None, t)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=M, n=N, k=K))
+    st = ft.ft_plan_stats_get(plan)
+    tau_ext = lambda u: u.tm if st.tau == 0 else u.tn
+    covered = sum(st.count_tau[j] * tau_ext(ft.ft_ukset_get(s, st.ukernel_id[j])) for j in range(st.n_ukernels))
+    if parts and covered == -(-(M if st.tau == 0 else N) // 16) * 16:
+        forced = ft.ft_forced_program(k1=st.ukernel_id[0], count1=st.count_tau[0],
+                                      k2=st.ukernel_id[1] if st.n_ukernels == 2 else 0,
+                                      count2=st.count_tau[1] if st.n_ukernels == 2 else 0, k_parts=parts)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=M, n=N, k=K), ft.FT_PLAN_FORCED, forced)
+    ref, refabs = oc.bmm(A, B, dtype, want_abs=True)
+    check(run(plan, A, B, nb * M * N), ref, refabs, str(case))
