@@ -47,6 +47,34 @@ def _resource_usage(log):
     return out
 
 
+OBJDUMP = os.environ.get("LLVM_OBJDUMP", "/opt/rocm/llvm/bin/llvm-objdump")
+
+
+def _readfirstlane_count(obj):
+    """Number of v_readfirstlane in the device code of one of our own dispatcher objects, or None
+    if the tools are missing.  A dispatcher has a few hundred (wave ids, uniform addresses).  Several
+    thousand mean the compiler lost track of what is uniform per workgroup and wrapped the buffer
+    accesses of every body in per-lane "waterfall" loops: such a build ran the store-bound
+    attention launches 10-30 % slower."""
+    import glob
+    import shutil
+    import tempfile
+    if not os.path.exists(OBJDUMP):
+        return None
+    tmp = tempfile.mkdtemp(prefix="ftuner_objdump_")
+    try:
+        local = os.path.join(tmp, os.path.basename(obj))
+        shutil.copy(obj, local)
+        subprocess.run([OBJDUMP, "--offloading", local], stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        dev = glob.glob(local + ".*gfx950*")
+        if not dev:
+            return None
+        p = subprocess.run([OBJDUMP, "-d", dev[0]], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
+        return p.stdout.count("v_readfirstlane_b32")
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+
+
 def _stale(obj, srcs):
     if not os.path.exists(obj):
         return True
@@ -102,6 +130,12 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False):
         allowed = 32 if "_gen_" in os.path.basename(obj) else 0
         if use.get("ScratchSize [bytes/lane]", 0) > allowed:
             raise RuntimeError(f"{os.path.basename(obj)} uses scratch memory: {use}")
+        n_rfl = _readfirstlane_count(obj)
+        if verbose or remarks:
+            print(f"    v_readfirstlane in its device code: {n_rfl}", flush=True)
+        if n_rfl is not None and n_rfl > 1500:
+            raise RuntimeError(f"{os.path.basename(obj)}: {n_rfl} v_readfirstlane: per-workgroup values are no longer "
+                               "known to be uniform (waterfall loops around buffer accesses)")
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in steps]
     _run(link, os.path.join(OUT, "link.log"))
     if verbose:
