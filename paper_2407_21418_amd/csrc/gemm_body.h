@@ -59,6 +59,7 @@ struct KArgs {
     // taking k-tiles [p * k_part_tiles, (p + 1) * k_part_tiles); partial tiles meet in ws
     uint32_t k_parts, k_part_tiles;
     uint32_t ws_tile_stride;          // floats between consecutive (tile, part) slabs of ws
+    uint32_t c_stream;                // 1: C is stored with the non-temporal hint (see store_acc_as)
     float *ws;                        // [n_tiles][k_parts][ws_tile_stride] fp32 partial tiles
     uint32_t *arrive;                 // [n_tiles][4] arrival counters, zero between launches
 };
@@ -102,12 +103,34 @@ __device__ __forceinline__ uint4 ld16(const uint16_t *p) {
 }
 
 // 8 elements starting at p, of which the first nvalid (0..8) exist; the rest read as zero.
+// Element by element: only for rows shorter than one chunk.
 __device__ __forceinline__ uint4 ld_partial(const uint16_t *p, int nvalid) {
     uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int e = 0; e < 8; ++e)
         if (e < nvalid) w[e >> 1] |= (uint32_t)p[e] << ((e & 1) * 16);
     return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// The 128-bit value v moved down by s elements of 16 bits, zeros moving in (s >= 8: all zero).
+// Selects only, so that no lane waits on another's branch.
+__device__ __forceinline__ uint4 shift_down_elems(uint4 v, uint32_t s) {
+    const bool s4 = s & 4u, s2 = s & 2u, s1 = s & 1u;
+    v = s4 ? make_uint4(v.z, v.w, 0u, 0u) : v;
+    v = s2 ? make_uint4(v.y, v.z, v.w, 0u) : v;
+    v = s1 ? make_uint4((v.x >> 16) | (v.y << 16), (v.y >> 16) | (v.z << 16), (v.z >> 16) | (v.w << 16), v.w >> 16) : v;
+    return s >= 8u ? make_uint4(0u, 0u, 0u, 0u) : v;
+}
+
+// The chunk of 8 elements at position x of a row of len >= 8 elements, elements beyond the row's
+// end reading as zero.  A chunk that straddles the end is fetched as the row's last 8 elements
+// and moved down, one 16-byte load from inside the row whatever x is: every lane issues its
+// load at once, where element-wise loads under a branch would queue one latency after another.
+__device__ __forceinline__ uint4 ld_row_chunk(const uint16_t *row, uint32_t x, uint32_t len, bool row_exists) {
+    const bool full = x + 8u <= len;
+    const uint32_t over = full ? 0u : (x + 8u - len < 8u ? x + 8u - len : 8u);
+    const uint4 v = ld16(row + (full ? x : len - 8u));
+    return shift_down_elems(v, row_exists ? over : 8u);
 }
 
 // Output element kinds of the epilogue: fp32, or the accumulator (+ bias) rounded once, to nearest
@@ -136,9 +159,12 @@ template <int OUT> __device__ __forceinline__ typename OutElem<OUT>::type out_cv
 // 16x16 block: acc[j]       -> row 4*(lane/16) + j,        column lane % 16
 // A wave tile that lies wholly inside C (uniform test) is stored without predication from one
 // per-lane pointer: one 64-bit add per row, the column blocks go into the instruction offsets.
-// C is written once and never read by this kernel: the stores are marked non-temporal so they
-// stream past the caches instead of evicting the operand panels (measured: +6 % on the bench sweep).
-template <int OUT, bool INTERIOR_PATH, bool M16, int BM, int BN, typename Acc>
+// C is written once and never read by this kernel. With STREAM the stores carry the non-temporal
+// hint and stream past the caches instead of evicting the operand panels (measured: +6 % on the
+// bench sweep). The hint is only safe for speed when every store instruction fills whole 128-byte
+// lines: partial lines written this way are not merged in the L2 and cost 2-3x the time of a plain
+// store (measured on fp32 score matrices with odd row pitch), so the host sets it per launch.
+template <int OUT, bool INTERIOR_PATH, bool STREAM, bool M16, int BM, int BN, typename Acc>
 __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const float *__restrict__ bias, uint32_t ldc,
                                              uint32_t M, uint32_t N, uint32_t m0w, uint32_t n0w, uint32_t lane,
                                              const Acc (&acc)[BM][BN]) {
@@ -161,7 +187,11 @@ __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const floa
                 const uint32_t r = bi * MB + (M16 ? e : 8 * (e / 4) + (e % 4));
                 T *rp = lp + (uint64_t)r * ldc;
 #pragma unroll
-                for (int bj = 0; bj < BN; ++bj) __builtin_nontemporal_store(out_cvt<OUT>(acc[bi][bj][e] + bv[bj]), &rp[bj * MB]);
+                for (int bj = 0; bj < BN; ++bj) {
+                    const T v = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
+                    if constexpr (STREAM) __builtin_nontemporal_store(v, &rp[bj * MB]);
+                    else rp[bj * MB] = v;
+                }
             }
         return;
     }
@@ -177,7 +207,7 @@ __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const floa
     const uint32_t num_records = ((rows_valid - 1) * ldc + cols_valid) * ES;
     T *tile = Cb + ((uint64_t)m0u * ldc + n0u);
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(tile, 0, (int)num_records, 0x00020000);
-    constexpr int AUX_NT = 2;             // cache-policy bits of the buffer instruction: nt (streaming)
+    constexpr int AUX_NT = STREAM ? 2 : 0;   // cache-policy bits of the buffer instruction: nt (streaming)
     uint32_t vb[BN];
 #pragma unroll
     for (int bj = 0; bj < BN; ++bj)
@@ -205,10 +235,13 @@ template <int DT, bool INTERIOR_PATH, bool M16, int BM, int BN, typename Acc>
 __device__ __forceinline__ void store_acc(const KArgs &g, uint64_t coff, uint32_t m0w, uint32_t n0w, uint32_t lane,
                                           const Acc (&acc)[BM][BN]) {
     constexpr int OUT16 = DT == 0 ? OUT_F16 : OUT_BF16;
-    if (g.out_kind == OUT_F32)
-        store_acc_as<OUT_F32, INTERIOR_PATH, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
-    else
-        store_acc_as<OUT16, INTERIOR_PATH, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+    if (g.out_kind == OUT_F32) {
+        if (g.c_stream) store_acc_as<OUT_F32, INTERIOR_PATH, true, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+        else store_acc_as<OUT_F32, INTERIOR_PATH, false, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+    } else {
+        // 16-bit outputs are always streamed (the host never clears c_stream for them)
+        store_acc_as<OUT16, INTERIOR_PATH, true, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+    }
 }
 
 template <int DT, int WM, int WN, int GM, int GN, int TK>
@@ -312,7 +345,8 @@ struct UKernelBody {
             for (int i = 0; i < A_ITERS; ++i) {
                 if (!g.is_conv) {
                     const uint16_t *p = Ab + a_off[i] + k0;
-                    if (!careful || kk + 8 <= K) ra[i] = ld16(p);
+                    if (!careful) ra[i] = ld16(p);
+                    else if (K >= 8u) ra[i] = ld_row_chunk(p - kk, kk, K, true);
                     else ra[i] = ld_partial(p, kk < K ? (int)(K - kk) : 0);
                 } else {
                     // k = (r*S + s)*Cin + c ; input pixel (p*stride - pad + r, q*stride - pad + s)
@@ -348,6 +382,10 @@ struct UKernelBody {
                 const uint16_t *p = pk + (b_off0 + i * b_rstep_ld);
                 if (!careful) { rb[i] = ld16(p); continue; }
                 uint32_t kr = k0 + b_krow0 + i * B_RSTEP;
+                if (N >= 8u) {
+                    rb[i] = ld_row_chunk(Bb + (kr < K ? kr : K - 1u) * g.ldb, b_col, N, kr < K);
+                    continue;
+                }
                 if (kr >= K) rb[i] = make_uint4(0, 0, 0, 0);
                 else if (b_col + 8 <= N) rb[i] = ld16(p);
                 else if (b_col < N) rb[i] = ld_partial(Bb + (kr * g.ldb + b_col), (int)(N - b_col));

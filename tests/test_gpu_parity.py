@@ -44,7 +44,8 @@ def test_every_ukernel_body(body, dtype, aligned):
     """Each compiled body alone (forced single-uKernel program): 2 x 2 tiles with a ragged tail
     on both axes, a k extent that is not a multiple of the k-tile, and batch 2.  aligned: row
     lengths are multiples of 8 elements (LDS-DMA bodies, zero-page k tail); otherwise odd row
-    lengths (general bodies: unaligned vector loads, element-wise partial chunks)."""
+    lengths (general bodies: unaligned vector loads, chunks that straddle a row's end fetched from
+    inside the row and shifted)."""
     tm, tn, wm, wn, gm, gn = body
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=8192, n_lo=0, n_hi=8192,
                                          k_lo=0, k_hi=4096))
@@ -120,7 +121,7 @@ def test_two_ukernel_program_mixed_in_one_launch():
     check(run(plan, p["A"], p["B"], M * N), ref, refabs, "mixed program")
 
 
-@pytest.mark.parametrize("L", [1, 7, 33, 77, 100, 257])
+@pytest.mark.parametrize("L", [1, 7, 8, 9, 15, 33, 77, 100, 257])
 def test_attention_bmm_dynamic_length(L):
     """QK^T (two dynamic space axes) and PV (dynamic reduce axis) with odd lengths: rows that
     are not 16-byte aligned, partial chunks, k tails."""
