@@ -408,3 +408,39 @@ def test_cached_plan_launches_like_a_fresh_one():
     got = run(cached, p["A"], p["B"], 528 * 768)
     check(got, ref, refabs, "cached plan")
     assert np.array_equal(got, run(ft.ft_plan_create(op, s, ft.ft_shape(m=528)), p["A"], p["B"], 528 * 768))
+
+
+def test_chained_dense_layers_on_one_stream():
+    """Three Dense + bias-add launches (Sec. 6.2) issued back to back on one stream with no host
+    wait, each reading the 16-bit C of the one before it, plans from the per-shape cache: every
+    stage is checked against the oracle applied to the bits that stage actually read."""
+    M, H, F = 300, 768, 3072
+    g = np.random.default_rng(4242)
+    dt = ft.FT_F16
+    ctx = si.normal_bits(g, (M, H), 1.0, dt)
+    stages = [("o", H, H), ("ffn1", F, H), ("ffn2", H, F)]
+    Wb = {n: si.normal_bits(g, (k, nn), 0.03, dt) for n, nn, k in stages}
+    bias = {n: g.normal(0, 0.5, nn).astype(np.float32) for n, nn, k in stages}
+    plans = {}
+    for n, nn, k in stages:
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dt, n=nn, k=k, m_lo=1, m_hi=8192,
+                                             out_dtype=ft.FT_OUT_SAME, epilogue=ft.FT_EPI_BIAS))
+        plans[n] = ft.ft_plan_cached(op, ft.ft_ukernels_derive(op), ft.ft_shape(m=M))
+    dW = {n: dev_bits(Wb[n]) for n in Wb}
+    dB = {n: torch.from_numpy(bias[n]).cuda() for n in bias}
+    bufs = {"ctx": dev_bits(ctx)}
+    for n, nn, k in stages:
+        bufs[n] = torch.full((M * nn,), 0x7e00, dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    src = "ctx"
+    for n, nn, k in stages:
+        ft.ft_launch_epilogue(plans[n], bufs[src].data_ptr(), dW[n].data_ptr(), bufs[n].data_ptr(), dB[n].data_ptr(), stream())
+        src = n
+    torch.cuda.synchronize()
+    src_bits = ctx
+    for n, nn, k in stages:
+        got_bits = bufs[n].cpu().numpy().view(np.uint16).reshape(M, nn)
+        ref, refabs = oc.matmul(src_bits, Wb[n], dt, want_abs=True)
+        ref = oe.add_bias(ref, bias[n])
+        check_epilogue(got_bits.view(np.float16).astype(np.float64), ref, refabs, bias[n], dt, f"chained stage {n}")
+        src_bits = got_bits
