@@ -71,15 +71,17 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const fl
     a->ws_tile_stride = p->ws_tile_stride;
     a->ws = static_cast<float *>(p->d_ws);
     a->arrive = static_cast<uint32_t *>(p->d_arrive);
-    // Non-temporal stores stream past the L2, which keeps the operand panels resident.  Where rows of
-    // C do not start on 128-byte lines, neighbouring tiles share lines; a streamed partial line goes
-    // to memory as it is, a plain one waits in the L2 for its other half (the launch order keeps a
-    // batch entry's tiles on one XCD).  Measured on fp32 score matrices with odd row pitch: plain
-    // stores win by 10-20 % when the reduce axis is a single k-tile (the launch is one long store
-    // stream), streamed ones win or tie with more k-tiles and with 16-bit outputs.
+    // Non-temporal stores stream past the L2, which keeps the operand panels resident.  A store
+    // instruction writes 128-byte row segments; where rows of C do not start on 64-byte blocks the
+    // segments of neighbouring tiles share blocks, a streamed partial block goes to memory as it is
+    // and a plain one waits in the L2 for its other half (the launch order keeps a batch entry's
+    // tiles on one XCD).  Measured on fp32 score matrices: with rows on 64-byte blocks streamed
+    // stores win (L = 240: 45 vs 58 us); otherwise plain stores win by 10-20 % when the reduce axis is
+    // a single k-tile (the launch is one long store stream), streamed ones win or tie with more
+    // k-tiles and with 16-bit outputs.
     const uint64_t es = a->out_kind == ftk::OUT_F32 ? 4 : 2;
-    const bool lines = reinterpret_cast<uintptr_t>(C) % 128 == 0 && (a->ldc * es) % 128 == 0 &&
-                       (a->strideC * es) % 128 == 0;
+    const bool lines = reinterpret_cast<uintptr_t>(C) % 64 == 0 && (a->ldc * es) % 64 == 0 &&
+                       (a->strideC * es) % 64 == 0;
     a->c_stream = (lines || es == 2 || a->K > 64) ? 1u : 0u;
 }
 

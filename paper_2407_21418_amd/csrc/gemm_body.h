@@ -161,8 +161,8 @@ template <int OUT> __device__ __forceinline__ typename OutElem<OUT>::type out_cv
 // per-lane pointer: one 64-bit add per row, the column blocks go into the instruction offsets.
 // C is written once and never read by this kernel. With STREAM the stores carry the non-temporal
 // hint and stream past the caches instead of evicting the operand panels (measured: +6 % on the
-// bench sweep). The hint is only safe for speed when every store instruction fills whole 128-byte
-// lines: partial lines written this way are not merged in the L2 and cost 2-3x the time of a plain
+// bench sweep). The hint is only safe for speed when every store instruction fills whole 64-byte
+// blocks: partial blocks written this way are not merged in the L2 and cost 2-3x the time of a plain
 // store (measured on fp32 score matrices with odd row pitch), so the host sets it per launch.
 template <int OUT, bool INTERIOR_PATH, bool STREAM, bool M16, int BM, int BN, typename Acc>
 __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const float *__restrict__ bias, uint32_t ldc,
