@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--dtype", choices=["f16", "bf16"], default="f16")
     ap.add_argument("--batch", type=int, default=16)
+    ap.add_argument("--lengths", default=",".join(str(t) for t in TABLE6_T), help="comma list of T (default: Table 6's)")
     a = ap.parse_args()
 
     import torch
@@ -67,7 +68,8 @@ def main():
         ops[name] = (op, ft.ft_ukernels_derive(op, hw, None))
     W = [{name: rand16((k, n)) for name, n, k in LAYER_GEMMS} for _ in range(a.layers)]
     bias = [{name: torch.zeros(n, dtype=torch.float32, device="cuda") for name, n, k in LAYER_GEMMS} for _ in range(a.layers)]
-    m_max = a.batch * max(TABLE6_T)
+    lengths = [int(t) for t in a.lengths.split(",")]
+    m_max = a.batch * max(lengths)
     m_cap = 1 << (m_max - 1).bit_length()
     x = rand16((m_cap, HIDDEN))
     ctx = rand16((m_cap, HIDDEN))
@@ -110,7 +112,7 @@ def main():
         return e0.elapsed_time(e1) * 1e3 / (a.iters * a.layers), t_lookup * 1e6 / n_launch, t_issue * 1e6 / n_launch
 
     rows = []
-    for T in TABLE6_T:
+    for T in lengths:
         M = a.batch * T
         Mb = max(16, 1 << (M - 1).bit_length())
         us_patch, us_lookup, us_issue = timed(M, ft.FT_PLAN_PATCHWORK)
