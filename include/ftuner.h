@@ -312,7 +312,8 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
  *   Conv2d: A = X [n,H,W,c_in], B = W [r,s,c_in,c_out], C = Y [n,P,Q,c_out] fp32.
  * A, B, C: device pointers owned by the caller (A, B at least 2-byte aligned, C 4-byte
  * aligned; 16-byte aligned A/B with row lengths that are multiples of 8 take the vector
- * path).  hip_stream: a hipStream_t (NULL = default stream).  Asynchronous; allocates
+ * path; any N is correct, rows of C that start on 64-byte blocks are written fastest, since
+ * neighbouring tiles then share no block of memory).  hip_stream: a hipStream_t (NULL = default stream).  Asynchronous; allocates
  * nothing and does not synchronise.  An empty plan launches nothing.  The current HIP device must
  * be the one the plan was created on (else FT_ERR_INVALID_ARG).
  * ------------------------------------------------------------------------------------- */
