@@ -47,7 +47,12 @@ def main():
     ap.add_argument("--dtype", choices=["f16", "bf16"], default="f16")
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--lengths", default=",".join(str(t) for t in TABLE6_T), help="comma list of T (default: Table 6's)")
+    ap.add_argument("--variants", default="patch,base,bucket",
+                    help="comma list: patch (the planner's plan, always run), base (pad-to-library plan), "
+                         "bucket (M padded to the next power of two); 'patch' alone is what the committed profile runs")
     a = ap.parse_args()
+    variants = set(a.variants.split(","))
+    assert variants <= {"patch", "base", "bucket"}, "--variants: patch[,base][,bucket]"
 
     import torch
     import paper_2407_21418_amd as ft
@@ -116,8 +121,8 @@ def main():
         M = a.batch * T
         Mb = max(16, 1 << (M - 1).bit_length())
         us_patch, us_lookup, us_issue = timed(M, ft.FT_PLAN_PATCHWORK)
-        us_base, _, _ = timed(M, ft.FT_PLAN_PAD_BASELINE)
-        us_bucket, _, _ = timed(Mb, ft.FT_PLAN_PATCHWORK)
+        us_base = timed(M, ft.FT_PLAN_PAD_BASELINE)[0] if "base" in variants else float("nan")
+        us_bucket = timed(Mb, ft.FT_PLAN_PATCHWORK)[0] if "bucket" in variants else float("nan")
         fl = layer_flops(M)
         rows.append(dict(T=T, M=M, us_per_layer=round(us_patch, 2), tflops=round(fl / us_patch / 1e6, 1),
                          us_per_layer_pad_baseline=round(us_base, 2), us_per_layer_bucketed=round(us_bucket, 2),
@@ -125,7 +130,10 @@ def main():
         print("T=%3d M=%4d  %7.1f us/layer %6.1f TFLOP/s | pad baseline %7.1f us (x%.2f) | bucketed to M=%4d %7.1f us (x%.2f) | host %.1f us/launch (lookup %.1f)"
               % (T, M, us_patch, fl / us_patch / 1e6, us_base, us_base / us_patch, Mb, us_bucket, us_bucket / us_patch,
                  us_issue, us_lookup), flush=True)
-    gm = lambda xs: math.exp(sum(math.log(v) for v in xs) / len(xs))
+    def gm(xs):
+        xs = [v for v in xs if v == v]
+        return math.exp(sum(math.log(v) for v in xs) / len(xs)) if xs else float("nan")
+
     print(json.dumps({"workload": "BERT-base dense layers chained, %d layers, batch %d, T in Table 6's lengths, %s in/out, bias fused"
                                   % (a.layers, a.batch, a.dtype),
                       "geomean_tflops": round(gm([r["tflops"] for r in rows]), 1),
