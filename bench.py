@@ -43,6 +43,37 @@ def geomean(xs):
     return math.exp(sum(math.log(x) for x in xs) / len(xs))
 
 
+def private_l2_floor_bytes(ft, np, plan, K, num_xcds):
+    """Bytes one launch of this plan must move across the L2 <-> fabric boundary when every XCD has
+    its own L2 and nothing is fetched twice by the same XCD: each XCD reads once the rows of A and the
+    columns of B that its tiles touch (workgroup b runs on XCD b % num_xcds), and C is written once.
+    Partial tiles of a reduce-axis split are not counted (the parts of a tile share an XCD)."""
+    desc = np.frombuffer(ft.ft_plan_descriptors(plan), dtype=np.dtype(
+        [("uk", "<u4"), ("batch", "<u4"), ("m0", "<u4"), ("n0", "<u4"), ("mv", "<u2"), ("nv", "<u2"), ("flags", "<u4")]))
+    rows = [set() for _ in range(num_xcds)]
+    cols = [set() for _ in range(num_xcds)]
+    c_elems = 0
+    for e, t in enumerate(ft.ft_plan_launch_order(plan)):
+        if t == 0xFFFFFFFF:
+            continue
+        d = desc[t]
+        x = e % num_xcds
+        rows[x].add((int(d["m0"]), int(d["mv"])))
+        cols[x].add((int(d["n0"]), int(d["nv"])))
+        c_elems += int(d["mv"]) * int(d["nv"])
+
+    def covered(spans):                               # length of the union of [start, start + len)
+        n, end = 0, 0
+        for a, l in sorted(spans):
+            lo, hi = max(a, end), a + l
+            if hi > lo:
+                n += hi - lo
+                end = hi
+        return n
+    read = sum(covered(rows[x]) + covered(cols[x]) for x in range(num_xcds)) * K * 2
+    return read + 4 * c_elems
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +155,7 @@ def main():
     per_class_flops = {}
     per_class_launches = {}
     per_class_bytes = {}
+    per_class_floor = {}
     for r in rows:
         M, N, K = r["M"], r["N"], r["K"]
         p = si.config1_problem(M, N, K)
@@ -179,6 +211,8 @@ def main():
                  kernel_class=st.kernel_class, useful=st.useful_elems, covered=st.covered_elems,
                  base_covered=sb.covered_elems, base_tiles=sb.n_tiles)
         k = "ft_dispatch_dt0_c%d" % st.kernel_class
+        r["bytes_private_l2_floor"] = private_l2_floor_bytes(ft, np, r["plan"], K, hw.num_xcds)
+        per_class_floor[k] = per_class_floor.get(k, 0.0) + r["bytes_private_l2_floor"] * args.steps
         per_class_time[k] = per_class_time.get(k, 0.0) + ms_cold * args.steps
         per_class_flops[k] = per_class_flops.get(k, 0.0) + flops * args.steps
         per_class_launches[k] = per_class_launches.get(k, 0) + args.steps
@@ -249,6 +283,11 @@ def main():
                      "traffic_note": "L2-miss read + write-back bytes per launch (rocprofv3 --pmc, copy-calibrated; "
                                      "Infinity Cache hits included), algorithmic bytes per launch: %d" % round(
                                          per_class_bytes[dom] / per_class_launches[dom]),
+                     "traffic_floor_private_l2": round(per_class_floor[dom] / per_class_launches[dom]),
+                     "traffic_floor_note": "bytes per launch if each of the 8 XCDs (private L2s) fetches the A rows and "
+                                           "B columns of its own tiles exactly once and C is written once, from the "
+                                           "plans' launch order; traffic above it is what the L2s re-fetch or the "
+                                           "reduce-axis split exchanges",
                      "avg_launch_us": round(1e3 * per_class_time[dom] / per_class_launches[dom], 3),
                      "launches": per_class_launches[dom],
                      "note": "achieved = algorithmic bytes (hbm) or useful flops (mfma) of the launches that ran "
