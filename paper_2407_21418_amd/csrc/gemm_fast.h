@@ -94,6 +94,80 @@ __device__ __forceinline__ bool k_part_exchange(const KArgs &g, uint32_t t, uint
     return true;
 }
 
+// s_waitcnt vmcnt(0) that also "produces" the registers of one row of blocks: the loads into them
+// are all issued above it and no use of them can be scheduled above it.
+template <int BN, typename Blk>
+__device__ __forceinline__ void landed(Blk (&row)[BN]) {
+    static_assert(BN == 1 || BN == 2 || BN == 4 || BN == 8, "blocks per row of a wave tile");
+    if constexpr (BN == 1) asm volatile("s_waitcnt vmcnt(0)" : "+v"(row[0]) :: "memory");
+    else if constexpr (BN == 2) asm volatile("s_waitcnt vmcnt(0)" : "+v"(row[0]), "+v"(row[1]) :: "memory");
+    else if constexpr (BN == 4)
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(row[0]), "+v"(row[1]), "+v"(row[2]), "+v"(row[3]) :: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(row[0]), "+v"(row[1]), "+v"(row[2]), "+v"(row[3]), "+v"(row[4]),
+                     "+v"(row[5]), "+v"(row[6]), "+v"(row[7]) :: "memory");
+}
+
+// The exchange for a wave's accumulator blocks (register r = ((bi * BN) + bj) * NE + e, as the slab
+// layout numbers them).  The loads of a slab are in flight together: into the accumulators themselves
+// for the first slab, into temporaries for the others -- a whole tile of them where it has at most
+// 64 registers, else one row of blocks at a time.  Written out this way because the compiler, left to
+// itself, waits for each load of a 128-register tile before it issues the next (measured: 27 us per
+// slab instead of 2).
+template <bool M16, int BM, int BN, typename Acc>
+__device__ __forceinline__ bool k_part_exchange_blocks(const KArgs &g, uint32_t t, uint32_t part, uint32_t wave,
+                                                       uint32_t lane, Acc (&acc)[BM][BN]) {
+    constexpr int NE = M16 ? 4 : 16, NREGW = BM * BN * NE;
+    constexpr int RB = NREGW <= 64 ? BM : 1;          // rows of blocks per batch of loads
+    const uint64_t tile0 = (uint64_t)t * g.k_parts * g.ws_tile_stride;
+    const uint32_t in_slab = wave * (NREGW * 64) + lane;
+    float *mine = g.ws + tile0 + (uint64_t)part * g.ws_tile_stride + in_slab;
+#pragma unroll
+    for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                __hip_atomic_store(mine + ((bi * BN + bj) * NE + e) * 64, acc[bi][bj][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!k_part_arrive_last(g, t, wave)) return false;
+    const float *p = g.ws + tile0 + in_slab;
+#pragma unroll
+    for (int b0 = 0; b0 < BM; b0 += RB) {
+#pragma unroll
+        for (int bi = b0; bi < b0 + RB; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                for (int e = 0; e < NE; ++e)
+                    acc[bi][bj][e] = __hip_atomic_load(p + ((bi * BN + bj) * NE + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int bi = b0; bi < b0 + RB; ++bi) landed<BN>(acc[bi]);
+    }
+    for (uint32_t q = 1; q < g.k_parts; ++q) {
+        p += g.ws_tile_stride;
+#pragma unroll
+        for (int b0 = 0; b0 < BM; b0 += RB) {
+            Acc other[RB][BN];
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                    for (int e = 0; e < NE; ++e)
+                        other[i][bj][e] = __hip_atomic_load(p + (((b0 + i) * BN + bj) * NE + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < RB; ++i) landed<BN>(other[i]);
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int bj = 0; bj < BN; ++bj)
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) acc[b0 + i][bj][e] += other[i][bj][e];
+        }
+    }
+    return true;
+}
+
 template <int DT, int WM, int WN, int GM, int GN>
 struct UKernelFast {
     static constexpr int TK = 64;
@@ -286,10 +360,7 @@ struct UKernelFast {
         // ---- epilogue ------------------------------------------------------------------------------
         // (bodies with more than 128 accumulator registers have no room for it: the host never splits them)
         if constexpr (WM * WN / 64 <= FT_KPART_ACC_MAX) if (g.k_parts > 1) {
-            constexpr int NE = M16 ? 4 : 16;
-            auto get = [&](int r) -> float { return acc[r / (BN * NE)][(r / NE) % BN][r % NE]; };
-            auto set = [&](int r, float x) { acc[r / (BN * NE)][(r / NE) % BN][r % NE] = x; };
-            if (!k_part_exchange<BM * BN * NE>(g, t, part, wave, lane, get, set)) return;
+            if (!k_part_exchange_blocks<M16>(g, t, part, wave, lane, acc)) return;
         }
         store_acc<DT, true, M16, BM, BN>(g, (uint64_t)d.batch * g.strideC, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
     }
