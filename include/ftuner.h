@@ -70,7 +70,9 @@ typedef struct ft_hw_model {
     uint32_t hbm_gbytes_per_s;               /* 8000; used for rooflines only                */
     uint32_t num_xcds;                       /* 8                                            */
     uint32_t part_exchange_clk;              /* reduce-axis split: latency of handing a partial
-                                                tile to the workgroup that sums them (4000)   */
+                                                tile to the workgroup that sums them (2000)   */
+    uint32_t part_exchange_bytes_per_clk;    /* rate at which that workgroup reads the k_parts
+                                                fp32 partial tiles (16); 0: not counted       */
 } ft_hw_model;
 
 /* gfx950 defaults; host only. out: host pointer. */

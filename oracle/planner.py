@@ -38,7 +38,8 @@ def default_hw():
                 max_waves_per_simd=8, lds_bytes_per_cu=163840, clock_mhz=2400,
                 mfma_flops_per_clk_per_cu=4096, bw_global_bytes_per_clk_per_cu=64,
                 bw_lds_bytes_per_clk_per_cu=256, ktile_latency_clk=400, solo_copy_exposed_pct=50,
-                part_exchange_clk=4000,
+                part_exchange_clk=2000,
+                part_exchange_bytes_per_clk=16,
                 hbm_gbytes_per_s=8000, num_xcds=8)
 
 
@@ -625,13 +626,17 @@ def cmr_split(u, block_bound, k_parts, K, hw, out_bytes):
     """compute_eff of uKernel u on this shape: the cached value when a tile is one workgroup; for
     a reduce-axis split, Eq. 6 re-evaluated on one part: its share of the k-tiles, 8 more bytes of
     global traffic per output element (the fp32 partial written once and read once) and the
-    exchange's round trips (part_exchange_clk)."""
+    exchange: its round trips (part_exchange_clk) plus the time the workgroup that arrives last
+    needs to read the k_parts fp32 partial tiles (tm * tn * 4 bytes each) at
+    part_exchange_bytes_per_clk (0 switches this term off)."""
     if k_parts == 1:
         return cmr_at(u, block_bound)
     r = 2 if min(u.max_wg_per_cu, block_bound) >= 2 else 1
     k_part = part_tiles(K, u.tk, k_parts) * u.tk
+    rate = hw["part_exchange_bytes_per_clk"]
+    exchange = hw["part_exchange_clk"] + ((k_parts * u.tm * u.tn * 4) // rate if rate else 0)
     cn, cd = compute_eff(u.tm, u.tn, u.gm, u.gn, k_part, hw, u.gk, u.tk, residents=r,
-                         out_bytes=out_bytes + 8, exchange_clk=hw["part_exchange_clk"])
+                         out_bytes=out_bytes + 8, exchange_clk=exchange)
     return (cn << Q) // cd
 
 

@@ -42,7 +42,7 @@ class ft_hw_model(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "num_cus", "simds_per_cu", "wave_size", "regs_per_lane", "max_waves_per_simd",
         "lds_bytes_per_cu", "clock_mhz", "mfma_flops_per_clk_per_cu", "bw_global_bytes_per_clk_per_cu",
-        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds", "part_exchange_clk")]
+        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds", "part_exchange_clk", "part_exchange_bytes_per_clk")]
 
 
 class ft_tuning(_S):

@@ -38,7 +38,8 @@ void hw_defaults(ft_hw_model *h) {
     h->solo_copy_exposed_pct = 50;
     h->hbm_gbytes_per_s = 8000;
     h->num_xcds = 8;
-    h->part_exchange_clk = 4000;
+    h->part_exchange_clk = 2000;
+    h->part_exchange_bytes_per_clk = 16;
 }
 
 void tuning_defaults(ft_tuning *t) {
@@ -246,8 +247,12 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
         const bool shared = std::min<uint32_t>(u.max_wg_per_cu, p.block_bound) >= 2;
         if (k_parts == 1) return shared ? u.cmr_shared_q20 : u.cmr_q20;
         u128 cn, cd;
+        // the exchange: round trips, plus the last workgroup reading k_parts fp32 partial tiles
+        const uint64_t slabs = (uint64_t)k_parts * u.tm * u.tn * 4;
+        const uint64_t exchange = hw.part_exchange_clk +
+                                  (hw.part_exchange_bytes_per_clk ? slabs / hw.part_exchange_bytes_per_clk : 0);
         compute_eff(u.tm, u.tn, u.gm, u.gn, u.gk, u.tk, part_tiles(K, u.tk, k_parts) * u.tk, shared ? 2 : 1,
-                    out_bytes + 8, hw, &cn, &cd, hw.part_exchange_clk);
+                    out_bytes + 8, hw, &cn, &cd, (uint32_t)exchange);
         return (uint64_t)((cn << QBITS) / cd);
     };
     uint64_t acc = 0;

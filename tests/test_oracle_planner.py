@@ -416,7 +416,9 @@ def test_split_program_counts_workgroups():
     assert (split.num_tiles, split.block_bound, split.occ_q) == (150, 2, (450 << 20) // 512)
     assert split.pad_q == whole.pad_q == 1 << 20 and split.k_parts == 3
     # its compute_eff is Eq. 6 on 16 k-tiles with the exchange, two workgroups per CU, normalised
-    n, d = P.compute_eff(64, 128, u.gm, u.gn, 1024, hw, residents=2, out_bytes=12, exchange_clk=hw["part_exchange_clk"])
+    # exchange: 2000 clk of round trips + 3 partial tiles of 64 x 128 fp32 read at 16 bytes per clock
+    assert (hw["part_exchange_clk"], hw["part_exchange_bytes_per_clk"]) == (2000, 16)
+    n, d = P.compute_eff(64, 128, u.gm, u.gn, 1024, hw, residents=2, out_bytes=12, exchange_clk=2000 + 3 * 64 * 128 * 4 // 16)
     assert split.cmr_q == (min((n << 20) // d, cap) << 20) // cap
     assert split.sia_q == (((split.cmr_q * split.pad_q) >> 20) * split.occ_q) >> 20
 
