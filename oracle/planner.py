@@ -316,7 +316,8 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     """Compile stage: HardwareAlign, then the filters of Alg. 1 and Sec. 4.3 over the workload
     (IsOverflow, Eq. 4 at block.bound = 1, CrossPick, Eq. 5, Eq. 6), in the canonical set order: larger
     smem_tile area first.  If no uKernel survives the workload filters (ranges too small to
-    ever fill the device), the set before them is kept."""
+    ever fill the device), the set before them is kept; likewise Eq. 6's threshold psi is not applied
+    when no uKernel reaches it (a reduce axis of a few elements: every loop is latency)."""
     hw = hw or default_hw()
     t = t or default_tuning()
     m_s, n_s, _ = op.gemm_static()
@@ -325,6 +326,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     shapes = workload_shapes(op)
     cand = []
     kept = []
+    psi_ok = []
     for wm, wn, mfma in wave_tiles():
         for gm, gn, gk in WAVE_GRIDS:
             if gk > 1 and not (256 <= wm * wn <= 4096):
@@ -355,8 +357,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     continue                                        # Eq. 4, block.bound = 1
                 budget = reg_budget(regs, hw)
                 cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, out_bytes=op.out_bytes)
-                if cn * t["psi_den"] < t["psi_num"] * cd:
-                    continue                                        # Eq. 6
+                psi_ok.append(cn * t["psi_den"] >= t["psi_num"] * cd)          # Eq. 6
                 cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
                           hw["max_waves_per_simd"])
                 cn2, cd2 = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, residents=2, out_bytes=op.out_bytes)
@@ -367,6 +368,8 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                     kept.append(op.batch_hi == 0 or passes_workload(tm, tn, shapes, hw, t, op.batch_hi))
                 else:
                     kept.append(passes_workload(tm, tn, shapes, hw, t))
+    if any(psi_ok):
+        cand, kept = [u for u, ok in zip(cand, psi_ok) if ok], [k for k, ok in zip(kept, psi_ok) if ok]
     if any(kept):
         cand = [u for u, k in zip(cand, kept) if k]
     cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))

@@ -629,7 +629,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
         if (sv.m) ms.assign(1, sv.m); else axis_samples(op->d.m_lo, op->d.m_hi, cap, ms);
         if (sv.n) ns.assign(1, sv.n); else axis_samples(op->d.n_lo, op->d.n_hi, cap, ns);
     }
-    std::vector<char> kept;
+    std::vector<char> kept, psi_ok;
     static const uint32_t sizes[4] = {16, 32, 64, 128};
     // wave grids over (rows, columns, reduce axis); the split-k grid lets each wave own the whole
     // tile and a quarter of k (accumulator tiles of 1024..4096 elements only)
@@ -668,7 +668,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 u128 cn, cd;
                 const uint32_t out_bytes = op->d.out_dtype == FT_OUT_SAME ? ELT : 4;
                 compute_eff(tm, tn, gm, gn, gk, tk, kref, 1, out_bytes, h, &cn, &cd);
-                if (cn * t.psi_den < (u128)t.psi_num * cd) continue;     // Eq. 6
+                psi_ok.push_back(cn * t.psi_den >= (u128)t.psi_num * cd ? 1 : 0);   // Eq. 6
                 ft_ukernel_info u;
                 std::memset(&u, 0, sizeof(u));
                 u.struct_size = sizeof(u);
@@ -689,6 +689,15 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                     kept.push_back(passes_workload(tm, tn, ms, ns, 1, h, t) ? 1 : 0);
             }
         }
+    // Eq. 6's threshold, unless no uKernel reaches it (a reduce axis of a few elements)
+    if (std::find(psi_ok.begin(), psi_ok.end(), 1) != psi_ok.end()) {
+        std::vector<ft_ukernel_info> f;
+        std::vector<char> fk;
+        for (size_t i = 0; i < set->uk.size(); ++i)
+            if (psi_ok[i]) { f.push_back(set->uk[i]); fk.push_back(kept[i]); }
+        set->uk.swap(f);
+        kept.swap(fk);
+    }
     // K.Filter: the uKernels that pass the workload filters; all of them if none does
     if (std::find(kept.begin(), kept.end(), 1) != kept.end()) {
         std::vector<ft_ukernel_info> f;

@@ -1,7 +1,10 @@
 """Seeded random shapes through the planner's own plans: Matmul with any M, N, K (aligned to 8
 elements or not), both input types, optional bias / 16-bit output, optional forced reduce-axis split
 and table order.  Same oracle and tolerance as the other parity tests; the cases are fixed by the
-seed, so a failure names its case."""
+seed, so a failure names its case.  FT_FUZZ_SEED / FT_FUZZ_CASES in the environment draw another or a
+longer list (a soak run; the defaults are what the suite runs)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -14,8 +17,13 @@ from gpu_util import check, check_epilogue, run, run_epilogue
 pytestmark = pytest.mark.gpu
 
 
+FUZZ_SEED = int(os.environ.get("FT_FUZZ_SEED", "20240721"))
+FUZZ_CASES = int(os.environ.get("FT_FUZZ_CASES", "0"))
+
+
 def _cases(n=72):
-    g = np.random.default_rng(20240721)
+    n = FUZZ_CASES or n
+    g = np.random.default_rng(FUZZ_SEED)
     out = []
     for i in range(n):
         aligned = bool(g.integers(0, 2))
@@ -34,7 +42,7 @@ def _cases(n=72):
 @pytest.mark.parametrize("case", _cases(), ids=lambda c: "c%d_%dx%dx%d_dt%d_e%d_p%d_t%d" % (c[0], c[1], c[2], c[3], c[4], c[5], c[6], int(c[7])))
 def test_random_matmul(case):
     i, M, N, K, dtype, epi, parts, table = case
-    g = np.random.default_rng(1000 + i)
+    g = np.random.default_rng([1000 + i, FUZZ_SEED])
     A = si.normal_bits(g, (M, K), 1.0, dtype)
     B = si.normal_bits(g, (K, N), 0.1, dtype)
     bias = g.standard_normal(N).astype(np.float32) if epi & 1 else None
@@ -66,7 +74,8 @@ def test_random_matmul(case):
 
 
 def _bmm_cases(n=48):
-    g = np.random.default_rng(99173)
+    n = FUZZ_CASES or n
+    g = np.random.default_rng(99173 if FUZZ_SEED == 20240721 else FUZZ_SEED + 1)
     out = []
     for i in range(n):
         aligned = bool(g.integers(0, 2))
@@ -87,7 +96,7 @@ def test_random_batched_matmul_all_axes_dynamic(case):
     """Batched Matmul with every extent dynamic (two dynamic space axes: the second-axis strips can
     apply and are switched on for half of the cases)."""
     i, nb, M, N, K, dtype, strips, parts = case
-    g = np.random.default_rng(5000 + i)
+    g = np.random.default_rng([5000 + i, FUZZ_SEED])
     A = si.normal_bits(g, (nb, M, K), 1.0, dtype)
     B = si.normal_bits(g, (nb, K, N), 0.2, dtype)
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=512, n_lo=0, n_hi=512,

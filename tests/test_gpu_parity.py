@@ -444,3 +444,17 @@ def test_chained_dense_layers_on_one_stream():
         ref = oe.add_bias(ref, bias[n])
         check_epilogue(got_bits.view(np.float16).astype(np.float64), ref, refabs, bias[n], dt, f"chained stage {n}")
         src_bits = got_bits
+
+
+@pytest.mark.parametrize("K", [1, 8, 12])
+def test_reduce_axis_of_a_few_elements(K):
+    """A static K below anything Eq. 6's threshold admits: the uKernel set is still derived and the
+    product is right (bf16, odd M, N = 304)."""
+    M, N = 543, 304
+    g = np.random.default_rng(31 + K)
+    A = si.normal_bits(g, (M, K), 1.0, ft.FT_BF16)
+    B = si.normal_bits(g, (K, N), 1.0, ft.FT_BF16)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_BF16, n=N, k=K, m_lo=0, m_hi=1024))
+    plan = ft.ft_plan_create(op, ft.ft_ukernels_derive(op), ft.ft_shape(m=M))
+    ref, refabs = oc.matmul(A, B, ft.FT_BF16, want_abs=True)
+    check(run(plan, A, B, M * N), ref, refabs, f"K={K}")

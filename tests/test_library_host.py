@@ -45,6 +45,7 @@ OPS = {
     "conv": P.Op(P.OP_CONV2D, P.F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1, m_range=(0, 1 << 22)),
     "odd_static_n": P.Op(P.OP_MATMUL, P.F16, n=1000, k=100, m_range=(1, 4096)),
     "dense3072_out16": P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(0, 8192), out_bytes=2),
+    "tiny_k": P.Op(P.OP_MATMUL, P.BF16, n=304, k=12, m_range=(0, 1024)),
 }
 
 
@@ -82,6 +83,8 @@ def shapes_for(name):
         ms = [1, 77, 1000, 4096]
     if name == "llm4096":
         ms = [1, 16, 45, 128, 300, 512, 1024, 2048, 8192]
+    if name == "tiny_k":
+        ms = [1, 77, 543, 1024]
     return [dict(m=m) for m in ms]
 
 

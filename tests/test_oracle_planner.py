@@ -558,3 +558,17 @@ def test_strips_only_when_asked_for_and_with_two_dynamic_axes():
     assert P.plan(one_axis, P.derive_ukernels(one_axis), (96, 141, 64, 141), t=on).program.strips == []
     mm = P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(0, 8192))
     assert P.plan(mm, P.derive_ukernels(mm), (1, 1232, 768, 768), t=on).program.strips == []
+
+
+def test_eq6_threshold_is_dropped_only_when_nothing_reaches_it():
+    """Eq. 6: with a reduce axis of a few elements every loop is latency and no uKernel reaches psi;
+    the set must not come out empty (the threshold is then not applied).  Where some reach it, those
+    that do not are still filtered out."""
+    hw, t = P.default_hw(), P.default_tuning()
+    below = lambda u, k: (lambda n, d: n * t["psi_den"] < t["psi_num"] * d)(
+        *P.compute_eff(u.tm, u.tn, u.gm, u.gn, k, hw, u.gk, u.tk, out_bytes=4))
+    tiny = P.derive_ukernels(P.Op(P.OP_MATMUL, P.BF16, n=304, k=12, m_range=(0, 1024)))
+    assert tiny and all(below(u, 12) for u in tiny)
+    assert P.plan(P.Op(P.OP_MATMUL, P.BF16, n=304, k=12, m_range=(0, 1024)), tiny, (1, 543, 304, 12)).descs
+    usual = P.derive_ukernels(P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(0, 8192)))
+    assert usual and not any(below(u, 768) for u in usual)
