@@ -115,3 +115,50 @@ def test_random_batched_matmul_all_axes_dynamic(case):
         plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=nb, m=M, n=N, k=K), ft.FT_PLAN_FORCED, forced)
     ref, refabs = oc.bmm(A, B, dtype, want_abs=True)
     check(run(plan, A, B, nb * M * N), ref, refabs, str(case))
+
+
+def _conv_cases(n=32):
+    n = FUZZ_CASES or n
+    g = np.random.default_rng(4711 if FUZZ_SEED == 20240721 else FUZZ_SEED + 2)
+    out = []
+    for i in range(n):
+        R = int(g.choice([1, 3, 5]))
+        S = int(g.choice([1, 3, 5]))
+        stride = int(g.integers(1, 4))
+        pad = int(g.integers(0, 3))
+        nimg = int(g.integers(1, 4))
+        H = int(g.integers(max(1, R - 2 * pad), 30))
+        W = int(g.integers(max(1, S - 2 * pad), 30))
+        Cin = int(g.choice([3, 8, 12, 16, 64, 72, 128]))
+        Cout = int(g.integers(1, 200))
+        dtype = int(g.integers(0, 2))
+        epi = int(g.integers(0, 4))
+        out.append((i, nimg, H, W, Cin, Cout, R, S, stride, pad, dtype, epi))
+    return out
+
+
+@pytest.mark.parametrize("case", _conv_cases(), ids=lambda c: "v%d_n%d_%dx%d_c%d_k%d_f%dx%d_s%d_p%d_dt%d_e%d" % c)
+def test_random_conv2d(case):
+    """Implicit-GEMM convolution with random geometry: filter 1/3/5, stride 1-3, padding 0-2, channel
+    counts that take the LDS-DMA gather (multiples of 64), the vector gather (multiples of 8) and the
+    element-wise gather; any c_out; optional bias / 16-bit output."""
+    i, nimg, H, W, Cin, Cout, R, S, stride, pad, dtype, epi = case
+    g = np.random.default_rng([9000 + i, FUZZ_SEED])
+    X = si.normal_bits(g, (nimg, H, W, Cin), 1.0, dtype)
+    Wt = si.normal_bits(g, (R, S, Cin, Cout), 0.2, dtype)
+    bias = g.standard_normal(Cout).astype(np.float32) if epi & 1 else None
+    out16 = dtype if epi & 2 else None
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=dtype, c_in=Cin, c_out=Cout, r=R, s=S, stride=stride,
+                                         pad=pad, m_lo=0, m_hi=1 << 20,
+                                         out_dtype=ft.FT_OUT_SAME if epi & 2 else ft.FT_OUT_F32,
+                                         epilogue=ft.FT_EPI_BIAS if epi & 1 else ft.FT_EPI_NONE))
+    plan = ft.ft_plan_create(op, ft.ft_ukernels_derive(op), ft.ft_shape(img_n=nimg, img_h=H, img_w=W))
+    ref, refabs = oc.conv2d_nhwc(X, Wt, dtype, stride=stride, pad=pad, want_abs=True)
+    ref, refabs = ref.reshape(-1, Cout), refabs.reshape(-1, Cout)
+    if epi:
+        if bias is not None:
+            ref = ref + bias[None, :]
+        got = run_epilogue(plan, X, Wt, ref.size, bias=bias, out16=out16)
+        check_epilogue(got, ref, refabs, bias[None, :] if bias is not None else None, out16, str(case))
+    else:
+        check(run(plan, X, Wt, ref.size), ref, refabs, str(case))
