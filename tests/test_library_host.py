@@ -409,3 +409,75 @@ def test_plan_cache_returns_the_same_plan_per_shape_and_flags():
     [t.start() for t in th]
     [t.join() for t in th]
     assert len(set(got)) == 1
+
+
+def _random_ops(n=90, seed=515):
+    """Seeded random operators of the three kinds with a few runtime shapes each (static extents from
+    tiny to LLM sized, 16-bit outputs, strips on for some batched ones)."""
+    import random
+    rnd = random.Random(seed)
+    ext = [1, 2, 5, 8, 12, 16, 24, 40, 64, 100, 128, 304, 768, 1000, 1536, 4096, 11008]
+    out = []
+    for i in range(n):
+        kind = rnd.choice([P.OP_MATMUL, P.OP_MATMUL, P.OP_BMM, P.OP_BMM, P.OP_CONV2D])
+        dt, ob = rnd.choice([P.F16, P.BF16]), rnd.choice([4, 4, 2])
+        strips = False
+        if kind == P.OP_MATMUL:
+            lo, hi = rnd.choice([0, 1]), rnd.choice([64, 1024, 8192])
+            op = P.Op(kind, dt, n=rnd.choice(ext), k=rnd.choice(ext), m_range=(lo, hi), out_bytes=ob)
+            shapes = [dict(m=rnd.randint(lo, hi)) for _ in range(3)]
+        elif kind == P.OP_BMM:
+            which, bh = rnd.choice(["qk", "pv", "all"]), rnd.choice([0, 12, 768])
+            strips = rnd.random() < 0.4
+            kw = dict(m_range=(0, 512), batch_hi=bh, out_bytes=ob)
+            if which == "qk":
+                kw.update(k=rnd.choice([16, 64, 128]), n_range=(0, 512))
+            elif which == "pv":
+                kw.update(n=rnd.choice([16, 64, 128]), k_range=(0, 512))
+            else:
+                kw.update(n_range=(0, 512), k_range=(0, 512))
+            op = P.Op(kind, dt, **kw)
+            shapes = []
+            for _ in range(3):
+                L = rnd.randint(0, 512)
+                sh = dict(batch=rnd.randint(0, bh or 96), m=L)
+                if which != "pv":
+                    sh["n"] = rnd.choice([L, rnd.randint(0, 512)])
+                if which != "qk":
+                    sh["k"] = rnd.choice([L, rnd.randint(0, 512)])
+                shapes.append(sh)
+        else:
+            r, pad = rnd.choice([1, 3, 5]), rnd.choice([0, 1, 2])
+            op = P.Op(kind, dt, c_in=rnd.choice([3, 8, 12, 64, 72]), c_out=rnd.choice([1, 8, 100, 128]), r=r, s=r,
+                      stride=rnd.choice([1, 2]), pad=pad, m_range=(0, 1 << 20), out_bytes=ob)
+            lo = max(1, r - 2 * pad)
+            shapes = [dict(img_n=rnd.randint(1, 8), img_h=rnd.randint(lo, 60), img_w=rnd.randint(lo, 60)) for _ in range(3)]
+        out.append((i, op, shapes, strips))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_ops(), ids=lambda c: "r%d_kind%d" % (c[0], c[1].kind))
+def test_random_operators_match_the_oracle(case):
+    """uKernel table and descriptor table of the library equal the oracle's, field by field and byte
+    by byte, for operators and shapes nobody picked by hand."""
+    _, op, shapes, strips = case
+    lib_t, ora_t = strips_on() if strips else (None, None)
+    uks = P.derive_ukernels(op, t=ora_t)
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop, None, lib_t)
+    assert ft.ft_ukset_size(s) == len(uks)
+    for i, w in enumerate(uks):
+        g = ft.ft_ukset_get(s, i)
+        assert (g.tm, g.tn, g.gk, g.stages, g.max_wg_per_cu, g.cmr_q20, g.cmr_shared_q20) == \
+               (w.tm, w.tn, w.gk, w.stages, w.max_wg_per_cu, w.cmr_q, w.cmr2_q)
+    for kw in shapes:
+        shape = oracle_shape(op, kw)
+        if op.kind != P.OP_BMM:
+            shape = (1,) + tuple(shape[1:])
+        want = P.plan(op, uks, shape, t=ora_t)
+        pl = ft.ft_plan_create(lop, s, ft.ft_shape(**kw), HOST)
+        assert ft.ft_plan_descriptors(pl) == b"".join(d.pack() for d in want.descs), kw
+        st = ft.ft_plan_stats_get(pl)
+        assert st.n_tiles == len(want.descs)
+        if want.program is not None:
+            assert (st.sia_q20, st.k_parts, st.k_part_tiles) == (want.program.sia_q, want.k_parts, want.k_part_tiles), kw
