@@ -87,20 +87,30 @@ def _bmm_cases(n=48):
         dtype = int(g.integers(0, 2))
         strips = bool(g.integers(0, 2))
         parts = int(g.choice([0, 0, 2, 3])) if aligned and not strips else 0
-        out.append((i, nb, M, N, K, dtype, strips, parts))
+        static = int(g.integers(0, 3))         # 0: every extent dynamic, 1: K static (QK^T-like), 2: N static (PV-like)
+        if static == 1:
+            K = int(g.choice([16, 64, 128]))
+        elif static == 2:
+            N = int(g.choice([16, 64, 128]))
+        out.append((i, nb, M, N, K, dtype, strips, parts, static))
     return out
 
 
-@pytest.mark.parametrize("case", _bmm_cases(), ids=lambda c: "b%d_%dx%dx%dx%d_dt%d_s%d_p%d" % (c[0], c[1], c[2], c[3], c[4], c[5], int(c[6]), c[7]))
+@pytest.mark.parametrize("case", _bmm_cases(), ids=lambda c: "b%d_%dx%dx%dx%d_dt%d_s%d_p%d_st%d" % (c[0], c[1], c[2], c[3], c[4], c[5], int(c[6]), c[7], c[8]))
 def test_random_batched_matmul_all_axes_dynamic(case):
-    """Batched Matmul with every extent dynamic (two dynamic space axes: the second-axis strips can
-    apply and are switched on for half of the cases)."""
-    i, nb, M, N, K, dtype, strips, parts = case
+    """Batched Matmul with every extent dynamic, or with a static reduce axis (QK^T-like: two dynamic
+    space axes, where the second-axis strips can apply; they are switched on for half of the cases) or
+    a static N (PV-like: dynamic reduce axis)."""
+    i, nb, M, N, K, dtype, strips, parts, static = case
     g = np.random.default_rng([5000 + i, FUZZ_SEED])
     A = si.normal_bits(g, (nb, M, K), 1.0, dtype)
     B = si.normal_bits(g, (nb, K, N), 0.2, dtype)
-    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, m_lo=0, m_hi=512, n_lo=0, n_hi=512,
-                                         k_lo=0, k_hi=512, batch_hi=768))
+    ranges = dict(m_lo=0, m_hi=512, n_lo=0, n_hi=512, k_lo=0, k_hi=512)
+    if static == 1:
+        ranges.update(k=K, k_lo=0, k_hi=0)
+    elif static == 2:
+        ranges.update(n=N, n_lo=0, n_hi=0)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, batch_hi=768, **ranges))
     t = ft.ft_tuning_default()
     t.second_axis_strips = 1 if strips else 0
     s = ft.ft_ukernels_derive(op, None, t)
