@@ -359,16 +359,29 @@ struct UKernelBody {
                         ra[i] = ok ? ld16(Ab + a_off[i] + ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch)
                                    : make_uint4(0, 0, 0, 0);
                     } else {
-                        uint32_t wv[4] = {0u, 0u, 0u, 0u};
+                        // channel count not a multiple of 8: the chunk's 8 elements come from up to 8
+                        // (tap, channel) positions.  One division finds the first; the others follow by
+                        // counting.  Every load is issued unconditionally (from the image's first element
+                        // where the position is in the halo or beyond K) and masked afterwards, so the
+                        // eight loads of a chunk, and those of the other chunks, are in flight together.
+                        uint32_t tap = kk / g.Cin, ch = kk % g.Cin;
+                        uint32_t r = tap / g.S, sx = tap % g.S;
+                        uint32_t val[8];
+#pragma unroll
                         for (int e = 0; e < 8; ++e) {
-                            uint32_t ke = kk + e;
-                            uint32_t tap = ke / g.Cin, ch = ke % g.Cin;
-                            uint32_t r = tap / g.S, s = tap % g.S;
-                            int h = (int)(p0 + r) - (int)g.cpad, w = (int)(q0 + s) - (int)g.cpad;
-                            if (ke < K && h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W)
-                                wv[e >> 1] |= (uint32_t)Ab[a_off[i] + ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch]
-                                              << ((e & 1) * 16);
+                            const int h = (int)(p0 + r) - (int)g.cpad, w = (int)(q0 + sx) - (int)g.cpad;
+                            const bool ok = kk + e < K && h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W;
+                            const uint32_t idx = ok ? ((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch : 0u;
+                            const uint32_t x = Ab[a_off[i] + idx];
+                            val[e] = ok ? x : 0u;
+                            if (++ch == g.Cin) {
+                                ch = 0;
+                                if (++sx == g.S) { sx = 0; ++r; }
+                            }
                         }
+                        uint32_t wv[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) wv[e] = val[2 * e] | (val[2 * e + 1] << 16);
                         ra[i] = make_uint4(wv[0], wv[1], wv[2], wv[3]);
                     }
                 }
