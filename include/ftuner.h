@@ -279,6 +279,24 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
  * FT_PLAN_FORCED is not cached (FT_ERR_INVALID_ARG). */
 ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_plan **out);
+/* Grouped plan: n_groups batched Matmul problems of DIFFERENT shapes run by ONE launch -- a batch
+ * of sequences of different lengths without padding them to the longest (the paper's motivation,
+ * Sec. 1 / Fig. 1(b): padded batches waste most of their work).  op must be a batched Matmul; groups[g]
+ * is a runtime shape of it (batch = number of equally shaped matrices of the group, e.g. the heads of
+ * one sequence; a group with an empty extent contributes nothing).  Each group gets the program the
+ * planner picks for its own shape (Sec. 5); the descriptor table is their concatenation in group
+ * order, and descriptor flags carry the group in bits 8..31 and the body in bits 1..7 (bit 0 as
+ * before).  Operands are packed group after group, each group's matrices densely packed as for a
+ * plain batched launch; ft_plan_group_layout reports where a group starts.  Launch with ft_launch /
+ * ft_launch_epilogue on the packed buffers.  The general bodies run it (any alignment); the reduce
+ * axis is never split.  flags: FT_PLAN_PATCHWORK or FT_PLAN_PAD_BASELINE, optionally
+ * FT_PLAN_HOST_ONLY.  groups: host pointer, read during the call only.  n_groups < 2^24. */
+ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
+                                 uint32_t flags, ft_plan **out);
+/* Element offsets of group `group`'s first matrices in the packed A, B and C buffers, and the
+ * buffers' total element counts for group == number of groups.  Host pointers. */
+ft_status ft_plan_group_layout(const ft_plan *plan, uint32_t group, uint64_t *off_a, uint64_t *off_b, uint64_t *off_c);
+
 /* *descs: host pointer to library-owned memory, valid until ft_plan_destroy. */
 ft_status ft_plan_descriptors(const ft_plan *plan, const ft_tile_desc **descs, uint64_t *n);
 /* Which descriptor each workgroup of the launch takes (Sec. 3: one uKernel = one thread block):

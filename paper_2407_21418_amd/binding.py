@@ -113,6 +113,8 @@ SYMBOLS = {
     "ft_ukset_get": (C.c_int32, [_P, u32, C.POINTER(ft_ukernel_info)]),
     "ft_ukset_destroy": (None, [_P]),
     "ft_plan_create": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, C.POINTER(ft_forced_program), C.POINTER(_P)]),
+    "ft_plan_create_grouped": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, u32, C.POINTER(_P)]),
+    "ft_plan_group_layout": (C.c_int32, [_P, u32, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64)]),
     "ft_plan_cached": (C.c_int32, [_P, _P, C.POINTER(ft_shape), u32, C.POINTER(_P)]),
     "ft_plan_descriptors": (C.c_int32, [_P, C.POINTER(C.POINTER(ft_tile_desc)), C.POINTER(u64)]),
     "ft_plan_launch_order": (C.c_int32, [_P, C.POINTER(u32), u64, C.POINTER(u64)]),
@@ -237,6 +239,22 @@ def ft_plan_create(op: Op, s: UkSet, shape: ft_shape, flags=FT_PLAN_PATCHWORK, f
                                 C.byref(forced) if forced is not None else None, C.byref(out)),
            "ft_plan_create")
     return Plan(out.value)
+
+
+def ft_plan_create_grouped(op: Op, s: UkSet, groups, flags=FT_PLAN_PATCHWORK) -> Plan:
+    """groups: sequence of ft_shape, one per group (batch = matrices of that shape)."""
+    arr = (ft_shape * max(1, len(groups)))(*groups)
+    out = _P()
+    _check(lib().ft_plan_create_grouped(op.ptr, s.ptr, arr, len(groups), flags, C.byref(out)), "ft_plan_create_grouped")
+    return Plan(out.value)
+
+
+def ft_plan_group_layout(p: Plan, group: int):
+    """(off_a, off_b, off_c): element offsets of the group's first matrices in the packed buffers;
+    group == number of groups gives the buffers' total element counts."""
+    a, b, c = u64(), u64(), u64()
+    _check(lib().ft_plan_group_layout(p.ptr, group, C.byref(a), C.byref(b), C.byref(c)), "ft_plan_group_layout")
+    return a.value, b.value, c.value
 
 
 def ft_plan_descriptors(p: Plan) -> bytes:

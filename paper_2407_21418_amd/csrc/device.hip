@@ -20,6 +20,11 @@ const launch_fn kLaunch[2][FT_NUM_CLASSES] = {
 // [dtype][1] = all bodies (512-register kernel)
 const launch_fn kLaunchGeneric[2][2] = {{ft_launch_dt0_gen_c1, ft_launch_dt0_gen_c2},
                                         {ft_launch_dt1_gen_c1, ft_launch_dt1_gen_c2}};
+// grouped launches: the general bodies behind a dispatcher that reads each group's shape
+const launch_fn kLaunchGrouped[2][2] = {{ft_launch_dt0_grp_c1, ft_launch_dt0_grp_c2},
+                                        {ft_launch_dt1_grp_c1, ft_launch_dt1_grp_c2}};
+static_assert(sizeof(ftk::GroupRec) == sizeof(ft_group_rec) && sizeof(ft_group_rec) == 40,
+              "the kernels read the host's group records as they are");
 
 static_assert(sizeof(ftk::TileDesc) == sizeof(ft_tile_desc) && sizeof(ft_tile_desc) == 24,
               "descriptor layout is part of the ABI");
@@ -96,6 +101,13 @@ ft_status ftd_upload(ft_plan *p) {
     if (e != hipSuccess) { p->d_descs = nullptr; return e == hipErrorOutOfMemory ? FT_ERR_OOM : hip_fail(e); }
     e = hipMemcpy(p->d_descs, p->descs.data(), bytes, hipMemcpyHostToDevice);
     if (e != hipSuccess) { ftd_release(p); return hip_fail(e); }
+    if (!p->groups.empty()) {
+        const size_t gbytes = p->groups.size() * sizeof(ft_group_rec);
+        e = hipMalloc(&p->d_groups, gbytes);
+        if (e != hipSuccess) { p->d_groups = nullptr; ftd_release(p); return e == hipErrorOutOfMemory ? FT_ERR_OOM : hip_fail(e); }
+        e = hipMemcpy(p->d_groups, p->groups.data(), gbytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { ftd_release(p); return hip_fail(e); }
+    }
     if (p->st.k_parts > 1) {
         const size_t ctr_bytes = p->descs.size() * 4 * sizeof(uint32_t);
         e = hipMalloc(&p->d_ws, (size_t)p->st.workspace_bytes);
@@ -113,6 +125,7 @@ void ftd_release(ft_plan *p) {
     if (p->d_descs) { (void)hipFree(p->d_descs); p->d_descs = nullptr; }
     if (p->d_ws) { (void)hipFree(p->d_ws); p->d_ws = nullptr; }
     if (p->d_arrive) { (void)hipFree(p->d_arrive); p->d_arrive = nullptr; }
+    if (p->d_groups) { (void)hipFree(p->d_groups); p->d_groups = nullptr; }
 }
 
 extern "C" {
@@ -152,6 +165,19 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
     if (plan->st.kernel_class >= FT_NUM_CLASSES || plan->op.dtype > 1) return FT_ERR_UNSUPPORTED;
     ftk::KArgs a;
     fill_args(plan, A, B, C, bias, &a);
+    if (!plan->groups.empty()) {
+        // grouped launch: the dispatcher takes shape, pitches and operand bases from the group records
+        if (!plan->d_groups) return FT_ERR_INVALID_ARG;
+        a.groups = static_cast<const ftk::GroupRec *>(plan->d_groups);
+        a.table_order = 1;
+        a.k_parts = 1;
+        const bool out16 = a.out_kind != ftk::OUT_F32;
+        const bool on_blocks = plan->grp_rows_on_blocks && reinterpret_cast<uintptr_t>(C) % 64 == 0;
+        a.c_stream = (on_blocks || out16 || plan->grp_k_min > 64) ? 1u : 0u;     // as for a plain launch
+        const int rc = kLaunchGrouped[plan->op.dtype][plan->grp_acc <= 64 ? 0 : 1](&a, 2 * plan->grp_stage_bytes, hip_stream);
+        if (rc != 0) return hip_fail((hipError_t)rc);
+        return FT_OK;
+    }
     // The LDS-DMA bodies need 16-byte aligned operands whose row pitches and reduce extent are
     // multiples of 8 elements (convolution: c_in a multiple of 64, c_out of 8); everything else
     // takes the general bodies.

@@ -84,6 +84,53 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     // names the slot (selects, no indexing: the arguments stay in SGPRs).
     uint32_t slot, t;
     TileDesc d;
+#ifdef FT_GROUPED
+    // Grouped launch (general bodies only): the table is the concatenation of the groups' programs,
+    // walked in table order.  A descriptor names its group (flags bits 8..31) and its body (bits 1..7);
+    // the group's record replaces the launch-wide shape, pitches and operand bases, read with scalar
+    // loads since the index is uniform.  The bodies see an ordinary batched problem.
+    t = table_index_of_workgroup(b, o.nx);
+    if (t >= g.n_tiles) return;
+    d = g.descs[t];
+    const uint32_t dflags = __builtin_amdgcn_readfirstlane(d.flags);
+    const GroupRec rec = g.groups[dflags >> 8];
+    KArgs gl = g;
+    gl.M = __builtin_amdgcn_readfirstlane(rec.m);
+    gl.N = __builtin_amdgcn_readfirstlane(rec.n);
+    gl.K = __builtin_amdgcn_readfirstlane(rec.k);
+    gl.lda = gl.K; gl.ldb = gl.N; gl.ldc = gl.N;
+    gl.strideA = (uint64_t)gl.M * gl.K;
+    gl.strideB = (uint64_t)gl.K * gl.N;
+    gl.strideC = (uint64_t)gl.M * gl.N;
+    auto uniform64 = [](uint64_t x) -> uint64_t {
+        return (uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)x) |
+               ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(x >> 32)) << 32);
+    };
+    const uint64_t offA = uniform64(rec.offA), offB = uniform64(rec.offB), offC = uniform64(rec.offC);
+    gl.A = g.A + offA;
+    gl.B = g.B + offB;
+    gl.C = g.out_kind == OUT_F32 ? static_cast<void *>(static_cast<float *>(g.C) + offC)
+                                 : static_cast<void *>(static_cast<uint16_t *>(g.C) + offC);
+    d.flags = dflags & 1u;
+    d.batch = __builtin_amdgcn_readfirstlane(d.batch);
+    d.m0 = __builtin_amdgcn_readfirstlane(d.m0);
+    d.n0 = __builtin_amdgcn_readfirstlane(d.n0);
+    t = __builtin_amdgcn_readfirstlane(t);
+    slot = 0;
+    (void)slot; (void)part;
+    switch ((dflags >> 1) & 0x7fu) {
+#define FT_X(CODE, WM, WN, GM, GN)                                              \
+    case CODE:                                                                  \
+        if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
+            UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(gl, d, smem);        \
+        break;
+        FT_FAMILY(FT_X)
+        FT_FAMILY_PARTIAL(FT_X)
+#undef FT_X
+    default: break;
+    }
+    return;
+#else
     if (g.table_order) {
         t = table_index_of_workgroup(b, o.nx);
         if (t >= g.n_tiles) return;             // the grid is rounded up to whole rounds of chunks
@@ -139,6 +186,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #endif
     default: break;
     }
+#endif
 }
 
 }  // namespace ftk

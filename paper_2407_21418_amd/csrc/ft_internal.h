@@ -23,6 +23,12 @@ struct ft_ukset {
     std::map<std::vector<uint32_t>, ft_plan *> cache;
 };
 
+// shape and operand offsets (in elements) of one group of a grouped launch; the kernels read it
+struct ft_group_rec {
+    uint32_t m, n, k, batch;
+    uint64_t off_a, off_b, off_c;
+};
+
 struct ft_plan {
     ft_op_desc op;
     ft_plan_stats st;
@@ -44,6 +50,13 @@ struct ft_plan {
     void *d_ws;                             // [n_tiles][k_parts][ws_tile_stride] floats
     void *d_arrive;                         // [n_tiles][4] counters, zero between launches
     int device;
+    // grouped launch (ft_plan_create_grouped): one record per group, device copy, launch parameters
+    std::vector<ft_group_rec> groups;
+    void *d_groups;
+    uint32_t grp_stage_bytes;               // largest LDS stage of the bodies the groups use
+    uint32_t grp_acc;                       // most accumulator registers of those bodies
+    uint32_t grp_k_min;                     // shortest reduce axis of the groups that have tiles
+    bool grp_rows_on_blocks;                // every group's rows of C start on 64-byte blocks (given such a C)
 };
 
 // device.hip

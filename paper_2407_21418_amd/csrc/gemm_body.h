@@ -31,6 +31,13 @@ struct TileDesc {            // mirrors the 24-byte descriptor of the C ABI
     uint32_t flags;
 };
 
+// One group of a grouped launch: `batch` matrices of one shape, densely packed; the offsets are in
+// elements from the launch's A, B and C pointers.
+struct GroupRec {
+    uint32_t m, n, k, batch;
+    uint64_t offA, offB, offC;
+};
+
 struct KArgs {
     const uint16_t *A;
     const uint16_t *B;
@@ -62,6 +69,7 @@ struct KArgs {
     uint32_t c_stream;                // 1: C is stored with the non-temporal hint (see store_acc_as)
     float *ws;                        // [n_tiles][k_parts][ws_tile_stride] fp32 partial tiles
     uint32_t *arrive;                 // [n_tiles][4] arrival counters, zero between launches
+    const GroupRec *groups;           // grouped launch: shape and operand offsets of each group, else NULL
 };
 
 enum { DT_F16 = 0, DT_BF16 = 1 };

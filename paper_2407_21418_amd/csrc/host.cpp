@@ -803,6 +803,8 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     pl->d_descs = nullptr;
     pl->d_ws = nullptr;
     pl->d_arrive = nullptr;
+    pl->d_groups = nullptr;
+    pl->grp_stage_bytes = 0; pl->grp_acc = 0; pl->grp_k_min = 0; pl->grp_rows_on_blocks = false;
     pl->ws_tile_stride = 0;
     pl->device = -1;
     pl->num_xcds = set->hw.num_xcds ? set->hw.num_xcds : 1;
@@ -1043,6 +1045,85 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         if (st != FT_OK) { delete pl; return st; }
     }
     *out = pl;
+    return FT_OK;
+}
+
+ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
+                                 uint32_t flags, ft_plan **out) {
+    if (!op || !set || !out || (n_groups && !groups) || n_groups >= (1u << 24)) return FT_ERR_INVALID_ARG;
+    if (op->d.kind != FT_OP_BMM) return FT_ERR_UNSUPPORTED;
+    const uint32_t mode = flags & FT_PLAN_MODE_MASK;
+    if (mode != FT_PLAN_PATCHWORK && mode != FT_PLAN_PAD_BASELINE) return FT_ERR_INVALID_ARG;
+    // an empty plan of the operator as the shell: the first group's shape with no batch entries
+    ft_plan *pl = nullptr;
+    {
+        ft_shape none;
+        std::memset(&none, 0, sizeof(none));
+        none.struct_size = sizeof(none);
+        if (n_groups) { none = groups[0]; none.batch = 0; }
+        else { none.m = op->d.m ? 0 : op->d.m_lo; none.n = op->d.n ? 0 : op->d.n_lo; none.k = op->d.k ? 0 : op->d.k_lo; }
+        ft_status st = ft_plan_create(op, set, &none, mode | FT_PLAN_HOST_ONLY, nullptr, &pl);
+        if (st != FT_OK) return st;
+    }
+    ft_plan_stats &s = pl->st;
+    const uint32_t es_c = op->d.out_dtype == FT_OUT_SAME ? 2 : 4;
+    uint64_t off_a = 0, off_b = 0, off_c = 0;
+    pl->grp_rows_on_blocks = true;
+    pl->grp_k_min = UINT32_MAX;
+    s.batch = 0; s.m = 0; s.n = 0; s.k = 0; s.useful_elems = 0; s.covered_elems = 0;
+    for (uint32_t gi = 0; gi < n_groups; ++gi) {
+        ft_plan *sub = nullptr;
+        ft_status st = ft_plan_create(op, set, &groups[gi], mode | FT_PLAN_HOST_ONLY, nullptr, &sub);
+        if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+        const ft_plan_stats &g = sub->st;
+        ft_group_rec rec;
+        rec.m = g.m; rec.n = g.n; rec.k = g.k; rec.batch = g.batch;
+        rec.off_a = off_a; rec.off_b = off_b; rec.off_c = off_c;
+        pl->groups.push_back(rec);
+        if (off_c * es_c % 64 || (uint64_t)g.n * es_c % 64) pl->grp_rows_on_blocks = false;
+        off_a += (uint64_t)g.batch * g.m * g.k;
+        off_b += (uint64_t)g.batch * g.k * g.n;
+        off_c += (uint64_t)g.batch * g.m * g.n;
+        for (ft_tile_desc d : sub->descs) {
+            const ft_ukernel_info &u = set->uk[d.ukernel_id];
+            const int code = ft_general_code(ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk));
+            if (code < 0 || code > 0x7f) { ft_plan_destroy(sub); ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
+            d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (gi << 8);
+            pl->descs.push_back(d);
+            pl->grp_stage_bytes = std::max(pl->grp_stage_bytes, ft_stage_bytes_of_code(code));
+            pl->grp_acc = std::max(pl->grp_acc, (uint32_t)ft_acc_of_code(code));
+        }
+        if (!sub->descs.empty()) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
+        s.batch += g.batch;
+        s.m = std::max(s.m, g.m); s.n = std::max(s.n, g.n); s.k = std::max(s.k, g.k);
+        s.useful_elems += g.useful_elems;
+        s.covered_elems += g.covered_elems;
+        ft_plan_destroy(sub);
+    }
+    ft_group_rec total;                        // one past the last group: the buffers' sizes
+    total.m = total.n = total.k = total.batch = 0;
+    total.off_a = off_a; total.off_b = off_b; total.off_c = off_c;
+    pl->groups.push_back(total);
+    if (pl->descs.size() > UINT32_MAX / 2) { ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
+    s.n_tiles = pl->descs.size();
+    s.n_ukernels = 0;                          // a program per group: no single pair of uKernels describes the plan
+    s.k_parts = 1; s.k_part_tiles = 0; s.workspace_bytes = 0;
+    s.lds_bytes = 2 * pl->grp_stage_bytes;
+    s.kernel_class = pl->grp_acc <= 64 ? 1 : 2;
+    s.table_order = 1;
+    pl->table_order = true;
+    if (!(flags & FT_PLAN_HOST_ONLY) && !pl->descs.empty()) {
+        ft_status st = ftd_upload(pl);
+        if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+    }
+    *out = pl;
+    return FT_OK;
+}
+
+ft_status ft_plan_group_layout(const ft_plan *plan, uint32_t group, uint64_t *off_a, uint64_t *off_b, uint64_t *off_c) {
+    if (!plan || !off_a || !off_b || !off_c || group >= plan->groups.size()) return FT_ERR_INVALID_ARG;
+    const ft_group_rec &r = plan->groups[group];
+    *off_a = r.off_a; *off_b = r.off_b; *off_c = r.off_c;
     return FT_OK;
 }
 

@@ -3,6 +3,7 @@ uKernel table and every plan are bit-identical to the planner oracle's, error co
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2407_21418_amd as ft
@@ -481,3 +482,68 @@ def test_random_operators_match_the_oracle(case):
         assert st.n_tiles == len(want.descs)
         if want.program is not None:
             assert (st.sia_q20, st.k_parts, st.k_part_tiles) == (want.program.sia_q, want.k_parts, want.k_part_tiles), kw
+
+
+# ---- grouped plans: one launch over groups of different shapes (Sec. 1 / Fig. 1(b): ragged batches) ----
+GROUPED = {
+    "qk": (OPS["qk_b768"], [dict(batch=12, m=L, n=L) for L in (77, 5, 128, 0, 257, 33, 100, 512)]),
+    "pv": (OPS["pv"], [dict(batch=12, m=L, k=L) for L in (77, 5, 128, 257, 1, 100)]),
+    "one": (OPS["qk"], [dict(batch=3, m=100, n=40)]),
+}
+
+
+@pytest.mark.parametrize("mode", [P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE])
+@pytest.mark.parametrize("name", sorted(GROUPED))
+def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
+    """Descriptor table = the oracle's plans of the groups one after the other, each descriptor tagged
+    with its group (flags bits 8..31; bits 1..7 name the compiled body and are the library's own);
+    operands packed group after group."""
+    op, groups = GROUPED[name]
+    uks = P.derive_ukernels(op)
+    lop = to_lib_op(op)
+    s = ft.ft_ukernels_derive(lop)
+    pl = ft.ft_plan_create_grouped(lop, s, [ft.ft_shape(**kw) for kw in groups], mode | HOST)
+    got = np.frombuffer(ft.ft_plan_descriptors(pl), dtype=np.dtype(
+        [("uk", "<u4"), ("batch", "<u4"), ("m0", "<u4"), ("n0", "<u4"), ("mv", "<u2"), ("nv", "<u2"), ("flags", "<u4")]))
+    at = 0
+    off = [0, 0, 0]
+    useful = covered = 0
+    for gi, kw in enumerate(groups):
+        shape = oracle_shape(op, kw)
+        want = P.plan(op, uks, shape, mode)
+        assert ft.ft_plan_group_layout(pl, gi) == tuple(off), (name, gi)
+        b, m, n, k = shape
+        off = [off[0] + b * m * k, off[1] + b * k * n, off[2] + b * m * n]
+        mine = got[at:at + len(want.descs)]
+        assert len(mine) == len(want.descs)
+        ref = np.frombuffer(b"".join(d.pack() for d in want.descs), dtype=got.dtype)
+        for f in ("uk", "batch", "m0", "n0", "mv", "nv"):
+            assert (mine[f] == ref[f]).all(), (name, gi, f)
+        assert ((mine["flags"] & 1) == (ref["flags"] & 1)).all() and ((mine["flags"] >> 8) == gi).all()
+        at += len(want.descs)
+        useful += want.useful
+        covered += want.covered if want.program is not None else 0
+    assert at == len(got)
+    assert ft.ft_plan_group_layout(pl, len(groups)) == tuple(off)
+    st = ft.ft_plan_stats_get(pl)
+    assert (st.n_tiles, st.useful_elems, st.covered_elems, st.k_parts, st.table_order) == (at, useful, covered, 1, 1)
+    order = ft.ft_plan_launch_order(pl)
+    assert sorted(t for t in order if t != 0xFFFFFFFF) == list(range(at))
+
+
+def test_grouped_plan_argument_checks():
+    lop = to_lib_op(OPS["qk"])
+    s = ft.ft_ukernels_derive(lop)
+    with pytest.raises(ft.FtError) as e:                       # a Matmul operator has no groups
+        mm = to_lib_op(OPS["dense768"])
+        ft.ft_plan_create_grouped(mm, ft.ft_ukernels_derive(mm), [ft.ft_shape(m=5)], HOST)
+    assert e.value.status == ft.FT_ERR_UNSUPPORTED
+    with pytest.raises(ft.FtError) as e:                       # a group outside the registered range
+        ft.ft_plan_create_grouped(lop, s, [ft.ft_shape(batch=1, m=5, n=5), ft.ft_shape(batch=1, m=513, n=5)], HOST)
+    assert e.value.status == ft.FT_ERR_OUT_OF_RANGE
+    with pytest.raises(ft.FtError):                            # forced programs are per shape
+        ft.ft_plan_create_grouped(lop, s, [ft.ft_shape(batch=1, m=5, n=5)], ft.FT_PLAN_FORCED | HOST)
+    empty = ft.ft_plan_create_grouped(lop, s, [], HOST)
+    assert ft.ft_plan_stats_get(empty).n_tiles == 0 and ft.ft_plan_group_layout(empty, 0) == (0, 0, 0)
+    with pytest.raises(ft.FtError):
+        ft.ft_plan_group_layout(empty, 1)
