@@ -284,7 +284,9 @@ ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, 
  * Sec. 1 / Fig. 1(b): padded batches waste most of their work).  op must be a batched Matmul; groups[g]
  * is a runtime shape of it (batch = number of equally shaped matrices of the group, e.g. the heads of
  * one sequence; a group with an empty extent contributes nothing).  Each group gets the program the
- * planner picks for its own shape (Sec. 5); the descriptor table is their concatenation in group
+ * planner picks for its shape at the batch of the whole launch (Sec. 5; the groups share the device:
+ * batch = the sum of the groups' batches, at most batch_hi); the descriptor table is the
+ * concatenation of the groups' own entries in group
  * order, and descriptor flags carry the group in bits 8..31 and the body in bits 1..7 (bit 0 as
  * before).  Operands are packed group after group, each group's matrices densely packed as for a
  * plain batched launch; ft_plan_group_layout reports where a group starts.  Launch with ft_launch /

@@ -1071,11 +1071,26 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
     pl->grp_rows_on_blocks = true;
     pl->grp_k_min = UINT32_MAX;
     s.batch = 0; s.m = 0; s.n = 0; s.k = 0; s.useful_elems = 0; s.covered_elems = 0;
+    // The groups share the device: a group's program is the one the planner picks for its shape at
+    // the batch of the whole launch (planned alone, a short group would be cut into small tiles to
+    // fill a device that the other groups fill anyway); its descriptors are those of its own entries.
+    uint64_t launch_batch = 0;
+    for (uint32_t gi = 0; gi < n_groups; ++gi) launch_batch += groups[gi].batch;
+    if (op->d.batch_hi && launch_batch > op->d.batch_hi) launch_batch = op->d.batch_hi;
+    if (launch_batch > UINT32_MAX) launch_batch = UINT32_MAX;
     for (uint32_t gi = 0; gi < n_groups; ++gi) {
         ft_plan *sub = nullptr;
-        ft_status st = ft_plan_create(op, set, &groups[gi], mode | FT_PLAN_HOST_ONLY, nullptr, &sub);
+        ft_shape as_launch = groups[gi];
+        const uint32_t own_batch = as_launch.batch;
+        if (own_batch) as_launch.batch = std::max<uint32_t>(own_batch, (uint32_t)launch_batch);
+        ft_status st = ft_plan_create(op, set, &as_launch, mode | FT_PLAN_HOST_ONLY, nullptr, &sub);
         if (st != FT_OK) { ft_plan_destroy(pl); return st; }
-        const ft_plan_stats &g = sub->st;
+        ft_plan_stats g = sub->st;
+        if (own_batch) {                       // per-entry figures are the same for every batch entry
+            g.useful_elems = g.useful_elems / g.batch * own_batch;
+            g.covered_elems = g.covered_elems / g.batch * own_batch;
+            g.batch = own_batch;
+        }
         ft_group_rec rec;
         rec.m = g.m; rec.n = g.n; rec.k = g.k; rec.batch = g.batch;
         rec.off_a = off_a; rec.off_b = off_b; rec.off_c = off_c;
@@ -1084,7 +1099,10 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
         off_a += (uint64_t)g.batch * g.m * g.k;
         off_b += (uint64_t)g.batch * g.k * g.n;
         off_c += (uint64_t)g.batch * g.m * g.n;
+        bool any = false;
         for (ft_tile_desc d : sub->descs) {
+            if (d.batch >= own_batch) continue;
+            any = true;
             const ft_ukernel_info &u = set->uk[d.ukernel_id];
             const int code = ft_general_code(ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk));
             if (code < 0 || code > 0x7f) { ft_plan_destroy(sub); ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
@@ -1093,7 +1111,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
             pl->grp_stage_bytes = std::max(pl->grp_stage_bytes, ft_stage_bytes_of_code(code));
             pl->grp_acc = std::max(pl->grp_acc, (uint32_t)ft_acc_of_code(code));
         }
-        if (!sub->descs.empty()) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
+        if (any) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
         s.batch += g.batch;
         s.m = std::max(s.m, g.m); s.n = std::max(s.n, g.n); s.k = std::max(s.k, g.k);
         s.useful_elems += g.useful_elems;

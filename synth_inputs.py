@@ -69,6 +69,13 @@ def config2_lengths():
     return {B: [int(v) for v in g.integers(1, 513, size=32)] for B in ATT_BATCH}
 
 
+def ragged_lengths(draw, n_seqs):
+    """Lengths of the sequences of one ragged batch: drawn like the attention configuration's
+    (uniform on 1..512), one independent length per sequence."""
+    g = rng(2, extra=7000003 + draw)
+    return [int(v) for v in g.integers(1, 513, size=n_seqs)]
+
+
 def config2_problem(B, L, which):
     """which = 'qk': (B*12,L,64)x(B*12,64,L); 'pv': (B*12,L,L)x(B*12,L,64)."""
     g = rng(2, extra=B * 1009 + L + (0 if which == "qk" else 500000))
