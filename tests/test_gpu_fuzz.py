@@ -172,3 +172,58 @@ def test_random_conv2d(case):
         check_epilogue(got, ref, refabs, bias[None, :] if bias is not None else None, out16, str(case))
     else:
         check(run(plan, X, Wt, ref.size), ref, refabs, str(case))
+
+
+def _grouped_cases(n=24):
+    n = FUZZ_CASES or n
+    g = np.random.default_rng(8086 if FUZZ_SEED == 20240721 else FUZZ_SEED + 3)
+    out = []
+    for i in range(n):
+        static = int(g.integers(0, 3))         # 0: every extent dynamic, 1: K static, 2: N static
+        fixed = int(g.choice([16, 64, 128]))
+        dims = []
+        for _ in range(int(g.integers(1, 21))):
+            b = int(g.integers(0, 5))
+            M, N, K = (int(g.integers(0 if j < 2 else 1, 301)) for j in range(3))
+            if bool(g.integers(0, 3) == 0):    # some aligned groups among the odd ones
+                M, N, K = M // 8 * 8, N // 8 * 8, max(8, K // 8 * 8)
+            if static == 1:
+                K = fixed
+            elif static == 2:
+                N = fixed
+            dims.append((b, M, N, K))
+        out.append((i, static, int(g.integers(0, 2)), int(g.integers(0, 2)), tuple(dims)))
+    return out
+
+
+@pytest.mark.parametrize("case", _grouped_cases(), ids=lambda c: "g%d_st%d_dt%d_base%d_n%d" % (c[0], c[1], c[2], c[3], len(c[4])))
+def test_random_grouped_launch(case):
+    """Grouped launches over 1-20 random groups (empty ones included): every group against the
+    oracle on its slice of the packed buffers; nothing outside C is written."""
+    import torch
+    from gpu_util import GUARD, alloc_out, dev_bits, out_view, stream
+    i, static, dtype, baseline, dims = case
+    ranges = dict(m_lo=0, m_hi=512, n_lo=0, n_hi=512, k_lo=0, k_hi=512)
+    if static == 1:
+        ranges.update(k=dims[0][3], k_lo=0, k_hi=0)
+    elif static == 2:
+        ranges.update(n=dims[0][2], n_lo=0, n_hi=0)
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, batch_hi=768, **ranges))
+    groups = [ft.ft_shape(batch=b, m=M, n=N, k=K) for b, M, N, K in dims]
+    plan = ft.ft_plan_create_grouped(op, ft.ft_ukernels_derive(op), groups,
+                                     ft.FT_PLAN_PAD_BASELINE if baseline else ft.FT_PLAN_PATCHWORK)
+    na, nb, nc = ft.ft_plan_group_layout(plan, len(groups))
+    g = np.random.default_rng([7000 + i, FUZZ_SEED])
+    A = si.normal_bits(g, (max(na, 1),), 1.0, dtype)
+    B = si.normal_bits(g, (max(nb, 1),), 0.3, dtype)
+    buf = alloc_out(nc)
+    dA, dB = dev_bits(A), dev_bits(B)
+    ft.ft_launch(plan, dA.data_ptr(), dB.data_ptr(), buf.data_ptr() + 4 * GUARD, stream())
+    torch.cuda.synchronize()
+    C = out_view(buf, nc)
+    for gi, (b, M, N, K) in enumerate(dims):
+        oa, ob, oc_ = ft.ft_plan_group_layout(plan, gi)
+        if b * M * N == 0:
+            continue
+        ref, refabs = oc.bmm(A[oa:oa + b * M * K].reshape(b, M, K), B[ob:ob + b * K * N].reshape(b, K, N), dtype, want_abs=True)
+        check(C[oc_:oc_ + b * M * N], ref, refabs, f"{case[:4]} group {gi} {b}x{M}x{N}x{K}")
