@@ -110,6 +110,13 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False):
                                       os.path.join(CSRC, "dispatch.hip"), "-o", obj]
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             gen.append((obj, cmd))
+    for dt in (0, 1):                         # grouped launches whose groups are all aligned: LDS-DMA bodies
+        for cl in (2, 1, 0):
+            obj = os.path.join(OUT, f"dispatch_dt{dt}_grpf_c{cl}.o")
+            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_GROUPED=1", "-c",
+                                      os.path.join(CSRC, "dispatch.hip"), "-o", obj]
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+            gen.append((obj, cmd))
     gen.sort(key=lambda oc: "_c2" not in oc[0])   # the 512-register kernels take longest: start them first
     steps = gen + steps
     for src in ("host.cpp", "device.hip"):

@@ -23,6 +23,8 @@ const launch_fn kLaunchGeneric[2][2] = {{ft_launch_dt0_gen_c1, ft_launch_dt0_gen
 // grouped launches: the general bodies behind a dispatcher that reads each group's shape
 const launch_fn kLaunchGrouped[2][2] = {{ft_launch_dt0_grp_c1, ft_launch_dt0_grp_c2},
                                         {ft_launch_dt1_grp_c1, ft_launch_dt1_grp_c2}};
+const launch_fn kLaunchGroupedFast[2][3] = {{ft_launch_dt0_grpf_c0, ft_launch_dt0_grpf_c1, ft_launch_dt0_grpf_c2},
+                                            {ft_launch_dt1_grpf_c0, ft_launch_dt1_grpf_c1, ft_launch_dt1_grpf_c2}};
 static_assert(sizeof(ftk::GroupRec) == sizeof(ft_group_rec) && sizeof(ft_group_rec) == 40,
               "the kernels read the host's group records as they are");
 
@@ -174,7 +176,10 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
         const bool out16 = a.out_kind != ftk::OUT_F32;
         const bool on_blocks = plan->grp_rows_on_blocks && reinterpret_cast<uintptr_t>(C) % 64 == 0;
         a.c_stream = (on_blocks || out16 || plan->grp_k_min > 64) ? 1u : 0u;     // as for a plain launch
-        const int rc = kLaunchGrouped[plan->op.dtype][plan->grp_acc <= 64 ? 0 : 1](&a, 2 * plan->grp_stage_bytes, hip_stream);
+        // every group aligned and the buffers too: the LDS-DMA bodies; else the general ones
+        const bool fast = plan->grp_aligned && reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0;
+        const int rc = fast ? kLaunchGroupedFast[plan->op.dtype][ft_class_of_acc((int)plan->grp_fast_acc)](&a, plan->grp_fast_lds, hip_stream)
+                            : kLaunchGrouped[plan->op.dtype][plan->grp_acc <= 64 ? 0 : 1](&a, 2 * plan->grp_stage_bytes, hip_stream);
         if (rc != 0) return hip_fail((hipError_t)rc);
         return FT_OK;
     }

@@ -85,15 +85,17 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     uint32_t slot, t;
     TileDesc d;
 #ifdef FT_GROUPED
-    // Grouped launch (general bodies only): the table is the concatenation of the groups' programs,
-    // walked in table order.  A descriptor names its group (flags bits 8..31) and its body (bits 1..7);
-    // the group's record replaces the launch-wide shape, pitches and operand bases, read with scalar
-    // loads since the index is uniform.  The bodies see an ordinary batched problem.
+    // Grouped launch: the table is the concatenation of the groups' programs, walked in table order.
+    // A descriptor names its group (flags bits 12..31), its body (bits 1..7) and that body's LDS ring
+    // depth (bits 8..11); the group's record replaces the launch-wide shape, pitches and operand
+    // bases, read with scalar loads since the index is uniform.  The bodies see an ordinary batched
+    // problem.  Compiled over the general bodies (any alignment) and over the LDS-DMA bodies (every
+    // group aligned; the host decides per launch).
     t = table_index_of_workgroup(b, o.nx);
     if (t >= g.n_tiles) return;
     d = g.descs[t];
     const uint32_t dflags = __builtin_amdgcn_readfirstlane(d.flags);
-    const GroupRec rec = g.groups[dflags >> 8];
+    const GroupRec rec = g.groups[dflags >> 12];
     KArgs gl = g;
     gl.M = __builtin_amdgcn_readfirstlane(rec.m);
     gl.N = __builtin_amdgcn_readfirstlane(rec.n);
@@ -118,7 +120,13 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     t = __builtin_amdgcn_readfirstlane(t);
     slot = 0;
     (void)slot; (void)part;
-    switch ((dflags >> 1) & 0x7fu) {
+    uint32_t gcode = (dflags >> 1) & 0x7fu;
+#ifdef FT_GENERIC
+    // the general path has no split-k wave grid: such a uKernel runs on its standard-grid twin
+#define FT_X(CODE, TM, TN, TWIN) if (gcode == CODE) gcode = TWIN;
+    FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+    switch (gcode) {
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
@@ -129,6 +137,26 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 #undef FT_X
     default: break;
     }
+#else
+    const uint32_t gstages = (dflags >> 8) & 0xfu;
+    switch (gcode) {
+#define FT_X(CODE, WM, WN, GM, GN)                                              \
+    case CODE:                                                                  \
+        if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
+            UKernelFast<FT_DT, WM, WN, GM, GN>::run(gl, d, smem, gstages, t, 0u); \
+        break;
+        FT_FAMILY(FT_X)
+#undef FT_X
+#define FT_X(CODE, TM, TN, TWIN)                                                \
+    case CODE:                                                                  \
+        if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \
+            UKernelSplitK<FT_DT, TM, TN>::run(gl, d, smem, gstages, t, 0u);     \
+        break;
+        FT_FAMILY_SPLITK(FT_X)
+#undef FT_X
+    default: break;
+    }
+#endif
     return;
 #else
     if (g.table_order) {

@@ -57,6 +57,8 @@ struct ft_plan {
     uint32_t grp_acc;                       // most accumulator registers of those bodies
     uint32_t grp_k_min;                     // shortest reduce axis of the groups that have tiles
     bool grp_rows_on_blocks;                // every group's rows of C start on 64-byte blocks (given such a C)
+    bool grp_aligned;                       // every group fits the LDS-DMA bodies (given 16-byte aligned A, B)
+    uint32_t grp_fast_lds, grp_fast_acc;    // LDS bytes and accumulator registers the LDS-DMA bodies need
 };
 
 // device.hip

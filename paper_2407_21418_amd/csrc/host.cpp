@@ -805,6 +805,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     pl->d_arrive = nullptr;
     pl->d_groups = nullptr;
     pl->grp_stage_bytes = 0; pl->grp_acc = 0; pl->grp_k_min = 0; pl->grp_rows_on_blocks = false;
+    pl->grp_aligned = false; pl->grp_fast_lds = 0; pl->grp_fast_acc = 0;
     pl->ws_tile_stride = 0;
     pl->device = -1;
     pl->num_xcds = set->hw.num_xcds ? set->hw.num_xcds : 1;
@@ -1050,7 +1051,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
 
 ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
                                  uint32_t flags, ft_plan **out) {
-    if (!op || !set || !out || (n_groups && !groups) || n_groups >= (1u << 24)) return FT_ERR_INVALID_ARG;
+    if (!op || !set || !out || (n_groups && !groups) || n_groups >= (1u << 20)) return FT_ERR_INVALID_ARG;
     if (op->d.kind != FT_OP_BMM) return FT_ERR_UNSUPPORTED;
     const uint32_t mode = flags & FT_PLAN_MODE_MASK;
     if (mode != FT_PLAN_PATCHWORK && mode != FT_PLAN_PAD_BASELINE) return FT_ERR_INVALID_ARG;
@@ -1069,6 +1070,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
     const uint32_t es_c = op->d.out_dtype == FT_OUT_SAME ? 2 : 4;
     uint64_t off_a = 0, off_b = 0, off_c = 0;
     pl->grp_rows_on_blocks = true;
+    pl->grp_aligned = true;
     pl->grp_k_min = UINT32_MAX;
     s.batch = 0; s.m = 0; s.n = 0; s.k = 0; s.useful_elems = 0; s.covered_elems = 0;
     // The groups share the device: a group's program is the one the planner picks for its shape at
@@ -1104,13 +1106,19 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
             if (d.batch >= own_batch) continue;
             any = true;
             const ft_ukernel_info &u = set->uk[d.ukernel_id];
-            const int code = ft_general_code(ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk));
-            if (code < 0 || code > 0x7f) { ft_plan_destroy(sub); ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
-            d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (gi << 8);
+            const int code = ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk);
+            if (code < 0 || code > 0x7f || u.stages > 0xf) { ft_plan_destroy(sub); ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
+            d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (u.stages << 8) | (gi << 12);
             pl->descs.push_back(d);
-            pl->grp_stage_bytes = std::max(pl->grp_stage_bytes, ft_stage_bytes_of_code(code));
-            pl->grp_acc = std::max(pl->grp_acc, (uint32_t)ft_acc_of_code(code));
+            const int twin = ft_general_code(code);          // what the general bodies run for it
+            pl->grp_stage_bytes = std::max(pl->grp_stage_bytes, ft_stage_bytes_of_code(twin));
+            pl->grp_acc = std::max(pl->grp_acc, (uint32_t)ft_acc_of_code(twin));
+            pl->grp_fast_lds = std::max(pl->grp_fast_lds, u.lds_bytes);
+            pl->grp_fast_acc = std::max(pl->grp_fast_acc, u.acc_regs);
         }
+        // LDS-DMA bodies: 16-byte aligned matrices, row lengths and reduce extent multiples of 8 elements
+        if (any && (g.k % 8 || g.n % 8 || rec.off_a % 8 || rec.off_b % 8 || ((uint64_t)g.m * g.k) % 8 || ((uint64_t)g.k * g.n) % 8))
+            pl->grp_aligned = false;
         if (any) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
         s.batch += g.batch;
         s.m = std::max(s.m, g.m); s.n = std::max(s.n, g.n); s.k = std::max(s.k, g.k);

@@ -5,9 +5,12 @@
 #define FT_CAT_(a, b, c, d) a##b##c##d
 #define FT_CAT(a, b, c, d) FT_CAT_(a, b, c, d)
 #if defined(FT_DT) && defined(FT_CLASS)
-#if defined(FT_GROUPED)
+#if defined(FT_GROUPED) && defined(FT_GENERIC)
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _grp_c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _grp_c, FT_CLASS)
+#elif defined(FT_GROUPED)
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _grpf_c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _grpf_c, FT_CLASS)
 #elif defined(FT_GENERIC)
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _gen_c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _gen_c, FT_CLASS)
@@ -32,4 +35,10 @@ int ft_launch_dt0_grp_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt0_grp_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grp_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grp_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_grpf_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_grpf_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_grpf_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_grpf_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_grpf_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_grpf_c2(const ftk::KArgs *, uint32_t, void *);
 }

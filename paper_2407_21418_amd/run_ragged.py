@@ -1,6 +1,6 @@
 """Ragged attention batches through the C ABI: one grouped launch against the alternatives.
 
-    python -m paper_2407_21418_amd.run_ragged [--seqs 64] [--heads 12] [--iters 20] [--draws 4]
+    python -m paper_2407_21418_amd.run_ragged [--seqs 64] [--heads 12] [--iters 20] [--draws 4] [--align 8]
 
 A batch holds --seqs sequences whose lengths are drawn like the attention configuration's (the
 paper's motivation, Sec. 1 / Fig. 1(b): sequence lengths in a batch differ widely and padding them to
@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--draws", type=int, default=4)
     ap.add_argument("--ring-mb", type=float, default=600.0)
+    ap.add_argument("--align", type=int, default=1, help="round every length up to a multiple of this (8: the "
+                    "grouped launch then runs the LDS-DMA bodies)")
     a = ap.parse_args()
 
     import torch
@@ -64,7 +66,7 @@ def main():
 
     rows = []
     for draw in range(a.draws):
-        lengths = si.ragged_lengths(draw, a.seqs)
+        lengths = [min(512, -(-L // a.align) * a.align) for L in si.ragged_lengths(draw, a.seqs)]
         Lmax = max(lengths)
         for which in ("qk", "pv"):
             op, uks = ops[which], sets[which]
@@ -105,7 +107,7 @@ def main():
                   % (draw, which, a.seqs, H, r["mean_len"], Lmax, us_grouped, r["tflops_grouped"], r["tiles"], us_padded,
                      us_padded / us_grouped, r["padded_work_ratio"], us_looped, us_looped / us_grouped), flush=True)
     gm = lambda xs: math.exp(sum(math.log(x) for x in xs) / len(xs))
-    print(json.dumps({"workload": "ragged attention batches, %d sequences x %d heads, fp16 in, fp32 out" % (a.seqs, H),
+    print(json.dumps({"workload": "ragged attention batches, %d sequences x %d heads, lengths rounded up to multiples of %d, fp16 in, fp32 out" % (a.seqs, H, a.align),
                       "speedup_vs_padded_geomean": round(gm([r["us_padded"] / r["us_grouped"] for r in rows]), 3),
                       "speedup_vs_looped_geomean": round(gm([r["us_looped"] / r["us_grouped"] for r in rows]), 3),
                       "rows": rows}))

@@ -181,11 +181,12 @@ def _grouped_cases(n=24):
     for i in range(n):
         static = int(g.integers(0, 3))         # 0: every extent dynamic, 1: K static, 2: N static
         fixed = int(g.choice([16, 64, 128]))
+        all_aligned = bool(g.integers(0, 3) == 0)   # every group aligned: the launch takes the LDS-DMA bodies
         dims = []
         for _ in range(int(g.integers(1, 21))):
             b = int(g.integers(0, 5))
             M, N, K = (int(g.integers(0 if j < 2 else 1, 301)) for j in range(3))
-            if bool(g.integers(0, 3) == 0):    # some aligned groups among the odd ones
+            if all_aligned or bool(g.integers(0, 3) == 0):    # else some aligned groups among the odd ones
                 M, N, K = M // 8 * 8, N // 8 * 8, max(8, K // 8 * 8)
             if static == 1:
                 K = fixed

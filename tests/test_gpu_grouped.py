@@ -112,3 +112,32 @@ def test_grouped_launch_with_bias_and_16_bit_output_and_relaunch():
         ref, refabs = oc.bmm(A[oa:oa + 2 * L * L].reshape(2, L, L), B[ob:ob + 2 * L * 64].reshape(2, L, 64), ft.FT_F16, want_abs=True)
         ref = ref + bias[None, None, :]
         check_epilogue(got[oc_:oc_ + 2 * L * 64], ref, refabs, bias[None, None, :], ft.FT_F16, f"grouped epilogue group {gi}")
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+def test_aligned_groups_take_the_vector_path_and_agree_with_the_general_one(dtype):
+    """Lengths that are multiples of 8: the grouped launch runs the LDS-DMA bodies.  The same
+    batch from an A that is only 2-byte aligned runs the general bodies; both against the oracle."""
+    lengths = [64, 8, 128, 256, 40, 512, 16, 0, 200]
+    for which in ("qk", "pv"):
+        if which == "qk":
+            op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, k=64, m_lo=0, m_hi=512, n_lo=0, n_hi=512, batch_hi=768))
+            groups = [ft.ft_shape(batch=6, m=L, n=L) for L in lengths]
+            dims = [(6, L, L, 64) for L in lengths]
+        else:
+            op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, n=64, m_lo=0, m_hi=512, k_lo=0, k_hi=512, batch_hi=768))
+            groups = [ft.ft_shape(batch=6, m=L, k=L) for L in lengths]
+            dims = [(6, L, 64, L) for L in lengths]
+        plan = ft.ft_plan_create_grouped(op, ft.ft_ukernels_derive(op), groups)
+        na, nb, nc = ft.ft_plan_group_layout(plan, len(groups))
+        g = np.random.default_rng(17 + dtype)
+        A = si.normal_bits(g, (na + 8,), 1.0, dtype)
+        B = si.normal_bits(g, (nb,), 0.2, dtype)
+        dA, dB = dev_bits(A), dev_bits(B)
+        for shift in (0, 1):                      # elements: 0 -> 16-byte aligned A, 1 -> 2-byte aligned
+            buf = alloc_out(nc)
+            ft.ft_launch(plan, dA.data_ptr() + 2 * shift, dB.data_ptr(), buf.data_ptr() + 4 * GUARD, stream())
+            torch.cuda.synchronize()
+            Cout = out_view(buf, nc)
+            assert np.isfinite(Cout).all()
+            check_groups(plan, dims, A[shift:shift + na], B, Cout, dtype, f"aligned ragged {which} shift {shift}")

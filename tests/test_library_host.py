@@ -496,7 +496,8 @@ GROUPED = {
 @pytest.mark.parametrize("name", sorted(GROUPED))
 def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
     """Descriptor table = the oracle's plans of the groups one after the other, each descriptor tagged
-    with its group (flags bits 8..31; bits 1..7 name the compiled body and are the library's own);
+    with its group (flags bits 12..31; bits 1..11 name the compiled body and its ring depth and are the
+    library's own);
     operands packed group after group."""
     op, groups = GROUPED[name]
     uks = P.derive_ukernels(op)
@@ -523,7 +524,7 @@ def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
         assert len(mine) == len(ref)
         for f in ("uk", "batch", "m0", "n0", "mv", "nv"):
             assert (mine[f] == ref[f]).all(), (name, gi, f)
-        assert ((mine["flags"] & 1) == (ref["flags"] & 1)).all() and ((mine["flags"] >> 8) == gi).all()
+        assert ((mine["flags"] & 1) == (ref["flags"] & 1)).all() and ((mine["flags"] >> 12) == gi).all()
         at += len(ref)
         useful += b * m * n
         covered += want.covered // max(b, launch_batch) * b if want.program is not None and b else 0
