@@ -285,7 +285,8 @@ ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, 
  * is a runtime shape of it (batch = number of equally shaped matrices of the group, e.g. the heads of
  * one sequence; a group with an empty extent contributes nothing).  Each group gets the program the
  * planner picks for its shape at the batch of the whole launch (Sec. 5; the groups share the device:
- * batch = the sum of the groups' batches, at most batch_hi); the descriptor table is the
+ * batch = the sum of the groups' batches rounded up to a power of two, at most batch_hi; the set
+ * caches the program per (shape, that batch), so later launches only copy tiles); the descriptor table is the
  * concatenation of the groups' own entries in group
  * order, and descriptor flags carry the group in bits 12..31, the body in bits 1..7 and its LDS ring
  * depth in bits 8..11 (bit 0 as before).  Operands are packed group after group, each group's matrices densely packed as for a
@@ -294,7 +295,7 @@ ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, 
  * and every group's n, k and matrix sizes are multiples of 8 elements the launch takes the faster
  * vector path.  The reduce axis is never split.  flags: FT_PLAN_PATCHWORK or FT_PLAN_PAD_BASELINE, optionally
  * FT_PLAN_HOST_ONLY.  groups: host pointer, read during the call only.  n_groups < 2^20. */
-ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
+ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
                                  uint32_t flags, ft_plan **out);
 /* Element offsets of group `group`'s first matrices in the packed A, B and C buffers, and the
  * buffers' total element counts for group == number of groups.  Host pointers. */

@@ -786,6 +786,9 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
     return FT_OK;
 }
 
+// set by ft_plan_create_grouped around its calls of ft_plan_create: the batch of the whole launch
+static thread_local uint64_t tl_launch_batch = 0;
+
 ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_forced_program *forced, ft_plan **out) {
     Resolved r;
@@ -830,6 +833,9 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         return FT_OK;
     }
 
+    // programs are scored for the batch the launch as a whole has (a group of a grouped launch shares
+    // the device with the other groups); the table is emitted for the shape's own batch
+    const uint64_t eval_batch = tl_launch_batch ? std::max<uint64_t>(r.batch, tl_launch_batch) : r.batch;
     Program best{};
     if (mode == FT_PLAN_PAD_BASELINE) {
         // pad every dynamic axis up to the largest uKernel of the set (Fig. 2)
@@ -838,7 +844,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         best.nparts = 1;
         best.part[0] = {0u, (uint32_t)(Hp / ext(u, tau))};
         best.k1 = 0; best.k2 = -1;
-        evaluate(best, *set, r.batch, r.M, r.N, tau);
+        evaluate(best, *set, eval_batch, r.M, r.N, tau);
         s.pool_size = 1;
         s.level = (uint32_t)level_of(best);
     } else if (mode == FT_PLAN_FORCED) {
@@ -869,7 +875,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
                 parts = (uint32_t)ceil_div(nk, per);
             }
         }
-        evaluate(best, *set, r.batch, r.M, r.N, tau, parts, r.K);
+        evaluate(best, *set, eval_batch, r.M, r.N, tau, parts, r.K);
         s.pool_size = 1;
         s.level = (uint32_t)level_of(best);
     } else {
@@ -904,18 +910,18 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
                     variants.clear();
                     strip_variants(p, *set, Wp, tau, variants);
                 }
-                evaluate(p, *set, r.batch, r.M, r.N, tau);
+                evaluate(p, *set, eval_batch, r.M, r.N, tau);
                 scored.push_back(p);
                 if (op->d.kind == FT_OP_MATMUL)
                     for (uint32_t kp : kPartChoices) {
                         if (kp == 1 || !split_allowed(p, *set, r.K, kp)) continue;
                         Program q = p;
-                        evaluate(q, *set, r.batch, r.M, r.N, tau, kp, r.K);
+                        evaluate(q, *set, eval_batch, r.M, r.N, tau, kp, r.K);
                         scored.push_back(q);
                     }
                 if (two_axes)
                     for (Program &q : variants) {
-                        evaluate(q, *set, r.batch, r.M, r.N, tau);
+                        evaluate(q, *set, eval_batch, r.M, r.N, tau);
                         scored.push_back(q);
                     }
             }
@@ -1049,7 +1055,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     return FT_OK;
 }
 
-ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
+ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
                                  uint32_t flags, ft_plan **out) {
     if (!op || !set || !out || (n_groups && !groups) || n_groups >= (1u << 20)) return FT_ERR_INVALID_ARG;
     if (op->d.kind != FT_OP_BMM) return FT_ERR_UNSUPPORTED;
@@ -1076,23 +1082,42 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
     // The groups share the device: a group's program is the one the planner picks for its shape at
     // the batch of the whole launch (planned alone, a short group would be cut into small tiles to
     // fill a device that the other groups fill anyway); its descriptors are those of its own entries.
+    // The batch is rounded up to a power of two so that launches of similar size share their programs:
+    // a group's program is cached in the uKernel set under (mode, m, n, k, that batch) as the plan of
+    // ONE batch entry, and every later launch replicates its tiles.
     uint64_t launch_batch = 0;
     for (uint32_t gi = 0; gi < n_groups; ++gi) launch_batch += groups[gi].batch;
+    { uint64_t p2 = 1; while (p2 < launch_batch) p2 <<= 1; launch_batch = p2; }
     if (op->d.batch_hi && launch_batch > op->d.batch_hi) launch_batch = op->d.batch_hi;
-    if (launch_batch > UINT32_MAX) launch_batch = UINT32_MAX;
+    if (launch_batch > (1u << 30)) launch_batch = 1u << 30;
     for (uint32_t gi = 0; gi < n_groups; ++gi) {
-        ft_plan *sub = nullptr;
-        ft_shape as_launch = groups[gi];
-        const uint32_t own_batch = as_launch.batch;
-        if (own_batch) as_launch.batch = std::max<uint32_t>(own_batch, (uint32_t)launch_batch);
-        ft_status st = ft_plan_create(op, set, &as_launch, mode | FT_PLAN_HOST_ONLY, nullptr, &sub);
-        if (st != FT_OK) { ft_plan_destroy(pl); return st; }
-        ft_plan_stats g = sub->st;
-        if (own_batch) {                       // per-entry figures are the same for every batch entry
-            g.useful_elems = g.useful_elems / g.batch * own_batch;
-            g.covered_elems = g.covered_elems / g.batch * own_batch;
-            g.batch = own_batch;
+        const uint32_t own_batch = groups[gi].batch;
+        const ft_plan *sub = nullptr;
+        {
+            ft_shape unit = groups[gi];
+            unit.batch = own_batch ? 1 : 0;
+            // validate the group's own shape first (its batch against batch_hi)
+            Resolved rr;
+            ft_status st = check_common(op, set, &groups[gi], &rr);
+            if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+            const std::vector<uint32_t> key = {mode | FT_PLAN_HOST_ONLY, 0xFFFFFFFFu, (uint32_t)launch_batch,
+                                               unit.batch, unit.m, unit.n, unit.k};
+            std::lock_guard<std::mutex> lock(set->cache_mu);
+            auto it = set->cache.find(key);
+            if (it == set->cache.end()) {
+                ft_plan *made = nullptr;
+                tl_launch_batch = launch_batch;
+                st = ft_plan_create(op, set, &unit, mode | FT_PLAN_HOST_ONLY, nullptr, &made);
+                tl_launch_batch = 0;
+                if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+                it = set->cache.emplace(key, made).first;
+            }
+            sub = it->second;
         }
+        ft_plan_stats g = sub->st;             // figures of one batch entry
+        g.useful_elems *= own_batch;
+        g.covered_elems *= own_batch;
+        g.batch = own_batch;
         ft_group_rec rec;
         rec.m = g.m; rec.n = g.n; rec.k = g.k; rec.batch = g.batch;
         rec.off_a = off_a; rec.off_b = off_b; rec.off_c = off_c;
@@ -1102,12 +1127,20 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
         off_b += (uint64_t)g.batch * g.k * g.n;
         off_c += (uint64_t)g.batch * g.m * g.n;
         bool any = false;
-        for (ft_tile_desc d : sub->descs) {
-            if (d.batch >= own_batch) continue;
+        // the table of `own_batch` entries in canonical order: per uKernel, per batch entry, its tiles
+        std::vector<ft_tile_desc> own;
+        for (size_t i = 0; i < sub->descs.size();) {
+            size_t j = i;
+            while (j < sub->descs.size() && sub->descs[j].ukernel_id == sub->descs[i].ukernel_id) ++j;
+            for (uint32_t b = 0; b < own_batch; ++b)
+                for (size_t t = i; t < j; ++t) { own.push_back(sub->descs[t]); own.back().batch = b; }
+            i = j;
+        }
+        for (ft_tile_desc d : own) {
             any = true;
             const ft_ukernel_info &u = set->uk[d.ukernel_id];
             const int code = ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk);
-            if (code < 0 || code > 0x7f || u.stages > 0xf) { ft_plan_destroy(sub); ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
+            if (code < 0 || code > 0x7f || u.stages > 0xf) { ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
             d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (u.stages << 8) | (gi << 12);
             pl->descs.push_back(d);
             const int twin = ft_general_code(code);          // what the general bodies run for it
@@ -1124,7 +1157,6 @@ ft_status ft_plan_create_grouped(const ft_op *op, const ft_ukset *set, const ft_
         s.m = std::max(s.m, g.m); s.n = std::max(s.n, g.n); s.k = std::max(s.k, g.k);
         s.useful_elems += g.useful_elems;
         s.covered_elems += g.covered_elems;
-        ft_plan_destroy(sub);
     }
     ft_group_rec total;                        // one past the last group: the buffers' sizes
     total.m = total.n = total.k = total.batch = 0;

@@ -509,13 +509,15 @@ def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
     at = 0
     off = [0, 0, 0]
     useful = covered = 0
-    launch_batch = sum(kw["batch"] for kw in groups)
+    launch_batch = 1
+    while launch_batch < sum(kw["batch"] for kw in groups):     # the launch's batch, rounded up to a power of two
+        launch_batch *= 2
     if op.batch_hi:
         launch_batch = min(launch_batch, op.batch_hi)
     for gi, kw in enumerate(groups):
         b, m, n, k = oracle_shape(op, kw)
         # the program for this shape at the launch's batch; the group's own batch entries of it
-        want = P.plan(op, uks, (max(b, launch_batch) if b else 0, m, n, k), mode)
+        want = P.plan(op, uks, (launch_batch if b else 0, m, n, k), mode)
         assert ft.ft_plan_group_layout(pl, gi) == tuple(off), (name, gi)
         off = [off[0] + b * m * k, off[1] + b * k * n, off[2] + b * m * n]
         ref = np.frombuffer(b"".join(d.pack() for d in want.descs), dtype=got.dtype)
@@ -527,7 +529,7 @@ def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
         assert ((mine["flags"] & 1) == (ref["flags"] & 1)).all() and ((mine["flags"] >> 12) == gi).all()
         at += len(ref)
         useful += b * m * n
-        covered += want.covered // max(b, launch_batch) * b if want.program is not None and b else 0
+        covered += want.covered // launch_batch * b if want.program is not None and b else 0
     assert at == len(got)
     assert ft.ft_plan_group_layout(pl, len(groups)) == tuple(off)
     st = ft.ft_plan_stats_get(pl)
