@@ -141,3 +141,30 @@ def test_aligned_groups_take_the_vector_path_and_agree_with_the_general_one(dtyp
             Cout = out_view(buf, nc)
             assert np.isfinite(Cout).all()
             check_groups(plan, dims, A[shift:shift + na], B, Cout, dtype, f"aligned ragged {which} shift {shift}")
+
+
+def test_grouped_plan_through_the_timing_entry_points_and_a_graph():
+    """Back-to-back launches of one grouped plan on rotating buffers, eagerly and as a replayed HIP
+    graph, with eager launches in between: every buffer set holds the bits of a single eager launch."""
+    lengths = [77, 128, 5, 300]
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=0, m_hi=512, n_lo=0, n_hi=512, batch_hi=768))
+    groups = [ft.ft_shape(batch=4, m=L, n=L) for L in lengths]
+    dims = [(4, L, L, 64) for L in lengths]
+    plan, A, B, single = run_grouped(op, groups, dims, ft.FT_F16, 23)
+    check_groups(plan, dims, A, B, single, ft.FT_F16, "single grouped launch")
+    nc = single.size
+    side = torch.cuda.Stream()
+    dA, dB = [dev_bits(A) for _ in range(3)], [dev_bits(B) for _ in range(3)]
+    for use_graph in (False, True, True):
+        bufs = [alloc_out(nc) for _ in range(3)]
+        torch.cuda.synchronize()
+        ms = ft.ft_launch_timed(plan, [t.data_ptr() for t in dA], [t.data_ptr() for t in dB],
+                                [b.data_ptr() + 4 * GUARD for b in bufs], side.cuda_stream, 7, graph=use_graph)
+        torch.cuda.synchronize()
+        assert 0.0 < ms < 10.0
+        for b in bufs:
+            assert np.array_equal(out_view(b, nc), single), f"timed grouped launches, graph={use_graph}"
+        buf = alloc_out(nc)
+        ft.ft_launch(plan, dA[0].data_ptr(), dB[0].data_ptr(), buf.data_ptr() + 4 * GUARD, stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(out_view(buf, nc), single), "eager launch between timed runs"
