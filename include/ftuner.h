@@ -287,7 +287,8 @@ ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, 
  * planner picks for its shape at the batch of the whole launch (Sec. 5; the groups share the device:
  * batch = the sum of the groups' batches rounded up to a power of two, at most batch_hi; the set
  * caches the program per (shape, that batch), so later launches only copy tiles); the descriptor table is the
- * concatenation of the groups' own entries in group
+ * concatenation of the groups' own entries, the groups with the longest reduce axis first (then the
+ * largest outputs: the workgroups with the most work start first), operands stay in group
  * order, and descriptor flags carry the group in bits 12..31, the body in bits 1..7 and its LDS ring
  * depth in bits 8..11 (bit 0 as before).  Operands are packed group after group, each group's matrices densely packed as for a
  * plain batched launch; ft_plan_group_layout reports where a group starts.  Launch with ft_launch /

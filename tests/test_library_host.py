@@ -495,7 +495,7 @@ GROUPED = {
 @pytest.mark.parametrize("mode", [P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE])
 @pytest.mark.parametrize("name", sorted(GROUPED))
 def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
-    """Descriptor table = the oracle's plans of the groups one after the other, each descriptor tagged
+    """Descriptor table = the oracle's plans of the groups one after the other (heaviest first), each descriptor tagged
     with its group (flags bits 12..31; bits 1..11 name the compiled body and its ring depth and are the
     library's own);
     operands packed group after group."""
@@ -514,12 +514,20 @@ def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
         launch_batch *= 2
     if op.batch_hi:
         launch_batch = min(launch_batch, op.batch_hi)
-    for gi, kw in enumerate(groups):
+    offs = []
+    for kw in groups:                               # operands: packed in group order
+        b, m, n, k = oracle_shape(op, kw)
+        offs.append(tuple(off))
+        off = [off[0] + b * m * k, off[1] + b * k * n, off[2] + b * m * n]
+    # the table: longest reduce axis first, then the largest outputs (stable)
+    order = sorted(range(len(groups)), key=lambda i: (-oracle_shape(op, groups[i])[3],
+                                                      -oracle_shape(op, groups[i])[1] * oracle_shape(op, groups[i])[2]))
+    for gi in order:
+        kw = groups[gi]
         b, m, n, k = oracle_shape(op, kw)
         # the program for this shape at the launch's batch; the group's own batch entries of it
         want = P.plan(op, uks, (launch_batch if b else 0, m, n, k), mode)
-        assert ft.ft_plan_group_layout(pl, gi) == tuple(off), (name, gi)
-        off = [off[0] + b * m * k, off[1] + b * k * n, off[2] + b * m * n]
+        assert ft.ft_plan_group_layout(pl, gi) == offs[gi], (name, gi)
         ref = np.frombuffer(b"".join(d.pack() for d in want.descs), dtype=got.dtype)
         ref = ref[ref["batch"] < b]
         mine = got[at:at + len(ref)]
