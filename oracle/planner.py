@@ -790,3 +790,39 @@ def exact_cover_counts(pl: Plan, uks: List[UKernel]):
     for d in pl.descs:
         cnt[d.batch, d.m0:d.m0 + d.m_valid, d.n0:d.n0 + d.n_valid] += 1
     return cnt
+
+
+def plan_grouped(op: Op, uks: List[UKernel], shapes, mode=PLAN_PATCHWORK, hw=None, t=None):
+    """Groups of batched Matmuls of different shapes in one launch (the motivation of Sec. 1 /
+    Fig. 1(b): sequences of one batch differ in length, and padding them to the longest wastes most
+    of the work).  shapes: one (batch, M, N, K) per group.  Returns (table, offsets):
+
+    offsets[g] = element offsets (A, B, C) of group g in buffers that pack the groups one after the
+    other in the order given, each group densely packed like a plain batched problem; one more
+    entry holds the totals.
+
+    table = list of (group, Desc).  The groups share the device, so a group's program is the one
+    plan() picks for its shape at the batch of the whole launch -- the sum of the groups' batches
+    rounded up to a power of two, at most batch_hi -- and the group contributes the descriptors of
+    its own batch entries of that plan.  The table lists the groups with the longest reduce axis
+    first, then the larger outputs (ties keep the given order): the workgroups with the most work
+    start first."""
+    offsets, off = [], (0, 0, 0)
+    for b, M, N, K in shapes:
+        offsets.append(off)
+        off = (off[0] + b * M * K, off[1] + b * K * N, off[2] + b * M * N)
+    offsets.append(off)
+    launch_batch = 1
+    while launch_batch < sum(s[0] for s in shapes):
+        launch_batch *= 2
+    if op.batch_hi:
+        launch_batch = min(launch_batch, op.batch_hi)
+    table = []
+    for g in sorted(range(len(shapes)), key=lambda i: (-shapes[i][3], -shapes[i][1] * shapes[i][2])):
+        b, M, N, K = shapes[g]
+        if b == 0:
+            continue
+        whole = plan(op, uks, (max(b, launch_batch), M, N, K), mode, hw, t)
+        table += [(g, d) for d in whole.descs if d.batch < b]
+    return table, offsets
+

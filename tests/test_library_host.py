@@ -506,41 +506,21 @@ def test_grouped_plan_is_the_concatenation_of_the_groups_plans(name, mode):
     pl = ft.ft_plan_create_grouped(lop, s, [ft.ft_shape(**kw) for kw in groups], mode | HOST)
     got = np.frombuffer(ft.ft_plan_descriptors(pl), dtype=np.dtype(
         [("uk", "<u4"), ("batch", "<u4"), ("m0", "<u4"), ("n0", "<u4"), ("mv", "<u2"), ("nv", "<u2"), ("flags", "<u4")]))
-    at = 0
-    off = [0, 0, 0]
-    useful = covered = 0
-    launch_batch = 1
-    while launch_batch < sum(kw["batch"] for kw in groups):     # the launch's batch, rounded up to a power of two
-        launch_batch *= 2
-    if op.batch_hi:
-        launch_batch = min(launch_batch, op.batch_hi)
-    offs = []
-    for kw in groups:                               # operands: packed in group order
-        b, m, n, k = oracle_shape(op, kw)
-        offs.append(tuple(off))
-        off = [off[0] + b * m * k, off[1] + b * k * n, off[2] + b * m * n]
-    # the table: longest reduce axis first, then the largest outputs (stable)
-    order = sorted(range(len(groups)), key=lambda i: (-oracle_shape(op, groups[i])[3],
-                                                      -oracle_shape(op, groups[i])[1] * oracle_shape(op, groups[i])[2]))
-    for gi in order:
-        kw = groups[gi]
-        b, m, n, k = oracle_shape(op, kw)
-        # the program for this shape at the launch's batch; the group's own batch entries of it
-        want = P.plan(op, uks, (launch_batch if b else 0, m, n, k), mode)
-        assert ft.ft_plan_group_layout(pl, gi) == offs[gi], (name, gi)
-        ref = np.frombuffer(b"".join(d.pack() for d in want.descs), dtype=got.dtype)
-        ref = ref[ref["batch"] < b]
-        mine = got[at:at + len(ref)]
-        assert len(mine) == len(ref)
-        for f in ("uk", "batch", "m0", "n0", "mv", "nv"):
-            assert (mine[f] == ref[f]).all(), (name, gi, f)
-        assert ((mine["flags"] & 1) == (ref["flags"] & 1)).all() and ((mine["flags"] >> 12) == gi).all()
-        at += len(ref)
-        useful += b * m * n
-        covered += want.covered // launch_batch * b if want.program is not None and b else 0
-    assert at == len(got)
-    assert ft.ft_plan_group_layout(pl, len(groups)) == tuple(off)
+    shapes = [oracle_shape(op, kw) for kw in groups]
+    table, offsets = P.plan_grouped(op, uks, shapes, mode)
+    for gi in range(len(groups) + 1):
+        assert ft.ft_plan_group_layout(pl, gi) == offsets[gi], (name, gi)
+    assert len(got) == len(table)
+    ref = np.frombuffer(b"".join(d.pack() for _, d in table), dtype=got.dtype)
+    for f in ("uk", "batch", "m0", "n0", "mv", "nv"):
+        assert (got[f] == ref[f]).all(), (name, f)
+    assert ((got["flags"] & 1) == (ref["flags"] & 1)).all()
+    assert (got["flags"] >> 12).tolist() == [g for g, _ in table]
+    at = len(table)
+    useful = sum(b * m * n for b, m, n, k in shapes)
     st = ft.ft_plan_stats_get(pl)
+    tile_area = {u.id: u.tm * u.tn for u in uks}
+    covered = sum(tile_area[d.ukernel_id] for _, d in table)
     assert (st.n_tiles, st.useful_elems, st.covered_elems, st.k_parts, st.table_order) == (at, useful, covered, 1, 1)
     order = ft.ft_plan_launch_order(pl)
     assert sorted(t for t in order if t != 0xFFFFFFFF) == list(range(at))

@@ -572,3 +572,39 @@ def test_eq6_threshold_is_dropped_only_when_nothing_reaches_it():
     assert P.plan(P.Op(P.OP_MATMUL, P.BF16, n=304, k=12, m_range=(0, 1024)), tiny, (1, 543, 304, 12)).descs
     usual = P.derive_ukernels(P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(0, 8192)))
     assert usual and not any(below(u, 768) for u in usual)
+
+
+def test_grouped_table_covers_every_group_exactly_once_heaviest_first():
+    """plan_grouped: brute-force cover of every group's outputs by its own descriptors (each element
+    of each batch entry exactly once, nothing from another group's shape), offsets by hand, and the
+    order of the table."""
+    op = P.Op(P.OP_BMM, P.F16, m_range=(0, 512), n_range=(0, 512), k_range=(0, 512), batch_hi=64)
+    uks = P.derive_ukernels(op)
+    shapes = [(2, 37, 50, 9), (3, 100, 7, 300), (0, 64, 64, 64), (1, 129, 257, 300), (2, 0, 40, 8), (4, 16, 16, 16)]
+    table, offsets = P.plan_grouped(op, uks, shapes)
+    # offsets: running sums of batch * M * K, batch * K * N, batch * M * N in the order given
+    assert offsets[0] == (0, 0, 0) and offsets[1] == (2 * 37 * 9, 2 * 9 * 50, 2 * 37 * 50)
+    assert offsets[-1] == (sum(b * m * k for b, m, n, k in shapes), sum(b * k * n for b, m, n, k in shapes),
+                           sum(b * m * n for b, m, n, k in shapes))
+    # order: reduce extent descending, then output size descending; empty groups contribute nothing
+    seen = []
+    for g, _ in table:
+        if not seen or seen[-1] != g:
+            seen.append(g)
+    assert seen == [3, 1, 5, 0]          # K = 300 twice (the larger output first), then K = 16, then K = 9
+    for g, (b, M, N, K) in enumerate(shapes):
+        count = [[[0] * N for _ in range(M)] for _ in range(b)]
+        for gg, d in table:
+            if gg != g:
+                continue
+            u = uks[d.ukernel_id]
+            assert d.batch < b and d.m_valid == min(u.tm, M - d.m0) and d.n_valid == min(u.tn, N - d.n0)
+            for i in range(d.m0, d.m0 + d.m_valid):
+                for j in range(d.n0, d.n0 + d.n_valid):
+                    count[d.batch][i][j] += 1
+        assert all(c == 1 for e in count for row in e for c in row), g
+    # the launch's batch: 12 entries -> 16; a group planned alone at its own batch may differ, at 16 it may not
+    b, M, N, K = shapes[1]
+    own = [d for g, d in table if g == 1]
+    at_launch = [d for d in P.plan(op, uks, (16, M, N, K)).descs if d.batch < b]
+    assert [d.pack() for d in own] == [d.pack() for d in at_launch]
