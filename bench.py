@@ -36,7 +36,7 @@ RING_BYTES = 600e6             # > 256 MB Infinity Cache + 8 x 4 MB L2
 # sweep), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
 # counters read for a plain 1 GiB copy (x2.0 and x1.0); see profiles/ft_dispatch_pmc.md.
 # Counters cannot be read from inside this process, so the figures are those of the committed profile.
-MEASURED_TRAFFIC_BYTES = {"ft_dispatch_dt0_c0": 20.43e6 + 5.32e6, "ft_dispatch_dt0_c1": 21.88e6 + 9.99e6}
+MEASURED_TRAFFIC_BYTES = {"ft_dispatch_dt0_c0": 19.77e6 + 5.66e6, "ft_dispatch_dt0_c1": 22.79e6 + 9.48e6}
 
 
 def geomean(xs):
