@@ -14,8 +14,9 @@ Headline `value`: geomean over the 21 GEMMs of useful TFLOP/s with operands resi
 but NOT in cache (each launch uses the next of a ring of buffer sets totalling > 600 MB).
 The same measurement with a single, cache-warm buffer set is reported beside it as
 `warm_cache`, the pad-to-library baseline plan as `pad_baseline`, the bucketed padding of serving
-stacks (M rounded up to the next power of two) as `bucketed_baseline`, and the latency of a single
-launch followed by a wait as `single_launch_us_geomean`.
+stacks (M rounded up to the next power of two) as `bucketed_baseline`, the latency of a single
+launch followed by a wait as `single_launch_us_geomean`, and, as a second workload of the same library,
+one ragged attention batch run as a single grouped launch (`ragged_attention`).
 
 Prints ONE JSON line on stdout; per-GEMM details go to the JSON file named by --detail.
 """
@@ -81,12 +82,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="time one HIP-graph replay of the launches instead of direct launches")
-    ap.add_argument("--variants", default="cold,warm,base,out16,bucket,single",
+    ap.add_argument("--variants", default="cold,warm,base,out16,bucket,single,ragged",
                     help="comma list of the timed variants: cold (headline), warm (one buffer set), base "
                          "(pad-to-library plan), out16 (same sweep with C stored as fp16, reported beside the "
                          "headline), bucket (M padded to the next power of two, the planner's plan for that "
-                         "shape), single (one launch between two events, median of 5); 'cold' alone is what the "
-                         "committed profiles run")
+                         "shape), single (one launch between two events, median of 5), ragged (a ragged attention "
+                         "batch as one grouped launch, informational); 'cold' alone is what the committed profiles run")
     ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -105,8 +106,8 @@ def main():
     stream = side.cuda_stream
     use_graph = args.graph
     variants = set(args.variants.split(","))
-    assert "cold" in variants and variants <= {"cold", "warm", "base", "out16", "bucket", "single"}, \
-        "--variants: cold[,warm][,base][,out16][,bucket][,single]"
+    assert "cold" in variants and variants <= {"cold", "warm", "base", "out16", "bucket", "single", "ragged"}, \
+        "--variants: cold[,warm][,base][,out16][,bucket][,single][,ragged]"
     hw = ft.ft_hw_query(0)
 
     def timed(plan, pa, pb, pc, iters, graph=None):
@@ -220,6 +221,17 @@ def main():
         del As, Bs, Cs
         torch.cuda.empty_cache()
 
+    # informational, beside the headline: a second workload of the same library, one ragged batch of
+    # attention (64 sequences x 12 heads, one length each) as ONE grouped launch against padding every
+    # sequence to the longest and against one launch per sequence
+    ragged = None
+    if "ragged" in variants:
+        from paper_2407_21418_amd import run_ragged
+        rr = run_ragged.measure(draws=1, iters=10)
+        ragged = {r["op"]: {"grouped_us": r["us_grouped"], "padded_to_longest_us": r["us_padded"],
+                            "one_launch_per_sequence_us": r["us_looped"], "useful_tflops": r["tflops_grouped"]} for r in rr}
+        ragged["note"] = "64 sequences x 12 heads, lengths uniform on 1..512, fp16 in, fp32 out, cold ring; not the headline"
+
     ms_per_step = sum(r["ms_cold"] for r in rows)
     value = geomean([r["tflops_cold"] for r in rows])
     warm = geomean([r["tflops_warm"] for r in rows]) if "warm" in variants else 0.0
@@ -268,6 +280,7 @@ def main():
                               "note": "M padded to the next power of two (>= 16), the planner's own plan for the padded "
                                       "shape, useful flops of the true M; cold"} if "bucket" in variants else None,
         "single_launch_us_geomean": round(geomean([r["us_single"] for r in rows]), 3) if "single" in variants else None,
+        "ragged_attention": ragged,
         "plan_ms_cold_total": round(t_plan_cold * 1e3, 3),
         "plan_us_cached_lookup": round(t_plan_cached_us, 2),
         "roofline": {"bound": "hbm" if hbm_bound else "mfma", "kernel": dom,

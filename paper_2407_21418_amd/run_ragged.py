@@ -32,6 +32,18 @@ def main():
     ap.add_argument("--align", type=int, default=1, help="round every length up to a multiple of this (8: the "
                     "grouped launch then runs the LDS-DMA bodies)")
     a = ap.parse_args()
+    rows = measure(a.seqs, a.heads, a.iters, a.draws, a.align, a.ring_mb, verbose=True)
+    gm = lambda xs: math.exp(sum(math.log(x) for x in xs) / len(xs))
+    print(json.dumps({"workload": "ragged attention batches, %d sequences x %d heads, lengths rounded up to multiples of %d, fp16 in, fp32 out" % (a.seqs, a.heads, a.align),
+                      "speedup_vs_padded_geomean": round(gm([r["us_padded"] / r["us_grouped"] for r in rows]), 3),
+                      "speedup_vs_looped_geomean": round(gm([r["us_looped"] / r["us_grouped"] for r in rows]), 3),
+                      "rows": rows}))
+
+
+def measure(seqs=64, heads=12, iters=20, draws=4, align=1, ring_mb=600.0, verbose=False):
+    """The measurement itself; returns one row per draw and operator."""
+    import argparse as _ap
+    a = _ap.Namespace(seqs=seqs, heads=heads, iters=iters, draws=draws, align=align, ring_mb=ring_mb)
 
     import torch
     import paper_2407_21418_amd as ft
@@ -102,15 +114,12 @@ def main():
                              tflops_grouped=round(flops / us_grouped / 1e6, 1), tiles=int(st.n_tiles),
                              padded_work_ratio=round(a.seqs * Lmax * Lmax / max(1, sum(L * L for L in lengths)), 2)))
             r = rows[-1]
-            print("draw %d %s: %d seqs x %d heads, L mean %.0f max %d | grouped %7.1f us (%5.1f TFLOP/s useful, %d tiles) | "
-                  "padded to max %7.1f us (x%.2f, %.2fx the work) | one launch per sequence %7.1f us (x%.2f)"
-                  % (draw, which, a.seqs, H, r["mean_len"], Lmax, us_grouped, r["tflops_grouped"], r["tiles"], us_padded,
-                     us_padded / us_grouped, r["padded_work_ratio"], us_looped, us_looped / us_grouped), flush=True)
-    gm = lambda xs: math.exp(sum(math.log(x) for x in xs) / len(xs))
-    print(json.dumps({"workload": "ragged attention batches, %d sequences x %d heads, lengths rounded up to multiples of %d, fp16 in, fp32 out" % (a.seqs, H, a.align),
-                      "speedup_vs_padded_geomean": round(gm([r["us_padded"] / r["us_grouped"] for r in rows]), 3),
-                      "speedup_vs_looped_geomean": round(gm([r["us_looped"] / r["us_grouped"] for r in rows]), 3),
-                      "rows": rows}))
+            if verbose:
+                print("draw %d %s: %d seqs x %d heads, L mean %.0f max %d | grouped %7.1f us (%5.1f TFLOP/s useful, %d tiles) | "
+                      "padded to max %7.1f us (x%.2f, %.2fx the work) | one launch per sequence %7.1f us (x%.2f)"
+                      % (draw, which, a.seqs, H, r["mean_len"], Lmax, us_grouped, r["tflops_grouped"], r["tiles"], us_padded,
+                         us_padded / us_grouped, r["padded_work_ratio"], us_looped, us_looped / us_grouped), flush=True)
+    return rows
 
 
 if __name__ == "__main__":
