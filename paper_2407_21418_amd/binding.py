@@ -8,7 +8,8 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libftuner.so")
+# FTUNER_LIB names another build of the same library (e.g. the development variant with timestamps)
+LIB_PATH = os.environ.get("FTUNER_LIB") or os.path.join(_HERE, "libftuner.so")
 
 FT_OK = 0
 FT_ERR_INVALID_ARG, FT_ERR_UNSUPPORTED, FT_ERR_OUT_OF_RANGE = -1, -2, -3

@@ -47,34 +47,6 @@ def _resource_usage(log):
     return out
 
 
-OBJDUMP = os.environ.get("LLVM_OBJDUMP", "/opt/rocm/llvm/bin/llvm-objdump")
-
-
-def _readfirstlane_count(obj):
-    """Number of v_readfirstlane in the device code of one of our own dispatcher objects, or None
-    if the tools are missing.  A dispatcher has a few hundred (wave ids, uniform addresses).  Several
-    thousand mean the compiler lost track of what is uniform per workgroup and wrapped the buffer
-    accesses of every body in per-lane "waterfall" loops: such a build ran the store-bound
-    attention launches 10-30 % slower."""
-    import glob
-    import shutil
-    import tempfile
-    if not os.path.exists(OBJDUMP):
-        return None
-    tmp = tempfile.mkdtemp(prefix="ftuner_objdump_")
-    try:
-        local = os.path.join(tmp, os.path.basename(obj))
-        shutil.copy(obj, local)
-        subprocess.run([OBJDUMP, "--offloading", local], stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-        dev = glob.glob(local + ".*gfx950*")
-        if not dev:
-            return None
-        p = subprocess.run([OBJDUMP, "-d", dev[0]], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
-        return p.stdout.count("v_readfirstlane_b32")
-    finally:
-        shutil.rmtree(tmp, ignore_errors=True)
-
-
 def _stale(obj, srcs):
     if not os.path.exists(obj):
         return True
@@ -82,8 +54,15 @@ def _stale(obj, srcs):
     return any(os.path.getmtime(s) > t for s in srcs)
 
 
-def build(verbose=True, remarks=True, jobs=None, incremental=False):
-    """incremental=True recompiles only objects older than the sources they include."""
+def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False):
+    """incremental=True recompiles only objects older than the sources they include.
+    trace=True builds the development variant libftuner_trace.so (-DFT_TRACE: workgroups leave
+    timestamps, see FT_MARK) from objects of its own; the product library is not touched."""
+    global OUT, LIB, COMMON
+    if trace:
+        OUT, LIB = os.path.join(HERE, "_build_trace"), os.path.join(HERE, "libftuner_trace.so")
+        if "-DFT_TRACE" not in COMMON:
+            COMMON = COMMON + ["-DFT_TRACE"]
     os.makedirs(OUT, exist_ok=True)
     hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + \
            [os.path.join(INC, "ftuner.h")]
@@ -123,10 +102,16 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False):
         obj = os.path.join(OUT, src.replace(".", "_") + ".o")
         steps.append((obj, [HIPCC] + COMMON + ["-c", os.path.join(CSRC, src), "-o", obj]))
     jobs = jobs or min(8, len(steps))
-    todo = steps
+    if trace:
+        # only the f16 LDS-DMA dispatchers and the launch code carry the marks; everything else is
+        # linked from the product build (same argument layout), which must exist
+        prod = os.path.join(HERE, "_build")
+        keep = lambda o: any(t in os.path.basename(o) for t in ("dispatch_dt0_c", "device_hip", "host_cpp"))
+        steps = [(o, c) if keep(o) else (os.path.join(prod, os.path.basename(o)), None) for o, c in steps]
+    todo = [(o, c) for o, c in steps if c is not None]
     if incremental:
         src_of = lambda cmd: cmd[cmd.index("-c") + 1]
-        todo = [(o, c) for o, c in steps if _stale(o, hdrs + [src_of(c)])]
+        todo = [(o, c) for o, c in todo if _stale(o, hdrs + [src_of(c)])]
     with cf.ThreadPoolExecutor(max_workers=jobs) as ex:
         futs = {ex.submit(_run, cmd, obj + ".log"): obj for obj, cmd in todo}
         for fut in cf.as_completed(futs):
@@ -145,12 +130,6 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False):
         allowed = 32 if ("_gen_" in os.path.basename(obj) or "_grp_" in os.path.basename(obj)) else 0
         if use.get("ScratchSize [bytes/lane]", 0) > allowed:
             raise RuntimeError(f"{os.path.basename(obj)} uses scratch memory: {use}")
-        n_rfl = _readfirstlane_count(obj)
-        if verbose or remarks:
-            print(f"    v_readfirstlane in its device code: {n_rfl}", flush=True)
-        if n_rfl is not None and n_rfl > 1500:
-            raise RuntimeError(f"{os.path.basename(obj)}: {n_rfl} v_readfirstlane: per-workgroup values are no longer "
-                               "known to be uniform (waterfall loops around buffer accesses)")
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in steps]
     _run(link, os.path.join(OUT, "link.log"))
     if verbose:
@@ -159,4 +138,4 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False):
 
 
 if __name__ == "__main__":
-    build(remarks="--remarks" in sys.argv, incremental="--incremental" in sys.argv)
+    build(remarks="--remarks" in sys.argv, incremental="--incremental" in sys.argv, trace="--trace" in sys.argv)

@@ -31,6 +31,10 @@ static_assert(sizeof(ftk::GroupRec) == sizeof(ft_group_rec) && sizeof(ft_group_r
 static_assert(sizeof(ftk::TileDesc) == sizeof(ft_tile_desc) && sizeof(ft_tile_desc) == 24,
               "descriptor layout is part of the ABI");
 
+#ifdef FT_TRACE
+uint64_t *g_trace = nullptr;      // development builds: where the next launches leave their timestamps
+#endif
+
 ft_status hip_fail(hipError_t e) {
     ftd_set_hip_error((int)e);
     return FT_ERR_HIP;
@@ -78,6 +82,9 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const fl
     a->ws_tile_stride = p->ws_tile_stride;
     a->ws = static_cast<float *>(p->d_ws);
     a->arrive = static_cast<uint32_t *>(p->d_arrive);
+#ifdef FT_TRACE
+    a->trace = g_trace;
+#endif
     // Non-temporal stores stream past the L2, which keeps the operand panels resident.  A store
     // instruction writes 128-byte row segments; where rows of C do not start on 64-byte blocks the
     // segments of neighbouring tiles share blocks, a streamed partial block goes to memory as it is
@@ -131,6 +138,11 @@ void ftd_release(ft_plan *p) {
 }
 
 extern "C" {
+
+#ifdef FT_TRACE
+// development builds only: device buffer of 8 x (workgroups of the largest launch) uint64, or NULL
+void ft_debug_set_trace(void *dev_buf) { g_trace = static_cast<uint64_t *>(dev_buf); }
+#endif
 
 ft_status ft_hw_query(int32_t hip_device, ft_hw_model *out) {
     if (!out) return FT_ERR_INVALID_ARG;

@@ -36,6 +36,7 @@ namespace ftk {
 
 __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    FT_MARK(g, 0);
     // The arguments span several cache lines and the compiler loads each field right before its
     // first use, so a cold scalar cache would be missed several times in a row (about half a
     // microsecond each, on the critical path of every workgroup).  Touch every line once, up front

@@ -336,14 +336,29 @@ struct UKernelFast {
                 for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
 
         // ---- prologue: fill S-1 stages ------------------------------------------------------------
+        FT_MARK(g, 1);
         for (uint32_t s = 0; s + 1 < S && s < nk; ++s) issue(s);
+        FT_MARK(g, 2);
 
         for (uint32_t kt = 0; kt < nk; ++kt) {
             // copies issued so far: tiles 0 .. min(kt+S-2, nk-1); tile kt must have landed
             uint32_t newest = kt + S - 2 < nk - 1 ? kt + S - 2 : nk - 1;
+#ifdef FT_TRACE
+            if (kt == nk / 2) FT_MARK_CLK(g, 8);
+#endif
             wait_tiles<0>((int)(newest - kt));
+#ifdef FT_TRACE
+            if (kt == nk / 2) FT_MARK_CLK(g, 9);
+#endif
             __builtin_amdgcn_s_barrier();      // tile kt visible to every wave; stage (kt-1)%S is free again
+#ifdef FT_TRACE
+            if (kt == 0) FT_MARK(g, 3);
+            if (kt == nk / 2) { FT_MARK(g, 4); FT_MARK_CLK(g, 10); }
+#endif
             if (kt + S - 1 < nk) issue(kt + S - 1);
+#ifdef FT_TRACE
+            if (kt == nk / 2) FT_MARK_CLK(g, 11);
+#endif
 
             const uint32_t soff = (kt % S) * STAGE_BYTES;
             const uint32_t a_addr = fa_addr0 + soff;
@@ -355,14 +370,24 @@ struct UKernelFast {
             u32x2 fb[2][BN][2];
             read_step<0, 0>(a_addr, b_addr, fa, fb);
             step<0>(a_addr, b_addr, fa, fb, acc);
+#ifdef FT_TRACE
+            if (kt == nk / 2) FT_MARK_CLK(g, 12);
+            if (kt == nk / 2 + 1) FT_MARK_CLK(g, 13);
+#endif
         }
 
         // ---- epilogue ------------------------------------------------------------------------------
+        FT_MARK(g, 5);
         // (bodies with more than 128 accumulator registers have no room for it: the host never splits them)
         if constexpr (WM * WN / 64 <= FT_KPART_ACC_MAX) if (g.k_parts > 1) {
             if (!k_part_exchange_blocks<M16>(g, t, part, wave, lane, acc)) return;
         }
+        FT_MARK(g, 6);
         store_acc<DT, true, M16, BM, BN>(g, (uint64_t)d.batch * g.strideC, m0 + wave_m * WM, n0 + wave_n * WN, lane, acc);
+#ifdef FT_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        FT_MARK(g, 7);
+#endif
     }
 
     // LDS reads of the A and B fragments of k-step ks into fragment set buf.  Row offsets of the
