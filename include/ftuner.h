@@ -73,6 +73,8 @@ typedef struct ft_hw_model {
                                                 tile to the workgroup that sums them (2000)   */
     uint32_t part_exchange_bytes_per_clk;    /* rate at which that workgroup reads the k_parts
                                                 fp32 partial tiles (16); 0: not counted       */
+    uint32_t phase_latency_clk;              /* two-team bodies: cost of the barrier that ends each
+                                                k-tile phase (150)                            */
 } ft_hw_model;
 
 /* gfx950 defaults; host only. out: host pointer. */
@@ -110,6 +112,11 @@ typedef struct ft_tuning {
     uint32_t second_axis_strips;                    /* 0: off (default: measured slower on gfx950,
                                                        where the fp32 score matrix is bound by its
                                                        own write), 1: on                           */
+    /* Two-team bodies (Sec. 3: a uKernel is one thread block; Fig. 7: its thread-level tiling): the
+     * standard wave grids again with EIGHT waves, two teams of four that take alternate k-tiles of
+     * the same tile, so that one team's copies overlap the other's MFMAs (gk = 2 in
+     * ft_ukernel_info).  Matmul and Conv2d.                                                     */
+    uint32_t two_team_bodies;                       /* 1: derive them, 0: four-wave bodies only (default) */
 } ft_tuning;
 enum { FT_SIA_LINEAR = 0, FT_SIA_PRODUCT = 1 };
 
@@ -163,9 +170,11 @@ typedef struct ft_ukernel_info {
     uint32_t id;                   /* index in the set                                       */
     uint32_t tm, tn, tk;           /* smem_tile: workgroup tile staged in LDS                */
     uint32_t wm, wn;               /* reg_tile: per-wave fp32 accumulator tile               */
-    uint32_t gm, gn, gk;           /* wave grid over rows, columns, reduce axis (gm*gn*gk = 4)*/
+    uint32_t gm, gn, gk;           /* wave grid over rows, columns, reduce axis: gm*gn*gk = 4 waves, or
+                                      gk = 2 with gm*gn = 4: two teams of four waves (eight in all)  */
     uint32_t mfma;                 /* 0: 32x32x16, 1: 16x16x32                               */
-    uint32_t stages;               /* LDS ring depth: k-tiles resident at once (2..8)        */
+    uint32_t stages;               /* LDS ring depth: k-tiles resident at once (2..8), per wave for
+                                      gk = 4 and per team for gk = 2                          */
     uint32_t lds_bytes;            /* gk*stages*(tm+tn)*tk*2                                 */
     uint32_t acc_regs;             /* wm*wn/64 per lane                                      */
     uint32_t regs;                 /* acc_regs + RestRegs                                    */

@@ -43,13 +43,13 @@ class ft_hw_model(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "num_cus", "simds_per_cu", "wave_size", "regs_per_lane", "max_waves_per_simd",
         "lds_bytes_per_cu", "clock_mhz", "mfma_flops_per_clk_per_cu", "bw_global_bytes_per_clk_per_cu",
-        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds", "part_exchange_clk", "part_exchange_bytes_per_clk")]
+        "bw_lds_bytes_per_clk_per_cu", "ktile_latency_clk", "solo_copy_exposed_pct", "hbm_gbytes_per_s", "num_xcds", "part_exchange_clk", "part_exchange_bytes_per_clk", "phase_latency_clk")]
 
 
 class ft_tuning(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "eps_min_pm", "eps_max_pm", "eps_step_pm", "lam_max_pm", "lam_min_pm", "lam_step_pm",
-        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form", "k_parts_max", "k_part_min_tiles", "second_axis_strips")]
+        "zeta", "rest_regs", "psi_num", "psi_den", "c0", "c1", "c2", "sia_form", "k_parts_max", "k_part_min_tiles", "second_axis_strips", "two_team_bodies")]
 
 
 class ft_op_desc(_S):

@@ -61,8 +61,10 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
     global OUT, LIB, COMMON
     if trace:
         OUT, LIB = os.path.join(HERE, "_build_trace"), os.path.join(HERE, "libftuner_trace.so")
-        if "-DFT_TRACE" not in COMMON:
-            COMMON = COMMON + ["-DFT_TRACE"]
+        # FT_DEBUG_DEFS / FT_TRACE_LIB: other development switches (see gemm_fast.h) and the file to write
+        extra = os.environ.get("FT_DEBUG_DEFS", "-DFT_TRACE").split()
+        COMMON = [c for c in COMMON if not c.startswith("-DFT_DEBUG") and c != "-DFT_TRACE"] + extra
+        LIB = os.environ.get("FT_TRACE_LIB", LIB)
     os.makedirs(OUT, exist_ok=True)
     hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + \
            [os.path.join(INC, "ftuner.h")]
@@ -71,6 +73,13 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
         for cl in (0, 1, 2):
             obj = os.path.join(OUT, f"dispatch_dt{dt}_c{cl}.o")
             cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-c",
+                                      os.path.join(CSRC, "dispatch.hip"), "-o", obj]
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+            steps.append((obj, cmd))
+    for dt in (0, 1):                         # two-team bodies: workgroups of eight waves
+        for cl in (0, 1):
+            obj = os.path.join(OUT, f"dispatch_dt{dt}_pp_c{cl}.o")
+            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_PP=1", "-c",
                                       os.path.join(CSRC, "dispatch.hip"), "-o", obj]
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             steps.append((obj, cmd))
@@ -106,7 +115,7 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
         # only the f16 LDS-DMA dispatchers and the launch code carry the marks; everything else is
         # linked from the product build (same argument layout), which must exist
         prod = os.path.join(HERE, "_build")
-        keep = lambda o: any(t in os.path.basename(o) for t in ("dispatch_dt0_c", "device_hip", "host_cpp"))
+        keep = lambda o: any(t in os.path.basename(o) for t in ("dispatch_dt0_c", "dispatch_dt0_pp_c", "device_hip", "host_cpp"))
         steps = [(o, c) if keep(o) else (os.path.join(prod, os.path.basename(o)), None) for o, c in steps]
     todo = [(o, c) for o, c in steps if c is not None]
     if incremental:
@@ -128,6 +137,8 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
         if verbose or remarks:
             print(f"  {os.path.basename(obj)}: {use}", flush=True)
         allowed = 32 if ("_gen_" in os.path.basename(obj) or "_grp_" in os.path.basename(obj)) else 0
+        if trace:
+            allowed = 1 << 20                 # development variants are not held to it
         if use.get("ScratchSize [bytes/lane]", 0) > allowed:
             raise RuntimeError(f"{os.path.basename(obj)} uses scratch memory: {use}")
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in steps]

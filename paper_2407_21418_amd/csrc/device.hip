@@ -16,6 +16,8 @@ const launch_fn kLaunch[2][FT_NUM_CLASSES] = {
     {ft_launch_dt1_c0, ft_launch_dt1_c1, ft_launch_dt1_c2},
 };
 
+// two-team bodies (eight waves): classes 0 and 1
+const launch_fn kLaunchTwoTeams[2][2] = {{ft_launch_dt0_pp_c0, ft_launch_dt0_pp_c1}, {ft_launch_dt1_pp_c0, ft_launch_dt1_pp_c1}};
 // general bodies: [dtype][0] = bodies with <= 64 accumulator registers (256-register kernel),
 // [dtype][1] = all bodies (512-register kernel)
 const launch_fn kLaunchGeneric[2][2] = {{ft_launch_dt0_gen_c1, ft_launch_dt0_gen_c2},
@@ -210,7 +212,10 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
         a.k_parts = 1;                 // these bodies walk the whole reduce axis in one workgroup
     }
     int rc;
-    if (fast) {
+    if (fast && plan->two_teams) {
+        if (plan->st.kernel_class > 1) return FT_ERR_UNSUPPORTED;
+        rc = kLaunchTwoTeams[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
+    } else if (fast) {
         rc = kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
     } else {
         // the general bodies stage through registers into two LDS stages, whatever ring depth the

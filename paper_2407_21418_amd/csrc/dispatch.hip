@@ -5,6 +5,8 @@
 // operands) and per dtype with -DFT_GENERIC=1 -DFT_CLASS={1,2} for the general bodies (any alignment,
 // ragged reduce axis, convolution gather): class 1 holds every body with at most 64 accumulator
 // registers in a 256-register kernel (two workgroups per CU), class 2 all of them in 512 registers.
+#include <mutex>
+
 #include "gemm_fast.h"
 #include "family.h"
 #include "launch_iface.h"
@@ -13,8 +15,18 @@
 #ifndef FT_DT
 #error "define FT_DT"
 #endif
+#define FT_MAX_DEVICES 64
 #ifndef FT_CLASS
 #error "define FT_CLASS"
+#endif
+
+#ifdef FT_PP
+// two-team workgroups: eight waves, two per SIMD; classes 0 (128 registers) and 1 (256 registers)
+#define FT_THREADS 512
+#define FT_TEAMS 2
+#else
+#define FT_THREADS 256
+#define FT_TEAMS 1
 #endif
 
 #if FT_CLASS == 0
@@ -22,8 +34,8 @@
 #define FT_ACC_MAX 32
 #elif FT_CLASS == 1
 #define FT_MIN_WAVES 2
-#ifdef FT_GENERIC
-#define FT_ACC_MAX 64        // the general bodies also hold their staging registers
+#if defined(FT_GENERIC) || defined(FT_PP)
+#define FT_ACC_MAX 64        // the general bodies also hold their staging registers; two teams: see family.h
 #else
 #define FT_ACC_MAX 128
 #endif
@@ -34,7 +46,7 @@
 
 namespace ftk {
 
-__global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
+__global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     FT_MARK(g, 0);
     // The arguments span several cache lines and the compiler loads each field right before its
@@ -192,6 +204,12 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
             UKernelBody<FT_DT, WM, WN, GM, GN, FT_TK>::run(g, d, smem);         \
         break;
+#elif defined(FT_PP)
+#define FT_X(CODE, WM, WN, GM, GN)                                              \
+    case CODE:                                                                  \
+        if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX && ((GM) * (WM) + (GN) * (WN)) * FT_TK * 2 <= FT_PP_STAGE_MAX) \
+            UKernelFast<FT_DT, WM, WN, GM, GN, 2>::run(g, d, smem, stages, t, part); \
+        break;
 #else
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
@@ -204,7 +222,7 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
         FT_FAMILY_PARTIAL(FT_X)
 #endif
 #undef FT_X
-#ifndef FT_GENERIC
+#if !defined(FT_GENERIC) && !defined(FT_PP)
 #define FT_X(CODE, TM, TN, TWIN)                                                \
     case CODE:                                                                  \
         if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \
@@ -221,17 +239,26 @@ __global__ __launch_bounds__(256, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs g) {
 }  // namespace ftk
 
 extern "C" int FT_LAUNCH_NAME(const ftk::KArgs *args, uint32_t lds_bytes, void *stream) {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ftk::FT_KERNEL_NAME),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
+    // the attribute is kept per device: set it once on each device this kernel is launched on
+    static std::mutex attr_mu;
+    static bool attr_done[FT_MAX_DEVICES] = {};
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return (int)e;
-        attr_done = true;
+        if (dev < 0 || dev >= FT_MAX_DEVICES) return (int)hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> lock(attr_mu);
+        if (!attr_done[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ftk::FT_KERNEL_NAME),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
+            if (e != hipSuccess) return (int)e;
+            attr_done[dev] = true;
+        }
     }
     const uint32_t nx = args->num_xcds ? args->num_xcds : 1;
     uint32_t grid = args->table_order ? ftk::table_grid(args->n_tiles, nx) : args->n_tiles;
     if (args->k_parts > 1) grid = (grid + nx - 1) / nx * nx * args->k_parts;
-    hipLaunchKernelGGL(ftk::FT_KERNEL_NAME, dim3(grid), dim3(256), lds_bytes,
+    hipLaunchKernelGGL(ftk::FT_KERNEL_NAME, dim3(grid), dim3(FT_THREADS), lds_bytes,
                        static_cast<hipStream_t>(stream), *args);
     return (int)hipGetLastError();
 }

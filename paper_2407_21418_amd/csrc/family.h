@@ -26,6 +26,11 @@
 // X(code, WM, WN, GM, GN) with GM*GN < 4.  Compiled into the general dispatcher only.
 #define FT_FAMILY_PARTIAL(X) X(37, 16, 16, 1, 2) X(38, 16, 16, 1, 1)
 
+// Two-team ("ping-pong") workgroups of eight waves run the standard-grid bodies above, gk = 2: both
+// teams' rings of at least two stages must fit the LDS and each wave keeps at most 64 accumulator
+// registers (two waves per SIMD in a 256-register kernel; class 0: <= 32 in 128 registers).
+#define FT_PP_STAGE_MAX 40960
+#define FT_PP_ACC_MAX 64
 #define FT_TK 64
 #define FT_NUM_CLASSES 3
 // bodies with more accumulator registers per lane than this cannot take part in a reduce-axis
@@ -37,7 +42,8 @@
 //   class 2: acc <= 256 (1 wave/SIMD,  <= 512 registers)
 static inline int ft_class_of_acc(int acc_regs) { return acc_regs <= 32 ? 0 : (acc_regs <= 128 ? 1 : 2); }
 static inline int ft_body_code(int wm, int wn, int gm, int gn, int gk) {
-    if (gk == 1) {
+    if (gk == 2 && ((gm * wm + gn * wn) * FT_TK * 2 > FT_PP_STAGE_MAX || wm * wn / 64 > FT_PP_ACC_MAX)) return -1;
+    if (gk == 1 || gk == 2) {            // two teams (gk = 2) run the standard-grid body of the same code
 #define FT_X(code, WM, WN, GM, GN) if (wm == WM && wn == WN && gm == GM && gn == GN) return code;
         FT_FAMILY(FT_X)
 #undef FT_X

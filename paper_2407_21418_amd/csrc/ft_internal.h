@@ -39,6 +39,7 @@ struct ft_plan {
     uint32_t slot_stages[4];
     uint32_t n_slots;
     bool table_order;                                      // workgroup b takes descriptor b (plans with strips)
+    bool two_teams;                                        // the plan's uKernels are two-team bodies (eight waves)
     uint32_t slot_first[2], slot_rows[2], slot_cols[2];   // tile grid of each constituent in the table
     uint32_t slot_group[2];                                // tile rows per group of the launch order
     uint32_t slot_m0[2], slot_n0[2], slot_tm[2], slot_tn[2];   // closed form of each constituent's descriptors

@@ -190,7 +190,10 @@ template <int OUT> __device__ __forceinline__ typename OutElem<OUT>::type out_cv
 // bench sweep). The hint is only safe for speed when every store instruction fills whole 64-byte
 // blocks: partial blocks written this way are not merged in the L2 and cost 2-3x the time of a plain
 // store (measured on fp32 score matrices with odd row pitch), so the host sets it per launch.
-template <int OUT, bool INTERIOR_PATH, bool STREAM, bool M16, int BM, int BN, typename Acc>
+// BI0..BI1 / BJ0..BJ1: the rows / columns of accumulator blocks this call stores (all by default; a
+// workgroup of two teams stores half of a wave tile from each).
+template <int OUT, bool INTERIOR_PATH, bool STREAM, bool M16, int BM, int BN, int BI0 = 0, int BI1 = BM, int BJ0 = 0,
+          int BJ1 = BN, typename Acc>
 __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const float *__restrict__ bias, uint32_t ldc,
                                              uint32_t M, uint32_t N, uint32_t m0w, uint32_t n0w, uint32_t lane,
                                              const Acc (&acc)[BM][BN]) {
@@ -200,20 +203,20 @@ __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const floa
     const uint32_t lrow = 4 * (lane / MB), lcol = lane % MB;
     float bv[BN];
 #pragma unroll
-    for (int bj = 0; bj < BN; ++bj) {
+    for (int bj = BJ0; bj < BJ1; ++bj) {
         const uint32_t col = n0w + bj * MB + lcol;
         bv[bj] = (bias != nullptr && col < N) ? bias[col] : 0.f;
     }
     if (INTERIOR_PATH && m0w + BM * MB <= M && n0w + BN * MB <= N) {
         T *lp = Cb + ((uint64_t)(m0w + lrow) * ldc + n0w + lcol);
 #pragma unroll
-        for (int bi = 0; bi < BM; ++bi)
+        for (int bi = BI0; bi < BI1; ++bi)
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
                 const uint32_t r = bi * MB + (M16 ? e : 8 * (e / 4) + (e % 4));
                 T *rp = lp + (uint64_t)r * ldc;
 #pragma unroll
-                for (int bj = 0; bj < BN; ++bj) {
+                for (int bj = BJ0; bj < BJ1; ++bj) {
                     const T v = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
                     if constexpr (STREAM) __builtin_nontemporal_store(v, &rp[bj * MB]);
                     else rp[bj * MB] = v;
@@ -236,16 +239,16 @@ __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const floa
     constexpr int AUX_NT = STREAM ? 2 : 0;   // cache-policy bits of the buffer instruction: nt (streaming)
     uint32_t vb[BN];
 #pragma unroll
-    for (int bj = 0; bj < BN; ++bj)
+    for (int bj = BJ0; bj < BJ1; ++bj)
         vb[bj] = (bj * MB + lcol < cols_valid) ? (lrow * ldc + bj * MB + lcol) * ES : 0x80000000u;
 #pragma unroll
-    for (int bi = 0; bi < BM; ++bi)
+    for (int bi = BI0; bi < BI1; ++bi)
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
             const uint32_t r = bi * MB + (M16 ? e : 8 * (e / 4) + (e % 4));
             const uint32_t roff = r * ldc * ES;                       // uniform
 #pragma unroll
-            for (int bj = 0; bj < BN; ++bj) {
+            for (int bj = BJ0; bj < BJ1; ++bj) {
                 const T v = out_cvt<OUT>(acc[bi][bj][e] + bv[bj]);
                 if constexpr (OUT == OUT_F32)
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), rsrc, (int)(vb[bj] + roff), 0, AUX_NT);
@@ -257,16 +260,17 @@ __device__ __forceinline__ void store_acc_as(void *Cv, uint64_t coff, const floa
 
 // The output kind is uniform per launch: fp32 or the 16-bit type of the inputs (DT).
 // INTERIOR_PATH = false keeps only the predicated loops (general bodies: less code).
-template <int DT, bool INTERIOR_PATH, bool M16, int BM, int BN, typename Acc>
+template <int DT, bool INTERIOR_PATH, bool M16, int BM, int BN, int BI0 = 0, int BI1 = BM, int BJ0 = 0, int BJ1 = BN,
+          typename Acc>
 __device__ __forceinline__ void store_acc(const KArgs &g, uint64_t coff, uint32_t m0w, uint32_t n0w, uint32_t lane,
                                           const Acc (&acc)[BM][BN]) {
     constexpr int OUT16 = DT == 0 ? OUT_F16 : OUT_BF16;
     if (g.out_kind == OUT_F32) {
-        if (g.c_stream) store_acc_as<OUT_F32, INTERIOR_PATH, true, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
-        else store_acc_as<OUT_F32, INTERIOR_PATH, false, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+        if (g.c_stream) store_acc_as<OUT_F32, INTERIOR_PATH, true, M16, BM, BN, BI0, BI1, BJ0, BJ1>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+        else store_acc_as<OUT_F32, INTERIOR_PATH, false, M16, BM, BN, BI0, BI1, BJ0, BJ1>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
     } else {
         // 16-bit outputs are always streamed (the host never clears c_stream for them)
-        store_acc_as<OUT16, INTERIOR_PATH, true, M16, BM, BN>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
+        store_acc_as<OUT16, INTERIOR_PATH, true, M16, BM, BN, BI0, BI1, BJ0, BJ1>(g.C, coff, g.bias, g.ldc, g.M, g.N, m0w, n0w, lane, acc);
     }
 }
 

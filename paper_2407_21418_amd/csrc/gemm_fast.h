@@ -168,8 +168,17 @@ __device__ __forceinline__ bool k_part_exchange_blocks(const KArgs &g, uint32_t 
     return true;
 }
 
-template <int DT, int WM, int WN, int GM, int GN>
+// TEAMS = 2 ("ping-pong"): the workgroup has eight waves, two per SIMD, in two teams of four.  A team
+// is a complete GM x GN wave grid with an LDS ring of its own; the teams take alternate k-tiles of the
+// SAME output tile and add their partial sums through LDS at the end.  The workgroup moves in phases
+// separated by s_barrier: while one team reads fragments and runs the MFMAs of its current k-tile, the
+// other issues the LDS-DMA copies of a later one and waits for its next to land; then they swap.  A
+// wave is held up while its copy instructions are accepted (measured: about as long as the MFMAs of a
+// k-tile take), so with one wave per SIMD copy and MFMA time add up; with two teams the SIMD's other
+// wave computes meanwhile.
+template <int DT, int WM, int WN, int GM, int GN, int TEAMS = 1>
 struct UKernelFast {
+    static_assert(TEAMS == 1 || TEAMS == 2, "one team of four waves, or two");
     static constexpr int TK = 64;
     static constexpr int TM = GM * WM, TN = GN * WN;
     static constexpr bool M16 = (WM == 16);
@@ -202,7 +211,9 @@ struct UKernelFast {
                                                uint32_t stages_in, uint32_t t, uint32_t part) {
         const uint32_t tid = threadIdx.x;
         const uint32_t lane = tid & 63u;
-        const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const uint32_t wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const uint32_t team = TEAMS == 2 ? wave_all >> 2 : 0u;         // waves 0-3 / 4-7: one wave per SIMD each
+        const uint32_t wave = TEAMS == 2 ? wave_all & 3u : wave_all;   // position in the team's wave grid
         const uint32_t wave_m = wave / GN, wave_n = wave % GN;
         const uint32_t m0 = d.m0, n0 = d.n0;
         const uint32_t M = g.M, N = g.N, K = g.K;
@@ -214,6 +225,8 @@ struct UKernelFast {
         const uint32_t nk = g.k_parts > 1 ? (nk_all - kt0 < g.k_part_tiles ? nk_all - kt0 : g.k_part_tiles) : nk_all;
         uint32_t S = stages_in < 2 ? 2u : stages_in;
         if (S > (uint32_t)MAX_AHEAD + 2) S = MAX_AHEAD + 2;
+        unsigned char *const smem_all = smem;
+        if constexpr (TEAMS == 2) smem += team * S * STAGE_BYTES;      // this team's ring
 
         // ---- copy assignments ---------------------------------------------------------------
         // A instruction i of this wave fills LDS bytes [wave*A_WAVE_BYTES + i*1024, +1024) of the
@@ -262,7 +275,8 @@ struct UKernelFast {
         auto issue_impl = [&](uint32_t kt, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
             unsigned char *st = smem + (kt % S) * STAGE_BYTES;
-            const uint32_t k0 = (kt0 + kt) * TK;
+            // (two teams: kt counts this team's k-tiles, every other one of the workgroup's)
+            const uint32_t k0 = (TEAMS == 2 ? kt0 + team + 2 * kt : kt0 + kt) * TK;
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
             const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
             const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
@@ -303,7 +317,10 @@ struct UKernelFast {
             }
         };
         auto issue = [&](uint32_t kt) {
-            if (k_tail && kt0 + kt + 1 == nk_all) issue_impl(kt, std::true_type{});
+#ifdef FT_DEBUG_NO_COPY          // development: only the first copies are issued (the loop then measures MFMA + LDS alone)
+            if (kt >= 1) return;
+#endif
+            if (k_tail && (TEAMS == 2 ? kt0 + team + 2 * kt : kt0 + kt) + 1 == nk_all) issue_impl(kt, std::true_type{});
             else issue_impl(kt, std::false_type{});
         };
 
@@ -335,6 +352,7 @@ struct UKernelFast {
 #pragma unroll
                 for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
 
+        if constexpr (TEAMS == 1) {
         // ---- prologue: fill S-1 stages ------------------------------------------------------------
         FT_MARK(g, 1);
         for (uint32_t s = 0; s + 1 < S && s < nk; ++s) issue(s);
@@ -388,6 +406,109 @@ struct UKernelFast {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         FT_MARK(g, 7);
 #endif
+        } else {
+        // ---- two teams -------------------------------------------------------------------------------
+        // Team T works on k-tiles T, T+2, ...: its j-th is copied in "load" phases and consumed in
+        // "compute" phases that alternate, team 1 one phase behind team 0:
+        //   phase p, team T, q = p - T:  q even -> L(q/2): issue the copies of tile q/2 + S-1 (into the stage
+        //   that C(q/2 - 1) read in the phase before), then wait until tile q/2 has landed;
+        //   q odd -> C(q/2): fragments + MFMAs of tile q/2.  One s_barrier ends every phase: it publishes
+        //   the landed tile to the team and frees the stage just read.  Every wave runs every barrier.
+        const uint32_t n_mine = nk > team ? (nk - team + 1) / 2 : 0u;
+        const uint32_t n_team0 = (nk + 1) / 2;
+        FT_MARK(g, 1);
+        for (uint32_t s = 0; s + 1 < S && s < n_mine; ++s) issue(s);
+        FT_MARK(g, 2);
+        // Written as a straight-line loop per team (the accumulators must not pass through a branch:
+        // the compiler would keep two copies of them); team 1 starts one barrier late and the teams
+        // run spare barriers at the end so that both execute 2 * n_team0 + 1 of them.
+        if (team == 1) __builtin_amdgcn_s_barrier();
+        for (uint32_t j = 0; j < n_mine; ++j) {
+            if (j + S - 1 < n_mine) issue(j + S - 1);
+            const uint32_t newest = j + S - 1 < n_mine - 1 ? j + S - 1 : n_mine - 1;
+            wait_tiles<0>((int)(newest - j));
+            __builtin_amdgcn_s_barrier();
+#ifdef FT_TRACE
+            if (j == 0) FT_MARK(g, 3);
+            if (j == n_mine / 2) FT_MARK(g, 4);
+#endif
+            const uint32_t soff = (j % S) * STAGE_BYTES;
+            const uint32_t a_addr = fa_addr0 + soff;
+            uint32_t b_addr[BN];
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + soff;
+            u32x4 fa[2][BM];
+            u32x2 fb[2][BN][2];
+            read_step<0, 0>(a_addr, b_addr, fa, fb);
+            step<0>(a_addr, b_addr, fa, fb, acc);
+            __builtin_amdgcn_s_barrier();
+        }
+        for (uint32_t x = (team == 1 ? 1u : 0u) + 2 * n_mine; x < 2 * n_team0 + 1; ++x) __builtin_amdgcn_s_barrier();
+        FT_MARK(g, 5);
+        // ---- sum of the two teams' partial tiles through LDS (the rings are idle now) ---------------
+        // Wave w of one team and wave w of the other hold the same wave tile.  Each team finishes half of
+        // its accumulator blocks (team 1 the upper half of the block rows, or of the block columns when
+        // there is one row) and hands the other half over; a wave tile of a single block is finished by
+        // team 0 alone.  Layout of a handed-over half: [wave][block][register][lane] floats.
+        constexpr int NE = M16 ? 4 : 16;
+        constexpr bool SPLIT_M = BM >= 2, SPLIT_N = !SPLIT_M && BN >= 2, SPLIT = SPLIT_M || SPLIT_N;
+        constexpr int NB_GIVE = SPLIT ? BM * BN / 2 : BM * BN;       // blocks a wave hands over (team 0: none if !SPLIT)
+        constexpr int XW = NB_GIVE * NE * 64;                        // floats per wave
+        static_assert(8 * XW * 4 <= 2 * 2 * STAGE_BYTES, "the exchange fits the smallest pair of rings");
+        float *const xmine = reinterpret_cast<float *>(smem_all) + (team * 4 + wave) * XW + lane;          // what I give
+        const float *const xtheirs = reinterpret_cast<const float *>(smem_all) + ((1 - team) * 4 + wave) * XW + lane;
+        auto owned_by_1 = [](int bi, int bj) { return SPLIT_M ? bi >= BM / 2 : (SPLIT_N ? bj >= BN / 2 : false); };
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) {
+                // a block changes hands when its owner is the other team (uniform per wave); the blocks a
+                // team receives are numbered in (bi, bj) order
+                const bool to1 = owned_by_1(bi, bj);
+                if (to1 ? team == 0 : team == 1) {
+                    const int slot = idx_of(bi, bj, to1);
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) xmine[(slot * NE + e) * 64] = acc[bi][bj][e];
+                }
+            }
+        __syncthreads();
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) {
+                const bool mine = owned_by_1(bi, bj) ? team == 1 : team == 0;
+                if (mine) {
+                    const int slot = idx_of(bi, bj, owned_by_1(bi, bj));
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) acc[bi][bj][e] += xtheirs[(slot * NE + e) * 64];
+                }
+            }
+        FT_MARK(g, 6);
+        const uint64_t coff = (uint64_t)d.batch * g.strideC;
+        const uint32_t m0w = m0 + wave_m * WM, n0w = n0 + wave_n * WN;
+        if constexpr (SPLIT_M) {
+            if (team == 0) store_acc<DT, true, M16, BM, BN, 0, BM / 2, 0, BN>(g, coff, m0w, n0w, lane, acc);
+            else store_acc<DT, true, M16, BM, BN, BM / 2, BM, 0, BN>(g, coff, m0w, n0w, lane, acc);
+        } else if constexpr (SPLIT_N) {
+            if (team == 0) store_acc<DT, true, M16, BM, BN, 0, BM, 0, BN / 2>(g, coff, m0w, n0w, lane, acc);
+            else store_acc<DT, true, M16, BM, BN, 0, BM, BN / 2, BN>(g, coff, m0w, n0w, lane, acc);
+        } else {
+            if (team == 0) store_acc<DT, true, M16, BM, BN>(g, coff, m0w, n0w, lane, acc);
+        }
+#ifdef FT_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        FT_MARK(g, 7);
+#endif
+        }
+    }
+
+    // Position of block (bi, bj) among the blocks its receiving team gets, in (bi, bj) order: blocks owned
+    // by team 1 (to_team1) count from the first such block, the others likewise.
+    static constexpr int idx_of(int bi, int bj, bool to_team1) {
+        constexpr bool SM = BM >= 2, SN = !SM && BN >= 2;
+        if (SM) return to_team1 ? (bi - BM / 2) * BN + bj : bi * BN + bj;
+        if (SN) return to_team1 ? bj - BN / 2 : bj;
+        return bi * BN + bj;
     }
 
     // LDS reads of the A and B fragments of k-step ks into fragment set buf.  Row offsets of the
@@ -415,6 +536,10 @@ struct UKernelFast {
     __device__ static __forceinline__ void step(uint32_t a_addr, const uint32_t (&b_addr)[BN], u32x4 (&fa)[2][BM],
                                                 u32x2 (&fb)[2][BN][2], Acc (&acc)[BM][BN]) {
         constexpr int buf = ks & 1;
+#ifdef FT_DEBUG_NO_MFMA          // development: copies and barriers only
+        if constexpr (ks == 0) wait_frag<0>(fa[0], fb[0]);
+        return;
+#endif
         if constexpr (ks + 1 < KS) {
             read_step<ks + 1, buf ^ 1>(a_addr, b_addr, fa, fb);
             wait_frag<NR>(fa[buf], fb[buf]);

@@ -40,6 +40,7 @@ void hw_defaults(ft_hw_model *h) {
     h->num_xcds = 8;
     h->part_exchange_clk = 2000;
     h->part_exchange_bytes_per_clk = 16;
+    h->phase_latency_clk = 150;
 }
 
 void tuning_defaults(ft_tuning *t) {
@@ -55,6 +56,7 @@ void tuning_defaults(ft_tuning *t) {
     t->k_parts_max = 8;
     t->k_part_min_tiles = 8;
     t->second_axis_strips = 0;
+    t->two_team_bodies = 0;
 }
 
 struct Gemm {                // GEMM view of an operator: static extents (0 = dynamic)
@@ -75,6 +77,9 @@ Gemm static_view(const ft_op_desc &d) {
 //       K_mem = max(t_ce, t_g, t_s) + t_l / residents
 //   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
 //       K_mem = t_ce + solo_copy_exposed_pct % of t_g + t_l
+//   two teams (gk = 2, eight waves): a SIMD holds one wave of each team; while one runs the MFMAs of its
+//       k-tile the other issues copies, one s_barrier per k-tile:
+//       K_mem = max(t_c, t_g, t_s) + phase_latency_clk * nk / residents
 // exchange_clk: a fixed time added to t_l: the round trips of a workgroup that hands its partial
 // tile to the others of a reduce-axis split.
 void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk, uint32_t tk, uint64_t kref,
@@ -85,9 +90,19 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk
     const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * out_bytes;                // data_r + data_w
     const u128 sbytes = (u128)(tm + tn) * kref * ELT + (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
     const u128 nk = ceil_div(kref, tk);
-    const u128 nk_w = ceil_div((uint64_t)nk, gk);
     const u128 r = residents >= 2 ? residents : 1;
     const u128 ed = 100;
+    if (gk == 2) {
+        // over the common denominator F * G * S * r
+        const u128 c2 = flops * G * S * r;
+        const u128 g2 = gbytes * F * S * r;
+        const u128 s2 = sbytes * F * G * r;
+        const u128 l2 = ((u128)hw.phase_latency_clk * nk + exchange_clk) * F * G * S;
+        *num = c2;
+        *den = std::max(c2, std::max(g2, s2)) + l2;
+        return;
+    }
+    const u128 nk_w = ceil_div((uint64_t)nk, gk);
     // everything over the common denominator F * G * S * nk * r * ed
     const u128 c = flops * G * S * nk * r * ed;
     const u128 ce = flops * G * S * gk * nk_w * r * ed;
@@ -326,7 +341,7 @@ bool split_allowed(const Program &p, const ft_ukset &set, uint64_t K, uint32_t k
     uint32_t per_cu = set.t.zeta;
     for (uint32_t i = 0; i < p.nparts; ++i) {
         const ft_ukernel_info &u = set.uk[p.part[i].id];
-        if (u.acc_regs > FT_KPART_ACC_MAX) return false;
+        if (u.acc_regs > FT_KPART_ACC_MAX || u.gk == 2) return false;   // (two teams already split the reduce axis)
         per_cu = std::min(per_cu, u.max_wg_per_cu);
     }
     if (p.tiles * k_parts > (uint64_t)set.hw.num_cus * per_cu) return false;
@@ -347,7 +362,8 @@ uint32_t strip_choices(const ft_ukernel_info &u, const ft_ukset &set, uint64_t W
     if (n_full < 1 || rem == 0) return 0;
     std::vector<const ft_ukernel_info *> c;
     for (const ft_ukernel_info &v : set.uk)
-        if (ext(v, tau) == ext(u, tau) && ext(v, 1 - tau) < e && ceil_by(rem, ext(v, 1 - tau)) < e) c.push_back(&v);
+        if (ext(v, tau) == ext(u, tau) && ext(v, 1 - tau) < e && ceil_by(rem, ext(v, 1 - tau)) < e &&
+            (v.gk == 2) == (u.gk == 2)) c.push_back(&v);
     std::stable_sort(c.begin(), c.end(), [&](const ft_ukernel_info *a, const ft_ukernel_info *b) {
         if (ext(*a, 1 - tau) != ext(*b, 1 - tau)) return ext(*a, 1 - tau) > ext(*b, 1 - tau);
         return a->id < b->id;
@@ -400,7 +416,8 @@ void build_pool(const ft_ukset &set, uint64_t Hp, uint32_t tau, std::vector<Prog
             bool found = false;
             for (size_t i2 = 0; i2 < n; ++i2) {
                 uint64_t e2 = ext(set.uk[i2], tau);
-                if (e2 != e1 && rem % e2 == 0) {
+                // (one launch has one workgroup size: two-team uKernels pair with two-team uKernels)
+                if (e2 != e1 && rem % e2 == 0 && (set.uk[i1].gk == 2) == (set.uk[i2].gk == 2)) {
                     Program p{};
                     p.nparts = 2;
                     p.part[0] = {(uint32_t)i1, (uint32_t)n1};
@@ -633,7 +650,9 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
     static const uint32_t sizes[4] = {16, 32, 64, 128};
     // wave grids over (rows, columns, reduce axis); the split-k grid lets each wave own the whole
     // tile and a quarter of k (accumulator tiles of 1024..4096 elements only)
-    static const uint32_t grids[4][3] = {{1, 4, 1}, {2, 2, 1}, {4, 1, 1}, {1, 1, 4}};
+    // (gk = 2: the standard grids again as two teams of four waves that take alternate k-tiles, Matmul
+    // and Conv2d only: grouped batched launches run workgroups of four waves)
+    static const uint32_t grids[7][3] = {{1, 4, 1}, {2, 2, 1}, {4, 1, 1}, {1, 1, 4}, {1, 4, 2}, {2, 2, 2}, {4, 1, 2}};
     for (uint32_t wm : sizes)
         for (uint32_t wn : sizes) {
             uint32_t mfma;
@@ -643,14 +662,16 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
             for (auto &g : grids) {
                 uint32_t gm = g[0], gn = g[1], gk = g[2], tk = FT_TK;
                 uint32_t tm = gm * wm, tn = gn * wn;
-                if (gk > 1 && (wm * wn < 256 || wm * wn > 4096)) continue;
+                if (gk == 4 && (wm * wn < 256 || wm * wn > 4096)) continue;
+                if (gk == 2 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM)) continue;
                 if (ft_body_code(wm, wn, gm, gn, gk) < 0) continue;      // no compiled body
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
                 if (sv.n && ceil_by(sv.n, GRANULE) % tn) continue;
                 uint32_t acc = wm * wn / h.wave_size;
                 uint32_t regs = acc + t.rest_regs;
-                if (regs > h.regs_per_lane) continue;                    // Eq. 4 at block.bound = 1
+                const uint32_t waves_per_simd = gk == 2 ? 2 : 1;
+                if (regs * waves_per_simd > h.regs_per_lane) continue;   // Eq. 4 at block.bound = 1
                 // registers are granted in power-of-two fractions of the file (128, 256, 512)
                 uint32_t budget = h.regs_per_lane / 4;
                 while (budget < regs) budget *= 2;
@@ -660,6 +681,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 // alone on the CU anyway gains nothing, the loop is bound by fetch bandwidth)
                 // (a split-k workgroup keeps one ring per wave and is meant to own the CU's LDS)
                 uint32_t stage_bytes = (tm + tn) * tk * ELT;
+                // (two teams: one ring per team; the workgroup owns the CU's LDS as well)
                 uint32_t stages = gk == 1 ? (h.lds_bytes_per_cu / t.zeta) / stage_bytes
                                           : h.lds_bytes_per_cu / (gk * stage_bytes);
                 stages = std::max(MIN_STAGES, std::min(MAX_STAGES, stages));
@@ -675,8 +697,8 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 u.tm = tm; u.tn = tn; u.tk = tk; u.wm = wm; u.wn = wn; u.gm = gm; u.gn = gn; u.gk = gk;
                 u.mfma = mfma; u.stages = stages; u.lds_bytes = lds; u.acc_regs = acc; u.regs = regs;
                 u.reg_budget = budget;
-                u.max_wg_per_cu = std::min(std::min(h.lds_bytes_per_cu / lds, h.regs_per_lane / budget),
-                                           h.max_waves_per_simd);
+                u.max_wg_per_cu = std::min(std::min(h.lds_bytes_per_cu / lds, h.regs_per_lane / budget / waves_per_simd),
+                                           h.max_waves_per_simd / waves_per_simd);
                 u.cmr_q20 = (uint64_t)((cn << QBITS) / cd);
                 compute_eff(tm, tn, gm, gn, gk, tk, kref, 2, out_bytes, h, &cn, &cd);
                 u.cmr_shared_q20 = (uint64_t)((cn << QBITS) / cd);
@@ -712,7 +734,8 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
         if (a.tn != b.tn) return a.tn > b.tn;
         if (a.tk != b.tk) return a.tk > b.tk;
         if (a.wm != b.wm) return a.wm > b.wm;
-        return a.wn > b.wn;
+        if (a.wn != b.wn) return a.wn > b.wn;
+        return a.gk < b.gk;
     });
     set->cap_q = 0;
     for (size_t i = 0; i < set->uk.size(); ++i) {
@@ -816,6 +839,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     for (int i = 0; i < 4; ++i) { pl->slot_id[i] = 0; pl->slot_code[i] = 0; pl->slot_stages[i] = MIN_STAGES; }
     pl->n_slots = 0;
     pl->table_order = false;
+    pl->two_teams = false;
     for (int i = 0; i < 2; ++i) {
         pl->slot_first[i] = 0; pl->slot_rows[i] = pl->slot_cols[i] = pl->slot_group[i] = 1;
         pl->slot_m0[i] = pl->slot_n0[i] = pl->slot_tm[i] = pl->slot_tn[i] = 0;
@@ -857,6 +881,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         if (forced->count2) {
             if (forced->k2 >= set->uk.size() || forced->k2 == forced->k1) { delete pl; return FT_ERR_INVALID_ARG; }
             total += (uint64_t)forced->count2 * ext(set->uk[forced->k2], tau);
+            if ((set->uk[forced->k1].gk == 2) != (set->uk[forced->k2].gk == 2)) { delete pl; return FT_ERR_INVALID_ARG; }
             best.nparts = 2;
             best.part[1] = {forced->k2, forced->count2};
             best.k2 = forced->k2;
@@ -868,7 +893,8 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         if (forced->k_parts > 1) {
             if (forced->k_parts > 64) { delete pl; return FT_ERR_INVALID_ARG; }
             bool room = true;
-            for (uint32_t i = 0; i < best.nparts; ++i) room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX;
+            for (uint32_t i = 0; i < best.nparts; ++i)
+                room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX && set->uk[best.part[i].id].gk != 2;
             if (room) {
                 const uint64_t nk = std::max<uint64_t>(ceil_div(r.K, FT_TK), 1);
                 const uint64_t per = ceil_div(nk, std::min<uint64_t>(forced->k_parts, nk));
@@ -954,6 +980,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     for (uint32_t i = 0; i < 2; ++i) { s.strip_ukernel_id[i] = UINT32_MAX; s.strip_tiles[i] = 0; s.main_tiles[i] = 0; }
     // slots 0, 1: the parts (the launch order is computed on their tile grids); 2, 3: strips
     auto set_slot = [&](uint32_t slot, const ft_ukernel_info &u) {
+        if (u.gk == 2) pl->two_teams = true;
         pl->slot_id[slot] = u.id;
         pl->slot_code[slot] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn, u.gk);
         pl->slot_stages[slot] = u.stages;

@@ -5,7 +5,10 @@
 #define FT_CAT_(a, b, c, d) a##b##c##d
 #define FT_CAT(a, b, c, d) FT_CAT_(a, b, c, d)
 #if defined(FT_DT) && defined(FT_CLASS)
-#if defined(FT_GROUPED) && defined(FT_GENERIC)
+#if defined(FT_PP)
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _pp_c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _pp_c, FT_CLASS)
+#elif defined(FT_GROUPED) && defined(FT_GENERIC)
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _grp_c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _grp_c, FT_CLASS)
 #elif defined(FT_GROUPED)
@@ -27,6 +30,10 @@ int ft_launch_dt0_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c0(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_pp_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_pp_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_pp_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_pp_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt0_gen_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt0_gen_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_gen_c1(const ftk::KArgs *, uint32_t, void *);
