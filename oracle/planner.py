@@ -39,7 +39,7 @@ def default_hw():
                 mfma_flops_per_clk_per_cu=4096, bw_global_bytes_per_clk_per_cu=64,
                 bw_lds_bytes_per_clk_per_cu=256, ktile_latency_clk=400, solo_copy_exposed_pct=50,
                 part_exchange_clk=2000,
-                part_exchange_bytes_per_clk=16,
+                part_exchange_bytes_per_clk=16, phase_latency_clk=150,
                 hbm_gbytes_per_s=8000, num_xcds=8)
 
 
@@ -50,7 +50,7 @@ def default_tuning():
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
                 zeta=2, rest_regs=72, psi_num=1, psi_den=64, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT,
-                k_parts_max=8, k_part_min_tiles=8, second_axis_strips=0)
+                k_parts_max=8, k_part_min_tiles=8, second_axis_strips=0, two_team_bodies=0)
 
 
 # --------------------------------------------------------------------------------------
@@ -216,8 +216,12 @@ def wave_tiles():
 
 
 # four wave64 per workgroup, one per SIMD, arranged over (rows, columns, reduce axis); in the
-# split-k grid every wave owns the whole tile and a quarter of k
-WAVE_GRIDS = ((1, 4, 1), (2, 2, 1), (4, 1, 1), (1, 1, 4))
+# split-k grid every wave owns the whole tile and a quarter of k.  gk = 2: the standard grids again
+# with eight waves, two teams of four (two waves per SIMD) that take alternate k-tiles of the tile
+# (tuning two_team_bodies; Matmul and Conv2d): while one team runs its MFMAs the other copies.
+WAVE_GRIDS = ((1, 4, 1), (2, 2, 1), (4, 1, 1), (1, 1, 4), (1, 4, 2), (2, 2, 2), (4, 1, 2))
+TWO_TEAM_STAGE_MAX = 40960                  # both teams' rings of two stages fit the LDS
+TWO_TEAM_ACC_MAX = 64                       # accumulator registers per lane of a two-team wave
 TK_CHOICES = (64,)                          # 64 16-bit elements = one 128-byte line
 MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
@@ -236,6 +240,9 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
       * residents == 1: the one wave of a SIMD issues its global->LDS copies and its MFMAs
         itself; a fraction solo_copy_exposed_pct of the copy time is not hidden:
             K_mem = t_ce + exposed * t_g + t_l
+      * two teams (gk == 2): a SIMD holds one wave of each team, copies and MFMAs of the two overlap
+        and every k-tile ends with one barrier:
+            K_mem = max(t_c, t_g, t_s) + phase_latency_clk * nk / residents
     exchange_clk: a fixed time added to K_mem (divided by residents like t_l): the round trips of
     a workgroup that hands its partial tile to the others of a reduce-axis split.
     Returns (numerator, denominator) of the exact ratio."""
@@ -244,8 +251,12 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
     gbytes = (tm + tn) * k_ref * ELT + tm * tn * out_bytes    # data_r + data_w
     sbytes = (tm + tn) * k_ref * ELT + k_ref * ELT * (tm * gn + tn * gm)   # data_tw + data_tr
     nk = ceil_div(k_ref, tk)
-    nk_w = ceil_div(nk, gk)
     r = residents if residents >= 2 else 1
+    if gk == 2:
+        # over the common denominator F * G * S * r
+        c2 = flops * G * S * r
+        return c2, max(c2, gbytes * F * S * r, sbytes * F * G * r) + (hw["phase_latency_clk"] * nk + exchange_clk) * F * G * S
+    nk_w = ceil_div(nk, gk)
     ed = 100
     # everything over the common denominator F * G * S * nk * r * ed
     c = flops * G * S * nk * r * ed
@@ -322,17 +333,21 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     t = t or default_tuning()
     m_s, n_s, _ = op.gemm_static()
     k_ref = op.k_ref()
-    waves_per_simd = 1                      # 4 waves on 4 SIMDs
     shapes = workload_shapes(op)
     cand = []
     kept = []
     psi_ok = []
     for wm, wn, mfma in wave_tiles():
         for gm, gn, gk in WAVE_GRIDS:
-            if gk > 1 and not (256 <= wm * wn <= 4096):
+            if gk == 4 and not (256 <= wm * wn <= 4096):
                 continue
+            if gk == 2 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM):
+                continue
+            waves_per_simd = 2 if gk == 2 else 1    # 4 waves on 4 SIMDs, or 8
             for tk in TK_CHOICES:
                 tm, tn = gm * wm, gn * wn
+                if gk == 2 and ((tm + tn) * tk * ELT > TWO_TEAM_STAGE_MAX or wm * wn // 64 > TWO_TEAM_ACC_MAX):
+                    continue
                 # static space axes are divided evenly (after rounding to the MFMA granule,
                 # the gfx950 form of "factors of the neighbours")
                 if m_s > 0 and ceil_by(m_s, GRANULE) % tm:
@@ -358,8 +373,8 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 budget = reg_budget(regs, hw)
                 cn, cd = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, out_bytes=op.out_bytes)
                 psi_ok.append(cn * t["psi_den"] >= t["psi_num"] * cd)          # Eq. 6
-                cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget,
-                          hw["max_waves_per_simd"])
+                cap = min(hw["lds_bytes_per_cu"] // lds, hw["regs_per_lane"] // budget // waves_per_simd,
+                          hw["max_waves_per_simd"] // waves_per_simd)
                 cn2, cd2 = compute_eff(tm, tn, gm, gn, k_ref, hw, gk, tk, residents=2, out_bytes=op.out_bytes)
                 cand.append(UKernel(tm, tn, tk, wm, wn, gm, gn, gk, mfma, stages, lds, acc, regs,
                                     budget, cap, (cn << Q) // cd, (cn2 << Q) // cd2))
@@ -372,7 +387,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
         cand, kept = [u for u, ok in zip(cand, psi_ok) if ok], [k for k, ok in zip(kept, psi_ok) if ok]
     if any(kept):
         cand = [u for u, k in zip(cand, kept) if k]
-    cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn))
+    cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn, u.gk))
     for i, u in enumerate(cand):
         u.id = i
     return cand
@@ -460,9 +475,10 @@ def _ext(u: UKernel, axis):
     return u.tm if axis == 0 else u.tn
 
 
-def build_pool(extents, Hp):
+def build_pool(extents, Hp, kinds=None):
     """Alg. 2 over the main-axis extents of the uKernel set (extents[i] belongs to uKernel
-    i) on the main-axis size Hp.  For each K1 in set order: a single-uKernel program when
+    i) on the main-axis size Hp.  kinds[i], if given, is the workgroup size class of uKernel i: one
+    launch has one workgroup size, so K2 must be of K1's kind.  For each K1 in set order: a single-uKernel program when
     K1 divides Hp; otherwise Hp = Num1*K1 + Num2*K2 with a second uKernel K2.
     Reading: on gfx950 every extent is a multiple of the 16-row granule, so the *first*
     success of the printed search (smallest Num1) is always Num1 = 1 followed by a long run
@@ -478,7 +494,7 @@ def build_pool(extents, Hp):
         for n1 in range(Hp // e1, 0, -1):
             rem = Hp - n1 * e1
             found = [(i2, rem // e2) for i2, e2 in enumerate(extents)
-                     if e2 != e1 and rem % e2 == 0]
+                     if e2 != e1 and rem % e2 == 0 and (kinds is None or kinds[i2] == kinds[i1])]
             if found:
                 pool.extend([(i1, n1), f] for f in found)
                 break
@@ -504,8 +520,8 @@ def split_allowed(parts, uks, K, k_parts, t, hw, tiles):
         return True
     if k_parts > t.get("k_parts_max", 1):
         return False
-    if any(uks[uid].acc_regs > KPART_ACC_MAX for uid, _ in parts):
-        return False
+    if any(uks[uid].acc_regs > KPART_ACC_MAX or uks[uid].gk == 2 for uid, _ in parts):
+        return False                                   # (two teams already split the reduce axis)
     per_cu = min([t["zeta"]] + [uks[uid].max_wg_per_cu for uid, _ in parts])
     if tiles * k_parts > hw["num_cus"] * per_cu:
         return False
@@ -532,7 +548,8 @@ def strip_choices(u, uks, Wp, tau):
     if n_full < 1 or rem == 0:
         return []
     cands = [v for v in uks
-             if _ext(v, tau) == _ext(u, tau) and _ext(v, 1 - tau) < e and ceil_by(rem, _ext(v, 1 - tau)) < e]
+             if _ext(v, tau) == _ext(u, tau) and _ext(v, 1 - tau) < e and ceil_by(rem, _ext(v, 1 - tau)) < e
+             and (v.gk == 2) == (u.gk == 2)]
     cands.sort(key=lambda v: (-_ext(v, 1 - tau), v.id))
     return [(v.id, n_full, ceil_div(rem, _ext(v, 1 - tau))) for v in cands[:STRIP_CHOICES]]
 
@@ -739,7 +756,7 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         pl.pool_size, pl.level = 1, 0 if prog.in_bound else 1
     else:
         Hp = ceil_by(M if tau == 0 else N, GRANULE)
-        covers = build_pool([_ext(u, tau) for u in uks], Hp)
+        covers = build_pool([_ext(u, tau) for u in uks], Hp, kinds=[u.gk == 2 for u in uks])
         if not covers:
             # Alg. 2 found nothing (the main axis is shorter than every extent the static
             # axes admit): pad it up to the uKernel with the smallest main-axis extent

@@ -50,12 +50,27 @@ OPS = {
 }
 
 
-@pytest.mark.parametrize("name", sorted(OPS))
+def teams_on():
+    lt = ft.ft_tuning_default()
+    lt.two_team_bodies = 1
+    return lt, dict(P.default_tuning(), two_team_bodies=1)
+
+
+TEAM_OPS = ["dense768+teams", "dense3072+teams", "dense768k3072+teams", "llm4096+teams", "conv+teams", "tiny_k+teams", "qk+teams"]
+
+
+@pytest.mark.parametrize("name", sorted(OPS) + TEAM_OPS)
 def test_ukernel_table_matches_oracle(name):
+    lib_t, ora_t = (None, None)
+    if name.endswith("+teams"):
+        name = name[:-len("+teams")]
+        lib_t, ora_t = teams_on()
     op = OPS[name]
-    want = P.derive_ukernels(op)
+    want = P.derive_ukernels(op, t=ora_t)
     lop = to_lib_op(op)
-    s = ft.ft_ukernels_derive(lop)
+    s = ft.ft_ukernels_derive(lop, None, lib_t)
+    if lib_t is not None:       # two-team uKernels are derived for Matmul and Conv2d, never for batched Matmul
+        assert any(w.gk == 2 for w in want) == (op.kind != P.OP_BMM)
     assert ft.ft_ukset_size(s) == len(want)
     for i, w in enumerate(want):
         g = ft.ft_ukset_get(s, i)
@@ -102,12 +117,15 @@ def strips_on():
 
 
 @pytest.mark.parametrize("mode", [P.PLAN_PATCHWORK, P.PLAN_PAD_BASELINE])
-@pytest.mark.parametrize("name", sorted(OPS) + ["qk_b768+strips"])
+@pytest.mark.parametrize("name", sorted(OPS) + ["qk_b768+strips"] + TEAM_OPS)
 def test_plans_bit_identical_to_oracle(name, mode):
     lib_t, ora_t = (None, None)
     if name.endswith("+strips"):
         name = name[:-len("+strips")]
         lib_t, ora_t = strips_on()
+    if name.endswith("+teams"):
+        name = name[:-len("+teams")]
+        lib_t, ora_t = teams_on()
     op = OPS[name]
     uks = P.derive_ukernels(op, t=ora_t)
     lop = to_lib_op(op)
