@@ -116,7 +116,7 @@ typedef struct ft_tuning {
      * standard wave grids again with EIGHT waves, two teams of four that take alternate k-tiles of
      * the same tile, so that one team's copies overlap the other's MFMAs (gk = 2 in
      * ft_ukernel_info).  Matmul and Conv2d.                                                     */
-    uint32_t two_team_bodies;                       /* 1: derive them, 0: four-wave bodies only (default) */
+    uint32_t two_team_bodies;                       /* 1: derive them (default), 0: four-wave bodies only */
 } ft_tuning;
 enum { FT_SIA_LINEAR = 0, FT_SIA_PRODUCT = 1 };
 

@@ -50,7 +50,7 @@ def default_tuning():
     return dict(eps_min_pm=500, eps_max_pm=950, eps_step_pm=10,
                 lam_max_pm=950, lam_min_pm=900, lam_step_pm=1,
                 zeta=2, rest_regs=72, psi_num=1, psi_den=64, c0=1, c1=1, c2=1, sia_form=SIA_PRODUCT,
-                k_parts_max=8, k_part_min_tiles=8, second_axis_strips=0, two_team_bodies=0)
+                k_parts_max=8, k_part_min_tiles=8, second_axis_strips=0, two_team_bodies=1)
 
 
 # --------------------------------------------------------------------------------------
@@ -341,8 +341,8 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
         for gm, gn, gk in WAVE_GRIDS:
             if gk == 4 and not (256 <= wm * wn <= 4096):
                 continue
-            if gk == 2 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM):
-                continue
+            if gk == 2 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM or ceil_div(k_ref, TK_CHOICES[0]) < 4):
+                continue                            # (each team wants at least two k-tiles)
             waves_per_simd = 2 if gk == 2 else 1    # 4 waves on 4 SIMDs, or 8
             for tk in TK_CHOICES:
                 tm, tn = gm * wm, gn * wn

@@ -56,7 +56,7 @@ void tuning_defaults(ft_tuning *t) {
     t->k_parts_max = 8;
     t->k_part_min_tiles = 8;
     t->second_axis_strips = 0;
-    t->two_team_bodies = 0;
+    t->two_team_bodies = 1;
 }
 
 struct Gemm {                // GEMM view of an operator: static extents (0 = dynamic)
@@ -663,7 +663,7 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
                 uint32_t gm = g[0], gn = g[1], gk = g[2], tk = FT_TK;
                 uint32_t tm = gm * wm, tn = gn * wn;
                 if (gk == 4 && (wm * wn < 256 || wm * wn > 4096)) continue;
-                if (gk == 2 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM)) continue;
+                if (gk == 2 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM || ceil_div(kref, FT_TK) < 4)) continue;   // (each team wants at least two k-tiles)
                 if (ft_body_code(wm, wn, gm, gn, gk) < 0) continue;      // no compiled body
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;

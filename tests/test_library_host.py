@@ -69,8 +69,8 @@ def test_ukernel_table_matches_oracle(name):
     want = P.derive_ukernels(op, t=ora_t)
     lop = to_lib_op(op)
     s = ft.ft_ukernels_derive(lop, None, lib_t)
-    if lib_t is not None:       # two-team uKernels are derived for Matmul and Conv2d, never for batched Matmul
-        assert any(w.gk == 2 for w in want) == (op.kind != P.OP_BMM)
+    if lib_t is not None:       # two-team uKernels: Matmul and Conv2d with at least four k-tiles, never batched Matmul
+        assert any(w.gk == 2 for w in want) == (op.kind != P.OP_BMM and op.k_ref() > 192)
     assert ft.ft_ukset_size(s) == len(want)
     for i, w in enumerate(want):
         g = ft.ft_ukset_get(s, i)
@@ -231,7 +231,7 @@ def test_pool_scores_match_oracle(name):
             continue
         tau = P.main_axis(op, M, N)
         Hp = P.ceil_by(M if tau == 0 else N, 16)
-        want = P.build_pool([u.tm if tau == 0 else u.tn for u in uks], Hp)
+        want = P.build_pool([u.tm if tau == 0 else u.tn for u in uks], Hp, kinds=[u.gk == 2 for u in uks])
         got = ft.ft_plan_pool(lop, s, ft.ft_shape(**kw))
         assert len(got) == len(want)
         for g, parts in zip(got, want):

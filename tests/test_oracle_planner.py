@@ -349,7 +349,7 @@ def test_sia_is_the_weighted_sum_and_top1_is_max():
     cap = P.cmr_cap(uks)
     shape = (1, 528, 3072, 768)
     pool = [P.evaluate(p, uks, 1, 528, 3072, 0, hw, t2, cap)
-            for p in P.build_pool([u.tm for u in uks], 528)]
+            for p in P.build_pool([u.tm for u in uks], 528, kinds=[u.gk == 2 for u in uks])]
     for p in pool:
         assert p.sia_q == 3 * p.cmr_q + 5 * p.pad_q + 7 * p.occ_q
         assert 0 <= p.cmr_q <= 1 << 20 and 0 < p.pad_q <= 1 << 20 and 0 < p.occ_q <= 1 << 20
@@ -398,7 +398,7 @@ def test_part_tiles_and_split_rules():
     if big.acc_regs > P.KPART_ACC_MAX:
         assert not P.split_allowed([(big.id, 1)], uks, 3072, 2, t, hw, 1)
     # a uKernel that owns its CU (split-k wave grid) offers one slot per CU
-    solo = next(u for u in uks if u.max_wg_per_cu == 1 and u.acc_regs <= P.KPART_ACC_MAX)
+    solo = next(u for u in uks if u.gk == 4 and u.max_wg_per_cu == 1 and u.acc_regs <= P.KPART_ACC_MAX)
     assert P.split_allowed([(solo.id, 1)], uks, 3072, 2, t, hw, 128)
     assert not P.split_allowed([(solo.id, 1)], uks, 3072, 2, t, hw, 129)
 
@@ -423,7 +423,7 @@ def test_split_program_counts_workgroups():
     assert split.sia_q == (((split.cmr_q * split.pad_q) >> 20) * split.occ_q) >> 20
 
 
-@pytest.mark.parametrize("M,N,K,expect_split", [(1600, 768, 3072, True), (1600, 768, 768, False),
+@pytest.mark.parametrize("M,N,K,expect_split", [(528, 768, 3072, True), (1600, 768, 768, False),
                                                 (16, 4096, 4096, True), (8192, 4096, 4096, False)])
 def test_plans_split_only_where_the_device_is_underfilled(M, N, K, expect_split):
     hw, t = P.default_hw(), P.default_tuning()
@@ -526,7 +526,7 @@ def test_every_strip_variant_is_an_exact_cover_and_pads_no_more():
     checked = 0
     for L in (33, 100, 141, 257):
         Hp = P.ceil_by(L, 16)
-        for parts in P.build_pool([u.tm for u in uks], Hp)[::7]:
+        for parts in P.build_pool([u.tm for u in uks], Hp, kinds=[u.gk == 2 for u in uks])[::7]:
             whole = P.evaluate(parts, uks, 2, L, L, 0, hw, t, cap)
             for strips in P.strip_variants(parts, uks, Hp, 0):
                 p = P.evaluate(parts, uks, 2, L, L, 0, hw, t, cap, strips=strips)
