@@ -103,7 +103,7 @@ def test_permutation_matrix_stays_bit_exact_when_split(dtype):
             continue
         plan = ft.ft_plan_create(op, s, ft.ft_shape(m=n), ft.FT_PLAN_FORCED,
                                  ft.ft_forced_program(k1=i, count1=n // u.tm, k_parts=3))
-        assert ft.ft_plan_stats_get(plan).k_parts == (3 if u.acc_regs <= P.KPART_ACC_MAX else 1)
+        assert ft.ft_plan_stats_get(plan).k_parts == (3 if u.acc_regs <= P.KPART_ACC_MAX and u.gk != 2 else 1)
         got = run(plan, A, B, n * N).reshape(n, N)
         assert np.array_equal(got, want), (u.tm, u.tn, u.wm, u.wn)
 
@@ -152,7 +152,7 @@ def test_split_plan_through_the_timing_entry_points_and_a_graph():
     """Back-to-back launches of one split plan on rotating buffers, eagerly and as a replayed HIP
     graph (the arrival counters are reset by the kernel itself, no memset node): every buffer set
     holds the same bits as a single eager launch."""
-    M, N, K = 1600, 768, 3072
+    M, N, K = 528, 768, 3072
     p = si.config1_problem(M, N, K)
     op = matmul_op(N, K, ft.FT_F16)
     s = ft.ft_ukernels_derive(op)
@@ -181,7 +181,7 @@ def test_relaunch_with_other_inputs_sees_no_stale_partials():
     """The workspace slabs are reused by every launch of a plan: launches with different operands,
     back to back on one stream without host synchronisation in between, must each give their own
     result (a partial tile left over from the previous launch, in any cache, would show)."""
-    M, N, K = 1600, 768, 3072
+    M, N, K = 528, 768, 3072
     op = matmul_op(N, K, ft.FT_F16)
     s = ft.ft_ukernels_derive(op)
     plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
