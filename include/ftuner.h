@@ -277,7 +277,12 @@ typedef struct ft_plan ft_plan;
  * be launched any number of times.  A plan with k_parts > 1 also owns workspace_bytes of device
  * memory for the fp32 partial tiles plus 16 bytes of counters per tile: launches of one such plan
  * must be ordered (same stream, or otherwise not overlapping), every launch leaves the counters
- * at zero, and the sum over the parts is taken in part order, so results are reproducible. */
+ * at zero, and the sum over the parts is taken in part order, so results are reproducible.
+ * The split and the two-team uKernels run in the bodies that copy 16-byte chunks straight into LDS:
+ * shapes whose K or N is not a multiple of 8 are never scored with a split.  If only the POINTERS
+ * passed to ft_launch turn out not to be 16-byte aligned, the launch runs the same tiles through the
+ * general four-wave bodies, one workgroup per tile (k_parts in ft_plan_stats then describes the plan,
+ * not that launch); results agree up to the order of the fp32 sums. */
 ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_forced_program *forced, ft_plan **out);
 /* The same plan through the set's per-shape cache (Sec. 5: the runtime stage is paid once per shape;
@@ -285,7 +290,9 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
  * earlier for the same shape and flags, or makes it (as ft_plan_create would, on the current HIP
  * device unless FT_PLAN_HOST_ONLY) and keeps it.  *out stays owned by the set: valid until
  * ft_ukset_destroy, never passed to ft_plan_destroy.  Safe to call from several threads; mode
- * FT_PLAN_FORCED is not cached (FT_ERR_INVALID_ARG). */
+ * FT_PLAN_FORCED is not cached (FT_ERR_INVALID_ARG).  A set keeps at most 65536 plans (each owns a
+ * descriptor table on the device); beyond that the call returns FT_ERR_OOM and ft_plan_create, whose
+ * plans the caller destroys, is the way. */
 ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_plan **out);
 /* Grouped plan: n_groups batched Matmul problems of DIFFERENT shapes run by ONE launch -- a batch

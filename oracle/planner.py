@@ -766,7 +766,8 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         pl.pool_size = len(covers)
         # Occupancy rescue (Matmul): every program is also scored with its tiles split over
         # 2, 3, ... workgroups along the reduce axis, where that is allowed
-        choices = K_PART_CHOICES if op.kind == OP_MATMUL else (1,)
+        # (the split runs in the LDS-DMA bodies only: rows of 16-byte chunks, K and N multiples of 8)
+        choices = K_PART_CHOICES if op.kind == OP_MATMUL and K % 8 == 0 and N % 8 == 0 else (1,)
         # Two dynamic space axes: every program is also scored with second-axis strips
         ms, ns, _ = op.gemm_static()
         two_axes = ms == 0 and ns == 0 and t.get("second_axis_strips", 0) != 0

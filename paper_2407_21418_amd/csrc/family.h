@@ -2,6 +2,7 @@
 // X(code, WM, WN, GM, GN); TK = 64 for all.  reg_tile = WM x WN per wave, smem_tile =
 // (GM*WM) x (GN*WN) x 64.  Rows of 16 use v_mfma_f32_16x16x32, all others v_mfma_f32_32x32x16.
 #pragma once
+#include <stdint.h>
 #define FT_FAMILY(X)                                                                     \
     X(0, 16, 16, 1, 4)   X(1, 16, 16, 2, 2)   X(2, 16, 16, 4, 1)                         \
     X(3, 16, 32, 1, 4)   X(4, 16, 32, 2, 2)   X(5, 16, 32, 4, 1)                         \

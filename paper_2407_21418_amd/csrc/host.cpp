@@ -560,6 +560,32 @@ ftk::LaunchOrder launch_order_of(const ft_plan &plan) {
 
 thread_local int g_last_hip_error = 0;
 
+// owns a handle under construction: released to the caller on success, destroyed on every other path
+// (error returns and exceptions alike)
+struct PlanGuard {
+    ft_plan *p;
+    ~PlanGuard() { if (p) ft_plan_destroy(p); }
+    ft_plan *release() { ft_plan *q = p; p = nullptr; return q; }
+};
+struct SetGuard {
+    ft_ukset *p;
+    ~SetGuard() { if (p) ft_ukset_destroy(p); }
+    ft_ukset *release() { ft_ukset *q = p; p = nullptr; return q; }
+};
+
+// No exception may cross the C boundary: every entry point that allocates runs its body in here.
+template <typename F> ft_status guarded(F &&body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return FT_ERR_OOM;
+    } catch (...) {
+        return FT_ERR_INVALID_ARG;
+    }
+}
+
+constexpr size_t kPlanCacheMax = 65536;      // plans a uKernel set keeps for ft_plan_cached / grouped plans
+
 }  // namespace
 
 void ftd_set_hip_error(int e) { g_last_hip_error = e; }
@@ -616,12 +642,17 @@ ft_status ft_op_register(const ft_op_desc *desc, ft_op **out) {
 
 void ft_op_destroy(ft_op *op) { delete op; }
 
+static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, const ft_tuning *tuning, ft_ukset **out);
 ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tuning *tuning, ft_ukset **out) {
+    return guarded([&] { return ukernels_derive_impl(op, hw, tuning, out); });
+}
+static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, const ft_tuning *tuning, ft_ukset **out) {
     if (!op || !out) return FT_ERR_INVALID_ARG;
     if (hw && hw->struct_size != sizeof(ft_hw_model)) return FT_ERR_INVALID_ARG;
     if (tuning && tuning->struct_size != sizeof(ft_tuning)) return FT_ERR_INVALID_ARG;
     ft_ukset *set = new (std::nothrow) ft_ukset;
     if (!set) return FT_ERR_OOM;
+    SetGuard set_guard{set};
     set->op = op->d;
     if (hw) set->hw = *hw; else hw_defaults(&set->hw);
     if (tuning) set->t = *tuning; else tuning_defaults(&set->t);
@@ -630,7 +661,6 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
     if (!h.num_cus || !h.wave_size || h.regs_per_lane < 4 || !h.mfma_flops_per_clk_per_cu || !h.bw_global_bytes_per_clk_per_cu ||
         !h.bw_lds_bytes_per_clk_per_cu || !t.zeta || !t.psi_den || t.sia_form > FT_SIA_PRODUCT ||
         (t.sia_form == FT_SIA_PRODUCT && (t.c0 > 4 || t.c1 > 4 || t.c2 > 4))) {
-        delete set;
         return FT_ERR_INVALID_ARG;
     }
     Gemm sv = static_view(op->d);
@@ -742,11 +772,8 @@ ft_status ft_ukernels_derive(const ft_op *op, const ft_hw_model *hw, const ft_tu
         set->uk[i].id = (uint32_t)i;
         set->cap_q = std::max(set->cap_q, std::max(set->uk[i].cmr_q20, set->uk[i].cmr_shared_q20));
     }
-    if (set->uk.empty()) {
-        delete set;
-        return FT_ERR_NO_COVER;
-    }
-    *out = set;
+    if (set->uk.empty()) return FT_ERR_NO_COVER;
+    *out = set_guard.release();
     return FT_OK;
 }
 
@@ -783,8 +810,14 @@ static ft_status check_common(const ft_op *op, const ft_ukset *set, const ft_sha
     return FT_OK;
 }
 
+static ft_status plan_pool_impl(const ft_op *op, const ft_ukset *set, const ft_shape *shape, ft_pool_entry *out,
+                                uint32_t cap, uint32_t *n);
 ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *shape, ft_pool_entry *out,
                        uint32_t cap, uint32_t *n) {
+    return guarded([&] { return plan_pool_impl(op, set, shape, out, cap, n); });
+}
+static ft_status plan_pool_impl(const ft_op *op, const ft_ukset *set, const ft_shape *shape, ft_pool_entry *out,
+                                uint32_t cap, uint32_t *n) {
     Resolved r;
     ft_status st = check_common(op, set, shape, &r);
     if (st != FT_OK) return st;
@@ -812,8 +845,14 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
 // set by ft_plan_create_grouped around its calls of ft_plan_create: the batch of the whole launch
 static thread_local uint64_t tl_launch_batch = 0;
 
+static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
+                                  const ft_forced_program *forced, ft_plan **out);
 ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_forced_program *forced, ft_plan **out) {
+    return guarded([&] { return plan_create_impl(op, set, shape, flags, forced, out); });
+}
+static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
+                                  const ft_forced_program *forced, ft_plan **out) {
     Resolved r;
     ft_status st = check_common(op, set, shape, &r);
     if (st != FT_OK) return st;
@@ -825,6 +864,8 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
 
     ft_plan *pl = new (std::nothrow) ft_plan;
     if (!pl) return FT_ERR_OOM;
+    PlanGuard plan_guard{pl};
+    pl->d_descs = nullptr; pl->d_ws = nullptr; pl->d_arrive = nullptr; pl->d_groups = nullptr;
     pl->op = op->d;
     pl->d_descs = nullptr;
     pl->d_ws = nullptr;
@@ -853,7 +894,7 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
     s.useful_elems = r.batch * r.M * r.N;
     s.k_parts = 1;
     if (r.batch == 0 || r.M == 0 || r.N == 0) {           // empty input: empty plan
-        *out = pl;
+        *out = plan_guard.release();
         return FT_OK;
     }
 
@@ -873,26 +914,26 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
         s.level = (uint32_t)level_of(best);
     } else if (mode == FT_PLAN_FORCED) {
         uint64_t Hp = ceil_by(tau == 0 ? r.M : r.N, GRANULE);
-        if (forced->k1 >= set->uk.size() || forced->count1 == 0) { delete pl; return FT_ERR_INVALID_ARG; }
+        if (forced->k1 >= set->uk.size() || forced->count1 == 0) return FT_ERR_INVALID_ARG;
         uint64_t total = (uint64_t)forced->count1 * ext(set->uk[forced->k1], tau);
         best.nparts = 1;
         best.part[0] = {forced->k1, forced->count1};
         best.k1 = forced->k1; best.k2 = -1;
         if (forced->count2) {
-            if (forced->k2 >= set->uk.size() || forced->k2 == forced->k1) { delete pl; return FT_ERR_INVALID_ARG; }
+            if (forced->k2 >= set->uk.size() || forced->k2 == forced->k1) return FT_ERR_INVALID_ARG;
             total += (uint64_t)forced->count2 * ext(set->uk[forced->k2], tau);
-            if ((set->uk[forced->k1].gk == 2) != (set->uk[forced->k2].gk == 2)) { delete pl; return FT_ERR_INVALID_ARG; }
+            if ((set->uk[forced->k1].gk == 2) != (set->uk[forced->k2].gk == 2)) return FT_ERR_INVALID_ARG;
             best.nparts = 2;
             best.part[1] = {forced->k2, forced->count2};
             best.k2 = forced->k2;
         }
-        if (total != Hp) { delete pl; return FT_ERR_NO_COVER; }
+        if (total != Hp) return FT_ERR_NO_COVER;
         // parts per tile: as asked, cut down to the k-tiles there are (no empty part); 1 if a
         // constituent has no registers left for the exchange
         uint32_t parts = 1;
         if (forced->k_parts > 1) {
-            if (forced->k_parts > 64) { delete pl; return FT_ERR_INVALID_ARG; }
-            bool room = true;
+            if (forced->k_parts > 64) return FT_ERR_INVALID_ARG;
+            bool room = op->d.kind == FT_OP_MATMUL && r.K % 8 == 0 && r.N % 8 == 0;     // as for the planner's own splits
             for (uint32_t i = 0; i < best.nparts; ++i)
                 room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX && set->uk[best.part[i].id].gk != 2;
             if (room) {
@@ -938,7 +979,8 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
                 }
                 evaluate(p, *set, eval_batch, r.M, r.N, tau);
                 scored.push_back(p);
-                if (op->d.kind == FT_OP_MATMUL)
+                // (the split runs in the LDS-DMA bodies only: rows of 16-byte chunks, K and N multiples of 8)
+                if (op->d.kind == FT_OP_MATMUL && r.K % 8 == 0 && r.N % 8 == 0)
                     for (uint32_t kp : kPartChoices) {
                         if (kp == 1 || !split_allowed(p, *set, r.K, kp)) continue;
                         Program q = p;
@@ -1076,14 +1118,20 @@ ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *s
 
     if (!(flags & FT_PLAN_HOST_ONLY)) {
         st = ftd_upload(pl);
-        if (st != FT_OK) { delete pl; return st; }
+        if (st != FT_OK) return st;
     }
-    *out = pl;
+    *out = plan_guard.release();
     return FT_OK;
 }
 
+static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
+                                          uint32_t flags, ft_plan **out);
 ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
                                  uint32_t flags, ft_plan **out) {
+    return guarded([&] { return plan_create_grouped_impl(op, set, groups, n_groups, flags, out); });
+}
+static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
+                                          uint32_t flags, ft_plan **out) {
     if (!op || !set || !out || (n_groups && !groups) || n_groups >= (1u << 20)) return FT_ERR_INVALID_ARG;
     if (op->d.kind != FT_OP_BMM) return FT_ERR_UNSUPPORTED;
     const uint32_t mode = flags & FT_PLAN_MODE_MASK;
@@ -1099,6 +1147,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
         ft_status st = ft_plan_create(op, set, &none, mode | FT_PLAN_HOST_ONLY, nullptr, &pl);
         if (st != FT_OK) return st;
     }
+    PlanGuard plan_guard{pl};
     ft_plan_stats &s = pl->st;
     const uint32_t es_c = op->d.out_dtype == FT_OUT_SAME ? 2 : 4;
     uint64_t off_a = 0, off_b = 0, off_c = 0;
@@ -1126,7 +1175,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
     for (uint32_t gi = 0; gi < n_groups; ++gi) {
         Resolved rr;
         ft_status st = check_common(op, set, &groups[gi], &rr);
-        if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+        if (st != FT_OK) return st;
         ft_group_rec &rec = recs[gi];
         rec.m = (uint32_t)rr.M; rec.n = (uint32_t)rr.N; rec.k = (uint32_t)rr.K; rec.batch = (uint32_t)rr.batch;
         rec.off_a = off_a; rec.off_b = off_b; rec.off_c = off_c;
@@ -1150,7 +1199,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
             // validate the group's own shape first (its batch against batch_hi)
             Resolved rr;
             ft_status st = check_common(op, set, &groups[gi], &rr);
-            if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+            if (st != FT_OK) return st;
             const std::vector<uint32_t> key = {mode | FT_PLAN_HOST_ONLY, 0xFFFFFFFFu, (uint32_t)launch_batch,
                                                unit.batch, unit.m, unit.n, unit.k};
             std::lock_guard<std::mutex> lock(set->cache_mu);
@@ -1158,10 +1207,13 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
             if (it == set->cache.end()) {
                 ft_plan *made = nullptr;
                 tl_launch_batch = launch_batch;
-                st = ft_plan_create(op, set, &unit, mode | FT_PLAN_HOST_ONLY, nullptr, &made);
+                st = ft_plan_create(op, set, &unit, mode | FT_PLAN_HOST_ONLY, nullptr, &made);   // (catches its own exceptions)
                 tl_launch_batch = 0;
-                if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+                if (st != FT_OK) return st;
+                PlanGuard made_guard{made};
+                if (set->cache.size() >= kPlanCacheMax) return FT_ERR_OOM;
                 it = set->cache.emplace(key, made).first;
+                made_guard.release();
             }
             sub = it->second;
         }
@@ -1184,7 +1236,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
             any = true;
             const ft_ukernel_info &u = set->uk[d.ukernel_id];
             const int code = ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk);
-            if (code < 0 || code > 0x7f || u.stages > 0xf) { ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
+            if (code < 0 || code > 0x7f || u.stages > 0xf) return FT_ERR_UNSUPPORTED;
             d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (u.stages << 8) | (gi << 12);
             pl->descs.push_back(d);
             const int twin = ft_general_code(code);          // what the general bodies run for it
@@ -1206,7 +1258,7 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
     total.m = total.n = total.k = total.batch = 0;
     total.off_a = off_a; total.off_b = off_b; total.off_c = off_c;
     pl->groups.push_back(total);
-    if (pl->descs.size() > UINT32_MAX / 2) { ft_plan_destroy(pl); return FT_ERR_UNSUPPORTED; }
+    if (pl->descs.size() > UINT32_MAX / 2) return FT_ERR_UNSUPPORTED;
     s.n_tiles = pl->descs.size();
     s.n_ukernels = 0;                          // a program per group: no single pair of uKernels describes the plan
     s.k_parts = 1; s.k_part_tiles = 0; s.workspace_bytes = 0;
@@ -1216,9 +1268,9 @@ ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape 
     pl->table_order = true;
     if (!(flags & FT_PLAN_HOST_ONLY) && !pl->descs.empty()) {
         ft_status st = ftd_upload(pl);
-        if (st != FT_OK) { ft_plan_destroy(pl); return st; }
+        if (st != FT_OK) return st;
     }
-    *out = pl;
+    *out = plan_guard.release();
     return FT_OK;
 }
 
@@ -1229,7 +1281,11 @@ ft_status ft_plan_group_layout(const ft_plan *plan, uint32_t group, uint64_t *of
     return FT_OK;
 }
 
+static ft_status plan_cached_impl(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags, const ft_plan **out);
 ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags, const ft_plan **out) {
+    return guarded([&] { return plan_cached_impl(op, set, shape, flags, out); });
+}
+static ft_status plan_cached_impl(const ft_op *op, ft_ukset *set, const ft_shape *shape, uint32_t flags, const ft_plan **out) {
     if (!op || !set || !shape || !out || shape->struct_size != sizeof(ft_shape)) return FT_ERR_INVALID_ARG;
     if ((flags & FT_PLAN_MODE_MASK) == FT_PLAN_FORCED) return FT_ERR_INVALID_ARG;
     const std::vector<uint32_t> key = {flags, shape->batch, shape->m, shape->n, shape->k,
@@ -1240,11 +1296,13 @@ ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, 
         *out = it->second;
         return FT_OK;
     }
+    if (set->cache.size() >= kPlanCacheMax) return FT_ERR_OOM;     // the cache is bounded: see ftuner.h
     ft_plan *pl = nullptr;
     ft_status st = ft_plan_create(op, set, shape, flags, nullptr, &pl);
     if (st != FT_OK) return st;
+    PlanGuard plan_guard{pl};
     set->cache.emplace(key, pl);
-    *out = pl;
+    *out = plan_guard.release();
     return FT_OK;
 }
 
