@@ -226,7 +226,7 @@ def main():
     # sequence to the longest and against one launch per sequence
     ragged = None
     if "ragged" in variants:
-        from paper_2407_21418_amd import run_ragged
+        import run_ragged
         rr = run_ragged.measure(draws=1, iters=10)
         ragged = {r["op"]: {"grouped_us": r["us_grouped"], "padded_to_longest_us": r["us_padded"],
                             "one_launch_per_sequence_us": r["us_looped"], "useful_tflops": r["tflops_grouped"]} for r in rr}

@@ -1,6 +1,6 @@
 """A second workload through the C ABI: the dense layers of a BERT-base encoder, chained on one stream.
 
-    python -m paper_2407_21418_amd.run_bert_chain [--layers 12] [--iters 20] [--dtype f16|bf16]
+    python run_bert_chain.py [--layers 12] [--iters 20] [--dtype f16|bf16]
 
 The paper's end-to-end BERT run is made of Dense + bias-add operators whose token count changes from
 request to request (Sec. 6.2; Table 6 lists the (T, 2304, 768) projection).  For every token count
@@ -28,7 +28,7 @@ import os
 import sys
 import time
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 TABLE6_T = (5, 24, 43, 62, 81, 100, 119, 128)
 HIDDEN, FFN = 768, 3072

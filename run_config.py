@@ -1,8 +1,8 @@
 """Time one of the workload configurations through the C ABI: patchwork plan vs pad-to-library plan.
 
-    python -m paper_2407_21418_amd.run_config --config 2     # attention BMM, B x 32 drawn lengths, QK^T and PV
-    python -m paper_2407_21418_amd.run_config --config 3     # LLM token-count GEMMs (K = 4096, N in {4096, 11008})
-    python -m paper_2407_21418_amd.run_config --config 4     # dynamic-resolution Conv2d
+    python run_config.py --config 2     # attention BMM, B x 32 drawn lengths, QK^T and PV
+    python run_config.py --config 3     # LLM token-count GEMMs (K = 4096, N in {4096, 11008})
+    python run_config.py --config 4     # dynamic-resolution Conv2d
 
 Shapes come from synth_inputs (the seeded draws of the configuration); operand values are random bit
 patterns made on the device (timing only).  Operands rotate over buffer sets totalling about
@@ -15,7 +15,7 @@ import math
 import os
 import sys
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def geomean(xs):

@@ -1,6 +1,6 @@
 """Ragged attention batches through the C ABI: one grouped launch against the alternatives.
 
-    python -m paper_2407_21418_amd.run_ragged [--seqs 64] [--heads 12] [--iters 20] [--draws 4] [--align 8]
+    python run_ragged.py [--seqs 64] [--heads 12] [--iters 20] [--draws 4] [--align 8]
 
 A batch holds --seqs sequences whose lengths are drawn like the attention configuration's (the
 paper's motivation, Sec. 1 / Fig. 1(b): sequence lengths in a batch differ widely and padding them to
@@ -19,7 +19,7 @@ import math
 import os
 import sys
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main():

@@ -1,6 +1,6 @@
 """Time one Matmul shape through the C ABI (plan + repeated launch); used for profiling.
 
-    python -m paper_2407_21418_amd.run_shape --m 8192 --n 4096 --k 4096 --dtype bf16 --iters 20
+    python run_shape.py --m 8192 --n 4096 --k 4096 --dtype bf16 --iters 20
     ... --force 256,256,128,128     # force the single-uKernel program (tm,tn,wm,wn), M % tm == 0
     ... --baseline                  # the pad-to-library plan
 
@@ -10,7 +10,7 @@ import argparse
 import os
 import sys
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main():
