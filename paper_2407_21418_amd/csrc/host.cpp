@@ -933,7 +933,7 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
         uint32_t parts = 1;
         if (forced->k_parts > 1) {
             if (forced->k_parts > 64) return FT_ERR_INVALID_ARG;
-            bool room = op->d.kind == FT_OP_MATMUL && r.K % 8 == 0 && r.N % 8 == 0;     // as for the planner's own splits
+            bool room = op->d.kind != FT_OP_CONV2D && r.K % 8 == 0 && r.N % 8 == 0;    // the split runs in the LDS-DMA Matmul bodies only
             for (uint32_t i = 0; i < best.nparts; ++i)
                 room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX && set->uk[best.part[i].id].gk != 2;
             if (room) {

@@ -12,7 +12,7 @@ from oracle import planner as P
 
 import torch
 
-from gpu_util import GUARD, alloc_out, check, check_epilogue, dev_bits, matmul_op, out_view, run, run_epilogue
+from gpu_util import GUARD, alloc_out, check, check_epilogue, dev_bits, matmul_op, out_view, run, run_epilogue, stream
 
 pytestmark = pytest.mark.gpu
 
@@ -129,23 +129,43 @@ def test_planner_chosen_split_matches_oracle(M, N, K):
     check(run(plan, A, B, M * N), ref, refabs, f"{M}x{N}x{K} k_parts {st.k_parts}")
 
 
-def test_unaligned_operands_ignore_the_split():
-    """Odd row lengths take the general bodies, which walk the whole reduce axis themselves."""
+def test_shapes_without_the_vector_path_are_never_split():
+    """Odd row lengths take the general bodies, which walk the whole reduce axis themselves: a forced
+    split is cut down to one part when the plan is made, so the statistics describe what runs."""
     M, N, K = 100, 203, 331
     g = np.random.default_rng(5)
     A = si.normal_bits(g, (M, K), 1.0, ft.FT_F16)
     B = si.normal_bits(g, (K, N), 1.0, ft.FT_F16)
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=0, m_hi=4096))
     s = ft.ft_ukernels_derive(op)
-    u = ft.ft_ukset_get(s, 0)
     Hp = -(-M // 16) * 16
     ids = [i for i in range(ft.ft_ukset_size(s)) if Hp % ft.ft_ukset_get(s, i).tm == 0]
     u = ft.ft_ukset_get(s, ids[0])
     plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED,
                              ft.ft_forced_program(k1=ids[0], count1=Hp // u.tm, k_parts=3))
-    assert ft.ft_plan_stats_get(plan).k_parts == 3
+    st = ft.ft_plan_stats_get(plan)
+    assert (st.k_parts, st.workspace_bytes) == (1, 0)
     ref, refabs = oc.matmul(A, B, si.F16, want_abs=True)
-    check(run(plan, A, B, M * N), ref, refabs, "general path, split ignored")
+    check(run(plan, A, B, M * N), ref, refabs, "general path")
+
+
+def test_split_plan_with_misaligned_pointers_runs_the_general_bodies():
+    """A plan that splits the reduce axis, launched on operands that are not 16-byte aligned: the same
+    tiles run through the general bodies, one workgroup per tile; the result is still right."""
+    M, N, K = 528, 768, 3072
+    p = si.config1_problem(M, N, K)
+    op = matmul_op(N, K, ft.FT_F16)
+    s = ft.ft_ukernels_derive(op)
+    plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M))
+    assert ft.ft_plan_stats_get(plan).k_parts > 1
+    ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+    A = torch.zeros(M * K + 8, dtype=torch.int16, device="cuda")
+    A[4:4 + M * K] = dev_bits(p["A"]).reshape(-1)            # 8 bytes past a 16-byte boundary
+    B = dev_bits(p["B"])
+    buf = alloc_out(M * N)
+    ft.ft_launch(plan, A.data_ptr() + 8, B.data_ptr(), buf.data_ptr() + 4 * GUARD, stream())
+    torch.cuda.synchronize()
+    check(out_view(buf, M * N), ref, refabs, "misaligned A")
 
 
 def test_split_plan_through_the_timing_entry_points_and_a_graph():
