@@ -369,6 +369,24 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
 ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
                              void *hip_stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: ft_launch_epilogue (bias may be NULL exactly as there) with
+ * nothing allocated anywhere on the way.  The partial tiles and arrival counters of a reduce-axis
+ * split, which ft_plan_create otherwise allocates per plan, live in one array that is part of the
+ * library's device code (32 MiB of partial tiles + 64 KiB of counters per GPU, held until the process
+ * ends), and a plan made with FT_PLAN_HOST_ONLY -- no device table, so no allocation at plan time
+ * either -- is accepted as long as its workgroups derive their tiles in closed form
+ * (ft_plan_stats.table_order == 0: every plan without second-axis strips; grouped plans and
+ * table-order plans without a device table: FT_ERR_UNSUPPORTED).  A plan whose split needs more than
+ * the array holds (n_tiles * k_parts * largest tile * 4 bytes > 32 MiB, or more than 4096 tiles) is
+ * refused with FT_ERR_UNSUPPORTED; nothing is launched then.  The call clears the counters it will use
+ * with a small kernel on hip_stream, then launches; it calls no allocating routine and does not
+ * synchronise.  All calls on one GPU share the array: calls that may overlap in time (different
+ * streams, different threads) race on it and must be ordered by the caller; ft_launch / ft_launch_epilogue
+ * with plans that own their workspace do not touch it.  Same results as ft_launch_epilogue, bit for bit. */
+ft_status ft_launch_noalloc(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
+                            void *hip_stream);
+
 /* Timing helper for benchmarks: launches the plan `iters` times back to back on hip_stream,
  * launch i using buffer set i % n_sets (A, B, C: host arrays of n_sets device pointers; rotating
  * over many sets keeps operands out of the caches), between two HIP events recorded on that same

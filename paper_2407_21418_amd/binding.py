@@ -124,6 +124,7 @@ SYMBOLS = {
     "ft_plan_pool": (C.c_int32, [_P, _P, C.POINTER(ft_shape), C.POINTER(ft_pool_entry), u32, C.POINTER(u32)]),
     "ft_launch": (C.c_int32, [_P, _P, _P, _P, _P]),
     "ft_launch_epilogue": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
+    "ft_launch_noalloc": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
     "ft_launch_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
                                     C.POINTER(C.c_float)]),
     "ft_launch_timed_graph": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
@@ -315,6 +316,11 @@ def ft_launch(p: Plan, A: int, B: int, Cptr: int, stream: int = 0):
 def ft_launch_epilogue(p: Plan, A: int, B: int, Cptr: int, bias: int, stream: int = 0):
     """As ft_launch, with bias = device address of N fp32 values (0 / None for none)."""
     _check(lib().ft_launch_epilogue(p.ptr, A, B, Cptr, bias or None, stream), "ft_launch_epilogue")
+
+
+def ft_launch_noalloc(p: Plan, A: int, B: int, Cptr: int, bias: int = 0, stream: int = 0):
+    """As ft_launch_epilogue, with the workspace of a reduce-axis split in the library's own device array."""
+    _check(lib().ft_launch_noalloc(p.ptr, A, B, Cptr, bias or None, stream), "ft_launch_noalloc")
 
 
 def ft_launch_timed(p: Plan, A, B, Cs, stream: int, iters: int, graph: bool = False) -> float:

@@ -2,11 +2,28 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 
 #include "family.h"
 #include "ft_internal.h"
 #include "gemm_body.h"
 #include "launch_iface.h"
+
+// Workspace of ft_launch_noalloc: the fp32 partial tiles and arrival counters of a reduce-axis split,
+// which ft_plan_create otherwise allocates per plan.  One copy per GPU, held until the process ends and
+// shared by every call on that GPU.  The name is a host-side handle only: its device address comes from
+// hipGetSymbolAddress (noalloc_scratch_of below) and that pointer is what the kernels are given.
+#define FT_NOALLOC_COUNTER_BYTES (64u << 10)
+#define FT_NOALLOC_PARTIAL_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[FT_NOALLOC_COUNTER_BYTES + FT_NOALLOC_PARTIAL_BYTES];
+
+namespace ftk {
+// zeroes n 32-bit words (a kernel, not a memset node: the call may be captured into a HIP graph)
+__global__ void ft_clear_words(uint32_t *p, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+}  // namespace ftk
 
 namespace {
 
@@ -40,6 +57,25 @@ uint64_t *g_trace = nullptr;      // development builds: where the next launches
 ft_status hip_fail(hipError_t e) {
     ftd_set_hip_error((int)e);
     return FT_ERR_HIP;
+}
+
+// Device address of `scratch` on the current device: looked up once per device, with that device
+// current, and kept (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+ft_status noalloc_scratch_of(int dev, unsigned char **out) {
+    static std::mutex mu;
+    static unsigned char *ptr_of[kMaxDevices] = {};
+    if (dev < 0 || dev >= kMaxDevices) return FT_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return FT_ERR_HIP;
+        ptr_of[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = ptr_of[dev];
+    return FT_OK;
 }
 
 void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const float *bias, ftk::KArgs *a) {
@@ -139,6 +175,9 @@ void ftd_release(ft_plan *p) {
     if (p->d_groups) { (void)hipFree(p->d_groups); p->d_groups = nullptr; }
 }
 
+static ft_status launch_common(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
+                               void *hip_stream, bool static_ws);
+
 extern "C" {
 
 #ifdef FT_TRACE
@@ -167,20 +206,50 @@ ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, 
 
 ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
                              void *hip_stream) {
+    return launch_common(plan, A, B, C, bias, hip_stream, false);
+}
+
+ft_status ft_launch_noalloc(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
+                            void *hip_stream) {
+    return launch_common(plan, A, B, C, bias, hip_stream, true);
+}
+
+}  // extern "C"
+
+// static_ws: the call is ft_launch_noalloc -- partial tiles and counters live in `scratch`, a plan
+// without a device table is accepted where the kernels derive their tiles in closed form
+static ft_status launch_common(const ft_plan *plan, const void *A, const void *B, void *C, const float *bias,
+                               void *hip_stream, bool static_ws) {
     if (!plan) return FT_ERR_INVALID_ARG;
     if ((plan->op.epilogue == FT_EPI_BIAS) != (bias != nullptr)) return FT_ERR_INVALID_ARG;
     if (plan->st.n_tiles == 0) return FT_OK;
     if (!A || !B || !C) return FT_ERR_INVALID_ARG;
-    if (!plan->d_descs) return FT_ERR_INVALID_ARG;              // host-only plan
+    if (!static_ws && !plan->d_descs) return FT_ERR_INVALID_ARG;   // host-only plan (found out without touching the GPU)
+    int dev = -1;
     {
-        int dev = -1;                                           // the plan's tables live on one device
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return hip_fail(e);
-        if (dev != plan->device) return FT_ERR_INVALID_ARG;
+    }
+    if (!static_ws) {
+        if (dev != plan->device) return FT_ERR_INVALID_ARG;     // the plan's tables live on one device
+    } else {
+        if (!plan->groups.empty()) return FT_ERR_UNSUPPORTED;   // grouped plans read their tables
+        if (plan->d_descs ? dev != plan->device : plan->table_order) return plan->d_descs ? FT_ERR_INVALID_ARG : FT_ERR_UNSUPPORTED;
     }
     if (plan->st.kernel_class >= FT_NUM_CLASSES || plan->op.dtype > 1) return FT_ERR_UNSUPPORTED;
     ftk::KArgs a;
     fill_args(plan, A, B, C, bias, &a);
+    if (static_ws && plan->st.k_parts > 1) {
+        const uint64_t ctr_bytes = plan->st.n_tiles * 4 * sizeof(uint32_t);
+        const uint64_t ws_bytes = plan->st.n_tiles * plan->st.k_parts * (uint64_t)plan->ws_tile_stride * sizeof(float);
+        if (ctr_bytes > FT_NOALLOC_COUNTER_BYTES || ws_bytes > FT_NOALLOC_PARTIAL_BYTES) return FT_ERR_UNSUPPORTED;
+        unsigned char *base = nullptr;
+        ft_status st = noalloc_scratch_of(dev, &base);
+        if (st != FT_OK) return st;
+        a.k_parts = plan->st.k_parts;
+        a.arrive = reinterpret_cast<uint32_t *>(base);
+        a.ws = reinterpret_cast<float *>(base + FT_NOALLOC_COUNTER_BYTES);
+    }
     if (!plan->groups.empty()) {
         // grouped launch: the dispatcher takes shape, pitches and operand bases from the group records
         if (!plan->d_groups) return FT_ERR_INVALID_ARG;
@@ -211,6 +280,14 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
         }
         a.k_parts = 1;                 // these bodies walk the whole reduce axis in one workgroup
     }
+    if (static_ws && a.k_parts > 1) {
+        // the array keeps what the last call on this GPU left in it: the counters this launch uses start at zero
+        const uint32_t words = (uint32_t)plan->st.n_tiles * 4u;
+        hipLaunchKernelGGL(ftk::ft_clear_words, dim3((words + 255u) / 256u), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                           a.arrive, words);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
     int rc;
     if (fast && plan->two_teams) {
         if (plan->st.kernel_class > 1) return FT_ERR_UNSUPPORTED;
@@ -232,6 +309,8 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
     if (rc != 0) return hip_fail((hipError_t)rc);
     return FT_OK;
 }
+
+extern "C" {
 
 ft_status ft_launch_timed(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
                           uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch) {
