@@ -33,11 +33,21 @@ sys.path.insert(0, ROOT)
 MFMA_PEAK_TFLOPS = 2516.6      # dense fp16/bf16 MFMA, 256 CU x 4096 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 RING_BYTES = 600e6             # > 256 MB Infinity Cache + 8 x 4 MB L2
-# Bytes crossing the L2 <-> fabric boundary per launch (average over the cold launches of this
-# sweep), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file scaled by what the same
-# counters read for a plain 1 GiB copy (x2.0 and x1.0); see profiles/ft_dispatch_pmc.md.
-# Counters cannot be read from inside this process, so the figures are those of the committed profile.
-MEASURED_TRAFFIC_BYTES = {"ft_dispatch_dt0_c0": 19.77e6 + 5.66e6, "ft_dispatch_dt0_c1": 22.79e6 + 9.48e6}
+REPEATS = 5                    # timed regions per GEMM and variant; the median is reported
+# Bytes crossing the L2 <-> fabric boundary per launch of each dispatcher kernel (average over the cold
+# launches of this sweep): counters cannot be read from inside this process, so the figures are those
+# of the committed counter runs of this same file, kept with their commands and calibration in
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "ft_dispatch_traffic.json")
+
+
+def measured_traffic(kernel):
+    """L2-miss read + write-back bytes per launch of `kernel` from the committed counter profile, or None."""
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            k = json.load(f)["kernels"].get(kernel)
+        return None if k is None else float(k["fetch_bytes"]) + float(k["write_bytes"])
+    except (OSError, ValueError, KeyError):
+        return None
 
 
 def geomean(xs):
@@ -110,8 +120,14 @@ def main():
         "--variants: cold[,warm][,base][,out16][,bucket][,single][,ragged]"
     hw = ft.ft_hw_query(0)
 
-    def timed(plan, pa, pb, pc, iters, graph=None):
+    def timed_once(plan, pa, pb, pc, iters, graph=None):
         return ft.ft_launch_timed(plan, pa, pb, pc, stream, iters, graph=use_graph if graph is None else graph)
+
+    def timed(plan, pa, pb, pc, iters, graph=None):
+        """Median over REPEATS regions of `iters` back-to-back launches each (ms per launch)."""
+        if graph is False:                                # warm-up calls
+            return timed_once(plan, pa, pb, pc, iters, graph)
+        return sorted(timed_once(plan, pa, pb, pc, iters, graph) for _ in range(REPEATS))[REPEATS // 2]
 
     shapes = si.config1_shapes()
     ops = {}
@@ -200,7 +216,7 @@ def main():
             del Ab, Cb
         us_single = float("inf")
         if "single" in variants:                     # one launch between two events, then a wait: median of 5
-            one = sorted(timed(r["plan"], pa[i + 1:i + 2], pb[i + 1:i + 2], pc[i + 1:i + 2], 1, graph=False) for i in range(5))
+            one = sorted(timed_once(r["plan"], pa[i + 1:i + 2], pb[i + 1:i + 2], pc[i + 1:i + 2], 1, graph=False) for i in range(5))
             us_single = one[2] * 1e3
         t_roof = max(flops / (MFMA_PEAK_TFLOPS * 1e12), bytes_alg / (HBM_PEAK_GBS * 1e9))
         r.update(ms_bucket=ms_bucket, tflops_bucket=flops / ms_bucket / 1e9, us_single=us_single)
@@ -211,15 +227,28 @@ def main():
                  roof_frac_cold=t_roof * 1e3 / ms_cold, n_tiles=st.n_tiles, n_ukernels=st.n_ukernels,
                  kernel_class=st.kernel_class, useful=st.useful_elems, covered=st.covered_elems,
                  base_covered=sb.covered_elems, base_tiles=sb.n_tiles)
-        k = "ft_dispatch_dt0_c%d" % st.kernel_class
+        two_team = st.n_ukernels > 0 and ft.ft_ukset_get(ops[(N, K)][1], st.ukernel_id[0]).gk == 2
+        k = ("ft_dispatch_dt0_pp_c%d" if two_team else "ft_dispatch_dt0_c%d") % st.kernel_class
+        r["kernel"] = k
         r["bytes_private_l2_floor"] = private_l2_floor_bytes(ft, np, r["plan"], K, hw.num_xcds)
         per_class_floor[k] = per_class_floor.get(k, 0.0) + r["bytes_private_l2_floor"] * args.steps
         per_class_time[k] = per_class_time.get(k, 0.0) + ms_cold * args.steps
         per_class_flops[k] = per_class_flops.get(k, 0.0) + flops * args.steps
         per_class_launches[k] = per_class_launches.get(k, 0) + args.steps
         per_class_bytes[k] = per_class_bytes.get(k, 0.0) + bytes_alg * args.steps
+        if not args.no_cpu_baseline:                    # set 0 holds the seeded problem: checked against the oracle below
+            timed_once(r["plan"], pa[:1], pb[:1], pc[:1], 1, graph=False)
+            r["C0"] = Cs[0].cpu().numpy()
         del As, Bs, Cs
         torch.cuda.empty_cache()
+
+    # attainable memory rates of this device beside the 8 TB/s of the roofline: plain streaming kernels over 1 GiB
+    sbuf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    sbuf.fill_(1)
+    torch.cuda.synchronize()
+    stream_read, stream_write, stream_copy = ft.ft_stream_rate(sbuf.data_ptr(), sbuf.data_ptr() + (1 << 30), 1 << 30, 5, stream)
+    del sbuf
+    torch.cuda.empty_cache()
 
     # informational, beside the headline: a second workload of the same library, one ragged batch of
     # attention (64 sequences x 12 heads, one length each) as ONE grouped launch against padding every
@@ -251,13 +280,13 @@ def main():
         "metric": "geomean TFLOP/s & % MFMA peak over dynamic-shape sweep; padding waste %",
         "value": round(value, 3),
         "unit": "TFLOP/s (geomean over 21 GEMMs, useful flops, operands from HBM)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "repeats": REPEATS,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "configs[1]: BERT-base-shaped dynamic sweep, 21 GEMMs, M=16*L, L in "
                                "{5,17,33,64,77,100,128}, (K,N) in {(768,768),(768,3072),(3072,768)}",
-                   "order": "shape-major: each GEMM launched `steps` times back to back",
+                   "order": "shape-major: each GEMM launched `steps` times back to back, %d such regions, the median one reported" % REPEATS,
                    "launch": "one HIP-graph replay of the `steps` launches" if use_graph else "direct launches",
                    "buffers": "ring of buffer sets > 600 MB per GEMM (cold caches)"},
         "pct_mfma_peak_geomean": round(100.0 * value / MFMA_PEAK_TFLOPS, 3),
@@ -292,10 +321,13 @@ def main():
                                     "achieved": round(achieved if hbm_bound else achieved_gbs, 3),
                                     "unit": "TFLOP/s" if hbm_bound else "GB/s",
                                     "frac": round(achieved / MFMA_PEAK_TFLOPS if hbm_bound else achieved_gbs / HBM_PEAK_GBS, 5)},
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dom),
+                     "traffic": measured_traffic(dom),
                      "traffic_note": "L2-miss read + write-back bytes per launch (rocprofv3 --pmc, copy-calibrated; "
-                                     "Infinity Cache hits included), algorithmic bytes per launch: %d" % round(
-                                         per_class_bytes[dom] / per_class_launches[dom]),
+                                     "Infinity Cache hits included) from profiles/ft_dispatch_traffic.json, "
+                                     "algorithmic bytes per launch: %d" % round(per_class_bytes[dom] / per_class_launches[dom]),
+                     "hbm_attainable_gbs": {"read": round(stream_read, 1), "write": round(stream_write, 1), "copy": round(stream_copy, 1),
+                                            "note": "plain streaming kernels over 1 GiB (ft_stream_rate), this run"},
+                     "frac_of_attainable": round(achieved_gbs / stream_copy, 5) if hbm_bound else None,
                      "traffic_floor_private_l2": round(per_class_floor[dom] / per_class_launches[dom]),
                      "traffic_floor_note": "bytes per launch if each of the 8 XCDs (private L2s) fetches the A rows and "
                                            "B columns of its own tiles exactly once and C is written once, from the "
@@ -323,6 +355,16 @@ def main():
             passes += 1
             if sum(secs) > 30.0:
                 break
+        # every benched GEMM's output (buffer set 0, the seeded problem) against the oracle: max relative
+        # error 2e-3 of fp32-accumulated fp16 products, per element against sum |a||b|
+        worst = 0.0
+        for r, p in zip(rows, probs):
+            ref, refabs = oc.matmul(p["A"], p["B"], si.F16, want_abs=True)
+            d = np.abs(r.pop("C0").astype(np.float64) - ref)
+            worst = max(worst, float((d / (refabs + 1e-30)).max()))
+            assert d.max() <= 2e-3 * np.abs(ref).max() and (d <= 2e-3 * refabs + 1e-30).all(), \
+                "benched GEMM %dx%dx%d differs from the oracle" % (r["M"], r["N"], r["K"])
+        out["verified"] = {"gemms": len(rows), "worst_error_over_sum_abs_products": worst, "tolerance": 2e-3}
         for r, s_ in zip(rows, secs):
             r["oracle_s"] = s_ / passes
         total = sum(secs)
@@ -334,7 +376,7 @@ def main():
 
     os.makedirs(os.path.dirname(args.detail), exist_ok=True)
     with open(args.detail, "w") as f:
-        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base", "plan16", "planb")} for r in rows], f, indent=1)
+        json.dump([{k: v for k, v in r.items() if k not in ("plan", "base", "plan16", "planb", "C0")} for r in rows], f, indent=1)
     print(json.dumps(out), flush=True)
 
 

@@ -395,6 +395,15 @@ ft_status ft_launch_noalloc(const ft_plan *plan, const void *A, const void *B, v
 ft_status ft_launch_timed(const ft_plan *plan, const void *const *A, const void *const *B, void *const *C,
                           uint32_t n_sets, void *hip_stream, uint32_t iters, float *ms_per_launch);
 
+/* Attainable memory rates of the device, for the figure reported beside the 8 TB/s roofline: streams
+ * `bytes` (>= 1 MiB; use far more than the 256 MB Infinity Cache) from src, to dst, and from src to dst
+ * with plain 16-byte-per-lane kernels, `iters` timed launches each after one untimed, between two HIP
+ * events on hip_stream, and stores GB/s (10^9 bytes; the copy counts bytes read + bytes written).
+ * src, dst: device pointers to `bytes` each, 16-byte aligned, caller-owned; dst is overwritten.
+ * The three results are host pointers.  Allocates nothing. */
+ft_status ft_stream_rate(const void *src, void *dst, uint64_t bytes, uint32_t iters, void *hip_stream, float *read_gbs,
+                         float *write_gbs, float *copy_gbs);
+
 /* Same measurement with the `iters` launches captured once into a HIP graph (stream capture of
  * ft_launch on hip_stream, which must not be the NULL stream) and replayed: one untimed replay,
  * then one replay between the two events.  Removes the host's per-launch cost from the timed

@@ -125,6 +125,7 @@ SYMBOLS = {
     "ft_launch": (C.c_int32, [_P, _P, _P, _P, _P]),
     "ft_launch_epilogue": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
     "ft_launch_noalloc": (C.c_int32, [_P, _P, _P, _P, _P, _P]),
+    "ft_stream_rate": (C.c_int32, [_P, _P, u64, u32, _P, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "ft_launch_timed": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
                                     C.POINTER(C.c_float)]),
     "ft_launch_timed_graph": (C.c_int32, [_P, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), u32, _P, u32,
@@ -321,6 +322,13 @@ def ft_launch_epilogue(p: Plan, A: int, B: int, Cptr: int, bias: int, stream: in
 def ft_launch_noalloc(p: Plan, A: int, B: int, Cptr: int, bias: int = 0, stream: int = 0):
     """As ft_launch_epilogue, with the workspace of a reduce-axis split in the library's own device array."""
     _check(lib().ft_launch_noalloc(p.ptr, A, B, Cptr, bias or None, stream), "ft_launch_noalloc")
+
+
+def ft_stream_rate(src: int, dst: int, nbytes: int, iters: int, stream: int = 0):
+    """(read, write, copy) GB/s of plain streaming kernels over nbytes at the device addresses src, dst."""
+    r, w, c = C.c_float(), C.c_float(), C.c_float()
+    _check(lib().ft_stream_rate(src, dst, nbytes, iters, stream, C.byref(r), C.byref(w), C.byref(c)), "ft_stream_rate")
+    return r.value, w.value, c.value
 
 
 def ft_launch_timed(p: Plan, A, B, Cs, stream: int, iters: int, graph: bool = False) -> float:

@@ -18,6 +18,7 @@ ft_status ft_launch_epilogue(const ft_plan *plan, const void *A, const void *B, 
 }
 ft_status ft_launch(const ft_plan *plan, const void *A, const void *B, void *C, void *s) { return ft_launch_epilogue(plan, A, B, C, nullptr, s); }
 ft_status ft_launch_noalloc(const ft_plan *, const void *, const void *, void *, const float *, void *) { return FT_ERR_UNSUPPORTED; }
+ft_status ft_stream_rate(const void *, void *, uint64_t, uint32_t, void *, float *, float *, float *) { return FT_ERR_UNSUPPORTED; }
 ft_status ft_launch_timed(const ft_plan *, const void *const *, const void *const *, void *const *, uint32_t, void *, uint32_t,
                           float *) { return FT_ERR_UNSUPPORTED; }
 ft_status ft_launch_timed_graph(const ft_plan *, const void *const *, const void *const *, void *const *, uint32_t, void *,
