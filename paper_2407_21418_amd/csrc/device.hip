@@ -27,26 +27,34 @@ __global__ void ft_clear_words(uint32_t *p, uint32_t n) {
 
 namespace ftk {
 // Streaming kernels for the attainable-bandwidth figure beside the roofline: every lane moves 16
-// bytes per step, a workgroup walks its share of the buffer in whole 4 KB rows, four rows in flight.
+// bytes per step, a workgroup walks its own contiguous segment in 4 KB rows, eight rows in flight.
 typedef uint32_t stream_u32x4 __attribute__((ext_vector_type(4)));
 template <int MODE>   // 0: read, 1: write, 2: copy
 __global__ __launch_bounds__(256) void ft_stream(const stream_u32x4 *__restrict__ src, stream_u32x4 *__restrict__ dst, uint64_t n16,
                                                  uint32_t *sink) {
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    // every workgroup streams one contiguous segment of the buffer
+    const uint64_t seg = (n16 + gridDim.x - 1) / gridDim.x;
+    const uint64_t end = (blockIdx.x + 1) * seg < n16 ? (blockIdx.x + 1) * seg : n16;
+    n16 = end;
+    const uint64_t stride = 256u;
     stream_u32x4 acc = {0u, 0u, 0u, 0u};
-    uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        if (MODE == 1) {
-            const stream_u32x4 v = {(uint32_t)i, 1u, 2u, 3u};
-            dst[i] = v; dst[i + stride] = v; dst[i + 2 * stride] = v; dst[i + 3 * stride] = v;
-        } else {
-            const stream_u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-            if (MODE == 0) acc += a ^ b ^ c ^ d;
-            else { dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d; }
+    uint64_t i = (uint64_t)blockIdx.x * seg + threadIdx.x;
+    constexpr int U = 8;                                   // 16-byte accesses in flight per lane
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        stream_u32x4 v[U];
+        if (MODE != 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = src[i + u * stride];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (MODE == 0) acc += v[u];
+            else if (MODE == 1) { const stream_u32x4 w = {(uint32_t)i, 1u, 2u, 3u}; dst[i + u * stride] = w; }
+            else dst[i + u * stride] = v[u];
         }
     }
     for (; i < n16; i += stride) {
-        if (MODE == 1) { const stream_u32x4 v = {(uint32_t)i, 1u, 2u, 3u}; dst[i] = v; }
+        if (MODE == 1) { const stream_u32x4 w = {(uint32_t)i, 1u, 2u, 3u}; dst[i] = w; }
         else if (MODE == 0) acc += src[i];
         else dst[i] = src[i];
     }

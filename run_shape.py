@@ -22,6 +22,8 @@ def main():
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--force", default="")
+    ap.add_argument("--k-parts", type=int, default=0, help="with --force: workgroups per tile along the reduce axis")
+    ap.add_argument("--teams", type=int, default=1, choices=[1, 2], help="with --force: 2 picks the eight-wave two-team uKernel of that tile")
     ap.add_argument("--baseline", action="store_true")
     ap.add_argument("--zeta", type=int, default=0, help="override the tuning's zeta (workgroups per CU)")
     ap.add_argument("--ring-mb", type=float, default=0.0, help="rotate over buffer sets totalling this many MB")
@@ -43,11 +45,12 @@ def main():
     if a.force:
         want = tuple(int(x) for x in a.force.split(","))
         ids = [i for i in range(ft.ft_ukset_size(uks))
-               if (lambda u: (u.tm, u.tn, u.wm, u.wn) == want)(ft.ft_ukset_get(uks, i))]
+               if (lambda u: (u.tm, u.tn, u.wm, u.wn) == want and (u.gk == 2) == (a.teams == 2))(ft.ft_ukset_get(uks, i))]
         if not ids:
             raise SystemExit("uKernel %s is not in the derived set" % (want,))
         mode, forced = ft.FT_PLAN_FORCED, ft.ft_forced_program(k1=ids[0], count1=-(-a.m // want[0] * want[0] // want[0]))
         forced.count1 = ((a.m + 15) // 16 * 16) // want[0]
+        forced.k_parts = a.k_parts
     plan = ft.ft_plan_create(op, uks, ft.ft_shape(m=a.m), mode, forced)
     st = ft.ft_plan_stats_get(plan)
     bytes_alg = 2 * (a.m * a.k + a.k * a.n) + 4 * a.m * a.n
@@ -69,8 +72,8 @@ def main():
     ms = ft.ft_launch_timed(plan, pa, pb, pc, s, a.iters)
     prog = [(ft.ft_ukset_get(uks, st.ukernel_id[i]), st.count_tau[i]) for i in range(st.n_ukernels)]
     desc = " + ".join("%dx(%dx%d w%dx%d gk%d s%d)" % (c, u.tm, u.tn, u.wm, u.wn, u.gk, u.stages) for u, c in prog)
-    print("%dx%dx%d %s: %s, %d tiles, class %d, lds %d: %.2f us, %.1f TFLOP/s, %.0f GB/s" % (
-        a.m, a.n, a.k, a.dtype, desc, st.n_tiles, st.kernel_class, st.lds_bytes, ms * 1e3,
+    print("%dx%dx%d %s: %s, %d tiles x %d parts, class %d, lds %d: %.2f us, %.1f TFLOP/s, %.0f GB/s" % (
+        a.m, a.n, a.k, a.dtype, desc, st.n_tiles, st.k_parts, st.kernel_class, st.lds_bytes, ms * 1e3,
         2.0 * a.m * a.n * a.k / ms / 1e9, bytes_alg / ms / 1e6), flush=True)
 
 
