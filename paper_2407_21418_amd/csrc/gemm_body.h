@@ -74,20 +74,15 @@ struct KArgs {
 };
 
 // Development aid, compiled only with -DFT_TRACE: workgroup b leaves the device-wide 100 MHz counter
-// at up to 8 points of its life in trace[16 b ..], so a launch can be laid out on one time axis;
-// slots 8..15 take shader-clock readings (FT_MARK_CLK) inside one k-tile of the main loop.
+// at up to 8 points of its life in trace[16 b ..], so a launch can be laid out on one time axis
+// (trace_timeline.py reads it; marks inside the k loop would disturb the loop's own in-order counters).
 #ifdef FT_TRACE
 #define FT_MARK(g, i)                                                                              \
     do {                                                                                           \
         if ((g).trace != nullptr && threadIdx.x == 0) (g).trace[blockIdx.x * 16u + (i)] = wall_clock64(); \
     } while (0)
-#define FT_MARK_CLK(g, i)                                                                          \
-    do {                                                                                           \
-        if ((g).trace != nullptr && threadIdx.x == 0) (g).trace[blockIdx.x * 16u + (i)] = clock64(); \
-    } while (0)
 #else
 #define FT_MARK(g, i) do { } while (0)
-#define FT_MARK_CLK(g, i) do { } while (0)
 #endif
 
 enum { DT_F16 = 0, DT_BF16 = 1 };

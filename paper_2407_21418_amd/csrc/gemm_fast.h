@@ -361,22 +361,13 @@ struct UKernelFast {
         for (uint32_t kt = 0; kt < nk; ++kt) {
             // copies issued so far: tiles 0 .. min(kt+S-2, nk-1); tile kt must have landed
             uint32_t newest = kt + S - 2 < nk - 1 ? kt + S - 2 : nk - 1;
-#ifdef FT_TRACE
-            if (kt == nk / 2) FT_MARK_CLK(g, 8);
-#endif
             wait_tiles<0>((int)(newest - kt));
-#ifdef FT_TRACE
-            if (kt == nk / 2) FT_MARK_CLK(g, 9);
-#endif
             __builtin_amdgcn_s_barrier();      // tile kt visible to every wave; stage (kt-1)%S is free again
 #ifdef FT_TRACE
             if (kt == 0) FT_MARK(g, 3);
-            if (kt == nk / 2) { FT_MARK(g, 4); FT_MARK_CLK(g, 10); }
+            if (kt == nk / 2) FT_MARK(g, 4);
 #endif
             if (kt + S - 1 < nk) issue(kt + S - 1);
-#ifdef FT_TRACE
-            if (kt == nk / 2) FT_MARK_CLK(g, 11);
-#endif
 
             const uint32_t soff = (kt % S) * STAGE_BYTES;
             const uint32_t a_addr = fa_addr0 + soff;
@@ -388,10 +379,6 @@ struct UKernelFast {
             u32x2 fb[2][BN][2];
             read_step<0, 0>(a_addr, b_addr, fa, fb);
             step<0>(a_addr, b_addr, fa, fb, acc);
-#ifdef FT_TRACE
-            if (kt == nk / 2) FT_MARK_CLK(g, 12);
-            if (kt == nk / 2 + 1) FT_MARK_CLK(g, 13);
-#endif
         }
 
         // ---- epilogue ------------------------------------------------------------------------------

@@ -10,7 +10,7 @@ planner picks by itself, their ratio; at the end the geomean of the ratios and t
 
     python sia_validation.py                 # 21 BERT-shaped GEMMs + 18 LLM-shaped ones
     python sia_validation.py --heldout       # 28 shapes the model constants were not fitted on
-    python sia_validation.py --two-team      # with the eight-wave two-team uKernels in the set
+    python sia_validation.py --four-wave     # without the eight-wave two-team uKernels in the set
     ... --json gpurun_out/sia.json           # every timed program with its scores, for fitting
 
 Prints a markdown table (kept under profiles/sia_validation.md).
@@ -30,7 +30,7 @@ KP_CHOICES = (2, 3, 4, 6, 8)
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--heldout", action="store_true")
-    ap.add_argument("--two-team", action="store_true")
+    ap.add_argument("--four-wave", action="store_true")
     ap.add_argument("--iters", type=int, default=30)
     ap.add_argument("--ring-mb", type=float, default=600.0)
     ap.add_argument("--json", default="")
@@ -43,8 +43,8 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     hw = ft.ft_hw_query(0)
     tuning = ft.ft_tuning_default()
-    if a.two_team:
-        tuning.two_team_bodies = 1
+    if a.four_wave:
+        tuning.two_team_bodies = 0
     if a.heldout:
         shapes = [(M, N, K, ft.FT_F16) for (N, K) in ((1024, 1024), (2304, 768), (5120, 2048), (1536, 4096))
                   for M in (96, 200, 400, 777, 1500, 3000, 6000)]
