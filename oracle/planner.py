@@ -219,7 +219,16 @@ def wave_tiles():
 # split-k grid every wave owns the whole tile and a quarter of k.  gk = 2: the standard grids again
 # with eight waves, two teams of four (two waves per SIMD) that take alternate k-tiles of the tile
 # (tuning two_team_bodies; Matmul and Conv2d): while one team runs its MFMAs the other copies.
-WAVE_GRIDS = ((1, 4, 1), (2, 2, 1), (4, 1, 1), (1, 1, 4), (1, 4, 2), (2, 2, 2), (4, 1, 2))
+# gm * gn = 8 (gk = 1): eight waves, two per SIMD, on the same k-tiles -- the largest tiles at half the
+# accumulator registers per wave; compiled for the wave tiles in EIGHT_WAVE_FAMILY only.
+WAVE_GRIDS = ((1, 4, 1), (2, 2, 1), (4, 1, 1), (1, 1, 4), (1, 4, 2), (2, 2, 2), (4, 1, 2), (2, 4, 1), (4, 2, 1))
+EIGHT_WAVE_FAMILY = {(128, 64, 2, 4), (64, 128, 4, 2), (64, 64, 2, 4), (64, 64, 4, 2)}      # (wm, wn, gm, gn)
+
+
+def eight_waves(u):
+    """Workgroups of eight waves (two teams, or an eight-wave grid) run in kernels of their own: the
+    uKernels of one launch are all of one kind."""
+    return u.gk == 2 or u.gm * u.gn == 8
 TWO_TEAM_STAGE_MAX = 40960                  # both teams' rings of two stages fit the LDS
 TWO_TEAM_ACC_MAX = 64                       # accumulator registers per lane of a two-team wave
 TK_CHOICES = (64,)                          # 64 16-bit elements = one 128-byte line
@@ -251,7 +260,8 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
     gbytes = (tm + tn) * k_ref * ELT + tm * tn * out_bytes    # data_r + data_w
     sbytes = (tm + tn) * k_ref * ELT + k_ref * ELT * (tm * gn + tn * gm)   # data_tw + data_tr
     nk = ceil_div(k_ref, tk)
-    r = residents if residents >= 2 else 1
+    # (an eight-wave grid has two waves per SIMD by itself: its phases overlap as those of two workgroups do)
+    r = residents if residents >= 2 else (2 if gm * gn == 8 else 1)
     if gk == 2:
         # over the common denominator F * G * S * r
         c2 = flops * G * S * r
@@ -343,7 +353,9 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 continue
             if gk == 2 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM or ceil_div(k_ref, TK_CHOICES[0]) < 4):
                 continue                            # (each team wants at least two k-tiles)
-            waves_per_simd = 2 if gk == 2 else 1    # 4 waves on 4 SIMDs, or 8
+            if gm * gn == 8 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM or (wm, wn, gm, gn) not in EIGHT_WAVE_FAMILY):
+                continue
+            waves_per_simd = 2 if (gk == 2 or gm * gn == 8) else 1    # 4 waves on 4 SIMDs, or 8
             for tk in TK_CHOICES:
                 tm, tn = gm * wm, gn * wn
                 if gk == 2 and ((tm + tn) * tk * ELT > TWO_TEAM_STAGE_MAX or wm * wn // 64 > TWO_TEAM_ACC_MAX):
@@ -387,7 +399,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
         cand, kept = [u for u, ok in zip(cand, psi_ok) if ok], [k for k, ok in zip(kept, psi_ok) if ok]
     if any(kept):
         cand = [u for u, k in zip(cand, kept) if k]
-    cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn, u.gk))
+    cand.sort(key=lambda u: (-(u.tm * u.tn), -u.tm, -u.tn, -u.tk, -u.wm, -u.wn, u.gk, -u.gm))
     for i, u in enumerate(cand):
         u.id = i
     return cand
@@ -520,8 +532,8 @@ def split_allowed(parts, uks, K, k_parts, t, hw, tiles):
         return True
     if k_parts > t.get("k_parts_max", 1):
         return False
-    if any(uks[uid].acc_regs > KPART_ACC_MAX or uks[uid].gk == 2 for uid, _ in parts):
-        return False                                   # (two teams already split the reduce axis)
+    if any(uks[uid].acc_regs > KPART_ACC_MAX or eight_waves(uks[uid]) for uid, _ in parts):
+        return False                                   # (four-wave bodies only)
     per_cu = min([t["zeta"]] + [uks[uid].max_wg_per_cu for uid, _ in parts])
     if tiles * k_parts > hw["num_cus"] * per_cu:
         return False
@@ -549,7 +561,7 @@ def strip_choices(u, uks, Wp, tau):
         return []
     cands = [v for v in uks
              if _ext(v, tau) == _ext(u, tau) and _ext(v, 1 - tau) < e and ceil_by(rem, _ext(v, 1 - tau)) < e
-             and (v.gk == 2) == (u.gk == 2)]
+             and eight_waves(v) == eight_waves(u)]
     cands.sort(key=lambda v: (-_ext(v, 1 - tau), v.id))
     return [(v.id, n_full, ceil_div(rem, _ext(v, 1 - tau))) for v in cands[:STRIP_CHOICES]]
 
@@ -756,7 +768,7 @@ def plan(op: Op, uks: List[UKernel], shape, mode=PLAN_PATCHWORK, hw=None, t=None
         pl.pool_size, pl.level = 1, 0 if prog.in_bound else 1
     else:
         Hp = ceil_by(M if tau == 0 else N, GRANULE)
-        covers = build_pool([_ext(u, tau) for u in uks], Hp, kinds=[u.gk == 2 for u in uks])
+        covers = build_pool([_ext(u, tau) for u in uks], Hp, kinds=[eight_waves(u) for u in uks])
         if not covers:
             # Alg. 2 found nothing (the main axis is shorter than every extent the static
             # axes admit): pad it up to the uKernel with the smallest main-axis extent

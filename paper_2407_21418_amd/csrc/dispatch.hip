@@ -222,6 +222,14 @@ __global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs
         FT_FAMILY_PARTIAL(FT_X)
 #endif
 #undef FT_X
+#if defined(FT_PP) && FT_CLASS == 1
+#define FT_X(CODE, WM, WN, GM, GN, TWIN)                                        \
+    case CODE:                                                                  \
+        UKernelFast<FT_DT, WM, WN, GM, GN, 1>::run(g, d, smem, stages, t, part); \
+        break;
+        FT_FAMILY_W8(FT_X)
+#undef FT_X
+#endif
 #if !defined(FT_GENERIC) && !defined(FT_PP)
 #define FT_X(CODE, TM, TN, TWIN)                                                \
     case CODE:                                                                  \

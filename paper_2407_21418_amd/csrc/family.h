@@ -27,6 +27,12 @@
 // X(code, WM, WN, GM, GN) with GM*GN < 4.  Compiled into the general dispatcher only.
 #define FT_FAMILY_PARTIAL(X) X(37, 16, 16, 1, 2) X(38, 16, 16, 1, 1)
 
+// Eight-wave grids (2 x 4 or 4 x 2 waves, two per SIMD, all on the same k-tile): X(code, WM, WN, GM, GN,
+// twin) with twin = the four-wave body of the same tile, which the general path runs instead.
+#define FT_FAMILY_W8(X)                                                                  \
+    X(40, 128, 64, 2, 4, 28) X(41, 64, 128, 4, 2, 28) X(42, 64, 64, 2, 4, 22) X(43, 64, 64, 4, 2, 25)
+#define FT_W8_ACC_MAX 128
+
 // Two-team ("ping-pong") workgroups of eight waves run the standard-grid bodies above, gk = 2: both
 // teams' rings of at least two stages must fit the LDS and each wave keeps at most 64 accumulator
 // registers (two waves per SIMD in a 256-register kernel; class 0: <= 32 in 128 registers).
@@ -44,6 +50,12 @@
 static inline int ft_class_of_acc(int acc_regs) { return acc_regs <= 32 ? 0 : (acc_regs <= 128 ? 1 : 2); }
 static inline int ft_body_code(int wm, int wn, int gm, int gn, int gk) {
     if (gk == 2 && ((gm * wm + gn * wn) * FT_TK * 2 > FT_PP_STAGE_MAX || wm * wn / 64 > FT_PP_ACC_MAX)) return -1;
+    if (gk == 1 && gm * gn == 8) {
+#define FT_X(code, WM, WN, GM, GN, TWIN) if (wm == WM && wn == WN && gm == GM && gn == GN) return code;
+        FT_FAMILY_W8(FT_X)
+#undef FT_X
+        return -1;
+    }
     if (gk == 1 || gk == 2) {            // two teams (gk = 2) run the standard-grid body of the same code
 #define FT_X(code, WM, WN, GM, GN) if (wm == WM && wn == WN && gm == GM && gn == GN) return code;
         FT_FAMILY(FT_X)
@@ -57,6 +69,9 @@ static inline int ft_body_code(int wm, int wn, int gm, int gn, int gk) {
 }
 // LDS bytes of one stage (A tile + B tile, tk = 64, 16-bit elements) of the body with this code
 static inline uint32_t ft_stage_bytes_of_code(int code) {
+#define FT_X(c, WM, WN, GM, GN, TWIN) if (code == c) return (uint32_t)(((GM) * (WM) + (GN) * (WN)) * FT_TK * 2);
+    FT_FAMILY_W8(FT_X)
+#undef FT_X
 #define FT_X(c, WM, WN, GM, GN) if (code == c) return (uint32_t)(((GM) * (WM) + (GN) * (WN)) * FT_TK * 2);
     FT_FAMILY(FT_X)
     FT_FAMILY_PARTIAL(FT_X)
@@ -68,6 +83,9 @@ static inline uint32_t ft_stage_bytes_of_code(int code) {
 }
 // accumulator registers per lane of the body with this code
 static inline int ft_acc_of_code(int code) {
+#define FT_X(c, WM, WN, GM, GN, TWIN) if (code == c) return (WM) * (WN) / 64;
+    FT_FAMILY_W8(FT_X)
+#undef FT_X
 #define FT_X(c, WM, WN, GM, GN) if (code == c) return (WM) * (WN) / 64;
     FT_FAMILY(FT_X)
     FT_FAMILY_PARTIAL(FT_X)
@@ -86,6 +104,9 @@ static inline int ft_is_partial_code(int code) {
 }
 // body the general path runs for a given code (split-k codes map to their standard-grid twin)
 static inline int ft_general_code(int code) {
+#define FT_X(c, WM, WN, GM, GN, TWIN) if (code == c) return TWIN;
+    FT_FAMILY_W8(FT_X)
+#undef FT_X
 #define FT_X(c, TM, TN, TWIN) if (code == c) return TWIN;
     FT_FAMILY_SPLITK(FT_X)
 #undef FT_X

@@ -179,6 +179,12 @@ __device__ __forceinline__ bool k_part_exchange_blocks(const KArgs &g, uint32_t 
 template <int DT, int WM, int WN, int GM, int GN, int TEAMS = 1>
 struct UKernelFast {
     static_assert(TEAMS == 1 || TEAMS == 2, "one team of four waves, or two");
+    // A single team may also be a grid of EIGHT waves (GM * GN = 8, two per SIMD) that share every
+    // k-tile: a 256 x 256 tile then costs a wave 128 accumulator registers instead of 256, and while
+    // one wave of a SIMD is held up issuing copies or waiting for fragments the other runs MFMAs.
+    static constexpr int NWT = GM * GN;               // waves of a team
+    static_assert(NWT == 4 || (NWT == 8 && TEAMS == 1) || NWT == 1,
+                  "four waves per team; eight in a single team (a 1 x 1 grid lends its fragment helpers to the split-k bodies)");
     static constexpr int TK = 64;
     static constexpr int TM = GM * WM, TN = GN * WN;
     static constexpr bool M16 = (WM == 16);
@@ -188,9 +194,9 @@ struct UKernelFast {
     static constexpr int BM = WM / MB, BN = WN / MB;
     static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TK * TN * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    // wave-level copy instructions per stage: each wave moves a quarter of A's rows and a quarter
-    // of B's rows (16 k-rows); a quarter smaller than 1 KB is moved by the low lanes only
-    static constexpr int A_WAVE_BYTES = A_BYTES / 4, B_WAVE_BYTES = B_BYTES / 4;
+    // wave-level copy instructions per stage: each wave of the team moves an equal share of A's rows
+    // and of B's rows; a share smaller than 1 KB is moved by the low lanes only
+    static constexpr int A_WAVE_BYTES = A_BYTES / (NWT == 1 ? 4 : NWT), B_WAVE_BYTES = B_BYTES / (NWT == 1 ? 4 : NWT);
     static constexpr int LA = (A_WAVE_BYTES + 1023) / 1024, LB = (B_WAVE_BYTES + 1023) / 1024;
     static constexpr int L = LA + LB;                 // vmcnt increments per stage per wave
     static constexpr int MAX_AHEAD = (63 / L) < 6 ? (63 / L) : 6;   // tiles in flight beyond the current
@@ -384,7 +390,7 @@ struct UKernelFast {
         // ---- epilogue ------------------------------------------------------------------------------
         FT_MARK(g, 5);
         // (bodies with more than 128 accumulator registers have no room for it: the host never splits them)
-        if constexpr (WM * WN / 64 <= FT_KPART_ACC_MAX) if (g.k_parts > 1) {
+        if constexpr (WM * WN / 64 <= FT_KPART_ACC_MAX && NWT == 4) if (g.k_parts > 1) {
             if (!k_part_exchange_blocks<M16>(g, t, part, wave, lane, acc)) return;
         }
         FT_MARK(g, 6);

@@ -77,6 +77,7 @@ Gemm static_view(const ft_op_desc &d) {
 //       K_mem = max(t_ce, t_g, t_s) + t_l / residents
 //   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
 //       K_mem = t_ce + solo_copy_exposed_pct % of t_g + t_l
+//   eight waves on the same k-tiles (gm * gn = 8): as residents = 2 even when alone on the CU
 //   two teams (gk = 2, eight waves): a SIMD holds one wave of each team; while one runs the MFMAs of its
 //       k-tile the other issues copies, one s_barrier per k-tile:
 //       K_mem = max(t_c, t_g, t_s) + phase_latency_clk * nk / residents
@@ -90,7 +91,8 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk
     const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * out_bytes;                // data_r + data_w
     const u128 sbytes = (u128)(tm + tn) * kref * ELT + (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
     const u128 nk = ceil_div(kref, tk);
-    const u128 r = residents >= 2 ? residents : 1;
+    // (an eight-wave grid has two waves per SIMD by itself: its phases overlap as those of two workgroups do)
+    const u128 r = residents >= 2 ? residents : (gm * gn == 8 ? 2 : 1);
     const u128 ed = 100;
     if (gk == 2) {
         // over the common denominator F * G * S * r
@@ -156,6 +158,9 @@ struct Program {
 };
 
 inline uint32_t ext(const ft_ukernel_info &u, uint32_t axis) { return axis == 0 ? u.tm : u.tn; }
+// workgroups of eight waves (two teams, or an eight-wave grid) run in kernels of their own: one launch,
+// one workgroup size
+inline bool eight_waves(const ft_ukernel_info &u) { return u.gk == 2 || u.gm * u.gn == 8; }
 
 // Reduce-axis split (occupancy rescue): k-tiles per part when the nk = ceil(K / tk) k-tiles are
 // dealt out in equal runs.
@@ -341,7 +346,7 @@ bool split_allowed(const Program &p, const ft_ukset &set, uint64_t K, uint32_t k
     uint32_t per_cu = set.t.zeta;
     for (uint32_t i = 0; i < p.nparts; ++i) {
         const ft_ukernel_info &u = set.uk[p.part[i].id];
-        if (u.acc_regs > FT_KPART_ACC_MAX || u.gk == 2) return false;   // (two teams already split the reduce axis)
+        if (u.acc_regs > FT_KPART_ACC_MAX || eight_waves(u)) return false;   // (four-wave bodies only)
         per_cu = std::min(per_cu, u.max_wg_per_cu);
     }
     if (p.tiles * k_parts > (uint64_t)set.hw.num_cus * per_cu) return false;
@@ -363,7 +368,7 @@ uint32_t strip_choices(const ft_ukernel_info &u, const ft_ukset &set, uint64_t W
     std::vector<const ft_ukernel_info *> c;
     for (const ft_ukernel_info &v : set.uk)
         if (ext(v, tau) == ext(u, tau) && ext(v, 1 - tau) < e && ceil_by(rem, ext(v, 1 - tau)) < e &&
-            (v.gk == 2) == (u.gk == 2)) c.push_back(&v);
+            eight_waves(v) == eight_waves(u)) c.push_back(&v);
     std::stable_sort(c.begin(), c.end(), [&](const ft_ukernel_info *a, const ft_ukernel_info *b) {
         if (ext(*a, 1 - tau) != ext(*b, 1 - tau)) return ext(*a, 1 - tau) > ext(*b, 1 - tau);
         return a->id < b->id;
@@ -417,7 +422,7 @@ void build_pool(const ft_ukset &set, uint64_t Hp, uint32_t tau, std::vector<Prog
             for (size_t i2 = 0; i2 < n; ++i2) {
                 uint64_t e2 = ext(set.uk[i2], tau);
                 // (one launch has one workgroup size: two-team uKernels pair with two-team uKernels)
-                if (e2 != e1 && rem % e2 == 0 && (set.uk[i1].gk == 2) == (set.uk[i2].gk == 2)) {
+                if (e2 != e1 && rem % e2 == 0 && eight_waves(set.uk[i1]) == eight_waves(set.uk[i2])) {
                     Program p{};
                     p.nparts = 2;
                     p.part[0] = {(uint32_t)i1, (uint32_t)n1};
@@ -682,7 +687,9 @@ static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, co
     // tile and a quarter of k (accumulator tiles of 1024..4096 elements only)
     // (gk = 2: the standard grids again as two teams of four waves that take alternate k-tiles, Matmul
     // and Conv2d only: grouped batched launches run workgroups of four waves)
-    static const uint32_t grids[7][3] = {{1, 4, 1}, {2, 2, 1}, {4, 1, 1}, {1, 1, 4}, {1, 4, 2}, {2, 2, 2}, {4, 1, 2}};
+    // (gm * gn = 8: eight waves, two per SIMD, on the same k-tiles -- the large tiles at half the accumulator
+    // registers per wave)
+    static const uint32_t grids[9][3] = {{1, 4, 1}, {2, 2, 1}, {4, 1, 1}, {1, 1, 4}, {1, 4, 2}, {2, 2, 2}, {4, 1, 2}, {2, 4, 1}, {4, 2, 1}};
     for (uint32_t wm : sizes)
         for (uint32_t wn : sizes) {
             uint32_t mfma;
@@ -694,13 +701,14 @@ static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, co
                 uint32_t tm = gm * wm, tn = gn * wn;
                 if (gk == 4 && (wm * wn < 256 || wm * wn > 4096)) continue;
                 if (gk == 2 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM || ceil_div(kref, FT_TK) < 4)) continue;   // (each team wants at least two k-tiles)
+                if (gm * gn == 8 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM)) continue;
                 if (ft_body_code(wm, wn, gm, gn, gk) < 0) continue;      // no compiled body
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;
                 if (sv.n && ceil_by(sv.n, GRANULE) % tn) continue;
                 uint32_t acc = wm * wn / h.wave_size;
                 uint32_t regs = acc + t.rest_regs;
-                const uint32_t waves_per_simd = gk == 2 ? 2 : 1;
+                const uint32_t waves_per_simd = (gk == 2 || gm * gn == 8) ? 2 : 1;
                 if (regs * waves_per_simd > h.regs_per_lane) continue;   // Eq. 4 at block.bound = 1
                 // registers are granted in power-of-two fractions of the file (128, 256, 512)
                 uint32_t budget = h.regs_per_lane / 4;
@@ -765,7 +773,8 @@ static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, co
         if (a.tk != b.tk) return a.tk > b.tk;
         if (a.wm != b.wm) return a.wm > b.wm;
         if (a.wn != b.wn) return a.wn > b.wn;
-        return a.gk < b.gk;
+        if (a.gk != b.gk) return a.gk < b.gk;
+        return a.gm > b.gm;
     });
     set->cap_q = 0;
     for (size_t i = 0; i < set->uk.size(); ++i) {
@@ -922,7 +931,7 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
         if (forced->count2) {
             if (forced->k2 >= set->uk.size() || forced->k2 == forced->k1) return FT_ERR_INVALID_ARG;
             total += (uint64_t)forced->count2 * ext(set->uk[forced->k2], tau);
-            if ((set->uk[forced->k1].gk == 2) != (set->uk[forced->k2].gk == 2)) return FT_ERR_INVALID_ARG;
+            if (eight_waves(set->uk[forced->k1]) != eight_waves(set->uk[forced->k2])) return FT_ERR_INVALID_ARG;
             best.nparts = 2;
             best.part[1] = {forced->k2, forced->count2};
             best.k2 = forced->k2;
@@ -935,7 +944,7 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
             if (forced->k_parts > 64) return FT_ERR_INVALID_ARG;
             bool room = op->d.kind != FT_OP_CONV2D && r.K % 8 == 0 && r.N % 8 == 0;    // the split runs in the LDS-DMA Matmul bodies only
             for (uint32_t i = 0; i < best.nparts; ++i)
-                room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX && set->uk[best.part[i].id].gk != 2;
+                room = room && set->uk[best.part[i].id].acc_regs <= FT_KPART_ACC_MAX && !eight_waves(set->uk[best.part[i].id]);
             if (room) {
                 const uint64_t nk = std::max<uint64_t>(ceil_div(r.K, FT_TK), 1);
                 const uint64_t per = ceil_div(nk, std::min<uint64_t>(forced->k_parts, nk));
@@ -1022,7 +1031,7 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
     for (uint32_t i = 0; i < 2; ++i) { s.strip_ukernel_id[i] = UINT32_MAX; s.strip_tiles[i] = 0; s.main_tiles[i] = 0; }
     // slots 0, 1: the parts (the launch order is computed on their tile grids); 2, 3: strips
     auto set_slot = [&](uint32_t slot, const ft_ukernel_info &u) {
-        if (u.gk == 2) pl->two_teams = true;
+        if (eight_waves(u)) pl->two_teams = true;
         pl->slot_id[slot] = u.id;
         pl->slot_code[slot] = (uint32_t)ft_body_code(u.wm, u.wn, u.gm, u.gn, u.gk);
         pl->slot_stages[slot] = u.stages;

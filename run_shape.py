@@ -23,6 +23,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--force", default="")
     ap.add_argument("--k-parts", type=int, default=0, help="with --force: workgroups per tile along the reduce axis")
+    ap.add_argument("--waves", type=int, default=4, choices=[4, 8], help="with --force: 8 picks the eight-wave grid of that tile")
     ap.add_argument("--teams", type=int, default=1, choices=[1, 2], help="with --force: 2 picks the eight-wave two-team uKernel of that tile")
     ap.add_argument("--baseline", action="store_true")
     ap.add_argument("--zeta", type=int, default=0, help="override the tuning's zeta (workgroups per CU)")
@@ -45,7 +46,7 @@ def main():
     if a.force:
         want = tuple(int(x) for x in a.force.split(","))
         ids = [i for i in range(ft.ft_ukset_size(uks))
-               if (lambda u: (u.tm, u.tn, u.wm, u.wn) == want and (u.gk == 2) == (a.teams == 2))(ft.ft_ukset_get(uks, i))]
+               if (lambda u: (u.tm, u.tn, u.wm, u.wn) == want and (u.gk == 2) == (a.teams == 2) and u.gm * u.gn == (8 if a.waves == 8 else 4))(ft.ft_ukset_get(uks, i))]
         if not ids:
             raise SystemExit("uKernel %s is not in the derived set" % (want,))
         mode, forced = ft.FT_PLAN_FORCED, ft.ft_forced_program(k1=ids[0], count1=-(-a.m // want[0] * want[0] // want[0]))

@@ -80,7 +80,7 @@ def main():
             us_ = [infos[e.k1]] + ([infos[e.k2]] if e.count2 else [])
             per_cu = min([tuning.zeta] + [u.max_wg_per_cu for u in us_])
             kps = [1] + [kp for kp in KP_CHOICES
-                         if all(u.acc_regs <= 128 and u.gk != 2 for u in us_) and e.n_tiles * kp <= hw.num_cus * per_cu
+                         if all(u.acc_regs <= 128 and u.gk != 2 and u.gm * u.gn != 8 for u in us_) and e.n_tiles * kp <= hw.num_cus * per_cu
                          and nk // kp >= tuning.k_part_min_tiles and -(-nk // -(-nk // kp)) == kp and kp <= tuning.k_parts_max]
             for kp in kps:
                 fp = ft.ft_forced_program(k1=e.k1, count1=e.count1, k2=(e.k2 if e.count2 else 0), count2=e.count2, k_parts=kp)
@@ -96,7 +96,7 @@ def main():
         best = min(res, key=lambda r: r["us"])
 
         def name(r):
-            s = " + ".join("%dx(%dx%d w%dx%d gk%d)" % (c, u["tm"], u["tn"], u["wm"], u["wn"], u["gk"]) for (_, c), u in zip(r["parts"], r["uk"]))
+            s = " + ".join("%dx(%dx%d w%dx%d g%dx%dx%d)" % (c, u["tm"], u["tn"], u["wm"], u["wn"], u["gm"], u["gn"], u["gk"]) for (_, c), u in zip(r["parts"], r["uk"]))
             return s + (" / %d parts" % r["kp"] if r["kp"] > 1 else "")
         pk = [r for r in res if r["pick"]]
         us_pick = pk[0]["us"] if pk else timed(pick_plan)          # the same program, timed in its turn

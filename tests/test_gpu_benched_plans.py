@@ -136,3 +136,31 @@ def test_every_two_team_body(body, dtype):
         assert ft.ft_plan_stats_get(plan).n_tiles == 8
         ref, refabs = oc.matmul(A, B, dtype, want_abs=True)
         check(run(plan, A, B, M * N), ref, refabs, f"two-team body {body} K {K} dtype {dtype}")
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+@pytest.mark.parametrize("body", sorted(P.EIGHT_WAVE_FAMILY), ids=lambda b: "w%dx%d_g%dx%d" % b)
+def test_every_eight_wave_grid_body(body, dtype):
+    """The eight-wave grids (two waves per SIMD on the same k-tiles; tiles of 256 x 256, 128 x 256 and
+    256 x 128), each alone as a forced program: 2 x 4 tiles with ragged tails, a k tail, one k-tile."""
+    wm, wn, gm, gn = body
+    tm, tn = wm * gm, wn * gn
+    for K in (200, 712, 64):
+        N, M = 4 * tn - 24, 2 * tm - 5
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dtype, n=N, k=K, m_lo=0, m_hi=1 << 16))
+        s = ft.ft_ukernels_derive(op)
+        ids = [i for i in range(ft.ft_ukset_size(s))
+               if (lambda u: (u.tm, u.tn, u.wm, u.wn, u.gm, u.gn, u.gk) == (tm, tn, wm, wn, gm, gn, 1))(ft.ft_ukset_get(s, i))]
+        if not ids:             # a static N that the tile does not divide after rounding to 16: use one it divides
+            N = 4 * tn
+            op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dtype, n=N, k=K, m_lo=0, m_hi=1 << 16))
+            s = ft.ft_ukernels_derive(op)
+            ids = [i for i in range(ft.ft_ukset_size(s))
+                   if (lambda u: (u.tm, u.tn, u.wm, u.wn, u.gm, u.gn, u.gk) == (tm, tn, wm, wn, gm, gn, 1))(ft.ft_ukset_get(s, i))]
+        assert len(ids) == 1, (body, K)
+        g = np.random.default_rng(wm + wn + gm + K + dtype)
+        A = si.normal_bits(g, (M, K), 1.0, dtype)
+        B = si.normal_bits(g, (K, N), 1.0, dtype)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED, ft.ft_forced_program(k1=ids[0], count1=2))
+        ref, refabs = oc.matmul(A, B, dtype, want_abs=True)
+        check(run(plan, A, B, M * N), ref, refabs, f"eight-wave body {body} K {K} dtype {dtype}")

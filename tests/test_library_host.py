@@ -231,7 +231,7 @@ def test_pool_scores_match_oracle(name):
             continue
         tau = P.main_axis(op, M, N)
         Hp = P.ceil_by(M if tau == 0 else N, 16)
-        want = P.build_pool([u.tm if tau == 0 else u.tn for u in uks], Hp, kinds=[u.gk == 2 for u in uks])
+        want = P.build_pool([u.tm if tau == 0 else u.tn for u in uks], Hp, kinds=[P.eight_waves(u) for u in uks])
         got = ft.ft_plan_pool(lop, s, ft.ft_shape(**kw))
         assert len(got) == len(want)
         for g, parts in zip(got, want):

@@ -349,7 +349,7 @@ def test_sia_is_the_weighted_sum_and_top1_is_max():
     cap = P.cmr_cap(uks)
     shape = (1, 528, 3072, 768)
     pool = [P.evaluate(p, uks, 1, 528, 3072, 0, hw, t2, cap)
-            for p in P.build_pool([u.tm for u in uks], 528, kinds=[u.gk == 2 for u in uks])]
+            for p in P.build_pool([u.tm for u in uks], 528, kinds=[P.eight_waves(u) for u in uks])]
     for p in pool:
         assert p.sia_q == 3 * p.cmr_q + 5 * p.pad_q + 7 * p.occ_q
         assert 0 <= p.cmr_q <= 1 << 20 and 0 < p.pad_q <= 1 << 20 and 0 < p.occ_q <= 1 << 20
@@ -526,7 +526,7 @@ def test_every_strip_variant_is_an_exact_cover_and_pads_no_more():
     checked = 0
     for L in (33, 100, 141, 257):
         Hp = P.ceil_by(L, 16)
-        for parts in P.build_pool([u.tm for u in uks], Hp, kinds=[u.gk == 2 for u in uks])[::7]:
+        for parts in P.build_pool([u.tm for u in uks], Hp, kinds=[P.eight_waves(u) for u in uks])[::7]:
             whole = P.evaluate(parts, uks, 2, L, L, 0, hw, t, cap)
             for strips in P.strip_variants(parts, uks, Hp, 0):
                 p = P.evaluate(parts, uks, 2, L, L, 0, hw, t, cap, strips=strips)

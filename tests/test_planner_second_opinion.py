@@ -47,7 +47,7 @@ def second_compute_eff(u, k_extent, residents, out_bytes, hw, exchange=0):
     data_tr = k_extent * 2 * (u.tm * u.gn + u.tn * u.gm)
     t_s = Fr(data_tw + data_tr, hw["bw_lds_bytes_per_clk_per_cu"])
     nk = -(-k_extent // u.tk)
-    res = residents if residents >= 2 else 1
+    res = residents if residents >= 2 else (2 if u.gm * u.gn == 8 else 1)      # eight waves overlap by themselves
     if u.gk == 2:
         k_mem = max(t_c, t_g, t_s) + Fr(hw["phase_latency_clk"] * nk + exchange, res)
         return t_c / k_mem
@@ -158,7 +158,7 @@ def test_second_opinion_equals_oracle_and_library(two_team):
         hw, t, uks = _oracle_side(op, two_team)
         tau = P.main_axis(op, M, N)
         Hp = P.ceil_by(M if tau == 0 else N, P.GRANULE)
-        pool = P.build_pool([P._ext(u, tau) for u in uks], Hp, kinds=[u.gk == 2 for u in uks])
+        pool = P.build_pool([P._ext(u, tau) for u in uks], Hp, kinds=[P.eight_waves(u) for u in uks])
         if not pool:
             continue
         cap_q = P.cmr_cap(uks)

@@ -28,6 +28,7 @@ def main():
     ap.add_argument("--k", type=int, required=True)
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--force", default="")
+    ap.add_argument("--waves", type=int, default=4, choices=[4, 8], help="with --force: 8 picks the eight-wave grid of that tile")
     ap.add_argument("--teams", type=int, default=1, choices=[1, 2])
     ap.add_argument("--k-parts", type=int, default=0)
     ap.add_argument("--ring-mb", type=float, default=700.0)
@@ -49,7 +50,7 @@ def main():
     if a.force:
         want = tuple(int(x) for x in a.force.split(","))
         ids = [i for i in range(ft.ft_ukset_size(uks))
-               if (lambda u: (u.tm, u.tn, u.wm, u.wn) == want and (u.gk == 2) == (a.teams == 2))(ft.ft_ukset_get(uks, i))]
+               if (lambda u: (u.tm, u.tn, u.wm, u.wn) == want and (u.gk == 2) == (a.teams == 2) and u.gm * u.gn == (8 if a.waves == 8 else 4))(ft.ft_ukset_get(uks, i))]
         if not ids:
             raise SystemExit("uKernel %s is not in the derived set" % (want,))
         mode = ft.FT_PLAN_FORCED
