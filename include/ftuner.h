@@ -115,7 +115,9 @@ typedef struct ft_tuning {
     /* Two-team bodies (Sec. 3: a uKernel is one thread block; Fig. 7: its thread-level tiling): the
      * standard wave grids again with EIGHT waves, two teams of four that take alternate k-tiles of
      * the same tile, so that one team's copies overlap the other's MFMAs (gk = 2 in
-     * ft_ukernel_info).  Matmul and Conv2d.                                                     */
+     * ft_ukernel_info).  Matmul and Conv2d.  The same switch derives the eight-wave GRIDS (gm*gn = 8,
+     * gk = 1: tiles of 256x256, 128x256 and 256x128 whose eight waves share every k-tile), Matmul only.
+     * Against block.bound an eight-wave grid counts twice: one workgroup puts two waves on each SIMD. */
     uint32_t two_team_bodies;                       /* 1: derive them (default), 0: four-wave bodies only */
 } ft_tuning;
 enum { FT_SIA_LINEAR = 0, FT_SIA_PRODUCT = 1 };
@@ -171,7 +173,8 @@ typedef struct ft_ukernel_info {
     uint32_t tm, tn, tk;           /* smem_tile: workgroup tile staged in LDS                */
     uint32_t wm, wn;               /* reg_tile: per-wave fp32 accumulator tile               */
     uint32_t gm, gn, gk;           /* wave grid over rows, columns, reduce axis: gm*gn*gk = 4 waves, or
-                                      gk = 2 with gm*gn = 4: two teams of four waves (eight in all)  */
+                                      gk = 2 with gm*gn = 4: two teams of four waves (eight in all), or
+                                      gm*gn = 8 with gk = 1: eight waves on the same k-tiles          */
     uint32_t mfma;                 /* 0: 32x32x16, 1: 16x16x32                               */
     uint32_t stages;               /* LDS ring depth: k-tiles resident at once (2..8), per wave for
                                       gk = 4 and per team for gk = 2                          */

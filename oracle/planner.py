@@ -236,6 +236,13 @@ MIN_STAGES, MAX_STAGES = 2, 8
 ELT = 2
 
 
+def waves_bound(u):
+    """What a uKernel offers against block.bound (Alg. 1: workgroups a CU should hold): its residency,
+    doubled for an eight-wave grid, whose one workgroup already puts two waves on every SIMD.  A
+    two-team workgroup also has eight waves, but its teams alternate on the k-tiles: it counts once."""
+    return u.max_wg_per_cu * (2 if u.gm * u.gn == 8 else 1)
+
+
 def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4, exchange_clk=0):
     """Eq. 6 / Eq. 7: (FLOPs / FLOPS) : K_mem, with K_mem read on gfx950 as the time the
     uKernel's k loop needs, so the ratio is the fraction of that time the MFMA pipes are busy.
@@ -249,6 +256,11 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
       * residents == 1: the one wave of a SIMD issues its global->LDS copies and its MFMAs
         itself; a fraction solo_copy_exposed_pct of the copy time is not hidden:
             K_mem = t_ce + exposed * t_g + t_l
+      * an eight-wave grid (gm * gn == 8) alone on its CU: the two waves of a SIMD pass the
+        workgroup's barriers together; they read their fragments at the same time (t_s at half the
+        LDS rate), half of the solo share of the copy time stays exposed, and the k-tile latency
+        is shared by the two waves but not hidden:
+            K_mem = max(t_c, 2 t_s) + exposed / 2 * t_g + 2/3 t_l
       * two teams (gk == 2): a SIMD holds one wave of each team, copies and MFMAs of the two overlap
         and every k-tile ends with one barrier:
             K_mem = max(t_c, t_g, t_s) + phase_latency_clk * nk / residents
@@ -260,8 +272,12 @@ def compute_eff(tm, tn, gm, gn, k_ref, hw, gk=1, tk=64, residents=1, out_bytes=4
     gbytes = (tm + tn) * k_ref * ELT + tm * tn * out_bytes    # data_r + data_w
     sbytes = (tm + tn) * k_ref * ELT + k_ref * ELT * (tm * gn + tn * gm)   # data_tw + data_tr
     nk = ceil_div(k_ref, tk)
-    # (an eight-wave grid has two waves per SIMD by itself: its phases overlap as those of two workgroups do)
-    r = residents if residents >= 2 else (2 if gm * gn == 8 else 1)
+    r = residents
+    if gm * gn == 8 and gk == 1 and residents < 2:
+        # over the common denominator F * G * S * 600
+        c8 = flops * G * S * 600
+        return c8, (max(c8, sbytes * F * G * 1200) + gbytes * F * S * 3 * hw["solo_copy_exposed_pct"]
+                    + (hw["ktile_latency_clk"] * nk + exchange_clk) * F * G * S * 400)
     if gk == 2:
         # over the common denominator F * G * S * r
         c2 = flops * G * S * r
@@ -353,7 +369,7 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
                 continue
             if gk == 2 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM or ceil_div(k_ref, TK_CHOICES[0]) < 4):
                 continue                            # (each team wants at least two k-tiles)
-            if gm * gn == 8 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM or (wm, wn, gm, gn) not in EIGHT_WAVE_FAMILY):
+            if gm * gn == 8 and (not t.get("two_team_bodies", 0) or op.kind != OP_MATMUL or (wm, wn, gm, gn) not in EIGHT_WAVE_FAMILY):
                 continue
             waves_per_simd = 2 if (gk == 2 or gm * gn == 8) else 1    # 4 waves on 4 SIMDs, or 8
             for tk in TK_CHOICES:
@@ -623,7 +639,7 @@ def evaluate(parts, uks, batch, M, N, tau, hw, t, cap_q, k_parts=1, K=0, out_byt
     # SetBound (Alg. 1): block.bound = min(K.wkl.block, zeta)
     p.block_bound = min(max(1, ceil_div(Wg, hw["num_cus"])), t["zeta"])
     ids = [c[0] for c in cons]
-    p.in_bound = all(uks[uid].max_wg_per_cu >= p.block_bound for uid in ids)
+    p.in_bound = all(waves_bound(uks[uid]) >= p.block_bound for uid in ids)
     occ = occ_fraction(Wg, hw["num_cus"])
     pad = pad_fraction(M * N, area)
     p.occ_q = (occ[0] << Q) // occ[1]

@@ -311,6 +311,8 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
                           : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
     if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
         for (int i = 0; i < 4; ++i) {
+            // (the planner derives no eight-wave grid for a convolution: its twin would run in the wrong kernel)
+            if (a.is_conv && ft_is_w8_code((int)a.slot_code[i])) return FT_ERR_UNSUPPORTED;
             a.slot_code[i] = (uint32_t)ft_general_code((int)a.slot_code[i]);
             // the twins of the narrowest tiles exist in the general dispatcher only
             if (ft_is_partial_code((int)a.slot_code[i])) fast = false;

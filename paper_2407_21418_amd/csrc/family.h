@@ -102,6 +102,13 @@ static inline int ft_is_partial_code(int code) {
 #undef FT_X
     return 0;
 }
+// an eight-wave grid body
+static inline int ft_is_w8_code(int code) {
+#define FT_X(c, WM, WN, GM, GN, TWIN) if (code == c) return 1;
+    FT_FAMILY_W8(FT_X)
+#undef FT_X
+    return 0;
+}
 // body the general path runs for a given code (split-k codes map to their standard-grid twin)
 static inline int ft_general_code(int code) {
 #define FT_X(c, WM, WN, GM, GN, TWIN) if (code == c) return TWIN;

@@ -77,7 +77,11 @@ Gemm static_view(const ft_op_desc &d) {
 //       K_mem = max(t_ce, t_g, t_s) + t_l / residents
 //   residents == 1: the single wave of a SIMD issues copies and MFMAs itself,
 //       K_mem = t_ce + solo_copy_exposed_pct % of t_g + t_l
-//   eight waves on the same k-tiles (gm * gn = 8): as residents = 2 even when alone on the CU
+//   eight waves on the same k-tiles (gm * gn = 8), alone on the CU: the two waves of a SIMD pass the
+//       workgroup's barriers together, so they read their fragments at the same time (t_s at half the
+//       LDS rate) and half as much of the copy time stays exposed as for a single wave; the latency
+//       of a k-tile is shared by the two but not hidden:
+//       K_mem = max(t_c, 2 t_s) + solo_copy_exposed_pct / 2 % of t_g + 2/3 t_l
 //   two teams (gk = 2, eight waves): a SIMD holds one wave of each team; while one runs the MFMAs of its
 //       k-tile the other issues copies, one s_barrier per k-tile:
 //       K_mem = max(t_c, t_g, t_s) + phase_latency_clk * nk / residents
@@ -91,9 +95,18 @@ void compute_eff(uint32_t tm, uint32_t tn, uint32_t gm, uint32_t gn, uint32_t gk
     const u128 gbytes = (u128)(tm + tn) * kref * ELT + (u128)tm * tn * out_bytes;                // data_r + data_w
     const u128 sbytes = (u128)(tm + tn) * kref * ELT + (u128)kref * ELT * ((u128)tm * gn + (u128)tn * gm);
     const u128 nk = ceil_div(kref, tk);
-    // (an eight-wave grid has two waves per SIMD by itself: its phases overlap as those of two workgroups do)
-    const u128 r = residents >= 2 ? residents : (gm * gn == 8 ? 2 : 1);
+    const u128 r = residents;
     const u128 ed = 100;
+    if (gm * gn == 8 && gk == 1 && residents < 2) {
+        // over the common denominator F * G * S * 600
+        const u128 c8 = flops * G * S * 600;
+        const u128 s8 = sbytes * F * G * 1200;
+        const u128 g8 = gbytes * F * S * 3 * hw.solo_copy_exposed_pct;
+        const u128 l8 = ((u128)hw.ktile_latency_clk * nk + exchange_clk) * F * G * S * 400;
+        *num = c8;
+        *den = std::max(c8, s8) + g8 + l8;
+        return;
+    }
     if (gk == 2) {
         // over the common denominator F * G * S * r
         const u128 c2 = flops * G * S * r;
@@ -161,6 +174,11 @@ inline uint32_t ext(const ft_ukernel_info &u, uint32_t axis) { return axis == 0 
 // workgroups of eight waves (two teams, or an eight-wave grid) run in kernels of their own: one launch,
 // one workgroup size
 inline bool eight_waves(const ft_ukernel_info &u) { return u.gk == 2 || u.gm * u.gn == 8; }
+
+// What a uKernel offers against Alg. 1's block.bound (workgroups a CU should hold): its residency, and
+// twice that for an eight-wave grid, whose workgroup already puts two waves on every SIMD.  (A two-team
+// workgroup does too, but its teams take turns on the k-tiles: it counts as one.)
+inline uint32_t waves_bound(const ft_ukernel_info &u) { return u.max_wg_per_cu * (u.gm * u.gn == 8 ? 2u : 1u); }
 
 // Reduce-axis split (occupancy rescue): k-tiles per part when the nk = ceil(K / tk) k-tiles are
 // dealt out in equal runs.
@@ -254,7 +272,7 @@ void evaluate(Program &p, const ft_ukset &set, uint64_t batch, uint64_t M, uint6
     p.block_bound = (uint32_t)std::min<uint64_t>(need, t.zeta);                     // SetBound
     p.in_bound = true;
     for (uint32_t i = 0; i < nreg; ++i)
-        if (set.uk[reg[i].id].max_wg_per_cu < p.block_bound) p.in_bound = false;
+        if (waves_bound(set.uk[reg[i].id]) < p.block_bound) p.in_bound = false;
     u128 on = wgs, od = ceil_by(wgs, hw.num_cus);                                   // Eq. 3
     u128 pn = (u128)M * N, pd = area;                                               // Eq. 2
     p.occ_q = (uint32_t)((on << QBITS) / od);
@@ -701,7 +719,9 @@ static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, co
                 uint32_t tm = gm * wm, tn = gn * wn;
                 if (gk == 4 && (wm * wn < 256 || wm * wn > 4096)) continue;
                 if (gk == 2 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM || ceil_div(kref, FT_TK) < 4)) continue;   // (each team wants at least two k-tiles)
-                if (gm * gn == 8 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM)) continue;
+                // (eight-wave grids: plain GEMMs only; the gather of the convolution and the batched walk
+                // have no body of that shape)
+                if (gm * gn == 8 && (!t.two_team_bodies || op->d.kind != FT_OP_MATMUL)) continue;
                 if (ft_body_code(wm, wn, gm, gn, gk) < 0) continue;      // no compiled body
                 // static space axes are divided evenly (after rounding to the MFMA granule)
                 if (sv.m && ceil_by(sv.m, GRANULE) % tm) continue;

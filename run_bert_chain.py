@@ -36,8 +36,8 @@ HIDDEN, FFN = 768, 3072
 LAYER_GEMMS = (("qkv", 3 * HIDDEN, HIDDEN), ("o", HIDDEN, HIDDEN), ("ffn1", FFN, HIDDEN), ("ffn2", HIDDEN, FFN))
 
 
-def layer_flops(M):
-    return sum(2.0 * M * n * k for _, n, k in LAYER_GEMMS)
+def layer_flops(M, only=None):
+    return sum(2.0 * M * n * k for name, n, k in LAYER_GEMMS if only is None or name in only)
 
 
 def main():
@@ -50,28 +50,36 @@ def main():
     ap.add_argument("--variants", default="patch,base,bucket",
                     help="comma list: patch (the planner's plan, always run), base (pad-to-library plan), "
                          "bucket (M padded to the next power of two); 'patch' alone is what the committed profile runs")
+    ap.add_argument("--only", default="", help="comma list of qkv,o,ffn1,ffn2: launch only these GEMMs of each layer")
+    ap.add_argument("--four-wave", action="store_true", help="uKernel sets without the eight-wave uKernels")
     a = ap.parse_args()
     variants = set(a.variants.split(","))
+    only = set(a.only.split(",")) if a.only else {name for name, _, _ in LAYER_GEMMS}
+    assert only <= {name for name, _, _ in LAYER_GEMMS}, "--only: qkv,o,ffn1,ffn2"
     assert variants <= {"patch", "base", "bucket"}, "--variants: patch[,base][,bucket]"
 
     import torch
     import paper_2407_21418_amd as ft
+    import synth_inputs as si
 
     assert torch.cuda.is_available(), "run_bert_chain needs a GPU"
     dt = ft.FT_F16 if a.dtype == "f16" else ft.FT_BF16
     stream_t = torch.cuda.Stream()
     stream = stream_t.cuda_stream
     hw = ft.ft_hw_query(0)
+    tuning = ft.ft_tuning_default()
+    if a.four_wave:
+        tuning.two_team_bodies = 0
 
-    def rand16(shape):
-        return torch.randint(-2, 3, shape, dtype=torch.int16, device="cuda").mul_(0x0400)
+    def rand16(shape, std=1.0):
+        return si.device_normal_bits(shape, si.F16 if a.dtype == "f16" else si.BF16, std)
 
     ops = {}
     for name, n, k in LAYER_GEMMS:
         op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dt, n=n, k=k, m_lo=1, m_hi=8192,
                                              out_dtype=ft.FT_OUT_SAME, epilogue=ft.FT_EPI_BIAS))
-        ops[name] = (op, ft.ft_ukernels_derive(op, hw, None))
-    W = [{name: rand16((k, n)) for name, n, k in LAYER_GEMMS} for _ in range(a.layers)]
+        ops[name] = (op, ft.ft_ukernels_derive(op, hw, tuning))
+    W = [{name: rand16((k, n), k ** -0.5) for name, n, k in LAYER_GEMMS} for _ in range(a.layers)]
     bias = [{name: torch.zeros(n, dtype=torch.float32, device="cuda") for name, n, k in LAYER_GEMMS} for _ in range(a.layers)]
     lengths = [int(t) for t in a.lengths.split(",")]
     m_max = a.batch * max(lengths)
@@ -90,6 +98,8 @@ def main():
         src, dst = x, x2
         for l in range(a.layers):
             for name, A, Cbuf in (("qkv", src, qkv), ("o", ctx, o), ("ffn1", o, h), ("ffn2", h, dst)):
+                if name not in only:
+                    continue
                 op, uks = ops[name]
                 t0 = time.perf_counter()
                 plan = ft.ft_plan_cached(op, uks, ft.ft_shape(m=M), flags)
@@ -113,7 +123,7 @@ def main():
             e1.record()
         t_issue = time.perf_counter() - t0
         e1.synchronize()
-        n_launch = a.iters * a.layers * 4
+        n_launch = a.iters * a.layers * len(only)
         return e0.elapsed_time(e1) * 1e3 / (a.iters * a.layers), t_lookup * 1e6 / n_launch, t_issue * 1e6 / n_launch
 
     rows = []
@@ -123,7 +133,7 @@ def main():
         us_patch, us_lookup, us_issue = timed(M, ft.FT_PLAN_PATCHWORK)
         us_base = timed(M, ft.FT_PLAN_PAD_BASELINE)[0] if "base" in variants else float("nan")
         us_bucket = timed(Mb, ft.FT_PLAN_PATCHWORK)[0] if "bucket" in variants else float("nan")
-        fl = layer_flops(M)
+        fl = layer_flops(M, only)
         rows.append(dict(T=T, M=M, us_per_layer=round(us_patch, 2), tflops=round(fl / us_patch / 1e6, 1),
                          us_per_layer_pad_baseline=round(us_base, 2), us_per_layer_bucketed=round(us_bucket, 2),
                          bucket_M=Mb, host_us_per_launch=round(us_issue, 2), lookup_us_per_launch=round(us_lookup, 2)))

@@ -45,7 +45,7 @@ def main():
         return ops[key]
 
     def rand16(shape):
-        return torch.randint(-2, 3, shape, dtype=torch.int16, device="cuda").mul_(0x0400)
+        return si.device_normal_bits(shape, si.BF16 if a.config == 3 else si.F16)
 
     def measure(op, uks, shape, a_shape, b_shape, c_elems, flops, bytes_alg):
         nsets = max(2, min(a.max_sets, int(math.ceil(a.ring_mb * 1e6 / bytes_alg))))

@@ -65,7 +65,7 @@ def measure(seqs=64, heads=12, iters=20, draws=4, align=1, ring_mb=600.0, verbos
         return (L, L, 64) if which == "qk" else (L, 64, L)
 
     def rand16(n):
-        return torch.randint(-2, 3, (max(n, 8),), dtype=torch.int16, device="cuda").mul_(0x0400)
+        return si.device_normal_bits((max(n, 8),), si.F16)
 
     def timed(plan, na, nb, nc):
         nsets = max(2, min(16, int(math.ceil(a.ring_mb * 1e6 / (2 * (na + nb) + 4 * nc)))))

@@ -34,6 +34,7 @@ def main():
 
     import torch
     import paper_2407_21418_amd as ft
+    import synth_inputs as si
 
     dt = ft.FT_F16 if a.dtype == "f16" else ft.FT_BF16
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dt, n=a.n, k=a.k, m_lo=1, m_hi=max(8192, a.m)))
@@ -56,8 +57,8 @@ def main():
     st = ft.ft_plan_stats_get(plan)
     bytes_alg = 2 * (a.m * a.k + a.k * a.n) + 4 * a.m * a.n
     nsets = max(1, int(a.ring_mb * 1e6 // bytes_alg))
-    A = [torch.randint(-2, 3, (a.m, a.k), dtype=torch.int16, device="cuda").mul_(0x0400) for _ in range(nsets)]
-    B = [torch.randint(-2, 3, (a.k, a.n), dtype=torch.int16, device="cuda").mul_(0x0400) for _ in range(nsets)]
+    A = [si.device_normal_bits((a.m, a.k), si.F16 if a.dtype == "f16" else si.BF16) for _ in range(nsets)]
+    B = [si.device_normal_bits((a.k, a.n), si.F16 if a.dtype == "f16" else si.BF16) for _ in range(nsets)]
     Cs = [torch.empty((a.m, a.n), dtype=torch.float32, device="cuda") for _ in range(nsets)]
     pa, pb, pc = [t.data_ptr() for t in A], [t.data_ptr() for t in B], [t.data_ptr() for t in Cs]
     s = torch.cuda.current_stream().cuda_stream

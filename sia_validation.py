@@ -62,8 +62,8 @@ def main():
         infos = [ft.ft_ukset_get(uks, i) for i in range(ft.ft_ukset_size(uks))]
         bytes_alg = 2 * (M * K + K * N) + 4 * M * N
         nsets = max(2, int(math.ceil(a.ring_mb * 1e6 / bytes_alg)))
-        A = [torch.randint(-3, 3, (M, K), dtype=torch.int16, device="cuda") for _ in range(nsets)]
-        B = [torch.randint(-3, 3, (K, N), dtype=torch.int16, device="cuda") for _ in range(nsets)]
+        A = [si.device_normal_bits((M, K), si.F16 if dt == ft.FT_F16 else si.BF16) for _ in range(nsets)]
+        B = [si.device_normal_bits((K, N), si.F16 if dt == ft.FT_F16 else si.BF16) for _ in range(nsets)]
         C = [torch.empty((M, N), dtype=torch.float32, device="cuda") for _ in range(nsets)]
         pa, pb, pc = [t.data_ptr() for t in A], [t.data_ptr() for t in B], [t.data_ptr() for t in C]
 

@@ -32,6 +32,15 @@ def uniform_bits(g, shape, lo, hi, dtype):
     return to_bits(g.uniform(lo, hi, size=shape).astype(np.float32), dtype)
 
 
+def device_normal_bits(shape, dtype, std=1.0):
+    """N(0, std^2) values as fp16 / bf16 bit patterns in a torch int16 tensor on the GPU: operands of the
+    timing harnesses, whose outputs nobody checks (drawn on the device, from torch's generator).  The
+    values matter for timings: the power an MFMA draws, and with it the clock, depends on its data."""
+    import torch
+    x = torch.randn(shape, device="cuda", dtype=torch.float32).mul_(std)
+    return x.to(torch.float16 if dtype == F16 else torch.bfloat16).view(torch.int16)
+
+
 # ---- configuration 0: one odd-M Matmul ------------------------------------------------
 def config0():
     g = rng(0)

@@ -297,6 +297,17 @@ def test_forced_program_mode():
     assert e.value.status == ft.FT_ERR_NO_COVER
 
 
+def test_eight_wave_grids_are_for_plain_gemms_only():
+    """Eight-wave grids (gm * gn = 8) have bodies for the plain GEMM walk only: a convolution or a batched
+    operator gets none; a large dense operator gets the three tile shapes."""
+    def grids(name):
+        s = ft.ft_ukernels_derive(to_lib_op(OPS[name]))
+        return {(u.tm, u.tn) for u in (ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))) if u.gm * u.gn == 8}
+    assert grids("conv") == set() and grids("qk") == set() and grids("pv") == set()
+    assert grids("llm4096") == {(256, 256), (128, 256), (256, 128)}
+    assert {(u.tm, u.tn) for u in P.derive_ukernels(OPS["conv"]) if u.gm * u.gn == 8} == set()
+
+
 def test_launch_order_is_a_balanced_permutation():
     """Every workgroup takes a distinct descriptor; each XCD (workgroup b -> XCD b % 8) gets an
     equal share (+-1) of EACH constituent's tiles, as contiguous slices of the table."""

@@ -9,6 +9,7 @@ What is evaluated, from the definitions:
          t_s = (data_transW + data_transR) / bw_S and K_mem read as the time of the k loop:
            a workgroup alone on its CU:  K_mem = t_ce + exposed * t_g + t_l
            workgroups sharing a CU:      K_mem = max(t_ce, t_g, t_s) + t_l / residents
+           eight-wave grid alone:        K_mem = max(t_c, 2 t_s) + exposed / 2 * t_g + 2/3 t_l
            two teams (gk = 2):           K_mem = max(t_c, t_g, t_s) + phase latency * nk / residents
          t_ce = t_c * gk * ceil(nk / gk) / nk, t_l = k-tile latency * ceil(nk / gk) (+ the exchange of a
          reduce-axis split), nk = ceil(K / tk)
@@ -47,7 +48,11 @@ def second_compute_eff(u, k_extent, residents, out_bytes, hw, exchange=0):
     data_tr = k_extent * 2 * (u.tm * u.gn + u.tn * u.gm)
     t_s = Fr(data_tw + data_tr, hw["bw_lds_bytes_per_clk_per_cu"])
     nk = -(-k_extent // u.tk)
-    res = residents if residents >= 2 else (2 if u.gm * u.gn == 8 else 1)      # eight waves overlap by themselves
+    res = residents
+    if u.gm * u.gn == 8 and u.gk == 1 and residents < 2:
+        t_l = Fr(hw["ktile_latency_clk"] * nk + exchange)
+        k_mem = max(t_c, 2 * t_s) + Fr(hw["solo_copy_exposed_pct"], 200) * t_g + Fr(2, 3) * t_l
+        return t_c / k_mem
     if u.gk == 2:
         k_mem = max(t_c, t_g, t_s) + Fr(hw["phase_latency_clk"] * nk + exchange, res)
         return t_c / k_mem
@@ -78,7 +83,9 @@ def second_opinion(parts, uks, op, batch, M, N, K, tau, hw, t, k_parts=1):
     wgs = tiles_all * k_parts
     cores = hw["num_cus"]
     block_bound = min(max(1, -(-wgs // cores)), t["zeta"])
-    out = {"block_bound": block_bound, "in_bound": all(r[0].max_wg_per_cu >= block_bound for r in regions),
+    # (an eight-wave grid brings two waves per SIMD with one workgroup: it counts twice against block.bound)
+    out = {"block_bound": block_bound,
+           "in_bound": all(r[0].max_wg_per_cu * (2 if r[0].gm * r[0].gn == 8 else 1) >= block_bound for r in regions),
            "pad_q": fl(Fr(M * N, sum(r[3] for r in regions)) * ONE),
            "occ_q": fl(Fr(wgs, cores * (-(-wgs // cores))) * ONE)}
     k_ref = op.k_ref()

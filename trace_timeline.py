@@ -37,6 +37,7 @@ def main():
     import numpy as np
     import torch
     import paper_2407_21418_amd as ft
+    import synth_inputs as si
 
     lib = ft.lib()
     if not hasattr(lib, "ft_debug_set_trace"):
@@ -59,8 +60,8 @@ def main():
     st = ft.ft_plan_stats_get(plan)
     bytes_alg = 2 * (a.m * a.k + a.k * a.n) + 4 * a.m * a.n
     nsets = max(3, int(a.ring_mb * 1e6 // bytes_alg))
-    A = [torch.randint(-2, 3, (a.m, a.k), dtype=torch.int16, device="cuda").mul_(0x0400) for _ in range(nsets)]
-    B = [torch.randint(-2, 3, (a.k, a.n), dtype=torch.int16, device="cuda").mul_(0x0400) for _ in range(nsets)]
+    A = [si.device_normal_bits((a.m, a.k), si.F16 if a.dtype == "f16" else si.BF16) for _ in range(nsets)]
+    B = [si.device_normal_bits((a.k, a.n), si.F16 if a.dtype == "f16" else si.BF16) for _ in range(nsets)]
     Cs = [torch.empty((a.m, a.n), dtype=torch.float32, device="cuda") for _ in range(nsets)]
     tr = torch.zeros((int(st.n_tiles) * max(1, st.k_parts) + 64) * 16, dtype=torch.int64, device="cuda")
     lib.ft_debug_set_trace(None)
