@@ -134,6 +134,14 @@ enum { FT_F16 = 0, FT_BF16 = 1 };
  * (the fused Dense + bias-add of the paper's BERT evaluation, Sec. 6.2). */
 enum { FT_OUT_F32 = 0, FT_OUT_SAME = 1 };
 enum { FT_EPI_NONE = 0, FT_EPI_BIAS = 1 };
+/* Layout of operand B (Matmul and BMM; the GEMM view itself, Sec. 4.1 / Fig. 12 caption, does not
+ * change): FT_B_KN, B[b,k,j] with j contiguous (row pitch N); FT_B_NK, the same matrix stored
+ * transposed, B[b,j,k] with k contiguous (row pitch K): the K matrix of an attention's Q K^T, a
+ * linear layer's weight as frameworks keep it.  With FT_B_NK the operator derives the four-wave
+ * standard grids only, and a launch needs operands the LDS-DMA bodies accept: 16-byte aligned
+ * pointers and a reduce extent that is a multiple of 8 (N may be anything); otherwise ft_launch
+ * returns FT_ERR_UNSUPPORTED (the general bodies have no such variant).                          */
+enum { FT_B_KN = 0, FT_B_NK = 1 };
 
 typedef struct ft_op_desc {
     uint32_t struct_size;
@@ -153,6 +161,7 @@ typedef struct ft_op_desc {
     uint32_t batch_hi;             /* BMM: largest batch count of the workload (the batch of a
                                       launch is a runtime value); 0 = unknown: the workload
                                       filters (CrossPick, Eq. 5) are skipped for this operator */
+    uint32_t b_layout;             /* FT_B_*: Matmul and BMM; Conv2d takes FT_B_KN (RSCK weights) */
 } ft_op_desc;
 
 typedef struct ft_op ft_op;

@@ -88,6 +88,17 @@ def bmm(A, B, dtype, want_abs=False):
     return (C, Cabs) if want_abs else C
 
 
+def matmul_nk(A, Bt, dtype, rows=None, want_abs=False):
+    """C[i,j] = sum_k A[i,k] Bt[j,k]: the Matmul of Sec. 4.1 with B handed over transposed ([N, K], k
+    contiguous).  The same definition on the re-laid-out operand."""
+    return matmul(A, np.ascontiguousarray(_bits(Bt).T), dtype, rows=rows, want_abs=want_abs)
+
+
+def bmm_nk(A, Bt, dtype, want_abs=False):
+    """C[b,i,j] = sum_k A[b,i,k] Bt[b,j,k] (BatchMatmul, Fig. 12 caption, B handed over as [b, N, K])."""
+    return bmm(A, np.ascontiguousarray(np.swapaxes(_bits(Bt), 1, 2)), dtype, want_abs=want_abs)
+
+
 def conv2d_nhwc(X, W, dtype, stride=1, pad=1, pixels=None, want_abs=False):
     """Y[n,p,q,k] = sum_{r,s,c} X[n,p*stride-pad+r,q*stride-pad+s,c] W[r,s,c,k], zero halo.
 

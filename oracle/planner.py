@@ -189,6 +189,7 @@ class Op:
     out_bytes: int = 4   # bytes per output element: fp32, or 2 when C has the inputs' 16-bit type
     batch_hi: int = 0    # BMM: largest batch count of the workload (the batch itself is a runtime
                          # value); 0 = unknown: the workload filters cannot be evaluated and are skipped
+    b_nk: bool = False   # operand B stored as [N][K] (k contiguous): four-wave standard grids only
 
     def gemm_static(self):
         if self.kind == OP_CONV2D:
@@ -365,6 +366,8 @@ def derive_ukernels(op: Op, hw=None, t=None) -> List[UKernel]:
     psi_ok = []
     for wm, wn, mfma in wave_tiles():
         for gm, gn, gk in WAVE_GRIDS:
+            if op.b_nk and (gk != 1 or gm * gn != 4):
+                continue
             if gk == 4 and not (256 <= wm * wn <= 4096):
                 continue
             if gk == 2 and (not t.get("two_team_bodies", 0) or op.kind == OP_BMM or ceil_div(k_ref, TK_CHOICES[0]) < 4):

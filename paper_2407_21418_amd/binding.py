@@ -18,6 +18,7 @@ FT_OP_MATMUL, FT_OP_BMM, FT_OP_CONV2D = 0, 1, 2
 FT_F16, FT_BF16 = 0, 1
 FT_OUT_F32, FT_OUT_SAME = 0, 1
 FT_EPI_NONE, FT_EPI_BIAS = 0, 1
+FT_B_KN, FT_B_NK = 0, 1
 FT_PLAN_PATCHWORK, FT_PLAN_PAD_BASELINE, FT_PLAN_FORCED, FT_PLAN_HOST_ONLY, FT_PLAN_TABLE_ORDER = 0, 1, 2, 16, 32
 FT_SIA_LINEAR, FT_SIA_PRODUCT = 0, 1
 
@@ -55,7 +56,7 @@ class ft_tuning(_S):
 class ft_op_desc(_S):
     _fields_ = [(n, u32) for n in (
         "struct_size", "kind", "dtype", "m", "n", "k", "m_lo", "m_hi", "n_lo", "n_hi", "k_lo", "k_hi",
-        "c_in", "c_out", "r", "s", "stride", "pad", "out_dtype", "epilogue", "batch_hi")]
+        "c_in", "c_out", "r", "s", "stride", "pad", "out_dtype", "epilogue", "batch_hi", "b_layout")]
 
 
 class ft_ukernel_info(_S):

@@ -105,6 +105,14 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
                                       os.path.join(CSRC, "dispatch.hip"), "-o", obj]
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             gen.append((obj, cmd))
+    for dt in (0, 1):                         # operand B as [N][K]: LDS-DMA bodies, plain and grouped launches
+        for cl in (2, 1, 0):
+            for tag, defs in (("nk", []), ("grpnk", ["-DFT_GROUPED=1"])):
+                obj = os.path.join(OUT, f"dispatch_dt{dt}_{tag}_c{cl}.o")
+                cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_BNK=1"] + defs + \
+                      ["-c", os.path.join(CSRC, "dispatch.hip"), "-o", obj]
+                cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+                gen.append((obj, cmd))
     gen.sort(key=lambda oc: "_c2" not in oc[0])   # the 512-register kernels take longest: start them first
     steps = gen + steps
     for src in ("host.cpp", "device.hip"):

@@ -81,6 +81,11 @@ const launch_fn kLaunchGrouped[2][2] = {{ft_launch_dt0_grp_c1, ft_launch_dt0_grp
                                         {ft_launch_dt1_grp_c1, ft_launch_dt1_grp_c2}};
 const launch_fn kLaunchGroupedFast[2][3] = {{ft_launch_dt0_grpf_c0, ft_launch_dt0_grpf_c1, ft_launch_dt0_grpf_c2},
                                             {ft_launch_dt1_grpf_c0, ft_launch_dt1_grpf_c1, ft_launch_dt1_grpf_c2}};
+// operand B as [N][K]: LDS-DMA bodies of the four-wave standard grids, plain and grouped
+const launch_fn kLaunchNK[2][3] = {{ft_launch_dt0_nk_c0, ft_launch_dt0_nk_c1, ft_launch_dt0_nk_c2},
+                                   {ft_launch_dt1_nk_c0, ft_launch_dt1_nk_c1, ft_launch_dt1_nk_c2}};
+const launch_fn kLaunchGroupedNK[2][3] = {{ft_launch_dt0_grpnk_c0, ft_launch_dt0_grpnk_c1, ft_launch_dt0_grpnk_c2},
+                                          {ft_launch_dt1_grpnk_c0, ft_launch_dt1_grpnk_c1, ft_launch_dt1_grpnk_c2}};
 static_assert(sizeof(ftk::GroupRec) == sizeof(ft_group_rec) && sizeof(ft_group_rec) == 40,
               "the kernels read the host's group records as they are");
 
@@ -126,7 +131,7 @@ void fill_args(const ft_plan *p, const void *A, const void *B, void *C, const fl
     a->descs = static_cast<const ftk::TileDesc *>(p->d_descs);
     a->n_tiles = (uint32_t)s.n_tiles;
     a->M = s.m; a->N = s.n; a->K = s.k;
-    a->lda = s.k; a->ldb = s.n; a->ldc = s.n;
+    a->lda = s.k; a->ldb = p->op.b_layout == FT_B_NK ? s.k : s.n; a->ldc = s.n;
     a->strideA = (uint64_t)s.m * s.k;
     a->strideB = (uint64_t)s.k * s.n;
     a->strideC = (uint64_t)s.m * s.n;
@@ -298,6 +303,12 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
         a.c_stream = (on_blocks || out16 || plan->grp_k_min > 64) ? 1u : 0u;     // as for a plain launch
         // every group aligned and the buffers too: the LDS-DMA bodies; else the general ones
         const bool fast = plan->grp_aligned && reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0;
+        if (plan->op.b_layout == FT_B_NK) {
+            if (!fast) return FT_ERR_UNSUPPORTED;       // no general bodies for this layout
+            const int rc = kLaunchGroupedNK[plan->op.dtype][ft_class_of_acc((int)plan->grp_fast_acc)](&a, plan->grp_fast_lds, hip_stream);
+            if (rc != 0) return hip_fail((hipError_t)rc);
+            return FT_OK;
+        }
         const int rc = fast ? kLaunchGroupedFast[plan->op.dtype][ft_class_of_acc((int)plan->grp_fast_acc)](&a, plan->grp_fast_lds, hip_stream)
                             : kLaunchGrouped[plan->op.dtype][plan->grp_acc <= 64 ? 0 : 1](&a, 2 * plan->grp_stage_bytes, hip_stream);
         if (rc != 0) return hip_fail((hipError_t)rc);
@@ -309,6 +320,11 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
     const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0);
     bool fast = a.is_conv ? (aligned && a.Cin % 64 == 0 && a.N % 8 == 0)
                           : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
+    if (plan->op.b_layout == FT_B_NK) {
+        // rows of B are k long, like A's: any N; no general bodies for this layout
+        if (!(aligned && a.K % 8 == 0)) return FT_ERR_UNSUPPORTED;
+        fast = true;
+    }
     if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
         for (int i = 0; i < 4; ++i) {
             // (the planner derives no eight-wave grid for a convolution: its twin would run in the wrong kernel)
@@ -328,7 +344,10 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
         if (e != hipSuccess) return hip_fail(e);
     }
     int rc;
-    if (fast && plan->two_teams) {
+    if (plan->op.b_layout == FT_B_NK) {
+        if (plan->two_teams) return FT_ERR_UNSUPPORTED;      // (such an operator derives none)
+        rc = kLaunchNK[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
+    } else if (fast && plan->two_teams) {
         if (plan->st.kernel_class > 1) return FT_ERR_UNSUPPORTED;
         rc = kLaunchTwoTeams[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
     } else if (fast) {

@@ -20,6 +20,14 @@
 #error "define FT_CLASS"
 #endif
 
+// -DFT_BNK=1 (with the fast bodies only): operand B is [N][K]; the four-wave standard grids, no split-k
+// wave grid (the host sends such a uKernel to its standard-grid twin)
+#ifdef FT_BNK
+#define FT_BNK_FLAG true
+#else
+#define FT_BNK_FLAG false
+#endif
+
 #ifdef FT_PP
 // two-team workgroups: eight waves, two per SIMD; classes 0 (128 registers) and 1 (256 registers)
 #define FT_THREADS 512
@@ -113,7 +121,7 @@ __global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs
     gl.M = __builtin_amdgcn_readfirstlane(rec.m);
     gl.N = __builtin_amdgcn_readfirstlane(rec.n);
     gl.K = __builtin_amdgcn_readfirstlane(rec.k);
-    gl.lda = gl.K; gl.ldb = gl.N; gl.ldc = gl.N;
+    gl.lda = gl.K; gl.ldb = FT_BNK_FLAG ? gl.K : gl.N; gl.ldc = gl.N;
     gl.strideA = (uint64_t)gl.M * gl.K;
     gl.strideB = (uint64_t)gl.K * gl.N;
     gl.strideC = (uint64_t)gl.M * gl.N;
@@ -156,10 +164,11 @@ __global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
-            UKernelFast<FT_DT, WM, WN, GM, GN>::run(gl, d, smem, gstages, t, 0u); \
+            UKernelFast<FT_DT, WM, WN, GM, GN, 1, FT_BNK_FLAG>::run(gl, d, smem, gstages, t, 0u); \
         break;
         FT_FAMILY(FT_X)
 #undef FT_X
+#ifndef FT_BNK
 #define FT_X(CODE, TM, TN, TWIN)                                                \
     case CODE:                                                                  \
         if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \
@@ -167,6 +176,7 @@ __global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs
         break;
         FT_FAMILY_SPLITK(FT_X)
 #undef FT_X
+#endif
     default: break;
     }
 #endif
@@ -214,7 +224,7 @@ __global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs
 #define FT_X(CODE, WM, WN, GM, GN)                                              \
     case CODE:                                                                  \
         if constexpr ((WM) * (WN) / 64 <= FT_ACC_MAX)                           \
-            UKernelFast<FT_DT, WM, WN, GM, GN>::run(g, d, smem, stages, t, part); \
+            UKernelFast<FT_DT, WM, WN, GM, GN, 1, FT_BNK_FLAG>::run(g, d, smem, stages, t, part); \
         break;
 #endif
         FT_FAMILY(FT_X)
@@ -230,7 +240,7 @@ __global__ __launch_bounds__(FT_THREADS, FT_MIN_WAVES) void FT_KERNEL_NAME(KArgs
         FT_FAMILY_W8(FT_X)
 #undef FT_X
 #endif
-#if !defined(FT_GENERIC) && !defined(FT_PP)
+#if !defined(FT_GENERIC) && !defined(FT_PP) && !defined(FT_BNK)
 #define FT_X(CODE, TM, TN, TWIN)                                                \
     case CODE:                                                                  \
         if constexpr ((TM) * (TN) / 64 <= FT_ACC_MAX)                           \

@@ -31,6 +31,11 @@ template <int OFF> __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr)
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
     return v;
 }
+template <int OFF> __device__ __forceinline__ u32x2 lds_read_b64(uint32_t addr) {
+    u32x2 v;
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
 template <int OFF> __device__ __forceinline__ u32x2 lds_read_tr16_b64(uint32_t addr) {
     u32x2 v;
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
@@ -176,9 +181,13 @@ __device__ __forceinline__ bool k_part_exchange_blocks(const KArgs &g, uint32_t 
 // wave is held up while its copy instructions are accepted (measured: about as long as the MFMAs of a
 // k-tile take), so with one wave per SIMD copy and MFMA time add up; with two teams the SIMD's other
 // wave computes meanwhile.
-template <int DT, int WM, int WN, int GM, int GN, int TEAMS = 1>
+// BNK: operand B is given as [N][K] (k contiguous, the layout of A; an attention's K matrix in Q K^T, a
+// linear layer's weight as stored): its tile is copied and laid out in LDS exactly like A's, rows
+// being output columns, and its fragments are read with plain reads instead of transposing ones.
+template <int DT, int WM, int WN, int GM, int GN, int TEAMS = 1, bool BNK = false>
 struct UKernelFast {
     static_assert(TEAMS == 1 || TEAMS == 2, "one team of four waves, or two");
+    static_assert(!BNK || (TEAMS == 1 && GM * GN == 4), "the [N][K] layout is built for the four-wave grids");
     // A single team may also be a grid of EIGHT waves (GM * GN = 8, two per SIMD) that share every
     // k-tile: a 256 x 256 tile then costs a wave 128 accumulator registers instead of 256, and while
     // one wave of a SIMD is held up issuing copies or waiting for fragments the other runs MFMAs.
@@ -268,12 +277,21 @@ struct UKernelFast {
         uint32_t goff_b[LB];
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
-            uint32_t o = wave * B_WAVE_BYTES + i * 1024 + lane * 16;
-            uint32_t krow = o / (TN * 2), p = (o % (TN * 2)) / 16;
-            uint32_t nc = p ^ swzB<TN>(krow);
-            uint32_t col = n0 + nc * 8;
-            if (col >= N) col = n0;                   // clamp: garbage columns are never stored
-            goff_b[i] = (krow * g.ldb + col) * 2;
+            if constexpr (!BNK) {
+                uint32_t o = wave * B_WAVE_BYTES + i * 1024 + lane * 16;
+                uint32_t krow = o / (TN * 2), p = (o % (TN * 2)) / 16;
+                uint32_t nc = p ^ swzB<TN>(krow);
+                uint32_t col = n0 + nc * 8;
+                if (col >= N) col = n0;               // clamp: garbage columns are never stored
+                goff_b[i] = (krow * g.ldb + col) * 2;
+            } else {
+                // as A: LDS row = output column of the tile, 128 bytes of k each
+                uint32_t row = (wave * B_WAVE_BYTES + i * 1024) / 128 + lane / 8;
+                uint32_t kc = (lane & 7u) ^ swzA(row);
+                uint32_t gn = n0 + row;
+                if (gn >= N) gn = N - 1;              // clamp: garbage columns are never stored
+                goff_b[i] = (gn * g.ldb + kc * 8) * 2;
+            }
         }
         const bool b_lane_on = (B_WAVE_BYTES >= 1024) || lane < (uint32_t)(B_WAVE_BYTES / 16);
         const bool k_tail = (K % TK) != 0;
@@ -314,10 +332,16 @@ struct UKernelFast {
             }
 #pragma unroll
             for (int i = 0; i < LB; ++i) {
-                const void *p = bbase + (uint32_t)(goff_b[i] + kb);
+                const void *p = bbase + (uint32_t)(goff_b[i] + (BNK ? ka : kb));
                 if constexpr (tail) {
-                    uint32_t krow = (wave * B_WAVE_BYTES + i * 1024 + lane * 16) / (TN * 2);
-                    if (k0 + krow >= K) p = ft_zero_page;
+                    if constexpr (!BNK) {
+                        uint32_t krow = (wave * B_WAVE_BYTES + i * 1024 + lane * 16) / (TN * 2);
+                        if (k0 + krow >= K) p = ft_zero_page;
+                    } else {
+                        uint32_t row = (wave * B_WAVE_BYTES + i * 1024) / 128 + lane / 8;
+                        uint32_t kc = (lane & 7u) ^ swzA(row);
+                        if (k0 + kc * 8 >= K) p = ft_zero_page;
+                    }
                 }
                 if (b_lane_on) lds_dma16(p, st + A_BYTES + wave * B_WAVE_BYTES + i * 1024);
             }
@@ -346,8 +370,14 @@ struct UKernelFast {
         uint32_t fb_addr[BN];
 #pragma unroll
         for (int bj = 0; bj < BN; ++bj) {
-            uint32_t col = wave_n * WN + bj * MB + fb_colgrp * 16 + (j16 & 3u) * 4;
-            fb_addr[bj] = sbase + A_BYTES + fb_row0 * (TN * 2) + (((col >> 3) ^ swzB<TN>(fb_row0)) << 4) + (col & 7u) * 2;
+            if constexpr (!BNK) {
+                uint32_t col = wave_n * WN + bj * MB + fb_colgrp * 16 + (j16 & 3u) * 4;
+                fb_addr[bj] = sbase + A_BYTES + fb_row0 * (TN * 2) + (((col >> 3) ^ swzB<TN>(fb_row0)) << 4) + (col & 7u) * 2;
+            } else {
+                // as A: row = output column wave_n*WN + bj*MB + lane%MB, chunk = lane/MB (+ the k-step's)
+                const uint32_t row = wave_n * WN + bj * MB + (lane % MB);
+                fb_addr[bj] = sbase + A_BYTES + row * (TK * 2) + (((lane / MB) ^ swzA(row)) << 4);
+            }
         }
 
         Acc acc[BM][BN];
@@ -513,8 +543,15 @@ struct UKernelFast {
     }
     template <int ks, int buf, int bj = 0>
     __device__ static __forceinline__ void read_b(const uint32_t (&b_addr)[BN], u32x2 (&fb)[2][BN][2]) {
-        fb[buf][bj][0] = lds_read_tr16_b64<(ks * KSTEP) * TN * 2>(b_addr[bj]);
-        fb[buf][bj][1] = lds_read_tr16_b64<(ks * KSTEP + 4) * TN * 2>(b_addr[bj]);
+        if constexpr (!BNK) {
+            fb[buf][bj][0] = lds_read_tr16_b64<(ks * KSTEP) * TN * 2>(b_addr[bj]);
+            fb[buf][bj][1] = lds_read_tr16_b64<(ks * KSTEP + 4) * TN * 2>(b_addr[bj]);
+        } else {
+            // the lane's 8 consecutive k of its column: two halves of one 16-byte chunk
+            const uint32_t bb = b_addr[bj] ^ (uint32_t)(ks * (KSTEP / 8) * 16);
+            fb[buf][bj][0] = lds_read_b64<0>(bb);
+            fb[buf][bj][1] = lds_read_b64<8>(bb);
+        }
         if constexpr (bj + 1 < BN) read_b<ks, buf, bj + 1>(b_addr, fb);
     }
     template <int ks, int buf>

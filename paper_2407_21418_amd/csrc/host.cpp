@@ -647,6 +647,7 @@ ft_status ft_op_register(const ft_op_desc *desc, ft_op **out) {
     const ft_op_desc &d = *desc;
     if (d.kind > FT_OP_CONV2D || d.dtype > FT_BF16) return FT_ERR_INVALID_ARG;
     if (d.out_dtype > FT_OUT_SAME || d.epilogue > FT_EPI_BIAS) return FT_ERR_INVALID_ARG;
+    if (d.b_layout > FT_B_NK || (d.b_layout == FT_B_NK && d.kind == FT_OP_CONV2D)) return FT_ERR_INVALID_ARG;
     if (d.kind == FT_OP_CONV2D) {
         if (!d.c_in || !d.c_out || !d.r || !d.s || !d.stride) return FT_ERR_INVALID_ARG;
         if (d.m_lo > d.m_hi) return FT_ERR_INVALID_ARG;
@@ -717,6 +718,8 @@ static ft_status ukernels_derive_impl(const ft_op *op, const ft_hw_model *hw, co
             for (auto &g : grids) {
                 uint32_t gm = g[0], gn = g[1], gk = g[2], tk = FT_TK;
                 uint32_t tm = gm * wm, tn = gn * wn;
+                // (B as [N][K]: bodies of the four-wave standard grids only)
+                if (op->d.b_layout == FT_B_NK && (gk != 1 || gm * gn != 4)) continue;
                 if (gk == 4 && (wm * wn < 256 || wm * wn > 4096)) continue;
                 if (gk == 2 && (!t.two_team_bodies || op->d.kind == FT_OP_BMM || ceil_div(kref, FT_TK) < 4)) continue;   // (each team wants at least two k-tiles)
                 // (eight-wave grids: plain GEMMs only; the gather of the convolution and the batched walk
@@ -1275,7 +1278,9 @@ static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const 
             pl->grp_fast_acc = std::max(pl->grp_fast_acc, u.acc_regs);
         }
         // LDS-DMA bodies: 16-byte aligned matrices, row lengths and reduce extent multiples of 8 elements
-        if (any && (g.k % 8 || g.n % 8 || rec.off_a % 8 || rec.off_b % 8 || ((uint64_t)g.m * g.k) % 8 || ((uint64_t)g.k * g.n) % 8))
+        // (B as [N][K]: its rows are k long too, so N may be anything)
+        if (any && (g.k % 8 || (g.n % 8 && op->d.b_layout != FT_B_NK) || rec.off_a % 8 || rec.off_b % 8 ||
+                    ((uint64_t)g.m * g.k) % 8 || ((uint64_t)g.k * g.n) % 8))
             pl->grp_aligned = false;
         if (any) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
         s.batch += g.batch;

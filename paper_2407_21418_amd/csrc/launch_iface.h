@@ -5,7 +5,13 @@
 #define FT_CAT_(a, b, c, d) a##b##c##d
 #define FT_CAT(a, b, c, d) FT_CAT_(a, b, c, d)
 #if defined(FT_DT) && defined(FT_CLASS)
-#if defined(FT_PP)
+#if defined(FT_BNK) && defined(FT_GROUPED)
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _grpnk_c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _grpnk_c, FT_CLASS)
+#elif defined(FT_BNK)
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _nk_c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _nk_c, FT_CLASS)
+#elif defined(FT_PP)
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _pp_c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _pp_c, FT_CLASS)
 #elif defined(FT_GROUPED) && defined(FT_GENERIC)
@@ -48,4 +54,16 @@ int ft_launch_dt0_grpf_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grpf_c0(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grpf_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grpf_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_nk_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_nk_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_nk_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_nk_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_grpnk_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_grpnk_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_nk_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_nk_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_grpnk_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_grpnk_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_grpnk_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_grpnk_c1(const ftk::KArgs *, uint32_t, void *);
 }

@@ -28,6 +28,7 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--ring-mb", type=float, default=600.0)
     ap.add_argument("--max-sets", type=int, default=48)
+    ap.add_argument("--b-nk", action="store_true", help="config 2: hand the K matrices of Q K^T over as [L, 64] (FT_B_NK)")
     a = ap.parse_args()
 
     import torch
@@ -74,7 +75,8 @@ def main():
                 for L in lengths[Bsz]:
                     if which == "qk":
                         op, uks = get_op("qk", ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=1, m_hi=512, n_lo=1, n_hi=512,
-                                                            batch_hi=max(si.ATT_BATCH) * si.ATT_HEADS))
+                                                            batch_hi=max(si.ATT_BATCH) * si.ATT_HEADS,
+                                                            b_layout=ft.FT_B_NK if a.b_nk else ft.FT_B_KN))
                         M, N, K, shape = L, L, 64, ft.ft_shape(batch=nb, m=L, n=L)
                     else:
                         op, uks = get_op("pv", ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, n=64, m_lo=1, m_hi=512, k_lo=1, k_hi=512,

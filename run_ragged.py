@@ -31,8 +31,10 @@ def main():
     ap.add_argument("--ring-mb", type=float, default=600.0)
     ap.add_argument("--align", type=int, default=1, help="round every length up to a multiple of this (8: the "
                     "grouped launch then runs the LDS-DMA bodies)")
+    ap.add_argument("--b-nk", action="store_true", help="Q K^T with the K matrices stored [L, 64] (FT_B_NK): the LDS-DMA "
+                    "bodies at every length")
     a = ap.parse_args()
-    rows = measure(a.seqs, a.heads, a.iters, a.draws, a.align, a.ring_mb, verbose=True)
+    rows = measure(a.seqs, a.heads, a.iters, a.draws, a.align, a.ring_mb, verbose=True, b_nk=a.b_nk)
     gm = lambda xs: math.exp(sum(math.log(x) for x in xs) / len(xs))
     print(json.dumps({"workload": "ragged attention batches, %d sequences x %d heads, lengths rounded up to multiples of %d, fp16 in, fp32 out" % (a.seqs, a.heads, a.align),
                       "speedup_vs_padded_geomean": round(gm([r["us_padded"] / r["us_grouped"] for r in rows]), 3),
@@ -40,7 +42,7 @@ def main():
                       "rows": rows}))
 
 
-def measure(seqs=64, heads=12, iters=20, draws=4, align=1, ring_mb=600.0, verbose=False):
+def measure(seqs=64, heads=12, iters=20, draws=4, align=1, ring_mb=600.0, verbose=False, b_nk=False):
     """The measurement itself; returns one row per draw and operator."""
     import argparse as _ap
     a = _ap.Namespace(seqs=seqs, heads=heads, iters=iters, draws=draws, align=align, ring_mb=ring_mb)
@@ -55,7 +57,7 @@ def measure(seqs=64, heads=12, iters=20, draws=4, align=1, ring_mb=600.0, verbos
     H = a.heads
     ops = {
         "qk": ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, k=64, m_lo=0, m_hi=512, n_lo=0, n_hi=512,
-                                              batch_hi=a.seqs * H)),
+                                              batch_hi=a.seqs * H, b_layout=ft.FT_B_NK if b_nk else ft.FT_B_KN)),
         "pv": ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, n=64, m_lo=0, m_hi=512, k_lo=0, k_hi=512,
                                               batch_hi=a.seqs * H)),
     }

@@ -29,7 +29,8 @@ def to_lib_op(op: P.Op):
                       m_lo=op.m_range[0], m_hi=op.m_range[1], n_lo=op.n_range[0], n_hi=op.n_range[1],
                       k_lo=op.k_range[0], k_hi=op.k_range[1], c_in=op.c_in, c_out=op.c_out, r=op.r, s=op.s,
                       stride=op.stride, pad=op.pad,
-                      out_dtype=ft.FT_OUT_SAME if op.out_bytes == 2 else ft.FT_OUT_F32, batch_hi=op.batch_hi)
+                      out_dtype=ft.FT_OUT_SAME if op.out_bytes == 2 else ft.FT_OUT_F32, batch_hi=op.batch_hi,
+                      b_layout=ft.FT_B_NK if op.b_nk else ft.FT_B_KN)
     return ft.ft_op_register(d)
 
 
@@ -44,6 +45,8 @@ OPS = {
     "pv": P.Op(P.OP_BMM, P.F16, n=64, m_range=(0, 512), k_range=(0, 512)),
     "onlyn": P.Op(P.OP_BMM, P.F16, m=64, k=64, n_range=(1, 512)),
     "conv": P.Op(P.OP_CONV2D, P.F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1, m_range=(0, 1 << 22)),
+    "qk_nk": P.Op(P.OP_BMM, P.F16, k=64, m_range=(0, 512), n_range=(0, 512), batch_hi=768, b_nk=True),
+    "dense768_nk": P.Op(P.OP_MATMUL, P.F16, n=768, k=768, m_range=(0, 8192), b_nk=True),
     "odd_static_n": P.Op(P.OP_MATMUL, P.F16, n=1000, k=100, m_range=(1, 4096)),
     "dense3072_out16": P.Op(P.OP_MATMUL, P.F16, n=3072, k=768, m_range=(0, 8192), out_bytes=2),
     "tiny_k": P.Op(P.OP_MATMUL, P.BF16, n=304, k=12, m_range=(0, 1024)),
@@ -81,7 +84,7 @@ def test_ukernel_table_matches_oracle(name):
 
 
 def shapes_for(name):
-    if name in ("qk", "qk_b768"):
+    if name in ("qk", "qk_b768", "qk_nk"):
         return [dict(batch=b, m=L, n=L) for b in (1, 12, 96) for L in (1, 7, 16, 33, 77, 100, 257, 512)] + \
                [dict(batch=768, m=L, n=L) for L in (133, 141, 183, 281, 313, 390, 415, 450)] + \
                [dict(batch=96, m=313, n=200), dict(batch=96, m=200, n=313), dict(batch=96, m=133, n=281), dict(batch=96, m=313, n=415)] + \
@@ -306,6 +309,21 @@ def test_eight_wave_grids_are_for_plain_gemms_only():
     assert grids("conv") == set() and grids("qk") == set() and grids("pv") == set()
     assert grids("llm4096") == {(256, 256), (128, 256), (256, 128)}
     assert {(u.tm, u.tn) for u in P.derive_ukernels(OPS["conv"]) if u.gm * u.gn == 8} == set()
+
+
+def test_b_layout_of_an_operator():
+    """FT_B_NK: Matmul and BMM only; the set holds four-wave standard grids only, like the oracle's."""
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_CONV2D, dtype=ft.FT_F16, c_in=64, c_out=128, r=3, s=3, stride=1, pad=1,
+                                        m_lo=0, m_hi=1 << 22, b_layout=ft.FT_B_NK))
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    with pytest.raises(ft.FtError) as e:
+        ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=64, k=64, m_lo=0, m_hi=64, b_layout=2))
+    assert e.value.status == ft.FT_ERR_INVALID_ARG
+    for name in ("qk_nk", "dense768_nk"):
+        s = ft.ft_ukernels_derive(to_lib_op(OPS[name]))
+        us = [ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))]
+        assert us and all(u.gk == 1 and u.gm * u.gn == 4 for u in us)
 
 
 def test_launch_order_is_a_balanced_permutation():

@@ -142,6 +142,29 @@ def test_bmm_is_per_batch_matmul():
         assert np.array_equal(C[b], oc.matmul(A[b], B[b], F16))
 
 
+def test_b_handed_over_as_nk():
+    """B stored [N, K]: C[i,j] = sum_k A[i,k] Bt[j,k] against numpy's einsum on the decoded values and
+    against a direct loop on a tiny case; a transposed operand with distinct rows and columns, so a
+    missing (or doubled) transposition cannot pass."""
+    g = np.random.default_rng(12)
+    A = si.normal_bits(g, (9, 14), 1.0, BF16)
+    Bt = si.normal_bits(g, (5, 14), 1.0, BF16)
+    C = oc.matmul_nk(A, Bt, BF16)
+    Ad, Bd = as_f64(A, BF16), as_f64(Bt, BF16)
+    assert C.shape == (9, 5)
+    assert np.allclose(C, np.einsum("ik,jk->ij", Ad, Bd), rtol=0, atol=1e-12 * np.abs(Ad).max() * np.abs(Bd).max() * 14)
+    for i in (0, 8):
+        for j in (0, 4):
+            assert abs(C[i, j] - sum(Ad[i, k] * Bd[j, k] for k in range(14))) <= 1e-12
+    Ab = si.normal_bits(g, (3, 7, 16), 1.0, F16)
+    Bb = si.normal_bits(g, (3, 11, 16), 1.0, F16)
+    Cb = oc.bmm_nk(Ab, Bb, F16)
+    ref = np.einsum("bik,bjk->bij", as_f64(Ab, F16), as_f64(Bb, F16))
+    assert Cb.shape == (3, 7, 11) and np.allclose(Cb, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+    rows = np.array([6, 0], dtype=np.int64)
+    assert np.array_equal(oc.matmul_nk(Ab[1], Bb[1], F16, rows=rows), Cb[1][rows])
+
+
 def _im2col(Xd, R, S, stride, pad):
     n, H, W, Cin = Xd.shape
     P = (H + 2 * pad - R) // stride + 1
