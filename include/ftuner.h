@@ -138,9 +138,9 @@ enum { FT_EPI_NONE = 0, FT_EPI_BIAS = 1 };
  * change): FT_B_KN, B[b,k,j] with j contiguous (row pitch N); FT_B_NK, the same matrix stored
  * transposed, B[b,j,k] with k contiguous (row pitch K): the K matrix of an attention's Q K^T, a
  * linear layer's weight as frameworks keep it.  With FT_B_NK the operator derives the four-wave
- * standard grids only, and a launch needs operands the LDS-DMA bodies accept: 16-byte aligned
- * pointers and a reduce extent that is a multiple of 8 (N may be anything); otherwise ft_launch
- * returns FT_ERR_UNSUPPORTED (the general bodies have no such variant).                          */
+ * standard grids only, and a launch needs operands the LDS-DMA bodies accept: a reduce extent of
+ * at least 8 (any alignment, any N); otherwise ft_launch returns FT_ERR_UNSUPPORTED (the general
+ * bodies have no such variant).                                                                  */
 enum { FT_B_KN = 0, FT_B_NK = 1 };
 
 typedef struct ft_op_desc {
@@ -290,11 +290,10 @@ typedef struct ft_plan ft_plan;
  * memory for the fp32 partial tiles plus 16 bytes of counters per tile: launches of one such plan
  * must be ordered (same stream, or otherwise not overlapping), every launch leaves the counters
  * at zero, and the sum over the parts is taken in part order, so results are reproducible.
- * The split and the two-team uKernels run in the bodies that copy 16-byte chunks straight into LDS:
- * shapes whose K or N is not a multiple of 8 are never scored with a split.  If only the POINTERS
- * passed to ft_launch turn out not to be 16-byte aligned, the launch runs the same tiles through the
- * general four-wave bodies, one workgroup per tile (k_parts in ft_plan_stats then describes the plan,
- * not that launch); results agree up to the order of the fp32 sums. */
+ * The split and the eight-wave uKernels run in the bodies that copy 16-byte chunks straight into LDS
+ * and have no code for rows that end inside a chunk: shapes whose K or N is not a multiple of 8 are
+ * never scored with a split, and a program of eight-wave uKernels runs its four-wave twins there.
+ * Pointer alignment does not matter (2-byte aligned operands are copied the same way). */
 ft_status ft_plan_create(const ft_op *op, const ft_ukset *set, const ft_shape *shape, uint32_t flags,
                          const ft_forced_program *forced, ft_plan **out);
 /* The same plan through the set's per-shape cache (Sec. 5: the runtime stage is paid once per shape;
@@ -320,9 +319,9 @@ ft_status ft_plan_cached(const ft_op *op, ft_ukset *set, const ft_shape *shape, 
  * order, and descriptor flags carry the group in bits 12..31, the body in bits 1..7 and its LDS ring
  * depth in bits 8..11 (bit 0 as before).  Operands are packed group after group, each group's matrices densely packed as for a
  * plain batched launch; ft_plan_group_layout reports where a group starts.  Launch with ft_launch /
- * ft_launch_epilogue on the packed buffers.  Any alignment works; when A and B are 16-byte aligned
- * and every group's n, k and matrix sizes are multiples of 8 elements the launch takes the faster
- * vector path.  The reduce axis is never split.  flags: FT_PLAN_PATCHWORK or FT_PLAN_PAD_BASELINE, optionally
+ * ft_launch_epilogue on the packed buffers.  Any alignment and any row length works; the launch
+ * takes the faster LDS-DMA bodies when every group's rows hold at least 8 elements (k >= 8 and, with B
+ * stored [K][N], n >= 8), else the general ones.  The reduce axis is never split.  flags: FT_PLAN_PATCHWORK or FT_PLAN_PAD_BASELINE, optionally
  * FT_PLAN_HOST_ONLY.  groups: host pointer, read during the call only.  n_groups < 2^20. */
 ft_status ft_plan_create_grouped(const ft_op *op, ft_ukset *set, const ft_shape *groups, uint32_t n_groups,
                                  uint32_t flags, ft_plan **out);
@@ -364,8 +363,8 @@ ft_status ft_plan_pool(const ft_op *op, const ft_ukset *set, const ft_shape *sha
  *   BMM:    A [batch,M,K], B [batch,K,N], C [batch,M,N], densely packed.
  *   Conv2d: A = X [n,H,W,c_in], B = W [r,s,c_in,c_out], C = Y [n,P,Q,c_out] fp32.
  * A, B, C: device pointers owned by the caller (A, B at least 2-byte aligned, C 4-byte
- * aligned; 16-byte aligned A/B with row lengths that are multiples of 8 take the vector
- * path; any N is correct, rows of C that start on 64-byte blocks are written fastest, since
+ * aligned; rows of at least 8 elements -- K >= 8 and, with B stored [K][N], N >= 8 -- take the
+ * LDS-DMA bodies whatever their length and alignment, shorter ones the general bodies; any N is correct, rows of C that start on 64-byte blocks are written fastest, since
  * neighbouring tiles then share no block of memory).  hip_stream: a hipStream_t (NULL = default stream).  Asynchronous; allocates
  * nothing and does not synchronise.  An empty plan launches nothing.  The current HIP device must
  * be the one the plan was created on (else FT_ERR_INVALID_ARG).

@@ -302,7 +302,8 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
         const bool on_blocks = plan->grp_rows_on_blocks && reinterpret_cast<uintptr_t>(C) % 64 == 0;
         a.c_stream = (on_blocks || out16 || plan->grp_k_min > 64) ? 1u : 0u;     // as for a plain launch
         // every group aligned and the buffers too: the LDS-DMA bodies; else the general ones
-        const bool fast = plan->grp_aligned && reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0;
+        // (the LDS-DMA bodies take any 2-byte aligned operand; grp_aligned: every group's rows hold a chunk)
+        const bool fast = plan->grp_aligned && reinterpret_cast<uintptr_t>(A) % 2 == 0 && reinterpret_cast<uintptr_t>(B) % 2 == 0;
         if (plan->op.b_layout == FT_B_NK) {
             if (!fast) return FT_ERR_UNSUPPORTED;       // no general bodies for this layout
             const int rc = kLaunchGroupedNK[plan->op.dtype][ft_class_of_acc((int)plan->grp_fast_acc)](&a, plan->grp_fast_lds, hip_stream);
@@ -314,18 +315,20 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
         if (rc != 0) return hip_fail((hipError_t)rc);
         return FT_OK;
     }
-    // The LDS-DMA bodies need 16-byte aligned operands whose row pitches and reduce extent are
-    // multiples of 8 elements (convolution: c_in a multiple of 64, c_out of 8); everything else
-    // takes the general bodies.
+    // The LDS-DMA copies take any 2-byte aligned source (measured on gfx950 with an in-bounds probe), so
+    // the LDS-DMA bodies run whatever the row pitches are.  Where a row ends inside a 16-byte chunk
+    // (K, or N with B stored [K][N], not a multiple of 8: "ragged") the single-team bodies fetch that
+    // chunk from inside the row and fix it up in LDS (gemm_fast.h); that needs rows of at least one chunk.  Convolution: c_in a multiple of 64, c_out of 8, 16-byte aligned operands.  Everything
+    // else takes the general bodies.
     const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0);
+    const bool even = (reinterpret_cast<uintptr_t>(A) % 2 == 0) && (reinterpret_cast<uintptr_t>(B) % 2 == 0);
+    const bool nk = plan->op.b_layout == FT_B_NK;
+    const bool ragged = !a.is_conv && (a.K % 8 != 0 || (!nk && a.N % 8 != 0));
     bool fast = a.is_conv ? (aligned && a.Cin % 64 == 0 && a.N % 8 == 0)
-                          : (aligned && a.K % 8 == 0 && a.N % 8 == 0 && a.strideA % 8 == 0 && a.strideB % 8 == 0);
-    if (plan->op.b_layout == FT_B_NK) {
-        // rows of B are k long, like A's: any N; no general bodies for this layout
-        if (!(aligned && a.K % 8 == 0)) return FT_ERR_UNSUPPORTED;
-        fast = true;
-    }
-    if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
+                          : (even && a.K >= 8 && (nk || a.N >= 8) && !(ragged && plan->two_teams));
+    // (no general bodies for B stored [N][K])
+    if (nk && !fast) return FT_ERR_UNSUPPORTED;
+    if (!fast || a.is_conv || ragged) {   // no split-k variant of the gather, of the general bodies or of the fix-up: use the twin
         for (int i = 0; i < 4; ++i) {
             // (the planner derives no eight-wave grid for a convolution: its twin would run in the wrong kernel)
             if (a.is_conv && ft_is_w8_code((int)a.slot_code[i])) return FT_ERR_UNSUPPORTED;
@@ -333,6 +336,7 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
             // the twins of the narrowest tiles exist in the general dispatcher only
             if (ft_is_partial_code((int)a.slot_code[i])) fast = false;
         }
+        if (nk && !fast) return FT_ERR_UNSUPPORTED;
         a.k_parts = 1;                 // these bodies walk the whole reduce axis in one workgroup
     }
     if (static_ws && a.k_parts > 1) {

@@ -143,6 +143,14 @@ __device__ __forceinline__ uint4 shift_down_elems(uint4 v, uint32_t s) {
     return s >= 8u ? make_uint4(0u, 0u, 0u, 0u) : v;
 }
 
+// The first n (0..8) of the 8 elements of v, the others zero.
+__device__ __forceinline__ uint4 keep_low_elems(uint4 v, uint32_t n) {
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) w[i] = n >= 2 * i + 2 ? w[i] : (n == 2 * i + 1 ? (w[i] & 0xffffu) : 0u);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 // The chunk of 8 elements at position x of a row of len >= 8 elements, elements beyond the row's
 // end reading as zero.  A chunk that straddles the end is fetched as the row's last 8 elements
 // and moved down, one 16-byte load from inside the row whatever x is: every lane issues its

@@ -294,7 +294,17 @@ struct UKernelFast {
             }
         }
         const bool b_lane_on = (B_WAVE_BYTES >= 1024) || lane < (uint32_t)(B_WAVE_BYTES / 16);
-        const bool k_tail = (K % TK) != 0;
+        // Ragged edges (the copies take any 2-byte aligned source, so row pitches may be anything).
+        // K % 8 != 0: the reduce extent ends inside a 16-byte chunk of A's rows (and of B's, stored [N][K]).
+        // Such a chunk is fetched as the row's LAST 8 elements -- inside the row, so inside the operand --
+        // and moved down in LDS once the tile has landed (fix_edges), zeros moving in: elements beyond K
+        // multiply as zero whatever follows the row.  N % 8 != 0 with B stored [K][N]: what a lane reads
+        // beyond N belongs to the next row and only reaches output columns that are never stored; only
+        // the operand's last row (k = K - 1) must not be read past its end and is fetched the same way.
+        // The host sends such launches here only for the single-team bodies and with K >= 8 (N >= 8).
+        // (Everything about them is computed where it is used, in the last k-tile: nothing more stays
+        // live in scalar registers through the loop.)
+        const bool k_tail = (K % TK) != 0 || (!BNK && !g.is_conv && (N % 8u) != 0);   // the last k-tile takes the checked copy code
 
         auto issue_impl = [&](uint32_t kt, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
@@ -304,6 +314,10 @@ struct UKernelFast {
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
             const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
             const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
+            // (the last k-tile's checks work on copies the compiler cannot see through: what they derive
+            // from K, N and the pitch is then computed here, not kept in scalar registers through the loop)
+            uint32_t Kt = K, Nt = N, ldbt = g.ldb;
+            if constexpr (tail) asm volatile("" : "+s"(Kt), "+s"(Nt), "+s"(ldbt));
             if (!g.is_conv) {
 #pragma unroll
                 for (int i = 0; i < LA; ++i) {
@@ -312,7 +326,8 @@ struct UKernelFast {
                         // logical chunk of this lane in instruction i (recomputed: tail tile only)
                         uint32_t row = (wave * A_WAVE_BYTES) / 128 + lane / 8 + i * 8;
                         uint32_t kc = (lane & 7u) ^ swzA(row);
-                        if (k0 + kc * 8 >= K) p = ft_zero_page;
+                        if (k0 + kc * 8 >= Kt) p = ft_zero_page;
+                        else if (k0 + kc * 8 + 8 > Kt) p = abase + (uint32_t)(goff_a[i] - kc * 16 + (Kt - 8u) * 2);   // the row's last 8
                     }
                     if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
                 }
@@ -335,12 +350,17 @@ struct UKernelFast {
                 const void *p = bbase + (uint32_t)(goff_b[i] + (BNK ? ka : kb));
                 if constexpr (tail) {
                     if constexpr (!BNK) {
-                        uint32_t krow = (wave * B_WAVE_BYTES + i * 1024 + lane * 16) / (TN * 2);
-                        if (k0 + krow >= K) p = ft_zero_page;
+                        uint32_t o = wave * B_WAVE_BYTES + i * 1024 + lane * 16;
+                        uint32_t krow = o / (TN * 2);
+                        if (k0 + krow >= Kt) p = ft_zero_page;
+                        else if (k0 + krow + 1 == Kt && (Nt % 8u) != 0 && (goff_b[i] - krow * ldbt * 2) / 2 + 8 > Nt)
+                            p = bbase + (uint32_t)(((Kt - 1u) * ldbt + Nt - 8u) * 2);     // the last row's last 8 (its ragged
+                                                                                        // chunk, or the tile's first read in place of one beyond N)
                     } else {
                         uint32_t row = (wave * B_WAVE_BYTES + i * 1024) / 128 + lane / 8;
                         uint32_t kc = (lane & 7u) ^ swzA(row);
-                        if (k0 + kc * 8 >= K) p = ft_zero_page;
+                        if (k0 + kc * 8 >= Kt) p = ft_zero_page;
+                        else if (k0 + kc * 8 + 8 > Kt) p = bbase + (uint32_t)(goff_b[i] - kc * 16 + (Kt - 8u) * 2);
                     }
                 }
                 if (b_lane_on) lds_dma16(p, st + A_BYTES + wave * B_WAVE_BYTES + i * 1024);
@@ -403,6 +423,15 @@ struct UKernelFast {
             if (kt == 0) FT_MARK(g, 3);
             if (kt == nk / 2) FT_MARK(g, 4);
 #endif
+            if (k_tail && kt0 + kt + 1 == nk_all && !g.is_conv) {       // uniform; the operand's last k-tile
+                uint32_t Kf = K, Nf = N;
+                asm volatile("" : "+s"(Kf), "+s"(Nf));        // (as in the copy code: nothing derived from them is hoisted)
+                const uint32_t k_frac = Kf % 8u, n_frac = BNK ? 0u : Nf % 8u;
+                if (k_frac | n_frac) {
+                    fix_edges(smem + (kt % S) * STAGE_BYTES, wave_all * 64u + lane, (kt0 + kt) * TK, Kf, Nf, n0, k_frac, n_frac);
+                    __builtin_amdgcn_s_barrier();
+                }
+            }
             if (kt + S - 1 < nk) issue(kt + S - 1);
 
             const uint32_t soff = (kt % S) * STAGE_BYTES;
@@ -532,6 +561,30 @@ struct UKernelFast {
         if (SM) return to_team1 ? (bi - BM / 2) * BN + bj : bi * BN + bj;
         if (SN) return to_team1 ? bj - BN / 2 : bj;
         return bi * BN + bj;
+    }
+
+    // The chunks of the last k-tile that were fetched as "the row's last 8 elements" (see run): moved
+    // down so that the row's element k0 + 8c sits at position 0 of chunk c, zeros behind the row's end.
+    __device__ static __forceinline__ void fix_edges(unsigned char *st, uint32_t tid, uint32_t k0, uint32_t K, uint32_t N,
+                                                     uint32_t n0, uint32_t k_frac, uint32_t n_frac) {
+        constexpr uint32_t NT = (NWT == 1 ? 4 : NWT) * 64u * TEAMS;
+        if (k_frac) {
+            const uint32_t c = (K - 1u - k0) / 8u;               // the chunk the reduce axis ends in
+            for (uint32_t r = tid; r < (uint32_t)(BNK ? TM + TN : TM); r += NT) {
+                // rows of A, then (B stored [N][K]) rows of B: same 128-byte rows, same swizzle
+                const uint32_t row = r < (uint32_t)TM ? r : r - TM;
+                uint4 *q = reinterpret_cast<uint4 *>(st + (r < (uint32_t)TM ? 0 : A_BYTES) + row * (TK * 2) + ((c ^ swzA(row)) << 4));
+                *q = shift_down_elems(*q, 8u - k_frac);
+            }
+        }
+        if constexpr (!BNK) {
+            // the operand's last row, where it ends inside this tile's columns
+            if (n_frac && N > n0 && N - n0 < (uint32_t)TN && tid == 0) {
+                const uint32_t krow = K - 1u - k0, nc = (N - 1u - n0) / 8u;
+                uint4 *q = reinterpret_cast<uint4 *>(st + A_BYTES + krow * (TN * 2) + ((nc ^ swzB<TN>(krow)) << 4));
+                *q = shift_down_elems(*q, 8u - n_frac);
+            }
+        }
     }
 
     // LDS reads of the A and B fragments of k-step ks into fragment set buf.  Row offsets of the

@@ -1267,8 +1267,15 @@ static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const 
         for (ft_tile_desc d : own) {
             any = true;
             const ft_ukernel_info &u = set->uk[d.ukernel_id];
-            const int code = ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk);
+            int code = ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk);
             if (code < 0 || code > 0x7f || u.stages > 0xf) return FT_ERR_UNSUPPORTED;
+            // a group whose rows end inside a 16-byte chunk runs the standard-grid twin of a split-k uKernel
+            // (the bodies that fix such chunks up); a twin that only the general dispatcher has keeps the
+            // whole launch there
+            if (rec.k % 8 || (op->d.b_layout != FT_B_NK && rec.n % 8)) {
+                code = ft_general_code(code);
+                if (ft_is_partial_code(code)) pl->grp_aligned = false;
+            }
             d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (u.stages << 8) | (gi << 12);
             pl->descs.push_back(d);
             const int twin = ft_general_code(code);          // what the general bodies run for it
@@ -1277,10 +1284,8 @@ static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const 
             pl->grp_fast_lds = std::max(pl->grp_fast_lds, u.lds_bytes);
             pl->grp_fast_acc = std::max(pl->grp_fast_acc, u.acc_regs);
         }
-        // LDS-DMA bodies: 16-byte aligned matrices, row lengths and reduce extent multiples of 8 elements
-        // (B as [N][K]: its rows are k long too, so N may be anything)
-        if (any && (g.k % 8 || (g.n % 8 && op->d.b_layout != FT_B_NK) || rec.off_a % 8 || rec.off_b % 8 ||
-                    ((uint64_t)g.m * g.k) % 8 || ((uint64_t)g.k * g.n) % 8))
+        // LDS-DMA bodies: rows of at least one 16-byte chunk (they fetch a row's ragged end from inside the row)
+        if (any && (g.k < 8 || (g.n < 8 && op->d.b_layout != FT_B_NK)))
             pl->grp_aligned = false;
         if (any) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
         s.batch += g.batch;

@@ -149,9 +149,9 @@ def test_shapes_without_the_vector_path_are_never_split():
     check(run(plan, A, B, M * N), ref, refabs, "general path")
 
 
-def test_split_plan_with_misaligned_pointers_runs_the_general_bodies():
-    """A plan that splits the reduce axis, launched on operands that are not 16-byte aligned: the same
-    tiles run through the general bodies, one workgroup per tile; the result is still right."""
+def test_split_plan_with_misaligned_pointers():
+    """A plan that splits the reduce axis, launched on operands that are not 16-byte aligned (the
+    LDS-DMA copies take any 2-byte aligned source): the result is still right."""
     M, N, K = 528, 768, 3072
     p = si.config1_problem(M, N, K)
     op = matmul_op(N, K, ft.FT_F16)
