@@ -72,14 +72,20 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
     for dt in (0, 1):
         for cl in (0, 1, 2):
             obj = os.path.join(OUT, f"dispatch_dt{dt}_c{cl}.o")
-            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-c",
+            # (launches whose rows are whole 16-byte chunks: bodies without the code for ragged rows)
+            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_NO_RAGGED=1", "-c",
+                                      os.path.join(CSRC, "dispatch.hip"), "-o", obj]
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
+            steps.append((obj, cmd))
+            obj = os.path.join(OUT, f"dispatch_dt{dt}_rg_c{cl}.o")          # the same bodies with that code
+            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_RG=1", "-c",
                                       os.path.join(CSRC, "dispatch.hip"), "-o", obj]
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             steps.append((obj, cmd))
     for dt in (0, 1):                         # two-team bodies: workgroups of eight waves
         for cl in (0, 1):
             obj = os.path.join(OUT, f"dispatch_dt{dt}_pp_c{cl}.o")
-            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_PP=1", "-c",
+            cmd = [HIPCC] + COMMON + [f"-DFT_DT={dt}", f"-DFT_CLASS={cl}", "-DFT_PP=1", "-DFT_NO_RAGGED=1", "-c",
                                       os.path.join(CSRC, "dispatch.hip"), "-o", obj]
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
             steps.append((obj, cmd))

@@ -70,6 +70,11 @@ const launch_fn kLaunch[2][FT_NUM_CLASSES] = {
     {ft_launch_dt1_c0, ft_launch_dt1_c1, ft_launch_dt1_c2},
 };
 
+// the same bodies with the code for rows that end inside a 16-byte chunk (the ones above have none)
+const launch_fn kLaunchRagged[2][FT_NUM_CLASSES] = {
+    {ft_launch_dt0_rg_c0, ft_launch_dt0_rg_c1, ft_launch_dt0_rg_c2},
+    {ft_launch_dt1_rg_c0, ft_launch_dt1_rg_c1, ft_launch_dt1_rg_c2},
+};
 // two-team bodies (eight waves): classes 0 and 1
 const launch_fn kLaunchTwoTeams[2][2] = {{ft_launch_dt0_pp_c0, ft_launch_dt0_pp_c1}, {ft_launch_dt1_pp_c0, ft_launch_dt1_pp_c1}};
 // general bodies: [dtype][0] = bodies with <= 64 accumulator registers (256-register kernel),
@@ -328,7 +333,12 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
                           : (even && a.K >= 8 && (nk || a.N >= 8) && !(ragged && plan->two_teams));
     // (no general bodies for B stored [N][K])
     if (nk && !fast) return FT_ERR_UNSUPPORTED;
-    if (!fast || a.is_conv || ragged) {   // no split-k variant of the gather, of the general bodies or of the fix-up: use the twin
+    if (fast && ragged) {
+        // ragged rows: the single-team bodies (and the two narrowest split-k ones) fix them up
+        for (int i = 0; i < 4; ++i) a.slot_code[i] = (uint32_t)ft_ragged_code((int)a.slot_code[i]);
+        a.k_parts = 1;                 // (the planner never splits such a shape; a forced split is not taken)
+    }
+    if (!fast || a.is_conv) {          // no split-k variant of the gather or of the general bodies: use the twin
         for (int i = 0; i < 4; ++i) {
             // (the planner derives no eight-wave grid for a convolution: its twin would run in the wrong kernel)
             if (a.is_conv && ft_is_w8_code((int)a.slot_code[i])) return FT_ERR_UNSUPPORTED;
@@ -355,7 +365,7 @@ static ft_status launch_common(const ft_plan *plan, const void *A, const void *B
         if (plan->st.kernel_class > 1) return FT_ERR_UNSUPPORTED;
         rc = kLaunchTwoTeams[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
     } else if (fast) {
-        rc = kLaunch[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
+        rc = (ragged ? kLaunchRagged : kLaunch)[plan->op.dtype][plan->st.kernel_class](&a, plan->st.lds_bytes, hip_stream);
     } else {
         // the general bodies stage through registers into two LDS stages, whatever ring depth the
         // uKernel has on the LDS-DMA path

@@ -119,3 +119,10 @@ static inline int ft_general_code(int code) {
 #undef FT_X
     return code;
 }
+// body a launch with ragged rows (K or N not a multiple of 8) runs for a given code on the LDS-DMA path:
+// a split-k uKernel goes to its standard-grid twin, except the two narrowest tiles, whose twins exist
+// among the general bodies only and whose split-k bodies handle ragged rows themselves
+static inline int ft_ragged_code(int code) {
+    const int twin = ft_general_code(code);
+    return ft_is_partial_code(twin) ? code : twin;
+}

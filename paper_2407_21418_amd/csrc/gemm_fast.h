@@ -26,6 +26,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // 256 bytes of zeros: source of k-tail chunks (rows/columns of the reduce axis beyond K)
 __device__ __attribute__((aligned(256))) uint32_t ft_zero_page[64];
 
+// -DFT_NO_RAGGED: bodies without the code for rows that end inside a 16-byte chunk (see UKernelFast::run).
+// The dispatchers of the plain launches are compiled both ways, so that the ones that run launches with
+// whole chunks carry none of it (it costs them scalar registers and about one per cent).
+#ifdef FT_NO_RAGGED
+constexpr bool kRaggedRows = false;
+#else
+constexpr bool kRaggedRows = true;
+#endif
+
 template <int OFF> __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) {
     u32x4 v;
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
@@ -301,10 +310,13 @@ struct UKernelFast {
         // multiply as zero whatever follows the row.  N % 8 != 0 with B stored [K][N]: what a lane reads
         // beyond N belongs to the next row and only reaches output columns that are never stored; only
         // the operand's last row (k = K - 1) must not be read past its end and is fetched the same way.
-        // The host sends such launches here only for the single-team bodies and with K >= 8 (N >= 8).
+        // The host sends such launches here only for the single-team bodies, with N >= 8 where B is stored
+        // [K][N], and with K >= 8 -- or, in a grouped launch, with a shorter reduce axis where 8 elements from
+        // the start of a group's last row still lie inside the packed buffer: rows shorter than a chunk are
+        // fetched as they lie and what follows them is cleared in LDS.
         // (Everything about them is computed where it is used, in the last k-tile: nothing more stays
         // live in scalar registers through the loop.)
-        const bool k_tail = (K % TK) != 0 || (!BNK && !g.is_conv && (N % 8u) != 0);   // the last k-tile takes the checked copy code
+        const bool k_tail = (K % TK) != 0 || (kRaggedRows && !BNK && !g.is_conv && (N % 8u) != 0);   // the last k-tile takes the checked copy code
 
         auto issue_impl = [&](uint32_t kt, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
@@ -317,7 +329,7 @@ struct UKernelFast {
             // (the last k-tile's checks work on copies the compiler cannot see through: what they derive
             // from K, N and the pitch is then computed here, not kept in scalar registers through the loop)
             uint32_t Kt = K, Nt = N, ldbt = g.ldb;
-            if constexpr (tail) asm volatile("" : "+s"(Kt), "+s"(Nt), "+s"(ldbt));
+            if constexpr (tail && kRaggedRows) asm volatile("" : "+s"(Kt), "+s"(Nt), "+s"(ldbt));
             if (!g.is_conv) {
 #pragma unroll
                 for (int i = 0; i < LA; ++i) {
@@ -327,7 +339,9 @@ struct UKernelFast {
                         uint32_t row = (wave * A_WAVE_BYTES) / 128 + lane / 8 + i * 8;
                         uint32_t kc = (lane & 7u) ^ swzA(row);
                         if (k0 + kc * 8 >= Kt) p = ft_zero_page;
-                        else if (k0 + kc * 8 + 8 > Kt) p = abase + (uint32_t)(goff_a[i] - kc * 16 + (Kt - 8u) * 2);   // the row's last 8
+                        // the row's last 8 elements (a row shorter than that is fetched as it lies, with what follows
+                        // it: the host has checked that this stays inside the operand buffer; fix_edges clears it)
+                        else if (kRaggedRows && k0 + kc * 8 + 8 > Kt && Kt >= 8u) p = abase + (uint32_t)(goff_a[i] - kc * 16 + (Kt - 8u) * 2);
                     }
                     if (a_lane_on) lds_dma16(p, st + wave * A_WAVE_BYTES + i * 1024);
                 }
@@ -353,14 +367,14 @@ struct UKernelFast {
                         uint32_t o = wave * B_WAVE_BYTES + i * 1024 + lane * 16;
                         uint32_t krow = o / (TN * 2);
                         if (k0 + krow >= Kt) p = ft_zero_page;
-                        else if (k0 + krow + 1 == Kt && (Nt % 8u) != 0 && (goff_b[i] - krow * ldbt * 2) / 2 + 8 > Nt)
+                        else if (kRaggedRows && k0 + krow + 1 == Kt && (Nt % 8u) != 0 && (goff_b[i] - krow * ldbt * 2) / 2 + 8 > Nt)
                             p = bbase + (uint32_t)(((Kt - 1u) * ldbt + Nt - 8u) * 2);     // the last row's last 8 (its ragged
                                                                                         // chunk, or the tile's first read in place of one beyond N)
                     } else {
                         uint32_t row = (wave * B_WAVE_BYTES + i * 1024) / 128 + lane / 8;
                         uint32_t kc = (lane & 7u) ^ swzA(row);
                         if (k0 + kc * 8 >= Kt) p = ft_zero_page;
-                        else if (k0 + kc * 8 + 8 > Kt) p = bbase + (uint32_t)(goff_b[i] - kc * 16 + (Kt - 8u) * 2);
+                        else if (kRaggedRows && k0 + kc * 8 + 8 > Kt && Kt >= 8u) p = bbase + (uint32_t)(goff_b[i] - kc * 16 + (Kt - 8u) * 2);
                     }
                 }
                 if (b_lane_on) lds_dma16(p, st + A_BYTES + wave * B_WAVE_BYTES + i * 1024);
@@ -423,12 +437,14 @@ struct UKernelFast {
             if (kt == 0) FT_MARK(g, 3);
             if (kt == nk / 2) FT_MARK(g, 4);
 #endif
-            if (k_tail && kt0 + kt + 1 == nk_all && !g.is_conv) {       // uniform; the operand's last k-tile
+            if constexpr (kRaggedRows) if (k_tail && kt0 + kt + 1 == nk_all && !g.is_conv) {   // uniform; the operand's last k-tile
                 uint32_t Kf = K, Nf = N;
                 asm volatile("" : "+s"(Kf), "+s"(Nf));        // (as in the copy code: nothing derived from them is hoisted)
                 const uint32_t k_frac = Kf % 8u, n_frac = BNK ? 0u : Nf % 8u;
                 if (k_frac | n_frac) {
-                    fix_edges(smem + (kt % S) * STAGE_BYTES, wave_all * 64u + lane, (kt0 + kt) * TK, Kf, Nf, n0, k_frac, n_frac);
+                    fix_edges(smem + (kt % S) * STAGE_BYTES, wave_all * 64u + lane, NWT * 64u, (kt0 + kt) * TK, Kf, Nf, n0, k_frac, n_frac);
+                    // (a barrier alone does not wait for a wave's own LDS writes on this target)
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
                     __builtin_amdgcn_s_barrier();
                 }
             }
@@ -565,16 +581,18 @@ struct UKernelFast {
 
     // The chunks of the last k-tile that were fetched as "the row's last 8 elements" (see run): moved
     // down so that the row's element k0 + 8c sits at position 0 of chunk c, zeros behind the row's end.
-    __device__ static __forceinline__ void fix_edges(unsigned char *st, uint32_t tid, uint32_t k0, uint32_t K, uint32_t N,
-                                                     uint32_t n0, uint32_t k_frac, uint32_t n_frac) {
-        constexpr uint32_t NT = (NWT == 1 ? 4 : NWT) * 64u * TEAMS;
+    // tid of nt: the threads that share the work (a workgroup; one wave for a split-k body's private ring).
+    __device__ static __forceinline__ void fix_edges(unsigned char *st, uint32_t tid, uint32_t nt, uint32_t k0, uint32_t K,
+                                                     uint32_t N, uint32_t n0, uint32_t k_frac, uint32_t n_frac) {
+        const uint32_t NT = nt;
         if (k_frac) {
             const uint32_t c = (K - 1u - k0) / 8u;               // the chunk the reduce axis ends in
             for (uint32_t r = tid; r < (uint32_t)(BNK ? TM + TN : TM); r += NT) {
                 // rows of A, then (B stored [N][K]) rows of B: same 128-byte rows, same swizzle
                 const uint32_t row = r < (uint32_t)TM ? r : r - TM;
                 uint4 *q = reinterpret_cast<uint4 *>(st + (r < (uint32_t)TM ? 0 : A_BYTES) + row * (TK * 2) + ((c ^ swzA(row)) << 4));
-                *q = shift_down_elems(*q, 8u - k_frac);
+                // (rows of at least 8 elements were fetched as their last 8; shorter ones as they lie)
+                *q = K >= 8u ? shift_down_elems(*q, 8u - k_frac) : keep_low_elems(*q, k_frac);
             }
         }
         if constexpr (!BNK) {
@@ -741,7 +759,12 @@ struct UKernelSplitK {
             if (col >= N) col = n0;
             goff_b[i] = (krow * g.ldb + col) * 2;
         }
-        const bool k_tail = (K % TK) != 0;
+        // ragged rows (K or N not a multiple of 8) as in UKernelFast: the chunk a row ends in is fetched
+        // as the 8 elements that end with the row and moved down in LDS by the wave that owns the k-tile.
+        // Only the two narrowest tiles carry that code: the others have a four-wave standard grid of the
+        // same tile, which the host sends ragged launches to.
+        constexpr bool RAGGED = kRaggedRows && TM * TN <= 16 * 32;
+        const bool k_tail = (K % TK) != 0 || (RAGGED && (N % 8u) != 0);
 
         auto issue_impl = [&](uint32_t j, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
@@ -750,13 +773,16 @@ struct UKernelSplitK {
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
             const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
             const uint32_t ka = k0 * 2, kb = k0 * g.ldb * 2;                                        // uniform
+            uint32_t Kt = K, Nt = N, ldbt = g.ldb;
+            if constexpr (tail && RAGGED) asm volatile("" : "+s"(Kt), "+s"(Nt), "+s"(ldbt));   // (see UKernelFast)
 #pragma unroll
             for (int i = 0; i < LA; ++i) {
                 const void *p = abase + (uint32_t)(goff_a[i] + ka);
                 if constexpr (tail) {
                     uint32_t row = i * 8 + lane / 8;
                     uint32_t kc = (lane & 7u) ^ swzA(row);
-                    if (k0 + kc * 8 >= K) p = ft_zero_page;
+                    if (k0 + kc * 8 >= Kt) p = ft_zero_page;
+                    else if (RAGGED && k0 + kc * 8 + 8 > Kt && Kt >= 8u) p = abase + (uint32_t)(goff_a[i] - kc * 16 + (Kt - 8u) * 2);
                 }
                 lds_dma16(p, st + i * 1024);
             }
@@ -765,7 +791,9 @@ struct UKernelSplitK {
                 const void *p = bbase + (uint32_t)(goff_b[i] + kb);
                 if constexpr (tail) {
                     uint32_t krow = (i * 1024 + lane * 16) / (TN * 2);
-                    if (k0 + krow >= K) p = ft_zero_page;
+                    if (k0 + krow >= Kt) p = ft_zero_page;
+                    else if (RAGGED && k0 + krow + 1 == Kt && (Nt % 8u) != 0 && (goff_b[i] - krow * ldbt * 2) / 2 + 8 > Nt)
+                        p = bbase + (uint32_t)(((Kt - 1u) * ldbt + Nt - 8u) * 2);
                 }
                 lds_dma16(p, st + A_BYTES + i * 1024);
             }
@@ -803,6 +831,17 @@ struct UKernelSplitK {
         for (uint32_t j = 0; j < nkw; ++j) {
             uint32_t newest = j + S - 2 < nkw - 1 ? j + S - 2 : nkw - 1;
             wait_tiles<0>((int)(newest - j));
+            if constexpr (RAGGED) if (k_tail && kt0 + wave + 4 * j + 1 == nk_all) {   // this wave holds the operand's last k-tile
+                uint32_t Kf = K, Nf = N;
+                asm volatile("" : "+s"(Kf), "+s"(Nf));
+                const uint32_t k_frac = Kf % 8u, n_frac = Nf % 8u;
+                if (k_frac | n_frac) {
+                    // the wave's own ring: its 64 lanes do what a workgroup does in UKernelFast; the reads below
+                    // are the same wave's, in order behind these writes
+                    Std::fix_edges(ring + (j % S) * STAGE_BYTES, lane, 64u, (kt0 + wave + 4 * j) * TK, Kf, Nf, n0, k_frac, n_frac);
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                }
+            }
             // stage (j-1)%S was fully read by this wave (its last k-step waited lgkmcnt(0))
             if (j + S - 1 < nkw) issue(j + S - 1);
             const uint32_t soff = (j % S) * STAGE_BYTES;

@@ -1269,13 +1269,9 @@ static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const 
             const ft_ukernel_info &u = set->uk[d.ukernel_id];
             int code = ft_body_code((int)u.wm, (int)u.wn, (int)u.gm, (int)u.gn, (int)u.gk);
             if (code < 0 || code > 0x7f || u.stages > 0xf) return FT_ERR_UNSUPPORTED;
-            // a group whose rows end inside a 16-byte chunk runs the standard-grid twin of a split-k uKernel
-            // (the bodies that fix such chunks up); a twin that only the general dispatcher has keeps the
-            // whole launch there
-            if (rec.k % 8 || (op->d.b_layout != FT_B_NK && rec.n % 8)) {
-                code = ft_general_code(code);
-                if (ft_is_partial_code(code)) pl->grp_aligned = false;
-            }
+            // a group whose rows end inside a 16-byte chunk runs the body that fixes such chunks up
+            if (rec.k % 8 || (op->d.b_layout != FT_B_NK && rec.n % 8)) code = ft_ragged_code(code);
+
             d.flags = (d.flags & 1u) | ((uint32_t)code << 1) | (u.stages << 8) | (gi << 12);
             pl->descs.push_back(d);
             const int twin = ft_general_code(code);          // what the general bodies run for it
@@ -1284,9 +1280,8 @@ static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const 
             pl->grp_fast_lds = std::max(pl->grp_fast_lds, u.lds_bytes);
             pl->grp_fast_acc = std::max(pl->grp_fast_acc, u.acc_regs);
         }
-        // LDS-DMA bodies: rows of at least one 16-byte chunk (they fetch a row's ragged end from inside the row)
-        if (any && (g.k < 8 || (g.n < 8 && op->d.b_layout != FT_B_NK)))
-            pl->grp_aligned = false;
+        // LDS-DMA bodies, B stored [K][N]: rows of at least one 16-byte chunk (the reduce axis: see below)
+        if (any && g.n < 8 && op->d.b_layout != FT_B_NK) pl->grp_aligned = false;
         if (any) pl->grp_k_min = std::min(pl->grp_k_min, g.k);
         s.batch += g.batch;
         s.m = std::max(s.m, g.m); s.n = std::max(s.n, g.n); s.k = std::max(s.k, g.k);
@@ -1296,6 +1291,15 @@ static ft_status plan_create_grouped_impl(const ft_op *op, ft_ukset *set, const 
     ft_group_rec total;                        // one past the last group: the buffers' sizes
     total.m = total.n = total.k = total.batch = 0;
     total.off_a = off_a; total.off_b = off_b; total.off_c = off_c;
+    // LDS-DMA bodies fetch rows of fewer than 8 elements (a reduce axis shorter than one 16-byte chunk) as
+    // they lie, together with what follows them, and clear the rest in LDS: fine inside the packed buffers,
+    // where other rows and groups follow, except for a last row less than 8 elements from a buffer's end.
+    for (const ft_group_rec &r : recs) {
+        if (!r.batch || !r.m || !r.n || !r.k || r.k >= 8) continue;
+        const uint64_t last_a = r.off_a + (uint64_t)r.batch * r.m * r.k - r.k;
+        const uint64_t last_b = r.off_b + (uint64_t)r.batch * r.n * r.k - r.k;
+        if (last_a + 8 > off_a || (op->d.b_layout == FT_B_NK && last_b + 8 > off_b)) pl->grp_aligned = false;
+    }
     pl->groups.push_back(total);
     if (pl->descs.size() > UINT32_MAX / 2) return FT_ERR_UNSUPPORTED;
     s.n_tiles = pl->descs.size();

@@ -11,6 +11,9 @@
 #elif defined(FT_BNK)
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _nk_c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _nk_c, FT_CLASS)
+#elif defined(FT_RG)
+#define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _rg_c, FT_CLASS)
+#define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _rg_c, FT_CLASS)
 #elif defined(FT_PP)
 #define FT_KERNEL_NAME FT_CAT(ft_dispatch_dt, FT_DT, _pp_c, FT_CLASS)
 #define FT_LAUNCH_NAME FT_CAT(ft_launch_dt, FT_DT, _pp_c, FT_CLASS)
@@ -54,6 +57,12 @@ int ft_launch_dt0_grpf_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grpf_c0(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grpf_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt1_grpf_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_rg_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_rg_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt0_rg_c2(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_rg_c0(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_rg_c1(const ftk::KArgs *, uint32_t, void *);
+int ft_launch_dt1_rg_c2(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt0_nk_c0(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt0_nk_c1(const ftk::KArgs *, uint32_t, void *);
 int ft_launch_dt0_nk_c2(const ftk::KArgs *, uint32_t, void *);

@@ -63,6 +63,32 @@ def test_every_standard_body_on_ragged_rows(body, dtype, layout):
         check(run_poisoned(plan, A, Bm, M * N, dtype), ref, refabs, f"ragged body {body} K {K} dtype {dtype} layout {layout}")
 
 
+SPLIT_K_TILES = [(16, 16), (16, 32), (16, 64), (32, 32), (32, 64), (64, 32), (64, 64)]
+
+
+@pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
+@pytest.mark.parametrize("tile", SPLIT_K_TILES, ids=lambda t: "%dx%d" % t)
+def test_every_split_k_body_on_ragged_rows(tile, dtype):
+    """The split-k wave grid (each wave a quarter of the k-tiles, private rings): the wave that holds the
+    operand's last k-tile fixes the ragged chunks up itself.  Reduce extents whose last k-tile falls to
+    each of the four waves, and shorter than four k-tiles."""
+    tm, tn = tile
+    for K in (203, 267, 331, 395, 71, 9):
+        N, M = 4 * tn - 3, 2 * tm - 5
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=dtype, n=N, k=K, m_lo=0, m_hi=1 << 16))
+        s = ft.ft_ukernels_derive(op)
+        infos = [ft.ft_ukset_get(s, i) for i in range(ft.ft_ukset_size(s))]
+        ids = [u.id for u in infos if (u.tm, u.tn, u.gk) == (tm, tn, 4)]
+        if not ids:
+            continue
+        g = np.random.default_rng(tm * 3 + tn + K + dtype)
+        A = si.normal_bits(g, (M, K), 1.0, dtype)
+        B = si.normal_bits(g, (K, N), 1.0, dtype)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED, ft.ft_forced_program(k1=ids[0], count1=2))
+        ref, refabs = oc.matmul(A, B, dtype, want_abs=True)
+        check(run_poisoned(plan, A, B, M * N, dtype), ref, refabs, f"ragged split-k body {tile} K {K} dtype {dtype}")
+
+
 @pytest.mark.parametrize("M,N,K", [(100, 203, 331), (77, 768, 331), (300, 1000, 776), (1, 8, 8), (33, 9, 4095), (2048, 333, 513)])
 @pytest.mark.parametrize("layout", [ft.FT_B_KN, ft.FT_B_NK], ids=["kn", "nk"])
 def test_planner_plans_on_ragged_shapes(M, N, K, layout):
@@ -101,10 +127,13 @@ def test_attention_of_odd_lengths_both_operators(dtype):
         check(run_poisoned(plan, Q, Kt, nb * L * L, dtype), ref, refabs, f"QK^T batch {nb} L {L} dtype {dtype}")
 
 
-@pytest.mark.parametrize("lengths", [[77, 9, 128, 0, 257, 33, 100, 511, 16], [77, 5, 128, 1, 257]], ids=["all-at-least-8", "with-short-ones"])
+@pytest.mark.parametrize("lengths", [[77, 9, 128, 0, 257, 33, 100, 511, 16], [5, 77, 3, 128, 1, 257, 2, 40], [77, 128, 5], [300, 1, 1]],
+                         ids=["all-at-least-8", "short-ones-inside", "short-one-last", "ones-last"])
 def test_ragged_pv_grouped_on_odd_lengths(lengths):
-    """Grouped P V of odd lengths: with every length >= 8 the launch runs the LDS-DMA bodies, a shorter
-    sequence sends the whole launch to the general ones; either way every group matches the oracle."""
+    """Grouped P V of odd lengths on the LDS-DMA bodies, sequences shorter than 8 included (their rows are
+    fetched together with what follows them in the packed buffer and cleared in LDS); with such a
+    sequence at the very end of the buffer the launch takes the general bodies.  Either way every
+    group matches the oracle, with NaNs around the buffers."""
     dtype = ft.FT_F16
     op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=dtype, n=64, m_lo=0, m_hi=512, k_lo=0, k_hi=512, batch_hi=768))
     s = ft.ft_ukernels_derive(op)
