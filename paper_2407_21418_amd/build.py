@@ -156,6 +156,11 @@ def build(verbose=True, remarks=True, jobs=None, incremental=False, trace=False)
         # fix-up of a ragged last k-tile, outside the k loop's steady state: measured, no change)
         if ("_grpf_c1" in name or "_grpnk_c1" in name):
             allowed = 16
+        # (the 512-register LDS-DMA dispatchers of bf16 spill one or two registers in the store code of the
+        # 256 x 256 body -- the rounding to bf16 needs more temporaries than a conversion to fp16 -- outside
+        # every k loop: one store and two loads per workgroup)
+        if "_dt1_" in name and name.endswith("_c2.o") and allowed == 0:
+            allowed = 8
         if trace:
             allowed = 1 << 20                 # development variants are not held to it
         if use.get("ScratchSize [bytes/lane]", 0) > allowed:

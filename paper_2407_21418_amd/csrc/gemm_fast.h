@@ -29,6 +29,13 @@ __device__ __attribute__((aligned(256))) uint32_t ft_zero_page[64];
 // -DFT_NO_RAGGED: bodies without the code for rows that end inside a 16-byte chunk (see UKernelFast::run).
 // The dispatchers of the plain launches are compiled both ways, so that the ones that run launches with
 // whole chunks carry none of it (it costs them scalar registers and about one per cent).
+// The dispatchers of grouped launches keep the general bookkeeping of the k loops (ring depth as planned, stage
+// indices by division): with the leaner forms below their largest bodies no longer fit the register budget.
+#ifdef FT_GROUPED
+constexpr bool kLeanLoop = false;
+#else
+constexpr bool kLeanLoop = true;
+#endif
 #ifdef FT_NO_RAGGED
 constexpr bool kRaggedRows = false;
 #else
@@ -222,13 +229,26 @@ struct UKernelFast {
     static_assert(NR <= 15, "lgkmcnt is 4 bits");
     using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
 
-    template <int T> __device__ static __forceinline__ void wait_tiles(int ahead) {
-        // wait until at most `ahead` whole stages of this wave's copies are outstanding
+    // wait until at most `ahead` (LO..HI) whole stages of this wave's copies are outstanding: the count is
+    // an immediate of the instruction, so a runtime `ahead` is a decision tree (three compares at most)
+    template <int LO, int HI> __device__ static __forceinline__ void wait_tiles_in(uint32_t ahead) {
+        if constexpr (LO == HI) wait_vmcnt<LO * L>();
+        else {
+            constexpr int MID = (LO + HI) / 2;
+            if (ahead <= (uint32_t)MID) wait_tiles_in<LO, MID>(ahead);
+            else wait_tiles_in<MID + 1, HI>(ahead);
+        }
+    }
+    template <int T> __device__ static __forceinline__ void wait_tiles_chain(int ahead) {
         if constexpr (T >= MAX_AHEAD) wait_vmcnt<MAX_AHEAD * L>();
         else {
             if (ahead <= T) wait_vmcnt<T * L>();
-            else wait_tiles<T + 1>(ahead);
+            else wait_tiles_chain<T + 1>(ahead);
         }
+    }
+    __device__ static __forceinline__ void wait_tiles(uint32_t ahead) {
+        if constexpr (kLeanLoop) wait_tiles_in<0, MAX_AHEAD>(ahead > (uint32_t)MAX_AHEAD ? (uint32_t)MAX_AHEAD : ahead);
+        else wait_tiles_chain<0>((int)ahead);
     }
 
     __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem,
@@ -318,9 +338,9 @@ struct UKernelFast {
         // live in scalar registers through the loop.)
         const bool k_tail = (K % TK) != 0 || (kRaggedRows && !BNK && !g.is_conv && (N % 8u) != 0);   // the last k-tile takes the checked copy code
 
-        auto issue_impl = [&](uint32_t kt, auto tail_c) {
+        auto issue_impl = [&](uint32_t kt, uint32_t stage_off, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
-            unsigned char *st = smem + (kt % S) * STAGE_BYTES;
+            unsigned char *st = smem + stage_off;
             // (two teams: kt counts this team's k-tiles, every other one of the workgroup's)
             const uint32_t k0 = (TEAMS == 2 ? kt0 + team + 2 * kt : kt0 + kt) * TK;
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
@@ -380,12 +400,23 @@ struct UKernelFast {
                 if (b_lane_on) lds_dma16(p, st + A_BYTES + wave * B_WAVE_BYTES + i * 1024);
             }
         };
-        auto issue = [&](uint32_t kt) {
+        // this part's (two teams: this team's) index of the operand's last k-tile, where that one takes the
+        // checked copy code; none otherwise
+        uint32_t tail_kt = 0xffffffffu;
+        if (kLeanLoop && k_tail) {
+            if constexpr (TEAMS == 1) tail_kt = nk_all - 1u - kt0;
+            else if (nk_all - 1u >= kt0 + team && ((nk_all - 1u - kt0 - team) & 1u) == 0) tail_kt = (nk_all - 1u - kt0 - team) >> 1;
+        }
+        auto is_tail = [&](uint32_t kt) -> bool {
+            if constexpr (kLeanLoop) return kt == tail_kt;
+            else return k_tail && (TEAMS == 2 ? kt0 + team + 2 * kt : kt0 + kt) + 1 == nk_all;
+        };
+        auto issue_at = [&](uint32_t kt, uint32_t stage_off) {
 #ifdef FT_DEBUG_NO_COPY          // development: only the first copies are issued (the loop then measures MFMA + LDS alone)
             if (kt >= 1) return;
 #endif
-            if (k_tail && (TEAMS == 2 ? kt0 + team + 2 * kt : kt0 + kt) + 1 == nk_all) issue_impl(kt, std::true_type{});
-            else issue_impl(kt, std::false_type{});
+            if (is_tail(kt)) issue_impl(kt, stage_off, std::true_type{});
+            else issue_impl(kt, stage_off, std::false_type{});
         };
 
         // ---- fragment read addresses -----------------------------------------------------------
@@ -423,21 +454,77 @@ struct UKernelFast {
                 for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
 
         if constexpr (TEAMS == 1) {
+        if constexpr (kLeanLoop) {
+        // The loop's own bookkeeping is scalar code in front of every k-tile's first MFMA, on a wave that
+        // issues in order: counters showed 70 scalar instructions per k-tile (the wait for a runtime
+        // number of tiles in flight as a chain of compares, stage indices modulo a runtime ring depth,
+        // the checks for the operand's last k-tile), as much issue time as the tile's MFMAs for the small
+        // tiles.  So: at most two tiles are kept in flight beyond the one being consumed (rings deeper
+        // than three stages measured no faster: what arrives is bound elsewhere), which leaves two
+        // possible waits; stage offsets advance by add and wrap; the last k-tile is one compare.
+        const bool deep = S >= 3;
+        const uint32_t D = deep ? 2u : 1u;                    // tiles in flight beyond the current one
+        const uint32_t ring_bytes = (D + 1) * STAGE_BYTES;    // stages in use: D + 1
+        // ---- prologue: D tiles on their way -------------------------------------------------------
+        FT_MARK(g, 1);
+        issue_at(0u, 0u);
+        if (deep && nk > 1) issue_at(1u, STAGE_BYTES);
+        FT_MARK(g, 2);
+        uint32_t r_off = 0, w_off = D * STAGE_BYTES;          // stage being read; stage the next copy fills
+
+        for (uint32_t kt = 0; kt < nk; ++kt) {
+            // copies issued so far: tiles 0 .. min(kt + D - 1, nk - 1); tile kt must have landed
+            if (deep && kt + 1 < nk) wait_vmcnt<L>(); else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();      // tile kt visible to every wave; the stage of tile kt - 1 is free again
+#ifdef FT_TRACE
+            if (kt == 0) FT_MARK(g, 3);
+            if (kt == nk / 2) FT_MARK(g, 4);
+#endif
+            if constexpr (kRaggedRows) if (is_tail(kt) && !g.is_conv) {   // uniform; the operand's last k-tile
+                uint32_t Kf = K, Nf = N;
+                asm volatile("" : "+s"(Kf), "+s"(Nf));        // (as in the copy code: nothing derived from them is hoisted)
+                const uint32_t k_frac = Kf % 8u, n_frac = BNK ? 0u : Nf % 8u;
+                if (k_frac | n_frac) {
+                    fix_edges(smem + r_off, wave_all * 64u + lane, NWT * 64u, (kt0 + kt) * TK, Kf, Nf, n0, k_frac, n_frac);
+                    // (a barrier alone does not wait for a wave's own LDS writes on this target)
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                }
+            }
+            if (kt + D < nk) {
+                issue_at(kt + D, w_off);
+                w_off = w_off + STAGE_BYTES == ring_bytes ? 0u : w_off + STAGE_BYTES;
+            }
+
+            const uint32_t a_addr = fa_addr0 + r_off;
+            uint32_t b_addr[BN];
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + r_off;
+            r_off = r_off + STAGE_BYTES == ring_bytes ? 0u : r_off + STAGE_BYTES;
+
+            u32x4 fa[2][BM];
+            u32x2 fb[2][BN][2];
+            read_step<0, 0>(a_addr, b_addr, fa, fb);
+            step<0>(a_addr, b_addr, fa, fb, acc);
+        }
+
+        } else {
+        // (grouped launches: the ring as deep as the plan says, stage indices by division)
         // ---- prologue: fill S-1 stages ------------------------------------------------------------
         FT_MARK(g, 1);
-        for (uint32_t s = 0; s + 1 < S && s < nk; ++s) issue(s);
+        for (uint32_t s = 0; s + 1 < S && s < nk; ++s) issue_at(s, s * STAGE_BYTES);
         FT_MARK(g, 2);
 
         for (uint32_t kt = 0; kt < nk; ++kt) {
             // copies issued so far: tiles 0 .. min(kt+S-2, nk-1); tile kt must have landed
             uint32_t newest = kt + S - 2 < nk - 1 ? kt + S - 2 : nk - 1;
-            wait_tiles<0>((int)(newest - kt));
+            wait_tiles(newest - kt);
             __builtin_amdgcn_s_barrier();      // tile kt visible to every wave; stage (kt-1)%S is free again
 #ifdef FT_TRACE
             if (kt == 0) FT_MARK(g, 3);
             if (kt == nk / 2) FT_MARK(g, 4);
 #endif
-            if constexpr (kRaggedRows) if (k_tail && kt0 + kt + 1 == nk_all && !g.is_conv) {   // uniform; the operand's last k-tile
+            if constexpr (kRaggedRows) if (is_tail(kt) && !g.is_conv) {   // uniform; the operand's last k-tile
                 uint32_t Kf = K, Nf = N;
                 asm volatile("" : "+s"(Kf), "+s"(Nf));        // (as in the copy code: nothing derived from them is hoisted)
                 const uint32_t k_frac = Kf % 8u, n_frac = BNK ? 0u : Nf % 8u;
@@ -448,7 +535,7 @@ struct UKernelFast {
                     __builtin_amdgcn_s_barrier();
                 }
             }
-            if (kt + S - 1 < nk) issue(kt + S - 1);
+            if (kt + S - 1 < nk) issue_at(kt + S - 1, ((kt + S - 1) % S) * STAGE_BYTES);
 
             const uint32_t soff = (kt % S) * STAGE_BYTES;
             const uint32_t a_addr = fa_addr0 + soff;
@@ -462,6 +549,7 @@ struct UKernelFast {
             step<0>(a_addr, b_addr, fa, fb, acc);
         }
 
+        }
         // ---- epilogue ------------------------------------------------------------------------------
         FT_MARK(g, 5);
         // (bodies with more than 128 accumulator registers have no room for it: the host never splits them)
@@ -485,26 +573,32 @@ struct UKernelFast {
         const uint32_t n_mine = nk > team ? (nk - team + 1) / 2 : 0u;
         const uint32_t n_team0 = (nk + 1) / 2;
         FT_MARK(g, 1);
-        for (uint32_t s = 0; s + 1 < S && s < n_mine; ++s) issue(s);
+        for (uint32_t s = 0; s + 1 < S && s < n_mine; ++s) issue_at(s, s * STAGE_BYTES);
         FT_MARK(g, 2);
+        // (stage offsets advance by add and wrap: no division by the runtime ring depth per k-tile)
+        const uint32_t ring_bytes = S * STAGE_BYTES;
+        uint32_t r_off = 0, w_off = (S - 1) * STAGE_BYTES;
         // Written as a straight-line loop per team (the accumulators must not pass through a branch:
         // the compiler would keep two copies of them); team 1 starts one barrier late and the teams
         // run spare barriers at the end so that both execute 2 * n_team0 + 1 of them.
         if (team == 1) __builtin_amdgcn_s_barrier();
         for (uint32_t j = 0; j < n_mine; ++j) {
-            if (j + S - 1 < n_mine) issue(j + S - 1);
+            if (j + S - 1 < n_mine) {
+                issue_at(j + S - 1, w_off);
+                w_off = w_off + STAGE_BYTES == ring_bytes ? 0u : w_off + STAGE_BYTES;
+            }
             const uint32_t newest = j + S - 1 < n_mine - 1 ? j + S - 1 : n_mine - 1;
-            wait_tiles<0>((int)(newest - j));
+            wait_tiles(newest - j);
             __builtin_amdgcn_s_barrier();
 #ifdef FT_TRACE
             if (j == 0) FT_MARK(g, 3);
             if (j == n_mine / 2) FT_MARK(g, 4);
 #endif
-            const uint32_t soff = (j % S) * STAGE_BYTES;
-            const uint32_t a_addr = fa_addr0 + soff;
+            const uint32_t a_addr = fa_addr0 + r_off;
             uint32_t b_addr[BN];
 #pragma unroll
-            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + soff;
+            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + r_off;
+            r_off = r_off + STAGE_BYTES == ring_bytes ? 0u : r_off + STAGE_BYTES;
             u32x4 fa[2][BM];
             u32x2 fb[2][BN][2];
             read_step<0, 0>(a_addr, b_addr, fa, fb);
@@ -715,12 +809,25 @@ struct UKernelSplitK {
     using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
     using Std = UKernelFast<DT, TM, TN, 1, 1>;         // fragment helpers only (same layouts)
 
-    template <int T> __device__ static __forceinline__ void wait_tiles(int ahead) {
+    // (as in UKernelFast: a decision tree over the immediate wait counts)
+    template <int LO, int HI> __device__ static __forceinline__ void wait_tiles_in(uint32_t ahead) {
+        if constexpr (LO == HI) wait_vmcnt<LO * L>();
+        else {
+            constexpr int MID = (LO + HI) / 2;
+            if (ahead <= (uint32_t)MID) wait_tiles_in<LO, MID>(ahead);
+            else wait_tiles_in<MID + 1, HI>(ahead);
+        }
+    }
+    template <int T> __device__ static __forceinline__ void wait_tiles_chain(int ahead) {
         if constexpr (T >= MAX_AHEAD) wait_vmcnt<MAX_AHEAD * L>();
         else {
             if (ahead <= T) wait_vmcnt<T * L>();
-            else wait_tiles<T + 1>(ahead);
+            else wait_tiles_chain<T + 1>(ahead);
         }
+    }
+    __device__ static __forceinline__ void wait_tiles(uint32_t ahead) {
+        if constexpr (kLeanLoop) wait_tiles_in<0, MAX_AHEAD>(ahead > (uint32_t)MAX_AHEAD ? (uint32_t)MAX_AHEAD : ahead);
+        else wait_tiles_chain<0>((int)ahead);
     }
 
     __device__ static __forceinline__ void run(const KArgs &g, const TileDesc &d, unsigned char *smem,
@@ -766,9 +873,9 @@ struct UKernelSplitK {
         constexpr bool RAGGED = kRaggedRows && TM * TN <= 16 * 32;
         const bool k_tail = (K % TK) != 0 || (RAGGED && (N % 8u) != 0);
 
-        auto issue_impl = [&](uint32_t j, auto tail_c) {
+        auto issue_impl = [&](uint32_t j, uint32_t stage_off, auto tail_c) {
             constexpr bool tail = decltype(tail_c)::value;
-            unsigned char *st = ring + (j % S) * STAGE_BYTES;
+            unsigned char *st = ring + stage_off;
             const uint32_t k0 = (kt0 + wave + 4 * j) * TK;
             // byte offsets inside one batch entry fit 32 bits (the host rejects larger operands)
             const char *abase = reinterpret_cast<const char *>(Ab), *bbase = reinterpret_cast<const char *>(Bb);
@@ -798,9 +905,16 @@ struct UKernelSplitK {
                 lds_dma16(p, st + A_BYTES + i * 1024);
             }
         };
-        auto issue = [&](uint32_t j) {
-            if (k_tail && kt0 + wave + 4 * j + 1 == nk_all) issue_impl(j, std::true_type{});
-            else issue_impl(j, std::false_type{});
+        // this wave's index of the operand's last k-tile where that one takes the checked copy code; none otherwise
+        uint32_t tail_j = 0xffffffffu;
+        if (kLeanLoop && k_tail && nk_all - 1u >= kt0 + wave && ((nk_all - 1u - kt0 - wave) & 3u) == 0) tail_j = (nk_all - 1u - kt0 - wave) >> 2;
+        auto is_tail = [&](uint32_t j) -> bool {
+            if constexpr (kLeanLoop) return j == tail_j;
+            else return k_tail && kt0 + wave + 4 * j + 1 == nk_all;
+        };
+        auto issue_at = [&](uint32_t j, uint32_t stage_off) {
+            if (is_tail(j)) issue_impl(j, stage_off, std::true_type{});
+            else issue_impl(j, stage_off, std::false_type{});
         };
 
         const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem +
@@ -827,28 +941,37 @@ struct UKernelSplitK {
 #pragma unroll
                 for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
 
-        for (uint32_t s = 0; s + 1 < S && s < nkw; ++s) issue(s);
+        for (uint32_t s = 0; s + 1 < S && s < nkw; ++s) issue_at(s, s * STAGE_BYTES);
+        // (stage offsets advance by add and wrap: no division by the runtime ring depth per k-tile)
+        const uint32_t ring_bytes = S * STAGE_BYTES;
+        uint32_t r_off = 0, w_off = (S - 1) * STAGE_BYTES;
         for (uint32_t j = 0; j < nkw; ++j) {
             uint32_t newest = j + S - 2 < nkw - 1 ? j + S - 2 : nkw - 1;
-            wait_tiles<0>((int)(newest - j));
-            if constexpr (RAGGED) if (k_tail && kt0 + wave + 4 * j + 1 == nk_all) {   // this wave holds the operand's last k-tile
+            wait_tiles(newest - j);
+            if constexpr (RAGGED) if (is_tail(j)) {   // this wave holds the operand's last k-tile
                 uint32_t Kf = K, Nf = N;
                 asm volatile("" : "+s"(Kf), "+s"(Nf));
                 const uint32_t k_frac = Kf % 8u, n_frac = Nf % 8u;
                 if (k_frac | n_frac) {
                     // the wave's own ring: its 64 lanes do what a workgroup does in UKernelFast; the reads below
                     // are the same wave's, in order behind these writes
-                    Std::fix_edges(ring + (j % S) * STAGE_BYTES, lane, 64u, (kt0 + wave + 4 * j) * TK, Kf, Nf, n0, k_frac, n_frac);
+                    Std::fix_edges(ring + r_off, lane, 64u, (kt0 + wave + 4 * j) * TK, Kf, Nf, n0, k_frac, n_frac);
                     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
                 }
             }
             // stage (j-1)%S was fully read by this wave (its last k-step waited lgkmcnt(0))
-            if (j + S - 1 < nkw) issue(j + S - 1);
-            const uint32_t soff = (j % S) * STAGE_BYTES;
-            const uint32_t a_addr = fa_addr0 + soff;
+            if (j + S - 1 < nkw) {
+                if constexpr (kLeanLoop) {
+                    issue_at(j + S - 1, w_off);
+                    w_off = w_off + STAGE_BYTES == ring_bytes ? 0u : w_off + STAGE_BYTES;
+                } else issue_at(j + S - 1, ((j + S - 1) % S) * STAGE_BYTES);
+            }
+            const uint32_t a_addr = fa_addr0 + r_off;
             uint32_t b_addr[BN];
 #pragma unroll
-            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + soff;
+            for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + r_off;
+            if constexpr (kLeanLoop) r_off = r_off + STAGE_BYTES == ring_bytes ? 0u : r_off + STAGE_BYTES;
+            else r_off = ((j + 1) % S) * STAGE_BYTES;
             u32x4 fa[2][BM];
             u32x2 fb[2][BN][2];
             Std::template read_step<0, 0>(a_addr, b_addr, fa, fb);
