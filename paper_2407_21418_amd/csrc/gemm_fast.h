@@ -459,22 +459,26 @@ struct UKernelFast {
         // issues in order: counters showed 70 scalar instructions per k-tile (the wait for a runtime
         // number of tiles in flight as a chain of compares, stage indices modulo a runtime ring depth,
         // the checks for the operand's last k-tile), as much issue time as the tile's MFMAs for the small
-        // tiles.  So: at most two tiles are kept in flight beyond the one being consumed (rings deeper
-        // than three stages measured no faster: what arrives is bound elsewhere), which leaves two
-        // possible waits; stage offsets advance by add and wrap; the last k-tile is one compare.
-        const bool deep = S >= 3;
-        const uint32_t D = deep ? 2u : 1u;                    // tiles in flight beyond the current one
+        // tiles.  So: at most three tiles are kept in flight beyond the one being consumed (deeper rings
+        // measured slower again: what arrives is bound elsewhere), which leaves three possible waits;
+        // stage offsets advance by add and wrap; the last k-tile is one compare.
+#ifndef FT_DMAX
+#define FT_DMAX 3             // (measured: four tiles ahead are slower again than three)
+#endif
+        const uint32_t D = S - 1 < (uint32_t)FT_DMAX ? S - 1 : (uint32_t)FT_DMAX;   // tiles in flight beyond the current one
         const uint32_t ring_bytes = (D + 1) * STAGE_BYTES;    // stages in use: D + 1
         // ---- prologue: D tiles on their way -------------------------------------------------------
         FT_MARK(g, 1);
-        issue_at(0u, 0u);
-        if (deep && nk > 1) issue_at(1u, STAGE_BYTES);
+        for (uint32_t s = 0; s < D && s < nk; ++s) issue_at(s, s * STAGE_BYTES);
         FT_MARK(g, 2);
         uint32_t r_off = 0, w_off = D * STAGE_BYTES;          // stage being read; stage the next copy fills
 
         for (uint32_t kt = 0; kt < nk; ++kt) {
             // copies issued so far: tiles 0 .. min(kt + D - 1, nk - 1); tile kt must have landed
-            if (deep && kt + 1 < nk) wait_vmcnt<L>(); else wait_vmcnt<0>();
+            {
+                const uint32_t left = nk - 1 - kt;
+                wait_tiles_in<0, FT_DMAX - 1>(left < D - 1 ? left : D - 1);
+            }
             __builtin_amdgcn_s_barrier();      // tile kt visible to every wave; the stage of tile kt - 1 is free again
 #ifdef FT_TRACE
             if (kt == 0) FT_MARK(g, 3);
@@ -501,11 +505,7 @@ struct UKernelFast {
 #pragma unroll
             for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + r_off;
             r_off = r_off + STAGE_BYTES == ring_bytes ? 0u : r_off + STAGE_BYTES;
-
-            u32x4 fa[2][BM];
-            u32x2 fb[2][BN][2];
-            read_step<0, 0>(a_addr, b_addr, fa, fb);
-            step<0>(a_addr, b_addr, fa, fb, acc);
+            compute_tile(a_addr, b_addr, acc);
         }
 
         } else {
@@ -599,10 +599,7 @@ struct UKernelFast {
 #pragma unroll
             for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + r_off;
             r_off = r_off + STAGE_BYTES == ring_bytes ? 0u : r_off + STAGE_BYTES;
-            u32x4 fa[2][BM];
-            u32x2 fb[2][BN][2];
-            read_step<0, 0>(a_addr, b_addr, fa, fb);
-            step<0>(a_addr, b_addr, fa, fb, acc);
+            compute_tile(a_addr, b_addr, acc);
             __builtin_amdgcn_s_barrier();
         }
         for (uint32_t x = (team == 1 ? 1u : 0u) + 2 * n_mine; x < 2 * n_team0 + 1; ++x) __builtin_amdgcn_s_barrier();
@@ -779,6 +776,75 @@ struct UKernelFast {
                          "+v"(b[1][0]), "+v"(b[1][1]), "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1]) : "n"(N));
         else
             static_assert(BM == 0, "unsupported fragment shape");
+    }
+
+    // Fragments and MFMAs of one k-tile.  Wave tiles of few MFMAs per k-step (two for 64 x 32) cannot hide
+    // an LDS round trip behind the step before: with the reads only one step ahead every step waited for
+    // its fragments (measured: 740 clocks per k-tile for 256 clocks of MFMAs).  Where four k-steps' worth
+    // of reads fit the counter of outstanding LDS operations two at a time, every step has a fragment set
+    // of its own and the reads run two steps ahead: one exposed round trip per k-tile instead of four.
+    static constexpr bool LOOKAHEAD2 = kLeanLoop && KS == 4 && 2 * NR <= 15;
+    template <int ks>
+    __device__ static __forceinline__ void read_set(uint32_t a_addr, const uint32_t (&b_addr)[BN], u32x4 (&a)[BM], u32x2 (&b)[BN][2]) {
+        const uint32_t aa = a_addr ^ (uint32_t)(ks * (KSTEP / 8) * 16);
+        read_set_a<0>(aa, a);
+#pragma unroll
+        for (int bj = 0; bj < BN; ++bj) {
+            if constexpr (!BNK) {
+                b[bj][0] = lds_read_tr16_b64<(ks * KSTEP) * TN * 2>(b_addr[bj]);
+                b[bj][1] = lds_read_tr16_b64<(ks * KSTEP + 4) * TN * 2>(b_addr[bj]);
+            } else {
+                const uint32_t bb = b_addr[bj] ^ (uint32_t)(ks * (KSTEP / 8) * 16);
+                b[bj][0] = lds_read_b64<0>(bb);
+                b[bj][1] = lds_read_b64<8>(bb);
+            }
+        }
+    }
+    template <int bi>
+    __device__ static __forceinline__ void read_set_a(uint32_t aa, u32x4 (&a)[BM]) {
+        a[bi] = lds_read_b128<bi * MB * TK * 2>(aa);
+        if constexpr (bi + 1 < BM) read_set_a<bi + 1>(aa, a);
+    }
+    __device__ static __forceinline__ void mfma_set(const u32x4 (&fa)[BM], const u32x2 (&fb)[BN][2], Acc (&acc)[BM][BN]) {
+#pragma unroll
+        for (int bi = 0; bi < BM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < BN; ++bj) {
+                uint4 a = __builtin_bit_cast(uint4, fa[bi]);
+                uint4 b = make_uint4(fb[bj][0][0], fb[bj][0][1], fb[bj][1][0], fb[bj][1][1]);
+                if constexpr (M16) acc[bi][bj] = mfma16<DT>(a, b, acc[bi][bj]);
+                else acc[bi][bj] = mfma32<DT>(a, b, acc[bi][bj]);
+            }
+    }
+    __device__ static __forceinline__ void compute_tile(uint32_t a_addr, const uint32_t (&b_addr)[BN], Acc (&acc)[BM][BN]) {
+        if constexpr (LOOKAHEAD2) {
+#ifdef FT_DEBUG_NO_MFMA
+            u32x4 a0[BM]; u32x2 b0[BN][2];
+            read_set<0>(a_addr, b_addr, a0, b0);
+            wait_frag<0>(a0, b0);
+#else
+            u32x4 a0[BM], a1[BM], a2[BM], a3[BM];
+            u32x2 b0[BN][2], b1[BN][2], b2[BN][2], b3[BN][2];
+            // (at most two sets' reads are outstanding at any time: the counter has four bits)
+            read_set<0>(a_addr, b_addr, a0, b0);
+            read_set<1>(a_addr, b_addr, a1, b1);
+            wait_frag<NR>(a0, b0);
+            read_set<2>(a_addr, b_addr, a2, b2);
+            mfma_set(a0, b0, acc);
+            wait_frag<NR>(a1, b1);
+            read_set<3>(a_addr, b_addr, a3, b3);
+            mfma_set(a1, b1, acc);
+            wait_frag<NR>(a2, b2);
+            mfma_set(a2, b2, acc);
+            wait_frag<0>(a3, b3);
+            mfma_set(a3, b3, acc);
+#endif
+        } else {
+            u32x4 fa[2][BM];
+            u32x2 fb[2][BN][2];
+            read_step<0, 0>(a_addr, b_addr, fa, fb);
+            step<0>(a_addr, b_addr, fa, fb, acc);
+        }
     }
 };
 
@@ -972,10 +1038,7 @@ struct UKernelSplitK {
             for (int bj = 0; bj < BN; ++bj) b_addr[bj] = fb_addr[bj] + r_off;
             if constexpr (kLeanLoop) r_off = r_off + STAGE_BYTES == ring_bytes ? 0u : r_off + STAGE_BYTES;
             else r_off = ((j + 1) % S) * STAGE_BYTES;
-            u32x4 fa[2][BM];
-            u32x2 fb[2][BN][2];
-            Std::template read_step<0, 0>(a_addr, b_addr, fa, fb);
-            Std::template step<0>(a_addr, b_addr, fa, fb, acc);
+            Std::compute_tile(a_addr, b_addr, acc);
         }
 
         // ---- sum the four partial tiles: partials go to the wave's own (now idle) ring as
