@@ -66,6 +66,65 @@ def test_every_ukernel_body(body, dtype, aligned):
     check(got, ref, refabs, f"body {body} dtype {dtype}")
 
 
+RING_BODIES = [  # (tm, tn, wm, wn, teams): single-team loops of both fragment schemes, split-k wave grids
+    (128, 64, 64, 32, 1), (64, 64, 32, 32, 1), (128, 128, 64, 64, 1), (256, 128, 128, 64, 1), (32, 128, 16, 64, 1),
+    (64, 64, 64, 64, 1), (16, 64, 16, 64, 1),
+]
+
+
+@pytest.mark.parametrize("zeta", [1, 2, 4])
+@pytest.mark.parametrize("body", RING_BODIES, ids=lambda b: "t%dx%d_w%dx%d_g%d" % b)
+def test_ring_depths_and_short_reduce_axes(body, zeta):
+    """The k loops keep one to three (single team) or ring depth - 1 (two teams, split-k grid) tiles in
+    flight: every ring depth the planner can hand over (zeta workgroups per CU sharing the LDS) against
+    reduce extents of one k-tile up to more than the deepest ring, whole and ragged, so that prologue,
+    steady state and drain of each loop run with every count of tiles."""
+    tm, tn, wm, wn, teams = body
+    tuning = ft.ft_tuning_default()
+    tuning.zeta = zeta
+    op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_BMM, dtype=ft.FT_F16, m_lo=0, m_hi=8192, n_lo=0, n_hi=8192,
+                                         k_lo=0, k_hi=4096))
+    s = ft.ft_ukernels_derive(op, ft.ft_hw_query(0), tuning)
+    ids = [i for i in range(ft.ft_ukset_size(s))
+           if (lambda u: (u.tm, u.tn, u.wm, u.wn) == (tm, tn, wm, wn) and (u.gk == 2) == (teams == 2)
+               and u.gm * u.gn * (1 if u.gk == 2 else u.gk) == 4)(ft.ft_ukset_get(s, i))]
+    if not ids:
+        pytest.skip("this ring does not fit the LDS share of that zeta")
+    M, N = 2 * tm - 5, 2 * tn - 8
+    for K in (64, 72, 128, 192, 200, 256, 320, 448, 584):
+        g = np.random.default_rng(K * 31 + tm + tn + zeta)
+        A = si.normal_bits(g, (1, M, K), 1.0, ft.FT_F16)
+        B = si.normal_bits(g, (1, K, N), 1.0, ft.FT_F16)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(batch=1, m=M, n=N, k=K), ft.FT_PLAN_FORCED,
+                                 ft.ft_forced_program(k1=ids[0], count1=2))
+        got = run(plan, A, B, M * N)
+        ref, refabs = oc.bmm(A, B, ft.FT_F16, want_abs=True)
+        check(got, ref, refabs, f"body {body} zeta {zeta} K {K} stages {ft.ft_ukset_get(s, ids[0]).stages}")
+
+
+@pytest.mark.parametrize("body", [(128, 64, 64, 32), (64, 64, 32, 32), (64, 16, 16, 16)], ids=lambda b: "t%dx%d_w%dx%d" % b)
+def test_two_team_rings_on_short_reduce_axes(body):
+    """Two-team uKernels (rings of 3, 5 and 8 stages per team) on reduce extents from the shortest they
+    are derived for (four k-tiles) up: each team then runs its loop with fewer tiles than its ring holds,
+    with exactly as many, and with more; odd tile counts give the teams different numbers of tiles."""
+    tm, tn, wm, wn = body
+    N = 768
+    for K in (256, 264, 320, 448, 576, 584, 1096):
+        op = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=1, m_hi=8192))
+        s = ft.ft_ukernels_derive(op)
+        ids = [i for i in range(ft.ft_ukset_size(s))
+               if (lambda u: (u.tm, u.tn, u.wm, u.wn, u.gk) == (tm, tn, wm, wn, 2))(ft.ft_ukset_get(s, i))]
+        assert len(ids) == 1
+        M = 2 * tm - 5
+        g = np.random.default_rng(K * 17 + tm + tn)
+        A = si.normal_bits(g, (M, K), 1.0, ft.FT_F16)
+        B = si.normal_bits(g, (K, N), 1.0, ft.FT_F16)
+        plan = ft.ft_plan_create(op, s, ft.ft_shape(m=M), ft.FT_PLAN_FORCED, ft.ft_forced_program(k1=ids[0], count1=2))
+        got = run(plan, A, B, M * N)
+        ref, refabs = oc.matmul(A, B, ft.FT_F16, want_abs=True)
+        check(got, ref, refabs, f"two-team body {body} K {K} stages {ft.ft_ukset_get(s, ids[0]).stages}")
+
+
 @pytest.mark.parametrize("dtype", [ft.FT_F16, ft.FT_BF16])
 def test_permutation_matrix_is_bit_exact(dtype):
     """A = permutation matrix: every output is a single product 1*b, exact in fp32; pins the
