@@ -228,6 +228,10 @@ struct UKernelFast {
     static constexpr int NR = BM + 2 * BN;            // LDS read instructions per k-step
     static_assert(NR <= 15, "lgkmcnt is 4 bits");
     using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
+    // the lean bookkeeping of the k loop (see run): not for grouped launches and not for the bodies with
+    // 256 accumulator registers (one wave per SIMD in a 512-register kernel), which measured 2-10 % slower
+    // with it, most with the convolution gather in the loop
+    static constexpr bool LEAN = kLeanLoop && WM * WN / 64 <= 128;
 
     // wait until at most `ahead` (LO..HI) whole stages of this wave's copies are outstanding: the count is
     // an immediate of the instruction, so a runtime `ahead` is a decision tree (three compares at most)
@@ -247,7 +251,7 @@ struct UKernelFast {
         }
     }
     __device__ static __forceinline__ void wait_tiles(uint32_t ahead) {
-        if constexpr (kLeanLoop) wait_tiles_in<0, MAX_AHEAD>(ahead > (uint32_t)MAX_AHEAD ? (uint32_t)MAX_AHEAD : ahead);
+        if constexpr (LEAN) wait_tiles_in<0, MAX_AHEAD>(ahead > (uint32_t)MAX_AHEAD ? (uint32_t)MAX_AHEAD : ahead);
         else wait_tiles_chain<0>((int)ahead);
     }
 
@@ -372,7 +376,10 @@ struct UKernelFast {
                 for (int i = 0; i < LA; ++i) {
                     const int h = (int)((a_pq[i] >> 16) + r) - (int)g.cpad;
                     const int w = (int)((a_pq[i] & 0xffffu) + sx) - (int)g.cpad;
-                    const bool ok = h >= 0 && h < (int)g.H && w >= 0 && w < (int)g.W;
+                    // (one unsigned compare per coordinate, joined without short-circuit: written with && the
+                    // compiler has at times turned the four tests of every copy into masked control flow,
+                    // 10 % of a convolution's time)
+                    const bool ok = ((uint32_t)h < g.H) & ((uint32_t)w < g.W);
                     // 32-bit byte offset first, one 64-bit add last (keeps the lane offsets in one register each)
                     const uint32_t off = goff_a[i] + (((uint32_t)h * g.W + (uint32_t)w) * g.Cin + ch0) * 2;
                     const void *p = ok ? static_cast<const void *>(abase + off) : static_cast<const void *>(ft_zero_page);
@@ -403,12 +410,12 @@ struct UKernelFast {
         // this part's (two teams: this team's) index of the operand's last k-tile, where that one takes the
         // checked copy code; none otherwise
         uint32_t tail_kt = 0xffffffffu;
-        if (kLeanLoop && k_tail) {
+        if (LEAN && k_tail) {
             if constexpr (TEAMS == 1) tail_kt = nk_all - 1u - kt0;
             else if (nk_all - 1u >= kt0 + team && ((nk_all - 1u - kt0 - team) & 1u) == 0) tail_kt = (nk_all - 1u - kt0 - team) >> 1;
         }
         auto is_tail = [&](uint32_t kt) -> bool {
-            if constexpr (kLeanLoop) return kt == tail_kt;
+            if constexpr (LEAN) return kt == tail_kt;
             else return k_tail && (TEAMS == 2 ? kt0 + team + 2 * kt : kt0 + kt) + 1 == nk_all;
         };
         auto issue_at = [&](uint32_t kt, uint32_t stage_off) {
@@ -454,7 +461,7 @@ struct UKernelFast {
                 for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
 
         if constexpr (TEAMS == 1) {
-        if constexpr (kLeanLoop) {
+        if constexpr (LEAN) {
         // The loop's own bookkeeping is scalar code in front of every k-tile's first MFMA, on a wave that
         // issues in order: counters showed 70 scalar instructions per k-tile (the wait for a runtime
         // number of tiles in flight as a chain of compares, stage indices modulo a runtime ring depth,
@@ -509,7 +516,7 @@ struct UKernelFast {
         }
 
         } else {
-        // (grouped launches: the ring as deep as the plan says, stage indices by division)
+        // (grouped launches, 256-register tiles: the ring as deep as the plan says, stage indices by division)
         // ---- prologue: fill S-1 stages ------------------------------------------------------------
         FT_MARK(g, 1);
         for (uint32_t s = 0; s + 1 < S && s < nk; ++s) issue_at(s, s * STAGE_BYTES);
