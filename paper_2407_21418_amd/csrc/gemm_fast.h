@@ -1014,13 +1014,19 @@ struct UKernelSplitK {
 #pragma unroll
                 for (int e = 0; e < (M16 ? 4 : 16); ++e) acc[bi][bj][e] = 0.f;
 
+        FT_MARK(g, 1);
         for (uint32_t s = 0; s + 1 < S && s < nkw; ++s) issue_at(s, s * STAGE_BYTES);
+        FT_MARK(g, 2);
         // (stage offsets advance by add and wrap: no division by the runtime ring depth per k-tile)
         const uint32_t ring_bytes = S * STAGE_BYTES;
         uint32_t r_off = 0, w_off = (S - 1) * STAGE_BYTES;
         for (uint32_t j = 0; j < nkw; ++j) {
             uint32_t newest = j + S - 2 < nkw - 1 ? j + S - 2 : nkw - 1;
             wait_tiles(newest - j);
+#ifdef FT_TRACE
+            if (j == 0) FT_MARK(g, 3);
+            if (j == nkw / 2) FT_MARK(g, 4);
+#endif
             if constexpr (RAGGED) if (is_tail(j)) {   // this wave holds the operand's last k-tile
                 uint32_t Kf = K, Nf = N;
                 asm volatile("" : "+s"(Kf), "+s"(Nf));
@@ -1048,6 +1054,7 @@ struct UKernelSplitK {
             Std::compute_tile(a_addr, b_addr, acc);
         }
 
+        FT_MARK(g, 5);
         // ---- sum the four partial tiles: partials go to the wave's own (now idle) ring as
         // [register][lane] floats, then wave w adds up and stores registers w*NREG/4 .. +NREG/4
         float *own = reinterpret_cast<float *>(ring);
@@ -1072,6 +1079,7 @@ struct UKernelSplitK {
         }
         if (g.k_parts > 1 && !k_part_exchange<PER>(g, t, part, wave, lane, [&](int r) -> float { return fin[r]; },
                                                   [&](int r, float x) { fin[r] = x; })) return;
+        FT_MARK(g, 6);
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const uint32_t r = wave * PER + q;          // uniform: register r of the tile's accumulator layout
@@ -1086,6 +1094,10 @@ struct UKernelSplitK {
                 else __builtin_nontemporal_store(out_cvt<DT == 0 ? OUT_F16 : OUT_BF16>(sum), static_cast<uint16_t *>(g.C) + o);
             }
         }
+#ifdef FT_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        FT_MARK(g, 7);
+#endif
     }
 };
 
