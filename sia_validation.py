@@ -11,7 +11,7 @@ planner picks by itself, their ratio; at the end the geomean of the ratios and t
     python sia_validation.py                 # 21 BERT-shaped GEMMs + 18 LLM-shaped ones
     python sia_validation.py --heldout       # 28 shapes the model constants were not fitted on
     python sia_validation.py --four-wave     # without the eight-wave two-team uKernels in the set
-    ... --json gpurun_out/sia.json           # every timed program with its scores, for fitting
+    ... --json sia.json                      # every timed program with its scores, for fitting
 
 Prints a markdown table (kept under profiles/sia_validation.md).
 """
