@@ -36,6 +36,11 @@ constexpr bool kLeanLoop = false;
 #else
 constexpr bool kLeanLoop = true;
 #endif
+// tiles a single-team body keeps in flight beyond the one it consumes, at most (measured: four are slower
+// again than three)
+#ifndef FT_DMAX
+#define FT_DMAX 3
+#endif
 #ifdef FT_NO_RAGGED
 constexpr bool kRaggedRows = false;
 #else
@@ -469,9 +474,6 @@ struct UKernelFast {
         // tiles.  So: at most three tiles are kept in flight beyond the one being consumed (deeper rings
         // measured slower again: what arrives is bound elsewhere), which leaves three possible waits;
         // stage offsets advance by add and wrap; the last k-tile is one compare.
-#ifndef FT_DMAX
-#define FT_DMAX 3             // (measured: four tiles ahead are slower again than three)
-#endif
         const uint32_t D = S - 1 < (uint32_t)FT_DMAX ? S - 1 : (uint32_t)FT_DMAX;   // tiles in flight beyond the current one
         const uint32_t ring_bytes = (D + 1) * STAGE_BYTES;    // stages in use: D + 1
         // ---- prologue: D tiles on their way -------------------------------------------------------
