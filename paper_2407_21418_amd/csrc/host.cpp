@@ -1127,6 +1127,55 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
         pl->ws_tile_stride = stride;
     }
 
+    // Launch order, second pass: for launches of modest size, count what the group heights chosen
+    // above really make the XCDs fetch -- every XCD reads once the A row panels and the B column
+    // panels of the tiles it runs together (windows of what its CUs hold at once) -- and take the
+    // height, any integer up to 16, that fetches least.  The closed form above stays the starting
+    // point and wins ties.
+    if (!best.has_strips && pl->descs.size() <= 4096) {
+        const uint32_t nx = pl->num_xcds;
+        const size_t total = pl->descs.size();
+        std::vector<uint64_t> kr, kc;
+        auto fetched = [&](uint32_t slot, uint32_t g) -> uint64_t {
+            ftk::LaunchOrder o = launch_order_of(*pl);
+            o.group[slot] = g;
+            const ft_ukernel_info &u = set->uk[best.part[slot].id];
+            const size_t held = (size_t)std::max<uint32_t>(1, set->hw.num_cus / nx) * std::max<uint32_t>(1, u.max_wg_per_cu);
+            uint64_t cost = 0;
+            auto close_window = [&] {
+                for (std::vector<uint64_t> *k : {&kr, &kc}) {
+                    std::sort(k->begin(), k->end());
+                    const uint64_t n = (uint64_t)(std::unique(k->begin(), k->end()) - k->begin());
+                    cost += n * (k == &kr ? u.tm : u.tn);
+                    k->clear();
+                }
+            };
+            for (uint32_t x = 0; x < nx; ++x) {
+                size_t in_window = 0;
+                for (size_t b = x; b < total; b += nx) {
+                    const ftk::TileOfWorkgroup w = ftk::tile_of_workgroup(o, (uint32_t)b);
+                    if (w.slot != slot) continue;
+                    kr.push_back((uint64_t)w.batch << 32 | w.m0);
+                    kc.push_back((uint64_t)w.batch << 32 | w.n0);
+                    if (++in_window == held) { close_window(); in_window = 0; }
+                }
+                close_window();
+            }
+            return cost;
+        };
+        for (uint32_t i = 0; i < best.nparts; ++i) {
+            if (pl->slot_rows[i] < 2 || pl->slot_cols[i] < 2) continue;
+            uint32_t best_g = pl->slot_group[i];
+            uint64_t best_cost = fetched(i, best_g);
+            for (uint32_t g = 1; g <= std::min<uint32_t>(16, pl->slot_rows[i]); ++g) {
+                if (g == pl->slot_group[i]) continue;
+                const uint64_t c = fetched(i, g);
+                if (c < best_cost) { best_cost = c; best_g = g; }
+            }
+            pl->slot_group[i] = best_g;
+        }
+    }
+
     // The kernels derive a workgroup's tile in closed form from the grids above instead of reading
     // the table: check that form against every descriptor; a plan that fails is walked in table
     // order (its workgroups then read their descriptors).

@@ -326,6 +326,52 @@ def test_b_layout_of_an_operator():
         assert us and all(u.gk == 1 and u.gm * u.gn == 4 for u in us)
 
 
+def test_launch_order_fetches_no_more_than_any_group_height():
+    """Single-uKernel plans of the encoder sweep: the bytes the eight private L2s must fetch under the
+    library's launch order (each XCD reads once the A row panels and B column panels of its tiles;
+    workgroup b -> XCD b % 8, every XCD a contiguous run of the walk) are those of the best group
+    height 1..16, found here by walking the tile grid with every height."""
+    import synth_inputs as si
+    dt = np.dtype([("uk", "<u4"), ("batch", "<u4"), ("m0", "<u4"), ("n0", "<u4"), ("mv", "<u2"), ("nv", "<u2"), ("flags", "<u4")])
+    nx, checked = 8, 0
+    sets = {}
+    for M, N, K in si.config1_shapes():
+        if (N, K) not in sets:
+            lop = ft.ft_op_register(ft.ft_op_desc(kind=ft.FT_OP_MATMUL, dtype=ft.FT_F16, n=N, k=K, m_lo=1, m_hi=8192))
+            sets[(N, K)] = (lop, ft.ft_ukernels_derive(lop))
+        lop, s = sets[(N, K)]
+        pl = ft.ft_plan_create(lop, s, ft.ft_shape(m=M), ft.FT_PLAN_PATCHWORK | HOST)
+        desc = np.frombuffer(ft.ft_plan_descriptors(pl), dtype=dt)
+        if len(set(desc["uk"].tolist())) != 1:
+            continue
+        n = len(desc)
+        cols = len(set(desc["n0"].tolist()))
+        rows = n // cols
+        tm, tn = int(desc["mv"].max()), int(desc["nv"].max())
+        if rows < 2 or cols < 2 or n > 8 * 32:        # (one round: all tiles of an XCD run together)
+            continue
+
+        def fetched(tiles_of_xcd):
+            return sum(len({t // cols for t in ts}) * tm + len({t % cols for t in ts}) * tn for ts in tiles_of_xcd)
+
+        order = ft.ft_plan_launch_order(pl)
+        lib = fetched([[t for b, t in enumerate(order) if b % nx == x] for x in range(nx)])
+        q, r = divmod(n, nx)
+        best = None
+        for g in range(1, min(16, rows) + 1):
+            walk = []                                   # tile indices in the order of the grouped walk
+            for first in range(0, rows, g):
+                gr = min(g, rows - first)
+                walk += [(first + w % gr) * cols + w // gr for w in range(gr * cols)]
+            assert sorted(walk) == list(range(n))
+            slices = [walk[x * q + min(x, r): x * q + min(x, r) + q + (1 if x < r else 0)] for x in range(nx)]
+            f = fetched(slices)
+            best = f if best is None else min(best, f)
+        assert lib == best, (M, N, K, rows, cols, lib, best)
+        checked += 1
+    assert checked >= 8
+
+
 def test_launch_order_is_a_balanced_permutation():
     """Every workgroup takes a distinct descriptor; each XCD (workgroup b -> XCD b % 8) gets an
     equal share (+-1) of EACH constituent's tiles, as contiguous slices of the table."""
