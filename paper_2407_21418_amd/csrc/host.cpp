@@ -1127,39 +1127,51 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
         pl->ws_tile_stride = stride;
     }
 
-    // Launch order, second pass: for launches of modest size, count what the group heights chosen
+    // Launch order, second pass: for launches of modest size (up to 1024 tiles), count what the group heights chosen
     // above really make the XCDs fetch -- every XCD reads once the A row panels and the B column
     // panels of the tiles it runs together (windows of what its CUs hold at once) -- and take the
     // height, any integer up to 16, that fetches least.  The closed form above stays the starting
     // point and wins ties.
-    if (!best.has_strips && pl->descs.size() <= 4096) {
+    if (!best.has_strips && pl->descs.size() <= 1024) {
         const uint32_t nx = pl->num_xcds;
         const size_t total = pl->descs.size();
-        std::vector<uint64_t> kr, kc;
-        auto fetched = [&](uint32_t slot, uint32_t g) -> uint64_t {
+        std::vector<uint32_t> seen_r, seen_c;              // window that last touched a row / column panel
+        // which tiles of a constituent an XCD takes, as positions in the walk of its grid, does not
+        // depend on the group heights: take them from the launch order once (a height of 1 walks the
+        // grid in table order, so a position is a descriptor index less the constituent's first)
+        std::vector<uint32_t> walk[2];                     // per constituent: positions, XCD by XCD
+        std::vector<uint32_t> walk_end[2];                 // ... and where each XCD's run ends
+        {
             ftk::LaunchOrder o = launch_order_of(*pl);
-            o.group[slot] = g;
-            const ft_ukernel_info &u = set->uk[best.part[slot].id];
-            const size_t held = (size_t)std::max<uint32_t>(1, set->hw.num_cus / nx) * std::max<uint32_t>(1, u.max_wg_per_cu);
-            uint64_t cost = 0;
-            auto close_window = [&] {
-                for (std::vector<uint64_t> *k : {&kr, &kc}) {
-                    std::sort(k->begin(), k->end());
-                    const uint64_t n = (uint64_t)(std::unique(k->begin(), k->end()) - k->begin());
-                    cost += n * (k == &kr ? u.tm : u.tn);
-                    k->clear();
-                }
-            };
+            o.group[0] = o.group[1] = 1;
             for (uint32_t x = 0; x < nx; ++x) {
-                size_t in_window = 0;
                 for (size_t b = x; b < total; b += nx) {
                     const ftk::TileOfWorkgroup w = ftk::tile_of_workgroup(o, (uint32_t)b);
-                    if (w.slot != slot) continue;
-                    kr.push_back((uint64_t)w.batch << 32 | w.m0);
-                    kc.push_back((uint64_t)w.batch << 32 | w.n0);
-                    if (++in_window == held) { close_window(); in_window = 0; }
+                    walk[w.slot].push_back(w.index - o.first[w.slot]);
                 }
-                close_window();
+                for (int i = 0; i < 2; ++i) walk_end[i].push_back((uint32_t)walk[i].size());
+            }
+        }
+        auto fetched = [&](uint32_t slot, uint32_t g) -> uint64_t {
+            const ft_ukernel_info &u = set->uk[best.part[slot].id];
+            const size_t held = (size_t)std::max<uint32_t>(1, set->hw.num_cus / nx) * std::max<uint32_t>(1, u.max_wg_per_cu);
+            const uint32_t rows = pl->slot_rows[slot], cols = pl->slot_cols[slot];
+            seen_r.assign((size_t)r.batch * rows, 0);
+            seen_c.assign((size_t)r.batch * cols, 0);
+            uint64_t cost = 0;
+            uint32_t window = 0;
+            size_t at = 0;
+            for (uint32_t x = 0; x < nx; ++x) {
+                size_t in_window = 0;
+                ++window;
+                for (; at < walk_end[slot][x]; ++at) {
+                    uint32_t bi, row, col;
+                    ftk::grouped_coords(walk[slot][at], rows, cols, g, &bi, &row, &col);
+                    const size_t ri = (size_t)bi * rows + row, ci = (size_t)bi * cols + col;
+                    if (seen_r[ri] != window) { seen_r[ri] = window; cost += u.tm; }
+                    if (seen_c[ci] != window) { seen_c[ci] = window; cost += u.tn; }
+                    if (++in_window == held) { ++window; in_window = 0; }
+                }
             }
             return cost;
         };
