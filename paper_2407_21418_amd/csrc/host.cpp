@@ -1156,8 +1156,10 @@ static ft_status plan_create_impl(const ft_op *op, const ft_ukset *set, const ft
             const ft_ukernel_info &u = set->uk[best.part[slot].id];
             const size_t held = (size_t)std::max<uint32_t>(1, set->hw.num_cus / nx) * std::max<uint32_t>(1, u.max_wg_per_cu);
             const uint32_t rows = pl->slot_rows[slot], cols = pl->slot_cols[slot];
-            seen_r.assign((size_t)r.batch * rows, 0);
-            seen_c.assign((size_t)r.batch * cols, 0);
+            // (batch entries as the walk numbers them: sized from the walk, not from the shape)
+            const size_t entries = ((size_t)walk[slot].size() + (size_t)rows * cols - 1) / ((size_t)rows * cols);
+            seen_r.assign(entries * rows, 0);
+            seen_c.assign(entries * cols, 0);
             uint64_t cost = 0;
             uint32_t window = 0;
             size_t at = 0;
